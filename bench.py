@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the TurboQuant hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic input that
+is already resident in HBM:  tq_quantize_prod over every key  ->
+tq_dequantize of every code  ->  tq_score of every query head against the
+codes of its KV head (query rotation included).  The default workload is the
+KV-cache configuration (8 KV heads x 16384 bf16 keys, d = 128, b = 3 =
+2-bit MSE stage + 1-bit QJL, 32 query heads, GQA 4:1).
+
+Prints ONE JSON line.  `value` is vectors quantised per second through the
+whole step.  `roofline` describes the call that takes the largest share of
+the step, timed with HIP events on the launch stream inside the timed
+region.  `cpu_baseline` is the CPU oracle on a bounded sample of the same
+workload (a reported baseline, not a target).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def build_workload(name: str):
+    import numpy as np
+    import torch
+
+    import paper_2504_19874_amd as tq
+    import workloads as W
+
+    cfg = W.CONFIGS[name]
+    prod = cfg.kind == "prod"
+    S = W.sketch_matrix(cfg.d, cfg.seed_s) if prod else None
+    p = tq.make_params(cfg.d, cfg.bits_mse, W.gaussian_matrix(cfg.d, cfg.seed_pi), S)
+    n = cfg.n * cfg.n_groups
+    if cfg.in_dtype == "bf16":
+        keys = W.kv_keys(cfg.n_groups, cfg.n, cfg.d, cfg.seed_x).reshape(n, cfg.d)
+        x = torch.from_numpy(keys.view(np.int16)).view(torch.bfloat16).cuda()
+        q = W.gaussian_queries(cfg.nq, cfg.d, cfg.seed_q, unit=False)
+        host_x = keys
+    else:
+        host_x = W.mixture_all(n, cfg.d, cfg.seed_x, cfg.seed_x) if cfg.n > 4096 else W.unit_gaussian_rows(n, cfg.d, cfg.seed_x)
+        x = torch.from_numpy(host_x).cuda()
+        q = (W.mixture_chunk(0, cfg.nq, cfg.d, cfg.seed_q, W.mixture_centers(cfg.d, cfg.seed_x))
+             if cfg.n > 4096 else W.unit_gaussian_rows(cfg.nq, cfg.d, cfg.seed_q))
+    bufs = dict(
+        x=x, q=torch.from_numpy(q).cuda(),
+        idx=torch.zeros((n, max(1, p.idx_words)), dtype=torch.int32, device="cuda"),
+        qjl=torch.zeros((n, p.qjl_words), dtype=torch.int32, device="cuda") if prod else None,
+        gamma=torch.zeros(n, dtype=torch.float32, device="cuda") if prod else None,
+        norm=None if cfg.unit_norm else torch.zeros(n, dtype=torch.float32, device="cuda"),
+        xt=torch.zeros((n, cfg.d), dtype=torch.float32, device="cuda"),
+        scores=torch.zeros((cfg.nq, cfg.n), dtype=torch.float32, device="cuda") if cfg.topk == 0 else None,
+        topk_idx=torch.zeros((cfg.nq, max(1, cfg.topk)), dtype=torch.int32, device="cuda"),
+        topk_val=torch.zeros((cfg.nq, max(1, cfg.topk)), dtype=torch.float32, device="cuda"),
+    )
+    p.reserve(n, cfg.nq, cfg.topk)
+    return cfg, p, bufs, host_x, q
+
+
+def make_calls(tq, cfg, p, b):
+    prod = cfg.kind == "prod"
+
+    def quantize():
+        if prod:
+            tq.tq_quantize_prod(p, b["x"], b["idx"], b["qjl"], b["gamma"], b["norm"])
+        else:
+            tq.tq_quantize_mse(p, b["x"], b["idx"], b["norm"])
+
+    def dequantize():
+        tq.tq_dequantize(p, b["idx"], b["qjl"], b["gamma"], b["norm"], b["xt"])
+
+    def score():
+        tq.tq_score(p, b["q"], cfg.n_groups, cfg.q_per_group, b["idx"], b["qjl"], b["gamma"], b["norm"],
+                    cfg.n, b["scores"], cfg.topk, b["topk_idx"] if cfg.topk else None,
+                    b["topk_val"] if cfg.topk else None)
+
+    return [("quantize", quantize), ("dequantize", dequantize), ("score", score)]
+
+
+def algorithmic_work(cfg, call: str):
+    """(flops, bytes) of one call, counting only what the method needs."""
+    n, d, nq = cfg.n * cfg.n_groups, cfg.d, cfg.nq
+    prod = cfg.kind == "prod"
+    in_b = 2 if cfg.in_dtype == "bf16" else 4
+    code_b = cfg.bits_mse * d / 8 + (d / 8 + 4 if prod else 0) + (0 if cfg.unit_norm else 4)
+    if call == "quantize":
+        return 2.0 * n * d * d * (2 if prod else 1), n * (d * in_b + code_b)
+    if call == "dequantize":
+        return 2.0 * n * d * d * (2 if prod else 1), n * (code_b + 4 * d)
+    pairs = float(cfg.nq) * cfg.n  # every query against the codes of its group
+    flops = 2.0 * pairs * d * (2 if prod else 1) + 2.0 * nq * d * d * (2 if prod else 1)
+    return flops, n * code_b + 4 * pairs + 4 * nq * d
+
+
+def cpu_baseline(cfg, host_x, q, budget_s=20.0):
+    """The oracle, untuned, on a bounded sample of the same workload."""
+    import numpy as np
+    from oracle import turboquant_oracle as o
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    prod = cfg.kind == "prod"
+    Pi = o.rotation_from_gaussian(__import__("workloads").gaussian_matrix(cfg.d, cfg.seed_pi))
+    S = __import__("workloads").sketch_matrix(cfg.d, cfg.seed_s) if prod else None
+    c32, t32, _ = o.codebook_fp32(cfg.d, cfg.bits_mse)
+    n_total = host_x.shape[0]
+    rows = min(n_total, 4096)
+    done_rows, elapsed = 0, 0.0
+    while True:
+        xs = host_x[:rows]
+        xs = o.bf16_bits_to_f64(xs) if cfg.in_dtype == "bf16" else xs
+        qs = q[: max(1, min(cfg.nq, cfg.q_per_group))]
+        t0 = time.perf_counter()
+        if prod:
+            r = o.quant_prod(xs, Pi, S, c32, t32, normalise=not cfg.unit_norm)
+            o.pack_planes(r["idx"], cfg.bits_mse), o.pack_signs(r["qjl"])
+            xt = o.dequant_prod(r["idx"], r["qjl"], r["gamma"], Pi, S, c32, r["norm"])
+        else:
+            idx, nu, _ = o.quant_mse(xs, Pi, t32, normalise=not cfg.unit_norm)
+            o.pack_planes(idx, cfg.bits_mse)
+            xt = o.dequant_mse(idx, Pi, c32, nu)
+        o.score(qs, xt)
+        dt = time.perf_counter() - t0
+        done_rows, elapsed = rows, dt
+        if rows >= n_total or dt * 4 > budget_s:
+            break
+        rows = min(n_total, rows * 4)
+    return {"value": done_rows / elapsed, "unit": "vectors/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"first {done_rows} of {n_total} vectors: quantize + pack + dequantize + score "
+                      f"against {qs.shape[0]} queries, {elapsed:.2f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C3b4", "C4", "C5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2504_19874_amd as tq
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    cfg, p, bufs, host_x, q = build_workload(args.workload)
+    calls = make_calls(tq, cfg, p, bufs)
+    n = cfg.n * cfg.n_groups
+
+    for _ in range(args.warmup):
+        for _, fn in calls:
+            fn()
+    torch.cuda.synchronize()
+
+    # events on torch's current stream, which is the stream every launch uses
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        ev[s][0].record()
+        for k, (_, fn) in enumerate(calls):
+            fn()
+            ev[s][k + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_per_step = wall * 1e3 / args.steps
+    per_call_ms = []
+    for k in range(len(calls)):
+        per_call_ms.append(sum(ev[s][k].elapsed_time(ev[s][k + 1]) for s in range(args.steps)) / args.steps)
+    dom = max(range(len(calls)), key=lambda k: per_call_ms[k])
+    dom_name = calls[dom][0]
+    flops, nbytes = algorithmic_work(cfg, dom_name)
+    dom_s = per_call_ms[dom] * 1e-3
+    mfma_bound = flops / (PEAK_FP32_MFMA_TFLOPS * 1e12) >= nbytes / (PEAK_HBM_GBS * 1e9)
+    if mfma_bound:
+        ach = flops / dom_s / 1e12
+        roof = {"bound": "mfma", "achieved": ach, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / PEAK_FP32_MFMA_TFLOPS, "traffic": None}
+    else:
+        ach = nbytes / dom_s / 1e9
+        roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": ach / PEAK_HBM_GBS, "traffic": None}
+    roof["kernel"] = f"tq_{dom_name}" + ("_prod" if dom_name == "quantize" and cfg.kind == "prod" else "")
+    roof["avg_ms"] = per_call_ms[dom]
+
+    out = {
+        "metric": "vectors quantized/s through quantize+dequantize+score (one GPU)",
+        "value": n / (ms_per_step * 1e-3),
+        "unit": "vectors/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: TurboQuant_{cfg.kind} b={cfg.bits} d={cfg.d}, "
+                               f"{cfg.n_groups}x{cfg.n} {cfg.in_dtype} vectors, {cfg.nq} queries "
+                               f"({cfg.q_per_group} per group)" + (f", top-{cfg.topk}" if cfg.topk else "")},
+        "per_call_ms": {name: per_call_ms[k] for k, (name, _) in enumerate(calls)},
+        "quantize_vectors_per_s": n / (per_call_ms[0] * 1e-3),
+        "scores_per_s": float(cfg.nq) * cfg.n / (per_call_ms[2] * 1e-3),
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, host_x, q)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

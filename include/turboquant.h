@@ -1,0 +1,165 @@
+/*
+ * turboquant.h - C ABI of the MI355X (gfx950) TurboQuant library.
+ *
+ * TurboQuant (arxiv 2504.19874) quantises d-dimensional vectors to b bits per
+ * coordinate: rotate by a random orthogonal matrix, replace every rotated
+ * coordinate by the index of the nearest centroid of a Lloyd-Max codebook,
+ * and (inner-product variant) add a 1-bit sketch of the residual.
+ *
+ * Conventions for every call
+ *  - "device" pointers are HIP device memory of the current device; "host"
+ *    pointers are ordinary host memory.  All pointers are borrowed: the
+ *    caller allocates, and keeps device buffers alive until the stream work
+ *    has finished.  The library allocates nothing and never synchronises;
+ *    device work is enqueued on `stream` (a hipStream_t passed as void*; NULL
+ *    is the default stream).
+ *  - Matrices are row-major fp32.  Vectors are rows.  d must be a multiple of
+ *    32 (GPU entry points), bits_mse in [0, 4].
+ *  - Every failure is a return code; nothing is launched when arguments are
+ *    rejected.
+ *
+ * Packed code layout (the b*d-bit string of Sec. 1.1; the paper fixes only its
+ * size): coordinates are taken in groups of 32 and stored as bit planes.
+ *    idx word [i][g*bits_mse + p], bit l  =  bit p of idx_{32g+l} of vector i
+ *    qjl word [i][g],              bit l  =  1 iff sign(S r)_{32g+l} = +1
+ * so one vector owns bits_mse*d/32 idx words and d/32 qjl words, contiguous.
+ * Per-vector scalars are separate fp32 arrays: gamma[i] = ||r||_2 (Alg. 2) and
+ * norm[i] = ||x||_2 (Sec. 1.3, norms kept in floating point).
+ */
+#ifndef TURBOQUANT_H
+#define TURBOQUANT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  TQ_OK = 0,
+  TQ_ERR_INVALID_ARG = 1, /* NULL where a pointer is required, bad size, bad enum */
+  TQ_ERR_UNSUPPORTED = 2, /* valid request outside what the kernels cover        */
+  TQ_ERR_HIP = 3,         /* a HIP runtime call or launch reported an error      */
+  TQ_ERR_WORKSPACE = 4    /* params.workspace is NULL or too small for the call  */
+} tq_status;
+
+typedef enum { TQ_F32 = 0, TQ_BF16 = 1 } tq_dtype;
+
+/* Human-readable name of a status (static storage). */
+const char* tq_status_string(tq_status s);
+
+/*
+ * Lloyd-Max codebook for one coordinate of a uniformly random unit vector in
+ * R^d: the minimiser of the continuous 1-D k-means problem of eq. (4) for the
+ * density f_X of Lemma 1, with 2^bits centroids.  Host only, fp64 inside.
+ *   d >= 3, bits in [0, 8].
+ *   centroids      host out, 2^bits floats, ascending, antisymmetric.
+ *   bounds         host out, 2^bits - 1 floats: midpoints of consecutive
+ *                  centroids (the Voronoi cell boundaries), computed in fp64
+ *                  and rounded once.  May be NULL when bits == 0.
+ *   cost_per_coord host out, nullable: C(f_X, bits); d times it is D_mse.
+ */
+tq_status tq_build_codebook(int32_t d, int32_t bits, float* centroids, float* bounds,
+                            double* cost_per_coord);
+
+/*
+ * Global parameters of Alg. 1 / Alg. 2 for one (d, bits_mse).
+ * TurboQuant_prod with total bit-width b uses bits_mse = b - 1.
+ */
+typedef struct tq_params {
+  int32_t d;
+  int32_t bits_mse;
+  const float* Pi;        /* device d*d: rotation, y = Pi x                         */
+  const float* PiT;       /* device d*d: transpose of Pi   (tq_dequantize)          */
+  const float* S;         /* device d*d: sketch matrix, N(0,1) entries; NULL = mse  */
+  const float* ST;        /* device d*d: transpose of S    (tq_dequantize, prod)    */
+  const float* SPiT;      /* device d*d: S * Pi^T          (tq_quantize_prod)       */
+  const float* centroids; /* host, 2^bits_mse floats (tq_build_codebook)            */
+  const float* bounds;    /* host, 2^bits_mse - 1 floats                            */
+  void* workspace;        /* device scratch, see tq_workspace_bytes                 */
+  size_t workspace_bytes;
+} tq_params;
+
+/*
+ * Fill the derived matrices from Pi and S on the device: PiT = Pi^T,
+ * ST = S^T, SPiT = S Pi^T.  S, ST, SPiT may all be NULL (mse only).
+ * S Pi^T lets the sketch of Alg. 2 (sign(S r), r = x - Pi^T y~) be taken in
+ * the rotated basis, S r = (S Pi^T)(y - y~), an exact identity for orthogonal
+ * Pi.
+ */
+tq_status tq_derive_params(int32_t d, const float* Pi, const float* S, float* PiT, float* ST,
+                           float* SPiT, void* stream);
+
+/* Device scratch large enough for any call with up to n vectors (per call),
+ * nq queries and this topk under these params. */
+size_t tq_workspace_bytes(const tq_params* p, int64_t n, int64_t nq, int32_t topk);
+
+/*
+ * Quant_mse of Alg. 1 for n vectors.
+ *   x     device, n rows of d values (fp32, or bf16 bit patterns), row stride
+ *         ldx elements.
+ *   idx   device out, n * (bits_mse*d/32) words.
+ *   norm  device out, n floats, or NULL.  Non-NULL: each row is divided by its
+ *         L2 norm before rotation and the norm is stored (a zero row stays
+ *         zero with norm 0).  NULL: rows are taken as unit-norm as given.
+ * A coordinate exactly on a cell boundary goes to the upper cell.
+ */
+tq_status tq_quantize_mse(const tq_params* p, const void* x, tq_dtype dtype, int64_t n,
+                          int64_t ldx, uint32_t* idx, float* norm, void* stream);
+
+/*
+ * Quant_prod of Alg. 2: idx from the MSE stage at bits_mse bits, then
+ * qjl = sign(S r) and gamma = ||r||_2 for the residual r of the
+ * (unit-normalised) vector.  sign(0) is +1.  Needs p->SPiT and, unless the
+ * fused d = 128 kernel applies, workspace.
+ *   qjl   device out, n * (d/32) words.   gamma device out, n floats.
+ */
+tq_status tq_quantize_prod(const tq_params* p, const void* x, tq_dtype dtype, int64_t n,
+                           int64_t ldx, uint32_t* idx, uint32_t* qjl, float* gamma, float* norm,
+                           void* stream);
+
+/*
+ * DeQuant_mse (Alg. 1) when qjl == NULL, DeQuant_prod (Alg. 2) otherwise:
+ *   x_out[i] = norm[i] * ( Pi^T c[idx_i]  +  sqrt(pi/2)/d * gamma[i] * S^T z_i ).
+ * norm may be NULL (= 1).  x_out: device, n rows of d floats, row stride ldo.
+ */
+tq_status tq_dequantize(const tq_params* p, const uint32_t* idx, const uint32_t* qjl,
+                        const float* gamma, const float* norm, int64_t n, float* x_out,
+                        int64_t ldo, void* stream);
+
+/*
+ * Inner-product estimates of Sec. 3.2 for every (query, code) pair inside a
+ * group: query row g*q_per_group + j is scored against the n_per_group codes
+ * of group g (code row g*n_per_group + i):
+ *   s = norm * ( <Pi q, c[idx]>  +  sqrt(pi/2)/d * gamma * <S q, z> ),
+ * the second term only when qjl != NULL.  Equal to <q, tq_dequantize(code)>.
+ *   q        device, n_groups*q_per_group rows of d floats, row stride ldq.
+ *   scores   device out [n_groups*q_per_group][lds], first n_per_group columns
+ *            written; may be NULL when only top-k is wanted.
+ *   topk     0, or 1..64: also return, per query, the indices (within the
+ *            group, int32) and values of the topk largest scores, descending,
+ *            equal scores ordered by lower index.  topk_idx/topk_val: device
+ *            out [n_groups*q_per_group][topk]; topk_val nullable.
+ * Uses workspace for the rotated queries (and for scores when scores==NULL).
+ */
+tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_groups,
+                   int32_t q_per_group, const uint32_t* idx, const uint32_t* qjl,
+                   const float* gamma, const float* norm, int64_t n_per_group, float* scores,
+                   int64_t lds, int32_t topk, int32_t* topk_idx, float* topk_val, void* stream);
+
+/*
+ * Codec stages on their own (HBM-bound; they are also what the bit-exactness
+ * tests drive): the decision idx_j = argmin_k |y_j - c_k| of Alg. 1 plus
+ * packing for given rotated coordinates y[n][d]; the sign packing of Alg. 2
+ * for given u = S r; and the table lookup y~_j = c[idx_j] of DeQuant_mse.
+ */
+tq_status tq_stage_pack(const tq_params* p, const float* y, int64_t n, uint32_t* idx, void* stream);
+tq_status tq_stage_sign_pack(int32_t d, const float* u, int64_t n, uint32_t* qjl, void* stream);
+tq_status tq_stage_unpack(const tq_params* p, const uint32_t* idx, int64_t n, float* y_tilde,
+                          void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TURBOQUANT_H */

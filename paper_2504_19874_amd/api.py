@@ -1,0 +1,156 @@
+"""Thin Python binding of the C ABI in include/turboquant.h.
+
+Argument marshalling only: every function takes torch tensors that already
+live on the GPU (plus numpy arrays for the host-side codebook), passes their
+addresses and the current HIP stream to the library, and raises on a non-zero
+status.  No arithmetic of the method happens here.
+"""
+from __future__ import annotations
+
+import ctypes as C
+
+import numpy as np
+import torch
+
+from . import _lib
+
+TQ_F32, TQ_BF16 = 0, 1
+
+
+class TurboQuantError(RuntimeError):
+    pass
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        name = _lib.load().tq_status_string(status).decode()
+        raise TurboQuantError(f"{what}: {name}")
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise TurboQuantError("expected a GPU tensor")
+    if not t.is_contiguous():
+        raise TurboQuantError("expected a contiguous tensor")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def tq_build_codebook(d: int, bits: int):
+    """-> (centroids float32[2^bits], bounds float32[2^bits-1], cost_per_coord)."""
+    lib = _lib.load()
+    c = np.zeros(1 << bits, dtype=np.float32)
+    t = np.zeros(max(1, (1 << bits) - 1), dtype=np.float32)
+    cost = C.c_double(0.0)
+    _check(lib.tq_build_codebook(d, bits, c.ctypes.data_as(C.c_void_p), t.ctypes.data_as(C.c_void_p),
+                                 C.byref(cost)), "tq_build_codebook")
+    return c, t[: (1 << bits) - 1].copy(), cost.value
+
+
+class Params:
+    """Owns the tq_params struct and keeps every buffer it points to alive."""
+
+    def __init__(self, d: int, bits_mse: int, Pi: torch.Tensor, S: torch.Tensor | None,
+                 centroids: np.ndarray, bounds: np.ndarray, device="cuda"):
+        lib = _lib.load()
+        self.d, self.bits_mse = int(d), int(bits_mse)
+        self.device = torch.device(device)
+        self.Pi = Pi.to(self.device, torch.float32).contiguous()
+        self.S = None if S is None else S.to(self.device, torch.float32).contiguous()
+        self.PiT = torch.empty_like(self.Pi)
+        self.ST = None if S is None else torch.empty_like(self.S)
+        self.SPiT = None if S is None else torch.empty_like(self.S)
+        self.centroids = np.ascontiguousarray(centroids, dtype=np.float32)
+        self.bounds = np.ascontiguousarray(bounds, dtype=np.float32)
+        if self.centroids.size != (1 << bits_mse) or self.bounds.size != (1 << bits_mse) - 1:
+            raise TurboQuantError("codebook size does not match bits_mse")
+        self._bounds_buf = self.bounds if self.bounds.size else np.zeros(1, dtype=np.float32)
+        self.workspace = None
+        self.c = _lib.TqParams()
+        self.c.d, self.c.bits_mse = self.d, self.bits_mse
+        self.c.Pi, self.c.PiT = self.Pi.data_ptr(), self.PiT.data_ptr()
+        self.c.S = 0 if self.S is None else self.S.data_ptr()
+        self.c.ST = 0 if self.ST is None else self.ST.data_ptr()
+        self.c.SPiT = 0 if self.SPiT is None else self.SPiT.data_ptr()
+        self.c.centroids = self.centroids.ctypes.data
+        self.c.bounds = self._bounds_buf.ctypes.data
+        self.c.workspace, self.c.workspace_bytes = 0, 0
+        _check(lib.tq_derive_params(self.d, _ptr(self.Pi), _ptr(self.S), _ptr(self.PiT), _ptr(self.ST),
+                                    _ptr(self.SPiT), _stream()), "tq_derive_params")
+
+    def reserve(self, n: int, nq: int = 0, topk: int = 0):
+        """Size the device workspace for calls with up to n vectors / nq queries."""
+        need = tq_workspace_bytes(self, n, nq, topk)
+        if self.workspace is None or self.workspace.numel() < need:
+            self.workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
+            self.c.workspace = self.workspace.data_ptr()
+            self.c.workspace_bytes = self.workspace.numel()
+        return self
+
+    @property
+    def idx_words(self) -> int:
+        return (self.d // 32) * self.bits_mse
+
+    @property
+    def qjl_words(self) -> int:
+        return self.d // 32
+
+
+def tq_workspace_bytes(p: Params, n: int, nq: int, topk: int) -> int:
+    return int(_lib.load().tq_workspace_bytes(C.byref(p.c), n, nq, topk))
+
+
+def _dtype_of(x: torch.Tensor) -> int:
+    if x.dtype == torch.float32:
+        return TQ_F32
+    if x.dtype == torch.bfloat16:
+        return TQ_BF16
+    raise TurboQuantError(f"unsupported input dtype {x.dtype}")
+
+
+def tq_quantize_mse(p: Params, x: torch.Tensor, idx: torch.Tensor, norm: torch.Tensor | None):
+    n = x.shape[0]
+    _check(_lib.load().tq_quantize_mse(C.byref(p.c), _ptr(x), _dtype_of(x), n, x.stride(0) if n else p.d,
+                                       _ptr(idx), _ptr(norm), _stream()), "tq_quantize_mse")
+
+
+def tq_quantize_prod(p: Params, x: torch.Tensor, idx: torch.Tensor, qjl: torch.Tensor,
+                     gamma: torch.Tensor, norm: torch.Tensor | None):
+    n = x.shape[0]
+    _check(_lib.load().tq_quantize_prod(C.byref(p.c), _ptr(x), _dtype_of(x), n, x.stride(0) if n else p.d,
+                                        _ptr(idx), _ptr(qjl), _ptr(gamma), _ptr(norm), _stream()),
+           "tq_quantize_prod")
+
+
+def tq_dequantize(p: Params, idx, qjl, gamma, norm, x_out: torch.Tensor):
+    n = x_out.shape[0]
+    _check(_lib.load().tq_dequantize(C.byref(p.c), _ptr(idx), _ptr(qjl), _ptr(gamma), _ptr(norm), n,
+                                     _ptr(x_out), x_out.stride(0) if n else p.d, _stream()), "tq_dequantize")
+
+
+def tq_score(p: Params, q: torch.Tensor, n_groups: int, q_per_group: int, idx, qjl, gamma, norm,
+             n_per_group: int, scores: torch.Tensor | None, topk: int = 0,
+             topk_idx: torch.Tensor | None = None, topk_val: torch.Tensor | None = None):
+    lds = scores.stride(0) if scores is not None and scores.shape[0] else n_per_group
+    _check(_lib.load().tq_score(C.byref(p.c), _ptr(q), q.stride(0) if q.shape[0] else p.d, n_groups,
+                                q_per_group, _ptr(idx), _ptr(qjl), _ptr(gamma), _ptr(norm), n_per_group,
+                                _ptr(scores), lds, topk, _ptr(topk_idx), _ptr(topk_val), _stream()),
+           "tq_score")
+
+
+def tq_stage_pack(p: Params, y: torch.Tensor, idx: torch.Tensor):
+    _check(_lib.load().tq_stage_pack(C.byref(p.c), _ptr(y), y.shape[0], _ptr(idx), _stream()), "tq_stage_pack")
+
+
+def tq_stage_sign_pack(d: int, u: torch.Tensor, qjl: torch.Tensor):
+    _check(_lib.load().tq_stage_sign_pack(d, _ptr(u), u.shape[0], _ptr(qjl), _stream()), "tq_stage_sign_pack")
+
+
+def tq_stage_unpack(p: Params, idx: torch.Tensor, y_tilde: torch.Tensor):
+    _check(_lib.load().tq_stage_unpack(C.byref(p.c), _ptr(idx), y_tilde.shape[0], _ptr(y_tilde), _stream()),
+           "tq_stage_unpack")

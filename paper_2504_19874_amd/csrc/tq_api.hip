@@ -1,0 +1,344 @@
+// C ABI entry points: argument validation, workspace carving, kernel launches.
+// No allocation, no synchronisation; everything is enqueued on the caller's
+// stream.
+#include <cmath>
+#include <cstring>
+
+#include "tq_internal.h"
+
+using namespace tq;
+
+namespace {
+
+constexpr int64_t kChunkRows = 65536;  // rows per pass when a residual workspace is needed
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+tq_status check_params(const tq_params* p, bool need_codebook) {
+  if (p == nullptr) return TQ_ERR_INVALID_ARG;
+  if (p->d <= 0 || p->bits_mse < 0) return TQ_ERR_INVALID_ARG;
+  if (p->d % 32 != 0 || p->bits_mse > 4 || p->d > 16384) return TQ_ERR_UNSUPPORTED;
+  if (need_codebook) {
+    if (p->centroids == nullptr) return TQ_ERR_INVALID_ARG;
+    if (p->bits_mse > 0 && p->bounds == nullptr) return TQ_ERR_INVALID_ARG;
+  }
+  return TQ_OK;
+}
+
+Codebook make_codebook(const tq_params* p) {
+  Codebook cb;
+  std::memset(&cb, 0, sizeof(cb));
+  cb.bits = p->bits_mse;
+  const int K = 1 << p->bits_mse;
+  for (int k = 0; k < K; ++k) cb.c[k] = p->centroids[k];
+  for (int k = 0; k + 1 < K; ++k) cb.t[k] = p->bounds[k];
+  return cb;
+}
+
+float kappa_of(int d) { return (float)(std::sqrt(1.5707963267948966) / (double)d); }
+
+tq_status from_hip(hipError_t e) { return e == hipSuccess ? TQ_OK : TQ_ERR_HIP; }
+
+struct Workspace {
+  char* base;
+  size_t size;
+  size_t used;
+  void* take(size_t bytes) {
+    const size_t off = round_up(used, 256);
+    if (base == nullptr || off + bytes > size) return nullptr;
+    used = off + bytes;
+    return base + off;
+  }
+};
+
+tq_status quantize_common(const tq_params* p, const void* x, tq_dtype dtype, int64_t n, int64_t ldx,
+                          uint32_t* idx, uint32_t* qjl, float* gamma, float* norm, bool prod,
+                          hipStream_t stream) {
+  tq_status st = check_params(p, true);
+  if (st != TQ_OK) return st;
+  if (n < 0 || ldx < p->d) return TQ_ERR_INVALID_ARG;
+  if (dtype != TQ_F32 && dtype != TQ_BF16) return TQ_ERR_INVALID_ARG;
+  if (n == 0) return TQ_OK;
+  if (x == nullptr || p->Pi == nullptr) return TQ_ERR_INVALID_ARG;
+  if (p->bits_mse > 0 && idx == nullptr) return TQ_ERR_INVALID_ARG;
+  if (prod && (qjl == nullptr || gamma == nullptr || p->SPiT == nullptr)) return TQ_ERR_INVALID_ARG;
+  if (ldx % 4 != 0 || !aligned16(p->Pi) || (prod && !aligned16(p->SPiT))) return TQ_ERR_UNSUPPORTED;
+  if (dtype == TQ_F32 ? !aligned16(x) : (reinterpret_cast<uintptr_t>(x) & 7u) != 0)
+    return TQ_ERR_UNSUPPORTED;
+
+  const int d = p->d;
+  const size_t esz = dtype == TQ_F32 ? 4 : 2;
+  const int words_per_row = (d / 32) * p->bits_mse;
+
+  GemmArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.W1 = p->Pi;
+  a.ldw = d;
+  a.M = d;
+  a.d = d;
+  a.segs = 1;
+  a.ldx = ldx;
+  a.normalise = norm != nullptr;
+  a.kappa = kappa_of(d);
+  a.cb = make_codebook(p);
+  const NKind nk = dtype == TQ_F32 ? N_F32 : N_BF16;
+
+  if (!prod) {
+    a.X = x;
+    a.n = n;
+    a.rownorm_out = norm;
+    a.words_out = idx;
+    return from_hip(launch_gemm(nk, E_QUANT, p->bits_mse, a, 1, stream));
+  }
+
+  // prod: pass 1 writes idx and the rotated-basis residual e = y - c[idx];
+  // pass 2 streams e (its row norms are gamma) against S Pi^T and packs signs.
+  Workspace ws{static_cast<char*>(p->workspace), p->workspace_bytes, 0};
+  int64_t chunk = n < kChunkRows ? n : kChunkRows;
+  float* resid = nullptr;
+  while (true) {
+    resid = static_cast<float*>(ws.take((size_t)chunk * d * sizeof(float)));
+    if (resid != nullptr || chunk <= 128) break;
+    ws.used = 0;
+    chunk = (chunk / 2 + 127) / 128 * 128;
+  }
+  if (resid == nullptr) return TQ_ERR_WORKSPACE;
+
+  for (int64_t r0 = 0; r0 < n; r0 += chunk) {
+    const int64_t rows = (n - r0 < chunk) ? n - r0 : chunk;
+    GemmArgs a1 = a;
+    a1.X = static_cast<const char*>(x) + (size_t)r0 * ldx * esz;
+    a1.n = rows;
+    a1.rownorm_out = norm ? norm + r0 : nullptr;
+    a1.words_out = idx ? idx + r0 * words_per_row : nullptr;
+    a1.resid_out = resid;
+    hipError_t e = launch_gemm(nk, E_QUANT, p->bits_mse, a1, 1, stream);
+    if (e != hipSuccess) return TQ_ERR_HIP;
+
+    GemmArgs a2;
+    std::memset(&a2, 0, sizeof(a2));
+    a2.W1 = p->SPiT;
+    a2.ldw = d;
+    a2.M = d;
+    a2.d = d;
+    a2.segs = 1;
+    a2.X = resid;
+    a2.ldx = d;
+    a2.n = rows;
+    a2.rownorm_out = gamma + r0;
+    a2.words_out = qjl + r0 * (d / 32);
+    e = launch_gemm(N_F32, E_SIGN, 0, a2, 1, stream);
+    if (e != hipSuccess) return TQ_ERR_HIP;
+  }
+  return TQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* tq_status_string(tq_status s) {
+  switch (s) {
+    case TQ_OK: return "TQ_OK";
+    case TQ_ERR_INVALID_ARG: return "TQ_ERR_INVALID_ARG";
+    case TQ_ERR_UNSUPPORTED: return "TQ_ERR_UNSUPPORTED";
+    case TQ_ERR_HIP: return "TQ_ERR_HIP";
+    case TQ_ERR_WORKSPACE: return "TQ_ERR_WORKSPACE";
+    default: return "TQ_ERR_UNKNOWN";
+  }
+}
+
+tq_status tq_derive_params(int32_t d, const float* Pi, const float* S, float* PiT, float* ST,
+                           float* SPiT, void* stream) {
+  if (d <= 0 || Pi == nullptr) return TQ_ERR_INVALID_ARG;
+  if (d % 32 != 0 || d > 16384) return TQ_ERR_UNSUPPORTED;
+  if ((ST != nullptr || SPiT != nullptr) && S == nullptr) return TQ_ERR_INVALID_ARG;
+  if (!aligned16(Pi) || (S && !aligned16(S)) || (SPiT && !aligned16(SPiT))) return TQ_ERR_UNSUPPORTED;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (PiT != nullptr && launch_transpose(d, Pi, PiT, s) != hipSuccess) return TQ_ERR_HIP;
+  if (ST != nullptr && launch_transpose(d, S, ST, s) != hipSuccess) return TQ_ERR_HIP;
+  if (SPiT != nullptr) {
+    // row m of S Pi^T is Pi applied to row m of S: the rotate contraction with
+    // the rows of S as the vectors, stored plainly
+    GemmArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.W1 = Pi;
+    a.ldw = d;
+    a.M = d;
+    a.d = d;
+    a.segs = 1;
+    a.X = S;
+    a.ldx = d;
+    a.n = d;
+    a.out = SPiT;
+    a.ldo = d;
+    if (launch_gemm(N_F32, E_STORE_T, 0, a, 1, s) != hipSuccess) return TQ_ERR_HIP;
+  }
+  return TQ_OK;
+}
+
+size_t tq_workspace_bytes(const tq_params* p, int64_t n, int64_t nq, int32_t topk) {
+  if (p == nullptr || p->d <= 0 || n < 0 || nq < 0) return 0;
+  const size_t d = (size_t)p->d;
+  const size_t rows = (size_t)(n < kChunkRows ? n : kChunkRows);
+  size_t bytes = round_up(rows * d * sizeof(float), 256);          // residual of quantize_prod
+  bytes += 2 * round_up((size_t)nq * d * sizeof(float), 256);      // rotated / sketched queries
+  if (topk > 0) bytes += round_up((size_t)nq * (size_t)(n + 3) * sizeof(float), 256);  // scores when not returned
+  return bytes + 256;
+}
+
+tq_status tq_quantize_mse(const tq_params* p, const void* x, tq_dtype dtype, int64_t n, int64_t ldx,
+                          uint32_t* idx, float* norm, void* stream) {
+  return quantize_common(p, x, dtype, n, ldx, idx, nullptr, nullptr, norm, false,
+                         static_cast<hipStream_t>(stream));
+}
+
+tq_status tq_quantize_prod(const tq_params* p, const void* x, tq_dtype dtype, int64_t n, int64_t ldx,
+                           uint32_t* idx, uint32_t* qjl, float* gamma, float* norm, void* stream) {
+  return quantize_common(p, x, dtype, n, ldx, idx, qjl, gamma, norm, true,
+                         static_cast<hipStream_t>(stream));
+}
+
+tq_status tq_dequantize(const tq_params* p, const uint32_t* idx, const uint32_t* qjl,
+                        const float* gamma, const float* norm, int64_t n, float* x_out, int64_t ldo,
+                        void* stream) {
+  tq_status st = check_params(p, true);
+  if (st != TQ_OK) return st;
+  if (n < 0 || ldo < p->d) return TQ_ERR_INVALID_ARG;
+  if (n == 0) return TQ_OK;
+  const bool prod = qjl != nullptr;
+  if (x_out == nullptr || p->PiT == nullptr || (p->bits_mse > 0 && idx == nullptr)) return TQ_ERR_INVALID_ARG;
+  if (prod && (gamma == nullptr || p->ST == nullptr)) return TQ_ERR_INVALID_ARG;
+  if (ldo % 4 != 0 || !aligned16(x_out) || !aligned16(p->PiT) || (prod && !aligned16(p->ST)))
+    return TQ_ERR_UNSUPPORTED;
+  GemmArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.W1 = p->PiT;  // x~[k] = sum_j Pi[j][k] y~[j]: rows of Pi^T against the decoded code
+  a.W2 = p->ST;
+  a.ldw = p->d;
+  a.M = p->d;
+  a.d = p->d;
+  a.segs = prod ? 2 : 1;
+  a.n = n;
+  a.idx = idx;
+  a.qjl = qjl;
+  a.gamma = gamma;
+  a.scale_in = norm;
+  a.out = x_out;
+  a.ldo = ldo;
+  a.kappa = kappa_of(p->d);
+  a.cb = make_codebook(p);
+  return from_hip(launch_gemm(N_CODE, E_STORE_T, p->bits_mse, a, 1, static_cast<hipStream_t>(stream)));
+}
+
+tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_groups,
+                   int32_t q_per_group, const uint32_t* idx, const uint32_t* qjl, const float* gamma,
+                   const float* norm, int64_t n_per_group, float* scores, int64_t lds, int32_t topk,
+                   int32_t* topk_idx, float* topk_val, void* stream) {
+  tq_status st = check_params(p, true);
+  if (st != TQ_OK) return st;
+  if (n_groups < 0 || q_per_group < 0 || n_per_group < 0 || ldq < p->d || topk < 0) return TQ_ERR_INVALID_ARG;
+  if (topk > 64 || n_per_group > 0x7fffffff) return TQ_ERR_UNSUPPORTED;
+  const int64_t nq = (int64_t)n_groups * q_per_group;
+  if (nq == 0) return TQ_OK;
+  const bool prod = qjl != nullptr;
+  if (q == nullptr || p->Pi == nullptr) return TQ_ERR_INVALID_ARG;
+  if (n_per_group > 0 && p->bits_mse > 0 && idx == nullptr) return TQ_ERR_INVALID_ARG;
+  if (prod && (gamma == nullptr || p->S == nullptr)) return TQ_ERR_INVALID_ARG;
+  if (scores == nullptr && topk == 0) return TQ_ERR_INVALID_ARG;
+  if (scores != nullptr && lds < n_per_group) return TQ_ERR_INVALID_ARG;
+  if (topk > 0 && topk_idx == nullptr) return TQ_ERR_INVALID_ARG;
+  if (ldq % 4 != 0 || !aligned16(q) || !aligned16(p->Pi) || (prod && !aligned16(p->S))) return TQ_ERR_UNSUPPORTED;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int d = p->d;
+
+  Workspace ws{static_cast<char*>(p->workspace), p->workspace_bytes, 0};
+  float* qr = static_cast<float*>(ws.take((size_t)nq * d * sizeof(float)));
+  float* qs = prod ? static_cast<float*>(ws.take((size_t)nq * d * sizeof(float))) : nullptr;
+  if (qr == nullptr || (prod && qs == nullptr)) return TQ_ERR_WORKSPACE;
+  int64_t ld_scores = lds;
+  if (scores == nullptr) {
+    ld_scores = (n_per_group + 3) / 4 * 4;
+    scores = static_cast<float*>(ws.take((size_t)nq * ld_scores * sizeof(float)));
+    if (scores == nullptr) return TQ_ERR_WORKSPACE;
+  }
+
+  // queries into the rotated basis and the sketch basis: Pi q and S q
+  {
+    GemmArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.W1 = p->Pi;
+    a.ldw = d;
+    a.M = d;
+    a.d = d;
+    a.segs = 1;
+    a.X = q;
+    a.ldx = ldq;
+    a.n = nq;
+    a.out = qr;
+    a.ldo = d;
+    if (launch_gemm(N_F32, E_STORE_T, 0, a, 1, s) != hipSuccess) return TQ_ERR_HIP;
+    if (prod) {
+      a.W1 = p->S;
+      a.out = qs;
+      if (launch_gemm(N_F32, E_STORE_T, 0, a, 1, s) != hipSuccess) return TQ_ERR_HIP;
+    }
+  }
+  if (n_per_group > 0) {
+    GemmArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.W1 = qr;
+    a.W2 = qs;
+    a.ldw = d;
+    a.w_group_stride = (int64_t)q_per_group * d;
+    a.M = q_per_group;
+    a.d = d;
+    a.segs = prod ? 2 : 1;
+    a.n = n_per_group;
+    a.idx = idx;
+    a.qjl = qjl;
+    a.gamma = gamma;
+    a.scale_in = norm;
+    a.out = scores;
+    a.ldo = ld_scores;
+    a.out_group_stride = (int64_t)q_per_group * ld_scores;
+    a.kappa = kappa_of(d);
+    a.cb = make_codebook(p);
+    if (launch_gemm(N_CODE, E_STORE_N, p->bits_mse, a, n_groups, s) != hipSuccess) return TQ_ERR_HIP;
+  }
+  if (topk > 0) {
+    if (launch_topk(scores, nq, n_per_group, ld_scores, topk, topk_idx, topk_val, s) != hipSuccess)
+      return TQ_ERR_HIP;
+  }
+  return TQ_OK;
+}
+
+tq_status tq_stage_pack(const tq_params* p, const float* y, int64_t n, uint32_t* idx, void* stream) {
+  tq_status st = check_params(p, true);
+  if (st != TQ_OK) return st;
+  if (n < 0) return TQ_ERR_INVALID_ARG;
+  if (n == 0 || p->bits_mse == 0) return TQ_OK;
+  if (y == nullptr || idx == nullptr) return TQ_ERR_INVALID_ARG;
+  return from_hip(launch_stage_pack(make_codebook(p), p->d, y, n, idx, static_cast<hipStream_t>(stream)));
+}
+
+tq_status tq_stage_sign_pack(int32_t d, const float* u, int64_t n, uint32_t* qjl, void* stream) {
+  if (d <= 0 || n < 0) return TQ_ERR_INVALID_ARG;
+  if (d % 32 != 0) return TQ_ERR_UNSUPPORTED;
+  if (n == 0) return TQ_OK;
+  if (u == nullptr || qjl == nullptr) return TQ_ERR_INVALID_ARG;
+  return from_hip(launch_stage_sign_pack(d, u, n, qjl, static_cast<hipStream_t>(stream)));
+}
+
+tq_status tq_stage_unpack(const tq_params* p, const uint32_t* idx, int64_t n, float* y_tilde,
+                          void* stream) {
+  tq_status st = check_params(p, true);
+  if (st != TQ_OK) return st;
+  if (n < 0) return TQ_ERR_INVALID_ARG;
+  if (n == 0) return TQ_OK;
+  if (y_tilde == nullptr || (p->bits_mse > 0 && idx == nullptr)) return TQ_ERR_INVALID_ARG;
+  return from_hip(launch_stage_unpack(make_codebook(p), p->d, idx, n, y_tilde, static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"

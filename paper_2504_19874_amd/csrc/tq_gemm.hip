@@ -1,0 +1,345 @@
+// Generic fp32 MFMA contraction for gfx950 with on-the-fly operand decoding
+// and fused quantisation epilogues.  See tq_internal.h for what it computes.
+//
+// Tiling.  One workgroup = 256 threads = 4 wavefronts arranged 2 x 2; the
+// workgroup owns a 128 (rows m) x 128 (vectors i) block of D, each wavefront
+// a 64 x 64 block = 2 x 2 tiles of v_mfma_f32_32x32x2_f32 (64 accumulator
+// registers).  K advances 32 at a time through LDS; both operand tiles are
+// stored [row][k] with a row stride of 36 floats, so that a lane's 16-byte
+// read of four consecutive k lands in banks 4*row + const: conflict free.
+//
+// Operand layout of v_mfma_f32_32x32x2_f32 (A is 32x2, B is 2x32, D is 32x32):
+//   A[i][k] sits in lane i + 32k, B[k][j] in lane j + 32k,
+//   D[i][j] in lane j + 32*((i/4)%2), register 4*(i/8) + i%4.
+// The contraction index may be visited in any order as long as A and B agree.
+// Here lane half h = lane/32 reads k = 8s + 4h + r at step (s, r), so one
+// ds_read_b128 per operand tile feeds four MFMA steps.
+//
+// D has the vector index on the lane (j) axis.  That is what lets the
+// epilogues work per lane: a lane holds 16 coordinates of ONE vector per tile,
+// builds its share of the packed words locally and merges with the other
+// half-wave through one cross-lane exchange.
+#include "tq_internal.h"
+
+namespace tq {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int TM = 128;      // rows of W per workgroup
+constexpr int TN = 128;      // vectors per workgroup
+constexpr int BK = 32;       // k per LDS stage
+constexpr int LDS_LD = 36;   // padded row stride (floats)
+constexpr int XCDS = 8;
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+template <int NKIND, int EKIND, int BITS>
+__global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a, const int tiles_m,
+                                                   const int tiles_n, const int per_xcd) {
+  __shared__ __attribute__((aligned(16))) float Ws[TM * LDS_LD];
+  __shared__ __attribute__((aligned(16))) float Ns[TN * LDS_LD];
+  __shared__ float row_ss[TN];
+  __shared__ float cent_s[16];
+
+  // workgroup -> tile.  Consecutive workgroup ids go round-robin over the 8
+  // XCDs; give every XCD a contiguous range of tiles, m fastest, so the m
+  // tiles that re-read the same block of vectors share one L2.
+  const int total = tiles_m * tiles_n;
+  const int logical = (int)(blockIdx.x % XCDS) * per_xcd + (int)(blockIdx.x / XCDS);
+  if (logical >= total) return;
+  const int tile_m = logical % tiles_m;
+  const int tile_n = logical / tiles_m;
+  const int group = blockIdx.y;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, h = lane >> 5;
+
+  const int m0 = tile_m * TM;
+  const int64_t n0 = (int64_t)tile_n * TN;
+  const int64_t vec_base = (int64_t)group * a.n;  // first vector row of this group
+  const float* W1 = a.W1 + (int64_t)group * a.w_group_stride;
+  const float* W2 = (a.segs > 1) ? a.W2 + (int64_t)group * a.w_group_stride : nullptr;
+
+  const int kt_per_seg = a.d / BK;
+  const int n_kt = kt_per_seg * a.segs;
+  const int words_per_row = kt_per_seg * BITS;
+
+  // staging: thread (row = tid/8 + 32p, col4 = tid%8) moves one 16-byte piece
+  const int srow = tid >> 3;
+  const int scol = (tid & 7) * 4;
+
+  if (NKIND == N_CODE && tid < 16) cent_s[tid] = a.cb.c[tid];
+
+  float4 wreg[4];
+  uint32_t nreg[16];
+  float ss[4] = {0.f, 0.f, 0.f, 0.f};
+  float kg[4] = {0.f, 0.f, 0.f, 0.f};
+  if (NKIND == N_CODE && a.segs > 1) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int64_t i = n0 + srow + 32 * p;
+      kg[p] = (i < a.n) ? a.kappa * a.gamma[vec_base + i] : 0.f;
+    }
+  }
+
+  auto load_tiles = [&](int kt) {
+    const int seg = kt >= kt_per_seg;
+    const int kk = (kt - seg * kt_per_seg) * BK;
+    const float* W = seg ? W2 : W1;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int m = m0 + srow + 32 * p;
+      wreg[p] = (m < a.M) ? *reinterpret_cast<const float4*>(W + (int64_t)m * a.ldw + kk + scol)
+                          : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int64_t i = n0 + srow + 32 * p;
+      const bool valid = i < a.n;
+      if (NKIND == N_F32) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (valid)
+          v = *reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(a.X) +
+                                              (vec_base + i) * a.ldx + kk + scol);
+        nreg[4 * p + 0] = v.x; nreg[4 * p + 1] = v.y; nreg[4 * p + 2] = v.z; nreg[4 * p + 3] = v.w;
+      } else if (NKIND == N_BF16) {
+        uint2 v = make_uint2(0, 0);
+        if (valid)
+          v = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(a.X) +
+                                              (vec_base + i) * a.ldx + kk + scol);
+        nreg[4 * p + 0] = v.x; nreg[4 * p + 1] = v.y;
+      } else {
+        const int g = kt - seg * kt_per_seg;
+        if (!seg) {
+#pragma unroll
+          for (int pl = 0; pl < BITS; ++pl)
+            nreg[4 * p + pl] = valid ? a.idx[(vec_base + i) * words_per_row + g * BITS + pl] : 0u;
+        } else {
+          nreg[4 * p] = valid ? a.qjl[(vec_base + i) * kt_per_seg + g] : 0u;
+        }
+      }
+    }
+  };
+
+  auto store_tiles = [&](int kt) {
+    const int seg = kt >= kt_per_seg;
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+      *reinterpret_cast<float4*>(&Ws[(srow + 32 * p) * LDS_LD + scol]) = wreg[p];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      float4 v;
+      if (NKIND == N_F32) {
+        v = make_float4(__uint_as_float(nreg[4 * p]), __uint_as_float(nreg[4 * p + 1]),
+                        __uint_as_float(nreg[4 * p + 2]), __uint_as_float(nreg[4 * p + 3]));
+      } else if (NKIND == N_BF16) {
+        v = make_float4(bf16_lo(nreg[4 * p]), bf16_hi(nreg[4 * p]), bf16_lo(nreg[4 * p + 1]),
+                        bf16_hi(nreg[4 * p + 1]));
+      } else {
+        float e[4];
+        if (!seg) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            uint32_t code = 0;
+#pragma unroll
+            for (int pl = 0; pl < BITS; ++pl) code |= ((nreg[4 * p + pl] >> (scol + q)) & 1u) << pl;
+            e[q] = cent_s[code];
+          }
+        } else {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) e[q] = ((nreg[4 * p] >> (scol + q)) & 1u) ? kg[p] : -kg[p];
+        }
+        v = make_float4(e[0], e[1], e[2], e[3]);
+      }
+      if (NKIND != N_CODE) ss[p] += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+      *reinterpret_cast<float4*>(&Ns[(srow + 32 * p) * LDS_LD + scol]) = v;
+    }
+  };
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  load_tiles(0);
+  __syncthreads();  // cent_s visible before the first decode
+  for (int kt = 0; kt < n_kt; ++kt) {
+    store_tiles(kt);
+    __syncthreads();
+    if (kt + 1 < n_kt) load_tiles(kt + 1);  // in flight while the MFMAs run
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      float4 av[2], bv[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        av[t] = *reinterpret_cast<const float4*>(&Ws[(wm * 64 + t * 32 + l32) * LDS_LD + 8 * s + 4 * h]);
+        bv[t] = *reinterpret_cast<const float4*>(&Ns[(wn * 64 + t * 32 + l32) * LDS_LD + 8 * s + 4 * h]);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i].x, bv[j].x, acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i].y, bv[j].y, acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i].z, bv[j].z, acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i].w, bv[j].w, acc[i][j], 0, 0, 0);
+        }
+    }
+    __syncthreads();
+  }
+
+  // squared norms of the streamed rows: 8 neighbouring lanes share a row
+  if (NKIND != N_CODE) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      float v = ss[p];
+      v += __shfl_xor(v, 1);
+      v += __shfl_xor(v, 2);
+      v += __shfl_xor(v, 4);
+      if ((tid & 7) == 0) row_ss[srow + 32 * p] = v;
+    }
+    __syncthreads();
+    if (a.rownorm_out != nullptr && tile_m == 0 && tid < TN) {
+      const int64_t i = n0 + tid;
+      if (i < a.n) a.rownorm_out[vec_base + i] = sqrtf(row_ss[tid]);
+    }
+  }
+
+  // ------------------------------- epilogue -------------------------------
+#pragma unroll
+  for (int tn = 0; tn < 2; ++tn) {
+    const int vloc = wn * 64 + tn * 32 + l32;
+    const int64_t i = n0 + vloc;
+    const bool valid = i < a.n;
+    float scale = 1.f;
+    if (EKIND == E_QUANT) {
+      if (a.normalise) {
+        const float nu = sqrtf(row_ss[vloc]);
+        scale = nu > 0.f ? 1.f / nu : 0.f;
+      }
+    } else if (EKIND == E_STORE_T || EKIND == E_STORE_N) {
+      if (a.scale_in != nullptr && valid) scale = a.scale_in[vec_base + i];
+    }
+#pragma unroll
+    for (int tm = 0; tm < 2; ++tm) {
+      const int mb = m0 + wm * 64 + tm * 32;  // first row of this 32x32 tile
+      const floatx16& c = acc[tm][tn];
+      if (EKIND == E_STORE_T) {
+        if (valid) {
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const int m = mb + 8 * k + 4 * h;
+            if (m < a.M)
+              *reinterpret_cast<float4*>(a.out + (vec_base + i) * a.ldo + m) =
+                  make_float4(c[4 * k] * scale, c[4 * k + 1] * scale, c[4 * k + 2] * scale,
+                              c[4 * k + 3] * scale);
+          }
+        }
+      } else if (EKIND == E_STORE_N) {
+        if (valid) {
+          float* o = a.out + (int64_t)group * a.out_group_stride + i;
+#pragma unroll
+          for (int k = 0; k < 4; ++k)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const int m = mb + 8 * k + 4 * h + r;
+              if (m < a.M) o[(int64_t)m * a.ldo] = c[4 * k + r] * scale;
+            }
+        }
+      } else {
+        constexpr int PL = (EKIND == E_SIGN) ? 1 : BITS;
+        uint32_t piece[PL > 0 ? PL : 1];
+#pragma unroll
+        for (int pl = 0; pl < (PL > 0 ? PL : 1); ++pl) piece[pl] = 0u;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          float e[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            uint32_t code;
+            if (EKIND == E_SIGN) {
+              code = (c[4 * k + r] >= 0.f) ? 1u : 0u;
+              e[r] = 0.f;
+            } else {
+              const float y = c[4 * k + r] * scale;
+              float yt = a.cb.c[0];
+              code = 0u;
+#pragma unroll
+              for (int j = 0; j < (1 << BITS) - 1; ++j) {
+                const bool ge = y >= a.cb.t[j];
+                code += ge ? 1u : 0u;
+                yt = ge ? a.cb.c[j + 1] : yt;
+              }
+              e[r] = y - yt;
+            }
+#pragma unroll
+            for (int pl = 0; pl < PL; ++pl) piece[pl] |= ((code >> pl) & 1u) << (8 * k + r);
+          }
+          if (EKIND == E_QUANT && a.resid_out != nullptr) {
+            const int m = mb + 8 * k + 4 * h;
+            if (valid && m < a.M)
+              *reinterpret_cast<float4*>(a.resid_out + (vec_base + i) * (int64_t)a.d + m) =
+                  make_float4(e[0], e[1], e[2], e[3]);
+          }
+        }
+        // merge the two half-waves (rows 8k+r and 8k+4+r) and let half tm&1 store
+#pragma unroll
+        for (int pl = 0; pl < PL; ++pl) {
+          uint32_t w = piece[pl] << (4 * h);
+          w |= (uint32_t)__shfl_xor((int)w, 32);
+          const int g = mb >> 5;
+          if (valid && mb < a.M && h == (tm & 1))
+            a.words_out[(vec_base + i) * (int64_t)(kt_per_seg * PL) + g * PL + pl] = w;
+        }
+      }
+    }
+  }
+}
+
+template <int NKIND, int EKIND, int BITS>
+static hipError_t launch_one(const GemmArgs& a, int n_groups, hipStream_t stream) {
+  const int tiles_m = (a.M + TM - 1) / TM;
+  const int64_t tiles_n64 = (a.n + TN - 1) / TN;
+  if (tiles_n64 * tiles_m > (int64_t)1 << 30) return hipErrorInvalidValue;
+  const int tiles_n = (int)tiles_n64;
+  const int total = tiles_m * tiles_n;
+  if (total == 0 || n_groups == 0) return hipSuccess;
+  const int per_xcd = (total + XCDS - 1) / XCDS;
+  dim3 grid(per_xcd * XCDS, n_groups, 1);
+  hipLaunchKernelGGL((gemm_kernel<NKIND, EKIND, BITS>), grid, dim3(256), 0, stream, a, tiles_m,
+                     tiles_n, per_xcd);
+  return hipGetLastError();
+}
+
+template <int NKIND, int EKIND>
+static hipError_t launch_bits(int bits, const GemmArgs& a, int g, hipStream_t s) {
+  switch (bits) {
+    case 0: return launch_one<NKIND, EKIND, 0>(a, g, s);
+    case 1: return launch_one<NKIND, EKIND, 1>(a, g, s);
+    case 2: return launch_one<NKIND, EKIND, 2>(a, g, s);
+    case 3: return launch_one<NKIND, EKIND, 3>(a, g, s);
+    case 4: return launch_one<NKIND, EKIND, 4>(a, g, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_gemm(NKind nk, EKind ek, int bits, const GemmArgs& a, int n_groups,
+                       hipStream_t stream) {
+  // only the combinations the library uses are instantiated
+  if (nk == N_F32 && ek == E_QUANT) return launch_bits<N_F32, E_QUANT>(bits, a, n_groups, stream);
+  if (nk == N_BF16 && ek == E_QUANT) return launch_bits<N_BF16, E_QUANT>(bits, a, n_groups, stream);
+  if (nk == N_F32 && ek == E_SIGN) return launch_one<N_F32, E_SIGN, 0>(a, n_groups, stream);
+  if (nk == N_F32 && ek == E_STORE_T) return launch_one<N_F32, E_STORE_T, 0>(a, n_groups, stream);
+  if (nk == N_CODE && ek == E_STORE_T) return launch_bits<N_CODE, E_STORE_T>(bits, a, n_groups, stream);
+  if (nk == N_CODE && ek == E_STORE_N) return launch_bits<N_CODE, E_STORE_N>(bits, a, n_groups, stream);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace tq

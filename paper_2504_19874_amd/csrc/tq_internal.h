@@ -1,0 +1,81 @@
+// Internal declarations shared by the HIP translation units of the library.
+// Nothing here is part of the C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/turboquant.h"
+
+namespace tq {
+
+// Codebook of Alg. 1 passed to kernels by value (lives in scalar registers).
+struct Codebook {
+  float c[16];  // centroids, ascending
+  float t[15];  // cell boundaries: midpoints of consecutive centroids
+  int bits;
+};
+
+// ---------------------------------------------------------------------------
+// The one contraction kernel.  It computes, for a block of "vectors" i (the
+// N side) and a block of "rows" m (the M side),
+//     D[m][i] = sum_k W[m][k] * V[i][k],        k over one or two segments,
+// with both operands contiguous along k, using v_mfma_f32_32x32x2_f32.
+// What V is and what happens to D are template choices:
+//   V:  fp32 rows / bf16 rows (optionally unit-normalised on the fly) or
+//       packed codes decoded on the fly (centroid values, then +-kappa*gamma)
+//   D:  stored transposed (out[i][m]) or plain (out[m][i]), or turned into
+//       packed indices (nearest centroid + bit planes) or packed signs.
+// ---------------------------------------------------------------------------
+enum NKind { N_F32 = 0, N_BF16 = 1, N_CODE = 2 };
+enum EKind { E_STORE_T = 0, E_STORE_N = 1, E_QUANT = 2, E_SIGN = 3 };
+
+struct GemmArgs {
+  // M side: W1 (segment 1) and W2 (segment 2), row stride ldw, M rows per group
+  const float* W1;
+  const float* W2;
+  int64_t ldw;
+  int64_t w_group_stride;  // elements between the W rows of consecutive groups
+  int M;
+  // K: d per segment
+  int d;
+  int segs;
+  // N side
+  const void* X;  // fp32 or bf16 rows
+  int64_t ldx;
+  int64_t n;                // vectors per group
+  const uint32_t* idx;      // codes: n_groups*n rows
+  const uint32_t* qjl;
+  const float* gamma;
+  const float* scale_in;    // per-vector factor applied to stored D (norm), nullable
+  int normalise;            // fp32/bf16 rows: divide by the row's L2 norm
+  float* rownorm_out;       // sqrt(sum of squares of the streamed row), nullable
+  // outputs
+  float* out;
+  int64_t ldo;
+  int64_t out_group_stride;
+  uint32_t* words_out;
+  float* resid_out;  // E_QUANT: y - c[idx], n rows of d floats, nullable
+  float kappa;       // sqrt(pi/2)/d
+  Codebook cb;
+};
+
+hipError_t launch_gemm(NKind nk, EKind ek, int bits, const GemmArgs& a, int n_groups,
+                       hipStream_t stream);
+
+// codec stages
+hipError_t launch_stage_pack(const Codebook& cb, int d, const float* y, int64_t n, uint32_t* idx,
+                             hipStream_t stream);
+hipError_t launch_stage_sign_pack(int d, const float* u, int64_t n, uint32_t* qjl,
+                                  hipStream_t stream);
+hipError_t launch_stage_unpack(const Codebook& cb, int d, const uint32_t* idx, int64_t n,
+                               float* y_tilde, hipStream_t stream);
+
+// out[c][r] = in[r][c] for a d x d matrix
+hipError_t launch_transpose(int d, const float* in, float* out, hipStream_t stream);
+
+// per-row top-k of scores[rows][ld] over the first n columns
+hipError_t launch_topk(const float* scores, int64_t rows, int64_t n, int64_t ld, int k,
+                       int32_t* out_idx, float* out_val, hipStream_t stream);
+
+}  // namespace tq

@@ -1,0 +1,129 @@
+// Per-query top-k over a row of scores (the "return top-10" step of the ANN
+// configurations).  One workgroup per row: every thread keeps its own sorted
+// list of the k best (value, index) it has seen while striding over the row,
+// then the 256 lists are merged by k rounds of a workgroup-wide arg-max.
+// Order: larger score first; equal scores by lower index.
+#include "tq_internal.h"
+
+namespace tq {
+
+__device__ __forceinline__ bool better(float va, int ia, float vb, int ib) {
+  return va > vb || (va == vb && ia < ib);
+}
+
+template <int KMAX>
+__global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ scores, const int64_t n,
+                                                   const int64_t ld, const int k,
+                                                   int32_t* __restrict__ out_idx,
+                                                   float* __restrict__ out_val) {
+  extern __shared__ unsigned char smem_raw[];
+  float* cand_v = reinterpret_cast<float*>(smem_raw);            // [256 * k]
+  int* cand_i = reinterpret_cast<int*>(cand_v + 256 * k);        // [256 * k]
+  __shared__ float red_v[4];
+  __shared__ int red_i[4];
+  __shared__ int red_slot[4];
+
+  const int tid = threadIdx.x;
+  const float* row = scores + (int64_t)blockIdx.x * ld;
+  const float NEG = -__builtin_inff();
+
+  float bv[KMAX];
+  int bi[KMAX];
+#pragma unroll
+  for (int j = 0; j < KMAX; ++j) {
+    bv[j] = NEG;
+    bi[j] = 0x7fffffff;
+  }
+  for (int64_t i = tid; i < n; i += 256) {
+    float v = row[i];
+    int id = (int)i;
+    // position k-1 holds this thread's current worst kept entry
+    bool take = false;
+#pragma unroll
+    for (int j = 0; j < KMAX; ++j)
+      if (j == k - 1) take = better(v, id, bv[j], bi[j]);
+    if (take) {
+      // insert by a single pass of compare-exchange from the top
+#pragma unroll
+      for (int j = 0; j < KMAX; ++j) {
+        if (j < k && better(v, id, bv[j], bi[j])) {
+          const float tv = bv[j];
+          const int ti = bi[j];
+          bv[j] = v;
+          bi[j] = id;
+          v = tv;
+          id = ti;
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < KMAX; ++j)
+    if (j < k) {
+      cand_v[tid * k + j] = bv[j];
+      cand_i[tid * k + j] = bi[j];
+    }
+  __syncthreads();
+
+  // k rounds: each thread's list is sorted, so its best remaining entry is at
+  // its own cursor; the workgroup picks the best of the 256 cursors.
+  int cursor = 0;
+  for (int r = 0; r < k; ++r) {
+    float v = (cursor < k) ? cand_v[tid * k + cursor] : NEG;
+    int id = (cursor < k) ? cand_i[tid * k + cursor] : 0x7fffffff;
+    int who = tid;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      const float ov = __shfl_xor(v, off);
+      const int oi = __shfl_xor(id, off);
+      const int ow = __shfl_xor(who, off);
+      if (better(ov, oi, v, id)) {
+        v = ov;
+        id = oi;
+        who = ow;
+      }
+    }
+    if ((tid & 63) == 0) {
+      red_v[tid >> 6] = v;
+      red_i[tid >> 6] = id;
+      red_slot[tid >> 6] = who;
+    }
+    __syncthreads();
+    float fv = red_v[0];
+    int fi = red_i[0], fw = red_slot[0];
+#pragma unroll
+    for (int w = 1; w < 4; ++w)
+      if (better(red_v[w], red_i[w], fv, fi)) {
+        fv = red_v[w];
+        fi = red_i[w];
+        fw = red_slot[w];
+      }
+    if (tid == fw) ++cursor;
+    if (tid == 0) {
+      out_idx[(int64_t)blockIdx.x * k + r] = (fi == 0x7fffffff) ? -1 : fi;
+      if (out_val != nullptr) out_val[(int64_t)blockIdx.x * k + r] = fv;
+    }
+    __syncthreads();
+  }
+}
+
+hipError_t launch_topk(const float* scores, int64_t rows, int64_t n, int64_t ld, int k,
+                       int32_t* out_idx, float* out_val, hipStream_t stream) {
+  if (rows == 0 || k == 0) return hipSuccess;
+  if (k < 1 || k > 64 || rows > 0x7fffffff || n > 0x7fffffff) return hipErrorInvalidValue;
+  const size_t smem = (size_t)256 * k * 8;
+  if (k <= 16)
+    hipLaunchKernelGGL((topk_kernel<16>), dim3((unsigned)rows), dim3(256), smem, stream, scores, n, ld, k,
+                       out_idx, out_val);
+  else {
+    // more than 64 KB of dynamic LDS has to be allowed explicitly
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&topk_kernel<64>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((topk_kernel<64>), dim3((unsigned)rows), dim3(256), smem, stream, scores, n, ld, k,
+                       out_idx, out_val);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace tq

@@ -1,0 +1,121 @@
+"""CPU-side checks of the boundary: the shared library loads, exports every
+symbol the header declares, builds the same codebook as the oracle, and
+rejects bad arguments with a status code before touching the GPU."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import turboquant_oracle as o
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2504_19874_amd import _lib
+    if not os.path.exists(_lib.LIB_PATH):
+        from paper_2504_19874_amd import build
+        build.build_library(verbose=False)
+    return _lib.load()
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "turboquant.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tq_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported_and_bound(lib):
+    from paper_2504_19874_amd import _lib
+    names = header_functions()
+    assert {"tq_build_codebook", "tq_quantize_mse", "tq_quantize_prod", "tq_dequantize", "tq_score"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in the header but not exported"
+        assert n in _lib.SIGNATURES, f"{n} has no ctypes signature"
+    assert set(_lib.SIGNATURES) == set(names)
+
+
+def test_params_struct_matches_header_layout():
+    from paper_2504_19874_amd import _lib
+    assert C.sizeof(_lib.TqParams) == 8 + 9 * 8
+    assert _lib.TqParams.Pi.offset == 8 and _lib.TqParams.workspace_bytes.offset == 72
+
+
+@pytest.mark.parametrize("d,bits", [(3, 2), (8, 3), (128, 1), (128, 2), (128, 3), (128, 4), (1536, 4), (3072, 1), (200, 5)])
+def test_codebook_builder_matches_oracle(lib, d, bits):
+    import paper_2504_19874_amd as tq
+    c, t, cost = tq.tq_build_codebook(d, bits)
+    c64, t64, cost_o = o.lloyd_max_codebook(d, bits)
+    assert np.max(np.abs(c - c64)) < 1e-7 / np.sqrt(d) and np.max(np.abs(t - t64)) < 1e-7 / np.sqrt(d)
+    assert np.array_equal(c, c64.astype(np.float32)) and np.array_equal(t, t64.astype(np.float32))
+    assert abs(cost / cost_o - 1) < 1e-8
+    assert np.array_equal(c, -c[::-1])
+
+
+def test_codebook_builder_rejects_bad_arguments(lib):
+    buf = (C.c_float * 256)()
+    assert lib.tq_build_codebook(2, 1, buf, buf, None) == 1
+    assert lib.tq_build_codebook(128, 9, buf, buf, None) == 1
+    assert lib.tq_build_codebook(128, 2, None, buf, None) == 1
+    assert lib.tq_build_codebook(128, 0, buf, None, None) == 0 and buf[0] == 0.0
+    assert lib.tq_status_string(0) == b"TQ_OK" and lib.tq_status_string(2) == b"TQ_ERR_UNSUPPORTED"
+
+
+def test_entry_points_validate_before_launching(lib):
+    from paper_2504_19874_amd import _lib
+    c = np.zeros(4, dtype=np.float32)
+    t = np.zeros(3, dtype=np.float32)
+    p = _lib.TqParams()
+    p.d, p.bits_mse = 100, 2  # not a multiple of 32
+    p.centroids, p.bounds = c.ctypes.data, t.ctypes.data
+    assert lib.tq_quantize_mse(C.byref(p), None, 0, 4, 100, None, None, None) == 2
+    p.d = 128
+    assert lib.tq_quantize_mse(C.byref(p), None, 0, 4, 128, None, None, None) == 1  # NULL x
+    assert lib.tq_quantize_mse(C.byref(p), None, 0, -1, 128, None, None, None) == 1
+    assert lib.tq_quantize_mse(C.byref(p), None, 7, 4, 128, None, None, None) == 1   # bad dtype
+    assert lib.tq_quantize_mse(C.byref(p), None, 0, 0, 128, None, None, None) == 0   # empty input is fine
+    p.bits_mse = 5
+    assert lib.tq_dequantize(C.byref(p), None, None, None, None, 1, None, 128, None) == 2
+    p.bits_mse = 2
+    assert lib.tq_dequantize(C.byref(p), None, None, None, None, 1, None, 128, None) == 1
+    assert lib.tq_score(C.byref(p), None, 128, 1, 1, None, None, None, None, 10, None, 10, 0, None, None, None) == 1
+    assert lib.tq_score(C.byref(p), None, 128, 1, 1, None, None, None, None, 10, None, 10, 65, None, None, None) == 2
+    assert lib.tq_stage_sign_pack(100, None, 1, None, None) == 2
+    assert lib.tq_workspace_bytes(C.byref(p), 1000, 10, 0) >= 1000 * 128 * 4 + 2 * 10 * 128 * 4
+    assert lib.tq_derive_params(128, None, None, None, None, None, None) == 1
+
+
+def test_rotation_helper_agrees_with_oracle_reading():
+    import paper_2504_19874_amd as tq
+    G = W.gaussian_matrix(96, 42)
+    a = tq.rotation_from_gaussian(G).numpy()
+    b = o.rotation_from_gaussian(G)
+    assert np.max(np.abs(a.astype(np.float64) - b.astype(np.float64))) < 1e-6
+    R = a.astype(np.float64).T @ G
+    assert np.all(np.diag(R) > 0) and np.max(np.abs(np.tril(R, -1))) < 1e-5
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    from paper_2504_19874_amd import _lib
+    monkeypatch.setattr(_lib, "_lib", None)
+    monkeypatch.setattr(_lib, "LIB_PATH", "/nonexistent/libturboquant.so")
+    with pytest.raises(RuntimeError, match="no CPU or PyTorch fallback"):
+        _lib.load()
+
+
+def test_workload_generators_are_seeded_and_shaped():
+    a = W.kv_keys_chunk(1, 0, 300, 128, 2, W.kv_outlier_channels(8, 128, 2))
+    b = W.kv_keys(2, 300, 128, 2)[1]
+    assert a.dtype == np.uint16 and np.array_equal(a, b)
+    v = o.bf16_bits_to_f64(a)
+    out = W.kv_outlier_channels(8, 128, 2)[1]
+    assert v[:, out].std() > 10 and np.delete(v, out, axis=1).std() < 1.2
+    c = W.mixture_centers(64, 4)
+    m1 = W.mixture_chunk(0, 100, 64, 4, c)
+    m2 = W.mixture_chunk(0, 50, 64, 4, c)
+    assert np.allclose(np.linalg.norm(m1, axis=1), 1, atol=1e-6) and m1.dtype == np.float32
+    assert W.CONFIGS["C5"].bits_mse == 1 and W.CONFIGS["C4"].bits_mse == 4

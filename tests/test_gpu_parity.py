@@ -1,0 +1,304 @@
+"""GPU parity tests: every C-ABI entry point against the CPU oracle on the same
+seeded inputs.  Sizes here are small enough for the oracle to finish in
+seconds yet span several 128-row tiles and ragged tails."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import turboquant_oracle as o
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+tq = pytest.importorskip("paper_2504_19874_amd")
+
+DEV = "cuda"
+
+
+def dev(a, dtype=None):
+    t = torch.as_tensor(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.to(DEV)
+
+
+def bf16_tensor(bits_u16):
+    return torch.as_tensor(np.ascontiguousarray(bits_u16).view(np.int16)).view(torch.bfloat16).to(DEV)
+
+
+_cache = {}
+
+
+def setup(d, bits_mse, prod, seed_pi=100, seed_s=200):
+    key = (d, bits_mse, prod, seed_pi, seed_s)
+    if key not in _cache:
+        Pi = o.rotation_from_gaussian(W.gaussian_matrix(d, seed_pi))
+        S = W.sketch_matrix(d, seed_s) if prod else None
+        c32, t32, _ = o.codebook_fp32(d, bits_mse)
+        p = tq.Params(d, bits_mse, torch.from_numpy(Pi), None if S is None else torch.from_numpy(S), c32, t32)
+        _cache[key] = (p, Pi, S, c32, t32)
+    return _cache[key]
+
+
+def words(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+# ------------------------------------------------------------------ setup
+
+
+def test_library_codebook_equals_oracle_tables():
+    for d, b in [(128, 2), (128, 3), (1536, 4), (3072, 1)]:
+        c, t, cost = tq.tq_build_codebook(d, b)
+        c32, t32, cost_o = o.codebook_fp32(d, b)
+        assert np.array_equal(c, c32) and np.array_equal(t, t32) and abs(cost / cost_o - 1) < 1e-8
+
+
+@pytest.mark.parametrize("d", [64, 128, 352])
+def test_derived_parameters(d):
+    p, Pi, S, _, _ = setup(d, 2, True)
+    torch.cuda.synchronize()
+    assert np.array_equal(p.PiT.cpu().numpy(), Pi.T)
+    assert np.array_equal(p.ST.cpu().numpy(), S.T)
+    want = S.astype(np.float64) @ Pi.astype(np.float64).T
+    P.check_close(p.SPiT.cpu().numpy(), want, np.linalg.norm(S, axis=1)[:, None] / math.sqrt(d), "S Pi^T", rel=2e-6)
+
+
+# ------------------------------------------------------------------ codec stages (bit exact)
+
+
+@pytest.mark.parametrize("d,bits,n", [(128, 2, 4096), (128, 1, 7), (96, 3, 129), (1536, 4, 513), (32, 4, 1),
+                                      (3072, 1, 70), (160, 3, 1000)])
+def test_stage_pack_bit_exact(d, bits, n):
+    p, Pi, _, c32, t32 = setup(d, bits, False)
+    x = W.unit_gaussian_rows(n, d, 40 + bits)
+    y = o.rotate(x, Pi)
+    # plant coordinates exactly on, just below and just above every boundary
+    flat = y.reshape(-1)
+    k = 0
+    for t in t32:
+        for v in (t, np.nextafter(t, np.float32(-1)), np.nextafter(t, np.float32(1))):
+            flat[(k * 37) % flat.size] = v
+            k += 1
+    want = o.pack_planes(o.nearest_centroid(y, t32), bits)
+    out = torch.zeros((n, p.idx_words), dtype=torch.int32, device=DEV)
+    tq.tq_stage_pack(p, dev(y), out)
+    assert np.array_equal(words(out), want)
+
+
+@pytest.mark.parametrize("d,n", [(128, 1000), (96, 3), (3072, 65)])
+def test_stage_sign_pack_bit_exact(d, n):
+    rng = np.random.default_rng(d + n)
+    u = rng.standard_normal((n, d)).astype(np.float32)
+    u.reshape(-1)[::17] = 0.0
+    u.reshape(-1)[5::19] = -0.0
+    out = torch.zeros((n, d // 32), dtype=torch.int32, device=DEV)
+    tq.tq_stage_sign_pack(d, dev(u), out)
+    assert np.array_equal(words(out), o.pack_signs(u >= 0))
+
+
+@pytest.mark.parametrize("d,bits,n", [(128, 2, 777), (1536, 4, 130), (64, 3, 5), (128, 0, 9)])
+def test_stage_unpack_exact(d, bits, n):
+    p, _, _, c32, _ = setup(d, bits, False)
+    rng = np.random.default_rng(bits)
+    idx = rng.integers(0, 1 << bits, size=(n, d)).astype(np.int32)
+    w = o.pack_planes(idx, bits)
+    out = torch.zeros((n, d), dtype=torch.float32, device=DEV)
+    tq.tq_stage_unpack(p, dev(w.view(np.int32)) if bits else None, out)
+    assert np.array_equal(out.cpu().numpy(), c32[idx])
+
+
+# ------------------------------------------------------------------ quantize
+
+
+def _quant_inputs(n, d, kind, seed):
+    x = W.unit_gaussian_rows(n, d, seed)
+    if kind == "unit":
+        return x, dev(x), False
+    x = (x.astype(np.float64) * np.exp(np.random.default_rng(seed).normal(0, 1.5, size=(n, 1)))).astype(np.float32)
+    if n > 3:
+        x[3] = 0.0  # a zero vector
+    if kind == "f32":
+        return x, dev(x), True
+    bits16 = W.f32_to_bf16_bits(x)
+    return o.bf16_bits_to_f64(bits16), bf16_tensor(bits16), True
+
+
+@pytest.mark.parametrize("d,bits,n,kind", [
+    (128, 2, 4096, "unit"), (128, 1, 300, "f32"), (128, 3, 129, "bf16"), (128, 4, 1, "f32"),
+    (256, 4, 515, "unit"), (96, 2, 257, "f32"), (1536, 4, 300, "unit"), (3072, 1, 140, "bf16"),
+    (64, 0, 40, "f32"),
+])
+def test_quantize_mse(d, bits, n, kind):
+    p, Pi, _, c32, t32 = setup(d, bits, False)
+    x_or, x_dev, normalise = _quant_inputs(n, d, kind, 7 * d + bits)
+    idx_or, nu_or, y_or = o.quant_mse(x_or, Pi, t32, normalise)
+    idx = torch.zeros((n, max(1, p.idx_words)), dtype=torch.int32, device=DEV)
+    norm = torch.zeros(n, dtype=torch.float32, device=DEV) if normalise else None
+    tq.tq_quantize_mse(p, x_dev, idx, norm)
+    if bits:
+        got = o.unpack_planes(words(idx)[:, : p.idx_words], bits, d)
+        P.check_indices(got, idx_or, y_or, t32)
+    if normalise:
+        P.check_close(norm.cpu().numpy(), nu_or, 0.0, "norm", rel=1e-6)
+
+
+def _run_prod(p, x_dev, n, normalise):
+    idx = torch.zeros((n, max(1, p.idx_words)), dtype=torch.int32, device=DEV)
+    qjl = torch.zeros((n, p.qjl_words), dtype=torch.int32, device=DEV)
+    gamma = torch.zeros(n, dtype=torch.float32, device=DEV)
+    norm = torch.zeros(n, dtype=torch.float32, device=DEV) if normalise else None
+    p.reserve(n, 0, 0)
+    tq.tq_quantize_prod(p, x_dev, idx, qjl, gamma, norm)
+    return idx, qjl, gamma, norm
+
+
+def _check_prod(p, Pi, S, c32, t32, x_or, normalise, idx, qjl, gamma, norm):
+    d, bits = p.d, p.bits_mse
+    xh, nu_or = o.unit_normalise(x_or, normalise)
+    y_or = o.rotate(xh, Pi)
+    idx_or = o.nearest_centroid(y_or, t32)
+    got = o.unpack_planes(words(idx)[:, : p.idx_words], bits, d) if bits else np.zeros_like(idx_or)
+    if bits:
+        P.check_indices(got, idx_or, y_or, t32)
+    # downstream of the GPU's own indices (teacher forcing)
+    r, gamma_or, u_or = o.residual_and_sketch(xh, got, Pi, S, c32)
+    P.check_close(gamma.cpu().numpy(), gamma_or, 0.0, "gamma", rel=1e-5)
+    s_norm = np.linalg.norm(S.astype(np.float64), axis=1)
+    P.check_signs(o.unpack_signs(words(qjl), d), u_or, s_norm[None, :] * gamma_or[:, None])
+    if normalise:
+        P.check_close(norm.cpu().numpy(), nu_or, 0.0, "norm", rel=1e-6)
+    return got, gamma_or
+
+
+@pytest.mark.parametrize("d,bits_mse,n,kind", [
+    (128, 2, 2000, "bf16"), (128, 3, 129, "f32"), (128, 1, 4096, "unit"), (128, 0, 100, "f32"),
+    (256, 2, 300, "unit"), (1536, 1, 200, "unit"), (96, 4, 130, "f32"),
+])
+def test_quantize_prod(d, bits_mse, n, kind):
+    p, Pi, S, c32, t32 = setup(d, bits_mse, True)
+    x_or, x_dev, normalise = _quant_inputs(n, d, kind, 11 * d + bits_mse)
+    out = _run_prod(p, x_dev, n, normalise)
+    _check_prod(p, Pi, S, c32, t32, x_or, normalise, *out)
+
+
+def test_quantize_is_deterministic_and_respects_row_stride():
+    d, n = 128, 1000
+    p, Pi, S, c32, t32 = setup(d, 2, True)
+    x = W.unit_gaussian_rows(n, d, 5)
+    xd = dev(x)
+    a = _run_prod(p, xd, n, True)
+    b = _run_prod(p, xd, n, True)
+    for u, v in zip(a, b):
+        assert torch.equal(u, v)
+    wide = torch.zeros((n, d + 64), dtype=torch.float32, device=DEV)
+    wide[:, :d] = xd
+    idx = torch.zeros((n, p.idx_words), dtype=torch.int32, device=DEV)
+    qjl = torch.zeros((n, p.qjl_words), dtype=torch.int32, device=DEV)
+    gamma = torch.zeros(n, dtype=torch.float32, device=DEV)
+    norm = torch.zeros(n, dtype=torch.float32, device=DEV)
+    import ctypes as C
+    from paper_2504_19874_amd import _lib
+    st = _lib.load().tq_quantize_prod(C.byref(p.c), wide.data_ptr(), 0, n, d + 64, idx.data_ptr(), qjl.data_ptr(),
+                                      gamma.data_ptr(), norm.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    assert st == 0
+    assert torch.equal(idx, a[0]) and torch.equal(qjl, a[1]) and torch.equal(gamma, a[2])
+
+
+def test_empty_and_error_paths():
+    d = 128
+    p, *_ = setup(d, 2, True)
+    e = torch.zeros((0, d), dtype=torch.float32, device=DEV)
+    tq.tq_quantize_mse(p, e, torch.zeros((0, p.idx_words), dtype=torch.int32, device=DEV), None)
+    tq.tq_dequantize(p, torch.zeros((0, p.idx_words), dtype=torch.int32, device=DEV), None, None, None, e)
+    with pytest.raises(tq.TurboQuantError, match="WORKSPACE"):
+        p2 = tq.Params(d, 2, p.Pi, p.S, p.centroids, p.bounds)
+        x = dev(W.unit_gaussian_rows(8, d, 1))
+        tq.tq_quantize_prod(p2, x, torch.zeros((8, 8), dtype=torch.int32, device=DEV),
+                            torch.zeros((8, 4), dtype=torch.int32, device=DEV),
+                            torch.zeros(8, dtype=torch.float32, device=DEV), None)
+
+
+# ------------------------------------------------------------------ dequantize / score / top-k
+
+
+@pytest.mark.parametrize("d,bits_mse,n,prod,with_norm", [
+    (128, 2, 1000, True, True), (128, 4, 129, False, False), (256, 3, 260, True, False),
+    (1536, 4, 150, False, True), (128, 0, 64, True, True), (96, 1, 131, True, True),
+])
+def test_dequantize(d, bits_mse, n, prod, with_norm):
+    p, Pi, S, c32, t32 = setup(d, bits_mse, prod)
+    rng = np.random.default_rng(d + n)
+    idx = rng.integers(0, 1 << bits_mse, size=(n, d)).astype(np.int32)
+    z = rng.integers(0, 2, size=(n, d)).astype(bool)
+    gamma = rng.uniform(0.05, 0.6, size=n).astype(np.float32)
+    norm = np.exp(rng.normal(0, 1, size=n)).astype(np.float32) if with_norm else None
+    idx_w = dev(o.pack_planes(idx, bits_mse).view(np.int32)) if bits_mse else None
+    out = torch.zeros((n, d), dtype=torch.float32, device=DEV)
+    if prod:
+        want = o.dequant_prod(idx, z, gamma, Pi, S, c32, norm)
+        tq.tq_dequantize(p, idx_w, dev(o.pack_signs(z).view(np.int32)), dev(gamma), None if norm is None else dev(norm), out)
+    else:
+        want = o.dequant_mse(idx, Pi, c32, norm)
+        tq.tq_dequantize(p, idx_w, None, None, None if norm is None else dev(norm), out)
+    scale = (np.ones(n) if norm is None else norm.astype(np.float64))[:, None] / math.sqrt(d)
+    P.check_close(out.cpu().numpy(), want, scale, "dequantized coordinate")
+
+
+@pytest.mark.parametrize("d,bits_mse,prod,n_groups,qpg,npg,topk", [
+    (128, 2, True, 8, 4, 1000, 0), (128, 2, False, 1, 64, 4096, 10), (128, 3, True, 2, 4, 129, 5),
+    (256, 4, False, 1, 130, 300, 10), (1536, 4, False, 1, 33, 257, 10), (128, 0, True, 1, 7, 100, 3),
+])
+def test_score_and_topk(d, bits_mse, prod, n_groups, qpg, npg, topk):
+    p, Pi, S, c32, t32 = setup(d, bits_mse, prod)
+    n, nq = n_groups * npg, n_groups * qpg
+    rng = np.random.default_rng(d + npg)
+    idx = rng.integers(0, 1 << bits_mse, size=(n, d)).astype(np.int32)
+    z = rng.integers(0, 2, size=(n, d)).astype(bool)
+    gamma = rng.uniform(0.05, 0.6, size=n).astype(np.float32)
+    norm = np.exp(rng.normal(0, 1, size=n)).astype(np.float32)
+    q = W.gaussian_queries(nq, d, 3, unit=False)
+    xt = o.dequant_prod(idx, z, gamma, Pi, S, c32, norm) if prod else o.dequant_mse(idx, Pi, c32, norm)
+    want = np.concatenate([o.score(q[g * qpg:(g + 1) * qpg], xt[g * npg:(g + 1) * npg]) for g in range(n_groups)])
+    idx_w = dev(o.pack_planes(idx, bits_mse).view(np.int32)) if bits_mse else None
+    qjl_w = dev(o.pack_signs(z).view(np.int32)) if prod else None
+    scores = torch.zeros((nq, npg), dtype=torch.float32, device=DEV)
+    ti = torch.zeros((nq, max(1, topk)), dtype=torch.int32, device=DEV)
+    tv = torch.zeros((nq, max(1, topk)), dtype=torch.float32, device=DEV)
+    p.reserve(n, nq, topk)
+    tq.tq_score(p, dev(q), n_groups, qpg, idx_w, qjl_w, dev(gamma) if prod else None, dev(norm), npg, scores,
+                topk, ti if topk else None, tv if topk else None)
+    qn = np.linalg.norm(q.astype(np.float64), axis=1)
+    scale = np.concatenate([qn[g * qpg:(g + 1) * qpg, None] * norm[None, g * npg:(g + 1) * npg] for g in range(n_groups)])
+    got = scores.cpu().numpy()
+    P.check_close(got, want, scale, "score")
+    if topk:
+        # exact against the GPU's own score matrix, tolerant against the oracle's
+        ref = o.topk(got, topk)
+        assert np.array_equal(ti.cpu().numpy(), ref)
+        assert np.array_equal(tv.cpu().numpy(), np.take_along_axis(got, ref, axis=1))
+        P.check_topk(ti.cpu().numpy(), want, topk, scale.max(axis=1))
+        # top-k without a score buffer gives the same answer
+        ti2 = torch.zeros_like(ti)
+        tq.tq_score(p, dev(q), n_groups, qpg, idx_w, qjl_w, dev(gamma) if prod else None, dev(norm), npg, None,
+                    topk, ti2, None)
+        assert torch.equal(ti, ti2)
+
+
+def test_score_equals_inner_product_with_dequantized_vectors():
+    d, n, nq = 128, 500, 9
+    p, Pi, S, c32, t32 = setup(d, 2, True)
+    x = W.kv_keys_chunk(0, 0, n, d, 2, W.kv_outlier_channels(8, d, 2))
+    idx, qjl, gamma, norm = _run_prod(p, bf16_tensor(x), n, True)
+    q = dev(W.gaussian_queries(nq, d, 3, unit=False))
+    xt = torch.zeros((n, d), dtype=torch.float32, device=DEV)
+    tq.tq_dequantize(p, idx, qjl, gamma, norm, xt)
+    s = torch.zeros((nq, n), dtype=torch.float32, device=DEV)
+    p.reserve(n, nq, 0)
+    tq.tq_score(p, q, 1, nq, idx, qjl, gamma, norm, n, s)
+    want = q.double().cpu().numpy() @ xt.double().cpu().numpy().T
+    scale = np.linalg.norm(q.cpu().numpy(), axis=1)[:, None] * norm.cpu().numpy()[None, :]
+    P.check_close(s.cpu().numpy(), want, scale, "score vs <q, dequantized>")
