@@ -143,7 +143,7 @@ def test_quantize_mse(d, bits, n, kind):
         got = o.unpack_planes(words(idx)[:, : p.idx_words], bits, d)
         P.check_indices(got, idx_or, y_or, t32)
     if normalise:
-        P.check_close(norm.cpu().numpy(), nu_or, 0.0, "norm", rel=1e-6)
+        P.check_close(norm.cpu().numpy(), nu_or, 0.0, "norm", rel=2e-6)
 
 
 def _run_prod(p, x_dev, n, normalise):
@@ -170,7 +170,7 @@ def _check_prod(p, Pi, S, c32, t32, x_or, normalise, idx, qjl, gamma, norm):
     s_norm = np.linalg.norm(S.astype(np.float64), axis=1)
     P.check_signs(o.unpack_signs(words(qjl), d), u_or, s_norm[None, :] * gamma_or[:, None])
     if normalise:
-        P.check_close(norm.cpu().numpy(), nu_or, 0.0, "norm", rel=1e-6)
+        P.check_close(norm.cpu().numpy(), nu_or, 0.0, "norm", rel=2e-6)
     return got, gamma_or
 
 
