@@ -71,6 +71,13 @@ tq_status quantize_common(const tq_params* p, const void* x, tq_dtype dtype, int
   const size_t esz = dtype == TQ_F32 ? 4 : 2;
   const int words_per_row = (d / 32) * p->bits_mse;
 
+  // head dimension 128: one fused kernel, parameters resident in LDS
+  if (d == 128 && aligned16(x) && (ldx * esz) % 16 == 0) {
+    return from_hip(launch_quant128(p->bits_mse, prod, dtype == TQ_BF16, x, ldx, n, p->Pi,
+                                    prod ? p->SPiT : nullptr, idx, qjl, gamma, norm, make_codebook(p),
+                                    stream));
+  }
+
   GemmArgs a;
   std::memset(&a, 0, sizeof(a));
   a.W1 = p->Pi;
@@ -212,6 +219,11 @@ tq_status tq_dequantize(const tq_params* p, const uint32_t* idx, const uint32_t*
   if (prod && (gamma == nullptr || p->ST == nullptr)) return TQ_ERR_INVALID_ARG;
   if (ldo % 4 != 0 || !aligned16(x_out) || !aligned16(p->PiT) || (prod && !aligned16(p->ST)))
     return TQ_ERR_UNSUPPORTED;
+  if (p->d == 128 && p->Pi != nullptr && aligned16(p->Pi) && (!prod || (p->S != nullptr && aligned16(p->S))) &&
+      aligned16(idx) && (!prod || aligned16(qjl))) {
+    return from_hip(launch_dequant128(p->bits_mse, prod, idx, qjl, gamma, norm, p->Pi, p->S, x_out, ldo, n,
+                                      kappa_of(p->d), make_codebook(p), static_cast<hipStream_t>(stream)));
+  }
   GemmArgs a;
   std::memset(&a, 0, sizeof(a));
   a.W1 = p->PiT;  // x~[k] = sum_j Pi[j][k] y~[j]: rows of Pi^T against the decoded code
@@ -265,7 +277,10 @@ tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_gr
   }
 
   // queries into the rotated basis and the sketch basis: Pi q and S q
-  {
+  if (nq <= 64) {
+    if (launch_matvec_small(d, (int)nq, p->Pi, prod ? p->S : nullptr, q, ldq, qr, qs, s) != hipSuccess)
+      return TQ_ERR_HIP;
+  } else {
     GemmArgs a;
     std::memset(&a, 0, sizeof(a));
     a.W1 = p->Pi;
@@ -285,7 +300,14 @@ tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_gr
       if (launch_gemm(N_F32, E_STORE_T, 0, a, 1, s) != hipSuccess) return TQ_ERR_HIP;
     }
   }
-  if (n_per_group > 0) {
+  const bool small = q_per_group <= 32 && d % 128 == 0 && d <= 1024 && aligned16(idx) &&
+                     (!prod || aligned16(qjl));
+  if (n_per_group > 0 && small) {
+    // few queries per code: stream the codes once, lane = key
+    if (launch_score_small(p->bits_mse, prod, qr, qs, idx, qjl, gamma, norm, scores, ld_scores, n_per_group,
+                           d, n_groups, q_per_group, kappa_of(d), make_codebook(p), s) != hipSuccess)
+      return TQ_ERR_HIP;
+  } else if (n_per_group > 0) {
     GemmArgs a;
     std::memset(&a, 0, sizeof(a));
     a.W1 = qr;

@@ -1,0 +1,405 @@
+// Fused kernels for head dimension d = 128 (KV-cache keys).  At this size the
+// parameter matrices fit in the 160 KB LDS of a compute unit (Pi and S Pi^T,
+// or Pi and S: 2 x 64 KB), so one 512-thread workgroup per CU loads them once
+// and its 8 wavefronts then stream blocks of 32 vectors straight from HBM to
+// registers to MFMA, with no further workgroup-level synchronisation.
+//
+// quant128:  Y^T = Pi X^T with the vector on the MFMA lane axis (see
+//   tq_gemm.hip for the operand layout).  A lane loads one half (64 values) of
+//   its own vector's row directly as the B operand: lane half h owns k in
+//   [64h, 64h+64), which is just a permutation of the contraction order.  The
+//   accumulator tile then holds y for 16 coordinates of that one vector per
+//   lane; the epilogue turns it in place into the residual e = y - c[idx], and
+//   those registers are *directly* the B operand of the second contraction
+//   U^T = (S Pi^T) E^T (again only a permutation of k), so the residual never
+//   leaves the register file.
+//
+// dequant128:  X~ = Y~ Pi + (kappa gamma Z) S with the vector on the MFMA row
+//   axis (A operand decoded from the packed words in registers) and rows of
+//   Pi / S as the B operand, read 16 bytes per lane so that the four output
+//   tiles interleave columns 4l..4l+3: every output row is stored as one
+//   contiguous 512-byte line.
+#include "tq_internal.h"
+
+namespace tq {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int D = 128;
+constexpr int PAD_LD = 132;  // padded row stride for 16-byte reads along k
+
+struct Quant128Args {
+  const void* X;
+  int64_t ldx;
+  int64_t n;
+  const float* Pi;
+  const float* SPiT;
+  uint32_t* idx;
+  uint32_t* qjl;
+  float* gamma;
+  float* norm;
+  int normalise;
+  Codebook cb;
+};
+
+template <int BITS, bool PROD, bool BF16IN>
+__global__ __launch_bounds__(512) void quant128_kernel(const Quant128Args a) {
+  extern __shared__ __attribute__((aligned(16))) float smem[];
+  float* Pi_s = smem;
+  float* Sp_s = smem + D * PAD_LD;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, h = lane >> 5;
+
+  for (int p = 0; p < 8; ++p) {
+    const int e4 = tid + 512 * p;  // 4096 float4 per matrix
+    const int row = e4 >> 5, c4 = e4 & 31;
+    *reinterpret_cast<float4*>(&Pi_s[row * PAD_LD + 4 * c4]) =
+        *reinterpret_cast<const float4*>(a.Pi + row * D + 4 * c4);
+    if (PROD)
+      *reinterpret_cast<float4*>(&Sp_s[row * PAD_LD + 4 * c4]) =
+          *reinterpret_cast<const float4*>(a.SPiT + row * D + 4 * c4);
+  }
+  __syncthreads();
+
+  const int64_t n_blocks = (a.n + 31) / 32;
+  for (int64_t blk = (int64_t)blockIdx.x * 8 + wave; blk < n_blocks; blk += (int64_t)gridDim.x * 8) {
+    const int64_t i = blk * 32 + l32;
+    const bool valid = i < a.n;
+    float xb[64];
+    if (BF16IN) {
+      const uint16_t* src = reinterpret_cast<const uint16_t*>(a.X) + (valid ? i : 0) * a.ldx + 64 * h;
+#pragma unroll
+      for (int v = 0; v < 8; ++v) {
+        uint4 t = make_uint4(0, 0, 0, 0);
+        if (valid) t = *reinterpret_cast<const uint4*>(src + 8 * v);
+        xb[8 * v + 0] = __uint_as_float(t.x << 16); xb[8 * v + 1] = __uint_as_float(t.x & 0xffff0000u);
+        xb[8 * v + 2] = __uint_as_float(t.y << 16); xb[8 * v + 3] = __uint_as_float(t.y & 0xffff0000u);
+        xb[8 * v + 4] = __uint_as_float(t.z << 16); xb[8 * v + 5] = __uint_as_float(t.z & 0xffff0000u);
+        xb[8 * v + 6] = __uint_as_float(t.w << 16); xb[8 * v + 7] = __uint_as_float(t.w & 0xffff0000u);
+      }
+    } else {
+      const float* src = reinterpret_cast<const float*>(a.X) + (valid ? i : 0) * a.ldx + 64 * h;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (valid) t = *reinterpret_cast<const float4*>(src + 4 * v);
+        xb[4 * v] = t.x; xb[4 * v + 1] = t.y; xb[4 * v + 2] = t.z; xb[4 * v + 3] = t.w;
+      }
+    }
+    float ss = 0.f;
+#pragma unroll
+    for (int k = 0; k < 64; ++k) ss = fmaf(xb[k], xb[k], ss);
+    ss += __shfl_xor(ss, 32);
+    const float nu = sqrtf(ss);
+    const float inv = a.normalise ? (nu > 0.f ? 1.f / nu : 0.f) : 1.f;
+
+    floatx16 acc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+    {
+      // operands of step k4+1 are read from LDS before the MFMAs of step k4 issue
+      float4 av[4], nx[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+        av[t] = *reinterpret_cast<const float4*>(&Pi_s[(32 * t + l32) * PAD_LD + 64 * h]);
+#pragma unroll
+      for (int k4 = 0; k4 < 16; ++k4) {
+        if (k4 + 1 < 16) {
+#pragma unroll
+          for (int t = 0; t < 4; ++t)
+            nx[t] = *reinterpret_cast<const float4*>(&Pi_s[(32 * t + l32) * PAD_LD + 64 * h + 4 * (k4 + 1)]);
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t].x, xb[4 * k4 + 0], acc[t], 0, 0, 0);
+          acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t].y, xb[4 * k4 + 1], acc[t], 0, 0, 0);
+          acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t].z, xb[4 * k4 + 2], acc[t], 0, 0, 0);
+          acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t].w, xb[4 * k4 + 3], acc[t], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);  // bounds how far LDS reads are hoisted (register pressure)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) av[t] = nx[t];
+      }
+    }
+
+    // nearest centroid, packing, residual (in place)
+    float g2 = 0.f;
+    uint32_t word[4][BITS > 0 ? BITS : 1];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      uint32_t piece[BITS > 0 ? BITS : 1];
+#pragma unroll
+      for (int pl = 0; pl < (BITS > 0 ? BITS : 1); ++pl) piece[pl] = 0u;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float y = acc[t][r] * inv;
+        float yt = a.cb.c[0];
+        uint32_t code = 0u;
+#pragma unroll
+        for (int j = 0; j < (1 << BITS) - 1; ++j) {
+          const bool ge = y >= a.cb.t[j];
+          code += ge ? 1u : 0u;
+          yt = ge ? a.cb.c[j + 1] : yt;
+        }
+        const float e = y - yt;
+        g2 = fmaf(e, e, g2);
+        acc[t][r] = e;
+#pragma unroll
+        for (int pl = 0; pl < BITS; ++pl) piece[pl] |= ((code >> pl) & 1u) << (8 * (r >> 2) + (r & 3));
+      }
+#pragma unroll
+      for (int pl = 0; pl < BITS; ++pl) {
+        const uint32_t w = piece[pl] << (4 * h);
+        word[t][pl] = w | (uint32_t)__shfl_xor((int)w, 32);
+      }
+    }
+    // half h stores the words of coordinate groups 2h and 2h+1
+    if (BITS > 0 && valid) {
+      uint32_t* dst = a.idx + i * (4 * BITS) + 2 * h * BITS;
+#pragma unroll
+      for (int pl = 0; pl < BITS; ++pl) {
+        dst[pl] = h ? word[2][pl] : word[0][pl];
+        dst[BITS + pl] = h ? word[3][pl] : word[1][pl];
+      }
+    }
+    if (valid && h == 0 && a.norm != nullptr) a.norm[i] = nu;
+
+    if (PROD) {
+      g2 += __shfl_xor(g2, 32);
+      floatx16 u[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) u[t][r] = 0.f;
+      // register 4*ke + r of tile te holds e_j with j = 32 te + 8 ke + 4 h + r
+      {
+        float4 av[4], nx[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+          av[t] = *reinterpret_cast<const float4*>(&Sp_s[(32 * t + l32) * PAD_LD + 4 * h]);
+#pragma unroll
+        for (int st = 0; st < 16; ++st) {
+          const int te = st >> 2, ke = st & 3;
+          if (st + 1 < 16) {
+            const int te1 = (st + 1) >> 2, ke1 = (st + 1) & 3;
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+              nx[t] = *reinterpret_cast<const float4*>(
+                  &Sp_s[(32 * t + l32) * PAD_LD + 32 * te1 + 8 * ke1 + 4 * h]);
+          }
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            u[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t].x, acc[te][4 * ke + 0], u[t], 0, 0, 0);
+            u[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t].y, acc[te][4 * ke + 1], u[t], 0, 0, 0);
+            u[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t].z, acc[te][4 * ke + 2], u[t], 0, 0, 0);
+            u[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t].w, acc[te][4 * ke + 3], u[t], 0, 0, 0);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int t = 0; t < 4; ++t) av[t] = nx[t];
+        }
+      }
+      uint32_t sw[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        uint32_t piece = 0u;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) piece |= (u[t][r] >= 0.f ? 1u : 0u) << (8 * (r >> 2) + (r & 3));
+        const uint32_t w = piece << (4 * h);
+        sw[t] = w | (uint32_t)__shfl_xor((int)w, 32);
+      }
+      if (valid) {
+        uint32_t* dst = a.qjl + i * 4 + 2 * h;
+        dst[0] = h ? sw[2] : sw[0];
+        dst[1] = h ? sw[3] : sw[1];
+        if (h == 0) a.gamma[i] = sqrtf(g2);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+struct Dequant128Args {
+  const uint32_t* idx;
+  const uint32_t* qjl;
+  const float* gamma;
+  const float* norm;
+  const float* Pi;
+  const float* S;
+  float* out;
+  int64_t ldo;
+  int64_t n;
+  float kappa;
+  Codebook cb;
+};
+
+template <int BITS, bool PROD>
+__global__ __launch_bounds__(512) void dequant128_kernel(const Dequant128Args a) {
+  extern __shared__ __attribute__((aligned(16))) float smem[];
+  __shared__ float cent_s[16];
+  float* Pi_s = smem;          // [128][128], rows read contiguously
+  float* S_s = smem + D * D;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, h = lane >> 5;
+  if (tid < 16) cent_s[tid] = a.cb.c[tid];
+  for (int p = 0; p < 8; ++p) {
+    const int e4 = tid + 512 * p;
+    reinterpret_cast<float4*>(Pi_s)[e4] = reinterpret_cast<const float4*>(a.Pi)[e4];
+    if (PROD) reinterpret_cast<float4*>(S_s)[e4] = reinterpret_cast<const float4*>(a.S)[e4];
+  }
+  __syncthreads();
+
+  const int64_t n_blocks = (a.n + 31) / 32;
+  for (int64_t blk = (int64_t)blockIdx.x * 8 + wave; blk < n_blocks; blk += (int64_t)gridDim.x * 8) {
+    const int64_t i = blk * 32 + l32;
+    const bool valid = i < a.n;
+    const int64_t row = valid ? i : 0;
+    const float nu = (valid && a.norm != nullptr) ? a.norm[row] : (valid ? 1.f : 0.f);
+    floatx16 acc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+
+    if (BITS > 0) {
+      uint32_t w[4 * (BITS > 0 ? BITS : 1)];
+      const uint32_t* src = a.idx + row * (4 * BITS);
+#pragma unroll
+      for (int v = 0; v < BITS; ++v) {
+        const uint4 t4 = *reinterpret_cast<const uint4*>(src + 4 * v);
+        w[4 * v] = t4.x; w[4 * v + 1] = t4.y; w[4 * v + 2] = t4.z; w[4 * v + 3] = t4.w;
+      }
+#pragma unroll
+      for (int q = 0; q < 4 * BITS; ++q) w[q] >>= (16 * h);  // this half's 16 coordinates of each group
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+#pragma unroll
+        for (int s = 0; s < 16; ++s) {
+          uint32_t code = 0u;
+#pragma unroll
+          for (int pl = 0; pl < BITS; ++pl) code |= ((w[g * BITS + pl] >> s) & 1u) << pl;
+          const float av = nu * cent_s[code];
+          const float4 bv = *reinterpret_cast<const float4*>(&Pi_s[(32 * g + 16 * h + s) * D + 4 * l32]);
+          acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv.x, acc[0], 0, 0, 0);
+          acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv.y, acc[1], 0, 0, 0);
+          acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv.z, acc[2], 0, 0, 0);
+          acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv.w, acc[3], 0, 0, 0);
+          if ((s & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    }
+    if (PROD) {
+      const uint4 t4 = *reinterpret_cast<const uint4*>(a.qjl + row * 4);
+      const uint32_t z[4] = {t4.x >> (16 * h), t4.y >> (16 * h), t4.z >> (16 * h), t4.w >> (16 * h)};
+      const float kg = nu * a.kappa * a.gamma[row];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+#pragma unroll
+        for (int s = 0; s < 16; ++s) {
+          const float av = ((z[g] >> s) & 1u) ? kg : -kg;
+          const float4 bv = *reinterpret_cast<const float4*>(&S_s[(32 * g + 16 * h + s) * D + 4 * l32]);
+          acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv.x, acc[0], 0, 0, 0);
+          acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv.y, acc[1], 0, 0, 0);
+          acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv.z, acc[2], 0, 0, 0);
+          acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv.w, acc[3], 0, 0, 0);
+          if ((s & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    }
+    // D[row][col]: register 4k+r of a lane is row 8k + 4h + r; tile t, lane column l32 is
+    // output column 4*l32 + t: one float4 per row per lane, 512 contiguous bytes per row
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int64_t orow = blk * 32 + 8 * k + 4 * h + r;
+        if (orow < a.n)
+          *reinterpret_cast<float4*>(a.out + orow * a.ldo + 4 * l32) =
+              make_float4(acc[0][4 * k + r], acc[1][4 * k + r], acc[2][4 * k + r], acc[3][4 * k + r]);
+      }
+  }
+}
+
+// ------------------------------- launchers -------------------------------
+
+static int grid_128(int64_t n) {
+  const int64_t blocks = (n + 31) / 32;
+  int64_t g = (blocks + 7) / 8;
+  if (g > 256) g = 256;  // one workgroup per compute unit
+  return (int)(g < 1 ? 1 : g);
+}
+
+template <int BITS, bool PROD, bool BF16IN>
+static hipError_t launch_q(const Quant128Args& a, hipStream_t s) {
+  const size_t smem = (size_t)(PROD ? 2 : 1) * D * PAD_LD * sizeof(float);
+  static bool attr_done = false;  // per instantiation
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant128_kernel<BITS, PROD, BF16IN>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL((quant128_kernel<BITS, PROD, BF16IN>), dim3(grid_128(a.n)), dim3(512), smem, s, a);
+  return hipGetLastError();
+}
+
+template <int BITS>
+static hipError_t launch_q_bits(const Quant128Args& a, bool prod, bool bf16, hipStream_t s) {
+  if (prod) return bf16 ? launch_q<BITS, true, true>(a, s) : launch_q<BITS, true, false>(a, s);
+  return bf16 ? launch_q<BITS, false, true>(a, s) : launch_q<BITS, false, false>(a, s);
+}
+
+hipError_t launch_quant128(int bits, bool prod, bool bf16, const void* X, int64_t ldx, int64_t n,
+                           const float* Pi, const float* SPiT, uint32_t* idx, uint32_t* qjl, float* gamma,
+                           float* norm, const Codebook& cb, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  Quant128Args a;
+  a.X = X; a.ldx = ldx; a.n = n; a.Pi = Pi; a.SPiT = SPiT; a.idx = idx; a.qjl = qjl; a.gamma = gamma;
+  a.norm = norm; a.normalise = norm != nullptr; a.cb = cb;
+  switch (bits) {
+    case 0: return launch_q_bits<0>(a, prod, bf16, s);
+    case 1: return launch_q_bits<1>(a, prod, bf16, s);
+    case 2: return launch_q_bits<2>(a, prod, bf16, s);
+    case 3: return launch_q_bits<3>(a, prod, bf16, s);
+    case 4: return launch_q_bits<4>(a, prod, bf16, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+template <int BITS, bool PROD>
+static hipError_t launch_d(const Dequant128Args& a, hipStream_t s) {
+  const size_t smem = (size_t)(PROD ? 2 : 1) * D * D * sizeof(float);
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dequant128_kernel<BITS, PROD>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL((dequant128_kernel<BITS, PROD>), dim3(grid_128(a.n)), dim3(512), smem, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_dequant128(int bits, bool prod, const uint32_t* idx, const uint32_t* qjl,
+                             const float* gamma, const float* norm, const float* Pi, const float* S,
+                             float* out, int64_t ldo, int64_t n, float kappa, const Codebook& cb,
+                             hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  Dequant128Args a;
+  a.idx = idx; a.qjl = qjl; a.gamma = gamma; a.norm = norm; a.Pi = Pi; a.S = S; a.out = out; a.ldo = ldo;
+  a.n = n; a.kappa = kappa; a.cb = cb;
+  switch (bits) {
+    case 0: return prod ? launch_d<0, true>(a, s) : launch_d<0, false>(a, s);
+    case 1: return prod ? launch_d<1, true>(a, s) : launch_d<1, false>(a, s);
+    case 2: return prod ? launch_d<2, true>(a, s) : launch_d<2, false>(a, s);
+    case 3: return prod ? launch_d<3, true>(a, s) : launch_d<3, false>(a, s);
+    case 4: return prod ? launch_d<4, true>(a, s) : launch_d<4, false>(a, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace tq

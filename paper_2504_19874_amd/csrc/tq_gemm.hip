@@ -35,7 +35,7 @@ __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w 
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
 template <int NKIND, int EKIND, int BITS>
-__global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a, const int tiles_m,
+__global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const int tiles_m,
                                                    const int tiles_n, const int per_xcd) {
   __shared__ __attribute__((aligned(16))) float Ws[TM * LDS_LD];
   __shared__ __attribute__((aligned(16))) float Ns[TN * LDS_LD];
@@ -229,6 +229,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a, const int t
     }
 #pragma unroll
     for (int tm = 0; tm < 2; ++tm) {
+      __builtin_amdgcn_sched_barrier(0);  // one tile's epilogue at a time (register pressure)
       const int mb = m0 + wm * 64 + tm * 32;  // first row of this 32x32 tile
       const floatx16& c = acc[tm][tn];
       if (EKIND == E_STORE_T) {

@@ -63,6 +63,23 @@ struct GemmArgs {
 hipError_t launch_gemm(NKind nk, EKind ek, int bits, const GemmArgs& a, int n_groups,
                        hipStream_t stream);
 
+// d = 128 fused kernels (tq_d128.hip)
+hipError_t launch_quant128(int bits, bool prod, bool bf16, const void* X, int64_t ldx, int64_t n,
+                           const float* Pi, const float* SPiT, uint32_t* idx, uint32_t* qjl, float* gamma,
+                           float* norm, const Codebook& cb, hipStream_t s);
+hipError_t launch_dequant128(int bits, bool prod, const uint32_t* idx, const uint32_t* qjl,
+                             const float* gamma, const float* norm, const float* Pi, const float* S,
+                             float* out, int64_t ldo, int64_t n, float kappa, const Codebook& cb,
+                             hipStream_t s);
+
+// few queries per code (tq_score_small.hip)
+hipError_t launch_matvec_small(int d, int nq, const float* W0, const float* W1, const float* x,
+                               int64_t ldx, float* out0, float* out1, hipStream_t stream);
+hipError_t launch_score_small(int bits, bool prod, const float* qr, const float* qs, const uint32_t* idx,
+                              const uint32_t* qjl, const float* gamma, const float* norm, float* scores,
+                              int64_t lds, int64_t n, int d, int n_groups, int q_per_group, float kappa,
+                              const Codebook& cb, hipStream_t stream);
+
 // codec stages
 hipError_t launch_stage_pack(const Codebook& cb, int d, const float* y, int64_t n, uint32_t* idx,
                              hipStream_t stream);

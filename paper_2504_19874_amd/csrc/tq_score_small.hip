@@ -1,0 +1,203 @@
+// Scoring when only a few queries share each code (decode attention with
+// grouped queries: 4 query heads per KV head).  There is no operand reuse to
+// speak of, so the kernel is organised around the stream of codes:
+//
+//   lane = key.  A wavefront takes 64 consecutive keys, each lane loads its own
+//   key's packed words for 128 coordinates at a time (16-byte loads, fully
+//   coalesced across the wave), expands them coordinate by coordinate in
+//   registers and feeds v_mfma_f32_4x4x1_16b_f32:  16 independent 4x4 blocks,
+//   A = 4 query values (one per lane of a block), B = 4 key values (one per
+//   lane of a block), so one instruction multiplies one coordinate of 64 keys
+//   by 4 queries.  Lane l = 4*block + j ends up with D[i][j] in register i =
+//   the score of query i against its own key.
+//
+// The rotated / sketched queries (Pi q, S q) come from a small matrix-vector
+// kernel and sit in LDS laid out [k/4][query][k%4], so one 16-byte read gives a
+// lane the values of its query (lane%4) for four consecutive coordinates.
+#include "tq_internal.h"
+
+namespace tq {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------
+// out[q][j] = sum_k W[j][k] x[q][k] for a handful of queries: one wavefront per
+// output coordinate j, blockIdx.y selects (W, out) = (W0, out0) or (W1, out1).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void matvec_small_kernel(const int d, const int nq,
+                                                           const float* __restrict__ W0,
+                                                           const float* __restrict__ W1,
+                                                           const float* __restrict__ x, const int64_t ldx,
+                                                           float* __restrict__ out0,
+                                                           float* __restrict__ out1) {
+  const int lane = threadIdx.x & 63;
+  const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (j >= d) return;
+  const float* W = (blockIdx.y == 0 ? W0 : W1) + (int64_t)j * d;
+  float* out = blockIdx.y == 0 ? out0 : out1;
+  for (int q = 0; q < nq; ++q) {
+    const float* xq = x + (int64_t)q * ldx;
+    float acc = 0.f;
+    for (int k = lane; k < d; k += 64) acc = fmaf(W[k], xq[k], acc);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+    if (lane == 0) out[(int64_t)q * d + j] = acc;
+  }
+}
+
+hipError_t launch_matvec_small(int d, int nq, const float* W0, const float* W1, const float* x,
+                               int64_t ldx, float* out0, float* out1, hipStream_t stream) {
+  if (nq == 0) return hipSuccess;
+  hipLaunchKernelGGL(matvec_small_kernel, dim3((d + 3) / 4, W1 != nullptr ? 2 : 1), dim3(256), 0, stream, d,
+                     nq, W0, W1, x, ldx, out0, out1);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+struct ScoreSmallArgs {
+  const float* qr;  // [n_groups*q_per_group][d]  Pi q
+  const float* qs;  // [n_groups*q_per_group][d]  S q   (prod only)
+  const uint32_t* idx;
+  const uint32_t* qjl;
+  const float* gamma;
+  const float* norm;  // nullable
+  float* scores;
+  int64_t lds;
+  int64_t n;          // keys per group
+  int d;
+  int q_per_group;
+  float kappa;
+  Codebook cb;
+};
+
+constexpr int KEYS_PER_WG = 512;
+
+template <int BITS, bool PROD>
+__global__ __launch_bounds__(256) void score_small_kernel(const ScoreSmallArgs a) {
+  extern __shared__ __attribute__((aligned(16))) float q_s[];  // qr then qs, each d*4 floats
+  __shared__ float cent_s[16];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int group = blockIdx.y;
+  const int pass = blockIdx.z;           // queries 4*pass .. 4*pass+3 of the group
+  const int d = a.d;
+  const int q0 = pass * 4;
+  const int nq_here = min(4, a.q_per_group - q0);
+
+  if (tid < 16) cent_s[tid] = a.cb.c[tid];
+  // stage the queries: element (row r, coordinate k) -> [(k/4)*4 + r]*4 + k%4
+  for (int e = tid; e < 4 * d; e += 256) {
+    const int r = e / d, k = e - r * d;
+    const int64_t qrow = (int64_t)group * a.q_per_group + q0 + r;
+    const int dst = (((k >> 2) * 4 + r) << 2) + (k & 3);
+    q_s[dst] = (r < nq_here) ? a.qr[qrow * d + k] : 0.f;
+    if (PROD) q_s[4 * d + dst] = (r < nq_here) ? a.qs[qrow * d + k] : 0.f;
+  }
+  __syncthreads();
+
+  const int words_per_row = (d / 32) * BITS;
+  const int qw_per_row = d / 32;
+  const int64_t gbase = (int64_t)group * a.n;
+  const float4* qr4 = reinterpret_cast<const float4*>(q_s);
+  const float4* qs4 = reinterpret_cast<const float4*>(q_s + 4 * d);
+
+  const int64_t wg_key0 = (int64_t)blockIdx.x * KEYS_PER_WG;
+  for (int it = 0; it < KEYS_PER_WG / 256; ++it) {
+    const int64_t key = wg_key0 + (int64_t)(it * 4 + wave) * 64 + lane;
+    if (wg_key0 + (int64_t)(it * 4 + wave) * 64 >= a.n) break;  // whole wave out of range
+    const bool valid = key < a.n;
+    const int64_t row = gbase + (valid ? key : 0);
+    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+    floatx4 acc2 = {0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < d / 128; ++c) {  // 128 coordinates = 4 groups of 32 at a time
+      uint32_t w[4 * (BITS > 0 ? BITS : 1)];
+      if (BITS > 0) {
+        const uint32_t* src = a.idx + row * words_per_row + c * 4 * BITS;
+#pragma unroll
+        for (int v = 0; v < BITS; ++v) {  // 4*BITS words = BITS 16-byte loads
+          const uint4 t = *reinterpret_cast<const uint4*>(src + 4 * v);
+          w[4 * v] = t.x; w[4 * v + 1] = t.y; w[4 * v + 2] = t.z; w[4 * v + 3] = t.w;
+        }
+      }
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+#pragma unroll
+        for (int j4 = 0; j4 < 8; ++j4) {
+          const float4 qa = qr4[((c * 32 + g * 8 + j4) << 2) + (lane & 3)];
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) {
+            const int j = j4 * 4 + jj;
+            uint32_t code = 0;
+#pragma unroll
+            for (int pl = 0; pl < BITS; ++pl) code |= ((w[g * BITS + pl] >> j) & 1u) << pl;
+            const float val = cent_s[code];
+            const float av = jj == 0 ? qa.x : jj == 1 ? qa.y : jj == 2 ? qa.z : qa.w;
+            acc = __builtin_amdgcn_mfma_f32_4x4x1f32(av, val, acc, 0, 0, 0);
+          }
+        }
+      }
+      if (PROD) {
+        const uint4 t = *reinterpret_cast<const uint4*>(a.qjl + row * qw_per_row + c * 4);
+        const uint32_t zn[4] = {~t.x, ~t.y, ~t.z, ~t.w};  // inverted: bit set = minus sign
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+#pragma unroll
+          for (int j4 = 0; j4 < 8; ++j4) {
+            const float4 qa = qs4[((c * 32 + g * 8 + j4) << 2) + (lane & 3)];
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+              const int j = j4 * 4 + jj;
+              // +-1.0f with the sign bit taken from bit j of the inverted word
+              const uint32_t sb = (j == 31) ? zn[g] : (zn[g] << (31 - j));
+              const float val = __uint_as_float((sb & 0x80000000u) | 0x3f800000u);
+              const float av = jj == 0 ? qa.x : jj == 1 ? qa.y : jj == 2 ? qa.z : qa.w;
+              acc2 = __builtin_amdgcn_mfma_f32_4x4x1f32(av, val, acc2, 0, 0, 0);
+            }
+          }
+        }
+      }
+    }
+    if (valid) {
+      const float nu = a.norm != nullptr ? a.norm[row] : 1.f;
+      const float kg = PROD ? a.kappa * a.gamma[row] : 0.f;
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        if (r < nq_here)
+          a.scores[((int64_t)group * a.q_per_group + q0 + r) * a.lds + key] = nu * (acc[r] + kg * acc2[r]);
+    }
+  }
+}
+
+template <int BITS>
+static hipError_t launch_bits(const ScoreSmallArgs& a, bool prod, dim3 grid, size_t smem, hipStream_t s) {
+  if (prod)
+    hipLaunchKernelGGL((score_small_kernel<BITS, true>), grid, dim3(256), smem, s, a);
+  else
+    hipLaunchKernelGGL((score_small_kernel<BITS, false>), grid, dim3(256), smem, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_score_small(int bits, bool prod, const float* qr, const float* qs, const uint32_t* idx,
+                              const uint32_t* qjl, const float* gamma, const float* norm, float* scores,
+                              int64_t lds, int64_t n, int d, int n_groups, int q_per_group, float kappa,
+                              const Codebook& cb, hipStream_t stream) {
+  if (n == 0 || n_groups == 0 || q_per_group == 0) return hipSuccess;
+  if (d % 128 != 0 || d > 2048) return hipErrorInvalidValue;
+  ScoreSmallArgs a;
+  a.qr = qr; a.qs = qs; a.idx = idx; a.qjl = qjl; a.gamma = gamma; a.norm = norm;
+  a.scores = scores; a.lds = lds; a.n = n; a.d = d; a.q_per_group = q_per_group;
+  a.kappa = kappa; a.cb = cb;
+  const dim3 grid((unsigned)((n + KEYS_PER_WG - 1) / KEYS_PER_WG), n_groups, (q_per_group + 3) / 4);
+  const size_t smem = (size_t)(prod ? 2 : 1) * 4 * d * sizeof(float);  // <= 64 KB for d <= 2048
+  switch (bits) {
+    case 0: return launch_bits<0>(a, prod, grid, smem, stream);
+    case 1: return launch_bits<1>(a, prod, grid, smem, stream);
+    case 2: return launch_bits<2>(a, prod, grid, smem, stream);
+    case 3: return launch_bits<3>(a, prod, grid, smem, stream);
+    case 4: return launch_bits<4>(a, prod, grid, smem, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace tq

@@ -155,11 +155,12 @@ def _ann_score_checks(cfg, p, Pi, S, c32, idx, qjl, gamma, prod):
     nqs = 48
     s = torch.zeros((nqs, n), dtype=torch.float32, device=DEV)
     tq.tq_score(p, qd[:nqs], 1, nqs, idx, qjl, gamma, None, n, s)
-    ref_v, ref_i = torch.topk(s, cfg.topk, dim=1)
-    assert torch.equal(tv[:nqs], ref_v), "top-k values differ from the top of the GPU's own score matrix"
-    same = (ti[:nqs].long() == ref_i).all(dim=1)
-    for r in (~same).nonzero().flatten().tolist():  # only ties may reorder
-        assert torch.equal(s[r][ti[r].long()], ref_v[r])
+    # the two calls rotate the queries with different kernels (few vs many queries), so the
+    # scores agree to rounding, not bit for bit: compare the top-k with the tolerance rule
+    s_np = s.cpu().numpy()
+    P.check_topk(ti[:nqs].cpu().numpy(), s_np, cfg.topk, np.ones(nqs))
+    ref_v, _ = torch.topk(s, cfg.topk, dim=1)
+    P.check_close(tv[:nqs].cpu().numpy(), ref_v.cpu().numpy(), 1.0, "top-k values", rel=2e-6)
     # sampled (query, code) pairs against the oracle, including each query's winners
     rng = np.random.default_rng(5)
     cols = np.unique(np.concatenate([rng.integers(0, n, size=3000), ti[:nqs].cpu().numpy().ravel()]))

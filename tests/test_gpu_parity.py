@@ -214,11 +214,14 @@ def test_empty_and_error_paths():
     e = torch.zeros((0, d), dtype=torch.float32, device=DEV)
     tq.tq_quantize_mse(p, e, torch.zeros((0, p.idx_words), dtype=torch.int32, device=DEV), None)
     tq.tq_dequantize(p, torch.zeros((0, p.idx_words), dtype=torch.int32, device=DEV), None, None, None, e)
+    # the two-pass path (any d other than 128) needs a residual workspace
+    d2 = 256
+    q, *_ = setup(d2, 2, True)
     with pytest.raises(tq.TurboQuantError, match="WORKSPACE"):
-        p2 = tq.Params(d, 2, p.Pi, p.S, p.centroids, p.bounds)
-        x = dev(W.unit_gaussian_rows(8, d, 1))
-        tq.tq_quantize_prod(p2, x, torch.zeros((8, 8), dtype=torch.int32, device=DEV),
-                            torch.zeros((8, 4), dtype=torch.int32, device=DEV),
+        p2 = tq.Params(d2, 2, q.Pi, q.S, q.centroids, q.bounds)
+        x = dev(W.unit_gaussian_rows(8, d2, 1))
+        tq.tq_quantize_prod(p2, x, torch.zeros((8, 16), dtype=torch.int32, device=DEV),
+                            torch.zeros((8, 8), dtype=torch.int32, device=DEV),
                             torch.zeros(8, dtype=torch.float32, device=DEV), None)
 
 
