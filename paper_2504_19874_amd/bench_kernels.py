@@ -1,0 +1,178 @@
+"""Per-entry-point timings against the MFMA / HBM rooflines for the five
+benchmark configurations (the table in the design doc comes from this).
+
+    python -m paper_2504_19874_amd.bench_kernels --config C2 [--reps 50]
+
+Prints one JSON object per entry point: average milliseconds (HIP events on the
+launch stream), algorithmic flops and bytes, and the fraction of the fp32-MFMA
+peak (157.3 TFLOP/s) or of the HBM peak (8 TB/s), whichever bounds the call.
+For configurations whose working set fits the 256 MB last-level cache the
+inputs are rotated through several buffer sets so HBM-bound figures are not
+cache figures ("cold"); `--warm` disables that.  Inputs come from the seeded
+generators in workloads/.  Also times a plain device-to-device copy of the
+same size as the stage kernels' traffic, as the reference for what a
+streaming kernel reaches on this chip.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_TF, PEAK_GBS = 157.3, 8000.0
+
+
+def timed(fn, reps, warmup=3):
+    import torch
+    for _ in range(warmup):
+        fn(0)
+    torch.cuda.synchronize()
+    e0 = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
+    e1 = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
+    for r in range(reps):
+        e0[r].record()
+        fn(r)
+        e1[r].record()
+    torch.cuda.synchronize()
+    ts = sorted(a.elapsed_time(b) for a, b in zip(e0, e1))
+    return sum(ts) / len(ts), ts[0], ts[len(ts) // 2]
+
+
+def report(name, cfg, ms, flops, nbytes, extra=None):
+    avg, mn, med = ms
+    t_mfma, t_hbm = flops / (PEAK_TF * 1e12), nbytes / (PEAK_GBS * 1e9)
+    bound = "mfma" if t_mfma >= t_hbm else "hbm"
+    out = {"config": cfg.name, "call": name, "avg_ms": round(avg, 5), "min_ms": round(mn, 5),
+           "median_ms": round(med, 5), "flops": flops, "bytes": nbytes, "bound": bound,
+           "frac_of_peak": round((t_mfma if bound == "mfma" else t_hbm) / (avg * 1e-3), 4),
+           "tflops": round(flops / (avg * 1e-3) / 1e12, 2), "gbs": round(nbytes / (avg * 1e-3) / 1e9, 1)}
+    if extra:
+        out.update(extra)
+    print(json.dumps(out), flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--config", default="C2")
+    ap.add_argument("--reps", type=int, default=0)
+    ap.add_argument("--warm", action="store_true")
+    ap.add_argument("--only", default="")
+    args = ap.parse_args()
+
+    import numpy as np
+    import torch
+
+    import paper_2504_19874_amd as tq
+    import workloads as W
+
+    cfg = W.CONFIGS[args.config]
+    prod = cfg.kind == "prod"
+    d, n, nq = cfg.d, cfg.n * cfg.n_groups, cfg.nq
+    big = n * d * 4 > (1 << 30)
+    reps = args.reps or (5 if big else 100)
+    S = W.sketch_matrix(d, cfg.seed_s) if prod else None
+    p = tq.make_params(d, cfg.bits_mse, W.gaussian_matrix(d, cfg.seed_pi), S).reserve(n, nq, cfg.topk)
+
+    # input sets: rotate through several when the working set would sit in cache
+    in_b = 2 if cfg.in_dtype == "bf16" else 4
+    sets = 1 if (big or args.warm) else max(1, min(12, int(300e6 // max(1, n * d * in_b)) + 1))
+    xs = []
+    for s in range(sets):
+        if cfg.in_dtype == "bf16":
+            keys = W.kv_keys(cfg.n_groups, cfg.n, d, cfg.seed_x + 1000 * s).reshape(n, d)
+            xs.append(torch.from_numpy(keys.view(np.int16)).view(torch.bfloat16).cuda())
+        elif big:
+            x = torch.empty((n, d), dtype=torch.float32, device="cuda")
+            for start, blk in W.mixture_rows(n, d, cfg.seed_x, cfg.seed_x):
+                x[start:start + blk.shape[0]] = torch.from_numpy(blk).cuda()
+            xs.append(x)
+        else:
+            xs.append(torch.from_numpy(W.unit_gaussian_rows(n, d, cfg.seed_x + 1000 * s)).cuda())
+    if big:
+        q = W.mixture_chunk(0, nq, d, cfg.seed_q, W.mixture_centers(d, cfg.seed_x))
+    else:
+        q = W.gaussian_queries(nq, d, cfg.seed_q, unit=cfg.unit_norm)
+    q = torch.from_numpy(q).cuda()
+
+    def new_codes():
+        return dict(idx=torch.zeros((n, max(1, p.idx_words)), dtype=torch.int32, device="cuda"),
+                    qjl=torch.zeros((n, p.qjl_words), dtype=torch.int32, device="cuda") if prod else None,
+                    gamma=torch.zeros(n, dtype=torch.float32, device="cuda") if prod else None,
+                    norm=None if cfg.unit_norm else torch.zeros(n, dtype=torch.float32, device="cuda"))
+
+    codes = [new_codes() for _ in range(sets)]
+
+    def quantize(r):
+        c, x = codes[r % sets], xs[r % sets]
+        if prod:
+            tq.tq_quantize_prod(p, x, c["idx"], c["qjl"], c["gamma"], c["norm"])
+        else:
+            tq.tq_quantize_mse(p, x, c["idx"], c["norm"])
+
+    code_b = cfg.bits_mse * d / 8 + (d / 8 + 4 if prod else 0) + (0 if cfg.unit_norm else 4)
+    want = [w for w in args.only.split(",") if w]
+
+    def on(name):
+        return not want or name in want
+
+    for s in range(sets):
+        quantize(s)
+    torch.cuda.synchronize()
+
+    if on("quantize"):
+        report("quantize", cfg, timed(quantize, reps), 2.0 * n * d * d * (2 if prod else 1), n * (d * in_b + code_b),
+               {"vectors_per_s": None, "input_sets": sets})
+
+    if on("dequantize"):
+        xt = [torch.empty((n, d), dtype=torch.float32, device="cuda") for _ in range(min(sets, 4) if not big else 1)]
+
+        def dequantize(r):
+            c = codes[r % sets]
+            tq.tq_dequantize(p, c["idx"], c["qjl"], c["gamma"], c["norm"], xt[r % len(xt)])
+
+        report("dequantize", cfg, timed(dequantize, reps), 2.0 * n * d * d * (2 if prod else 1), n * (code_b + 4 * d))
+        del xt
+
+    if on("score"):
+        sc = None if cfg.topk else [torch.empty((nq, cfg.n), dtype=torch.float32, device="cuda")
+                                    for _ in range(min(sets, 8))]
+        ti = torch.zeros((nq, max(1, cfg.topk)), dtype=torch.int32, device="cuda")
+        tv = torch.zeros((nq, max(1, cfg.topk)), dtype=torch.float32, device="cuda")
+
+        def score(r):
+            c = codes[r % sets]
+            tq.tq_score(p, q, cfg.n_groups, cfg.q_per_group, c["idx"], c["qjl"], c["gamma"], c["norm"], cfg.n,
+                        None if cfg.topk else sc[r % len(sc)], cfg.topk, ti if cfg.topk else None,
+                        tv if cfg.topk else None)
+
+        pairs = float(nq) * cfg.n
+        out_b = 0 if cfg.topk else 4 * pairs
+        report("score" + (f"+top{cfg.topk}" if cfg.topk else ""), cfg, timed(score, reps),
+               2.0 * pairs * d * (2 if prod else 1) + 2.0 * nq * d * d * (2 if prod else 1),
+               n * code_b + out_b + 4 * nq * d, {"scores_per_s": None, "pairs": pairs})
+
+    if on("stage") and cfg.bits_mse > 0:
+        # codec stages on rotated coordinates of the same shape
+        rows = n if not big else min(n, 1 << 20)
+        ysets = 1 if big else sets
+        ys = [torch.randn((rows, d), dtype=torch.float32, device="cuda") / d ** 0.5 for _ in range(ysets)]
+        iw = [torch.zeros((rows, p.idx_words), dtype=torch.int32, device="cuda") for _ in range(ysets)]
+        report("stage_pack", cfg, timed(lambda r: tq.tq_stage_pack(p, ys[r % ysets], iw[r % ysets]), reps),
+               0.0, rows * (4 * d + cfg.bits_mse * d / 8))
+        report("stage_unpack", cfg, timed(lambda r: tq.tq_stage_unpack(p, iw[r % ysets], ys[r % ysets]), reps),
+               0.0, rows * (4 * d + cfg.bits_mse * d / 8))
+        qw = [torch.zeros((rows, d // 32), dtype=torch.int32, device="cuda") for _ in range(ysets)]
+        report("stage_sign_pack", cfg, timed(lambda r: tq.tq_stage_sign_pack(d, ys[r % ysets], qw[r % ysets]), reps),
+               0.0, rows * (4 * d + d / 8))
+        dst = [torch.empty_like(y) for y in ys]
+        report("plain_copy(torch)", cfg, timed(lambda r: dst[r % ysets].copy_(ys[r % ysets]), reps),
+               0.0, rows * 8 * d)
+
+
+if __name__ == "__main__":
+    main()

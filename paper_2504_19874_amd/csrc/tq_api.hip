@@ -277,7 +277,7 @@ tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_gr
   }
 
   // queries into the rotated basis and the sketch basis: Pi q and S q
-  if (nq <= 64) {
+  if (nq <= 64 && d <= 4096) {
     if (launch_matvec_small(d, (int)nq, p->Pi, prod ? p->S : nullptr, q, ldq, qr, qs, s) != hipSuccess)
       return TQ_ERR_HIP;
   } else {

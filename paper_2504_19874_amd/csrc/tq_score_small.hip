@@ -21,35 +21,52 @@ namespace tq {
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 // ---------------------------------------------------------------------------
-// out[q][j] = sum_k W[j][k] x[q][k] for a handful of queries: one wavefront per
-// output coordinate j, blockIdx.y selects (W, out) = (W0, out0) or (W1, out1).
+// out[q][j] = sum_k W[j][k] x[q][k] for a handful of queries.  One thread per
+// output (q, j), j fastest; a workgroup stages its queries in LDS and every
+// thread walks its own row of W with 16-byte loads (each 128-byte line of W is
+// consumed by the thread that fetched it).  blockIdx.z selects (W0, out0) or
+// (W1, out1); blockIdx.y a block of 4 queries; blockIdx.x a block of 64 rows j.
 // ---------------------------------------------------------------------------
+constexpr int MV_Q = 4;
+
 __global__ __launch_bounds__(256) void matvec_small_kernel(const int d, const int nq,
                                                            const float* __restrict__ W0,
                                                            const float* __restrict__ W1,
                                                            const float* __restrict__ x, const int64_t ldx,
                                                            float* __restrict__ out0,
                                                            float* __restrict__ out1) {
-  const int lane = threadIdx.x & 63;
-  const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (j >= d) return;
-  const float* W = (blockIdx.y == 0 ? W0 : W1) + (int64_t)j * d;
-  float* out = blockIdx.y == 0 ? out0 : out1;
-  for (int q = 0; q < nq; ++q) {
-    const float* xq = x + (int64_t)q * ldx;
-    float acc = 0.f;
-    for (int k = lane; k < d; k += 64) acc = fmaf(W[k], xq[k], acc);
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
-    if (lane == 0) out[(int64_t)q * d + j] = acc;
+  extern __shared__ __attribute__((aligned(16))) float xs[];  // [MV_Q][d]
+  const int tid = threadIdx.x;
+  const int q0 = blockIdx.y * MV_Q;
+  for (int e = tid; e < MV_Q * d; e += 256) {
+    const int r = e / d, k = e - r * d;
+    xs[e] = (q0 + r < nq) ? x[(int64_t)(q0 + r) * ldx + k] : 0.f;
   }
+  __syncthreads();
+  const int j = blockIdx.x * 64 + (tid & 63);
+  const int r = tid >> 6;  // query within the block of 4: one per wavefront
+  if (j >= d || q0 + r >= nq) return;
+  const float4* w4 = reinterpret_cast<const float4*>((blockIdx.z == 0 ? W0 : W1) + (int64_t)j * d);
+  const float4* x4 = reinterpret_cast<const float4*>(xs + r * d);
+  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+#pragma unroll 8
+  for (int k4 = 0; k4 < d / 4; ++k4) {
+    const float4 w = w4[k4];
+    const float4 v = x4[k4];
+    a0 = fmaf(w.x, v.x, a0);
+    a1 = fmaf(w.y, v.y, a1);
+    a2 = fmaf(w.z, v.z, a2);
+    a3 = fmaf(w.w, v.w, a3);
+  }
+  (blockIdx.z == 0 ? out0 : out1)[(int64_t)(q0 + r) * d + j] = (a0 + a1) + (a2 + a3);
 }
 
 hipError_t launch_matvec_small(int d, int nq, const float* W0, const float* W1, const float* x,
                                int64_t ldx, float* out0, float* out1, hipStream_t stream) {
   if (nq == 0) return hipSuccess;
-  hipLaunchKernelGGL(matvec_small_kernel, dim3((d + 3) / 4, W1 != nullptr ? 2 : 1), dim3(256), 0, stream, d,
-                     nq, W0, W1, x, ldx, out0, out1);
+  if (d % 4 != 0 || (size_t)MV_Q * d * sizeof(float) > 65536) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(matvec_small_kernel, dim3((d + 63) / 64, (nq + MV_Q - 1) / MV_Q, W1 != nullptr ? 2 : 1),
+                     dim3(256), (size_t)MV_Q * d * sizeof(float), stream, d, nq, W0, W1, x, ldx, out0, out1);
   return hipGetLastError();
 }
 
@@ -70,9 +87,7 @@ struct ScoreSmallArgs {
   Codebook cb;
 };
 
-constexpr int KEYS_PER_WG = 512;
-
-template <int BITS, bool PROD>
+template <int BITS, bool PROD, int KPL>
 __global__ __launch_bounds__(256) void score_small_kernel(const ScoreSmallArgs a) {
   extern __shared__ __attribute__((aligned(16))) float q_s[];  // qr then qs, each d*4 floats
   __shared__ float cent_s[16];
@@ -102,80 +117,100 @@ __global__ __launch_bounds__(256) void score_small_kernel(const ScoreSmallArgs a
   const float4* qr4 = reinterpret_cast<const float4*>(q_s);
   const float4* qs4 = reinterpret_cast<const float4*>(q_s + 4 * d);
 
-  const int64_t wg_key0 = (int64_t)blockIdx.x * KEYS_PER_WG;
-  for (int it = 0; it < KEYS_PER_WG / 256; ++it) {
-    const int64_t key = wg_key0 + (int64_t)(it * 4 + wave) * 64 + lane;
-    if (wg_key0 + (int64_t)(it * 4 + wave) * 64 >= a.n) break;  // whole wave out of range
-    const bool valid = key < a.n;
-    const int64_t row = gbase + (valid ? key : 0);
-    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-    floatx4 acc2 = {0.f, 0.f, 0.f, 0.f};
-    for (int c = 0; c < d / 128; ++c) {  // 128 coordinates = 4 groups of 32 at a time
-      uint32_t w[4 * (BITS > 0 ? BITS : 1)];
+  // a wavefront owns 64*KPL consecutive keys; lane l takes keys base + u*64 + l.
+  // The KPL keys of a lane share every query read and give independent MFMA chains.
+  const int64_t base = ((int64_t)blockIdx.x * 4 + wave) * (64 * KPL);
+  if (base >= a.n) return;
+  int64_t row[KPL];
+  bool valid[KPL];
+  floatx4 acc[KPL], acc2[KPL];
+#pragma unroll
+  for (int u = 0; u < KPL; ++u) {
+    const int64_t key = base + u * 64 + lane;
+    valid[u] = key < a.n;
+    row[u] = gbase + (valid[u] ? key : 0);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) { acc[u][r] = 0.f; acc2[u][r] = 0.f; }
+  }
+  for (int c = 0; c < d / 128; ++c) {  // 128 coordinates = 4 groups of 32 at a time
+    uint32_t w[KPL][4 * (BITS > 0 ? BITS : 1)];
+    uint32_t zn[KPL][4];
+#pragma unroll
+    for (int u = 0; u < KPL; ++u) {
       if (BITS > 0) {
-        const uint32_t* src = a.idx + row * words_per_row + c * 4 * BITS;
+        const uint32_t* src = a.idx + row[u] * words_per_row + c * 4 * BITS;
 #pragma unroll
         for (int v = 0; v < BITS; ++v) {  // 4*BITS words = BITS 16-byte loads
           const uint4 t = *reinterpret_cast<const uint4*>(src + 4 * v);
-          w[4 * v] = t.x; w[4 * v + 1] = t.y; w[4 * v + 2] = t.z; w[4 * v + 3] = t.w;
-        }
-      }
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-#pragma unroll
-        for (int j4 = 0; j4 < 8; ++j4) {
-          const float4 qa = qr4[((c * 32 + g * 8 + j4) << 2) + (lane & 3)];
-#pragma unroll
-          for (int jj = 0; jj < 4; ++jj) {
-            const int j = j4 * 4 + jj;
-            uint32_t code = 0;
-#pragma unroll
-            for (int pl = 0; pl < BITS; ++pl) code |= ((w[g * BITS + pl] >> j) & 1u) << pl;
-            const float val = cent_s[code];
-            const float av = jj == 0 ? qa.x : jj == 1 ? qa.y : jj == 2 ? qa.z : qa.w;
-            acc = __builtin_amdgcn_mfma_f32_4x4x1f32(av, val, acc, 0, 0, 0);
-          }
+          w[u][4 * v] = t.x; w[u][4 * v + 1] = t.y; w[u][4 * v + 2] = t.z; w[u][4 * v + 3] = t.w;
         }
       }
       if (PROD) {
-        const uint4 t = *reinterpret_cast<const uint4*>(a.qjl + row * qw_per_row + c * 4);
-        const uint32_t zn[4] = {~t.x, ~t.y, ~t.z, ~t.w};  // inverted: bit set = minus sign
+        const uint4 t = *reinterpret_cast<const uint4*>(a.qjl + row[u] * qw_per_row + c * 4);
+        zn[u][0] = ~t.x; zn[u][1] = ~t.y; zn[u][2] = ~t.z; zn[u][3] = ~t.w;  // bit set = minus sign
+      }
+    }
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
+    for (int g = 0; g < 4; ++g) {
 #pragma unroll
-          for (int j4 = 0; j4 < 8; ++j4) {
-            const float4 qa = qs4[((c * 32 + g * 8 + j4) << 2) + (lane & 3)];
+      for (int j4 = 0; j4 < 8; ++j4) {
+        const float4 qa = qr4[((c * 32 + g * 8 + j4) << 2) + (lane & 3)];
+        float4 qb = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (PROD) qb = qs4[((c * 32 + g * 8 + j4) << 2) + (lane & 3)];
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
-              const int j = j4 * 4 + jj;
+        for (int jj = 0; jj < 4; ++jj) {
+          const int j = j4 * 4 + jj;
+          const float av = jj == 0 ? qa.x : jj == 1 ? qa.y : jj == 2 ? qa.z : qa.w;
+          const float bv = jj == 0 ? qb.x : jj == 1 ? qb.y : jj == 2 ? qb.z : qb.w;
+#pragma unroll
+          for (int u = 0; u < KPL; ++u) {
+            if (BITS > 0) {
+              uint32_t code = 0;
+#pragma unroll
+              for (int pl = 0; pl < BITS; ++pl) code |= ((w[u][g * BITS + pl] >> j) & 1u) << pl;
+              acc[u] = __builtin_amdgcn_mfma_f32_4x4x1f32(av, cent_s[code], acc[u], 0, 0, 0);
+            }
+            if (PROD) {
               // +-1.0f with the sign bit taken from bit j of the inverted word
-              const uint32_t sb = (j == 31) ? zn[g] : (zn[g] << (31 - j));
+              const uint32_t sb = zn[u][g] << (31 - j);
               const float val = __uint_as_float((sb & 0x80000000u) | 0x3f800000u);
-              const float av = jj == 0 ? qa.x : jj == 1 ? qa.y : jj == 2 ? qa.z : qa.w;
-              acc2 = __builtin_amdgcn_mfma_f32_4x4x1f32(av, val, acc2, 0, 0, 0);
+              acc2[u] = __builtin_amdgcn_mfma_f32_4x4x1f32(bv, val, acc2[u], 0, 0, 0);
             }
           }
         }
       }
     }
-    if (valid) {
-      const float nu = a.norm != nullptr ? a.norm[row] : 1.f;
-      const float kg = PROD ? a.kappa * a.gamma[row] : 0.f;
+  }
+#pragma unroll
+  for (int u = 0; u < KPL; ++u) {
+    if (valid[u]) {
+      const float nu = a.norm != nullptr ? a.norm[row[u]] : 1.f;
+      const float kg = PROD ? a.kappa * a.gamma[row[u]] : 0.f;
+      const int64_t key = base + u * 64 + lane;
 #pragma unroll
       for (int r = 0; r < 4; ++r)
         if (r < nq_here)
-          a.scores[((int64_t)group * a.q_per_group + q0 + r) * a.lds + key] = nu * (acc[r] + kg * acc2[r]);
+          a.scores[((int64_t)group * a.q_per_group + q0 + r) * a.lds + key] = nu * (acc[u][r] + kg * acc2[u][r]);
     }
   }
 }
 
-template <int BITS>
-static hipError_t launch_bits(const ScoreSmallArgs& a, bool prod, dim3 grid, size_t smem, hipStream_t s) {
-  if (prod)
-    hipLaunchKernelGGL((score_small_kernel<BITS, true>), grid, dim3(256), smem, s, a);
+template <int BITS, bool PROD>
+static hipError_t launch_kpl(const ScoreSmallArgs& a, int n_groups, size_t smem, hipStream_t s) {
+  // two keys per lane once there is enough work to keep every SIMD busy anyway
+  const bool big = a.n * (int64_t)n_groups >= (int64_t)1 << 19;
+  const int kpl = big ? 2 : 1;
+  const dim3 grid((unsigned)((a.n + 256 * kpl - 1) / (256 * kpl)), n_groups, (a.q_per_group + 3) / 4);
+  if (big)
+    hipLaunchKernelGGL((score_small_kernel<BITS, PROD, 2>), grid, dim3(256), smem, s, a);
   else
-    hipLaunchKernelGGL((score_small_kernel<BITS, false>), grid, dim3(256), smem, s, a);
+    hipLaunchKernelGGL((score_small_kernel<BITS, PROD, 1>), grid, dim3(256), smem, s, a);
   return hipGetLastError();
+}
+
+template <int BITS>
+static hipError_t launch_bits(const ScoreSmallArgs& a, bool prod, int n_groups, size_t smem, hipStream_t s) {
+  return prod ? launch_kpl<BITS, true>(a, n_groups, smem, s) : launch_kpl<BITS, false>(a, n_groups, smem, s);
 }
 
 hipError_t launch_score_small(int bits, bool prod, const float* qr, const float* qs, const uint32_t* idx,
@@ -183,19 +218,18 @@ hipError_t launch_score_small(int bits, bool prod, const float* qr, const float*
                               int64_t lds, int64_t n, int d, int n_groups, int q_per_group, float kappa,
                               const Codebook& cb, hipStream_t stream) {
   if (n == 0 || n_groups == 0 || q_per_group == 0) return hipSuccess;
-  if (d % 128 != 0 || d > 2048) return hipErrorInvalidValue;
+  if (d % 128 != 0 || d > 1024) return hipErrorInvalidValue;
   ScoreSmallArgs a;
   a.qr = qr; a.qs = qs; a.idx = idx; a.qjl = qjl; a.gamma = gamma; a.norm = norm;
   a.scores = scores; a.lds = lds; a.n = n; a.d = d; a.q_per_group = q_per_group;
   a.kappa = kappa; a.cb = cb;
-  const dim3 grid((unsigned)((n + KEYS_PER_WG - 1) / KEYS_PER_WG), n_groups, (q_per_group + 3) / 4);
-  const size_t smem = (size_t)(prod ? 2 : 1) * 4 * d * sizeof(float);  // <= 64 KB for d <= 2048
+  const size_t smem = (size_t)(prod ? 2 : 1) * 4 * d * sizeof(float);  // <= 32 KB
   switch (bits) {
-    case 0: return launch_bits<0>(a, prod, grid, smem, stream);
-    case 1: return launch_bits<1>(a, prod, grid, smem, stream);
-    case 2: return launch_bits<2>(a, prod, grid, smem, stream);
-    case 3: return launch_bits<3>(a, prod, grid, smem, stream);
-    case 4: return launch_bits<4>(a, prod, grid, smem, stream);
+    case 0: return launch_bits<0>(a, prod, n_groups, smem, stream);
+    case 1: return launch_bits<1>(a, prod, n_groups, smem, stream);
+    case 2: return launch_bits<2>(a, prod, n_groups, smem, stream);
+    case 3: return launch_bits<3>(a, prod, n_groups, smem, stream);
+    case 4: return launch_bits<4>(a, prod, n_groups, smem, stream);
     default: return hipErrorInvalidValue;
   }
 }

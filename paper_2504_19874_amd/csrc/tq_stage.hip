@@ -9,17 +9,80 @@
 // number (= how many boundaries are <= y) is the XOR of the masks whose
 // position k satisfies k mod 2^p == 2^p - 1 (parity of floor(count / 2^p)).  So a b-bit decision costs
 // 2^b - 1 compares per 64 coordinates and no per-lane integer work.
+#include <utility>
+
 #include "tq_internal.h"
 
 namespace tq {
 
 constexpr int CHUNKS = 8;  // 64-coordinate chunks per wavefront iteration
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// put a wave-uniform 32-bit value into one lane of a vector register.  The value
+// usually comes straight from a vector compare (VALU-written scalar register);
+// v_writelane_b32 must not read such a register in the very next cycles, and the
+// compiler does not track hazards inside inline asm, so the value is first
+// copied by a scalar move (scalar reads of VALU-written registers are
+// interlocked by hardware, and scalar-written registers are safe to read).
+template <int LANE>
+__device__ __forceinline__ int write_lane(int old, uint32_t uniform_value) {
+  uint32_t tmp;
+  asm volatile("s_mov_b32 %1, %2\n\tv_writelane_b32 %0, %1, %3"
+               : "+v"(old), "=&s"(tmp)
+               : "s"(uniform_value), "n"(LANE));
+  return old;
+}
+
+// output word W of a super-chunk lives in lane W%64 of register W/64
+template <int W, int N>
+__device__ __forceinline__ void put_word(int (&mine)[N], uint32_t uniform_value) {
+  mine[W >> 6] = write_lane<(W & 63)>(mine[W >> 6], uniform_value);
+}
+
+template <int C, int PL, int N, int... P>
+__device__ __forceinline__ void route_planes(std::integer_sequence<int, P...>, const uint64_t (&plane)[PL],
+                                             int (&mine)[N]) {
+  ((put_word<(C * 2 + 0) * PL + P>(mine, (uint32_t)plane[P]),
+    put_word<(C * 2 + 1) * PL + P>(mine, (uint32_t)(plane[P] >> 32))),
+   ...);
+}
+
+template <int BITS, bool SIGN_ONLY, int C, int N>
+__device__ __forceinline__ void pack_chunk(const Codebook& cb, const float v, int (&mine)[N]) {
+  constexpr int PL = SIGN_ONLY ? 1 : BITS;
+  uint64_t plane[PL];
+  if (SIGN_ONLY) {
+    plane[0] = __ballot(v >= 0.f);
+  } else {
+#pragma unroll
+    for (int pl = 0; pl < PL; ++pl) plane[pl] = 0ull;
+#pragma unroll
+    for (int k = 0; k < (1 << BITS) - 1; ++k) {
+      const uint64_t m = __ballot(v >= cb.t[k]);
+#pragma unroll
+      for (int pl = 0; pl < PL; ++pl)
+        if ((k & ((1 << pl) - 1)) == (1 << pl) - 1) plane[pl] ^= m;
+    }
+  }
+  // the masks are wave-uniform scalars: drop each 32-bit half into the lane that stores it
+  route_planes<C, PL>(std::make_integer_sequence<int, PL>{}, plane, mine);
+  __builtin_amdgcn_sched_barrier(0);  // one chunk's masks at a time (scalar register pressure)
+}
+
+template <int BITS, bool SIGN_ONLY, int N, int... C>
+__device__ __forceinline__ void pack_chunks(std::integer_sequence<int, C...>, const Codebook& cb,
+                                            const float (&v)[CHUNKS], int (&mine)[N]) {
+  (pack_chunk<BITS, SIGN_ONLY, C>(cb, v[C], mine), ...);
+}
+
 template <int BITS, bool SIGN_ONLY>
 __global__ __launch_bounds__(256) void stage_pack_kernel(const Codebook cb, const float* __restrict__ y,
                                                          const int64_t n_groups32,  // groups of 32 floats
                                                          uint32_t* __restrict__ out) {
   constexpr int PL = SIGN_ONLY ? 1 : BITS;
+  constexpr int WORDS = CHUNKS * 2 * PL;       // output words per super-chunk
+  constexpr int PER_LANE = (WORDS + 63) / 64;  // lane L holds word L (and L+64 ...)
   const int lane = threadIdx.x & 63;
   const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
   const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
@@ -28,53 +91,31 @@ __global__ __launch_bounds__(256) void stage_pack_kernel(const Codebook cb, cons
   const int64_t n_super = (n_chunks + CHUNKS - 1) / CHUNKS;
   for (int64_t sc = wave; sc < n_super; sc += n_waves) {
     const int64_t c0 = sc * CHUNKS;
+    const float* src = y + c0 * 64 + lane;
     float v[CHUNKS];
+    if ((c0 + CHUNKS) * 64 <= total) {  // whole super-chunk in range: no per-load guards
 #pragma unroll
-    for (int c = 0; c < CHUNKS; ++c) {
-      const int64_t ch = c0 + c;
-      v[c] = (ch * 64 + lane < total) ? y[ch * 64 + lane] : 0.f;
+      for (int c = 0; c < CHUNKS; ++c) v[c] = __builtin_nontemporal_load(src + c * 64);
+    } else {
+#pragma unroll
+      for (int c = 0; c < CHUNKS; ++c) v[c] = ((c0 + c) * 64 + lane < total) ? src[c * 64] : 0.f;
     }
-    // lane L of the wave ends up holding output word L (and L+64, ... if any)
-    // of this super-chunk: word index = (chunk*2 + half)*PL + plane
-    constexpr int WORDS = CHUNKS * 2 * PL;
-    constexpr int PER_LANE = (WORDS + 63) / 64;
-    uint32_t mine[PER_LANE > 0 ? PER_LANE : 1];
+    int mine[PER_LANE];
 #pragma unroll
-    for (int q = 0; q < (PER_LANE > 0 ? PER_LANE : 1); ++q) mine[q] = 0u;
-#pragma unroll
-    for (int c = 0; c < CHUNKS; ++c) {
-      uint64_t plane[PL > 0 ? PL : 1];
-      if (SIGN_ONLY) {
-        plane[0] = __ballot(v[c] >= 0.f);
-      } else {
-#pragma unroll
-        for (int pl = 0; pl < PL; ++pl) plane[pl] = 0ull;
-#pragma unroll
-        for (int k = 0; k < (1 << BITS) - 1; ++k) {
-          const uint64_t m = __ballot(v[c] >= cb.t[k]);
-#pragma unroll
-          for (int pl = 0; pl < PL; ++pl)
-            if ((k & ((1 << pl) - 1)) == (1 << pl) - 1) plane[pl] ^= m;
-        }
-      }
-#pragma unroll
-      for (int pl = 0; pl < PL; ++pl) {
-        const int w_lo = (c * 2 + 0) * PL + pl;
-        const int w_hi = (c * 2 + 1) * PL + pl;
-        if (lane == (w_lo & 63)) mine[w_lo >> 6] = (uint32_t)plane[pl];
-        if (lane == (w_hi & 63)) mine[w_hi >> 6] = (uint32_t)(plane[pl] >> 32);
-      }
-    }
+    for (int q = 0; q < PER_LANE; ++q) mine[q] = 0;
+    pack_chunks<BITS, SIGN_ONLY>(std::make_integer_sequence<int, CHUNKS>{}, cb, v, mine);
     const int64_t word0 = c0 * 2 * PL;
     const int64_t word_end = n_groups32 * PL;
 #pragma unroll
     for (int q = 0; q < PER_LANE; ++q) {
       const int w = q * 64 + lane;
-      if (w < WORDS && word0 + w < word_end) out[word0 + w] = mine[q];
+      if (w < WORDS && word0 + w < word_end) out[word0 + w] = (uint32_t)mine[q];
     }
   }
 }
 
+// Each lane produces 4 consecutive coordinates (one 16-byte store); the 8 lanes
+// that share a 32-coordinate group read the same plane words.
 template <int BITS>
 __global__ __launch_bounds__(256) void stage_unpack_kernel(const Codebook cb, const uint32_t* __restrict__ idx,
                                                            const int64_t n_groups32,  // groups of 32 coords
@@ -82,15 +123,35 @@ __global__ __launch_bounds__(256) void stage_unpack_kernel(const Codebook cb, co
   __shared__ float cent_s[16];
   if (threadIdx.x < 16) cent_s[threadIdx.x] = cb.c[threadIdx.x];
   __syncthreads();
-  const int64_t total = n_groups32 * 32;
+  const int64_t n_quads = n_groups32 * 8;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += stride) {
-    const int64_t g = e >> 5;
-    const int l = (int)(e & 31);
-    uint32_t code = 0;
+  constexpr int U = 4;
+  for (int64_t q0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q0 < n_quads; q0 += stride * U) {
+    uint32_t w[U][BITS > 0 ? BITS : 1];
 #pragma unroll
-    for (int pl = 0; pl < BITS; ++pl) code |= ((idx[g * BITS + pl] >> l) & 1u) << pl;
-    out[e] = cent_s[code];
+    for (int u = 0; u < U; ++u) {
+      const int64_t qd = q0 + u * stride;
+      if (qd < n_quads) {
+#pragma unroll
+        for (int pl = 0; pl < BITS; ++pl) w[u][pl] = idx[(qd >> 3) * BITS + pl] >> (4 * (int)(qd & 7));
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t qd = q0 + u * stride;
+      if (qd < n_quads) {
+        float e[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          uint32_t code = 0;
+#pragma unroll
+          for (int pl = 0; pl < BITS; ++pl) code |= ((w[u][pl] >> k) & 1u) << pl;
+          e[k] = cent_s[code];
+        }
+        f32x4 o4 = {e[0], e[1], e[2], e[3]};
+        __builtin_nontemporal_store(o4, reinterpret_cast<f32x4*>(out) + qd);
+      }
+    }
   }
 }
 
@@ -148,7 +209,7 @@ hipError_t launch_stage_sign_pack(int d, const float* u, int64_t n, uint32_t* qj
 template <int BITS>
 static hipError_t unpack_bits(const Codebook& cb, const uint32_t* idx, int64_t groups, float* out,
                               hipStream_t s) {
-  hipLaunchKernelGGL((stage_unpack_kernel<BITS>), dim3(grid_for(64 * 4, groups * 32)), dim3(256), 0, s, cb,
+  hipLaunchKernelGGL((stage_unpack_kernel<BITS>), dim3(grid_for(64 * 4, groups * 8)), dim3(256), 0, s, cb,
                      idx, groups, out);
   return hipGetLastError();
 }
