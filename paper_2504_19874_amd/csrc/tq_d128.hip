@@ -62,45 +62,64 @@ __global__ __launch_bounds__(512) void quant128_kernel(const Quant128Args a) {
   }
   __syncthreads();
 
+  // fp32 MFMA and ordinary vector instructions do not overlap on this chip (a
+  // wavefront doing v_fma while another does v_mfma_f32 takes the sum of both
+  // times), so every vector instruction outside the contractions costs MFMA
+  // time: the epilogues below are written for instruction count.
+  constexpr int RAW = BF16IN ? 8 : 16;  // 16-byte loads per lane for one half row
   const int64_t n_blocks = (a.n + 31) / 32;
-  for (int64_t blk = (int64_t)blockIdx.x * 8 + wave; blk < n_blocks; blk += (int64_t)gridDim.x * 8) {
+  const int64_t blk_stride = (int64_t)gridDim.x * 8;
+  int64_t blk = (int64_t)blockIdx.x * 8 + wave;
+  uint4 raw[RAW];
+  auto load_raw = [&](int64_t b) {
+    const int64_t i = b * 32 + l32;
+    const bool ok = i < a.n;
+    const char* src = reinterpret_cast<const char*>(a.X) +
+                      ((ok ? i : 0) * a.ldx + 64 * h) * (BF16IN ? 2 : 4);
+#pragma unroll
+    for (int v = 0; v < RAW; ++v)
+      raw[v] = ok ? *reinterpret_cast<const uint4*>(src + 16 * v) : make_uint4(0, 0, 0, 0);
+  };
+  if (blk < n_blocks) load_raw(blk);
+
+  for (; blk < n_blocks; blk += blk_stride) {
     const int64_t i = blk * 32 + l32;
     const bool valid = i < a.n;
     float xb[64];
     if (BF16IN) {
-      const uint16_t* src = reinterpret_cast<const uint16_t*>(a.X) + (valid ? i : 0) * a.ldx + 64 * h;
 #pragma unroll
       for (int v = 0; v < 8; ++v) {
-        uint4 t = make_uint4(0, 0, 0, 0);
-        if (valid) t = *reinterpret_cast<const uint4*>(src + 8 * v);
-        xb[8 * v + 0] = __uint_as_float(t.x << 16); xb[8 * v + 1] = __uint_as_float(t.x & 0xffff0000u);
-        xb[8 * v + 2] = __uint_as_float(t.y << 16); xb[8 * v + 3] = __uint_as_float(t.y & 0xffff0000u);
-        xb[8 * v + 4] = __uint_as_float(t.z << 16); xb[8 * v + 5] = __uint_as_float(t.z & 0xffff0000u);
-        xb[8 * v + 6] = __uint_as_float(t.w << 16); xb[8 * v + 7] = __uint_as_float(t.w & 0xffff0000u);
+        xb[8 * v + 0] = __uint_as_float(raw[v].x << 16); xb[8 * v + 1] = __uint_as_float(raw[v].x & 0xffff0000u);
+        xb[8 * v + 2] = __uint_as_float(raw[v].y << 16); xb[8 * v + 3] = __uint_as_float(raw[v].y & 0xffff0000u);
+        xb[8 * v + 4] = __uint_as_float(raw[v].z << 16); xb[8 * v + 5] = __uint_as_float(raw[v].z & 0xffff0000u);
+        xb[8 * v + 6] = __uint_as_float(raw[v].w << 16); xb[8 * v + 7] = __uint_as_float(raw[v].w & 0xffff0000u);
       }
     } else {
-      const float* src = reinterpret_cast<const float*>(a.X) + (valid ? i : 0) * a.ldx + 64 * h;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (valid) t = *reinterpret_cast<const float4*>(src + 4 * v);
-        xb[4 * v] = t.x; xb[4 * v + 1] = t.y; xb[4 * v + 2] = t.z; xb[4 * v + 3] = t.w;
+        xb[4 * v] = __uint_as_float(raw[v].x); xb[4 * v + 1] = __uint_as_float(raw[v].y);
+        xb[4 * v + 2] = __uint_as_float(raw[v].z); xb[4 * v + 3] = __uint_as_float(raw[v].w);
       }
     }
-    float ss = 0.f;
+    float inv = 1.f, nu = 1.f;
+    if (a.normalise) {
+      float s0 = 0.f, s1 = 0.f;
 #pragma unroll
-    for (int k = 0; k < 64; ++k) ss = fmaf(xb[k], xb[k], ss);
-    ss += __shfl_xor(ss, 32);
-    const float nu = sqrtf(ss);
-    const float inv = a.normalise ? (nu > 0.f ? 1.f / nu : 0.f) : 1.f;
+      for (int k = 0; k < 64; k += 2) {
+        s0 = fmaf(xb[k], xb[k], s0);
+        s1 = fmaf(xb[k + 1], xb[k + 1], s1);
+      }
+      float ss = s0 + s1;
+      ss += __shfl_xor(ss, 32);
+      nu = sqrtf(ss);
+      inv = nu > 0.f ? 1.f / nu : 0.f;
+    }
 
     floatx16 acc[4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
     {
-      // operands of step k4+1 are read from LDS before the MFMAs of step k4 issue
+      // operands of step k4+1 are read from LDS before the MFMAs of step k4 issue;
+      // the very first MFMA of each tile takes a zero C operand instead of a cleared register
+      const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       float4 av[4], nx[4];
 #pragma unroll
       for (int t = 0; t < 4; ++t)
@@ -113,46 +132,63 @@ __global__ __launch_bounds__(512) void quant128_kernel(const Quant128Args a) {
             nx[t] = *reinterpret_cast<const float4*>(&Pi_s[(32 * t + l32) * PAD_LD + 64 * h + 4 * (k4 + 1)]);
         }
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t].x, xb[4 * k4 + 0], acc[t], 0, 0, 0);
-          acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t].y, xb[4 * k4 + 1], acc[t], 0, 0, 0);
-          acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t].z, xb[4 * k4 + 2], acc[t], 0, 0, 0);
-          acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t].w, xb[4 * k4 + 3], acc[t], 0, 0, 0);
-        }
+        for (int t = 0; t < 4; ++t)
+          acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t].x, xb[4 * k4 + 0], k4 == 0 ? zero : acc[t], 0, 0, 0);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t].y, xb[4 * k4 + 1], acc[t], 0, 0, 0);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t].z, xb[4 * k4 + 2], acc[t], 0, 0, 0);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t].w, xb[4 * k4 + 3], acc[t], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);  // bounds how far LDS reads are hoisted (register pressure)
 #pragma unroll
         for (int t = 0; t < 4; ++t) av[t] = nx[t];
       }
     }
+    // the next block's rows travel from HBM while this block is finished
+    if (blk + blk_stride < n_blocks) load_raw(blk + blk_stride);
 
-    // nearest centroid, packing, residual (in place)
+    // nearest centroid, packing, residual (in place).  Bit p of the bucket number is the XOR
+    // of the compare masks at positions k = 2^p - 1 (mod 2^p); a 4-bit nibble of a plane is
+    // built by shift-and-add-carry, most significant element first.
     float g2 = 0.f;
     uint32_t word[4][BITS > 0 ? BITS : 1];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      uint32_t piece[BITS > 0 ? BITS : 1];
+      uint32_t nib[4][BITS > 0 ? BITS : 1];
 #pragma unroll
-      for (int pl = 0; pl < (BITS > 0 ? BITS : 1); ++pl) piece[pl] = 0u;
+      for (int k = 0; k < 4; ++k) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float y = acc[t][r] * inv;
-        float yt = a.cb.c[0];
-        uint32_t code = 0u;
+        for (int pl = 0; pl < (BITS > 0 ? BITS : 1); ++pl) nib[k][pl] = 0u;
 #pragma unroll
-        for (int j = 0; j < (1 << BITS) - 1; ++j) {
-          const bool ge = y >= a.cb.t[j];
-          code += ge ? 1u : 0u;
-          yt = ge ? a.cb.c[j + 1] : yt;
+        for (int r = 3; r >= 0; --r) {
+          const float y = acc[t][4 * k + r] * inv;
+          float yt = a.cb.c[0];
+          bool bit[BITS > 0 ? BITS : 1];
+#pragma unroll
+          for (int pl = 0; pl < (BITS > 0 ? BITS : 1); ++pl) bit[pl] = false;
+#pragma unroll
+          for (int j = 0; j < (1 << BITS) - 1; ++j) {
+            const bool ge = y >= a.cb.t[j];
+            yt = ge ? a.cb.c[j + 1] : yt;
+#pragma unroll
+            for (int pl = 0; pl < BITS; ++pl)
+              if ((j & ((1 << pl) - 1)) == (1 << pl) - 1) bit[pl] = bit[pl] != ge;
+          }
+          float e = y - yt;
+          asm volatile("" : "+v"(e));  // keep the residual here: sunk later it would need the masks again
+          g2 = fmaf(e, e, g2);
+          acc[t][4 * k + r] = e;
+#pragma unroll
+          for (int pl = 0; pl < BITS; ++pl) {
+            nib[k][pl] = nib[k][pl] + nib[k][pl] + (bit[pl] ? 1u : 0u);
+            asm volatile("" : "+v"(nib[k][pl]));  // consume this element's masks now (scalar registers)
+          }
         }
-        const float e = y - yt;
-        g2 = fmaf(e, e, g2);
-        acc[t][r] = e;
-#pragma unroll
-        for (int pl = 0; pl < BITS; ++pl) piece[pl] |= ((code >> pl) & 1u) << (8 * (r >> 2) + (r & 3));
       }
 #pragma unroll
       for (int pl = 0; pl < BITS; ++pl) {
-        const uint32_t w = piece[pl] << (4 * h);
+        const uint32_t w = (nib[0][pl] | (nib[1][pl] << 8) | (nib[2][pl] << 16) | (nib[3][pl] << 24)) << (4 * h);
         word[t][pl] = w | (uint32_t)__shfl_xor((int)w, 32);
       }
     }
@@ -170,12 +206,9 @@ __global__ __launch_bounds__(512) void quant128_kernel(const Quant128Args a) {
     if (PROD) {
       g2 += __shfl_xor(g2, 32);
       floatx16 u[4];
-#pragma unroll
-      for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) u[t][r] = 0.f;
       // register 4*ke + r of tile te holds e_j with j = 32 te + 8 ke + 4 h + r
       {
+        const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         float4 av[4], nx[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t)
@@ -191,12 +224,14 @@ __global__ __launch_bounds__(512) void quant128_kernel(const Quant128Args a) {
                   &Sp_s[(32 * t + l32) * PAD_LD + 32 * te1 + 8 * ke1 + 4 * h]);
           }
 #pragma unroll
-          for (int t = 0; t < 4; ++t) {
-            u[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t].x, acc[te][4 * ke + 0], u[t], 0, 0, 0);
-            u[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t].y, acc[te][4 * ke + 1], u[t], 0, 0, 0);
-            u[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t].z, acc[te][4 * ke + 2], u[t], 0, 0, 0);
-            u[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t].w, acc[te][4 * ke + 3], u[t], 0, 0, 0);
-          }
+          for (int t = 0; t < 4; ++t)
+            u[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t].x, acc[te][4 * ke + 0], st == 0 ? zero : u[t], 0, 0, 0);
+#pragma unroll
+          for (int t = 0; t < 4; ++t) u[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t].y, acc[te][4 * ke + 1], u[t], 0, 0, 0);
+#pragma unroll
+          for (int t = 0; t < 4; ++t) u[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t].z, acc[te][4 * ke + 2], u[t], 0, 0, 0);
+#pragma unroll
+          for (int t = 0; t < 4; ++t) u[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[t].w, acc[te][4 * ke + 3], u[t], 0, 0, 0);
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int t = 0; t < 4; ++t) av[t] = nx[t];
@@ -205,10 +240,15 @@ __global__ __launch_bounds__(512) void quant128_kernel(const Quant128Args a) {
       uint32_t sw[4];
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
-        uint32_t piece = 0u;
+        uint32_t nib[4];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) piece |= (u[t][r] >= 0.f ? 1u : 0u) << (8 * (r >> 2) + (r & 3));
-        const uint32_t w = piece << (4 * h);
+        for (int k = 0; k < 4; ++k) {
+          nib[k] = 0u;
+#pragma unroll
+          for (int r = 3; r >= 0; --r) nib[k] = nib[k] + nib[k] + (u[t][4 * k + r] >= 0.f ? 1u : 0u);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        const uint32_t w = (nib[0] | (nib[1] << 8) | (nib[2] << 16) | (nib[3] << 24)) << (4 * h);
         sw[t] = w | (uint32_t)__shfl_xor((int)w, 32);
       }
       if (valid) {

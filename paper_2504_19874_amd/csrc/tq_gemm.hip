@@ -41,6 +41,7 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
   __shared__ __attribute__((aligned(16))) float Ns[TN * LDS_LD];
   __shared__ float row_ss[TN];
   __shared__ float cent_s[16];
+  __shared__ float thr_s[16];
 
   // workgroup -> tile.  Consecutive workgroup ids go round-robin over the 8
   // XCDs; give every XCD a contiguous range of tiles, m fastest, so the m
@@ -72,7 +73,12 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
   const int srow = tid >> 3;
   const int scol = (tid & 7) * 4;
 
-  if (NKIND == N_CODE && tid < 16) cent_s[tid] = a.cb.c[tid];
+  // the codebook goes to LDS once; indexing the argument block by thread id reads it from
+  // memory, so its 31 entries never occupy scalar registers
+  if ((NKIND == N_CODE || EKIND == E_QUANT) && tid < 16) {
+    cent_s[tid] = a.cb.c[tid];
+    thr_s[tid] = tid < 15 ? a.cb.t[tid] : 0.f;
+  }
 
   float4 wreg[4];
   uint32_t nreg[16];
@@ -213,6 +219,17 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
   }
 
   // ------------------------------- epilogue -------------------------------
+  // The epilogue takes the codebook from LDS into vector registers: with up to 31 table
+  // entries, the argument block and the compare masks all live at once the scalar file would
+  // overflow (spills through v_writelane), while vector registers are plentiful here.
+  constexpr int NT = (EKIND == E_QUANT) ? (1 << BITS) - 1 : 0;
+  float tv[NT > 0 ? NT : 1], cv[NT + 1];
+  if (EKIND == E_QUANT) {
+#pragma unroll
+    for (int j = 0; j < NT; ++j) tv[j] = thr_s[j];
+#pragma unroll
+    for (int j = 0; j <= NT; ++j) cv[j] = cent_s[j];
+  }
 #pragma unroll
   for (int tn = 0; tn < 2; ++tn) {
     const int vloc = wn * 64 + tn * 32 + l32;
@@ -256,32 +273,43 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
         }
       } else {
         constexpr int PL = (EKIND == E_SIGN) ? 1 : BITS;
-        uint32_t piece[PL > 0 ? PL : 1];
-#pragma unroll
-        for (int pl = 0; pl < (PL > 0 ? PL : 1); ++pl) piece[pl] = 0u;
+        constexpr int PLN = PL > 0 ? PL : 1;
+        // a 4-bit nibble of each bit plane per k, most significant element first; bit p of the
+        // bucket number is the XOR of the compare masks at positions j = 2^p - 1 (mod 2^p)
+        uint32_t nib[4][PLN];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
           float e[4];
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            uint32_t code;
+          for (int pl = 0; pl < PLN; ++pl) nib[k][pl] = 0u;
+#pragma unroll
+          for (int r = 3; r >= 0; --r) {
+            bool bit[PLN];
+#pragma unroll
+            for (int pl = 0; pl < PLN; ++pl) bit[pl] = false;
             if (EKIND == E_SIGN) {
-              code = (c[4 * k + r] >= 0.f) ? 1u : 0u;
+              bit[0] = c[4 * k + r] >= 0.f;
               e[r] = 0.f;
             } else {
               const float y = c[4 * k + r] * scale;
-              float yt = a.cb.c[0];
-              code = 0u;
+              float yt = cv[0];
 #pragma unroll
-              for (int j = 0; j < (1 << BITS) - 1; ++j) {
-                const bool ge = y >= a.cb.t[j];
-                code += ge ? 1u : 0u;
-                yt = ge ? a.cb.c[j + 1] : yt;
+              for (int j = 0; j < NT; ++j) {
+                const bool ge = y >= tv[j];
+                yt = ge ? cv[j + 1] : yt;
+#pragma unroll
+                for (int pl = 0; pl < PL; ++pl)
+                  if ((j & ((1 << pl) - 1)) == (1 << pl) - 1) bit[pl] = bit[pl] != ge;
               }
-              e[r] = y - yt;
+              float ev = y - yt;
+              asm volatile("" : "+v"(ev));  // computed here, while the compare masks are live
+              e[r] = ev;
             }
 #pragma unroll
-            for (int pl = 0; pl < PL; ++pl) piece[pl] |= ((code >> pl) & 1u) << (8 * k + r);
+            for (int pl = 0; pl < PL; ++pl) {
+              nib[k][pl] = nib[k][pl] + nib[k][pl] + (bit[pl] ? 1u : 0u);
+              asm volatile("" : "+v"(nib[k][pl]));  // consume this element's masks now (scalar registers)
+            }
           }
           if (EKIND == E_QUANT && a.resid_out != nullptr) {
             const int m = mb + 8 * k + 4 * h;
@@ -290,6 +318,10 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
                   make_float4(e[0], e[1], e[2], e[3]);
           }
         }
+        uint32_t piece[PLN];
+#pragma unroll
+        for (int pl = 0; pl < PLN; ++pl)
+          piece[pl] = nib[0][pl] | (nib[1][pl] << 8) | (nib[2][pl] << 16) | (nib[3][pl] << 24);
         // merge the two half-waves (rows 8k+r and 8k+4+r) and let half tm&1 store
 #pragma unroll
         for (int pl = 0; pl < PL; ++pl) {
