@@ -102,6 +102,19 @@ def algorithmic_work(cfg, call: str):
     return flops, n * code_b + 4 * pairs + 4 * nq * d
 
 
+def measured_traffic(workload: str, kernel: str):
+    """HBM bytes per launch of the dominant call, from the rocprofv3 --pmc FETCH_SIZE and
+    WRITE_SIZE runs recorded under profiles/ (scaled there by a plain copy of known size);
+    None when no measurement has been recorded for this workload and call."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            table = json.load(f)
+        return table[workload][kernel]["traffic_bytes"]
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def cpu_baseline(cfg, host_x, q, budget_s=20.0):
     """The oracle, untuned, on a bounded sample of the same workload."""
     import numpy as np
@@ -149,6 +162,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C3b4", "C4", "C5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
@@ -165,6 +180,14 @@ def main():
     cfg, p, bufs, host_x, q = build_workload(args.workload)
     calls = make_calls(tq, cfg, p, bufs)
     n = cfg.n * cfg.n_groups
+
+    if args.calibration_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)  # 256 MiB read + 256 MiB written, shows up as one elementwise kernel
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         for _, fn in calls:
@@ -202,6 +225,7 @@ def main():
                 "frac": ach / PEAK_HBM_GBS, "traffic": None}
     roof["kernel"] = f"tq_{dom_name}" + ("_prod" if dom_name == "quantize" and cfg.kind == "prod" else "")
     roof["avg_ms"] = per_call_ms[dom]
+    roof["traffic"] = measured_traffic(cfg.name, roof["kernel"])
 
     out = {
         "metric": "vectors quantized/s through quantize+dequantize+score (one GPU)",

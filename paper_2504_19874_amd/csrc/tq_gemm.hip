@@ -37,8 +37,9 @@ __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w 
 template <int NKIND, int EKIND, int BITS>
 __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const int tiles_m,
                                                    const int tiles_n, const int per_xcd) {
-  __shared__ __attribute__((aligned(16))) float Ws[TM * LDS_LD];
-  __shared__ __attribute__((aligned(16))) float Ns[TN * LDS_LD];
+  __shared__ __attribute__((aligned(16))) float stage_s[(TM + TN) * LDS_LD];
+  float* const Ws = stage_s;                // [TM][LDS_LD]
+  float* const Ns = stage_s + TM * LDS_LD;  // [TN][LDS_LD]
   __shared__ float row_ss[TN];
   __shared__ float cent_s[16];
   __shared__ float thr_s[16];
@@ -148,16 +149,24 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
       } else {
         float e[4];
         if (!seg) {
+          // four coordinates at once: each plane's 4 bits are spread to one bit per byte by a
+          // multiply (bit i lands at 8i), planes are merged so that byte q holds 4*code_q,
+          // which is the byte offset into the LDS centroid table
+          uint32_t x = 0;
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            uint32_t code = 0;
-#pragma unroll
-            for (int pl = 0; pl < BITS; ++pl) code |= ((nreg[4 * p + pl] >> (scol + q)) & 1u) << pl;
-            e[q] = cent_s[code];
+          for (int pl = 0; pl < BITS; ++pl) {
+            const uint32_t nibble = (nreg[4 * p + pl] >> scol) & 0xFu;
+            x |= ((nibble * 0x00204081u) & 0x01010101u) << (pl + 2);
           }
-        } else {
 #pragma unroll
-          for (int q = 0; q < 4; ++q) e[q] = ((nreg[4 * p] >> (scol + q)) & 1u) ? kg[p] : -kg[p];
+          for (int q = 0; q < 4; ++q)
+            e[q] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(cent_s) + ((x >> (8 * q)) & 0xFFu));
+        } else {
+          // +-kappa*gamma: the sign bit comes from the inverted qjl bit
+          const uint32_t zn = ~nreg[4 * p] >> scol;
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            e[q] = __uint_as_float(((zn << (31 - q)) & 0x80000000u) | __float_as_uint(kg[p]));
         }
         v = make_float4(e[0], e[1], e[2], e[3]);
       }
@@ -230,6 +239,47 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
 #pragma unroll
     for (int j = 0; j <= NT; ++j) cv[j] = cent_s[j];
   }
+  if (EKIND == E_STORE_T) {
+    // D is held with the vector on the lane axis, so a lane owns 4 consecutive m of one
+    // vector: stored directly that is 16 bytes per lane at a row stride.  Instead the tile is
+    // turned in LDS, 64 vectors at a time (the two wavefronts with the same wn), and written
+    // out by all threads along m.
+    constexpr int T_LD = TM + 4;
+    float* const T = stage_s;  // [64][T_LD] <= (TM + TN) * LDS_LD floats
+#pragma unroll 1
+    for (int w = 0; w < 2; ++w) {
+      __syncthreads();
+      if (wn == w) {
+#pragma unroll
+        for (int tn = 0; tn < 2; ++tn) {
+          const int64_t i = n0 + wn * 64 + tn * 32 + l32;
+          float scale = 1.f;
+          if (a.scale_in != nullptr && i < a.n) scale = a.scale_in[vec_base + i];
+#pragma unroll
+          for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+              const floatx16& c = acc[tm][tn];
+              *reinterpret_cast<float4*>(&T[(tn * 32 + l32) * T_LD + wm * 64 + tm * 32 + 8 * k + 4 * h]) =
+                  make_float4(c[4 * k] * scale, c[4 * k + 1] * scale, c[4 * k + 2] * scale, c[4 * k + 3] * scale);
+            }
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int f = tid + 256 * j;  // 64 rows x 32 float4
+        const int row = f >> 5, c4 = f & 31;
+        const int64_t i = n0 + w * 64 + row;
+        const int m = m0 + 4 * c4;
+        if (i < a.n && m < a.M)
+          *reinterpret_cast<float4*>(a.out + (vec_base + i) * a.ldo + m) =
+              *reinterpret_cast<const float4*>(&T[row * T_LD + 4 * c4]);
+      }
+    }
+    return;
+  }
+
 #pragma unroll
   for (int tn = 0; tn < 2; ++tn) {
     const int vloc = wn * 64 + tn * 32 + l32;
@@ -250,16 +300,7 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
       const int mb = m0 + wm * 64 + tm * 32;  // first row of this 32x32 tile
       const floatx16& c = acc[tm][tn];
       if (EKIND == E_STORE_T) {
-        if (valid) {
-#pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            const int m = mb + 8 * k + 4 * h;
-            if (m < a.M)
-              *reinterpret_cast<float4*>(a.out + (vec_base + i) * a.ldo + m) =
-                  make_float4(c[4 * k] * scale, c[4 * k + 1] * scale, c[4 * k + 2] * scale,
-                              c[4 * k + 3] * scale);
-          }
-        }
+        // handled below, through LDS, so that rows leave the chip as whole 512-byte lines
       } else if (EKIND == E_STORE_N) {
         if (valid) {
           float* o = a.out + (int64_t)group * a.out_group_stride + i;
