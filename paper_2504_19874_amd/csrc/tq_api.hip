@@ -191,6 +191,7 @@ size_t tq_workspace_bytes(const tq_params* p, int64_t n, int64_t nq, int32_t top
   const size_t rows = (size_t)(n < kChunkRows ? n : kChunkRows);
   size_t bytes = round_up(rows * d * sizeof(float), 256);          // residual of quantize_prod
   bytes += 2 * round_up((size_t)nq * d * sizeof(float), 256);      // rotated / sketched queries
+  bytes += round_up(score_i8_workspace_bytes(p->d, nq), 256);      // or their int8 digit images
   if (topk > 0) bytes += round_up((size_t)nq * (size_t)(n + 3) * sizeof(float), 256);  // scores when not returned
   return bytes + 256;
 }
@@ -265,11 +266,30 @@ tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_gr
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int d = p->d;
 
+  const bool small_i8 = q_per_group <= 32 && d % 64 == 0 && d <= 512 && p->bits_mse <= 3;
   Workspace ws{static_cast<char*>(p->workspace), p->workspace_bytes, 0};
+  int64_t ld_scores = lds;
+  if (small_i8) {
+    // few queries per code: masked sums of fixed-point query digits on the int8 matrix cores;
+    // its own preparation kernel rotates the queries and writes their digit images
+    void* img = ws.take(score_i8_workspace_bytes(d, nq));
+    if (img == nullptr) return TQ_ERR_WORKSPACE;
+    if (scores == nullptr) {
+      ld_scores = (n_per_group + 3) / 4 * 4;
+      scores = static_cast<float*>(ws.take((size_t)nq * ld_scores * sizeof(float)));
+      if (scores == nullptr) return TQ_ERR_WORKSPACE;
+    }
+    if (launch_score_i8(p->bits_mse, prod, p->Pi, p->S, q, ldq, img, idx, qjl, gamma, norm, scores, ld_scores,
+                        n_per_group, d, n_groups, q_per_group, kappa_of(d), make_codebook(p), s) != hipSuccess)
+      return TQ_ERR_HIP;
+    if (topk > 0 &&
+        launch_topk(scores, nq, n_per_group, ld_scores, topk, topk_idx, topk_val, s) != hipSuccess)
+      return TQ_ERR_HIP;
+    return TQ_OK;
+  }
   float* qr = static_cast<float*>(ws.take((size_t)nq * d * sizeof(float)));
   float* qs = prod ? static_cast<float*>(ws.take((size_t)nq * d * sizeof(float))) : nullptr;
   if (qr == nullptr || (prod && qs == nullptr)) return TQ_ERR_WORKSPACE;
-  int64_t ld_scores = lds;
   if (scores == nullptr) {
     ld_scores = (n_per_group + 3) / 4 * 4;
     scores = static_cast<float*>(ws.take((size_t)nq * ld_scores * sizeof(float)));

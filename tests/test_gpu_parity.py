@@ -254,6 +254,9 @@ def test_dequantize(d, bits_mse, n, prod, with_norm):
 @pytest.mark.parametrize("d,bits_mse,prod,n_groups,qpg,npg,topk", [
     (128, 2, True, 8, 4, 1000, 0), (128, 2, False, 1, 64, 4096, 10), (128, 3, True, 2, 4, 129, 5),
     (256, 4, False, 1, 130, 300, 10), (1536, 4, False, 1, 33, 257, 10), (128, 0, True, 1, 7, 100, 3),
+    # few queries per code: int8 path (bits <= 3, d <= 512) and the fp32 lane-per-key path (the rest)
+    (384, 1, False, 2, 5, 130, 4), (512, 3, True, 1, 4, 2100, 0), (64, 2, True, 3, 2, 77, 0),
+    (128, 4, True, 2, 4, 300, 0), (640, 2, True, 1, 3, 200, 0), (128, 2, True, 1, 32, 1100, 0),
 ])
 def test_score_and_topk(d, bits_mse, prod, n_groups, qpg, npg, topk):
     p, Pi, S, c32, t32 = setup(d, bits_mse, prod)
