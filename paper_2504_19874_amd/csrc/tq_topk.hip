@@ -13,7 +13,7 @@ __device__ __forceinline__ bool better(float va, int ia, float vb, int ib) {
 
 template <int KMAX>
 __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ scores, const int64_t n,
-                                                   const int64_t ld, const int k,
+                                                   const int64_t ld, const int k, const int vec4,
                                                    int32_t* __restrict__ out_idx,
                                                    float* __restrict__ out_val) {
   extern __shared__ unsigned char smem_raw[];
@@ -34,15 +34,12 @@ __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ sco
     bv[j] = NEG;
     bi[j] = 0x7fffffff;
   }
-  for (int64_t i = tid; i < n; i += 256) {
-    float v = row[i];
-    int id = (int)i;
-    // position k-1 holds this thread's current worst kept entry
-    bool take = false;
-#pragma unroll
-    for (int j = 0; j < KMAX; ++j)
-      if (j == k - 1) take = better(v, id, bv[j], bi[j]);
-    if (take) {
+  // position k-1 of a thread's list is its current worst kept entry: almost every element is
+  // rejected by one compare against it
+  float worst_v = NEG;
+  int worst_i = 0x7fffffff;
+  auto consider = [&](float v, int id) {
+    if (better(v, id, worst_v, worst_i)) {
       // insert by a single pass of compare-exchange from the top
 #pragma unroll
       for (int j = 0; j < KMAX; ++j) {
@@ -54,8 +51,38 @@ __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ sco
           v = tv;
           id = ti;
         }
+        if (j == k - 1) {
+          worst_v = bv[j];
+          worst_i = bi[j];
+        }
       }
     }
+  };
+  if (vec4) {
+    // 16-byte loads, four of them in flight per thread before any compare
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    const f32x4* row4 = reinterpret_cast<const f32x4*>(row);
+    const int64_t n4 = n >> 2;
+    constexpr int U = 4;
+    for (int64_t i0 = tid; i0 < n4; i0 += 256 * U) {
+      f32x4 v[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int64_t i = i0 + 256 * u;
+        v[u] = i < n4 ? __builtin_nontemporal_load(row4 + i) : f32x4{NEG, NEG, NEG, NEG};
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int id = (int)((i0 + 256 * u) << 2);
+        consider(v[u].x, id);
+        consider(v[u].y, id + 1);
+        consider(v[u].z, id + 2);
+        consider(v[u].w, id + 3);
+      }
+    }
+    for (int64_t i = (n4 << 2) + tid; i < n; i += 256) consider(row[i], (int)i);
+  } else {
+    for (int64_t i = tid; i < n; i += 256) consider(row[i], (int)i);
   }
 #pragma unroll
   for (int j = 0; j < KMAX; ++j)
@@ -112,15 +139,16 @@ hipError_t launch_topk(const float* scores, int64_t rows, int64_t n, int64_t ld,
   if (rows == 0 || k == 0) return hipSuccess;
   if (k < 1 || k > 64 || rows > 0x7fffffff || n > 0x7fffffff) return hipErrorInvalidValue;
   const size_t smem = (size_t)256 * k * 8;
+  const int vec4 = (ld % 4 == 0) && ((reinterpret_cast<uintptr_t>(scores) & 15u) == 0);
   if (k <= 16)
-    hipLaunchKernelGGL((topk_kernel<16>), dim3((unsigned)rows), dim3(256), smem, stream, scores, n, ld, k,
+    hipLaunchKernelGGL((topk_kernel<16>), dim3((unsigned)rows), dim3(256), smem, stream, scores, n, ld, k, vec4,
                        out_idx, out_val);
   else {
     // more than 64 KB of dynamic LDS has to be allowed explicitly
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&topk_kernel<64>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((topk_kernel<64>), dim3((unsigned)rows), dim3(256), smem, stream, scores, n, ld, k,
+    hipLaunchKernelGGL((topk_kernel<64>), dim3((unsigned)rows), dim3(256), smem, stream, scores, n, ld, k, vec4,
                        out_idx, out_val);
   }
   return hipGetLastError();
