@@ -21,9 +21,12 @@
 // half-wave through one cross-lane exchange.
 #include "tq_internal.h"
 
+#include <type_traits>
+
 namespace tq {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int TM = 128;      // rows of W per workgroup
 constexpr int TN = 128;      // vectors per workgroup
@@ -37,9 +40,9 @@ __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w 
 template <int NKIND, int EKIND, int BITS>
 __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const int tiles_m,
                                                    const int tiles_n, const int per_xcd) {
-  __shared__ __attribute__((aligned(16))) float stage_s[(TM + TN) * LDS_LD];
-  float* const Ws = stage_s;                // [TM][LDS_LD]
-  float* const Ns = stage_s + TM * LDS_LD;  // [TN][LDS_LD]
+  // two staging buffers of [TM + TN][LDS_LD] floats: one is read by the MFMAs while the next
+  // k-tile is written into the other, so a k-step costs a single workgroup barrier
+  extern __shared__ __attribute__((aligned(16))) float stage_s[];
   __shared__ float row_ss[TN];
   __shared__ float cent_s[16];
   __shared__ float thr_s[16];
@@ -63,8 +66,6 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
   const int m0 = tile_m * TM;
   const int64_t n0 = (int64_t)tile_n * TN;
   const int64_t vec_base = (int64_t)group * a.n;  // first vector row of this group
-  const float* W1 = a.W1 + (int64_t)group * a.w_group_stride;
-  const float* W2 = (a.segs > 1) ? a.W2 + (int64_t)group * a.w_group_stride : nullptr;
 
   const int kt_per_seg = a.d / BK;
   const int n_kt = kt_per_seg * a.segs;
@@ -81,62 +82,73 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
     thr_s[tid] = tid < 15 ? a.cb.t[tid] : 0.f;
   }
 
-  float4 wreg[4];
-  uint32_t nreg[16];
-  float ss[4] = {0.f, 0.f, 0.f, 0.f};
+  // Addresses are a per-tile uniform base plus a small per-thread offset.  Rows past the end
+  // of either operand are clamped onto the last valid row: what they produce is never stored.
+  const int rows_m = min(TM, a.M - m0);
+  const int rows_n = (int)min((int64_t)TN, a.n - n0);
+  const float* const W1 = a.W1 + (int64_t)group * a.w_group_stride + (int64_t)m0 * a.ldw;
+  const float* const W2 =
+      (a.segs > 1) ? a.W2 + (int64_t)group * a.w_group_stride + (int64_t)m0 * a.ldw : nullptr;
+  const float* const Xf = reinterpret_cast<const float*>(a.X) + (NKIND == N_F32 ? (vec_base + n0) * a.ldx : 0);
+  const uint16_t* const Xh =
+      reinterpret_cast<const uint16_t*>(a.X) + (NKIND == N_BF16 ? (vec_base + n0) * a.ldx : 0);
+  const uint32_t* const Ci = a.idx + (NKIND == N_CODE ? (vec_base + n0) * words_per_row : 0);
+  const uint32_t* const Cq = a.qjl + ((NKIND == N_CODE && a.segs > 1) ? (vec_base + n0) * kt_per_seg : 0);
+  uint32_t woff[4], noff[4], qoff[4];
   float kg[4] = {0.f, 0.f, 0.f, 0.f};
-  if (NKIND == N_CODE && a.segs > 1) {
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const int64_t i = n0 + srow + 32 * p;
-      kg[p] = (i < a.n) ? a.kappa * a.gamma[vec_base + i] : 0.f;
-    }
+  for (int p = 0; p < 4; ++p) {
+    const uint32_t rm = (uint32_t)min(srow + 32 * p, rows_m - 1);
+    const uint32_t rn = (uint32_t)min(srow + 32 * p, rows_n - 1);
+    woff[p] = rm * (uint32_t)a.ldw + scol;
+    noff[p] = (NKIND == N_CODE) ? rn * (uint32_t)words_per_row : rn * (uint32_t)a.ldx + scol;
+    qoff[p] = rn * (uint32_t)kt_per_seg;
+    if (NKIND == N_CODE && a.segs > 1) kg[p] = a.kappa * a.gamma[vec_base + n0 + rn];
   }
 
-  auto load_tiles = [&](int kt) {
-    const int seg = kt >= kt_per_seg;
-    const int kk = (kt - seg * kt_per_seg) * BK;
-    const float* W = seg ? W2 : W1;
+  f32x4 wreg[4];  // native vectors: these stay in registers
+  uint32_t nreg[16];
+  float ss[4] = {0.f, 0.f, 0.f, 0.f};
+
+  // global -> registers for k-tile kt; SEG (0: rotated codebook part, 1: sign sketch part)
+  // only matters for packed codes and is a compile-time constant of each loop below
+  auto load_tiles = [&](auto seg_c, int kt) {
+    constexpr int SEG = decltype(seg_c)::value;
+    const int g = kt - SEG * kt_per_seg;
+    const float* W = (SEG ? W2 : W1) + g * BK;
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const int m = m0 + srow + 32 * p;
-      wreg[p] = (m < a.M) ? *reinterpret_cast<const float4*>(W + (int64_t)m * a.ldw + kk + scol)
-                          : make_float4(0.f, 0.f, 0.f, 0.f);
-    }
+    for (int p = 0; p < 4; ++p) wreg[p] = *reinterpret_cast<const f32x4*>(W + woff[p]);
+    if (NKIND == N_F32) {
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const int64_t i = n0 + srow + 32 * p;
-      const bool valid = i < a.n;
-      if (NKIND == N_F32) {
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (valid)
-          v = *reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(a.X) +
-                                              (vec_base + i) * a.ldx + kk + scol);
+      for (int p = 0; p < 4; ++p) {
+        const uint4 v = *reinterpret_cast<const uint4*>(Xf + g * BK + noff[p]);
         nreg[4 * p + 0] = v.x; nreg[4 * p + 1] = v.y; nreg[4 * p + 2] = v.z; nreg[4 * p + 3] = v.w;
-      } else if (NKIND == N_BF16) {
-        uint2 v = make_uint2(0, 0);
-        if (valid)
-          v = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(a.X) +
-                                              (vec_base + i) * a.ldx + kk + scol);
-        nreg[4 * p + 0] = v.x; nreg[4 * p + 1] = v.y;
-      } else {
-        const int g = kt - seg * kt_per_seg;
-        if (!seg) {
-#pragma unroll
-          for (int pl = 0; pl < BITS; ++pl)
-            nreg[4 * p + pl] = valid ? a.idx[(vec_base + i) * words_per_row + g * BITS + pl] : 0u;
-        } else {
-          nreg[4 * p] = valid ? a.qjl[(vec_base + i) * kt_per_seg + g] : 0u;
-        }
       }
+    } else if (NKIND == N_BF16) {
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        const uint2 v = *reinterpret_cast<const uint2*>(Xh + g * BK + noff[p]);
+        nreg[4 * p + 0] = v.x; nreg[4 * p + 1] = v.y;
+      }
+    } else if (SEG == 0) {
+      const uint32_t* C = Ci + g * BITS;
+#pragma unroll
+      for (int p = 0; p < 4; ++p)
+#pragma unroll
+        for (int pl = 0; pl < BITS; ++pl) nreg[4 * p + pl] = C[noff[p] + pl];
+    } else {
+      const uint32_t* C = Cq + g;
+#pragma unroll
+      for (int p = 0; p < 4; ++p) nreg[4 * p] = C[qoff[p]];
     }
   };
 
-  auto store_tiles = [&](int kt) {
-    const int seg = kt >= kt_per_seg;
+  // registers -> staging buffer (decoding packed codes on the way)
+  auto store_tiles = [&](auto seg_c, float* Ws, float* Ns) {
+    constexpr int SEG = decltype(seg_c)::value;
 #pragma unroll
     for (int p = 0; p < 4; ++p)
-      *reinterpret_cast<float4*>(&Ws[(srow + 32 * p) * LDS_LD + scol]) = wreg[p];
+      *reinterpret_cast<f32x4*>(&Ws[(srow + 32 * p) * LDS_LD + scol]) = wreg[p];
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
       float4 v;
@@ -148,7 +160,7 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
                         bf16_hi(nreg[4 * p + 1]));
       } else {
         float e[4];
-        if (!seg) {
+        if (SEG == 0) {
           // four coordinates at once: each plane's 4 bits are spread to one bit per byte by a
           // multiply (bit i lands at 8i), planes are merged so that byte q holds 4*code_q,
           // which is the byte offset into the LDS centroid table
@@ -183,12 +195,8 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  load_tiles(0);
-  __syncthreads();  // cent_s visible before the first decode
-  for (int kt = 0; kt < n_kt; ++kt) {
-    store_tiles(kt);
-    __syncthreads();
-    if (kt + 1 < n_kt) load_tiles(kt + 1);  // in flight while the MFMAs run
+  constexpr int BUF = (TM + TN) * LDS_LD;
+  auto mfma_tile = [&](const float* Ws, const float* Ns) {
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       float4 av[2], bv[2];
@@ -207,7 +215,40 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i].w, bv[j].w, acc[i][j], 0, 0, 0);
         }
     }
+  };
+
+  // Step kt: the registers hold k-tile kt+1 (segment SN); it goes into the buffer that step
+  // kt-1 read, k-tile kt+2 (segment SF) is requested, and the MFMAs run on k-tile kt.  The
+  // barrier that ends the step both publishes the new buffer and retires the old one.
+  auto steps = [&](int kt_begin, int kt_end, auto sn_c, auto sf_c) {
+    for (int kt = kt_begin; kt < kt_end; ++kt) {
+      float* const cur = stage_s + (kt & 1) * BUF;
+      float* const nxt = stage_s + ((kt + 1) & 1) * BUF;
+      if (kt + 1 < n_kt) store_tiles(sn_c, nxt, nxt + TM * LDS_LD);
+      if (kt + 2 < n_kt) load_tiles(sf_c, kt + 2);
+      mfma_tile(cur, cur + TM * LDS_LD);
+      __syncthreads();
+    }
+  };
+  using S0 = std::integral_constant<int, 0>;
+  using S1 = std::integral_constant<int, 1>;
+
+  load_tiles(S0{}, 0);
+  __syncthreads();  // cent_s visible before the first decode
+  store_tiles(S0{}, stage_s, stage_s + TM * LDS_LD);
+  if (NKIND == N_CODE && a.segs > 1) {
+    if (n_kt > 1) {
+      if (kt_per_seg > 1) load_tiles(S0{}, 1);
+      else load_tiles(S1{}, 1);
+    }
     __syncthreads();
+    steps(0, kt_per_seg - 2, S0{}, S0{});
+    if (kt_per_seg >= 2) steps(kt_per_seg - 2, kt_per_seg - 1, S0{}, S1{});
+    steps(kt_per_seg - 1, n_kt, S1{}, S1{});
+  } else {
+    if (n_kt > 1) load_tiles(S0{}, 1);
+    __syncthreads();
+    steps(0, n_kt, S0{}, S0{});
   }
 
   // squared norms of the streamed rows: 8 neighbouring lanes share a row
@@ -387,7 +428,11 @@ static hipError_t launch_one(const GemmArgs& a, int n_groups, hipStream_t stream
   if (total == 0 || n_groups == 0) return hipSuccess;
   const int per_xcd = (total + XCDS - 1) / XCDS;
   dim3 grid(per_xcd * XCDS, n_groups, 1);
-  hipLaunchKernelGGL((gemm_kernel<NKIND, EKIND, BITS>), grid, dim3(256), 0, stream, a, tiles_m,
+  constexpr int lds_bytes = 2 * (TM + TN) * LDS_LD * (int)sizeof(float);  // above the 64 KB default limit
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<NKIND, EKIND, BITS>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((gemm_kernel<NKIND, EKIND, BITS>), grid, dim3(256), lds_bytes, stream, a, tiles_m,
                      tiles_n, per_xcd);
   return hipGetLastError();
 }
