@@ -266,7 +266,7 @@ tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_gr
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int d = p->d;
 
-  const bool small_i8 = q_per_group <= 32 && d % 64 == 0 && d <= 512 && p->bits_mse <= 3;
+  const bool small_i8 = q_per_group <= 32 && score_i8_applicable(p->bits_mse, d, make_codebook(p));
   Workspace ws{static_cast<char*>(p->workspace), p->workspace_bytes, 0};
   int64_t ld_scores = lds;
   if (small_i8) {
@@ -279,7 +279,7 @@ tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_gr
       scores = static_cast<float*>(ws.take((size_t)nq * ld_scores * sizeof(float)));
       if (scores == nullptr) return TQ_ERR_WORKSPACE;
     }
-    if (launch_score_i8(p->bits_mse, prod, p->Pi, p->S, q, ldq, img, idx, qjl, gamma, norm, scores, ld_scores,
+    if (launch_score_i8(p->bits_mse, prod, p->Pi, p->S, p->PiT, p->ST, q, ldq, img, idx, qjl, gamma, norm, scores, ld_scores,
                         n_per_group, d, n_groups, q_per_group, kappa_of(d), make_codebook(p), s) != hipSuccess)
       return TQ_ERR_HIP;
     if (topk > 0 &&

@@ -82,7 +82,9 @@ hipError_t launch_score_small(int bits, bool prod, const float* qr, const float*
 
 // few queries per code on the integer matrix cores (tq_score_i8.hip)
 size_t score_i8_workspace_bytes(int d, int64_t nq);
-hipError_t launch_score_i8(int bits, bool prod, const float* Pi, const float* S, const float* q, int64_t ldq,
+bool score_i8_applicable(int bits, int d, const Codebook& cb);  // d % 128 == 0, d <= 512, symmetric table
+hipError_t launch_score_i8(int bits, bool prod, const float* Pi, const float* S, const float* PiT, const float* ST,
+                           const float* q, int64_t ldq,
                            void* workspace, const uint32_t* idx, const uint32_t* qjl, const float* gamma,
                            const float* norm, float* scores, int64_t lds, int64_t n, int d, int n_groups,
                            int q_per_group, float kappa, const Codebook& cb, hipStream_t stream);

@@ -3,115 +3,167 @@
 // The estimator of Sec. 3.2 in the rotated basis,
 //     s = nu * ( sum_j qr_j c[idx_j]  +  kappa gamma sum_j qs_j z_j ),
 // only ever multiplies query coordinates by a function of a few BITS of the
-// code.  Written out over the bit planes b_p of idx (the packed layout stores
-// exactly these planes),
-//     c[idx] = sum over subsets S of planes of  coef_S * prod_{p in S} b_p ,
-// (coef = Moebius transform of the centroid table), so
-//     sum_j qr_j c[idx_j] = coef_0 * sum_j qr_j + sum_S coef_S * M_S,
-//     M_S = sum of qr_j over the coordinates where all planes in S are 1,
+// code.  Over the bit planes b_p of idx (the packed layout stores exactly these
+// planes) the centroid table has the Walsh expansion
+//     c[idx] = sum over subsets S of planes of  w_S * prod_{p in S} (2 b_p - 1),
+// and a product of +-1 factors is +-1 according to the parity of the planes in
+// S, i.e. to one bit of the XOR of those plane words.  Hence
+//     sum_j qr_j c[idx_j] = const * sum_j qr_j + sum_S coef_S * M_S,
+//     M_S = sum of qr_j over the coordinates where the XOR of the planes in S is 1,
 // and likewise sum_j qs_j z_j = 2 * M_Z - sum_j qs_j with Z the qjl plane.
+// A codebook that is symmetric about zero (the Lloyd-Max solution for the
+// symmetric coordinate density of Lemma 1 is) has w_S = 0 for every S of even
+// size, which leaves 1, 2, 4, 8 terms for 1..4 bits; terms whose coefficient is
+// exactly zero are never formed: this path is taken only for tables with
+// c[K-1-v] = -c[v] exactly (score_i8_applicable), nothing is approximated.
 // Every M is a 0/1-masked sum: an int8 x int8 contraction on the matrix cores
 // (v_mfma_i32_16x16x64_i8) between fixed-point digits of the queries and the
-// mask expanded to one byte per bit.  Unlike fp32 MFMA, this does not compete
-// with the vector ALU for the expansion work, and the expansion itself is one
-// LDS lookup per 8 coordinates (byte -> 8 bytes) instead of per-coordinate
-// bit fiddling.
+// mask expanded to one byte per bit; the expansion is one LDS lookup per 8
+// coordinates (byte -> 8 bytes) instead of per-coordinate bit fiddling.
 //
-// Fixed point: per query, Q_j = round(q_j * 2^e) with |Q_j| < 2^20, offset to
-// q'_j = Q_j + 2^20 in [0, 2^21) and split into three 7-bit digits (0..127, so
-// they are valid signed bytes).  Rows of the A operand: 4 queries x (3 digits +
-// one row of ones); the ones row yields popcount(mask), which removes the
-// offset: sum_j mask_j Q_j = D0 + 2^7 D1 + 2^14 D2 - 2^20 popcount.  Integer
-// arithmetic is exact; the only rounding is that of q to 21 bits (relative
-// 2^-20 of the query's largest coordinate), far inside the 1e-4 tolerance.
+// Fixed point: per query, Q_j = round(q_j * 2^e) with |Q_j| < 2^20, written in
+// balanced base 128: Q = D0 + 2^7 D1 + 2^14 D2 with digits in [-64, 64] (valid
+// signed bytes).  Rows of the A operand: 4 queries x (3 digits + one unused
+// row).  Integer arithmetic is exact; the only rounding is that of q to 21 bits
+// (relative 2^-20 of the query's largest coordinate), far inside 1e-4.
 //
 // Operand layout of v_mfma_i32_16x16x64_i8: A row / B column = lane % 16, the
 // lane's 16 bytes are 16 values of k for k-chunk lane / 16 (any bijection of k
 // works as long as A and B use the same one); D[4*(lane/16) + r][lane % 16] in
 // register r.  With row = 4*query + digit a lane ends up holding the three
-// digit sums and the popcount for ONE (query, key) pair.
+// digit sums for ONE (query, key) pair.
+//
+// Which coordinates a lane feeds: d is a multiple of 128 here, so the d/32
+// plane-word groups of a key split evenly over the four k-chunks: lane chunk kq
+// owns groups kq, kq+4, ...; k-step s = 2i + h uses half h (16 coordinates) of
+// its i-th group.  A lane therefore loads whole words of its own groups only:
+// no word is fetched twice and the 16 keys x 4 chunks of a tile read one
+// contiguous span of the code arrays.
+//
+// LDS lookups by data-dependent address collide on banks when all lanes share
+// one 2 KB table (measured: that was the bound of this kernel).  The table is
+// therefore replicated 32 times, copy c = lane % 32 living in banks 2c, 2c+1
+// (entry e of copy c at dword 64 e + 2 c): every lookup is conflict free.  The
+// 64 KB table is filled while the code words are in flight.
 #include "tq_internal.h"
+
+#include <type_traits>
 
 namespace tq {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// coordinate block of (k-step s, k-chunk kq): 16 coordinates starting here
+__host__ __device__ constexpr int i8_coord0(int s, int kq) { return 32 * (kq + 4 * (s >> 1)) + 16 * (s & 1); }
 
 // ---------------------------------------------------------------------------
 // Query preparation for the int8 path: rotate / sketch one query per workgroup
 // (y = W q for W = Pi or S), choose the fixed-point scale, and write the digit
 // bytes in the order the scoring kernel's A operand wants them.
-// grid (nq, 1 or 2 matrices), 128 threads; thread j owns output coordinate j.
+// grid (nq, 1 or 2 matrices), 512 threads.  Row j of W is read by the 32 lanes
+// of a half-wavefront, 16 bytes each, and reduced across them.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(128) void prep_i8_kernel(const int d, const float* __restrict__ W0,
+template <int P>  // P = d / 128: 16-byte pieces per lane per row; a half-wavefront owns 8 P rows
+__global__ __launch_bounds__(512) void prep_i8_kernel(const int d, const float* __restrict__ W0,
                                                       const float* __restrict__ W1,
                                                       const float* __restrict__ x, const int64_t ldx,
                                                       uint4* __restrict__ img, float* __restrict__ scal) {
-  extern __shared__ __attribute__((aligned(16))) float prep_s[];  // x[d] then y[d]
-  float* xs = prep_s;
-  float* ys = prep_s + d;
-  __shared__ float red_mx[2];
-  __shared__ int red_tot[2];
+  __shared__ float ys[512];
+  __shared__ float red_mx[8];
+  __shared__ int red_tot[8];
   const int tid = threadIdx.x;
+  const int l32 = tid & 31, hw = tid >> 5;  // 16 half-wavefronts
   const int64_t q = blockIdx.x;
   const int mat = blockIdx.y;
   const float* W = mat == 0 ? W0 : W1;
-  for (int k = tid; k < d; k += 128) xs[k] = x[q * ldx + k];
-  __syncthreads();
-  float mx = 0.f;
-  for (int j = tid; j < d; j += 128) {
-    const float4* w4 = reinterpret_cast<const float4*>(W + (int64_t)j * d);
-    const float4* x4 = reinterpret_cast<const float4*>(xs);
-    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-#pragma unroll 8
-    for (int k4 = 0; k4 < d / 4; ++k4) {
-      const float4 w = w4[k4], v = x4[k4];
-      a0 = fmaf(w.x, v.x, a0); a1 = fmaf(w.y, v.y, a1); a2 = fmaf(w.z, v.z, a2); a3 = fmaf(w.w, v.w, a3);
+  // this lane's share of the query, then 8 rows at a time, all their loads in flight together
+  f32x4 xv[P];
+#pragma unroll
+  for (int c = 0; c < P; ++c) xv[c] = *reinterpret_cast<const f32x4*>(x + q * ldx + 128 * c + 4 * l32);
+#pragma unroll 1
+  for (int r0 = 0; r0 < 8 * P; r0 += 8) {
+    f32x4 wv[8][P];
+#pragma unroll
+    for (int r = 0; r < 8; ++r)
+#pragma unroll
+      for (int c = 0; c < P; ++c)
+        wv[r][c] = *reinterpret_cast<const f32x4*>(W + (int64_t)(hw + 16 * (r0 + r)) * d + 128 * c + 4 * l32);
+    float part[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      float acc = 0.f;
+#pragma unroll
+      for (int c = 0; c < P; ++c) {
+        acc = fmaf(wv[r][c].x, xv[c].x, acc); acc = fmaf(wv[r][c].y, xv[c].y, acc);
+        acc = fmaf(wv[r][c].z, xv[c].z, acc); acc = fmaf(wv[r][c].w, xv[c].w, acc);
+      }
+      part[r] = acc;
     }
-    const float y = (a0 + a1) + (a2 + a3);
-    ys[j] = y;
-    mx = fmaxf(mx, fabsf(y));
+#pragma unroll
+    for (int off = 16; off >= 1; off >>= 1)
+#pragma unroll
+      for (int r = 0; r < 8; ++r) part[r] += __shfl_xor(part[r], off);
+#pragma unroll
+    for (int r = 0; r < 8; ++r)
+      if (l32 == r) ys[hw + 16 * (r0 + r)] = part[r];
   }
+  __syncthreads();
+  float mx = tid < d ? fabsf(ys[tid]) : 0.f;
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
   if ((tid & 63) == 0) red_mx[tid >> 6] = mx;
   __syncthreads();
-  mx = fmaxf(red_mx[0], red_mx[1]);
+  mx = red_mx[0];
+#pragma unroll
+  for (int w = 1; w < 8; ++w) mx = fmaxf(mx, red_mx[w]);
   // power-of-two scale with |Q| < 2^20
   int e = 0;
   if (mx > 0.f) (void)frexpf(mx, &e);  // mx = f * 2^e, f in [0.5, 1)
   const float sc = ldexpf(1.f, 19 - e);
-  int tot = 0;
-  for (int j = tid; j < d; j += 128) tot += __float2int_rn(ys[j] * sc);
+  int tot = tid < d ? __float2int_rn(ys[tid] * sc) : 0;
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) tot += __shfl_xor(tot, off);
   if ((tid & 63) == 0) red_tot[tid >> 6] = tot;
   __syncthreads();
   if (tid == 0) {
+    int t = 0;
+#pragma unroll
+    for (int w = 0; w < 8; ++w) t += red_tot[w];
     scal[(q * 2 + mat) * 2 + 0] = ldexpf(1.f, e - 19);
-    scal[(q * 2 + mat) * 2 + 1] = (float)(red_tot[0] + red_tot[1]) * ldexpf(1.f, e - 19);
+    scal[(q * 2 + mat) * 2 + 1] = (float)t * ldexpf(1.f, e - 19);
   }
   const int ks = d >> 6;
-  for (int u = tid; u < ks * 16; u += 128) {  // unit = (k-step s, digit dg, k-chunk kq)
+  for (int u = tid; u < ks * 16; u += 512) {  // unit = (k-step s, digit dg, k-chunk kq)
     const int kq = u & 3, dg = (u >> 2) & 3, s = u >> 4;
+    const int c0 = i8_coord0(s, kq);
     uint32_t w[4] = {0, 0, 0, 0};
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
-      const int Q = __float2int_rn(ys[64 * s + 16 * kq + k] * sc);
-      const uint32_t qp = (uint32_t)(Q + (1 << 20));
-      const uint32_t byte = dg == 3 ? 1u : ((qp >> (7 * dg)) & 0x7Fu);
-      w[k >> 2] |= byte << (8 * (k & 3));
+      // balanced digits: D0, D1 in [-64, 63], D2 in [-64, 64]
+      const int Q = __float2int_rn(ys[c0 + k] * sc);
+      const int d0 = ((Q + 64) & 127) - 64;
+      const int Q1 = (Q - d0) >> 7;
+      const int d1 = ((Q1 + 64) & 127) - 64;
+      const int d2 = (Q1 - d1) >> 7;
+      const int dig = dg == 0 ? d0 : dg == 1 ? d1 : dg == 2 ? d2 : 0;
+      w[k >> 2] |= ((uint32_t)dig & 0xFFu) << (8 * (k & 3));
     }
     img[((q * 2 + mat) * ks + s) * 16 + dg * 4 + kq] = make_uint4(w[0], w[1], w[2], w[3]);
   }
 }
 
 // Image of one query's A operand, written by prep_i8_kernel: for matrix m (0: Pi q, 1: S q),
-// k-step s, digit row dg, k-chunk kq the 16 bytes of coordinates 64 s + 16 kq .. + 15.
+// k-step s, digit row dg, k-chunk kq the 16 bytes of coordinates i8_coord0(s, kq) .. + 15.
 //   bytes:   img[((q * 2 + m) * ks + s) * 16 + dg * 4 + kq]      (16-byte units)
 //   scalars: scal[(q * 2 + m) * 2 + {0: 1/scale, 1: sum of the rounded coordinates}]
 struct ScoreI8Args {
   const uint4* img;
   const float* scal;
+  const float* PiT;  // fused variant only: transposed matrices and the raw queries
+  const float* ST;
+  const float* x;
+  int64_t ldx;
   const uint32_t* idx;
   const uint32_t* qjl;
   const float* gamma;
@@ -121,190 +173,447 @@ struct ScoreI8Args {
   int64_t n;
   int d;
   int q_per_group;
-  int keys_per_wg;
   float kappa;
-  float coef[8];  // coef[S] for plane subsets S = 0 .. 2^BITS - 1
+  float coef[16];  // coef[0]: factor of sum_j qr_j; coef[S]: factor of M_S (odd |S| only)
 };
 
 constexpr int I8_MAX_KS = 8;  // d <= 512
+// the terms the kernel evaluates: plane subsets of odd size (symmetric codebook)
+__host__ __device__ constexpr bool i8_term(int m) { return __builtin_popcount((unsigned)m) & 1; }
+// tiles of 16 keys per wavefront: as many as the register file holds code words for
+__host__ __device__ constexpr int i8_tiles(int bits, int ksm) { return (bits >= 4 ? 16 : 32) / ksm; }
+constexpr int I8_COPIES = 32;
+constexpr int I8_TABLE_BYTES = 256 * I8_COPIES * 8;
 
-// KSM: compile-time bound on the number of 64-coordinate k-steps (register arrays)
-template <int BITS, bool PROD, int KSM>
-__global__ __launch_bounds__(256) void score_i8_kernel(const ScoreI8Args a) {
-  __shared__ __attribute__((aligned(8))) uint2 expand_s[256];  // byte -> one byte per bit
+// KSM: compile-time bound on the number of 64-coordinate k-steps (register arrays).
+// A wavefront owns i8_tiles() tiles of 16 keys and requests all their code words up front.
+//
+// FUSED (d = 128 only): the workgroup prepares its own four queries while its code words are
+// in flight, instead of reading images written by prep_i8_kernel.  Wavefront w accumulates
+// y_j = sum_k W^T[k][j] x_k for matrix w/4, half (w/2)%2 of k and columns j = tid % 128, the
+// query coordinates coming through scalar registers; wavefront w then digitises (matrix w/4,
+// query w%4).  The 128 KB of matrix reads per workgroup hit in L2.
+template <int BITS, bool PROD, int KSM, bool FUSED>
+__global__ __launch_bounds__(512) void score_i8_kernel(const ScoreI8Args a) {
+  __shared__ __attribute__((aligned(16))) uint2 expand_s[256 * I8_COPIES];  // [256][32]: byte -> one byte per bit
+  extern __shared__ __attribute__((aligned(16))) unsigned char fused_s[];   // fused variant: partial sums, digits, scalars
+  constexpr int GI = KSM / 2;      // plane-word groups per lane
+  constexpr int TILES = i8_tiles(BITS, KSM);  // tiles per wavefront
+  constexpr int NM = (1 << BITS) - 1;
+  constexpr int NW = BITS > 0 ? BITS : 1;
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // in a scalar register: addresses built from it are uniform
   const int col = lane & 15;   // key within a tile / row of A
   const int kq = lane >> 4;    // k-chunk; also the query whose sums this lane receives
   const int group = blockIdx.y;
   const int q0 = blockIdx.z * 4;
-  const int d = a.d;
-  const int ks = d >> 6;  // k-steps of 64 coordinates
+  const int d = FUSED ? 128 : a.d;
+  const int ks = d >> 6;  // k-steps of 64 coordinates (even)
+  const int gi = ks >> 1;
 
-  {
-    uint32_t lo = 0, hi = 0;
-#pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      lo |= ((tid >> b) & 1u) << (8 * b);
-      hi |= ((tid >> (b + 4)) & 1u) << (8 * b);
-    }
-    expand_s[tid] = make_uint2(lo, hi);
-  }
-
-  // ---- A operands: digits of this group's queries, kept in registers -----------------
-  // lane = row + 16*kq, row = 4*query + digit; digit 3 is the row of ones
+  // lane = row + 16*kq of the A operand, row = 4*query + digit
   const int a_query = col >> 2, a_digit = col & 3;
   const bool a_live = q0 + a_query < a.q_per_group;
   const int64_t qrow = (int64_t)group * a.q_per_group + q0 + (a_live ? a_query : 0);
-  v4i ar[KSM], as_[KSM];
-#pragma unroll
-  for (int s = 0; s < KSM; ++s) {
-    uint4 r = make_uint4(0, 0, 0, 0), z = make_uint4(0, 0, 0, 0);
-    if (s < ks) {
-      if (BITS > 0) r = a.img[((qrow * 2 + 0) * ks + s) * 16 + a_digit * 4 + kq];
-      if (PROD) z = a.img[((qrow * 2 + 1) * ks + s) * 16 + a_digit * 4 + kq];
-    }
-    ar[s] = v4i{(int)r.x, (int)r.y, (int)r.z, (int)r.w};
-    as_[s] = v4i{(int)z.x, (int)z.y, (int)z.z, (int)z.w};
-  }
-  // scale and coordinate sum of the query kq whose results this lane receives
-  const bool q_live = q0 + kq < a.q_per_group;
-  const int64_t orow = (int64_t)group * a.q_per_group + q0 + (q_live ? kq : 0);
-  const float r_inv = a.scal[(orow * 2 + 0) * 2], r_sum = a.scal[(orow * 2 + 0) * 2 + 1];
-  const float s_inv = PROD ? a.scal[(orow * 2 + 1) * 2] : 0.f, s_sum = PROD ? a.scal[(orow * 2 + 1) * 2 + 1] : 0.f;
+  // the query kq whose results this lane receives
   const bool out_live = q0 + kq < a.q_per_group;
+  const int64_t orow = (int64_t)group * a.q_per_group + q0 + (out_live ? kq : 0);
+  v4i ar[KSM], as_[KSM];
+  float r_inv = 0.f, r_sum = 0.f, s_inv = 0.f, s_sum = 0.f;
+
+  // ---- 1. what the query side needs from memory is requested first (loads return in order) --
+  // not fused: digit images and scalars written by prep_i8_kernel
+  // fused:     this thread's column of the transposed matrix, 64 values of k
+  float wv[FUSED ? 64 : 1];
+  const int p_mat = wave >> 2, p_kh = (wave >> 1) & 1, p_j = tid & 127;
+  const bool p_work = p_mat == 0 ? BITS > 0 : PROD;  // uniform
+  if (!FUSED) {
+#pragma unroll
+    for (int s = 0; s < KSM; ++s) {
+      uint4 r = make_uint4(0, 0, 0, 0), z = make_uint4(0, 0, 0, 0);
+      if (s < ks) {
+        if (BITS > 0) r = a.img[((qrow * 2 + 0) * ks + s) * 16 + a_digit * 4 + kq];
+        if (PROD) z = a.img[((qrow * 2 + 1) * ks + s) * 16 + a_digit * 4 + kq];
+      }
+      ar[s] = v4i{(int)r.x, (int)r.y, (int)r.z, (int)r.w};
+      as_[s] = v4i{(int)z.x, (int)z.y, (int)z.z, (int)z.w};
+    }
+    if (BITS > 0) {
+      r_inv = a.scal[(orow * 2 + 0) * 2];
+      r_sum = a.scal[(orow * 2 + 0) * 2 + 1];
+    }
+    if (PROD) {
+      s_inv = a.scal[(orow * 2 + 1) * 2];
+      s_sum = a.scal[(orow * 2 + 1) * 2 + 1];
+    }
+  } else if (p_work) {
+    const float* WT = (p_mat ? a.ST : a.PiT) + (64 * p_kh) * 128 + p_j;
+#pragma unroll
+    for (int k = 0; k < 64; ++k) wv[k] = WT[k * 128];
+  }
+
+  // ---- 2. every code word of this wavefront's keys goes in flight: the first tile can start
+  // while the later ones are still on their way ------------------------------------------
+  const int groups = d >> 5;
+  const int words_per_row = groups * BITS;
+  const int64_t gbase = (int64_t)group * a.n;
+  const int64_t wave_key0 = ((int64_t)blockIdx.x * 8 + wave) * (16 * TILES);
+  const bool full = wave_key0 + 16 * TILES <= a.n;  // uniform: no key of this wavefront is past the end
+  uint32_t pw[TILES][GI][NW], zw[TILES][GI];
+  float kg[TILES], nu[TILES];
+  auto load_codes = [&](auto clamp_c) {
+    constexpr bool CLAMP = decltype(clamp_c)::value;
+    // one base address per array and lane; without clamping the tiles are constant offsets from it
+    const int64_t key0 = wave_key0 + col;
+    const int64_t row0 = gbase + (key0 < a.n ? key0 : a.n - 1);
+    const uint32_t* const pi0 = a.idx + row0 * words_per_row + kq * BITS;
+    const uint32_t* const pz0 = a.qjl + (PROD ? row0 * groups + kq : 0);
+    const float* const pg0 = a.gamma + (PROD ? row0 : 0);
+    const float* const pn0 = a.norm + (a.norm != nullptr ? row0 : 0);
+#pragma unroll
+    for (int t = 0; t < TILES; ++t) {
+      // rows advance by 16 per tile; a clamped row (results of such lanes are not stored) moves
+      // back by the same number of rows in every array
+      int back = 0;
+      if (CLAMP) back = (int)(key0 + 16 * t < a.n ? 0 : key0 + 16 * t - (a.n - 1)) - (int)(key0 < a.n ? 0 : key0 - (a.n - 1));
+      const int dr = 16 * t - back;  // row - row0
+      const uint32_t* pi = pi0 + dr * words_per_row;
+      const uint32_t* pz = pz0 + dr * groups;
+#pragma unroll
+      for (int i = 0; i < GI; ++i) {
+        const int io = i < gi ? i : 0;
+#pragma unroll
+        for (int pl = 0; pl < BITS; ++pl) pw[t][i][pl] = pi[io * 4 * BITS + pl];
+        zw[t][i] = PROD ? pz[io * 4] : 0u;
+      }
+      kg[t] = PROD ? pg0[dr] : 0.f;
+      nu[t] = a.norm != nullptr ? pn0[dr] : 1.f;
+    }
+  };
+  if (full) load_codes(std::false_type{});
+  else load_codes(std::true_type{});
+
+  // ---- 2b. (fused) rotate / sketch and digitise this workgroup's four queries ------------
+  float* const part_s = reinterpret_cast<float*>(fused_s);  // [2][2][4][128]
+  signed char* const dig_s = reinterpret_cast<signed char*>(part_s + 2 * 2 * 4 * 128);                // [2][4][4][128]
+  float* const scal_s = reinterpret_cast<float*>(dig_s + 2 * 4 * 4 * 128);                             // [2][4][2]
+  if (FUSED) {
+    if (p_work) {
+      const float* xq[4];  // uniform addresses: the query coordinates arrive in scalar registers
+#pragma unroll
+      for (int qi = 0; qi < 4; ++qi) {
+        const int64_t r = (int64_t)group * a.q_per_group + (q0 + qi < a.q_per_group ? q0 + qi : q0);
+        xq[qi] = a.x + r * a.ldx + 64 * p_kh;
+      }
+      float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int k = 0; k < 64; ++k)
+#pragma unroll
+        for (int qi = 0; qi < 4; ++qi) acc[qi] = fmaf(wv[k], xq[qi][k], acc[qi]);
+#pragma unroll
+      for (int qi = 0; qi < 4; ++qi) part_s[((p_mat * 2 + p_kh) * 4 + qi) * 128 + p_j] = acc[qi];
+    }
+    __syncthreads();
+    const int mat = wave >> 2, qi = wave & 3;
+    if (mat == 0 ? BITS > 0 : PROD) {
+      const bool live = q0 + qi < a.q_per_group;
+      float y[2];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int j = lane + 64 * u;
+        y[u] = live ? part_s[((mat * 2 + 0) * 4 + qi) * 128 + j] + part_s[((mat * 2 + 1) * 4 + qi) * 128 + j] : 0.f;
+      }
+      float mx = fmaxf(fabsf(y[0]), fabsf(y[1]));
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+      int e = 0;
+      if (mx > 0.f) (void)frexpf(mx, &e);  // mx = f * 2^e, f in [0.5, 1): |Q| <= 2^19
+      const float sc = ldexpf(1.f, 19 - e);
+      int Q[2], tot;
+      Q[0] = __float2int_rn(y[0] * sc);
+      Q[1] = __float2int_rn(y[1] * sc);
+      tot = Q[0] + Q[1];
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) tot += __shfl_xor(tot, off);
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int d0 = ((Q[u] + 64) & 127) - 64;
+        const int Q1 = (Q[u] - d0) >> 7;
+        const int d1 = ((Q1 + 64) & 127) - 64;
+        const int d2 = (Q1 - d1) >> 7;
+        signed char* o = dig_s + (mat * 4 + qi) * 4 * 128 + lane + 64 * u;
+        o[0] = (signed char)d0;
+        o[128] = (signed char)d1;
+        o[256] = (signed char)d2;
+        o[384] = 0;
+      }
+      if (lane == 0) {
+        scal_s[(mat * 4 + qi) * 2 + 0] = ldexpf(1.f, e - 19);
+        scal_s[(mat * 4 + qi) * 2 + 1] = (float)tot * ldexpf(1.f, e - 19);
+      }
+    }
+  }
+
+  // ---- 3. the expansion table, 32 bank-private copies ------------------------------------
+  // thread -> (entry tid/32 + 16 i, copy tid%32): consecutive threads write consecutive
+  // addresses; the low nibble of the entry is the thread's own, the high nibble is i
+  {
+    const uint32_t lo = (((uint32_t)tid >> 5) * 0x00204081u) & 0x01010101u;  // bit i of the nibble -> byte i
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const uint32_t hi = ((uint32_t)i * 0x00204081u) & 0x01010101u;
+      expand_s[tid + 512 * i] = make_uint2(lo, hi);
+    }
+  }
   __syncthreads();
 
-  const int words_per_row = (d >> 5) * BITS;
-  const int qw_per_row = d >> 5;
-  const int64_t gbase = (int64_t)group * a.n;
-  const int half_shift = 16 * (kq & 1);  // this lane's 16 coordinates inside a 32-bit word
-  const char* const table = reinterpret_cast<const char*>(expand_s);
+  if (FUSED) {
+#pragma unroll
+    for (int s = 0; s < KSM; ++s) {
+      ar[s] = v4i{0, 0, 0, 0};
+      as_[s] = v4i{0, 0, 0, 0};
+      if (s < 2) {
+        const int c0 = i8_coord0(s, kq);
+        if (BITS > 0) ar[s] = *reinterpret_cast<const v4i*>(dig_s + ((0 * 4 + a_query) * 4 + a_digit) * 128 + c0);
+        if (PROD) as_[s] = *reinterpret_cast<const v4i*>(dig_s + ((1 * 4 + a_query) * 4 + a_digit) * 128 + c0);
+      }
+    }
+    if (BITS > 0) {
+      r_inv = scal_s[(0 * 4 + kq) * 2];
+      r_sum = scal_s[(0 * 4 + kq) * 2 + 1];
+    }
+    if (PROD) {
+      s_inv = scal_s[(1 * 4 + kq) * 2];
+      s_sum = scal_s[(1 * 4 + kq) * 2 + 1];
+    }
+  }
 
-  auto expand16 = [&](uint32_t w16) -> v4i {  // low 16 bits -> 16 bytes of 0/1
-    const uint2 lo = *reinterpret_cast<const uint2*>(table + ((w16 << 3) & 0x7F8u));
-    const uint2 hi = *reinterpret_cast<const uint2*>(table + ((w16 >> 5) & 0x7F8u));
+  const uint32_t copy_off = (uint32_t)(lane & (I8_COPIES - 1)) * 8u;
+  const char* const table = reinterpret_cast<const char*>(expand_s);
+  // bits [16 h, 16 h + 16) of w -> 16 bytes of 0/1.  Table offset = 256 * byte + 8 * copy: one
+  // byte permute puts byte k of w into bits 8..15 above the copy offset in bits 0..7.
+  auto expand16 = [&](uint32_t w, int h) -> v4i {
+    const uint32_t o0 = __builtin_amdgcn_perm(w, copy_off, h ? 0x0c0c0600u : 0x0c0c0400u);
+    const uint32_t o1 = __builtin_amdgcn_perm(w, copy_off, h ? 0x0c0c0700u : 0x0c0c0500u);
+    const uint2 lo = *reinterpret_cast<const uint2*>(table + o0);
+    const uint2 hi = *reinterpret_cast<const uint2*>(table + o1);
     return v4i{(int)lo.x, (int)lo.y, (int)hi.x, (int)hi.y};
   };
-  auto masked_sum = [&](const v4i& acc) -> float {  // D0 + 2^7 D1 + 2^14 D2 - 2^20 popcount
-    return (float)(acc[0] + (acc[1] << 7) + (acc[2] << 14) - (acc[3] << 20));
+  auto digits_sum = [&](const v4i& acc) -> float {  // D0 + 2^7 D1 + 2^14 D2
+    return (float)(acc[0] + acc[1] * 128 + acc[2] * 16384);
   };
 
-  // A wavefront takes 4 tiles of 16 keys per pass and requests all of their code words
-  // before touching any: the kernel lives on bytes in flight, not on arithmetic.
-  constexpr int TPP = 4;                // tiles per pass
-  constexpr int NM = (1 << BITS) - 1;   // number of non-empty plane subsets
-  constexpr int NW = BITS > 0 ? BITS : 1;
-  const int64_t wg_key0 = (int64_t)blockIdx.x * a.keys_per_wg;
-  const int passes = a.keys_per_wg / (4 * 16 * TPP);
-  for (int pass = 0; pass < passes; ++pass) {
-    const int64_t pass0 = wg_key0 + ((int64_t)pass * 4 + wave) * (16 * TPP);
-    if (pass0 >= a.n) break;
-    int64_t row[TPP];
-    bool valid[TPP];
-    uint32_t pw[TPP][KSM][NW], zw[TPP][KSM];
-    float kg[TPP], nu[TPP];
+  // per-lane constants of the final combination
+  float cr[NM > 0 ? NM : 1];
 #pragma unroll
-    for (int t = 0; t < TPP; ++t) {
-      const int64_t key = pass0 + t * 16 + col;
-      valid[t] = key < a.n;
-      row[t] = gbase + (valid[t] ? key : 0);
+  for (int m = 1; m <= NM; ++m) cr[m - 1] = a.coef[m] * r_inv;
+  const float base_r = a.coef[0] * r_sum;
+  const float zs = 2.f * s_inv;
+  float* const out0 = a.scores + ((int64_t)group * a.q_per_group + q0 + kq) * a.lds + wave_key0 + col;
+
+  // The tiles run as a three-stage software pipeline, written out in source order: while the
+  // MFMAs of tile t issue, the table lookups of tile t+1 are already on their way and the
+  // sums of tile t-1 are combined and stored, so no stage waits for its own latency.
+  // A wavefront whose keys all exist runs it without per-tile bounds tests; the last
+  // wavefront of a group takes the guarded version.
+  constexpr int NT = (BITS > 0 ? (1 << (BITS - 1)) : 0) + (PROD ? 1 : 0);  // masked sums per tile
+  constexpr int NTA = NT > 0 ? NT : 1;
+  auto run_tiles = [&](auto full_c) {
+    constexpr bool FULL = decltype(full_c)::value;
+    constexpr bool PIPE = KSM * NTA <= 12;
+    v4i bop[2][PIPE ? KSM : 1][NTA];  // expanded B operands of the tiles in flight
+    v4i acc[2][NTA];       // sums of two tiles
+    auto lookups = [&](int t, v4i (&b)[PIPE ? KSM : 1][NTA]) {
+      if (!PIPE) return;
 #pragma unroll
       for (int s = 0; s < KSM; ++s) {
         if (s >= ks) break;
-        const int g = 2 * s + (kq >> 1);  // the 32-coordinate group this lane's k-chunk lies in
+        int j = 0;
 #pragma unroll
-        for (int pl = 0; pl < BITS; ++pl) pw[t][s][pl] = a.idx[row[t] * words_per_row + g * BITS + pl];
-        if (PROD) zw[t][s] = a.qjl[row[t] * qw_per_row + g];
+        for (int m = 1; m <= NM; ++m) {
+          if (!i8_term(m)) continue;
+          uint32_t w = 0u;
+#pragma unroll
+          for (int pl = 0; pl < BITS; ++pl)
+            if (m & (1 << pl)) w ^= pw[t][s >> 1][pl];
+          b[s][j++] = expand16(w, s & 1);
+        }
+        if (PROD) b[s][j] = expand16(zw[t][s >> 1], s & 1);
       }
-      kg[t] = PROD ? a.kappa * a.gamma[row[t]] : 0.f;
-      nu[t] = a.norm != nullptr ? a.norm[row[t]] : 1.f;
-    }
+    };
+    auto mfmas = [&](const v4i (&b)[PIPE ? KSM : 1][NTA], v4i (&c)[NTA]) {
+      if (!PIPE) return;
 #pragma unroll
-    for (int t = 0; t < TPP; ++t) {
-      v4i acc[NM > 0 ? NM : 1], accz = {0, 0, 0, 0};
-#pragma unroll
-      for (int m = 0; m < (NM > 0 ? NM : 1); ++m) acc[m] = v4i{0, 0, 0, 0};
+      for (int j = 0; j < NTA; ++j) c[j] = v4i{0, 0, 0, 0};
 #pragma unroll
       for (int s = 0; s < KSM; ++s) {  // unrolled so the A registers are indexed statically
         if (s >= ks) break;
 #pragma unroll
-        for (int m = 1; m <= NM; ++m) {
-          uint32_t w = 0xFFFFFFFFu;
-#pragma unroll
-          for (int pl = 0; pl < BITS; ++pl)
-            if (m & (1 << pl)) w &= pw[t][s][pl];
-          acc[m - 1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ar[s], expand16(w >> half_shift), acc[m - 1], 0, 0, 0);
-        }
-        if (PROD)
-          accz = __builtin_amdgcn_mfma_i32_16x16x64_i8(as_[s], expand16(zw[t][s] >> half_shift), accz, 0, 0, 0);
+        for (int j = 0; j < NT; ++j)
+          c[j] = __builtin_amdgcn_mfma_i32_16x16x64_i8((PROD && j == NT - 1) ? as_[s] : ar[s], b[s][j], c[j], 0, 0, 0);
       }
-      float total = a.coef[0] * r_sum;
+    };
+    auto finish = [&](int t, const v4i (&c)[NTA]) {
+      float total = base_r;
+      int j = 0;
 #pragma unroll
-      for (int m = 1; m <= NM; ++m) total = fmaf(a.coef[m], masked_sum(acc[m - 1]) * r_inv, total);
-      if (PROD) total = fmaf(kg[t], 2.f * masked_sum(accz) * s_inv - s_sum, total);
+      for (int m = 1; m <= NM; ++m)
+        if (i8_term(m)) total = fmaf(cr[m - 1], digits_sum(c[j++]), total);
+      if (PROD) total = fmaf(a.kappa * kg[t], fmaf(zs, digits_sum(c[NT - 1]), -s_sum), total);
       total *= nu[t];
-      if (valid[t] && out_live)
-        a.scores[((int64_t)group * a.q_per_group + q0 + kq) * a.lds + pass0 + t * 16 + col] = total;
+      if (out_live && (FULL || wave_key0 + t * 16 + col < a.n)) out0[t * 16] = total;
+    };
+    if (PIPE) {
+      lookups(0, bop[0]);
+#pragma unroll
+      for (int t = 0; t < TILES; ++t) {
+        if (!FULL && wave_key0 + t * 16 >= a.n) {  // uniform over the wavefront
+          if (t > 0) finish(t - 1, acc[(t - 1) & 1]);
+          return;
+        }
+        if (t + 1 < TILES) lookups(t + 1, bop[(t + 1) & 1]);
+        mfmas(bop[t & 1], acc[t & 1]);
+        if (t > 0) finish(t - 1, acc[(t - 1) & 1]);
+      }
+      finish(TILES - 1, acc[(TILES - 1) & 1]);
+    } else {
+      // too many operand registers for two tiles in flight: one k-step of one tile at a time
+#pragma unroll
+      for (int t = 0; t < TILES; ++t) {
+        if (!FULL && wave_key0 + t * 16 >= a.n) return;
+#pragma unroll
+        for (int j = 0; j < NTA; ++j) acc[0][j] = v4i{0, 0, 0, 0};
+#pragma unroll
+        for (int s = 0; s < KSM; ++s) {
+          if (s >= ks) break;
+          int j = 0;
+#pragma unroll
+          for (int m = 1; m <= NM; ++m) {
+            if (!i8_term(m)) continue;
+            uint32_t w = 0u;
+#pragma unroll
+            for (int pl = 0; pl < BITS; ++pl)
+              if (m & (1 << pl)) w ^= pw[t][s >> 1][pl];
+            acc[0][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ar[s], expand16(w, s & 1), acc[0][j], 0, 0, 0);
+            ++j;
+          }
+          if (PROD)
+            acc[0][NT - 1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(as_[s], expand16(zw[t][s >> 1], s & 1), acc[0][NT - 1], 0, 0, 0);
+        }
+        finish(t, acc[0]);
+      }
     }
-  }
+  };
+  if (full) run_tiles(std::true_type{});
+  else run_tiles(std::false_type{});
 }
 
-template <int BITS, bool PROD>
-static hipError_t launch_ks(const ScoreI8Args& a, dim3 grid, hipStream_t s) {
-  const int ks = a.d >> 6;
-  if (ks <= 2)
-    hipLaunchKernelGGL((score_i8_kernel<BITS, PROD, 2>), grid, dim3(256), 0, s, a);
-  else if (ks <= 4)
-    hipLaunchKernelGGL((score_i8_kernel<BITS, PROD, 4>), grid, dim3(256), 0, s, a);
-  else
-    hipLaunchKernelGGL((score_i8_kernel<BITS, PROD, 8>), grid, dim3(256), 0, s, a);
+constexpr int I8_FUSED_EXTRA = 2 * 2 * 4 * 128 * 4 + 2 * 4 * 4 * 128 + 2 * 4 * 2 * 4;  // partial sums, digits, scalars
+
+template <int BITS, bool PROD, int KSM, bool FUSED>
+static hipError_t launch_one(const ScoreI8Args& a, int n_groups, hipStream_t s) {
+  const int64_t per_wg = 8 * 16 * i8_tiles(BITS, KSM);
+  const dim3 grid((unsigned)((a.n + per_wg - 1) / per_wg), n_groups, (a.q_per_group + 3) / 4);
+  constexpr int lds = FUSED ? I8_FUSED_EXTRA : 0;  // on top of the 64 KB table
+  hipLaunchKernelGGL((score_i8_kernel<BITS, PROD, KSM, FUSED>), grid, dim3(512), lds, s, a);
   return hipGetLastError();
 }
 
+template <int BITS, bool PROD>
+static hipError_t launch_ks(const ScoreI8Args& a, int n_groups, bool fused, hipStream_t s) {
+  const int ks = a.d >> 6;
+  if (fused) return launch_one<BITS, PROD, 2, true>(a, n_groups, s);
+  if (ks <= 2) return launch_one<BITS, PROD, 2, false>(a, n_groups, s);
+  if (ks <= 4) return launch_one<BITS, PROD, 4, false>(a, n_groups, s);
+  return launch_one<BITS, PROD, 8, false>(a, n_groups, s);
+}
+
 template <int BITS>
-static hipError_t launch_bits(const ScoreI8Args& a, bool prod, dim3 grid, hipStream_t s) {
-  return prod ? launch_ks<BITS, true>(a, grid, s) : launch_ks<BITS, false>(a, grid, s);
+static hipError_t launch_bits(const ScoreI8Args& a, bool prod, int n_groups, bool fused, hipStream_t s) {
+  return prod ? launch_ks<BITS, true>(a, n_groups, fused, s) : launch_ks<BITS, false>(a, n_groups, fused, s);
 }
 
 size_t score_i8_workspace_bytes(int d, int64_t nq) {
   return (size_t)nq * 2 * ((size_t)(d >> 6) * 256 + 16) + 512;
 }
 
-hipError_t launch_score_i8(int bits, bool prod, const float* Pi, const float* S, const float* q, int64_t ldq,
+// Walsh coefficients of the centroid table over the bit planes of the index:
+//   c[v] = sum_S w_S chi_S(v),  chi_S(v) = prod_{p in S} (2 v_p - 1) = sgn_S * (2 x_S(v) - 1),
+// x_S(v) = XOR of the bits of v in S, sgn_S = +1 for odd |S| and -1 for even |S|.  Summed in
+// pairs (v, K-1-v): for even |S| chi_S agrees on the pair, so a table with c[K-1-v] = -c[v]
+// gives exactly zero there.
+static void walsh(int bits, const Codebook& cb, double* w) {
+  const int K = 1 << bits;
+  for (int sset = 0; sset < K; ++sset) {
+    double acc = 0.0;
+    const int size = __builtin_popcount(sset);
+    for (int v = 0; v < (K > 1 ? K / 2 : 1); ++v) {
+      const int par = __builtin_popcount(v & sset) & 1;
+      const double chi = ((size - par) & 1) ? -1.0 : 1.0;  // (-1)^(number of zero bits of v in S)
+      if (K == 1) acc += cb.c[0];
+      else if (size & 1) acc += chi * ((double)cb.c[v] - (double)cb.c[K - 1 - v]);
+      else acc += chi * ((double)cb.c[v] + (double)cb.c[K - 1 - v]);
+    }
+    w[sset] = acc / K;
+  }
+}
+
+bool score_i8_applicable(int bits, int d, const Codebook& cb) {
+  if (bits < 0 || bits > 4 || d % 128 != 0 || d > 64 * I8_MAX_KS) return false;
+  double w[16];
+  walsh(bits, cb, w);
+  for (int sset = 1; sset < (1 << bits); ++sset)
+    if (!i8_term(sset) && w[sset] != 0.0) return false;  // not symmetric about zero
+  return true;
+}
+
+hipError_t launch_score_i8(int bits, bool prod, const float* Pi, const float* S, const float* PiT, const float* ST,
+                           const float* q, int64_t ldq,
                            void* workspace, const uint32_t* idx, const uint32_t* qjl, const float* gamma,
                            const float* norm, float* scores, int64_t lds, int64_t n, int d, int n_groups,
                            int q_per_group, float kappa, const Codebook& cb, hipStream_t stream) {
   if (n_groups == 0 || q_per_group == 0) return hipSuccess;
-  if (bits < 0 || bits > 3 || d % 64 != 0 || d > 64 * I8_MAX_KS) return hipErrorInvalidValue;
+  if (bits < 0 || bits > 4 || d % 128 != 0 || d > 64 * I8_MAX_KS) return hipErrorInvalidValue;
   const int64_t nq = (int64_t)n_groups * q_per_group;
   uint4* img = static_cast<uint4*>(workspace);
   float* scal = reinterpret_cast<float*>(static_cast<char*>(workspace) + (size_t)nq * 2 * (d >> 6) * 256);
-  hipLaunchKernelGGL(prep_i8_kernel, dim3((unsigned)nq, prod ? 2 : 1), dim3(128), (size_t)2 * d * sizeof(float),
-                     stream, d, Pi, S, q, ldq, img, scal);
+  // d = 128 with the transposed matrices at hand: the scoring kernel prepares the queries itself
+  const bool fused = d == 128 && (bits == 0 || PiT != nullptr) && (!prod || ST != nullptr);
+  if (n == 0) return hipSuccess;
+  if (!fused) {
+    const dim3 pgrid((unsigned)nq, prod ? 2 : 1);
+    switch (d >> 7) {
+      case 1: hipLaunchKernelGGL(prep_i8_kernel<1>, pgrid, dim3(512), 0, stream, d, Pi, S, q, ldq, img, scal); break;
+      case 2: hipLaunchKernelGGL(prep_i8_kernel<2>, pgrid, dim3(512), 0, stream, d, Pi, S, q, ldq, img, scal); break;
+      case 3: hipLaunchKernelGGL(prep_i8_kernel<3>, pgrid, dim3(512), 0, stream, d, Pi, S, q, ldq, img, scal); break;
+      default: hipLaunchKernelGGL(prep_i8_kernel<4>, pgrid, dim3(512), 0, stream, d, Pi, S, q, ldq, img, scal); break;
+    }
+  }
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess || n == 0) return e;
+  if (e != hipSuccess) return e;
   ScoreI8Args a;
-  a.img = img; a.scal = scal; a.idx = idx; a.qjl = qjl; a.gamma = gamma; a.norm = norm;
+  a.img = img; a.scal = scal; a.PiT = PiT; a.ST = ST; a.x = q; a.ldx = ldq; a.idx = idx; a.qjl = qjl; a.gamma = gamma; a.norm = norm;
   a.scores = scores; a.lds = lds; a.n = n; a.d = d; a.q_per_group = q_per_group; a.kappa = kappa;
-  // Moebius transform of the centroid table over the bit planes of the index
-  double f[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  double w[16];
+  walsh(bits, cb, w);
+  // sum_j q_j c[idx_j] = (w_0 - sum_S sgn_S w_S) * sum_j q_j + sum_S 2 sgn_S w_S M_S
   const int K = 1 << bits;
-  for (int v = 0; v < K; ++v) f[v] = cb.c[v];
-  for (int pl = 0; pl < bits; ++pl)
-    for (int v = 0; v < K; ++v)
-      if (v & (1 << pl)) f[v] -= f[v ^ (1 << pl)];
-  for (int v = 0; v < 8; ++v) a.coef[v] = (float)f[v];
-  // enough workgroups for every CU when the problem allows it, at least 64 keys per wavefront pass
-  int64_t per_wg = 1024;  // a multiple of 256 = 4 wavefronts x 4 tiles x 16 keys
-  while (per_wg > 256 && (n + per_wg - 1) / per_wg * n_groups < 1024) per_wg >>= 1;
-  a.keys_per_wg = (int)per_wg;
-  const dim3 grid((unsigned)((n + per_wg - 1) / per_wg), n_groups, (q_per_group + 3) / 4);
+  double c0 = w[0];
+  for (int v = 0; v < 16; ++v) a.coef[v] = 0.f;
+  for (int sset = 1; sset < K; ++sset) {
+    const double sgn = (__builtin_popcount(sset) & 1) ? 1.0 : -1.0;
+    if (!i8_term(sset) && w[sset] != 0.0) return hipErrorInvalidValue;  // see score_i8_applicable
+    c0 -= sgn * w[sset];
+    a.coef[sset] = (float)(2.0 * sgn * w[sset]);
+  }
+  a.coef[0] = (float)c0;
   switch (bits) {
-    case 0: return launch_bits<0>(a, prod, grid, stream);
-    case 1: return launch_bits<1>(a, prod, grid, stream);
-    case 2: return launch_bits<2>(a, prod, grid, stream);
-    case 3: return launch_bits<3>(a, prod, grid, stream);
+    case 0: return launch_bits<0>(a, prod, n_groups, fused, stream);
+    case 1: return launch_bits<1>(a, prod, n_groups, fused, stream);
+    case 2: return launch_bits<2>(a, prod, n_groups, fused, stream);
+    case 3: return launch_bits<3>(a, prod, n_groups, fused, stream);
+    case 4: return launch_bits<4>(a, prod, n_groups, fused, stream);
     default: return hipErrorInvalidValue;
   }
 }
