@@ -1,0 +1,50 @@
+// Shared by the two few-query scoring kernels on the integer matrix cores
+// (tq_score_i8.hip: any d that is a multiple of 128 up to 512, queries prepared by a
+// kernel of their own; tq_score_i8_128.hip: d = 128 with everything in one kernel).
+#pragma once
+#include "tq_internal.h"
+
+namespace tq {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// coordinate block of (k-step s, k-chunk kq): 16 coordinates starting here
+__host__ __device__ constexpr int i8_coord0(int s, int kq) { return 32 * (kq + 4 * (s >> 1)) + 16 * (s & 1); }
+
+// Image of one query's A operand, written by prep_i8_kernel: for matrix m (0: Pi q, 1: S q),
+// k-step s, digit row dg, k-chunk kq the 16 bytes of coordinates i8_coord0(s, kq) .. + 15.
+//   bytes:   img[((q * 2 + m) * ks + s) * 16 + dg * 4 + kq]      (16-byte units)
+//   scalars: scal[(q * 2 + m) * 2 + {0: 1/scale, 1: sum of the rounded coordinates}]
+struct ScoreI8Args {
+  const uint4* img;
+  const float* scal;
+  const float* PiT;  // fused variant only: transposed matrices and the raw queries
+  const float* ST;
+  const float* x;
+  int64_t ldx;
+  const uint32_t* idx;
+  const uint32_t* qjl;
+  const float* gamma;
+  const float* norm;
+  float* scores;
+  int64_t lds;
+  int64_t n;
+  int64_t total_rows;  // rows in the code arrays (all groups)
+  int d;
+  int q_per_group;
+  float kappa;
+  float coef[16];  // coef[0]: factor of sum_j qr_j; coef[S]: factor of M_S (odd |S| only)
+};
+
+constexpr int I8_MAX_KS = 8;  // d <= 512
+// the terms the kernel evaluates: plane subsets of odd size (symmetric codebook)
+__host__ __device__ constexpr bool i8_term(int m) { return __builtin_popcount((unsigned)m) & 1; }
+// tiles of 16 keys per wavefront: as many as the register file holds code words for
+__host__ __device__ constexpr int i8_tiles(int bits, int ksm) { return (bits >= 4 ? 16 : 32) / ksm; }
+constexpr int I8_COPIES = 32;
+constexpr int I8_TABLE_BYTES = 256 * I8_COPIES * 8;
+
+
+hipError_t launch_score_i8_128(int bits, bool prod, const ScoreI8Args& a, int n_groups, hipStream_t stream);
+
+}  // namespace tq

@@ -45,17 +45,14 @@
 // therefore replicated 32 times, copy c = lane % 32 living in banks 2c, 2c+1
 // (entry e of copy c at dword 64 e + 2 c): every lookup is conflict free.  The
 // 64 KB table is filled while the code words are in flight.
-#include "tq_internal.h"
+#include "tq_score_i8.h"
 
 #include <type_traits>
 
 namespace tq {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// coordinate block of (k-step s, k-chunk kq): 16 coordinates starting here
-__host__ __device__ constexpr int i8_coord0(int s, int kq) { return 32 * (kq + 4 * (s >> 1)) + 16 * (s & 1); }
 
 // ---------------------------------------------------------------------------
 // Query preparation for the int8 path: rotate / sketch one query per workgroup
@@ -153,50 +150,11 @@ __global__ __launch_bounds__(512) void prep_i8_kernel(const int d, const float* 
   }
 }
 
-// Image of one query's A operand, written by prep_i8_kernel: for matrix m (0: Pi q, 1: S q),
-// k-step s, digit row dg, k-chunk kq the 16 bytes of coordinates i8_coord0(s, kq) .. + 15.
-//   bytes:   img[((q * 2 + m) * ks + s) * 16 + dg * 4 + kq]      (16-byte units)
-//   scalars: scal[(q * 2 + m) * 2 + {0: 1/scale, 1: sum of the rounded coordinates}]
-struct ScoreI8Args {
-  const uint4* img;
-  const float* scal;
-  const float* PiT;  // fused variant only: transposed matrices and the raw queries
-  const float* ST;
-  const float* x;
-  int64_t ldx;
-  const uint32_t* idx;
-  const uint32_t* qjl;
-  const float* gamma;
-  const float* norm;
-  float* scores;
-  int64_t lds;
-  int64_t n;
-  int d;
-  int q_per_group;
-  float kappa;
-  float coef[16];  // coef[0]: factor of sum_j qr_j; coef[S]: factor of M_S (odd |S| only)
-};
-
-constexpr int I8_MAX_KS = 8;  // d <= 512
-// the terms the kernel evaluates: plane subsets of odd size (symmetric codebook)
-__host__ __device__ constexpr bool i8_term(int m) { return __builtin_popcount((unsigned)m) & 1; }
-// tiles of 16 keys per wavefront: as many as the register file holds code words for
-__host__ __device__ constexpr int i8_tiles(int bits, int ksm) { return (bits >= 4 ? 16 : 32) / ksm; }
-constexpr int I8_COPIES = 32;
-constexpr int I8_TABLE_BYTES = 256 * I8_COPIES * 8;
-
 // KSM: compile-time bound on the number of 64-coordinate k-steps (register arrays).
 // A wavefront owns i8_tiles() tiles of 16 keys and requests all their code words up front.
-//
-// FUSED (d = 128 only): the workgroup prepares its own four queries while its code words are
-// in flight, instead of reading images written by prep_i8_kernel.  Wavefront w accumulates
-// y_j = sum_k W^T[k][j] x_k for matrix w/4, half (w/2)%2 of k and columns j = tid % 128, the
-// query coordinates coming through scalar registers; wavefront w then digitises (matrix w/4,
-// query w%4).  The 128 KB of matrix reads per workgroup hit in L2.
-template <int BITS, bool PROD, int KSM, bool FUSED>
+template <int BITS, bool PROD, int KSM>
 __global__ __launch_bounds__(512) void score_i8_kernel(const ScoreI8Args a) {
   __shared__ __attribute__((aligned(16))) uint2 expand_s[256 * I8_COPIES];  // [256][32]: byte -> one byte per bit
-  extern __shared__ __attribute__((aligned(16))) unsigned char fused_s[];   // fused variant: partial sums, digits, scalars
   constexpr int GI = KSM / 2;      // plane-word groups per lane
   constexpr int TILES = i8_tiles(BITS, KSM);  // tiles per wavefront
   constexpr int NM = (1 << BITS) - 1;
@@ -208,7 +166,7 @@ __global__ __launch_bounds__(512) void score_i8_kernel(const ScoreI8Args a) {
   const int kq = lane >> 4;    // k-chunk; also the query whose sums this lane receives
   const int group = blockIdx.y;
   const int q0 = blockIdx.z * 4;
-  const int d = FUSED ? 128 : a.d;
+  const int d = a.d;
   const int ks = d >> 6;  // k-steps of 64 coordinates (even)
   const int gi = ks >> 1;
 
@@ -222,35 +180,25 @@ __global__ __launch_bounds__(512) void score_i8_kernel(const ScoreI8Args a) {
   v4i ar[KSM], as_[KSM];
   float r_inv = 0.f, r_sum = 0.f, s_inv = 0.f, s_sum = 0.f;
 
-  // ---- 1. what the query side needs from memory is requested first (loads return in order) --
-  // not fused: digit images and scalars written by prep_i8_kernel
-  // fused:     this thread's column of the transposed matrix, 64 values of k
-  float wv[FUSED ? 64 : 1];
-  const int p_mat = wave >> 2, p_kh = (wave >> 1) & 1, p_j = tid & 127;
-  const bool p_work = p_mat == 0 ? BITS > 0 : PROD;  // uniform
-  if (!FUSED) {
+  // ---- 1. A operands first (loads return in order): digit images and scalars written by
+  // prep_i8_kernel ------------------------------------------------------------------------
 #pragma unroll
-    for (int s = 0; s < KSM; ++s) {
-      uint4 r = make_uint4(0, 0, 0, 0), z = make_uint4(0, 0, 0, 0);
-      if (s < ks) {
-        if (BITS > 0) r = a.img[((qrow * 2 + 0) * ks + s) * 16 + a_digit * 4 + kq];
-        if (PROD) z = a.img[((qrow * 2 + 1) * ks + s) * 16 + a_digit * 4 + kq];
-      }
-      ar[s] = v4i{(int)r.x, (int)r.y, (int)r.z, (int)r.w};
-      as_[s] = v4i{(int)z.x, (int)z.y, (int)z.z, (int)z.w};
+  for (int s = 0; s < KSM; ++s) {
+    uint4 r = make_uint4(0, 0, 0, 0), z = make_uint4(0, 0, 0, 0);
+    if (s < ks) {
+      if (BITS > 0) r = a.img[((qrow * 2 + 0) * ks + s) * 16 + a_digit * 4 + kq];
+      if (PROD) z = a.img[((qrow * 2 + 1) * ks + s) * 16 + a_digit * 4 + kq];
     }
-    if (BITS > 0) {
-      r_inv = a.scal[(orow * 2 + 0) * 2];
-      r_sum = a.scal[(orow * 2 + 0) * 2 + 1];
-    }
-    if (PROD) {
-      s_inv = a.scal[(orow * 2 + 1) * 2];
-      s_sum = a.scal[(orow * 2 + 1) * 2 + 1];
-    }
-  } else if (p_work) {
-    const float* WT = (p_mat ? a.ST : a.PiT) + (64 * p_kh) * 128 + p_j;
-#pragma unroll
-    for (int k = 0; k < 64; ++k) wv[k] = WT[k * 128];
+    ar[s] = v4i{(int)r.x, (int)r.y, (int)r.z, (int)r.w};
+    as_[s] = v4i{(int)z.x, (int)z.y, (int)z.z, (int)z.w};
+  }
+  if (BITS > 0) {
+    r_inv = a.scal[(orow * 2 + 0) * 2];
+    r_sum = a.scal[(orow * 2 + 0) * 2 + 1];
+  }
+  if (PROD) {
+    s_inv = a.scal[(orow * 2 + 1) * 2];
+    s_sum = a.scal[(orow * 2 + 1) * 2 + 1];
   }
 
   // ---- 2. every code word of this wavefront's keys goes in flight: the first tile can start
@@ -294,67 +242,6 @@ __global__ __launch_bounds__(512) void score_i8_kernel(const ScoreI8Args a) {
   if (full) load_codes(std::false_type{});
   else load_codes(std::true_type{});
 
-  // ---- 2b. (fused) rotate / sketch and digitise this workgroup's four queries ------------
-  float* const part_s = reinterpret_cast<float*>(fused_s);  // [2][2][4][128]
-  signed char* const dig_s = reinterpret_cast<signed char*>(part_s + 2 * 2 * 4 * 128);                // [2][4][4][128]
-  float* const scal_s = reinterpret_cast<float*>(dig_s + 2 * 4 * 4 * 128);                             // [2][4][2]
-  if (FUSED) {
-    if (p_work) {
-      const float* xq[4];  // uniform addresses: the query coordinates arrive in scalar registers
-#pragma unroll
-      for (int qi = 0; qi < 4; ++qi) {
-        const int64_t r = (int64_t)group * a.q_per_group + (q0 + qi < a.q_per_group ? q0 + qi : q0);
-        xq[qi] = a.x + r * a.ldx + 64 * p_kh;
-      }
-      float acc[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int k = 0; k < 64; ++k)
-#pragma unroll
-        for (int qi = 0; qi < 4; ++qi) acc[qi] = fmaf(wv[k], xq[qi][k], acc[qi]);
-#pragma unroll
-      for (int qi = 0; qi < 4; ++qi) part_s[((p_mat * 2 + p_kh) * 4 + qi) * 128 + p_j] = acc[qi];
-    }
-    __syncthreads();
-    const int mat = wave >> 2, qi = wave & 3;
-    if (mat == 0 ? BITS > 0 : PROD) {
-      const bool live = q0 + qi < a.q_per_group;
-      float y[2];
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const int j = lane + 64 * u;
-        y[u] = live ? part_s[((mat * 2 + 0) * 4 + qi) * 128 + j] + part_s[((mat * 2 + 1) * 4 + qi) * 128 + j] : 0.f;
-      }
-      float mx = fmaxf(fabsf(y[0]), fabsf(y[1]));
-#pragma unroll
-      for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
-      int e = 0;
-      if (mx > 0.f) (void)frexpf(mx, &e);  // mx = f * 2^e, f in [0.5, 1): |Q| <= 2^19
-      const float sc = ldexpf(1.f, 19 - e);
-      int Q[2], tot;
-      Q[0] = __float2int_rn(y[0] * sc);
-      Q[1] = __float2int_rn(y[1] * sc);
-      tot = Q[0] + Q[1];
-#pragma unroll
-      for (int off = 32; off >= 1; off >>= 1) tot += __shfl_xor(tot, off);
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const int d0 = ((Q[u] + 64) & 127) - 64;
-        const int Q1 = (Q[u] - d0) >> 7;
-        const int d1 = ((Q1 + 64) & 127) - 64;
-        const int d2 = (Q1 - d1) >> 7;
-        signed char* o = dig_s + (mat * 4 + qi) * 4 * 128 + lane + 64 * u;
-        o[0] = (signed char)d0;
-        o[128] = (signed char)d1;
-        o[256] = (signed char)d2;
-        o[384] = 0;
-      }
-      if (lane == 0) {
-        scal_s[(mat * 4 + qi) * 2 + 0] = ldexpf(1.f, e - 19);
-        scal_s[(mat * 4 + qi) * 2 + 1] = (float)tot * ldexpf(1.f, e - 19);
-      }
-    }
-  }
-
   // ---- 3. the expansion table, 32 bank-private copies ------------------------------------
   // thread -> (entry tid/32 + 16 i, copy tid%32): consecutive threads write consecutive
   // addresses; the low nibble of the entry is the thread's own, the high nibble is i
@@ -367,27 +254,6 @@ __global__ __launch_bounds__(512) void score_i8_kernel(const ScoreI8Args a) {
     }
   }
   __syncthreads();
-
-  if (FUSED) {
-#pragma unroll
-    for (int s = 0; s < KSM; ++s) {
-      ar[s] = v4i{0, 0, 0, 0};
-      as_[s] = v4i{0, 0, 0, 0};
-      if (s < 2) {
-        const int c0 = i8_coord0(s, kq);
-        if (BITS > 0) ar[s] = *reinterpret_cast<const v4i*>(dig_s + ((0 * 4 + a_query) * 4 + a_digit) * 128 + c0);
-        if (PROD) as_[s] = *reinterpret_cast<const v4i*>(dig_s + ((1 * 4 + a_query) * 4 + a_digit) * 128 + c0);
-      }
-    }
-    if (BITS > 0) {
-      r_inv = scal_s[(0 * 4 + kq) * 2];
-      r_sum = scal_s[(0 * 4 + kq) * 2 + 1];
-    }
-    if (PROD) {
-      s_inv = scal_s[(1 * 4 + kq) * 2];
-      s_sum = scal_s[(1 * 4 + kq) * 2 + 1];
-    }
-  }
 
   const uint32_t copy_off = (uint32_t)(lane & (I8_COPIES - 1)) * 8u;
   const char* const table = reinterpret_cast<const char*>(expand_s);
@@ -509,29 +375,25 @@ __global__ __launch_bounds__(512) void score_i8_kernel(const ScoreI8Args a) {
   else run_tiles(std::false_type{});
 }
 
-constexpr int I8_FUSED_EXTRA = 2 * 2 * 4 * 128 * 4 + 2 * 4 * 4 * 128 + 2 * 4 * 2 * 4;  // partial sums, digits, scalars
-
-template <int BITS, bool PROD, int KSM, bool FUSED>
+template <int BITS, bool PROD, int KSM>
 static hipError_t launch_one(const ScoreI8Args& a, int n_groups, hipStream_t s) {
   const int64_t per_wg = 8 * 16 * i8_tiles(BITS, KSM);
   const dim3 grid((unsigned)((a.n + per_wg - 1) / per_wg), n_groups, (a.q_per_group + 3) / 4);
-  constexpr int lds = FUSED ? I8_FUSED_EXTRA : 0;  // on top of the 64 KB table
-  hipLaunchKernelGGL((score_i8_kernel<BITS, PROD, KSM, FUSED>), grid, dim3(512), lds, s, a);
+  hipLaunchKernelGGL((score_i8_kernel<BITS, PROD, KSM>), grid, dim3(512), 0, s, a);
   return hipGetLastError();
 }
 
 template <int BITS, bool PROD>
-static hipError_t launch_ks(const ScoreI8Args& a, int n_groups, bool fused, hipStream_t s) {
+static hipError_t launch_ks(const ScoreI8Args& a, int n_groups, hipStream_t s) {
   const int ks = a.d >> 6;
-  if (fused) return launch_one<BITS, PROD, 2, true>(a, n_groups, s);
-  if (ks <= 2) return launch_one<BITS, PROD, 2, false>(a, n_groups, s);
-  if (ks <= 4) return launch_one<BITS, PROD, 4, false>(a, n_groups, s);
-  return launch_one<BITS, PROD, 8, false>(a, n_groups, s);
+  if (ks <= 2) return launch_one<BITS, PROD, 2>(a, n_groups, s);
+  if (ks <= 4) return launch_one<BITS, PROD, 4>(a, n_groups, s);
+  return launch_one<BITS, PROD, 8>(a, n_groups, s);
 }
 
 template <int BITS>
-static hipError_t launch_bits(const ScoreI8Args& a, bool prod, int n_groups, bool fused, hipStream_t s) {
-  return prod ? launch_ks<BITS, true>(a, n_groups, fused, s) : launch_ks<BITS, false>(a, n_groups, fused, s);
+static hipError_t launch_bits(const ScoreI8Args& a, bool prod, int n_groups, hipStream_t s) {
+  return prod ? launch_ks<BITS, true>(a, n_groups, s) : launch_ks<BITS, false>(a, n_groups, s);
 }
 
 size_t score_i8_workspace_bytes(int d, int64_t nq) {
@@ -578,23 +440,10 @@ hipError_t launch_score_i8(int bits, bool prod, const float* Pi, const float* S,
   const int64_t nq = (int64_t)n_groups * q_per_group;
   uint4* img = static_cast<uint4*>(workspace);
   float* scal = reinterpret_cast<float*>(static_cast<char*>(workspace) + (size_t)nq * 2 * (d >> 6) * 256);
-  // d = 128 with the transposed matrices at hand: the scoring kernel prepares the queries itself
-  const bool fused = d == 128 && (bits == 0 || PiT != nullptr) && (!prod || ST != nullptr);
   if (n == 0) return hipSuccess;
-  if (!fused) {
-    const dim3 pgrid((unsigned)nq, prod ? 2 : 1);
-    switch (d >> 7) {
-      case 1: hipLaunchKernelGGL(prep_i8_kernel<1>, pgrid, dim3(512), 0, stream, d, Pi, S, q, ldq, img, scal); break;
-      case 2: hipLaunchKernelGGL(prep_i8_kernel<2>, pgrid, dim3(512), 0, stream, d, Pi, S, q, ldq, img, scal); break;
-      case 3: hipLaunchKernelGGL(prep_i8_kernel<3>, pgrid, dim3(512), 0, stream, d, Pi, S, q, ldq, img, scal); break;
-      default: hipLaunchKernelGGL(prep_i8_kernel<4>, pgrid, dim3(512), 0, stream, d, Pi, S, q, ldq, img, scal); break;
-    }
-  }
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
   ScoreI8Args a;
   a.img = img; a.scal = scal; a.PiT = PiT; a.ST = ST; a.x = q; a.ldx = ldq; a.idx = idx; a.qjl = qjl; a.gamma = gamma; a.norm = norm;
-  a.scores = scores; a.lds = lds; a.n = n; a.d = d; a.q_per_group = q_per_group; a.kappa = kappa;
+  a.scores = scores; a.lds = lds; a.n = n; a.total_rows = (int64_t)n_groups * n; a.d = d; a.q_per_group = q_per_group; a.kappa = kappa;
   double w[16];
   walsh(bits, cb, w);
   // sum_j q_j c[idx_j] = (w_0 - sum_S sgn_S w_S) * sum_j q_j + sum_S 2 sgn_S w_S M_S
@@ -608,12 +457,26 @@ hipError_t launch_score_i8(int bits, bool prod, const float* Pi, const float* S,
     a.coef[sset] = (float)(2.0 * sgn * w[sset]);
   }
   a.coef[0] = (float)c0;
+  // d = 128 with the transposed matrices at hand and 16-byte aligned codes: one kernel does it all
+  const auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
+  if (d == 128 && (bits > 0 || prod) && (bits == 0 || (PiT != nullptr && al16(idx))) &&
+      (!prod || (ST != nullptr && al16(qjl))))
+    return launch_score_i8_128(bits, prod, a, n_groups, stream);
+  const dim3 pgrid((unsigned)nq, prod ? 2 : 1);
+  switch (d >> 7) {
+    case 1: hipLaunchKernelGGL(prep_i8_kernel<1>, pgrid, dim3(512), 0, stream, d, Pi, S, q, ldq, img, scal); break;
+    case 2: hipLaunchKernelGGL(prep_i8_kernel<2>, pgrid, dim3(512), 0, stream, d, Pi, S, q, ldq, img, scal); break;
+    case 3: hipLaunchKernelGGL(prep_i8_kernel<3>, pgrid, dim3(512), 0, stream, d, Pi, S, q, ldq, img, scal); break;
+    default: hipLaunchKernelGGL(prep_i8_kernel<4>, pgrid, dim3(512), 0, stream, d, Pi, S, q, ldq, img, scal); break;
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
   switch (bits) {
-    case 0: return launch_bits<0>(a, prod, n_groups, fused, stream);
-    case 1: return launch_bits<1>(a, prod, n_groups, fused, stream);
-    case 2: return launch_bits<2>(a, prod, n_groups, fused, stream);
-    case 3: return launch_bits<3>(a, prod, n_groups, fused, stream);
-    case 4: return launch_bits<4>(a, prod, n_groups, fused, stream);
+    case 0: return launch_bits<0>(a, prod, n_groups, stream);
+    case 1: return launch_bits<1>(a, prod, n_groups, stream);
+    case 2: return launch_bits<2>(a, prod, n_groups, stream);
+    case 3: return launch_bits<3>(a, prod, n_groups, stream);
+    case 4: return launch_bits<4>(a, prod, n_groups, stream);
     default: return hipErrorInvalidValue;
   }
 }
