@@ -4,18 +4,19 @@
 // v_mfma_i32_16x16x64_i8, Walsh terms of a symmetric codebook); what differs is
 // how the data gets to the matrix cores.
 //
-// Measured on the first version of this path: the time went neither into HBM
-// nor into the MFMAs but into issuing loads.  A lane that fetches its own
-// 8-byte share of 16 different code rows makes the memory pipeline touch every
-// cache line four times, and 64 such instructions per wavefront kept it busy for
-// several microseconds before the first MFMA could start.  So here
+// Measured with cycle stamps inside the kernel: what a workgroup waits for is
+// neither HBM as such nor the MFMAs but its own loads.  A compute unit takes in
+// only 10-14 bytes per clock (outstanding misses x line size / latency), and a
+// lane that fetches its own 8-byte share of 16 different code rows makes the
+// memory pipeline touch every cache line four times on top of that.  So here
 //   * a wavefront reads the codes of its keys as plain contiguous 16-byte-per-
 //     lane loads (1 KB per instruction) and parks them in a private LDS region;
 //     the tiles later pick their words out of LDS in operand order,
 //   * the workgroup prepares its own four queries while those loads are in
 //     flight (y = Pi q and S q from the transposed matrices, column per thread,
-//     query coordinates through scalar registers; then digits into LDS),
-//     instead of waiting for a separate kernel,
+//     query coordinates through scalar registers; then digits into LDS).  That
+//     re-reads 128 KB of matrices per workgroup, which is cheaper than the
+//     launch-and-latency chain of a preparation kernel in front,
 //   * the 64 KB expansion table is filled in the same window.
 //
 // Workgroup = 512 threads = 8 wavefronts; a wavefront owns 256 consecutive keys

@@ -1,0 +1,118 @@
+"""Turn rocprofv3 CSV output into the short summaries kept under profiles/.
+
+    python -m paper_2504_19874_amd.profile_summary stats  <dir with *_kernel_stats.csv>
+    python -m paper_2504_19874_amd.profile_summary traffic <FETCH_SIZE dir> <WRITE_SIZE dir> \
+           --workload C2 [--json profiles/traffic.json]
+
+`stats` prints a markdown table of the per-kernel durations (rocprofv3
+--kernel-trace --stats --output-format csv).  `traffic` reads the two
+--pmc runs (FETCH_SIZE in one, WRITE_SIZE in the other; both made with
+bench.py --calibration-copy so that a plain 256 MiB device copy is in the same
+trace), derives the scale factor of each counter from that copy, prints the
+per-kernel table and, with --json, records bytes per launch for the library's
+entry points in the file bench.py reads for `roofline.traffic`.
+"""
+from __future__ import annotations
+
+import argparse
+import collections
+import csv
+import glob
+import json
+import os
+import sys
+
+COPY_KIB = 256 * 1024  # what bench.py --calibration-copy reads and writes
+# kernel name prefix -> entry point whose dominant kernel it is
+ENTRY_OF = (("tq::quant128_kernel", "tq_quantize_prod"), ("tq::dequant128_kernel", "tq_dequantize"),
+            ("tq::score_i8_128_kernel", "tq_score"), ("tq::score_i8_kernel", "tq_score"),
+            ("tq::score_small_kernel", "tq_score"), ("tq::gemm_kernel<0, 2", "tq_quantize"),
+            ("tq::gemm_kernel<1, 2", "tq_quantize"), ("tq::gemm_kernel<2, 0", "tq_dequantize"),
+            ("tq::gemm_kernel<2, 1", "tq_score"))
+
+
+def find(dirname, suffix):
+    hits = sorted(glob.glob(os.path.join(dirname, "**", "*" + suffix), recursive=True))
+    if not hits:
+        sys.exit(f"no *{suffix} under {dirname}")
+    return hits[-1]
+
+
+def short(name, width=90):
+    name = name.replace("void ", "")
+    return name if len(name) <= width else name[:width - 3] + "..."
+
+
+def stats(dirname):
+    rows = list(csv.DictReader(open(find(dirname, "kernel_stats.csv"))))
+    print("| kernel | calls | avg ns | min ns | max ns | % |")
+    print("|---|---|---|---|---|---|")
+    for r in rows:
+        print(f"| `{short(r['Name'])}` | {r['Calls']} | {float(r['AverageNs']):.0f} | {r['MinNs']} | {r['MaxNs']} | "
+              f"{float(r['Percentage']):.2f} |")
+
+
+def per_kernel(dirname, counter):
+    acc = collections.defaultdict(list)
+    for r in csv.DictReader(open(find(dirname, "counter_collection.csv"))):
+        if r["Counter_Name"] == counter:
+            acc[r["Kernel_Name"]].append(float(r["Counter_Value"]))
+    return acc
+
+
+def traffic(fetch_dir, write_dir, workload, json_path):
+    fetch, write = per_kernel(fetch_dir, "FETCH_SIZE"), per_kernel(write_dir, "WRITE_SIZE")
+    copy = [k for k in fetch if "copyBuffer" in k or "direct_copy" in k or "CUDAFunctor" in k]
+    copy = max(copy, key=lambda k: max(fetch[k])) if copy else None
+    if copy is None or max(fetch[copy]) < COPY_KIB / 8:
+        sys.exit("no calibration copy in the trace (run bench.py with --calibration-copy)")
+    f_scale = COPY_KIB / max(fetch[copy])
+    w_scale = COPY_KIB / max(write[copy])
+    print(f"calibration copy `{short(copy, 60)}`: FETCH_SIZE {max(fetch[copy]):.1f} KiB -> scale {f_scale:.4f}, "
+          f"WRITE_SIZE {max(write[copy]):.1f} KiB -> scale {w_scale:.4f}\n")
+    print("| call | kernel | launches | FETCH_SIZE KiB | WRITE_SIZE KiB | HBM bytes (scaled) |")
+    print("|---|---|---|---|---|---|")
+    table = {}
+    for k in sorted(fetch):
+        if not k.startswith("void tq::") and not k.startswith("tq::"):
+            continue
+        name = k.replace("void ", "")
+        entry = next((e for p, e in ENTRY_OF if name.startswith(p)), "")
+        f, w = sum(fetch[k]) / len(fetch[k]), sum(write[k]) / len(write[k])
+        total = (f * f_scale + w * w_scale) * 1024
+        print(f"| {entry} | `{short(k, 70)}` | {len(fetch[k])} | {f:.1f} | {w:.1f} | {total / 1e6:.2f} MB |")
+        if entry and len(fetch[k]) > 2:
+            table[entry] = {"kernel": name.split("(")[0], "fetch_kib_raw": round(f, 1), "write_kib_raw": round(w, 1),
+                            "fetch_scale": round(f_scale, 4), "write_scale": round(w_scale, 4),
+                            "traffic_bytes": int(total), "launches_averaged": len(fetch[k])}
+    if json_path:
+        try:
+            with open(json_path) as fh:
+                doc = json.load(fh)
+        except (OSError, ValueError):
+            doc = {}
+        doc[workload] = table
+        with open(json_path, "w") as fh:
+            json.dump(doc, fh, indent=1)
+            fh.write("\n")
+
+
+def main():
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    sub = ap.add_subparsers(dest="cmd", required=True)
+    s = sub.add_parser("stats")
+    s.add_argument("dir")
+    t = sub.add_parser("traffic")
+    t.add_argument("fetch_dir")
+    t.add_argument("write_dir")
+    t.add_argument("--workload", required=True)
+    t.add_argument("--json", default="")
+    args = ap.parse_args()
+    if args.cmd == "stats":
+        stats(args.dir)
+    else:
+        traffic(args.fetch_dir, args.write_dir, args.workload, args.json)
+
+
+if __name__ == "__main__":
+    main()
