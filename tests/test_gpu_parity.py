@@ -257,6 +257,13 @@ def test_dequantize(d, bits_mse, n, prod, with_norm):
     # few queries per code: int8 path (bits <= 3, d <= 512) and the fp32 lane-per-key path (the rest)
     (384, 1, False, 2, 5, 130, 4), (512, 3, True, 1, 4, 2100, 0), (64, 2, True, 3, 2, 77, 0),
     (128, 4, True, 2, 4, 300, 0), (640, 2, True, 1, 3, 200, 0), (128, 2, True, 1, 32, 1100, 0),
+    # d = 128 single-kernel path: every bit width, one workgroup exactly (2048 keys), a ragged tail, several
+    # workgroups, query blocks that are not multiples of 4, a handful of keys
+    (128, 1, False, 3, 5, 2048, 0), (128, 3, False, 1, 4, 4100, 0), (128, 4, False, 2, 2, 2049, 3),
+    (128, 0, True, 2, 4, 2300, 0), (128, 1, True, 1, 1, 5, 0), (128, 3, True, 1, 9, 6000, 0),
+    # d = 256..512: preparation kernel + int8 scoring kernel
+    (256, 2, True, 2, 4, 1500, 0), (256, 4, True, 1, 3, 600, 0), (512, 1, False, 1, 8, 700, 0),
+    (384, 3, True, 1, 2, 300, 0), (512, 4, False, 1, 4, 1100, 5),
 ])
 def test_score_and_topk(d, bits_mse, prod, n_groups, qpg, npg, topk):
     p, Pi, S, c32, t32 = setup(d, bits_mse, prod)
@@ -292,6 +299,31 @@ def test_score_and_topk(d, bits_mse, prod, n_groups, qpg, npg, topk):
         tq.tq_score(p, dev(q), n_groups, qpg, idx_w, qjl_w, dev(gamma) if prod else None, dev(norm), npg, None,
                     topk, ti2, None)
         assert torch.equal(ti, ti2)
+
+
+@pytest.mark.parametrize("d,bits_mse,prod", [(128, 2, True), (256, 3, False)])
+def test_score_with_a_codebook_that_is_not_symmetric(d, bits_mse, prod):
+    """The few-query int8 kernels assume c[K-1-v] = -c[v]; any other table must be routed to a
+    kernel that does not, and still match the oracle."""
+    _, Pi, S, c_sym, _ = setup(d, bits_mse, prod)
+    c32 = (c_sym.astype(np.float64) + 0.003 * np.arange(c_sym.size) / math.sqrt(d)).astype(np.float32)
+    t32 = ((c32[:-1].astype(np.float64) + c32[1:].astype(np.float64)) / 2).astype(np.float32)
+    p = tq.Params(d, bits_mse, torch.from_numpy(Pi), None if S is None else torch.from_numpy(S), c32, t32)
+    n, nq = 700, 4
+    rng = np.random.default_rng(11)
+    idx = rng.integers(0, 1 << bits_mse, size=(n, d)).astype(np.int32)
+    z = rng.integers(0, 2, size=(n, d)).astype(bool)
+    gamma = rng.uniform(0.05, 0.6, size=n).astype(np.float32)
+    norm = np.exp(rng.normal(0, 1, size=n)).astype(np.float32)
+    q = W.gaussian_queries(nq, d, 5, unit=False)
+    xt = o.dequant_prod(idx, z, gamma, Pi, S, c32, norm) if prod else o.dequant_mse(idx, Pi, c32, norm)
+    want = o.score(q, xt)
+    scores = torch.zeros((nq, n), dtype=torch.float32, device=DEV)
+    p.reserve(n, nq, 0)
+    tq.tq_score(p, dev(q), 1, nq, dev(o.pack_planes(idx, bits_mse).view(np.int32)),
+                dev(o.pack_signs(z).view(np.int32)) if prod else None, dev(gamma) if prod else None, dev(norm), n, scores)
+    scale = np.linalg.norm(q.astype(np.float64), axis=1)[:, None] * norm[None, :]
+    P.check_close(scores.cpu().numpy(), want, scale, "score, asymmetric codebook")
 
 
 def test_score_equals_inner_product_with_dequantized_vectors():
