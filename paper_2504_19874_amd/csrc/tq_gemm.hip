@@ -429,9 +429,13 @@ static hipError_t launch_one(const GemmArgs& a, int n_groups, hipStream_t stream
   const int per_xcd = (total + XCDS - 1) / XCDS;
   dim3 grid(per_xcd * XCDS, n_groups, 1);
   constexpr int lds_bytes = 2 * (TM + TN) * LDS_LD * (int)sizeof(float);  // above the 64 KB default limit
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<NKIND, EKIND, BITS>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-  if (e != hipSuccess) return e;
+  static bool attr_done = false;  // per instantiation: the limit has to be raised once
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<NKIND, EKIND, BITS>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
   hipLaunchKernelGGL((gemm_kernel<NKIND, EKIND, BITS>), grid, dim3(256), lds_bytes, stream, a, tiles_m,
                      tiles_n, per_xcd);
   return hipGetLastError();

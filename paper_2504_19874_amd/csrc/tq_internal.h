@@ -67,6 +67,11 @@ hipError_t launch_gemm(NKind nk, EKind ek, int bits, const GemmArgs& a, int n_gr
 hipError_t launch_quant128(int bits, bool prod, bool bf16, const void* X, int64_t ldx, int64_t n,
                            const float* Pi, const float* SPiT, uint32_t* idx, uint32_t* qjl, float* gamma,
                            float* norm, const Codebook& cb, hipStream_t s);
+// d = 128, few vectors: one workgroup per block of 32 (tq_d128_small.hip)
+constexpr int64_t kSmallQuantRows = 32768;
+hipError_t launch_quant128_small(int bits, bool prod, bool bf16, const void* X, int64_t ldx, int64_t n,
+                                 const float* Pi, const float* SPiT, uint32_t* idx, uint32_t* qjl,
+                                 float* gamma, float* norm, const Codebook& cb, hipStream_t s);
 hipError_t launch_dequant128(int bits, bool prod, const uint32_t* idx, const uint32_t* qjl,
                              const float* gamma, const float* norm, const float* Pi, const float* S,
                              float* out, int64_t ldo, int64_t n, float kappa, const Codebook& cb,
