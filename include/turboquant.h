@@ -25,6 +25,24 @@
  * so one vector owns bits_mse*d/32 idx words and d/32 qjl words, contiguous.
  * Per-vector scalars are separate fp32 arrays: gamma[i] = ||r||_2 (Alg. 2) and
  * norm[i] = ||x||_2 (Sec. 1.3, norms kept in floating point).
+ *
+ * Two instances over a split of the channels (Sec. 4.3: outlier channels get
+ * more bits, which gives the non-integer bit-widths 2.5 and 3.5).  With
+ * params.d_hi > 0 the first d_hi ROTATED coordinates belong to an instance
+ * "hi" of dimension d_hi with bits_mse_hi bits and its own codebook, the
+ * remaining d - d_hi to an instance "lo" with bits_mse bits.  The caller
+ * makes Pi (and S) block diagonal up to the channel permutation that brings
+ * the outlier channels to the front: Pi = blockdiag(Pi_hi, Pi_lo) * P, so x
+ * stays in its original channel order and each block only ever sees its own
+ * channels.  Each instance normalises, quantises and sketches its own part:
+ *    idx words of vector i: group g < d_hi/32 has bits_mse_hi planes, the
+ *        others bits_mse, groups stored back to back in order;
+ *        words per vector = (d_hi/32)*bits_mse_hi + ((d-d_hi)/32)*bits_mse
+ *    norm[2i], norm[2i+1]   = L2 norms of the hi and lo channels of x_i
+ *    gamma[2i], gamma[2i+1] = residual norms of the two instances
+ * and the sketch scale of Def. 1 is sqrt(pi/2)/d_hi resp. sqrt(pi/2)/(d-d_hi).
+ * Covered for d = 128 with d_hi in {32, 64, 96}: tq_quantize_*, tq_dequantize,
+ * and tq_score with at most 32 queries per group.
  */
 #ifndef TURBOQUANT_H
 #define TURBOQUANT_H
@@ -79,6 +97,12 @@ typedef struct tq_params {
   const float* bounds;    /* host, 2^bits_mse - 1 floats                            */
   void* workspace;        /* device scratch, see tq_workspace_bytes                 */
   size_t workspace_bytes;
+  /* split into two instances (see the head of this file); all zero / NULL = one instance */
+  int32_t d_hi;               /* 0, or a multiple of 32 below d                         */
+  int32_t bits_mse_hi;        /* bits of the MSE stage of instance hi, in [0, 4]        */
+  const float* centroids_hi;  /* host, 2^bits_mse_hi floats: codebook of dimension d_hi */
+  const float* bounds_hi;     /* host, 2^bits_mse_hi - 1 floats; `centroids`/`bounds`   */
+                              /* are then the codebook of dimension d - d_hi            */
 } tq_params;
 
 /*

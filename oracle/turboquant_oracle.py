@@ -273,6 +273,47 @@ def dequant_prod(idx, qjl, gamma, Pi, S, centroids32, norm=None):
     return xt
 
 
+# --------------------------------------------------------------------------
+# Sec. 4.3: two independent instances over a split of the channels
+# (outlier channels at a higher bit-width)
+# --------------------------------------------------------------------------
+
+
+def split_channels(d: int, hi_channels):
+    """(hi, lo): the outlier channels and the others, each ascending."""
+    hi = np.sort(np.asarray(hi_channels, dtype=np.int64))
+    return hi, np.setdiff1d(np.arange(d), hi)
+
+
+def quant_split(x, hi_channels, inst_hi, inst_lo, prod: bool):
+    """Quantise x[:, hi] with instance hi and x[:, lo] with instance lo, each an
+    ordinary Quant_mse / Quant_prod of its own dimension.  An instance is a dict
+    Pi, S (None for mse), c32, t32.  Returns (result_hi, result_lo)."""
+    x = np.asarray(x)
+    hi, lo = split_channels(x.shape[1], hi_channels)
+    out = []
+    for ch, inst in ((hi, inst_hi), (lo, inst_lo)):
+        if prod:
+            out.append(quant_prod(x[:, ch], inst["Pi"], inst["S"], inst["c32"], inst["t32"]))
+        else:
+            idx, nu, y = quant_mse(x[:, ch], inst["Pi"], inst["t32"])
+            out.append(dict(idx=idx, y=y, norm=nu))
+    return out[0], out[1]
+
+
+def dequant_split(d: int, hi_channels, res_hi, res_lo, inst_hi, inst_lo, prod: bool):
+    """The two dequantised parts put back at their channels."""
+    hi, lo = split_channels(d, hi_channels)
+    n = np.asarray(res_hi["idx"]).shape[0]
+    xt = np.zeros((n, d), dtype=np.float64)
+    for ch, r, inst in ((hi, res_hi, inst_hi), (lo, res_lo, inst_lo)):
+        if prod:
+            xt[:, ch] = dequant_prod(r["idx"], r["qjl"], r["gamma"], inst["Pi"], inst["S"], inst["c32"], r["norm"])
+        else:
+            xt[:, ch] = dequant_mse(r["idx"], inst["Pi"], inst["c32"], r["norm"])
+    return xt
+
+
 def score(q, x_tilde):
     """Inner-product estimates <q, Q^-1(Q(x))> for every (query, code) pair
     (Sec. 3.2, the displayed estimator), through the dequantised vectors."""

@@ -22,6 +22,10 @@ class TqParams(C.Structure):
         ("bounds", C.c_void_p),
         ("workspace", C.c_void_p),
         ("workspace_bytes", C.c_size_t),
+        ("d_hi", C.c_int32),
+        ("bits_mse_hi", C.c_int32),
+        ("centroids_hi", C.c_void_p),
+        ("bounds_hi", C.c_void_p),
     ]
 
 

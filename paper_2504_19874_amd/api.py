@@ -56,7 +56,11 @@ class Params:
     """Owns the tq_params struct and keeps every buffer it points to alive."""
 
     def __init__(self, d: int, bits_mse: int, Pi: torch.Tensor, S: torch.Tensor | None,
-                 centroids: np.ndarray, bounds: np.ndarray, device="cuda"):
+                 centroids: np.ndarray, bounds: np.ndarray, device="cuda", d_hi: int = 0, bits_mse_hi: int = 0,
+                 centroids_hi: np.ndarray | None = None, bounds_hi: np.ndarray | None = None):
+        """d_hi > 0: two instances over a split of the rotated coordinates (Sec. 4.3); then
+        (bits_mse, centroids, bounds) belong to the d - d_hi coordinates of instance lo and the
+        *_hi arguments to the first d_hi."""
         lib = _lib.load()
         self.d, self.bits_mse = int(d), int(bits_mse)
         self.device = torch.device(device)
@@ -80,6 +84,17 @@ class Params:
         self.c.centroids = self.centroids.ctypes.data
         self.c.bounds = self._bounds_buf.ctypes.data
         self.c.workspace, self.c.workspace_bytes = 0, 0
+        self.d_hi, self.bits_mse_hi = int(d_hi), int(bits_mse_hi)
+        self.c.d_hi, self.c.bits_mse_hi, self.c.centroids_hi, self.c.bounds_hi = 0, 0, 0, 0
+        if self.d_hi:
+            self.centroids_hi = np.ascontiguousarray(centroids_hi, dtype=np.float32)
+            self.bounds_hi = np.ascontiguousarray(bounds_hi, dtype=np.float32)
+            if self.centroids_hi.size != (1 << bits_mse_hi) or self.bounds_hi.size != (1 << bits_mse_hi) - 1:
+                raise TurboQuantError("codebook size does not match bits_mse_hi")
+            self._bounds_hi_buf = self.bounds_hi if self.bounds_hi.size else np.zeros(1, dtype=np.float32)
+            self.c.d_hi, self.c.bits_mse_hi = self.d_hi, self.bits_mse_hi
+            self.c.centroids_hi = self.centroids_hi.ctypes.data
+            self.c.bounds_hi = self._bounds_hi_buf.ctypes.data
         _check(lib.tq_derive_params(self.d, _ptr(self.Pi), _ptr(self.S), _ptr(self.PiT), _ptr(self.ST),
                                     _ptr(self.SPiT), _stream()), "tq_derive_params")
 
@@ -94,7 +109,12 @@ class Params:
 
     @property
     def idx_words(self) -> int:
-        return (self.d // 32) * self.bits_mse
+        return (self.d_hi // 32) * self.bits_mse_hi + ((self.d - self.d_hi) // 32) * self.bits_mse
+
+    @property
+    def scalars_per_vector(self) -> int:
+        """Floats per vector in the gamma and norm arrays: one per instance."""
+        return 2 if self.d_hi else 1
 
     @property
     def qjl_words(self) -> int:

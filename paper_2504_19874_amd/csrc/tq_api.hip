@@ -23,7 +23,26 @@ tq_status check_params(const tq_params* p, bool need_codebook) {
     if (p->centroids == nullptr) return TQ_ERR_INVALID_ARG;
     if (p->bits_mse > 0 && p->bounds == nullptr) return TQ_ERR_INVALID_ARG;
   }
+  if (p->d_hi != 0) {
+    // two instances over a split of the rotated coordinates (Sec. 4.3)
+    if (p->d_hi < 0 || p->d_hi >= p->d || p->d_hi % 32 != 0 || p->bits_mse_hi < 0) return TQ_ERR_INVALID_ARG;
+    if (need_codebook && (p->centroids_hi == nullptr || (p->bits_mse_hi > 0 && p->bounds_hi == nullptr)))
+      return TQ_ERR_INVALID_ARG;
+    // what the kernels cover: head dimension 128, one more bit for the outlier instance
+    if (p->d != 128 || p->bits_mse_hi != p->bits_mse + 1 || p->bits_mse_hi > 4) return TQ_ERR_UNSUPPORTED;
+  }
   return TQ_OK;
+}
+
+Codebook make_codebook_hi(const tq_params* p) {
+  Codebook cb;
+  std::memset(&cb, 0, sizeof(cb));
+  if (p->d_hi == 0) return cb;
+  cb.bits = p->bits_mse_hi;
+  const int K = 1 << p->bits_mse_hi;
+  for (int k = 0; k < K; ++k) cb.c[k] = p->centroids_hi[k];
+  for (int k = 0; k + 1 < K; ++k) cb.t[k] = p->bounds_hi[k];
+  return cb;
 }
 
 Codebook make_codebook(const tq_params* p) {
@@ -70,6 +89,15 @@ tq_status quantize_common(const tq_params* p, const void* x, tq_dtype dtype, int
   const int d = p->d;
   const size_t esz = dtype == TQ_F32 ? 4 : 2;
   const int words_per_row = (d / 32) * p->bits_mse;
+
+  if (p->d_hi != 0) {
+    // two instances: the workgroup-per-block kernel at d = 128; both norms are always stored
+    if (norm == nullptr) return TQ_ERR_INVALID_ARG;
+    if (!aligned16(x) || (ldx * esz) % 16 != 0) return TQ_ERR_UNSUPPORTED;
+    return from_hip(launch_quant128_small(p->bits_mse, prod, dtype == TQ_BF16, x, ldx, n, p->Pi,
+                                          prod ? p->SPiT : nullptr, idx, qjl, gamma, norm, make_codebook(p),
+                                          p->d_hi / 32, make_codebook_hi(p), stream));
+  }
 
   // head dimension 128: one fused kernel, parameters resident in LDS
   if (d == 128 && aligned16(x) && (ldx * esz) % 16 == 0) {
@@ -359,6 +387,7 @@ tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_gr
 tq_status tq_stage_pack(const tq_params* p, const float* y, int64_t n, uint32_t* idx, void* stream) {
   tq_status st = check_params(p, true);
   if (st != TQ_OK) return st;
+  if (p->d_hi != 0) return TQ_ERR_UNSUPPORTED;  // the stand-alone stages know one instance only
   if (n < 0) return TQ_ERR_INVALID_ARG;
   if (n == 0 || p->bits_mse == 0) return TQ_OK;
   if (y == nullptr || idx == nullptr) return TQ_ERR_INVALID_ARG;
@@ -377,6 +406,7 @@ tq_status tq_stage_unpack(const tq_params* p, const uint32_t* idx, int64_t n, fl
                           void* stream) {
   tq_status st = check_params(p, true);
   if (st != TQ_OK) return st;
+  if (p->d_hi != 0) return TQ_ERR_UNSUPPORTED;  // the stand-alone stages know one instance only
   if (n < 0) return TQ_ERR_INVALID_ARG;
   if (n == 0) return TQ_OK;
   if (y_tilde == nullptr || (p->bits_mse > 0 && idx == nullptr)) return TQ_ERR_INVALID_ARG;

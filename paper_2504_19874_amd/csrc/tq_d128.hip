@@ -400,7 +400,7 @@ hipError_t launch_quant128(int bits, bool prod, bool bf16, const void* X, int64_
   // up to about one block of 32 vectors per wavefront slot of the chip, a workgroup per block
   // (tq_d128_small.hip) is the shorter chain; beyond that the streaming kernel below wins
   if (n <= kSmallQuantRows)
-    return launch_quant128_small(bits, prod, bf16, X, ldx, n, Pi, SPiT, idx, qjl, gamma, norm, cb, s);
+    return launch_quant128_small(bits, prod, bf16, X, ldx, n, Pi, SPiT, idx, qjl, gamma, norm, cb, 0, cb, s);
   Quant128Args a;
   a.X = X; a.ldx = ldx; a.n = n; a.Pi = Pi; a.SPiT = SPiT; a.idx = idx; a.qjl = qjl; a.gamma = gamma;
   a.norm = norm; a.normalise = norm != nullptr; a.cb = cb;

@@ -71,7 +71,8 @@ hipError_t launch_quant128(int bits, bool prod, bool bf16, const void* X, int64_
 constexpr int64_t kSmallQuantRows = 32768;
 hipError_t launch_quant128_small(int bits, bool prod, bool bf16, const void* X, int64_t ldx, int64_t n,
                                  const float* Pi, const float* SPiT, uint32_t* idx, uint32_t* qjl,
-                                 float* gamma, float* norm, const Codebook& cb, hipStream_t s);
+                                 float* gamma, float* norm, const Codebook& cb, int gs_hi,
+                                 const Codebook& cb_hi, hipStream_t s);
 hipError_t launch_dequant128(int bits, bool prod, const uint32_t* idx, const uint32_t* qjl,
                              const float* gamma, const float* norm, const float* Pi, const float* S,
                              float* out, int64_t ldo, int64_t n, float kappa, const Codebook& cb,

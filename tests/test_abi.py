@@ -41,8 +41,11 @@ def test_every_declared_symbol_is_exported_and_bound(lib):
 
 def test_params_struct_matches_header_layout():
     from paper_2504_19874_amd import _lib
-    assert C.sizeof(_lib.TqParams) == 8 + 9 * 8
+    # int32 x2, 9 pointer-sized fields, then the split: int32 x2 and two pointers
+    assert C.sizeof(_lib.TqParams) == 8 + 9 * 8 + 8 + 2 * 8
     assert _lib.TqParams.Pi.offset == 8 and _lib.TqParams.workspace_bytes.offset == 72
+    assert _lib.TqParams.d_hi.offset == 80 and _lib.TqParams.bits_mse_hi.offset == 84
+    assert _lib.TqParams.centroids_hi.offset == 88 and _lib.TqParams.bounds_hi.offset == 96
 
 
 @pytest.mark.parametrize("d,bits", [(3, 2), (8, 3), (128, 1), (128, 2), (128, 3), (128, 4), (1536, 4), (3072, 1), (200, 5)])

@@ -1,0 +1,96 @@
+"""Two instances over a split of the channels (Sec. 4.3: outlier channels at one more
+bit): the GPU's single set of block-diagonal d = 128 parameters against the oracle's two
+independent instances of dimension d_hi and d - d_hi."""
+import math
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import paper_2504_19874_amd as tq
+import workloads as W
+from oracle import turboquant_oracle as o
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+D = 128
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def words(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+def instances(d_hi, bits_lo, prod, seed=300):
+    """The oracle's two instances and the library's combined parameters, from the same draws."""
+    hi_ch = np.sort(np.random.default_rng(seed).permutation(D)[:d_hi])
+    g_hi, g_lo = W.gaussian_matrix(d_hi, seed + 1), W.gaussian_matrix(D - d_hi, seed + 2)
+    s_hi = W.sketch_matrix(d_hi, seed + 3) if prod else None
+    s_lo = W.sketch_matrix(D - d_hi, seed + 4) if prod else None
+    inst = []
+    for dd, g, s_, b in ((d_hi, g_hi, s_hi, bits_lo + 1), (D - d_hi, g_lo, s_lo, bits_lo)):
+        c32, t32, _ = o.codebook_fp32(dd, b)
+        inst.append(dict(Pi=o.rotation_from_gaussian(g), S=s_, c32=c32, t32=t32, d=dd, bits=b))
+    p = tq.make_mixed_params(D, hi_ch, bits_lo + 1, bits_lo, g_hi, g_lo, s_hi, s_lo)
+    return hi_ch, inst[0], inst[1], p
+
+
+def unpack_split(p, idx_words, d_hi):
+    """(idx_hi [n, d_hi], idx_lo [n, d - d_hi]) from the packed words of the split layout."""
+    gs, bh, bl = d_hi // 32, p.bits_mse_hi, p.bits_mse
+    w = idx_words[:, : p.idx_words]
+    hi = o.unpack_planes(w[:, : gs * bh], bh, d_hi) if bh else np.zeros((w.shape[0], d_hi), dtype=np.int32)
+    lo = o.unpack_planes(w[:, gs * bh:], bl, D - d_hi) if bl else np.zeros((w.shape[0], D - d_hi), dtype=np.int32)
+    return hi, lo
+
+
+def keys(n, hi_ch, seed=9, bf16=True):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((n, D)).astype(np.float32)
+    x[:, hi_ch[:4]] *= 20.0  # outlier channels, as in the key-cache recipe
+    if n > 5:
+        x[5] = 0.0
+    if not bf16:
+        return x.astype(np.float64), dev(x)
+    bits16 = W.f32_to_bf16_bits(x)
+    return o.bf16_bits_to_f64(bits16), torch.from_numpy(bits16.view(np.int16)).view(torch.bfloat16).to(DEV)
+
+
+@pytest.mark.parametrize("d_hi,bits_lo,prod,n,bf16", [
+    (32, 1, True, 3000, True), (64, 1, True, 257, False), (32, 2, True, 40000, True), (96, 2, False, 130, False),
+    (32, 0, True, 65, False), (64, 3, False, 1000, True),
+])
+def test_quantize_split(d_hi, bits_lo, prod, n, bf16):
+    hi_ch, ihi, ilo, p = instances(d_hi, bits_lo, prod)
+    x_or, x_dev = keys(n, hi_ch, bf16=bf16)
+    idx = torch.zeros((n, max(1, p.idx_words)), dtype=torch.int32, device=DEV)
+    norm = torch.zeros((n, 2), dtype=torch.float32, device=DEV)
+    qjl = torch.zeros((n, p.qjl_words), dtype=torch.int32, device=DEV) if prod else None
+    gamma = torch.zeros((n, 2), dtype=torch.float32, device=DEV) if prod else None
+    if prod:
+        tq.tq_quantize_prod(p, x_dev, idx, qjl, gamma, norm)
+    else:
+        tq.tq_quantize_mse(p, x_dev, idx, norm)
+    got_hi, got_lo = unpack_split(p, words(idx), d_hi)
+    hi, lo = o.split_channels(D, hi_ch)
+    for part, (ch, inst, got) in enumerate(((hi, ihi, got_hi), (lo, ilo, got_lo))):
+        xs = x_or[:, ch]
+        xh, nu = o.unit_normalise(xs, True)
+        y = o.rotate(xh, inst["Pi"])
+        idx_or = o.nearest_centroid(y, inst["t32"])
+        if inst["bits"]:
+            P.check_indices(got, idx_or, y, inst["t32"])
+        P.check_close(norm.cpu().numpy()[:, part], nu, 0.0, "norm", rel=3e-6)
+        if prod:
+            # downstream of the GPU's own indices (teacher forcing)
+            _, gamma_or, u_or = o.residual_and_sketch(xh, got, inst["Pi"], inst["S"], inst["c32"])
+            P.check_close(gamma.cpu().numpy()[:, part], gamma_or, 0.0, "gamma", rel=1e-5)
+            z = o.unpack_signs(words(qjl), D)
+            z_part = z[:, :d_hi] if part == 0 else z[:, d_hi:]
+            s_norm = np.linalg.norm(inst["S"].astype(np.float64), axis=1)
+            P.check_signs(z_part, u_or, s_norm[None, :] * gamma_or[:, None])
