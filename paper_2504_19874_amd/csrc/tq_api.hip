@@ -248,10 +248,19 @@ tq_status tq_dequantize(const tq_params* p, const uint32_t* idx, const uint32_t*
   if (prod && (gamma == nullptr || p->ST == nullptr)) return TQ_ERR_INVALID_ARG;
   if (ldo % 4 != 0 || !aligned16(x_out) || !aligned16(p->PiT) || (prod && !aligned16(p->ST)))
     return TQ_ERR_UNSUPPORTED;
+  if (p->d_hi != 0) {
+    // two instances: d = 128 kernel only; idx rows are not 16-byte multiples there
+    if (norm == nullptr || idx == nullptr || p->Pi == nullptr || (prod && p->S == nullptr)) return TQ_ERR_INVALID_ARG;
+    if (!aligned16(p->Pi) || (prod && (!aligned16(p->S) || !aligned16(qjl)))) return TQ_ERR_UNSUPPORTED;
+    return from_hip(launch_dequant128(p->bits_mse, prod, idx, qjl, gamma, norm, p->Pi, p->S, x_out, ldo, n,
+                                      kappa_of(p->d - p->d_hi), make_codebook(p), p->d_hi / 32,
+                                      kappa_of(p->d_hi), make_codebook_hi(p), static_cast<hipStream_t>(stream)));
+  }
   if (p->d == 128 && p->Pi != nullptr && aligned16(p->Pi) && (!prod || (p->S != nullptr && aligned16(p->S))) &&
       aligned16(idx) && (!prod || aligned16(qjl))) {
     return from_hip(launch_dequant128(p->bits_mse, prod, idx, qjl, gamma, norm, p->Pi, p->S, x_out, ldo, n,
-                                      kappa_of(p->d), make_codebook(p), static_cast<hipStream_t>(stream)));
+                                      kappa_of(p->d), make_codebook(p), 0, 0.f, make_codebook(p),
+                                      static_cast<hipStream_t>(stream)));
   }
   GemmArgs a;
   std::memset(&a, 0, sizeof(a));

@@ -274,18 +274,26 @@ struct Dequant128Args {
   int64_t n;
   float kappa;
   Codebook cb;
+  // two instances over a split of the rotated coordinates (MIXED): groups [0, gs_hi) belong to
+  // instance hi with BITS + 1 planes, codebook cb_hi and sketch scale kappa_hi
+  int gs_hi;
+  float kappa_hi;
+  Codebook cb_hi;
 };
 
-template <int BITS, bool PROD>
+template <int BITS, bool PROD, bool MIXED>
 __global__ __launch_bounds__(512) void dequant128_kernel(const Dequant128Args a) {
   extern __shared__ __attribute__((aligned(16))) float smem[];
   __shared__ float cent_s[16];
+  __shared__ float cent_hi_s[32];
   float* Pi_s = smem;          // [128][128], rows read contiguously
   float* S_s = smem + D * D;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, h = lane >> 5;
   if (tid < 16) cent_s[tid] = a.cb.c[tid];
+  if (MIXED && tid < 16) cent_hi_s[tid] = a.cb_hi.c[tid];
+  const int gs = MIXED ? a.gs_hi : 0;
   for (int p = 0; p < 8; ++p) {
     const int e4 = tid + 512 * p;
     reinterpret_cast<float4*>(Pi_s)[e4] = reinterpret_cast<const float4*>(a.Pi)[e4];
@@ -298,31 +306,60 @@ __global__ __launch_bounds__(512) void dequant128_kernel(const Dequant128Args a)
     const int64_t i = blk * 32 + l32;
     const bool valid = i < a.n;
     const int64_t row = valid ? i : 0;
-    const float nu = (valid && a.norm != nullptr) ? a.norm[row] : (valid ? 1.f : 0.f);
+    // per-instance scalars: index 1 = instance hi (MIXED only), index 0 = the (only / lo) instance
+    float nu[2], kg[2] = {0.f, 0.f};
+    if (MIXED) {
+      nu[1] = valid ? a.norm[2 * row] : 0.f;
+      nu[0] = valid ? a.norm[2 * row + 1] : 0.f;
+      if (PROD) {
+        kg[1] = nu[1] * a.kappa_hi * a.gamma[2 * row];
+        kg[0] = nu[0] * a.kappa * a.gamma[2 * row + 1];
+      }
+    } else {
+      nu[0] = nu[1] = (valid && a.norm != nullptr) ? a.norm[row] : (valid ? 1.f : 0.f);
+      if (PROD) kg[0] = kg[1] = nu[0] * a.kappa * a.gamma[row];
+    }
     floatx16 acc[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
 
-    if (BITS > 0) {
-      uint32_t w[4 * (BITS > 0 ? BITS : 1)];
-      const uint32_t* src = a.idx + row * (4 * BITS);
+    if (BITS > 0 || MIXED) {
+      // plane words of each group, shifted to this half's 16 coordinates; a group of instance lo
+      // has no plane BITS (left zero), so one decode serves both
+      constexpr int NP = BITS + (MIXED ? 1 : 0);
+      constexpr int BD = BITS > 0 ? BITS : 1;
+      uint32_t wg[4][NP > 0 ? NP : 1];
+      if (MIXED) {
+        const uint32_t* src = a.idx + row * (4 * BITS + gs);
 #pragma unroll
-      for (int v = 0; v < BITS; ++v) {
-        const uint4 t4 = *reinterpret_cast<const uint4*>(src + 4 * v);
-        w[4 * v] = t4.x; w[4 * v + 1] = t4.y; w[4 * v + 2] = t4.z; w[4 * v + 3] = t4.w;
+        for (int g = 0; g < 4; ++g) {
+          const int base = g < gs ? g * (BITS + 1) : gs * (BITS + 1) + (g - gs) * BITS;
+#pragma unroll
+          for (int pl = 0; pl < NP; ++pl) wg[g][pl] = (pl < BITS || g < gs) ? src[base + pl] >> (16 * h) : 0u;
+        }
+      } else {
+        const uint32_t* src = a.idx + row * (4 * BITS);
+#pragma unroll
+        for (int v = 0; v < BITS; ++v) {
+          const uint4 t4 = *reinterpret_cast<const uint4*>(src + 4 * v);
+          const uint32_t w4[4] = {t4.x, t4.y, t4.z, t4.w};
+#pragma unroll
+          for (int q = 0; q < 4; ++q) wg[(4 * v + q) / BD][(4 * v + q) % BD] = w4[q] >> (16 * h);
+        }
       }
 #pragma unroll
-      for (int q = 0; q < 4 * BITS; ++q) w[q] >>= (16 * h);  // this half's 16 coordinates of each group
-#pragma unroll
       for (int g = 0; g < 4; ++g) {
+        const bool ghi = MIXED && g < gs;  // uniform
+        const float* const tab = ghi ? cent_hi_s : cent_s;
+        const float nug = ghi ? nu[1] : nu[0];
 #pragma unroll
         for (int s = 0; s < 16; ++s) {
           uint32_t code = 0u;
 #pragma unroll
-          for (int pl = 0; pl < BITS; ++pl) code |= ((w[g * BITS + pl] >> s) & 1u) << pl;
-          const float av = nu * cent_s[code];
+          for (int pl = 0; pl < NP; ++pl) code |= ((wg[g][pl] >> s) & 1u) << pl;
+          const float av = nug * tab[code];
           const float4 bv = *reinterpret_cast<const float4*>(&Pi_s[(32 * g + 16 * h + s) * D + 4 * l32]);
           acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv.x, acc[0], 0, 0, 0);
           acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv.y, acc[1], 0, 0, 0);
@@ -335,12 +372,12 @@ __global__ __launch_bounds__(512) void dequant128_kernel(const Dequant128Args a)
     if (PROD) {
       const uint4 t4 = *reinterpret_cast<const uint4*>(a.qjl + row * 4);
       const uint32_t z[4] = {t4.x >> (16 * h), t4.y >> (16 * h), t4.z >> (16 * h), t4.w >> (16 * h)};
-      const float kg = nu * a.kappa * a.gamma[row];
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
+        const float kgg = (MIXED && g < gs) ? kg[1] : kg[0];
 #pragma unroll
         for (int s = 0; s < 16; ++s) {
-          const float av = ((z[g] >> s) & 1u) ? kg : -kg;
+          const float av = ((z[g] >> s) & 1u) ? kgg : -kgg;
           const float4 bv = *reinterpret_cast<const float4*>(&S_s[(32 * g + 16 * h + s) * D + 4 * l32]);
           acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv.x, acc[0], 0, 0, 0);
           acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv.y, acc[1], 0, 0, 0);
@@ -414,28 +451,38 @@ hipError_t launch_quant128(int bits, bool prod, bool bf16, const void* X, int64_
   }
 }
 
-template <int BITS, bool PROD>
-static hipError_t launch_d(const Dequant128Args& a, hipStream_t s) {
+template <int BITS, bool PROD, bool MIXED>
+static hipError_t launch_dm(const Dequant128Args& a, hipStream_t s) {
   const size_t smem = (size_t)(PROD ? 2 : 1) * D * D * sizeof(float);
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dequant128_kernel<BITS, PROD>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dequant128_kernel<BITS, PROD, MIXED>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL((dequant128_kernel<BITS, PROD>), dim3(grid_128(a.n)), dim3(512), smem, s, a);
+  hipLaunchKernelGGL((dequant128_kernel<BITS, PROD, MIXED>), dim3(grid_128(a.n)), dim3(512), smem, s, a);
   return hipGetLastError();
+}
+
+template <int BITS, bool PROD>
+static hipError_t launch_d(const Dequant128Args& a, hipStream_t s) {
+  if (a.gs_hi > 0) {
+    if (BITS >= 4) return hipErrorInvalidValue;
+    return launch_dm<(BITS < 4 ? BITS : 0), PROD, true>(a, s);
+  }
+  return launch_dm<BITS, PROD, false>(a, s);
 }
 
 hipError_t launch_dequant128(int bits, bool prod, const uint32_t* idx, const uint32_t* qjl,
                              const float* gamma, const float* norm, const float* Pi, const float* S,
                              float* out, int64_t ldo, int64_t n, float kappa, const Codebook& cb,
-                             hipStream_t s) {
+                             int gs_hi, float kappa_hi, const Codebook& cb_hi, hipStream_t s) {
   if (n == 0) return hipSuccess;
+  if (gs_hi < 0 || gs_hi > 3 || (gs_hi > 0 && (cb_hi.bits != bits + 1 || norm == nullptr))) return hipErrorInvalidValue;
   Dequant128Args a;
   a.idx = idx; a.qjl = qjl; a.gamma = gamma; a.norm = norm; a.Pi = Pi; a.S = S; a.out = out; a.ldo = ldo;
-  a.n = n; a.kappa = kappa; a.cb = cb;
+  a.n = n; a.kappa = kappa; a.cb = cb; a.gs_hi = gs_hi; a.kappa_hi = kappa_hi; a.cb_hi = cb_hi;
   switch (bits) {
     case 0: return prod ? launch_d<0, true>(a, s) : launch_d<0, false>(a, s);
     case 1: return prod ? launch_d<1, true>(a, s) : launch_d<1, false>(a, s);

@@ -94,3 +94,42 @@ def test_quantize_split(d_hi, bits_lo, prod, n, bf16):
             z_part = z[:, :d_hi] if part == 0 else z[:, d_hi:]
             s_norm = np.linalg.norm(inst["S"].astype(np.float64), axis=1)
             P.check_signs(z_part, u_or, s_norm[None, :] * gamma_or[:, None])
+
+
+def random_codes(p, ihi, ilo, d_hi, n, prod, seed=21):
+    """Random codes of both instances, in the oracle's form and packed in the split layout."""
+    rng = np.random.default_rng(seed)
+    res, packed = [], []
+    for inst in (ihi, ilo):
+        dd, b = inst["d"], inst["bits"]
+        r = dict(idx=rng.integers(0, 1 << b, size=(n, dd)).astype(np.int32),
+                 norm=np.exp(rng.normal(0, 1, size=n)).astype(np.float32))
+        if prod:
+            r["qjl"] = rng.integers(0, 2, size=(n, dd)).astype(bool)
+            r["gamma"] = rng.uniform(0.05, 0.6, size=n).astype(np.float32)
+        res.append(r)
+        packed.append(o.pack_planes(r["idx"], b) if b else np.zeros((n, 0), dtype=np.uint32))
+    idx_w = np.concatenate(packed, axis=1)
+    assert idx_w.shape[1] == p.idx_words
+    norm = np.stack([res[0]["norm"], res[1]["norm"]], axis=1)
+    qjl_w = gamma = None
+    if prod:
+        qjl_w = o.pack_signs(np.concatenate([res[0]["qjl"], res[1]["qjl"]], axis=1))
+        gamma = np.stack([res[0]["gamma"], res[1]["gamma"]], axis=1)
+    return res, idx_w, qjl_w, gamma, norm
+
+
+@pytest.mark.parametrize("d_hi,bits_lo,prod,n", [(32, 1, True, 777), (64, 2, True, 130), (96, 1, False, 65), (32, 3, False, 300),
+                                                (32, 0, True, 40)])
+def test_dequantize_split(d_hi, bits_lo, prod, n):
+    hi_ch, ihi, ilo, p = instances(d_hi, bits_lo, prod)
+    res, idx_w, qjl_w, gamma, norm = random_codes(p, ihi, ilo, d_hi, n, prod)
+    want = o.dequant_split(D, hi_ch, res[0], res[1], ihi, ilo, prod)
+    out = torch.zeros((n, D), dtype=torch.float32, device=DEV)
+    tq.tq_dequantize(p, dev(idx_w.view(np.int32)), dev(qjl_w.view(np.int32)) if prod else None,
+                     dev(gamma) if prod else None, dev(norm), out)
+    scale = np.zeros((n, D))
+    hi, lo = o.split_channels(D, hi_ch)
+    scale[:, hi] = norm[:, :1] / math.sqrt(d_hi)
+    scale[:, lo] = norm[:, 1:] / math.sqrt(D - d_hi)
+    P.check_close(out.cpu().numpy(), want, scale, "dequantized coordinate")
