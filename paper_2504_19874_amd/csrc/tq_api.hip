@@ -303,9 +303,30 @@ tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_gr
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int d = p->d;
 
-  const bool small_i8 = q_per_group <= 32 && score_i8_applicable(p->bits_mse, d, make_codebook(p));
   Workspace ws{static_cast<char*>(p->workspace), p->workspace_bytes, 0};
   int64_t ld_scores = lds;
+  if (p->d_hi != 0) {
+    // two instances over a split of the coordinates: few queries per code at d = 128 only
+    if (norm == nullptr || (n_per_group > 0 && idx == nullptr)) return TQ_ERR_INVALID_ARG;
+    if (q_per_group > 32 || !score_i8_split_applicable(p->bits_mse, make_codebook(p), make_codebook_hi(p)))
+      return TQ_ERR_UNSUPPORTED;
+    void* img = ws.take(score_i8_workspace_bytes(d, nq));
+    if (img == nullptr) return TQ_ERR_WORKSPACE;
+    if (scores == nullptr) {
+      ld_scores = (n_per_group + 3) / 4 * 4;
+      scores = static_cast<float*>(ws.take((size_t)nq * ld_scores * sizeof(float)));
+      if (scores == nullptr) return TQ_ERR_WORKSPACE;
+    }
+    if (launch_score_i8_split(p->bits_mse, prod, p->Pi, p->S, q, ldq, img, idx, qjl, gamma, norm, scores, ld_scores,
+                              n_per_group, n_groups, q_per_group, p->d_hi / 32, kappa_of(d - p->d_hi),
+                              kappa_of(p->d_hi), make_codebook(p), make_codebook_hi(p), s) != hipSuccess)
+      return TQ_ERR_HIP;
+    if (topk > 0 &&
+        launch_topk(scores, nq, n_per_group, ld_scores, topk, topk_idx, topk_val, s) != hipSuccess)
+      return TQ_ERR_HIP;
+    return TQ_OK;
+  }
+  const bool small_i8 = q_per_group <= 32 && score_i8_applicable(p->bits_mse, d, make_codebook(p));
   if (small_i8) {
     // few queries per code: masked sums of fixed-point query digits on the int8 matrix cores;
     // its own preparation kernel rotates the queries and writes their digit images

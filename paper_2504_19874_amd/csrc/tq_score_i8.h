@@ -14,7 +14,8 @@ __host__ __device__ constexpr int i8_coord0(int s, int kq) { return 32 * (kq + 4
 // Image of one query's A operand, written by prep_i8_kernel: for matrix m (0: Pi q, 1: S q),
 // k-step s, digit row dg, k-chunk kq the 16 bytes of coordinates i8_coord0(s, kq) .. + 15.
 //   bytes:   img[((q * 2 + m) * ks + s) * 16 + dg * 4 + kq]      (16-byte units)
-//   scalars: scal[(q * 2 + m) * 2 + {0: 1/scale, 1: sum of the rounded coordinates}]
+//   scalars: scal[(q * 2 + m) * 4 + {0: 1/scale, 1: sum of the rounded coordinates, 2 and 3: the same sum over
+//            the first d_hi coordinates and over the others (split into two instances)}]
 struct ScoreI8Args {
   const uint4* img;
   const float* scal;
@@ -46,5 +47,8 @@ constexpr int I8_TABLE_BYTES = 256 * I8_COPIES * 8;
 
 
 hipError_t launch_score_i8_128(int bits, bool prod, const ScoreI8Args& a, int n_groups, hipStream_t stream);
+void i8_walsh(int bits, const Codebook& cb, double* w);  // Walsh coefficients of a centroid table (tq_score_i8.hip)
+hipError_t launch_prep_i8_128(int d_hi, const float* Pi, const float* S, const float* q, int64_t ldq, int64_t nq,
+                              bool prod, uint4* img, float* scal, hipStream_t stream);
 
 }  // namespace tq

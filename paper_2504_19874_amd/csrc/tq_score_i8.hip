@@ -62,13 +62,13 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // of a half-wavefront, 16 bytes each, and reduced across them.
 // ---------------------------------------------------------------------------
 template <int P>  // P = d / 128: 16-byte pieces per lane per row; a half-wavefront owns 8 P rows
-__global__ __launch_bounds__(512) void prep_i8_kernel(const int d, const float* __restrict__ W0,
+__global__ __launch_bounds__(512) void prep_i8_kernel(const int d, const int d_hi, const float* __restrict__ W0,
                                                       const float* __restrict__ W1,
                                                       const float* __restrict__ x, const int64_t ldx,
                                                       uint4* __restrict__ img, float* __restrict__ scal) {
   __shared__ float ys[512];
   __shared__ float red_mx[8];
-  __shared__ int red_tot[8];
+  __shared__ int red_tot[8], red_hi[8];
   const int tid = threadIdx.x;
   const int l32 = tid & 31, hw = tid >> 5;  // 16 half-wavefronts
   const int64_t q = blockIdx.x;
@@ -119,16 +119,28 @@ __global__ __launch_bounds__(512) void prep_i8_kernel(const int d, const float* 
   if (mx > 0.f) (void)frexpf(mx, &e);  // mx = f * 2^e, f in [0.5, 1)
   const float sc = ldexpf(1.f, 19 - e);
   int tot = tid < d ? __float2int_rn(ys[tid] * sc) : 0;
+  int tot_hi = tid < d_hi ? tot : 0;  // the first d_hi coordinates: instance hi of a split (Sec. 4.3)
 #pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) tot += __shfl_xor(tot, off);
-  if ((tid & 63) == 0) red_tot[tid >> 6] = tot;
+  for (int off = 32; off >= 1; off >>= 1) {
+    tot += __shfl_xor(tot, off);
+    tot_hi += __shfl_xor(tot_hi, off);
+  }
+  if ((tid & 63) == 0) {
+    red_tot[tid >> 6] = tot;
+    red_hi[tid >> 6] = tot_hi;
+  }
   __syncthreads();
   if (tid == 0) {
-    int t = 0;
+    int t = 0, th = 0;
 #pragma unroll
-    for (int w = 0; w < 8; ++w) t += red_tot[w];
-    scal[(q * 2 + mat) * 2 + 0] = ldexpf(1.f, e - 19);
-    scal[(q * 2 + mat) * 2 + 1] = (float)t * ldexpf(1.f, e - 19);
+    for (int w = 0; w < 8; ++w) {
+      t += red_tot[w];
+      th += red_hi[w];
+    }
+    scal[(q * 2 + mat) * 4 + 0] = ldexpf(1.f, e - 19);
+    scal[(q * 2 + mat) * 4 + 1] = (float)t * ldexpf(1.f, e - 19);
+    scal[(q * 2 + mat) * 4 + 2] = (float)th * ldexpf(1.f, e - 19);
+    scal[(q * 2 + mat) * 4 + 3] = (float)(t - th) * ldexpf(1.f, e - 19);
   }
   const int ks = d >> 6;
   for (int u = tid; u < ks * 16; u += 512) {  // unit = (k-step s, digit dg, k-chunk kq)
@@ -193,12 +205,12 @@ __global__ __launch_bounds__(512) void score_i8_kernel(const ScoreI8Args a) {
     as_[s] = v4i{(int)z.x, (int)z.y, (int)z.z, (int)z.w};
   }
   if (BITS > 0) {
-    r_inv = a.scal[(orow * 2 + 0) * 2];
-    r_sum = a.scal[(orow * 2 + 0) * 2 + 1];
+    r_inv = a.scal[(orow * 2 + 0) * 4];
+    r_sum = a.scal[(orow * 2 + 0) * 4 + 1];
   }
   if (PROD) {
-    s_inv = a.scal[(orow * 2 + 1) * 2];
-    s_sum = a.scal[(orow * 2 + 1) * 2 + 1];
+    s_inv = a.scal[(orow * 2 + 1) * 4];
+    s_sum = a.scal[(orow * 2 + 1) * 4 + 1];
   }
 
   // ---- 2. every code word of this wavefront's keys goes in flight: the first tile can start
@@ -405,7 +417,7 @@ size_t score_i8_workspace_bytes(int d, int64_t nq) {
 // x_S(v) = XOR of the bits of v in S, sgn_S = +1 for odd |S| and -1 for even |S|.  Summed in
 // pairs (v, K-1-v): for even |S| chi_S agrees on the pair, so a table with c[K-1-v] = -c[v]
 // gives exactly zero there.
-static void walsh(int bits, const Codebook& cb, double* w) {
+void i8_walsh(int bits, const Codebook& cb, double* w) {
   const int K = 1 << bits;
   for (int sset = 0; sset < K; ++sset) {
     double acc = 0.0;
@@ -421,10 +433,18 @@ static void walsh(int bits, const Codebook& cb, double* w) {
   }
 }
 
+// the d = 128 preparation kernel for the split variant (tq_score_i8_split.hip)
+hipError_t launch_prep_i8_128(int d_hi, const float* Pi, const float* S, const float* q, int64_t ldq, int64_t nq,
+                              bool prod, uint4* img, float* scal, hipStream_t stream) {
+  hipLaunchKernelGGL(prep_i8_kernel<1>, dim3((unsigned)nq, prod ? 2 : 1), dim3(512), 0, stream, 128, d_hi, Pi, S, q, ldq,
+                     img, scal);
+  return hipGetLastError();
+}
+
 bool score_i8_applicable(int bits, int d, const Codebook& cb) {
   if (bits < 0 || bits > 4 || d % 128 != 0 || d > 64 * I8_MAX_KS) return false;
   double w[16];
-  walsh(bits, cb, w);
+  i8_walsh(bits, cb, w);
   for (int sset = 1; sset < (1 << bits); ++sset)
     if (!i8_term(sset) && w[sset] != 0.0) return false;  // not symmetric about zero
   return true;
@@ -445,7 +465,7 @@ hipError_t launch_score_i8(int bits, bool prod, const float* Pi, const float* S,
   a.img = img; a.scal = scal; a.PiT = PiT; a.ST = ST; a.x = q; a.ldx = ldq; a.idx = idx; a.qjl = qjl; a.gamma = gamma; a.norm = norm;
   a.scores = scores; a.lds = lds; a.n = n; a.total_rows = (int64_t)n_groups * n; a.d = d; a.q_per_group = q_per_group; a.kappa = kappa;
   double w[16];
-  walsh(bits, cb, w);
+  i8_walsh(bits, cb, w);
   // sum_j q_j c[idx_j] = (w_0 - sum_S sgn_S w_S) * sum_j q_j + sum_S 2 sgn_S w_S M_S
   const int K = 1 << bits;
   double c0 = w[0];
@@ -464,10 +484,10 @@ hipError_t launch_score_i8(int bits, bool prod, const float* Pi, const float* S,
     return launch_score_i8_128(bits, prod, a, n_groups, stream);
   const dim3 pgrid((unsigned)nq, prod ? 2 : 1);
   switch (d >> 7) {
-    case 1: hipLaunchKernelGGL(prep_i8_kernel<1>, pgrid, dim3(512), 0, stream, d, Pi, S, q, ldq, img, scal); break;
-    case 2: hipLaunchKernelGGL(prep_i8_kernel<2>, pgrid, dim3(512), 0, stream, d, Pi, S, q, ldq, img, scal); break;
-    case 3: hipLaunchKernelGGL(prep_i8_kernel<3>, pgrid, dim3(512), 0, stream, d, Pi, S, q, ldq, img, scal); break;
-    default: hipLaunchKernelGGL(prep_i8_kernel<4>, pgrid, dim3(512), 0, stream, d, Pi, S, q, ldq, img, scal); break;
+    case 1: hipLaunchKernelGGL(prep_i8_kernel<1>, pgrid, dim3(512), 0, stream, d, 0, Pi, S, q, ldq, img, scal); break;
+    case 2: hipLaunchKernelGGL(prep_i8_kernel<2>, pgrid, dim3(512), 0, stream, d, 0, Pi, S, q, ldq, img, scal); break;
+    case 3: hipLaunchKernelGGL(prep_i8_kernel<3>, pgrid, dim3(512), 0, stream, d, 0, Pi, S, q, ldq, img, scal); break;
+    default: hipLaunchKernelGGL(prep_i8_kernel<4>, pgrid, dim3(512), 0, stream, d, 0, Pi, S, q, ldq, img, scal); break;
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

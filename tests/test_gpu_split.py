@@ -133,3 +133,31 @@ def test_dequantize_split(d_hi, bits_lo, prod, n):
     scale[:, hi] = norm[:, :1] / math.sqrt(d_hi)
     scale[:, lo] = norm[:, 1:] / math.sqrt(D - d_hi)
     P.check_close(out.cpu().numpy(), want, scale, "dequantized coordinate")
+
+
+@pytest.mark.parametrize("d_hi,bits_lo,prod,n_groups,qpg,npg,topk", [
+    (32, 1, True, 8, 4, 1000, 0), (64, 1, True, 2, 5, 2100, 0), (32, 2, True, 1, 4, 130, 5), (96, 2, False, 2, 3, 300, 0),
+    (32, 0, True, 1, 1, 77, 0), (64, 3, False, 1, 9, 1500, 4),
+])
+def test_score_split(d_hi, bits_lo, prod, n_groups, qpg, npg, topk):
+    hi_ch, ihi, ilo, p = instances(d_hi, bits_lo, prod)
+    n, nq = n_groups * npg, n_groups * qpg
+    res, idx_w, qjl_w, gamma, norm = random_codes(p, ihi, ilo, d_hi, n, prod, seed=5)
+    q = W.gaussian_queries(nq, D, 3, unit=False)
+    q[:, hi_ch[:4]] *= 10.0  # queries see the outlier channels too
+    xt = o.dequant_split(D, hi_ch, res[0], res[1], ihi, ilo, prod)
+    want = np.concatenate([o.score(q[g * qpg:(g + 1) * qpg], xt[g * npg:(g + 1) * npg]) for g in range(n_groups)])
+    scores = torch.zeros((nq, npg), dtype=torch.float32, device=DEV)
+    ti = torch.zeros((nq, max(1, topk)), dtype=torch.int32, device=DEV)
+    p.reserve(n, nq, topk)
+    tq.tq_score(p, dev(q), n_groups, qpg, dev(idx_w.view(np.int32)), dev(qjl_w.view(np.int32)) if prod else None,
+                dev(gamma) if prod else None, dev(norm), npg, scores, topk, ti if topk else None, None)
+    hi, lo = o.split_channels(D, hi_ch)
+    q64 = q.astype(np.float64)
+    # natural scale of a pair: sum over the instances of |q part| * stored norm
+    qs = np.stack([np.linalg.norm(q64[:, hi], axis=1), np.linalg.norm(q64[:, lo], axis=1)], axis=1)
+    scale = np.concatenate([qs[g * qpg:(g + 1) * qpg] @ norm[g * npg:(g + 1) * npg].T for g in range(n_groups)])
+    got = scores.cpu().numpy()
+    P.check_close(got, want, scale, "score")
+    if topk:
+        assert np.array_equal(ti.cpu().numpy(), o.topk(got, topk))
