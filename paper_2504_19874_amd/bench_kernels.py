@@ -75,8 +75,17 @@ def main():
     d, n, nq = cfg.d, cfg.n * cfg.n_groups, cfg.nq
     big = n * d * 4 > (1 << 30)
     reps = args.reps or (5 if big else 100)
-    S = W.sketch_matrix(d, cfg.seed_s) if prod else None
-    p = tq.make_params(d, cfg.bits_mse, W.gaussian_matrix(d, cfg.seed_pi), S).reserve(n, nq, cfg.topk)
+    if cfg.d_hi:
+        # two instances over a channel split: cfg.bits belongs to the d - d_hi ordinary channels
+        hi = W.kv_hi_channels(cfg.n_groups, d, cfg.seed_x, cfg.d_hi)
+        p = tq.make_mixed_params(d, hi, cfg.bits_mse + 1, cfg.bits_mse, W.gaussian_matrix(cfg.d_hi, cfg.seed_pi),
+                                 W.gaussian_matrix(d - cfg.d_hi, cfg.seed_pi + 1),
+                                 W.sketch_matrix(cfg.d_hi, cfg.seed_s) if prod else None,
+                                 W.sketch_matrix(d - cfg.d_hi, cfg.seed_s + 1) if prod else None).reserve(n, nq, cfg.topk)
+    else:
+        S = W.sketch_matrix(d, cfg.seed_s) if prod else None
+        p = tq.make_params(d, cfg.bits_mse, W.gaussian_matrix(d, cfg.seed_pi), S).reserve(n, nq, cfg.topk)
+    spv = p.scalars_per_vector
 
     # input sets: rotate through several when the working set would sit in cache
     in_b = 2 if cfg.in_dtype == "bf16" else 4
@@ -102,8 +111,8 @@ def main():
     def new_codes():
         return dict(idx=torch.zeros((n, max(1, p.idx_words)), dtype=torch.int32, device="cuda"),
                     qjl=torch.zeros((n, p.qjl_words), dtype=torch.int32, device="cuda") if prod else None,
-                    gamma=torch.zeros(n, dtype=torch.float32, device="cuda") if prod else None,
-                    norm=None if cfg.unit_norm else torch.zeros(n, dtype=torch.float32, device="cuda"))
+                    gamma=torch.zeros((n, spv), dtype=torch.float32, device="cuda") if prod else None,
+                    norm=None if cfg.unit_norm else torch.zeros((n, spv), dtype=torch.float32, device="cuda"))
 
     codes = [new_codes() for _ in range(sets)]
 
@@ -114,7 +123,9 @@ def main():
         else:
             tq.tq_quantize_mse(p, x, c["idx"], c["norm"])
 
-    code_b = cfg.bits_mse * d / 8 + (d / 8 + 4 if prod else 0) + (0 if cfg.unit_norm else 4)
+    code_b = 4 * p.idx_words + (d / 8 + 4 * spv if prod else 0) + (0 if cfg.unit_norm else 4 * spv)
+    # algorithmic contraction size per vector: two instances rotate their own channels only
+    dd = float(cfg.d_hi ** 2 + (d - cfg.d_hi) ** 2) if cfg.d_hi else float(d * d)
     want = [w for w in args.only.split(",") if w]
 
     def on(name):
@@ -125,7 +136,7 @@ def main():
     torch.cuda.synchronize()
 
     if on("quantize"):
-        report("quantize", cfg, timed(quantize, reps), 2.0 * n * d * d * (2 if prod else 1), n * (d * in_b + code_b),
+        report("quantize", cfg, timed(quantize, reps), 2.0 * n * dd * (2 if prod else 1), n * (d * in_b + code_b),
                {"vectors_per_s": None, "input_sets": sets})
 
     if on("dequantize"):
@@ -135,7 +146,7 @@ def main():
             c = codes[r % sets]
             tq.tq_dequantize(p, c["idx"], c["qjl"], c["gamma"], c["norm"], xt[r % len(xt)])
 
-        report("dequantize", cfg, timed(dequantize, reps), 2.0 * n * d * d * (2 if prod else 1), n * (code_b + 4 * d))
+        report("dequantize", cfg, timed(dequantize, reps), 2.0 * n * dd * (2 if prod else 1), n * (code_b + 4 * d))
         del xt
 
     if on("score"):
@@ -153,10 +164,10 @@ def main():
         pairs = float(nq) * cfg.n
         out_b = 0 if cfg.topk else 4 * pairs
         report("score" + (f"+top{cfg.topk}" if cfg.topk else ""), cfg, timed(score, reps),
-               2.0 * pairs * d * (2 if prod else 1) + 2.0 * nq * d * d * (2 if prod else 1),
+               2.0 * pairs * d * (2 if prod else 1) + 2.0 * nq * dd * (2 if prod else 1),
                n * code_b + out_b + 4 * nq * d, {"scores_per_s": None, "pairs": pairs})
 
-    if on("stage") and cfg.bits_mse > 0:
+    if on("stage") and cfg.bits_mse > 0 and not cfg.d_hi:
         # codec stages on rotated coordinates of the same shape
         rows = n if not big else min(n, 1 << 20)
         ysets = 1 if big else sets

@@ -161,3 +161,40 @@ def test_score_split(d_hi, bits_lo, prod, n_groups, qpg, npg, topk):
     P.check_close(got, want, scale, "score")
     if topk:
         assert np.array_equal(ti.cpu().numpy(), o.topk(got, topk))
+
+
+def test_split_end_to_end_statistics():
+    """quantise + score through the library on isotropic keys: the estimate is unbiased and its
+    mean squared error is the sum of the two instances' pi/(2 d_part) * d_part C(f_X, b_mse) *
+    ||x_part||^2 ||q_part||^2 (Theorem 2's proof per instance), here for 2.5 bits per channel."""
+    d_hi, bits_lo, n, nq = 64, 1, 20000, 32
+    hi_ch, ihi, ilo, p = instances(d_hi, bits_lo, True)
+    rng = np.random.default_rng(31)
+    x = rng.standard_normal((n, D)).astype(np.float32)
+    q = rng.standard_normal((nq, D)).astype(np.float32)
+    idx = torch.zeros((n, p.idx_words), dtype=torch.int32, device=DEV)
+    qjl = torch.zeros((n, p.qjl_words), dtype=torch.int32, device=DEV)
+    gamma = torch.zeros((n, 2), dtype=torch.float32, device=DEV)
+    norm = torch.zeros((n, 2), dtype=torch.float32, device=DEV)
+    tq.tq_quantize_prod(p, dev(x), idx, qjl, gamma, norm)
+    s = torch.zeros((nq, n), dtype=torch.float32, device=DEV)
+    p.reserve(n, nq, 0)
+    tq.tq_score(p, dev(q), 1, nq, idx, qjl, gamma, norm, n, s)
+    # dequantise agrees with the scores
+    xt = torch.zeros((n, D), dtype=torch.float32, device=DEV)
+    tq.tq_dequantize(p, idx, qjl, gamma, norm, xt)
+    est = s.cpu().numpy().astype(np.float64)
+    x64, q64 = x.astype(np.float64), q.astype(np.float64)
+    via = q64 @ xt.cpu().numpy().astype(np.float64).T
+    P.check_close(est, via, np.linalg.norm(q64, axis=1)[:, None] * np.linalg.norm(x64, axis=1)[None, :], "score vs <q, x~>")
+    exact = q64 @ x64.T
+    err = est - exact
+    hi, lo = o.split_channels(D, hi_ch)
+    var = np.zeros_like(exact)
+    for ch, inst in ((hi, ihi), (lo, ilo)):
+        cost = o.lloyd_max_codebook(len(ch), inst["bits"])[2]
+        var += (math.pi / (2 * len(ch))) * len(ch) * cost * np.sum(q64[:, ch] ** 2, axis=1)[:, None] * \
+            np.sum(x64[:, ch] ** 2, axis=1)[None, :]
+    assert abs(np.sum(err * exact) / np.sum(exact * exact)) < 0.01
+    # the formula is an expectation over S; one fixed 64 x 64 draw sits within ~10 % of it
+    assert abs(np.mean(err ** 2) / np.mean(var) - 1) < 0.12

@@ -36,6 +36,7 @@ class Config:
     seed_q: int
     seed_pi: int
     seed_s: int
+    d_hi: int = 0  # > 0: that many outlier channels form a second instance with bits + 1 (Sec. 4.3)
 
     @property
     def bits_mse(self) -> int:
@@ -47,6 +48,9 @@ CONFIGS = {
     "C2": Config("C2", "prod", 3, 128, 16384, 8, 32, 4, "bf16", False, 0, 2, 3, 100, 200),
     "C3": Config("C3", "prod", 3, 128, 65536, 8, 32, 4, "bf16", False, 0, 2, 3, 100, 200),
     "C3b4": Config("C3b4", "prod", 4, 128, 65536, 8, 32, 4, "bf16", False, 0, 2, 3, 100, 200),
+    # 2.5 bits per channel: 64 outlier channels at b = 3, 64 at b = 2 (shapes of C2 / C3)
+    "C2m": Config("C2m", "prod", 2, 128, 16384, 8, 32, 4, "bf16", False, 0, 2, 3, 100, 200, 64),
+    "C3m": Config("C3m", "prod", 2, 128, 65536, 8, 32, 4, "bf16", False, 0, 2, 3, 100, 200, 64),
     "C4": Config("C4", "mse", 4, 1536, 1000000, 1, 1000, 1000, "f32", True, 10, 4, 5, 101, 201),
     "C5": Config("C5", "prod", 2, 3072, 1000000, 1, 1000, 1000, "f32", True, 10, 6, 7, 102, 202),
 }
@@ -83,6 +87,15 @@ def kv_outlier_channels(n_heads: int, d: int, seed: int, n_out: int = 4) -> np.n
     permutation."""
     rng = np.random.default_rng([seed, 2])
     return np.stack([rng.permutation(d)[:n_out] for _ in range(n_heads)])
+
+
+def kv_hi_channels(n_heads: int, d: int, seed: int, d_hi: int) -> np.ndarray:
+    """The channel set given more bits when the key cache is split into two
+    instances: every head's outlier channels, filled up to d_hi with the
+    lowest-numbered remaining channels.  Ascending."""
+    out = np.unique(kv_outlier_channels(n_heads, d, seed))[:d_hi]
+    rest = np.setdiff1d(np.arange(d), out)[: d_hi - out.size]
+    return np.sort(np.concatenate([out, rest]))
 
 
 def kv_keys_chunk(head: int, start: int, rows: int, d: int, seed: int,
