@@ -22,6 +22,10 @@ Readings taken where the paper is silent (each listed in the design notes):
   * gamma is the residual norm of the unit-normalised vector;
   * the packed layout is groups of 32 coordinates stored as bit planes.
 
+The split into two instances over the channels (Sec. 4.3) is a composition
+of the functions above and nothing else; its bookkeeping is pinned by the
+per-instance distortion and variance it must show (tests/test_oracle_quant.py).
+
 Pinned by tests/test_oracle_*.py (closed forms, the paper's printed values,
 brute force).  The only part with no external pin is the exact index vector
 of one particular input under one particular Pi ("parity unpinned" for that

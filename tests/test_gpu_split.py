@@ -198,3 +198,57 @@ def test_split_end_to_end_statistics():
     assert abs(np.sum(err * exact) / np.sum(exact * exact)) < 0.01
     # the formula is an expectation over S; one fixed 64 x 64 draw sits within ~10 % of it
     assert abs(np.mean(err ** 2) / np.mean(var) - 1) < 0.12
+
+
+def test_c3m_full_size():
+    """The 2.5-bit decode configuration at its full size, in the launch shapes bench_kernels times:
+    524288 bf16 keys of 8 heads quantised as two instances (64 + 64 channels), 4 queries per head."""
+    cfg = W.CONFIGS["C3m"]
+    d_hi, bits_lo = cfg.d_hi, cfg.bits_mse
+    hi_ch = W.kv_hi_channels(cfg.n_groups, D, cfg.seed_x, d_hi)
+    g_hi, g_lo = W.gaussian_matrix(d_hi, cfg.seed_pi), W.gaussian_matrix(D - d_hi, cfg.seed_pi + 1)
+    s_hi, s_lo = W.sketch_matrix(d_hi, cfg.seed_s), W.sketch_matrix(D - d_hi, cfg.seed_s + 1)
+    inst = []
+    for dd, g, s_, b in ((d_hi, g_hi, s_hi, bits_lo + 1), (D - d_hi, g_lo, s_lo, bits_lo)):
+        c32, t32, _ = o.codebook_fp32(dd, b)
+        inst.append(dict(Pi=o.rotation_from_gaussian(g), S=s_, c32=c32, t32=t32, d=dd, bits=b))
+    ihi, ilo = inst
+    p = tq.make_mixed_params(D, hi_ch, bits_lo + 1, bits_lo, g_hi, g_lo, s_hi, s_lo)
+    keys = W.kv_keys(cfg.n_groups, cfg.n, D, cfg.seed_x).reshape(-1, D)
+    n = keys.shape[0]
+    q = W.gaussian_queries(cfg.nq, D, cfg.seed_q, unit=False)
+    idx = torch.zeros((n, p.idx_words), dtype=torch.int32, device=DEV)
+    qjl = torch.zeros((n, p.qjl_words), dtype=torch.int32, device=DEV)
+    gamma = torch.zeros((n, 2), dtype=torch.float32, device=DEV)
+    norm = torch.zeros((n, 2), dtype=torch.float32, device=DEV)
+    p.reserve(n, cfg.nq, 0)
+    tq.tq_quantize_prod(p, torch.from_numpy(keys.view(np.int16)).view(torch.bfloat16).to(DEV), idx, qjl, gamma, norm)
+    scores = torch.zeros((cfg.nq, cfg.n), dtype=torch.float32, device=DEV)
+    tq.tq_score(p, dev(q), cfg.n_groups, cfg.q_per_group, idx, qjl, gamma, norm, cfg.n, scores)
+    got_hi, got_lo = unpack_split(p, words(idx), d_hi)
+    z = o.unpack_signs(words(qjl), D)
+    g_np, nu_np, s_gpu = gamma.cpu().numpy(), norm.cpu().numpy(), scores.cpu().numpy()
+    hi, lo = o.split_channels(D, hi_ch)
+    # quantisation against the oracle on a sample of rows from every head
+    sample = np.unique(np.concatenate([np.arange(0, 2000), np.arange(n - 2000, n),
+                                       np.random.default_rng(5).integers(0, n, size=6000)]))
+    x_or = o.bf16_bits_to_f64(keys[sample])
+    for part, (ch, it, got) in enumerate(((hi, ihi, got_hi), (lo, ilo, got_lo))):
+        xh, nu = o.unit_normalise(x_or[:, ch], True)
+        y = o.rotate(xh, it["Pi"])
+        P.check_indices(got[sample], o.nearest_centroid(y, it["t32"]), y, it["t32"])
+        P.check_close(nu_np[sample, part], nu, 0.0, "C3m norm", rel=3e-6)
+        _, gamma_or, u_or = o.residual_and_sketch(xh, got[sample], it["Pi"], it["S"], it["c32"])
+        P.check_close(g_np[sample, part], gamma_or, 0.0, "C3m gamma", rel=1e-5)
+        zp = z[sample][:, :d_hi] if part == 0 else z[sample][:, d_hi:]
+        P.check_signs(zp, u_or, np.linalg.norm(it["S"].astype(np.float64), axis=1)[None, :] * gamma_or[:, None])
+    # scores of every head against the oracle's estimate from the GPU's own codes
+    q64 = q.astype(np.float64)
+    qs_n = np.stack([np.linalg.norm(q64[:, hi], axis=1), np.linalg.norm(q64[:, lo], axis=1)], axis=1)
+    for g in range(cfg.n_groups):
+        rows = slice(g * cfg.n, (g + 1) * cfg.n)
+        rh = dict(idx=got_hi[rows], qjl=z[rows][:, :d_hi], gamma=g_np[rows, 0], norm=nu_np[rows, 0])
+        rl = dict(idx=got_lo[rows], qjl=z[rows][:, d_hi:], gamma=g_np[rows, 1], norm=nu_np[rows, 1])
+        xt = o.dequant_split(D, hi_ch, rh, rl, ihi, ilo, True)
+        qsl = slice(g * cfg.q_per_group, (g + 1) * cfg.q_per_group)
+        P.check_close(s_gpu[qsl], o.score(q[qsl], xt), qs_n[qsl] @ nu_np[rows].T, f"C3m logits, head {g}")
