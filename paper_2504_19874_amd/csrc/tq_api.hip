@@ -326,7 +326,10 @@ tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_gr
       return TQ_ERR_HIP;
     return TQ_OK;
   }
-  const bool small_i8 = q_per_group <= 32 && score_i8_applicable(p->bits_mse, d, make_codebook(p));
+  // few queries per code; with a short code list also a few more (every block of 4 queries re-reads the
+  // codes, which costs less than the launches of the contraction path while the list is short)
+  const bool small_i8 = (q_per_group <= 32 || (q_per_group <= 64 && n_per_group <= 16384)) &&
+                        score_i8_applicable(p->bits_mse, d, make_codebook(p));
   if (small_i8) {
     // few queries per code: masked sums of fixed-point query digits on the int8 matrix cores;
     // its own preparation kernel rotates the queries and writes their digit images
