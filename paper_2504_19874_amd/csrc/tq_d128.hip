@@ -480,6 +480,10 @@ hipError_t launch_dequant128(int bits, bool prod, const uint32_t* idx, const uin
                              int gs_hi, float kappa_hi, const Codebook& cb_hi, hipStream_t s) {
   if (n == 0) return hipSuccess;
   if (gs_hi < 0 || gs_hi > 3 || (gs_hi > 0 && (cb_hi.bits != bits + 1 || norm == nullptr))) return hipErrorInvalidValue;
+  // a few blocks of 32 vectors: one workgroup per block is the shorter chain (tq_d128_small_dq.hip)
+  if (n <= kSmallDequantRows)
+    return launch_dequant128_small(bits, prod, idx, qjl, gamma, norm, Pi, S, out, ldo, n, kappa, cb, gs_hi, kappa_hi,
+                                   cb_hi, s);
   Dequant128Args a;
   a.idx = idx; a.qjl = qjl; a.gamma = gamma; a.norm = norm; a.Pi = Pi; a.S = S; a.out = out; a.ldo = ldo;
   a.n = n; a.kappa = kappa; a.cb = cb; a.gs_hi = gs_hi; a.kappa_hi = kappa_hi; a.cb_hi = cb_hi;

@@ -68,11 +68,16 @@ hipError_t launch_quant128(int bits, bool prod, bool bf16, const void* X, int64_
                            const float* Pi, const float* SPiT, uint32_t* idx, uint32_t* qjl, float* gamma,
                            float* norm, const Codebook& cb, hipStream_t s);
 // d = 128, few vectors: one workgroup per block of 32 (tq_d128_small.hip)
-constexpr int64_t kSmallQuantRows = 32768;
+constexpr int64_t kSmallQuantRows = 24576;
 hipError_t launch_quant128_small(int bits, bool prod, bool bf16, const void* X, int64_t ldx, int64_t n,
                                  const float* Pi, const float* SPiT, uint32_t* idx, uint32_t* qjl,
                                  float* gamma, float* norm, const Codebook& cb, int gs_hi,
                                  const Codebook& cb_hi, hipStream_t s);
+hipError_t launch_dequant128_small(int bits, bool prod, const uint32_t* idx, const uint32_t* qjl,
+                                   const float* gamma, const float* norm, const float* Pi, const float* S,
+                                   float* out, int64_t ldo, int64_t n, float kappa, const Codebook& cb,
+                                   int gs_hi, float kappa_hi, const Codebook& cb_hi, hipStream_t s);
+constexpr int64_t kSmallDequantRows = 24576;
 hipError_t launch_dequant128(int bits, bool prod, const uint32_t* idx, const uint32_t* qjl,
                              const float* gamma, const float* norm, const float* Pi, const float* S,
                              float* out, int64_t ldo, int64_t n, float kappa, const Codebook& cb,
