@@ -91,19 +91,19 @@ tq_status quantize_common(const tq_params* p, const void* x, tq_dtype dtype, int
   const int words_per_row = (d / 32) * p->bits_mse;
 
   if (p->d_hi != 0) {
-    // two instances: the workgroup-per-block kernel at d = 128; both norms are always stored
+    // two instances: the d = 128 kernels; both norms are always stored
     if (norm == nullptr) return TQ_ERR_INVALID_ARG;
     if (!aligned16(x) || (ldx * esz) % 16 != 0) return TQ_ERR_UNSUPPORTED;
-    return from_hip(launch_quant128_small(p->bits_mse, prod, dtype == TQ_BF16, x, ldx, n, p->Pi,
-                                          prod ? p->SPiT : nullptr, idx, qjl, gamma, norm, make_codebook(p),
-                                          p->d_hi / 32, make_codebook_hi(p), stream));
+    return from_hip(launch_quant128(p->bits_mse, prod, dtype == TQ_BF16, x, ldx, n, p->Pi,
+                                    prod ? p->SPiT : nullptr, idx, qjl, gamma, norm, make_codebook(p),
+                                    p->d_hi / 32, make_codebook_hi(p), stream));
   }
 
   // head dimension 128: one fused kernel, parameters resident in LDS
   if (d == 128 && aligned16(x) && (ldx * esz) % 16 == 0) {
     return from_hip(launch_quant128(p->bits_mse, prod, dtype == TQ_BF16, x, ldx, n, p->Pi,
-                                    prod ? p->SPiT : nullptr, idx, qjl, gamma, norm, make_codebook(p),
-                                    stream));
+                                    prod ? p->SPiT : nullptr, idx, qjl, gamma, norm, make_codebook(p), 0,
+                                    make_codebook(p), stream));
   }
 
   GemmArgs a;

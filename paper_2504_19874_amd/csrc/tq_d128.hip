@@ -19,11 +19,9 @@
 //   Pi / S as the B operand, read 16 bytes per lane so that the four output
 //   tiles interleave columns 4l..4l+3: every output row is stored as one
 //   contiguous 512-byte line.
-#include "tq_internal.h"
+#include "tq_d128_tile.h"
 
 namespace tq {
-
-typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int D = 128;
 constexpr int PAD_LD = 132;  // padded row stride for 16-byte reads along k
@@ -40,9 +38,14 @@ struct Quant128Args {
   float* norm;
   int normalise;
   Codebook cb;
+  // two instances over a split of the rotated coordinates (MIXED, Sec. 4.3): coordinate groups
+  // (= output tiles) [0, gs_hi) are quantised with BITS + 1 bits and cb_hi, each instance
+  // normalised by the norm of its own rotated coordinates
+  int gs_hi;
+  Codebook cb_hi;
 };
 
-template <int BITS, bool PROD, bool BF16IN>
+template <int BITS, bool PROD, bool BF16IN, bool MIXED>
 __global__ __launch_bounds__(512) void quant128_kernel(const Quant128Args a) {
   extern __shared__ __attribute__((aligned(16))) float smem[];
   float* Pi_s = smem;
@@ -102,7 +105,7 @@ __global__ __launch_bounds__(512) void quant128_kernel(const Quant128Args a) {
       }
     }
     float inv = 1.f, nu = 1.f;
-    if (a.normalise) {
+    if (!MIXED && a.normalise) {
       float s0 = 0.f, s1 = 0.f;
 #pragma unroll
       for (int k = 0; k < 64; k += 2) {
@@ -148,11 +151,51 @@ __global__ __launch_bounds__(512) void quant128_kernel(const Quant128Args a) {
     // the next block's rows travel from HBM while this block is finished
     if (blk + blk_stride < n_blocks) load_raw(blk + blk_stride);
 
+    float g2 = 0.f, g2_hi = 0.f;
+    if (MIXED) {
+      // norms of the two instances from the rotated coordinates, then tile by tile with the
+      // instance's own codebook and bit count
+      const int gs = a.gs_hi;
+      float s_hi = 0.f, s_lo = 0.f;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+          s0 = fmaf(acc[t][r], acc[t][r], s0);
+          s1 = fmaf(acc[t][r + 1], acc[t][r + 1], s1);
+        }
+        const float ts = s0 + s1;
+        s_hi += t < gs ? ts : 0.f;
+        s_lo += t < gs ? 0.f : ts;
+      }
+      s_hi += __shfl_xor(s_hi, 32);
+      s_lo += __shfl_xor(s_lo, 32);
+      const float nu_hi = sqrtf(s_hi), nu_lo = sqrtf(s_lo);
+      const float inv_hi = nu_hi > 0.f ? 1.f / nu_hi : 0.f, inv_lo = nu_lo > 0.f ? 1.f / nu_lo : 0.f;
+      const int wpr = 4 * BITS + gs;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        uint32_t wd[4] = {0u, 0u, 0u, 0u};
+        const bool thi = t < gs;  // uniform
+        if (thi) g2_hi += quantise_tile<(BITS < 4 ? BITS + 1 : 4)>(acc[t], inv_hi, a.cb_hi, h, wd);
+        else g2 += quantise_tile<BITS>(acc[t], inv_lo, a.cb, h, wd);
+        // both half-waves hold the merged words; half t / 2 stores them
+        if (valid && h == (t >> 1)) {
+          uint32_t* dst = a.idx + i * wpr + (thi ? t * (BITS + 1) : gs * (BITS + 1) + (t - gs) * BITS);
+#pragma unroll
+          for (int pl = 0; pl < BITS + 1; ++pl)
+            if (pl < BITS || thi) dst[pl] = wd[pl];
+        }
+      }
+      if (valid && h == 0) {
+        a.norm[2 * i] = nu_hi;
+        a.norm[2 * i + 1] = nu_lo;
+      }
+    } else {
     // nearest centroid, packing, residual (in place).  Bit p of the bucket number is the XOR
     // of the compare masks at positions k = 2^p - 1 (mod 2^p); a 4-bit nibble of a plane is
     // built by shift-and-add-carry, most significant element first.
-    float g2 = 0.f;
-    uint32_t word[4][BITS > 0 ? BITS : 1];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       uint32_t nib[4][BITS > 0 ? BITS : 1];
@@ -188,23 +231,18 @@ __global__ __launch_bounds__(512) void quant128_kernel(const Quant128Args a) {
       }
 #pragma unroll
       for (int pl = 0; pl < BITS; ++pl) {
-        const uint32_t w = (nib[0][pl] | (nib[1][pl] << 8) | (nib[2][pl] << 16) | (nib[3][pl] << 24)) << (4 * h);
-        word[t][pl] = w | (uint32_t)__shfl_xor((int)w, 32);
-      }
-    }
-    // half h stores the words of coordinate groups 2h and 2h+1
-    if (BITS > 0 && valid) {
-      uint32_t* dst = a.idx + i * (4 * BITS) + 2 * h * BITS;
-#pragma unroll
-      for (int pl = 0; pl < BITS; ++pl) {
-        dst[pl] = h ? word[2][pl] : word[0][pl];
-        dst[BITS + pl] = h ? word[3][pl] : word[1][pl];
+        uint32_t w = (nib[0][pl] | (nib[1][pl] << 8) | (nib[2][pl] << 16) | (nib[3][pl] << 24)) << (4 * h);
+        w |= (uint32_t)__shfl_xor((int)w, 32);
+        // both half-waves hold the merged word; half t / 2 stores it (coordinate group t)
+        if (valid && h == (t >> 1)) a.idx[i * (4 * BITS) + t * BITS + pl] = w;
       }
     }
     if (valid && h == 0 && a.norm != nullptr) a.norm[i] = nu;
 
+    }
     if (PROD) {
       g2 += __shfl_xor(g2, 32);
+      if (MIXED) g2_hi += __shfl_xor(g2_hi, 32);
       floatx16 u[4];
       // register 4*ke + r of tile te holds e_j with j = 32 te + 8 ke + 4 h + r
       {
@@ -255,7 +293,14 @@ __global__ __launch_bounds__(512) void quant128_kernel(const Quant128Args a) {
         uint32_t* dst = a.qjl + i * 4 + 2 * h;
         dst[0] = h ? sw[2] : sw[0];
         dst[1] = h ? sw[3] : sw[1];
-        if (h == 0) a.gamma[i] = sqrtf(g2);
+        if (h == 0) {
+          if (MIXED) {
+            a.gamma[2 * i] = sqrtf(g2_hi);
+            a.gamma[2 * i + 1] = sqrtf(g2);
+          } else {
+            a.gamma[i] = sqrtf(g2);
+          }
+        }
       }
     }
   }
@@ -410,37 +455,47 @@ static int grid_128(int64_t n) {
   return (int)(g < 1 ? 1 : g);
 }
 
-template <int BITS, bool PROD, bool BF16IN>
+template <int BITS, bool PROD, bool BF16IN, bool MIXED>
 static hipError_t launch_q(const Quant128Args& a, hipStream_t s) {
   const size_t smem = (size_t)(PROD ? 2 : 1) * D * PAD_LD * sizeof(float);
   static bool attr_done = false;  // per instantiation
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant128_kernel<BITS, PROD, BF16IN>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant128_kernel<BITS, PROD, BF16IN, MIXED>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL((quant128_kernel<BITS, PROD, BF16IN>), dim3(grid_128(a.n)), dim3(512), smem, s, a);
+  hipLaunchKernelGGL((quant128_kernel<BITS, PROD, BF16IN, MIXED>), dim3(grid_128(a.n)), dim3(512), smem, s, a);
   return hipGetLastError();
+}
+
+template <int BITS, bool MIXED>
+static hipError_t launch_q_in(const Quant128Args& a, bool prod, bool bf16, hipStream_t s) {
+  if (prod) return bf16 ? launch_q<BITS, true, true, MIXED>(a, s) : launch_q<BITS, true, false, MIXED>(a, s);
+  return bf16 ? launch_q<BITS, false, true, MIXED>(a, s) : launch_q<BITS, false, false, MIXED>(a, s);
 }
 
 template <int BITS>
 static hipError_t launch_q_bits(const Quant128Args& a, bool prod, bool bf16, hipStream_t s) {
-  if (prod) return bf16 ? launch_q<BITS, true, true>(a, s) : launch_q<BITS, true, false>(a, s);
-  return bf16 ? launch_q<BITS, false, true>(a, s) : launch_q<BITS, false, false>(a, s);
+  if (a.gs_hi > 0) {
+    if (BITS >= 4) return hipErrorInvalidValue;
+    return launch_q_in<(BITS < 4 ? BITS : 0), true>(a, prod, bf16, s);
+  }
+  return launch_q_in<BITS, false>(a, prod, bf16, s);
 }
 
 hipError_t launch_quant128(int bits, bool prod, bool bf16, const void* X, int64_t ldx, int64_t n,
                            const float* Pi, const float* SPiT, uint32_t* idx, uint32_t* qjl, float* gamma,
-                           float* norm, const Codebook& cb, hipStream_t s) {
+                           float* norm, const Codebook& cb, int gs_hi, const Codebook& cb_hi, hipStream_t s) {
   if (n == 0) return hipSuccess;
+  if (gs_hi < 0 || gs_hi > 3 || (gs_hi > 0 && (cb_hi.bits != bits + 1 || norm == nullptr))) return hipErrorInvalidValue;
   // up to about one block of 32 vectors per wavefront slot of the chip, a workgroup per block
   // (tq_d128_small.hip) is the shorter chain; beyond that the streaming kernel below wins
   if (n <= kSmallQuantRows)
-    return launch_quant128_small(bits, prod, bf16, X, ldx, n, Pi, SPiT, idx, qjl, gamma, norm, cb, 0, cb, s);
+    return launch_quant128_small(bits, prod, bf16, X, ldx, n, Pi, SPiT, idx, qjl, gamma, norm, cb, gs_hi, cb_hi, s);
   Quant128Args a;
   a.X = X; a.ldx = ldx; a.n = n; a.Pi = Pi; a.SPiT = SPiT; a.idx = idx; a.qjl = qjl; a.gamma = gamma;
-  a.norm = norm; a.normalise = norm != nullptr; a.cb = cb;
+  a.norm = norm; a.normalise = norm != nullptr; a.cb = cb; a.gs_hi = gs_hi; a.cb_hi = cb_hi;
   switch (bits) {
     case 0: return launch_q_bits<0>(a, prod, bf16, s);
     case 1: return launch_q_bits<1>(a, prod, bf16, s);

@@ -1,0 +1,57 @@
+// The per-tile decision step shared by the d = 128 quantisation kernels.
+#pragma once
+#include "tq_internal.h"
+
+namespace tq {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// One output tile (32 coordinates x 32 vectors, 16 coordinates per lane) through the decision
+// of Alg. 1: nearest centroid, packing, residual (in place).  Bit p of the bucket number is the
+// XOR of the compare masks at positions k = 2^p - 1 (mod 2^p); a 4-bit nibble of a plane is
+// built by shift-and-add-carry, most significant element first.  Returns the lane's share of
+// the squared residual norm; word[p] is the finished plane word (both half-waves merged).
+template <int B>
+__device__ __forceinline__ float quantise_tile(floatx16& acc, const float inv, const Codebook& cb, const int h,
+                                               uint32_t (&word)[4]) {
+  float g2 = 0.f;
+  uint32_t nib[4][B > 0 ? B : 1];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+#pragma unroll
+    for (int pl = 0; pl < (B > 0 ? B : 1); ++pl) nib[k][pl] = 0u;
+#pragma unroll
+    for (int r = 3; r >= 0; --r) {
+      const float y = acc[4 * k + r] * inv;
+      float yt = cb.c[0];
+      bool bit[B > 0 ? B : 1];
+#pragma unroll
+      for (int pl = 0; pl < (B > 0 ? B : 1); ++pl) bit[pl] = false;
+#pragma unroll
+      for (int j = 0; j < (1 << B) - 1; ++j) {
+        const bool ge = y >= cb.t[j];
+        yt = ge ? cb.c[j + 1] : yt;
+#pragma unroll
+        for (int pl = 0; pl < B; ++pl)
+          if ((j & ((1 << pl) - 1)) == (1 << pl) - 1) bit[pl] = bit[pl] != ge;
+      }
+      float e = y - yt;
+      asm volatile("" : "+v"(e));  // keep the residual here: sunk later it would need the masks again
+      g2 = fmaf(e, e, g2);
+      acc[4 * k + r] = e;
+#pragma unroll
+      for (int pl = 0; pl < B; ++pl) {
+        nib[k][pl] = nib[k][pl] + nib[k][pl] + (bit[pl] ? 1u : 0u);
+        asm volatile("" : "+v"(nib[k][pl]));  // consume this element's masks now (scalar registers)
+      }
+    }
+  }
+#pragma unroll
+  for (int pl = 0; pl < B; ++pl) {
+    const uint32_t w = (nib[0][pl] | (nib[1][pl] << 8) | (nib[2][pl] << 16) | (nib[3][pl] << 24)) << (4 * h);
+    word[pl] = w | (uint32_t)__shfl_xor((int)w, 32);
+  }
+  return g2;
+}
+
+}  // namespace tq

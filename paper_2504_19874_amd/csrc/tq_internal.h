@@ -66,7 +66,7 @@ hipError_t launch_gemm(NKind nk, EKind ek, int bits, const GemmArgs& a, int n_gr
 // d = 128 fused kernels (tq_d128.hip)
 hipError_t launch_quant128(int bits, bool prod, bool bf16, const void* X, int64_t ldx, int64_t n,
                            const float* Pi, const float* SPiT, uint32_t* idx, uint32_t* qjl, float* gamma,
-                           float* norm, const Codebook& cb, hipStream_t s);
+                           float* norm, const Codebook& cb, int gs_hi, const Codebook& cb_hi, hipStream_t s);
 // d = 128, few vectors: one workgroup per block of 32 (tq_d128_small.hip)
 constexpr int64_t kSmallQuantRows = 24576;
 hipError_t launch_quant128_small(int bits, bool prod, bool bf16, const void* X, int64_t ldx, int64_t n,
