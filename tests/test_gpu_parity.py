@@ -131,6 +131,8 @@ def _quant_inputs(n, d, kind, seed):
     (128, 2, 4096, "unit"), (128, 1, 300, "f32"), (128, 3, 129, "bf16"), (128, 4, 1, "f32"),
     (256, 4, 515, "unit"), (96, 2, 257, "f32"), (1536, 4, 300, "unit"), (3072, 1, 140, "bf16"),
     (64, 0, 40, "f32"),
+    # d = 128 above the small-batch threshold: the streaming kernel
+    (128, 1, 30000, "f32"), (128, 4, 25000, "unit"), (128, 3, 40000, "bf16"),
 ])
 def test_quantize_mse(d, bits, n, kind):
     p, Pi, _, c32, t32 = setup(d, bits, False)
@@ -177,6 +179,8 @@ def _check_prod(p, Pi, S, c32, t32, x_or, normalise, idx, qjl, gamma, norm):
 @pytest.mark.parametrize("d,bits_mse,n,kind", [
     (128, 2, 2000, "bf16"), (128, 3, 129, "f32"), (128, 1, 4096, "unit"), (128, 0, 100, "f32"),
     (256, 2, 300, "unit"), (1536, 1, 200, "unit"), (96, 4, 130, "f32"),
+    # d = 128 above the small-batch threshold: the streaming kernel
+    (128, 0, 26000, "f32"), (128, 1, 33000, "unit"), (128, 4, 25001, "bf16"),
 ])
 def test_quantize_prod(d, bits_mse, n, kind):
     p, Pi, S, c32, t32 = setup(d, bits_mse, True)
@@ -231,6 +235,8 @@ def test_empty_and_error_paths():
 @pytest.mark.parametrize("d,bits_mse,n,prod,with_norm", [
     (128, 2, 1000, True, True), (128, 4, 129, False, False), (256, 3, 260, True, False),
     (1536, 4, 150, False, True), (128, 0, 64, True, True), (96, 1, 131, True, True),
+    # d = 128 above the small-batch threshold: the streaming kernel
+    (128, 2, 30000, True, True), (128, 3, 25000, False, False), (128, 0, 26001, True, True), (128, 4, 24600, False, True),
 ])
 def test_dequantize(d, bits_mse, n, prod, with_norm):
     p, Pi, S, c32, t32 = setup(d, bits_mse, prod)
