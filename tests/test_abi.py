@@ -90,6 +90,23 @@ def test_entry_points_validate_before_launching(lib):
     assert lib.tq_stage_sign_pack(100, None, 1, None, None) == 2
     assert lib.tq_workspace_bytes(C.byref(p), 1000, 10, 0) >= 1000 * 128 * 4 + 2 * 10 * 128 * 4
     assert lib.tq_derive_params(128, None, None, None, None, None, None) == 1
+    # two instances over a channel split: what is malformed, and what the kernels do not cover
+    c_hi = np.zeros(8, dtype=np.float32)
+    t_hi = np.zeros(7, dtype=np.float32)
+    p.d_hi, p.bits_mse_hi = 48, 3  # not a multiple of 32
+    p.centroids_hi, p.bounds_hi = c_hi.ctypes.data, t_hi.ctypes.data
+    assert lib.tq_quantize_mse(C.byref(p), None, 0, 4, 128, None, None, None) == 1
+    p.d_hi = 128  # no channel left for the other instance
+    assert lib.tq_quantize_mse(C.byref(p), None, 0, 4, 128, None, None, None) == 1
+    p.d_hi, p.centroids_hi = 32, None
+    assert lib.tq_quantize_mse(C.byref(p), None, 0, 4, 128, None, None, None) == 1
+    p.centroids_hi, p.bits_mse_hi = c_hi.ctypes.data, 2  # the outlier instance must have one more bit
+    assert lib.tq_quantize_mse(C.byref(p), None, 0, 4, 128, None, None, None) == 2
+    p.bits_mse_hi, p.d, p.d_hi = 3, 256, 64  # head dimension 128 only
+    assert lib.tq_quantize_mse(C.byref(p), None, 0, 4, 256, None, None, None) == 2
+    p.d, p.d_hi = 128, 64
+    assert lib.tq_quantize_mse(C.byref(p), None, 0, 0, 128, None, None, None) == 0   # valid and empty
+    assert lib.tq_stage_pack(C.byref(p), None, 4, None, None) == 2                   # stages know one instance
 
 
 def test_rotation_helper_agrees_with_oracle_reading():
