@@ -317,7 +317,7 @@ tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_gr
       scores = static_cast<float*>(ws.take((size_t)nq * ld_scores * sizeof(float)));
       if (scores == nullptr) return TQ_ERR_WORKSPACE;
     }
-    if (launch_score_i8_split(p->bits_mse, prod, p->Pi, p->S, q, ldq, img, idx, qjl, gamma, norm, scores, ld_scores,
+    if (launch_score_i8_split(p->bits_mse, prod, p->Pi, p->S, p->PiT, p->ST, q, ldq, img, idx, qjl, gamma, norm, scores, ld_scores,
                               n_per_group, n_groups, q_per_group, p->d_hi / 32, kappa_of(d - p->d_hi),
                               kappa_of(p->d_hi), make_codebook(p), make_codebook_hi(p), s) != hipSuccess)
       return TQ_ERR_HIP;
@@ -331,8 +331,8 @@ tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_gr
   const bool small_i8 = (q_per_group <= 32 || (q_per_group <= 64 && n_per_group <= 16384)) &&
                         score_i8_applicable(p->bits_mse, d, make_codebook(p));
   if (small_i8) {
-    // few queries per code: masked sums of fixed-point query digits on the int8 matrix cores;
-    // its own preparation kernel rotates the queries and writes their digit images
+    // few queries per code: masked sums of fixed-point query digits on the int8 matrix cores (at
+    // d = 128 one kernel; otherwise a preparation kernel rotates the queries and writes their digits)
     void* img = ws.take(score_i8_workspace_bytes(d, nq));
     if (img == nullptr) return TQ_ERR_WORKSPACE;
     if (scores == nullptr) {

@@ -96,7 +96,8 @@ size_t score_i8_workspace_bytes(int d, int64_t nq);
 bool score_i8_applicable(int bits, int d, const Codebook& cb);
 // d = 128 split into two instances (tq_score_i8_split.hip)
 bool score_i8_split_applicable(int bits_lo, const Codebook& cb_lo, const Codebook& cb_hi);
-hipError_t launch_score_i8_split(int bits_lo, bool prod, const float* Pi, const float* S, const float* q, int64_t ldq,
+hipError_t launch_score_i8_split(int bits_lo, bool prod, const float* Pi, const float* S, const float* PiT,
+                                 const float* ST, const float* q, int64_t ldq,
                                  void* workspace, const uint32_t* idx, const uint32_t* qjl, const float* gamma,
                                  const float* norm, float* scores, int64_t lds, int64_t n, int n_groups,
                                  int q_per_group, int gs_hi, float kappa_lo, float kappa_hi, const Codebook& cb_lo,

@@ -22,7 +22,7 @@
 // Workgroup = 512 threads = 8 wavefronts; a wavefront owns 256 consecutive keys
 // = 16 tiles of 16, staged ROUND tiles at a time.  grid = (ceil(n / 2048),
 // groups, ceil(queries per group / 4)).
-#include "tq_score_i8.h"
+#include "tq_score_i8_prep.h"
 
 #include <type_traits>
 
@@ -36,33 +36,6 @@ constexpr int TILES_128 = 16;  // tiles per wavefront
 __host__ __device__ constexpr int round_tiles(int bits) { return bits <= 3 ? 8 : 4; }
 // bytes of one wavefront's staging region: idx, qjl, gamma, norm of 16 * round_tiles rows
 __host__ __device__ constexpr int stage_bytes(int bits) { return 16 * round_tiles(bits) * (16 * bits + 16 + 4 + 4); }
-constexpr int PREP_BYTES = 2 * 2 * 4 * 128 * 4 + 2 * 4 * 4 * 128 + 2 * 4 * 2 * 4;  // partial sums, digits, scalars
-
-// max / sum over the 64 lanes: four DPP steps inside each row of 16, then the four rows
-// through scalar registers
-template <int CTRL>
-__device__ __forceinline__ int dpp_move(int v) {
-  return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xF, 0xF, false);
-}
-__device__ __forceinline__ float wave_max(float v) {
-  v = fmaxf(v, __int_as_float(dpp_move<0xB1>(__float_as_int(v))));   // quad_perm [1,0,3,2]
-  v = fmaxf(v, __int_as_float(dpp_move<0x4E>(__float_as_int(v))));   // quad_perm [2,3,0,1]
-  v = fmaxf(v, __int_as_float(dpp_move<0x141>(__float_as_int(v))));  // row_half_mirror
-  v = fmaxf(v, __int_as_float(dpp_move<0x140>(__float_as_int(v))));  // row_mirror
-  const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
-  const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
-  const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
-  const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
-  return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
-}
-__device__ __forceinline__ int wave_sum(int v) {
-  v += dpp_move<0xB1>(v);
-  v += dpp_move<0x4E>(v);
-  v += dpp_move<0x141>(v);
-  v += dpp_move<0x140>(v);
-  return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) + __builtin_amdgcn_readlane(v, 32) +
-         __builtin_amdgcn_readlane(v, 48);
-}
 
 template <int BITS, bool PROD>
 __global__ __launch_bounds__(512) void score_i8_128_kernel(const ScoreI8Args a) {
@@ -91,18 +64,11 @@ __global__ __launch_bounds__(512) void score_i8_128_kernel(const ScoreI8Args a) 
   unsigned char* const stage = dyn_s + wave * stage_bytes(BITS);
   float* const part_s = reinterpret_cast<float*>(dyn_s + 8 * stage_bytes(BITS));        // [2][2][4][128]
   signed char* const dig_s = reinterpret_cast<signed char*>(part_s + 2 * 2 * 4 * 128);  // [2][4][4][128]
-  float* const scal_s = reinterpret_cast<float*>(dig_s + 2 * 4 * 4 * 128);              // [2][4][2]
+  float* const scal_s = reinterpret_cast<float*>(dig_s + 2 * 4 * 4 * 128);              // [2][4][4]
 
   // ---- 1. this thread's column of the transposed matrix: 64 values of k ---------------------
-  // wavefront w: matrix w / 4, half (w / 2) % 2 of k, columns j = tid % 128
-  float wv[64];
-  const int p_mat = wave >> 2, p_kh = (wave >> 1) & 1, p_j = tid & 127;
-  const bool p_work = p_mat == 0 ? BITS > 0 : PROD;  // uniform
-  if (p_work) {
-    const float* WT = (p_mat ? a.ST : a.PiT) + (64 * p_kh) * 128 + p_j;
-#pragma unroll
-    for (int k = 0; k < 64; ++k) wv[k] = WT[k * 128];
-  }
+  I8Prep<(BITS > 0), PROD> prep;
+  prep.load(a, wave, tid);
 
   // ---- 2. the codes of this wavefront's keys, as contiguous 16-byte pieces ---------------------
   // Pieces past the end of the arrays are clamped onto the last one (never used: the
@@ -154,62 +120,10 @@ __global__ __launch_bounds__(512) void score_i8_128_kernel(const ScoreI8Args a) 
     }
   }
 
-  // ---- 4. rotate / sketch this workgroup's four queries --------------------------------------
-  if (p_work) {
-    const float* xq[4];  // uniform addresses: the query coordinates arrive in scalar registers
-#pragma unroll
-    for (int qi = 0; qi < 4; ++qi) {
-      const int64_t r = (int64_t)group * a.q_per_group + (q0 + qi < a.q_per_group ? q0 + qi : q0);
-      xq[qi] = a.x + r * a.ldx + 64 * p_kh;
-    }
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int k = 0; k < 64; ++k)
-#pragma unroll
-      for (int qi = 0; qi < 4; ++qi) acc[qi] = fmaf(wv[k], xq[qi][k], acc[qi]);
-#pragma unroll
-    for (int qi = 0; qi < 4; ++qi) part_s[((p_mat * 2 + p_kh) * 4 + qi) * 128 + p_j] = acc[qi];
-  }
+  // ---- 4. rotate / sketch this workgroup's four queries, 5. fixed point --------------------------
+  prep.matvec(a, group, q0, part_s);
   __syncthreads();
-
-  // ---- 5. fixed point: wavefront w digitises (matrix w / 4, query w % 4) ---------------------
-  {
-    const int mat = wave >> 2, qi = wave & 3;
-    if (mat == 0 ? BITS > 0 : PROD) {
-      const bool live = q0 + qi < a.q_per_group;
-      float y[2];
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const int j = lane + 64 * u;
-        y[u] = live ? part_s[((mat * 2 + 0) * 4 + qi) * 128 + j] + part_s[((mat * 2 + 1) * 4 + qi) * 128 + j] : 0.f;
-      }
-      const float mx = wave_max(fmaxf(fabsf(y[0]), fabsf(y[1])));
-      int e = 0;
-      if (mx > 0.f) (void)frexpf(mx, &e);  // mx = f * 2^e, f in [0.5, 1): |Q| <= 2^19
-      const float sc = ldexpf(1.f, 19 - e);
-      int Q[2];
-      Q[0] = __float2int_rn(y[0] * sc);
-      Q[1] = __float2int_rn(y[1] * sc);
-      const int tot = wave_sum(Q[0] + Q[1]);
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        // balanced base 128: D0, D1 in [-64, 63], D2 in [-64, 64]
-        const int d0 = ((Q[u] + 64) & 127) - 64;
-        const int Q1 = (Q[u] - d0) >> 7;
-        const int d1 = ((Q1 + 64) & 127) - 64;
-        const int d2 = (Q1 - d1) >> 7;
-        signed char* o = dig_s + (mat * 4 + qi) * 4 * 128 + lane + 64 * u;
-        o[0] = (signed char)d0;
-        o[128] = (signed char)d1;
-        o[256] = (signed char)d2;
-        o[384] = 0;
-      }
-      if (lane == 0) {
-        scal_s[(mat * 4 + qi) * 2 + 0] = ldexpf(1.f, e - 19);
-        scal_s[(mat * 4 + qi) * 2 + 1] = (float)tot * ldexpf(1.f, e - 19);
-      }
-    }
-  }
+  prep.digitise(a, q0, wave, lane, 0, part_s, dig_s, scal_s);
   __syncthreads();  // table, digits and scalars are in LDS
 
   // ---- 6. A operands: lane = row + 16 kq, row = 4 * query + digit ---------------------------
@@ -226,12 +140,12 @@ __global__ __launch_bounds__(512) void score_i8_128_kernel(const ScoreI8Args a) 
     if (PROD) as_[s] = *reinterpret_cast<const v4i*>(dig_s + ((1 * 4 + a_query) * 4 + a_digit) * 128 + c0);
   }
   if (BITS > 0) {
-    r_inv = scal_s[(0 * 4 + kq) * 2];
-    r_sum = scal_s[(0 * 4 + kq) * 2 + 1];
+    r_inv = scal_s[(0 * 4 + kq) * 4];
+    r_sum = scal_s[(0 * 4 + kq) * 4 + 1];
   }
   if (PROD) {
-    s_inv = scal_s[(1 * 4 + kq) * 2];
-    s_sum = scal_s[(1 * 4 + kq) * 2 + 1];
+    s_inv = scal_s[(1 * 4 + kq) * 4];
+    s_sum = scal_s[(1 * 4 + kq) * 4 + 1];
   }
 
   const uint32_t copy_off = (uint32_t)(lane & (I8_COPIES - 1)) * 8u;
@@ -369,7 +283,7 @@ __global__ __launch_bounds__(512) void score_i8_128_kernel(const ScoreI8Args a) 
 
 template <int BITS, bool PROD>
 static hipError_t launch_128(const ScoreI8Args& a, int n_groups, hipStream_t s) {
-  constexpr int lds = 8 * stage_bytes(BITS) + PREP_BYTES;  // on top of the 64 KB table
+  constexpr int lds = 8 * stage_bytes(BITS) + I8_PREP_BYTES;  // on top of the 64 KB table
   static_assert(I8_TABLE_BYTES + lds <= 160 * 1024, "LDS budget");
   const int64_t per_wg = 8 * 16 * TILES_128;
   const dim3 grid((unsigned)((a.n + per_wg - 1) / per_wg), n_groups, (a.q_per_group + 3) / 4);

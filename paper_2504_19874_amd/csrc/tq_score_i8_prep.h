@@ -1,0 +1,125 @@
+// In-kernel query preparation shared by the single-kernel d = 128 scoring kernels
+// (tq_score_i8_128.hip, tq_score_i8_split.hip): a workgroup of 8 wavefronts rotates / sketches
+// its own four queries from the transposed matrices and writes their balanced base-128 digits.
+//
+//   load      wavefront w requests its thread's column of matrix w / 4 (0: Pi^T, 1: S^T), half
+//             (w / 2) % 2 of k, column j = tid % 128: 64 values, to be issued before anything else
+//   matvec    y_j partial sums for the four queries (query coordinates through scalar
+//             registers) -> part_s[matrix][half][query][j]
+//   (barrier)
+//   digitise  wavefront w takes (matrix w / 4, query w % 4): power-of-two scale with |Q| <= 2^19,
+//             digits -> dig_s[matrix][query][digit][j] (digit 3 = 0), scalars -> scal_s[matrix][query]
+//             [0: 1/scale, 1: sum of the rounded coordinates, 2: that sum over j < d_hi, 3: over the rest]
+//   (barrier)
+#pragma once
+#include "tq_score_i8.h"
+
+namespace tq {
+
+constexpr int I8_PREP_BYTES = 2 * 2 * 4 * 128 * 4 + 2 * 4 * 4 * 128 + 2 * 4 * 4 * 4;  // partial sums, digits, scalars
+
+// max / sum over the 64 lanes: four DPP steps inside each row of 16, then the four rows
+// through scalar registers
+template <int CTRL>
+__device__ __forceinline__ int dpp_move(int v) {
+  return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xF, 0xF, false);
+}
+__device__ __forceinline__ float wave_max(float v) {
+  v = fmaxf(v, __int_as_float(dpp_move<0xB1>(__float_as_int(v))));   // quad_perm [1,0,3,2]
+  v = fmaxf(v, __int_as_float(dpp_move<0x4E>(__float_as_int(v))));   // quad_perm [2,3,0,1]
+  v = fmaxf(v, __int_as_float(dpp_move<0x141>(__float_as_int(v))));  // row_half_mirror
+  v = fmaxf(v, __int_as_float(dpp_move<0x140>(__float_as_int(v))));  // row_mirror
+  const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+  const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+  const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+  const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+  return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+__device__ __forceinline__ int wave_sum(int v) {
+  v += dpp_move<0xB1>(v);
+  v += dpp_move<0x4E>(v);
+  v += dpp_move<0x141>(v);
+  v += dpp_move<0x140>(v);
+  return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) + __builtin_amdgcn_readlane(v, 32) +
+         __builtin_amdgcn_readlane(v, 48);
+}
+
+template <bool HAVE_R, bool PROD>
+struct I8Prep {
+  float wv[64];
+  int mat, kh, j;
+  bool work;
+
+  __device__ __forceinline__ void load(const ScoreI8Args& a, int wave, int tid) {
+    mat = wave >> 2;
+    kh = (wave >> 1) & 1;
+    j = tid & 127;
+    work = mat == 0 ? HAVE_R : PROD;  // uniform
+    if (work) {
+      const float* WT = (mat ? a.ST : a.PiT) + (64 * kh) * 128 + j;
+#pragma unroll
+      for (int k = 0; k < 64; ++k) wv[k] = WT[k * 128];
+    }
+  }
+
+  __device__ __forceinline__ void matvec(const ScoreI8Args& a, int group, int q0, float* part_s) {
+    if (!work) return;
+    const float* xq[4];  // uniform addresses: the query coordinates arrive in scalar registers
+#pragma unroll
+    for (int qi = 0; qi < 4; ++qi) {
+      const int64_t r = (int64_t)group * a.q_per_group + (q0 + qi < a.q_per_group ? q0 + qi : q0);
+      xq[qi] = a.x + r * a.ldx + 64 * kh;
+    }
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < 64; ++k)
+#pragma unroll
+      for (int qi = 0; qi < 4; ++qi) acc[qi] = fmaf(wv[k], xq[qi][k], acc[qi]);
+#pragma unroll
+    for (int qi = 0; qi < 4; ++qi) part_s[((mat * 2 + kh) * 4 + qi) * 128 + j] = acc[qi];
+  }
+
+  __device__ __forceinline__ static void digitise(const ScoreI8Args& a, int q0, int wave, int lane, int d_hi,
+                                                  const float* part_s, signed char* dig_s, float* scal_s) {
+    const int m = wave >> 2, qi = wave & 3;
+    if (!(m == 0 ? HAVE_R : PROD)) return;
+    const bool live = q0 + qi < a.q_per_group;
+    float y[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int c = lane + 64 * u;
+      y[u] = live ? part_s[((m * 2 + 0) * 4 + qi) * 128 + c] + part_s[((m * 2 + 1) * 4 + qi) * 128 + c] : 0.f;
+    }
+    const float mx = wave_max(fmaxf(fabsf(y[0]), fabsf(y[1])));
+    int e = 0;
+    if (mx > 0.f) (void)frexpf(mx, &e);  // mx = f * 2^e, f in [0.5, 1): |Q| <= 2^19
+    const float sc = ldexpf(1.f, 19 - e);
+    int Q[2];
+    Q[0] = __float2int_rn(y[0] * sc);
+    Q[1] = __float2int_rn(y[1] * sc);
+    const int tot = wave_sum(Q[0] + Q[1]);
+    const int tot_hi = wave_sum((lane < d_hi ? Q[0] : 0) + (lane + 64 < d_hi ? Q[1] : 0));
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      // balanced base 128: D0, D1 in [-64, 63], D2 in [-64, 64]
+      const int d0 = ((Q[u] + 64) & 127) - 64;
+      const int Q1 = (Q[u] - d0) >> 7;
+      const int d1 = ((Q1 + 64) & 127) - 64;
+      const int d2 = (Q1 - d1) >> 7;
+      signed char* o = dig_s + (m * 4 + qi) * 4 * 128 + lane + 64 * u;
+      o[0] = (signed char)d0;
+      o[128] = (signed char)d1;
+      o[256] = (signed char)d2;
+      o[384] = 0;
+    }
+    if (lane == 0) {
+      const float inv = ldexpf(1.f, e - 19);
+      scal_s[(m * 4 + qi) * 4 + 0] = inv;
+      scal_s[(m * 4 + qi) * 4 + 1] = (float)tot * inv;
+      scal_s[(m * 4 + qi) * 4 + 2] = (float)tot_hi * inv;
+      scal_s[(m * 4 + qi) * 4 + 3] = (float)(tot - tot_hi) * inv;
+    }
+  }
+};
+
+}  // namespace tq

@@ -12,9 +12,11 @@
 // kernel's operand layout a lane's k-chunk IS one coordinate group, so "sum
 // over one instance only" is an A operand with the other instance's lanes
 // zeroed: every mask is expanded once and fed to two MFMAs, one per instance.
-// Queries are prepared by prep_i8_kernel, which also leaves the per-instance
-// sums of the rounded query coordinates.
-#include "tq_score_i8.h"
+// Queries are prepared inside the kernel while the code words are in flight
+// (FUSED, needs the transposed matrices; see tq_score_i8_prep.h), or by
+// prep_i8_kernel beforehand; either leaves the per-instance sums of the rounded
+// query coordinates.
+#include "tq_score_i8_prep.h"
 
 namespace tq {
 
@@ -26,9 +28,13 @@ struct SplitArgs {
 
 constexpr int SPLIT_TILES = 8;  // tiles of 16 keys per wavefront
 
-template <int BITS, bool PROD>
+template <int BITS, bool PROD, bool FUSED>
 __global__ __launch_bounds__(512) void score_i8_split_kernel(const ScoreI8Args a, const SplitArgs sp) {
   __shared__ __attribute__((aligned(16))) uint2 expand_s[256 * I8_COPIES];  // [256][32]: byte -> one byte per bit
+  extern __shared__ __attribute__((aligned(16))) unsigned char prep_s[];   // FUSED: partial sums, digits, scalars
+  float* const part_s = reinterpret_cast<float*>(prep_s);                               // [2][2][4][128]
+  signed char* const dig_s = reinterpret_cast<signed char*>(part_s + 2 * 2 * 4 * 128);  // [2][4][4][128]
+  float* const scal_s = reinterpret_cast<float*>(dig_s + 2 * 4 * 4 * 128);              // [2][4][4]
   constexpr int NP = BITS + 1;            // planes of instance hi
   constexpr int NMH = (1 << NP) - 1;      // plane subsets of hi
   constexpr int NML = (1 << BITS) - 1;    // plane subsets of lo (a prefix of hi's)
@@ -49,24 +55,30 @@ __global__ __launch_bounds__(512) void score_i8_split_kernel(const ScoreI8Args a
   const bool out_live = q0 + kq < a.q_per_group;
   const int64_t orow = (int64_t)group * a.q_per_group + q0 + (out_live ? kq : 0);
   v4i ar[2][2], as_[2][2];  // [instance: 0 lo, 1 hi][k-step]
+  float r_inv = 0.f, r_sum_hi = 0.f, r_sum_lo = 0.f, s_inv = 0.f, s_sum_hi = 0.f, s_sum_lo = 0.f;
+  const v4i zero = v4i{0, 0, 0, 0};
+  I8Prep<true, PROD> prep;
+  if (FUSED) {
+    prep.load(a, wave, tid);  // this thread's column of the transposed matrix, before anything else
+  } else {
 #pragma unroll
-  for (int s = 0; s < 2; ++s) {
-    const uint4 r = a.img[((qrow * 2 + 0) * 2 + s) * 16 + a_digit * 4 + kq];
-    const uint4 z = PROD ? a.img[((qrow * 2 + 1) * 2 + s) * 16 + a_digit * 4 + kq] : make_uint4(0, 0, 0, 0);
-    const v4i rv = v4i{(int)r.x, (int)r.y, (int)r.z, (int)r.w}, zv = v4i{(int)z.x, (int)z.y, (int)z.z, (int)z.w};
-    const v4i zero = v4i{0, 0, 0, 0};
-    ar[1][s] = g_hi ? rv : zero;
-    ar[0][s] = g_hi ? zero : rv;
-    as_[1][s] = g_hi ? zv : zero;
-    as_[0][s] = g_hi ? zero : zv;
-  }
-  const float r_inv = a.scal[(orow * 2 + 0) * 4];
-  const float r_sum_hi = a.scal[(orow * 2 + 0) * 4 + 2], r_sum_lo = a.scal[(orow * 2 + 0) * 4 + 3];
-  float s_inv = 0.f, s_sum_hi = 0.f, s_sum_lo = 0.f;
-  if (PROD) {
-    s_inv = a.scal[(orow * 2 + 1) * 4];
-    s_sum_hi = a.scal[(orow * 2 + 1) * 4 + 2];
-    s_sum_lo = a.scal[(orow * 2 + 1) * 4 + 3];
+    for (int s = 0; s < 2; ++s) {
+      const uint4 r = a.img[((qrow * 2 + 0) * 2 + s) * 16 + a_digit * 4 + kq];
+      const uint4 z = PROD ? a.img[((qrow * 2 + 1) * 2 + s) * 16 + a_digit * 4 + kq] : make_uint4(0, 0, 0, 0);
+      const v4i rv = v4i{(int)r.x, (int)r.y, (int)r.z, (int)r.w}, zv = v4i{(int)z.x, (int)z.y, (int)z.z, (int)z.w};
+      ar[1][s] = g_hi ? rv : zero;
+      ar[0][s] = g_hi ? zero : rv;
+      as_[1][s] = g_hi ? zv : zero;
+      as_[0][s] = g_hi ? zero : zv;
+    }
+    r_inv = a.scal[(orow * 2 + 0) * 4];
+    r_sum_hi = a.scal[(orow * 2 + 0) * 4 + 2];
+    r_sum_lo = a.scal[(orow * 2 + 0) * 4 + 3];
+    if (PROD) {
+      s_inv = a.scal[(orow * 2 + 1) * 4];
+      s_sum_hi = a.scal[(orow * 2 + 1) * 4 + 2];
+      s_sum_lo = a.scal[(orow * 2 + 1) * 4 + 3];
+    }
   }
 
   // ---- code words of this wavefront's keys: plane words of the lane's own group --------------
@@ -100,7 +112,32 @@ __global__ __launch_bounds__(512) void score_i8_split_kernel(const ScoreI8Args a
       expand_s[tid + 512 * i] = make_uint2(lo, hi);
     }
   }
+  if (FUSED) {
+    prep.matvec(a, group, q0, part_s);
+    __syncthreads();
+    prep.digitise(a, q0, wave, lane, 32 * gs, part_s, dig_s, scal_s);
+  }
   __syncthreads();
+  if (FUSED) {
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      const int c0 = i8_coord0(s, kq);
+      const v4i rv = *reinterpret_cast<const v4i*>(dig_s + ((0 * 4 + a_query) * 4 + a_digit) * 128 + c0);
+      const v4i zv = PROD ? *reinterpret_cast<const v4i*>(dig_s + ((1 * 4 + a_query) * 4 + a_digit) * 128 + c0) : zero;
+      ar[1][s] = g_hi ? rv : zero;
+      ar[0][s] = g_hi ? zero : rv;
+      as_[1][s] = g_hi ? zv : zero;
+      as_[0][s] = g_hi ? zero : zv;
+    }
+    r_inv = scal_s[(0 * 4 + kq) * 4];
+    r_sum_hi = scal_s[(0 * 4 + kq) * 4 + 2];
+    r_sum_lo = scal_s[(0 * 4 + kq) * 4 + 3];
+    if (PROD) {
+      s_inv = scal_s[(1 * 4 + kq) * 4];
+      s_sum_hi = scal_s[(1 * 4 + kq) * 4 + 2];
+      s_sum_lo = scal_s[(1 * 4 + kq) * 4 + 3];
+    }
+  }
 
   const uint32_t copy_off = (uint32_t)(lane & (I8_COPIES - 1)) * 8u;
   const char* const table = reinterpret_cast<const char*>(expand_s);
@@ -168,12 +205,25 @@ __global__ __launch_bounds__(512) void score_i8_split_kernel(const ScoreI8Args a
   }
 }
 
-template <int BITS, bool PROD>
-static hipError_t launch_split(const ScoreI8Args& a, const SplitArgs& sp, int n_groups, hipStream_t s) {
+template <int BITS, bool PROD, bool FUSED>
+static hipError_t launch_split_one(const ScoreI8Args& a, const SplitArgs& sp, int n_groups, hipStream_t s) {
   const int64_t per_wg = 8 * 16 * SPLIT_TILES;
   const dim3 grid((unsigned)((a.n + per_wg - 1) / per_wg), n_groups, (a.q_per_group + 3) / 4);
-  hipLaunchKernelGGL((score_i8_split_kernel<BITS, PROD>), grid, dim3(512), 0, s, a, sp);
+  constexpr int lds = FUSED ? I8_PREP_BYTES : 0;  // on top of the 64 KB table
+  static bool attr_done = false;  // per instantiation: the limit has to be raised once
+  if (FUSED && !attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_i8_split_kernel<BITS, PROD, FUSED>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL((score_i8_split_kernel<BITS, PROD, FUSED>), grid, dim3(512), lds, s, a, sp);
   return hipGetLastError();
+}
+
+template <int BITS, bool PROD>
+static hipError_t launch_split(const ScoreI8Args& a, const SplitArgs& sp, int n_groups, bool fused, hipStream_t s) {
+  return fused ? launch_split_one<BITS, PROD, true>(a, sp, n_groups, s) : launch_split_one<BITS, PROD, false>(a, sp, n_groups, s);
 }
 
 // c[v] = sum_S w_S chi_S(v) rewritten over masked sums (see tq_score_i8.hip):
@@ -200,7 +250,8 @@ bool score_i8_split_applicable(int bits_lo, const Codebook& cb_lo, const Codeboo
          walsh_coefficients(bits_lo + 1, cb_hi, tmp);
 }
 
-hipError_t launch_score_i8_split(int bits_lo, bool prod, const float* Pi, const float* S, const float* q, int64_t ldq,
+hipError_t launch_score_i8_split(int bits_lo, bool prod, const float* Pi, const float* S, const float* PiT,
+                                 const float* ST, const float* q, int64_t ldq,
                                  void* workspace, const uint32_t* idx, const uint32_t* qjl, const float* gamma,
                                  const float* norm, float* scores, int64_t lds, int64_t n, int n_groups,
                                  int q_per_group, int gs_hi, float kappa_lo, float kappa_hi, const Codebook& cb_lo,
@@ -210,10 +261,14 @@ hipError_t launch_score_i8_split(int bits_lo, bool prod, const float* Pi, const 
   const int64_t nq = (int64_t)n_groups * q_per_group;
   uint4* img = static_cast<uint4*>(workspace);
   float* scal = reinterpret_cast<float*>(static_cast<char*>(workspace) + (size_t)nq * 2 * 2 * 256);
-  hipError_t e = launch_prep_i8_128(32 * gs_hi, Pi, S, q, ldq, nq, prod, img, scal, stream);
-  if (e != hipSuccess) return e;
+  // with the transposed matrices at hand the scoring kernel prepares the queries itself
+  const bool fused = PiT != nullptr && (!prod || ST != nullptr);
+  if (!fused) {
+    hipError_t e = launch_prep_i8_128(32 * gs_hi, Pi, S, q, ldq, nq, prod, img, scal, stream);
+    if (e != hipSuccess) return e;
+  }
   ScoreI8Args a;
-  a.img = img; a.scal = scal; a.PiT = nullptr; a.ST = nullptr; a.x = q; a.ldx = ldq; a.idx = idx; a.qjl = qjl;
+  a.img = img; a.scal = scal; a.PiT = PiT; a.ST = ST; a.x = q; a.ldx = ldq; a.idx = idx; a.qjl = qjl;
   a.gamma = gamma; a.norm = norm; a.scores = scores; a.lds = lds; a.n = n; a.total_rows = (int64_t)n_groups * n;
   a.d = 128; a.q_per_group = q_per_group; a.kappa = kappa_lo;
   SplitArgs sp;
@@ -222,14 +277,14 @@ hipError_t launch_score_i8_split(int bits_lo, bool prod, const float* Pi, const 
   if (!walsh_coefficients(bits_lo, cb_lo, a.coef) || !walsh_coefficients(bits_lo + 1, cb_hi, sp.coef_hi))
     return hipErrorInvalidValue;
   switch (bits_lo * 2 + (prod ? 1 : 0)) {
-    case 0: return launch_split<0, false>(a, sp, n_groups, stream);
-    case 1: return launch_split<0, true>(a, sp, n_groups, stream);
-    case 2: return launch_split<1, false>(a, sp, n_groups, stream);
-    case 3: return launch_split<1, true>(a, sp, n_groups, stream);
-    case 4: return launch_split<2, false>(a, sp, n_groups, stream);
-    case 5: return launch_split<2, true>(a, sp, n_groups, stream);
-    case 6: return launch_split<3, false>(a, sp, n_groups, stream);
-    case 7: return launch_split<3, true>(a, sp, n_groups, stream);
+    case 0: return launch_split<0, false>(a, sp, n_groups, fused, stream);
+    case 1: return launch_split<0, true>(a, sp, n_groups, fused, stream);
+    case 2: return launch_split<1, false>(a, sp, n_groups, fused, stream);
+    case 3: return launch_split<1, true>(a, sp, n_groups, fused, stream);
+    case 4: return launch_split<2, false>(a, sp, n_groups, fused, stream);
+    case 5: return launch_split<2, true>(a, sp, n_groups, fused, stream);
+    case 6: return launch_split<3, false>(a, sp, n_groups, fused, stream);
+    case 7: return launch_split<3, true>(a, sp, n_groups, fused, stream);
     default: return hipErrorInvalidValue;
   }
 }

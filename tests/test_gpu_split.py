@@ -139,8 +139,13 @@ def test_dequantize_split(d_hi, bits_lo, prod, n):
     (32, 1, True, 8, 4, 1000, 0), (64, 1, True, 2, 5, 2100, 0), (32, 2, True, 1, 4, 130, 5), (96, 2, False, 2, 3, 300, 0),
     (32, 0, True, 1, 1, 77, 0), (64, 3, False, 1, 9, 1500, 4),
 ])
-def test_score_split(d_hi, bits_lo, prod, n_groups, qpg, npg, topk):
+@pytest.mark.parametrize("own_prep", [True, False])
+def test_score_split(d_hi, bits_lo, prod, n_groups, qpg, npg, topk, own_prep):
+    """own_prep: the scoring kernel rotates its queries itself (needs the transposed matrices);
+    without them a preparation kernel runs first."""
     hi_ch, ihi, ilo, p = instances(d_hi, bits_lo, prod)
+    if not own_prep:
+        p.c.PiT = 0
     n, nq = n_groups * npg, n_groups * qpg
     res, idx_w, qjl_w, gamma, norm = random_codes(p, ihi, ilo, d_hi, n, prod, seed=5)
     q = W.gaussian_queries(nq, D, 3, unit=False)
