@@ -25,6 +25,10 @@ Readings taken where the paper is silent (each listed in the design notes):
 The split into two instances over the channels (Sec. 4.3) is a composition
 of the functions above and nothing else; its bookkeeping is pinned by the
 per-instance distortion and variance it must show (tests/test_oracle_quant.py).
+The attention read-out over a quantised cache (attend) is softmax of the
+scores times the dequantised values; pinned in tests/test_oracle_attend.py by a
+scalar-loop brute force and by the cases with a known answer (equal logits, one
+dominant key, a common shift of the logits, a single key).
 
 Pinned by tests/test_oracle_*.py (closed forms, the paper's printed values,
 brute force).  The only part with no external pin is the exact index vector
@@ -322,6 +326,23 @@ def score(q, x_tilde):
     """Inner-product estimates <q, Q^-1(Q(x))> for every (query, code) pair
     (Sec. 3.2, the displayed estimator), through the dequantised vectors."""
     return np.asarray(q, dtype=np.float64) @ np.asarray(x_tilde, dtype=np.float64).T
+
+
+def attend(q, k_tilde, v_tilde, scale: float):
+    """Decoder attention of a few queries over a quantised key/value cache
+    (the use of Sec. 4.3: keys AND values of past tokens are kept as codes):
+        logits_i = scale * <q, k~_i>      (the estimator of Sec. 3.2 on the keys)
+        p        = softmax(logits)
+        out      = sum_i p_i v~_i         (v~ = DeQuant of the value codes)
+    The paper states nothing about the value side beyond DeQuant, so this is
+    the textbook attention read-out applied to the dequantised cache.  The
+    maximum is subtracted before exp (no effect on the value in exact
+    arithmetic)."""
+    logits = float(scale) * score(q, k_tilde)
+    logits = logits - logits.max(axis=1, keepdims=True)
+    w = np.exp(logits)
+    p = w / w.sum(axis=1, keepdims=True)
+    return p @ np.asarray(v_tilde, dtype=np.float64)
 
 
 def topk(scores, k: int):
