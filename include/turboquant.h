@@ -173,6 +173,36 @@ tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_gr
                    int64_t lds, int32_t topk, int32_t* topk_idx, float* topk_val, void* stream);
 
 /*
+ * Attention read-out of a few queries over a quantised key/value cache
+ * (Sec. 4.3: keys and values of past tokens are kept as codes; the paper gives
+ * the value side nothing beyond DeQuant, so this is the usual read-out on the
+ * dequantised cache).  For query row g*q_per_group + j and the n_per_group
+ * cached tokens of group g:
+ *   logit_i = scale * tq_score(pk; q, key code i)      (estimator of Sec. 3.2)
+ *   out     = sum_i softmax(logit)_i * tq_dequantize(pv; value code i).
+ * DeQuant is linear in the decoded code, so the sum is taken over the codes in
+ * the rotated basis and rotated back once per query; no dequantised value is
+ * ever written.
+ *   pk, pv    parameters of the key and of the value codes (they may be the
+ *             same object).  Key codes: anything tq_score accepts, including
+ *             the two-instance split.  Value codes: one instance (d_hi == 0),
+ *             bits_mse >= 0; v_qjl/v_gamma NULL for an MSE value cache.
+ *   k_*, v_*  device, codes of n_groups*n_per_group tokens, layouts as above.
+ *   out       device out [n_groups*q_per_group][ldo], pv->d floats per row;
+ *             zero rows when n_per_group == 0.
+ * Uses pk->workspace only: tq_attend_workspace_bytes() bytes.  pk->d and pv->d
+ * may differ (q has pk->d columns).
+ */
+size_t tq_attend_workspace_bytes(const tq_params* pk, const tq_params* pv, int32_t n_groups,
+                                 int32_t q_per_group, int64_t n_per_group);
+tq_status tq_attend(const tq_params* pk, const tq_params* pv, const float* q, int64_t ldq,
+                    int32_t n_groups, int32_t q_per_group, const uint32_t* k_idx,
+                    const uint32_t* k_qjl, const float* k_gamma, const float* k_norm,
+                    const uint32_t* v_idx, const uint32_t* v_qjl, const float* v_gamma,
+                    const float* v_norm, int64_t n_per_group, float scale, float* out, int64_t ldo,
+                    void* stream);
+
+/*
  * Codec stages on their own (HBM-bound; they are also what the bit-exactness
  * tests drive): the decision idx_j = argmin_k |y_j - c_k| of Alg. 1 plus
  * packing for given rotated coordinates y[n][d]; the sign packing of Alg. 2

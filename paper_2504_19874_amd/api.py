@@ -37,6 +37,17 @@ def _ptr(t):
     return C.c_void_p(t.data_ptr())
 
 
+def _ptr_rows(t):
+    """A matrix whose row stride is passed separately: rows may be padded."""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise TurboQuantError("expected a GPU tensor")
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise TurboQuantError("expected a matrix with contiguous rows")
+    return C.c_void_p(t.data_ptr())
+
+
 def _stream():
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
 
@@ -135,14 +146,14 @@ def _dtype_of(x: torch.Tensor) -> int:
 
 def tq_quantize_mse(p: Params, x: torch.Tensor, idx: torch.Tensor, norm: torch.Tensor | None):
     n = x.shape[0]
-    _check(_lib.load().tq_quantize_mse(C.byref(p.c), _ptr(x), _dtype_of(x), n, x.stride(0) if n else p.d,
+    _check(_lib.load().tq_quantize_mse(C.byref(p.c), _ptr_rows(x), _dtype_of(x), n, x.stride(0) if n else p.d,
                                        _ptr(idx), _ptr(norm), _stream()), "tq_quantize_mse")
 
 
 def tq_quantize_prod(p: Params, x: torch.Tensor, idx: torch.Tensor, qjl: torch.Tensor,
                      gamma: torch.Tensor, norm: torch.Tensor | None):
     n = x.shape[0]
-    _check(_lib.load().tq_quantize_prod(C.byref(p.c), _ptr(x), _dtype_of(x), n, x.stride(0) if n else p.d,
+    _check(_lib.load().tq_quantize_prod(C.byref(p.c), _ptr_rows(x), _dtype_of(x), n, x.stride(0) if n else p.d,
                                         _ptr(idx), _ptr(qjl), _ptr(gamma), _ptr(norm), _stream()),
            "tq_quantize_prod")
 
@@ -150,17 +161,37 @@ def tq_quantize_prod(p: Params, x: torch.Tensor, idx: torch.Tensor, qjl: torch.T
 def tq_dequantize(p: Params, idx, qjl, gamma, norm, x_out: torch.Tensor):
     n = x_out.shape[0]
     _check(_lib.load().tq_dequantize(C.byref(p.c), _ptr(idx), _ptr(qjl), _ptr(gamma), _ptr(norm), n,
-                                     _ptr(x_out), x_out.stride(0) if n else p.d, _stream()), "tq_dequantize")
+                                     _ptr_rows(x_out), x_out.stride(0) if n else p.d, _stream()), "tq_dequantize")
 
 
 def tq_score(p: Params, q: torch.Tensor, n_groups: int, q_per_group: int, idx, qjl, gamma, norm,
              n_per_group: int, scores: torch.Tensor | None, topk: int = 0,
              topk_idx: torch.Tensor | None = None, topk_val: torch.Tensor | None = None):
     lds = scores.stride(0) if scores is not None and scores.shape[0] else n_per_group
-    _check(_lib.load().tq_score(C.byref(p.c), _ptr(q), q.stride(0) if q.shape[0] else p.d, n_groups,
+    _check(_lib.load().tq_score(C.byref(p.c), _ptr_rows(q), q.stride(0) if q.shape[0] else p.d, n_groups,
                                 q_per_group, _ptr(idx), _ptr(qjl), _ptr(gamma), _ptr(norm), n_per_group,
-                                _ptr(scores), lds, topk, _ptr(topk_idx), _ptr(topk_val), _stream()),
+                                _ptr_rows(scores), lds, topk, _ptr(topk_idx), _ptr(topk_val), _stream()),
            "tq_score")
+
+
+def tq_attend_workspace_bytes(pk: Params, pv: Params, n_groups: int, q_per_group: int, n_per_group: int) -> int:
+    return int(_lib.load().tq_attend_workspace_bytes(C.byref(pk.c), C.byref(pv.c), n_groups, q_per_group,
+                                                     n_per_group))
+
+
+def tq_attend(pk: Params, pv: Params, q: torch.Tensor, n_groups: int, q_per_group: int, k_codes, v_codes,
+              n_per_group: int, scale: float, out: torch.Tensor):
+    """k_codes, v_codes: (idx, qjl, gamma, norm) tensors, None where the quantiser has no such output.
+    Sizes pk's workspace for the call when it is too small."""
+    need = tq_attend_workspace_bytes(pk, pv, n_groups, q_per_group, n_per_group)
+    if pk.workspace is None or pk.workspace.numel() < need:
+        pk.workspace = torch.empty(need, dtype=torch.uint8, device=pk.device)
+        pk.c.workspace = pk.workspace.data_ptr()
+        pk.c.workspace_bytes = pk.workspace.numel()
+    _check(_lib.load().tq_attend(C.byref(pk.c), C.byref(pv.c), _ptr_rows(q), q.stride(0) if q.shape[0] else pk.d,
+                                 n_groups, q_per_group, *[_ptr(t) for t in k_codes], *[_ptr(t) for t in v_codes],
+                                 n_per_group, C.c_float(scale), _ptr_rows(out), out.stride(0) if out.shape[0] else pv.d,
+                                 _stream()), "tq_attend")
 
 
 def tq_stage_pack(p: Params, y: torch.Tensor, idx: torch.Tensor):

@@ -4,7 +4,7 @@
 #include <cmath>
 #include <cstring>
 
-#include "tq_internal.h"
+#include "tq_attend.h"
 
 using namespace tq;
 
@@ -415,6 +415,73 @@ tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_gr
       return TQ_ERR_HIP;
   }
   return TQ_OK;
+}
+
+namespace {
+struct AttendPlan {
+  int nchunks;
+  int64_t ld_scores;
+  size_t scores_bytes, part_bytes, score_ws_bytes;
+};
+AttendPlan attend_plan(const tq_params* pk, const tq_params* pv, int64_t nq, int64_t n_per_group) {
+  AttendPlan pl;
+  pl.nchunks = attend_simple_chunks(n_per_group);
+  pl.ld_scores = (n_per_group + 3) / 4 * 4;
+  pl.scores_bytes = round_up((size_t)nq * pl.ld_scores * sizeof(float), 256);
+  pl.part_bytes = round_up((size_t)nq * pl.nchunks * attend_part_stride(pv->d) * sizeof(float), 256);
+  pl.score_ws_bytes = tq_workspace_bytes(pk, 0, nq, 0);
+  return pl;
+}
+}  // namespace
+
+size_t tq_attend_workspace_bytes(const tq_params* pk, const tq_params* pv, int32_t n_groups, int32_t q_per_group,
+                                 int64_t n_per_group) {
+  if (pk == nullptr || pv == nullptr || pk->d <= 0 || pv->d <= 0 || n_groups < 0 || q_per_group < 0 || n_per_group < 0)
+    return 0;
+  const AttendPlan pl = attend_plan(pk, pv, (int64_t)n_groups * q_per_group, n_per_group);
+  return pl.scores_bytes + pl.part_bytes + pl.score_ws_bytes + 512;
+}
+
+tq_status tq_attend(const tq_params* pk, const tq_params* pv, const float* q, int64_t ldq, int32_t n_groups,
+                    int32_t q_per_group, const uint32_t* k_idx, const uint32_t* k_qjl, const float* k_gamma,
+                    const float* k_norm, const uint32_t* v_idx, const uint32_t* v_qjl, const float* v_gamma,
+                    const float* v_norm, int64_t n_per_group, float scale, float* out, int64_t ldo, void* stream) {
+  tq_status st = check_params(pk, true);
+  if (st != TQ_OK) return st;
+  st = check_params(pv, true);
+  if (st != TQ_OK) return st;
+  if (n_groups < 0 || q_per_group < 0 || n_per_group < 0 || ldo < pv->d) return TQ_ERR_INVALID_ARG;
+  const int64_t nq = (int64_t)n_groups * q_per_group;
+  if (nq == 0) return TQ_OK;
+  const bool v_prod = v_qjl != nullptr;
+  if (out == nullptr || pv->Pi == nullptr || (v_prod && (v_gamma == nullptr || pv->S == nullptr)))
+    return TQ_ERR_INVALID_ARG;
+  if (n_per_group > 0 && (v_norm == nullptr || (pv->bits_mse > 0 && v_idx == nullptr))) return TQ_ERR_INVALID_ARG;
+  if (pv->d_hi != 0 || pv->d > 4096 || n_groups > 65535 || q_per_group > 4 * 65535) return TQ_ERR_UNSUPPORTED;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+
+  const AttendPlan pl = attend_plan(pk, pv, nq, n_per_group);
+  Workspace ws{static_cast<char*>(pk->workspace), pk->workspace_bytes, 0};
+  float* scores = static_cast<float*>(ws.take(pl.scores_bytes));
+  float* part = static_cast<float*>(ws.take(pl.part_bytes));
+  char* rest = static_cast<char*>(ws.take(pl.score_ws_bytes));
+  if (scores == nullptr || part == nullptr || rest == nullptr) return TQ_ERR_WORKSPACE;
+  if (n_per_group > 0) {
+    tq_params pk_inner = *pk;  // the scoring call carves its own needs from what is left
+    pk_inner.workspace = rest;
+    pk_inner.workspace_bytes = pl.score_ws_bytes;
+    st = tq_score(&pk_inner, q, ldq, n_groups, q_per_group, k_idx, k_qjl, k_gamma, k_norm, n_per_group, scores,
+                  pl.ld_scores, 0, nullptr, nullptr, stream);
+    if (st != TQ_OK) return st;
+    AttendArgs a;
+    a.scores = scores; a.lds = pl.ld_scores;
+    a.idx = v_idx; a.qjl = v_qjl; a.gamma = v_gamma; a.norm = v_norm;
+    a.part = part; a.nchunks = pl.nchunks; a.n = n_per_group; a.d = pv->d; a.q_per_group = q_per_group;
+    a.scale = scale; a.cb = make_codebook(pv);
+    if (launch_attend_values(v_prod, a, n_groups, s) != hipSuccess) return TQ_ERR_HIP;
+  }
+  return from_hip(launch_attend_combine(part, pl.nchunks, pv->d, nq, pv->Pi, v_prod ? pv->S : nullptr,
+                                        kappa_of(pv->d), out, ldo, s));
 }
 
 tq_status tq_stage_pack(const tq_params* p, const float* y, int64_t n, uint32_t* idx, void* stream) {

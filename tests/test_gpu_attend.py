@@ -1,0 +1,169 @@
+"""GPU parity of tq_attend (attention read-out over a quantised key/value cache) against the
+oracle: softmax of the Sec. 3.2 scores of the key codes times the dequantised value codes.
+
+Tolerance.  A logit carries the score tolerance: |d logit| <= e := 1e-4 * scale * |q| * max nu_K.
+Softmax weights then move by a factor within exp(+-2e), so the output moves by at most
+(exp(2e) - 1) * sum_i p_i |v~_i| on top of the 1e-4 of its own arithmetic; per coordinate the natural
+size of v~_i is nu_V,i / sqrt(d).
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import turboquant_oracle as o
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+tq = pytest.importorskip("paper_2504_19874_amd")
+
+DEV = "cuda"
+
+
+def dev(a):
+    return None if a is None else torch.as_tensor(np.ascontiguousarray(a)).to(DEV)
+
+
+_cache = {}
+
+
+def setup(d, bits_mse, prod, seed_pi, seed_s):
+    key = (d, bits_mse, prod, seed_pi, seed_s)
+    if key not in _cache:
+        Pi = o.rotation_from_gaussian(W.gaussian_matrix(d, seed_pi))
+        S = W.sketch_matrix(d, seed_s) if prod else None
+        c32, t32, _ = o.codebook_fp32(d, bits_mse)
+        p = tq.Params(d, bits_mse, torch.from_numpy(Pi), None if S is None else torch.from_numpy(S), c32, t32)
+        _cache[key] = (p, Pi, S, c32)
+    return _cache[key]
+
+
+def random_codes(rng, n, d, bits_mse, prod, norm_sigma):
+    """Uniformly random codes: (oracle-side arrays, device tensors in the packed layout)."""
+    idx = rng.integers(0, 1 << bits_mse, size=(n, d)).astype(np.int32)
+    z = rng.integers(0, 2, size=(n, d)).astype(bool) if prod else None
+    gamma = rng.uniform(0.05, 0.6, size=n).astype(np.float32) if prod else None
+    norm = np.exp(rng.normal(0, norm_sigma, size=n)).astype(np.float32)
+    packed = (dev(o.pack_planes(idx, bits_mse).view(np.int32)) if bits_mse else None,
+              dev(o.pack_signs(z).view(np.int32)) if prod else None, dev(gamma), dev(norm))
+    return (idx, z, gamma, norm), packed
+
+
+def dequant(codes, Pi, S, c32):
+    idx, z, gamma, norm = codes
+    return o.dequant_mse(idx, Pi, c32, norm) if z is None else o.dequant_prod(idx, z, gamma, Pi, S, c32, norm)
+
+
+def check_attend(out, want, q, scale, k_norm, v_tilde, p_want, d, n_groups, qpg, npg):
+    qn = np.linalg.norm(q.astype(np.float64), axis=1)
+    for g in range(n_groups):
+        rows = slice(g * qpg, (g + 1) * qpg)
+        e = 1e-4 * abs(scale) * qn[rows] * float(k_norm[g * npg:(g + 1) * npg].max())
+        size = p_want[rows] @ np.abs(v_tilde[g * npg:(g + 1) * npg])  # sum_i p_i |v~_i|, per coordinate
+        lim = (P.REL_TOL + np.expm1(2 * e))[:, None] * (size + np.abs(want[rows]))
+        err = np.abs(out[rows] - want[rows])
+        worst = float((err / np.maximum(lim, 1e-300)).max())
+        assert worst <= 1.0, f"attend: error {worst:.3f}x the tolerance (max abs err {err.max():.3e})"
+
+
+CASES = [
+    # d, key bits_mse, key prod, value bits_mse, value prod, groups, queries per group, tokens per group
+    (128, 2, True, 2, False, 2, 4, 3000),
+    (128, 2, True, 1, True, 1, 5, 1100),
+    (128, 3, True, 3, False, 3, 1, 700),
+    (128, 1, False, 4, False, 1, 4, 2049),
+    (128, 2, True, 0, True, 1, 2, 300),
+    (64, 2, True, 2, True, 2, 3, 1500),
+    (256, 3, False, 2, False, 1, 4, 1025),
+    (128, 2, True, 2, False, 1, 4, 1),
+    (128, 2, True, 2, False, 8, 4, 4100),
+]
+
+
+@pytest.mark.parametrize("d,kb,kprod,vb,vprod,n_groups,qpg,npg", CASES)
+def test_attend(d, kb, kprod, vb, vprod, n_groups, qpg, npg):
+    pk, Pik, Sk, ck = setup(d, kb, kprod, 100, 200)
+    pv, Piv, Sv, cv = setup(d, vb, vprod, 300, 400)
+    n, nq = n_groups * npg, n_groups * qpg
+    rng = np.random.default_rng(1000 * d + npg)
+    k_codes, k_dev = random_codes(rng, n, d, kb, kprod, 0.3)
+    v_codes, v_dev = random_codes(rng, n, d, vb, vprod, 1.0)
+    q = W.gaussian_queries(nq, d, 3, unit=False)
+    scale = 1.0 / math.sqrt(d)
+    kt, vt = dequant(k_codes, Pik, Sk, ck), dequant(v_codes, Piv, Sv, cv)
+    want = np.concatenate([o.attend(q[g * qpg:(g + 1) * qpg], kt[g * npg:(g + 1) * npg], vt[g * npg:(g + 1) * npg], scale)
+                           for g in range(n_groups)])
+    p_want = np.concatenate([o.attend(q[g * qpg:(g + 1) * qpg], kt[g * npg:(g + 1) * npg], np.eye(npg), scale)
+                             for g in range(n_groups)])
+    out = torch.full((nq, d), float("nan"), dtype=torch.float32, device=DEV)
+    tq.tq_attend(pk, pv, dev(q), n_groups, qpg, k_dev, v_dev, npg, scale, out)
+    check_attend(out.cpu().numpy().astype(np.float64), want, q, scale, k_codes[3], vt, p_want, d, n_groups, qpg, npg)
+
+
+def test_attend_sharp_softmax_and_padded_rows():
+    """A scale large enough that a handful of tokens carry the weight; output rows wider than d."""
+    d, n_groups, qpg, npg = 128, 2, 4, 2500
+    pk, Pik, Sk, ck = setup(d, 2, True, 100, 200)
+    pv, Piv, Sv, cv = setup(d, 2, False, 300, 400)
+    n, nq = n_groups * npg, n_groups * qpg
+    rng = np.random.default_rng(5)
+    k_codes, k_dev = random_codes(rng, n, d, 2, True, 0.3)
+    v_codes, v_dev = random_codes(rng, n, d, 2, False, 1.0)
+    q = W.gaussian_queries(nq, d, 7, unit=True)
+    scale = 60.0
+    kt, vt = dequant(k_codes, Pik, Sk, ck), dequant(v_codes, Piv, Sv, cv)
+    want = np.concatenate([o.attend(q[g * qpg:(g + 1) * qpg], kt[g * npg:(g + 1) * npg], vt[g * npg:(g + 1) * npg], scale)
+                           for g in range(n_groups)])
+    p_want = np.concatenate([o.attend(q[g * qpg:(g + 1) * qpg], kt[g * npg:(g + 1) * npg], np.eye(npg), scale)
+                             for g in range(n_groups)])
+    assert p_want.max(axis=1).min() > 0.02  # the case is what it says
+    buf = torch.full((nq, d + 32), float("nan"), dtype=torch.float32, device=DEV)
+    tq.tq_attend(pk, pv, dev(q), n_groups, qpg, k_dev, v_dev, npg, scale, buf[:, :d])
+    assert torch.isnan(buf[:, d:]).all()
+    check_attend(buf[:, :d].cpu().numpy().astype(np.float64), want, q, scale, k_codes[3], vt, p_want, d, n_groups,
+                 qpg, npg)
+
+
+def test_attend_without_tokens_gives_zero_rows():
+    d = 128
+    pk, *_ = setup(d, 2, True, 100, 200)
+    pv, *_ = setup(d, 2, False, 300, 400)
+    out = torch.full((4, d), float("nan"), dtype=torch.float32, device=DEV)
+    tq.tq_attend(pk, pv, dev(W.gaussian_queries(4, d, 3, unit=False)), 1, 4, (None, None, None, None),
+                 (None, None, None, None), 0, 1.0, out)
+    assert torch.equal(out, torch.zeros_like(out))
+
+
+def test_attend_equals_softmax_of_scores_times_dequantized_values():
+    """The library against itself: tq_score + torch softmax + tq_dequantize on codes made by tq_quantize_*."""
+    d, n_groups, qpg, npg = 128, 2, 4, 1800
+    pk, *_ = setup(d, 2, True, 100, 200)
+    pv, *_ = setup(d, 3, False, 300, 400)
+    n, nq = n_groups * npg, n_groups * qpg
+    keys = torch.from_numpy(W.unit_gaussian_rows(n, d, 21)).to(DEV) * 3.0
+    vals = torch.from_numpy(W.unit_gaussian_rows(n, d, 22)).to(DEV) * 2.0
+    ki = torch.zeros((n, pk.idx_words), dtype=torch.int32, device=DEV)
+    kz = torch.zeros((n, pk.qjl_words), dtype=torch.int32, device=DEV)
+    kg = torch.zeros(n, dtype=torch.float32, device=DEV)
+    kn = torch.zeros(n, dtype=torch.float32, device=DEV)
+    pk.reserve(n, nq, 0)
+    tq.tq_quantize_prod(pk, keys, ki, kz, kg, kn)
+    vi = torch.zeros((n, pv.idx_words), dtype=torch.int32, device=DEV)
+    vn = torch.zeros(n, dtype=torch.float32, device=DEV)
+    pv.reserve(n, nq, 0)
+    tq.tq_quantize_mse(pv, vals, vi, vn)
+    q = torch.from_numpy(W.gaussian_queries(nq, d, 23, unit=False)).to(DEV)
+    scale = 1.0 / math.sqrt(d)
+    s = torch.zeros((nq, npg), dtype=torch.float32, device=DEV)
+    tq.tq_score(pk, q, n_groups, qpg, ki, kz, kg, kn, npg, s)
+    vt = torch.zeros((n, d), dtype=torch.float32, device=DEV)
+    tq.tq_dequantize(pv, vi, None, None, vn, vt)
+    p = torch.softmax(s.double() * scale, dim=1)
+    want = torch.cat([p[g * qpg:(g + 1) * qpg] @ vt[g * npg:(g + 1) * npg].double() for g in range(n_groups)])
+    out = torch.zeros((nq, d), dtype=torch.float32, device=DEV)
+    tq.tq_attend(pk, pv, q, n_groups, qpg, (ki, kz, kg, kn), (vi, None, None, vn), npg, scale, out)
+    size = torch.cat([p[g * qpg:(g + 1) * qpg] @ vt[g * npg:(g + 1) * npg].double().abs() for g in range(n_groups)])
+    assert ((out.double() - want).abs() <= 1e-4 * (size + want.abs())).all()
