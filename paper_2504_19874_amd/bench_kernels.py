@@ -62,6 +62,8 @@ def main():
     ap.add_argument("--reps", type=int, default=0)
     ap.add_argument("--warm", action="store_true")
     ap.add_argument("--only", default="")
+    ap.add_argument("--value-bits", type=int, default=2, help="attend: bits of the MSE stage of the value codes")
+    ap.add_argument("--value-prod", action="store_true", help="attend: value codes from TurboQuant_prod")
     args = ap.parse_args()
 
     import numpy as np
@@ -166,6 +168,38 @@ def main():
         report("score" + (f"+top{cfg.topk}" if cfg.topk else ""), cfg, timed(score, reps),
                2.0 * pairs * d * (2 if prod else 1) + 2.0 * nq * dd * (2 if prod else 1),
                n * code_b + out_b + 4 * nq * d, {"scores_per_s": None, "pairs": pairs})
+
+    if on("attend") and not cfg.topk and cfg.q_per_group <= 32 and not big:
+        # attention read-out: the key codes above plus a value cache of the same shape
+        vprod = args.value_prod
+        pv = tq.make_params(d, args.value_bits, W.gaussian_matrix(d, cfg.seed_pi + 7),
+                            W.sketch_matrix(d, cfg.seed_s + 7) if vprod else None).reserve(n, nq, 0)
+        vsets = []
+        for s in range(sets):
+            v = torch.from_numpy(W.unit_gaussian_rows(n, d, cfg.seed_x + 500 + s)).cuda() * 2.0
+            vc = dict(idx=torch.zeros((n, max(1, pv.idx_words)), dtype=torch.int32, device="cuda"),
+                      qjl=torch.zeros((n, pv.qjl_words), dtype=torch.int32, device="cuda") if vprod else None,
+                      gamma=torch.zeros(n, dtype=torch.float32, device="cuda") if vprod else None,
+                      norm=torch.zeros(n, dtype=torch.float32, device="cuda"))
+            if vprod:
+                tq.tq_quantize_prod(pv, v, vc["idx"], vc["qjl"], vc["gamma"], vc["norm"])
+            else:
+                tq.tq_quantize_mse(pv, v, vc["idx"], vc["norm"])
+            vsets.append(vc)
+        outs = [torch.empty((nq, d), dtype=torch.float32, device="cuda") for _ in range(min(sets, 8))]
+        knorm = [c["norm"] if c["norm"] is not None else torch.ones((n, spv), dtype=torch.float32, device="cuda")
+                 for c in codes]
+
+        def attend(r):
+            c, vc = codes[r % sets], vsets[r % sets]
+            tq.tq_attend(p, pv, q, cfg.n_groups, cfg.q_per_group, (c["idx"], c["qjl"], c["gamma"], knorm[r % sets]),
+                         (vc["idx"], vc["qjl"], vc["gamma"], vc["norm"]), cfg.n, 1.0 / d ** 0.5, outs[r % len(outs)])
+
+        pairs = float(nq) * cfg.n
+        vcode_b = 4 * pv.idx_words + 4 + (d / 8 + 4 if vprod else 0)
+        report(f"attend(v{'prod' if vprod else 'mse'}{args.value_bits})", cfg, timed(attend, reps),
+               2.0 * pairs * d * ((2 if prod else 1) + (2 if vprod else 1)), n * (code_b + vcode_b) + 8 * nq * d,
+               {"pairs": pairs})
 
     if on("stage") and cfg.bits_mse > 0 and not cfg.d_hi:
         # codec stages on rotated coordinates of the same shape

@@ -419,13 +419,15 @@ tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_gr
 
 namespace {
 struct AttendPlan {
+  bool fast;  // the d = 128 kernel on the integer matrix cores takes the value codes
   int nchunks;
   int64_t ld_scores;
   size_t scores_bytes, part_bytes, score_ws_bytes;
 };
-AttendPlan attend_plan(const tq_params* pk, const tq_params* pv, int64_t nq, int64_t n_per_group) {
+AttendPlan attend_plan(const tq_params* pk, const tq_params* pv, bool v_prod, int64_t nq, int64_t n_per_group) {
   AttendPlan pl;
-  pl.nchunks = attend_simple_chunks(n_per_group);
+  pl.fast = pv->centroids != nullptr && attend128_applicable(pv->d, v_prod, make_codebook(pv));
+  pl.nchunks = pl.fast ? attend128_chunks(n_per_group) : attend_simple_chunks(n_per_group);
   pl.ld_scores = (n_per_group + 3) / 4 * 4;
   pl.scores_bytes = round_up((size_t)nq * pl.ld_scores * sizeof(float), 256);
   pl.part_bytes = round_up((size_t)nq * pl.nchunks * attend_part_stride(pv->d) * sizeof(float), 256);
@@ -438,7 +440,8 @@ size_t tq_attend_workspace_bytes(const tq_params* pk, const tq_params* pv, int32
                                  int64_t n_per_group) {
   if (pk == nullptr || pv == nullptr || pk->d <= 0 || pv->d <= 0 || n_groups < 0 || q_per_group < 0 || n_per_group < 0)
     return 0;
-  const AttendPlan pl = attend_plan(pk, pv, (int64_t)n_groups * q_per_group, n_per_group);
+  // sized for the kernel with the shorter chunks, whichever the call then takes
+  const AttendPlan pl = attend_plan(pk, pv, true, (int64_t)n_groups * q_per_group, n_per_group);
   return pl.scores_bytes + pl.part_bytes + pl.score_ws_bytes + 512;
 }
 
@@ -460,7 +463,7 @@ tq_status tq_attend(const tq_params* pk, const tq_params* pv, const float* q, in
   if (pv->d_hi != 0 || pv->d > 4096 || n_groups > 65535 || q_per_group > 4 * 65535) return TQ_ERR_UNSUPPORTED;
   hipStream_t s = static_cast<hipStream_t>(stream);
 
-  const AttendPlan pl = attend_plan(pk, pv, nq, n_per_group);
+  const AttendPlan pl = attend_plan(pk, pv, v_prod, nq, n_per_group);
   Workspace ws{static_cast<char*>(pk->workspace), pk->workspace_bytes, 0};
   float* scores = static_cast<float*>(ws.take(pl.scores_bytes));
   float* part = static_cast<float*>(ws.take(pl.part_bytes));
@@ -478,7 +481,8 @@ tq_status tq_attend(const tq_params* pk, const tq_params* pv, const float* q, in
     a.idx = v_idx; a.qjl = v_qjl; a.gamma = v_gamma; a.norm = v_norm;
     a.part = part; a.nchunks = pl.nchunks; a.n = n_per_group; a.d = pv->d; a.q_per_group = q_per_group;
     a.scale = scale; a.cb = make_codebook(pv);
-    if (launch_attend_values(v_prod, a, n_groups, s) != hipSuccess) return TQ_ERR_HIP;
+    if ((pl.fast ? launch_attend128(a, n_groups, s) : launch_attend_values(v_prod, a, n_groups, s)) != hipSuccess)
+      return TQ_ERR_HIP;
   }
   return from_hip(launch_attend_combine(part, pl.nchunks, pv->d, nq, pv->Pi, v_prod ? pv->S : nullptr,
                                         kappa_of(pv->d), out, ldo, s));

@@ -47,6 +47,7 @@ constexpr int I8_TABLE_BYTES = 256 * I8_COPIES * 8;
 
 
 hipError_t launch_score_i8_128(int bits, bool prod, const ScoreI8Args& a, int n_groups, hipStream_t stream);
+bool i8_coefficients(int bits, const Codebook& cb, float* coef);  // factors of the masked sums (tq_score_i8.hip)
 void i8_walsh(int bits, const Codebook& cb, double* w);  // Walsh coefficients of a centroid table (tq_score_i8.hip)
 hipError_t launch_prep_i8_128(int d_hi, const float* Pi, const float* S, const float* q, int64_t ldq, int64_t nq,
                               bool prod, uint4* img, float* scal, hipStream_t stream);

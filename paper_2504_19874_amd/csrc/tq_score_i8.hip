@@ -441,6 +441,25 @@ hipError_t launch_prep_i8_128(int d_hi, const float* Pi, const float* S, const f
   return hipGetLastError();
 }
 
+// sum_j q_j c[idx_j] = coef[0] * sum_j q_j + sum over the odd-sized plane subsets S of coef[S] * M_S, where M_S
+// is the sum of q_j over the coordinates whose index bits in S XOR to 1.  False for a table that is not
+// symmetric about zero (its even-sized subsets do not vanish).
+bool i8_coefficients(int bits, const Codebook& cb, float* coef) {
+  double w[16];
+  i8_walsh(bits, cb, w);
+  const int K = 1 << bits;
+  double c0 = w[0];
+  for (int v = 0; v < 16; ++v) coef[v] = 0.f;
+  for (int sset = 1; sset < K; ++sset) {
+    const double sgn = (__builtin_popcount(sset) & 1) ? 1.0 : -1.0;
+    if (!i8_term(sset) && w[sset] != 0.0) return false;
+    c0 -= sgn * w[sset];
+    coef[sset] = (float)(2.0 * sgn * w[sset]);
+  }
+  coef[0] = (float)c0;
+  return true;
+}
+
 bool score_i8_applicable(int bits, int d, const Codebook& cb) {
   if (bits < 0 || bits > 4 || d % 128 != 0 || d > 64 * I8_MAX_KS) return false;
   double w[16];
@@ -464,19 +483,7 @@ hipError_t launch_score_i8(int bits, bool prod, const float* Pi, const float* S,
   ScoreI8Args a;
   a.img = img; a.scal = scal; a.PiT = PiT; a.ST = ST; a.x = q; a.ldx = ldq; a.idx = idx; a.qjl = qjl; a.gamma = gamma; a.norm = norm;
   a.scores = scores; a.lds = lds; a.n = n; a.total_rows = (int64_t)n_groups * n; a.d = d; a.q_per_group = q_per_group; a.kappa = kappa;
-  double w[16];
-  i8_walsh(bits, cb, w);
-  // sum_j q_j c[idx_j] = (w_0 - sum_S sgn_S w_S) * sum_j q_j + sum_S 2 sgn_S w_S M_S
-  const int K = 1 << bits;
-  double c0 = w[0];
-  for (int v = 0; v < 16; ++v) a.coef[v] = 0.f;
-  for (int sset = 1; sset < K; ++sset) {
-    const double sgn = (__builtin_popcount(sset) & 1) ? 1.0 : -1.0;
-    if (!i8_term(sset) && w[sset] != 0.0) return hipErrorInvalidValue;  // see score_i8_applicable
-    c0 -= sgn * w[sset];
-    a.coef[sset] = (float)(2.0 * sgn * w[sset]);
-  }
-  a.coef[0] = (float)c0;
+  if (!i8_coefficients(bits, cb, a.coef)) return hipErrorInvalidValue;  // see score_i8_applicable
   // d = 128 with the transposed matrices at hand and 16-byte aligned codes: one kernel does it all
   const auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
   if (d == 128 && (bits > 0 || prod) && (bits == 0 || (PiT != nullptr && al16(idx))) &&

@@ -80,6 +80,8 @@ CASES = [
     (256, 3, False, 2, False, 1, 4, 1025),
     (128, 2, True, 2, False, 1, 4, 1),
     (128, 2, True, 2, False, 8, 4, 4100),
+    (128, 3, True, 1, False, 2, 7, 2048),
+    (128, 0, True, 3, False, 1, 4, 6200),
 ]
 
 
