@@ -5,6 +5,7 @@
 #include <cstring>
 
 #include "tq_attend.h"
+#include "tq_score_i8.h"
 
 using namespace tq;
 
@@ -464,25 +465,37 @@ tq_status tq_attend(const tq_params* pk, const tq_params* pv, const float* q, in
   hipStream_t s = static_cast<hipStream_t>(stream);
 
   const AttendPlan pl = attend_plan(pk, pv, v_prod, nq, n_per_group);
+  if (pl.nchunks > 4096) return TQ_ERR_UNSUPPORTED;  // the joining kernel keeps one factor per chunk in LDS
   Workspace ws{static_cast<char*>(pk->workspace), pk->workspace_bytes, 0};
   float* scores = static_cast<float*>(ws.take(pl.scores_bytes));
   float* part = static_cast<float*>(ws.take(pl.part_bytes));
   char* rest = static_cast<char*>(ws.take(pl.score_ws_bytes));
   if (scores == nullptr || part == nullptr || rest == nullptr) return TQ_ERR_WORKSPACE;
   if (n_per_group > 0) {
-    tq_params pk_inner = *pk;  // the scoring call carves its own needs from what is left
-    pk_inner.workspace = rest;
-    pk_inner.workspace_bytes = pl.score_ws_bytes;
-    st = tq_score(&pk_inner, q, ldq, n_groups, q_per_group, k_idx, k_qjl, k_gamma, k_norm, n_per_group, scores,
-                  pl.ld_scores, 0, nullptr, nullptr, stream);
-    if (st != TQ_OK) return st;
     AttendArgs a;
     a.scores = scores; a.lds = pl.ld_scores;
     a.idx = v_idx; a.qjl = v_qjl; a.gamma = v_gamma; a.norm = v_norm;
     a.part = part; a.nchunks = pl.nchunks; a.n = n_per_group; a.d = pv->d; a.q_per_group = q_per_group;
     a.scale = scale; a.cb = make_codebook(pv);
-    if ((pl.fast ? launch_attend128(a, n_groups, s) : launch_attend_values(v_prod, a, n_groups, s)) != hipSuccess)
-      return TQ_ERR_HIP;
+    // keys the single-kernel d = 128 scoring path takes are scored inside the read-out kernel
+    const bool k_prod = k_qjl != nullptr;
+    ScoreI8Args ka;
+    const bool fused = pl.fast && pk->d == 128 && pk->d_hi == 0 && q != nullptr && ldq >= 128 &&
+                       score128_args(pk->bits_mse, k_prod, pk->PiT, pk->ST, q, ldq, k_idx, k_qjl, k_gamma, k_norm,
+                                     n_per_group, n_groups, q_per_group, kappa_of(128), make_codebook(pk), &ka);
+    if (fused) {
+      if (launch_attend128(pk->bits_mse, k_prod, &ka, a, n_groups, s) != hipSuccess) return TQ_ERR_HIP;
+    } else {
+      tq_params pk_inner = *pk;  // the scoring call carves its own needs from what is left
+      pk_inner.workspace = rest;
+      pk_inner.workspace_bytes = pl.score_ws_bytes;
+      st = tq_score(&pk_inner, q, ldq, n_groups, q_per_group, k_idx, k_qjl, k_gamma, k_norm, n_per_group, scores,
+                    pl.ld_scores, 0, nullptr, nullptr, stream);
+      if (st != TQ_OK) return st;
+      if ((pl.fast ? launch_attend128(0, false, nullptr, a, n_groups, s) : launch_attend_values(v_prod, a, n_groups, s)) !=
+          hipSuccess)
+        return TQ_ERR_HIP;
+    }
   }
   return from_hip(launch_attend_combine(part, pl.nchunks, pv->d, nq, pv->Pi, v_prod ? pv->S : nullptr,
                                         kappa_of(pv->d), out, ldo, s));

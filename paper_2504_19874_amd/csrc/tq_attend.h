@@ -28,7 +28,8 @@ struct AttendArgs {
 // d = 128 on the integer matrix cores (tq_attend_128.hip)
 int attend128_chunks(int64_t n);
 bool attend128_applicable(int d, bool prod, const Codebook& cb);
-hipError_t launch_attend128(const AttendArgs& a, int n_groups, hipStream_t s);
+struct ScoreI8Args;
+hipError_t launch_attend128(int kb, bool kprod, const ScoreI8Args* ka, const AttendArgs& a, int n_groups, hipStream_t s);
 
 int attend_simple_chunks(int64_t n);
 hipError_t launch_attend_values(bool prod, const AttendArgs& a, int n_groups, hipStream_t s);

@@ -103,27 +103,58 @@ __global__ __launch_bounds__(256) void attend_values_kernel(const AttendArgs a) 
 // one workgroup per query: join the chunks, then back to the original basis
 __global__ __launch_bounds__(256) void attend_combine_kernel(const float* part, int nchunks, int d, const float* Pi,
                                                              const float* S, float kappa, float* out, int64_t ldo) {
-  extern __shared__ float y_s[];  // [2][d]: the two rotated-basis sums, normalised
+  extern __shared__ float sm[];  // y_s[2 d]: the two rotated-basis sums, normalised; e_s[nchunks]; o_s[256]
+  __shared__ float red_s[4];
+  float* const y_s = sm;
+  float* const e_s = sm + 2 * d;
+  float* const o_s = e_s + nchunks;
   const int tid = threadIdx.x;
   const int stride = attend_part_stride(d);
   const float* p = part + (int64_t)blockIdx.x * nchunks * stride;
-  float M = -INFINITY;
-  for (int c = 0; c < nchunks; ++c) M = fmaxf(M, p[(int64_t)c * stride]);
-  float L = 0.f;
-  for (int c = 0; c < nchunks; ++c) L += expf(p[(int64_t)c * stride] - M) * p[(int64_t)c * stride + 1];
-  const float invL = L > 0.f ? 1.f / L : 0.f;  // no keys at all: the output is zero
-  for (int j = tid; j < 2 * d; j += 256) {
+  float mx = -INFINITY;
+  for (int c = tid; c < nchunks; c += 256) mx = fmaxf(mx, p[(int64_t)c * stride]);
+  const float M = block_reduce(mx, true, red_s, tid);
+  float ls = 0.f;
+  for (int c = tid; c < nchunks; c += 256) {
+    const float e = expf(p[(int64_t)c * stride] - M);
+    e_s[c] = e;
+    ls = fmaf(e, p[(int64_t)c * stride + 1], ls);
+  }
+  const float L = block_reduce(ls, false, red_s, tid);  // its barriers also publish e_s
+  const float invL = L > 0.f ? 1.f / L : 0.f;            // no keys at all: the output is zero
+  for (int j = tid; j < (S != nullptr ? 2 * d : d); j += 256) {
     float acc = 0.f;
-    for (int c = 0; c < nchunks; ++c) acc = fmaf(expf(p[(int64_t)c * stride] - M), p[(int64_t)c * stride + 4 + j], acc);
+#pragma unroll 8
+    for (int c = 0; c < nchunks; ++c) acc = fmaf(e_s[c], p[(int64_t)c * stride + 4 + j], acc);
     y_s[j] = acc * invL;
   }
   __syncthreads();
-  for (int k = tid; k < d; k += 256) {
+  // out[k] = sum_j Pi[j][k] y[j] + kappa sum_j S[j][k] z[j]; for small d the j range is split over the threads
+  const int parts = d <= 256 ? 256 / d : 1;
+  const int span = d / parts;
+  for (int k0 = 0; k0 < d; k0 += 256) {  // one trip unless d > 256
+    const int item = k0 + tid, k = parts > 1 ? tid % d : item, part_ = parts > 1 ? tid / d : 0;
     float o = 0.f, oz = 0.f;
-    for (int j = 0; j < d; ++j) o = fmaf(Pi[(int64_t)j * d + k], y_s[j], o);
-    if (S != nullptr)
-      for (int j = 0; j < d; ++j) oz = fmaf(S[(int64_t)j * d + k], y_s[d + j], oz);
-    out[(int64_t)blockIdx.x * ldo + k] = fmaf(kappa, oz, o);
+    if (k < d && part_ < parts) {
+      const int j0 = part_ * span;
+#pragma unroll 8
+      for (int j = j0; j < j0 + span; ++j) o = fmaf(Pi[(int64_t)j * d + k], y_s[j], o);
+      if (S != nullptr) {
+#pragma unroll 8
+        for (int j = j0; j < j0 + span; ++j) oz = fmaf(S[(int64_t)j * d + k], y_s[d + j], oz);
+      }
+    }
+    o = fmaf(kappa, oz, o);
+    if (parts > 1) {
+      o_s[tid] = o;
+      __syncthreads();
+      if (tid < d) {
+        for (int t = 1; t < parts; ++t) o += o_s[tid + t * d];
+        out[(int64_t)blockIdx.x * ldo + tid] = o;
+      }
+    } else if (k < d) {
+      out[(int64_t)blockIdx.x * ldo + k] = o;
+    }
   }
 }
 
@@ -144,7 +175,7 @@ hipError_t launch_attend_values(bool prod, const AttendArgs& a, int n_groups, hi
 hipError_t launch_attend_combine(const float* part, int nchunks, int d, int64_t nq, const float* Pi, const float* S,
                                  float kappa, float* out, int64_t ldo, hipStream_t s) {
   if (nq == 0) return hipSuccess;
-  hipLaunchKernelGGL(attend_combine_kernel, dim3((unsigned)nq), dim3(256), 2 * d * sizeof(float), s, part, nchunks, d,
+  hipLaunchKernelGGL(attend_combine_kernel, dim3((unsigned)nq), dim3(256), (2 * d + nchunks + 256) * sizeof(float), s, part, nchunks, d,
                      Pi, S, kappa, out, ldo);
   return hipGetLastError();
 }

@@ -1,311 +1,10 @@
-// Attention read-out at d = 128 (see tq_attend.hip for the decomposition): the softmax-weighted
-// sum of decoded value codes on the integer matrix cores.
-//
-// With a centroid table symmetric about zero, c[idx] = coef[0] + sum over the odd-sized plane
-// subsets S of coef[S] * x_S(idx), x_S = XOR of the index bits in S (tq_score_i8.hip).  So for
-// every query q and coordinate j
-//     sum_i w_qi c[idx_ij] = coef[0] * sum_i w_qi + sum_S coef[S] * sum_i w_qi x_S(idx_ij):
-// sums of weights over the KEYS selected by a bit mask.  The weights w_qi = exp(logit - m) * nu_i
-// are scaled by a power of two to 26-bit integers and split into four balanced base-128 digits;
-// one v_mfma_i32_16x16x64_i8 multiplies the 16 rows (4 queries x 4 digits) with 64 keys x 16
-// coordinates of 0/1 bytes.
-//
-// The contraction runs over keys, but a code word holds 32 COORDINATES of one key.  Each lane
-// therefore takes the words of 16 keys (one coordinate group, one plane) and transposes the
-// 16 x 32 bit block in registers (two 16 x 16 transposes side by side in the halves of a 32-bit
-// register); the transposed words go through LDS to the lanes that need them as B operands, which
-// expand 16 bits (16 keys of one coordinate) to 16 bytes through a 256-entry table, as the scoring
-// kernels do.
-//
-// Workgroup of 8 wavefronts = 2048 keys of one group, 4 queries; a wavefront takes 128 keys per
-// pass, two passes.  Per pass and wavefront: 2 k-blocks of 64 keys x 8 coordinate blocks x terms
-// MFMAs.
-#include "tq_attend.h"
-#include "tq_score_i8_prep.h"
+// Attention read-out at d = 128 on the integer matrix cores: which kernel variant a call takes
+// (the kernel itself is in tq_attend_128_kernel.h).
+#include <cstring>
+
+#include "tq_attend_128_kernel.h"
 
 namespace tq {
-
-namespace {
-
-constexpr int AT_PASSES = 2;
-constexpr int AT_WAVE_KEYS = 128;
-constexpr int AT_CHUNK = 8 * AT_WAVE_KEYS * AT_PASSES;
-constexpr int AT_WD_BYTES = 8 * 4 * 4 * AT_WAVE_KEYS;  // weight digits [wave][query][digit][key]
-constexpr int AT_XCH_BYTES = 8 * 8 * 64 * 4;            // per plane: [wave][block of 16 keys][64 words]
-constexpr int AT_RED_FLOATS = 3 * 8 * 4;
-
-__host__ __device__ constexpr int attend128_lds(int vb) { return AT_WD_BYTES + vb * AT_XCH_BYTES + AT_RED_FLOATS * 4; }
-
-struct Coefs {
-  float c[16];
-};
-
-__device__ __forceinline__ float wave_sum_f(float v) {
-  v += __int_as_float(dpp_move<0xB1>(__float_as_int(v)));
-  v += __int_as_float(dpp_move<0x4E>(__float_as_int(v)));
-  v += __int_as_float(dpp_move<0x141>(__float_as_int(v)));
-  v += __int_as_float(dpp_move<0x140>(__float_as_int(v)));
-  const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
-  const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
-  const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
-  const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
-  return (r0 + r1) + (r2 + r3);
-}
-
-// x[i] bit c (16 rows, 32 columns)  ->  x[c'] bit t = old x[t] bit c' and x[c'] bit 16 + t = old x[t] bit 16 + c':
-// two 16 x 16 transposes, one in each half of the registers
-__device__ __forceinline__ void transpose16x32(uint32_t (&x)[16]) {
-#define TQ_SWAP_STAGE(J, M)                                      \
-  _Pragma("unroll") for (int k = 0; k < 16; ++k) if (!(k & J)) { \
-    const uint32_t a = x[k], b = x[k + J];                       \
-    x[k + J] = ((a >> J) & M) | (b & ~M);                        \
-    x[k] = (a & ~(M << J)) | ((b << J) & (M << J));              \
-  }
-  TQ_SWAP_STAGE(8, 0x00FF00FFu)
-  TQ_SWAP_STAGE(4, 0x0F0F0F0Fu)
-  TQ_SWAP_STAGE(2, 0x33333333u)
-  TQ_SWAP_STAGE(1, 0x55555555u)
-#undef TQ_SWAP_STAGE
-}
-
-template <int VB>
-__global__ __launch_bounds__(512) void attend128_kernel(const AttendArgs a, const Coefs cf) {
-  __shared__ __attribute__((aligned(16))) uint2 expand_s[256 * I8_COPIES];  // byte -> one byte per bit, 32 copies
-  extern __shared__ __attribute__((aligned(16))) unsigned char dyn_s[];
-  constexpr int ROUNDS = (VB + 1) / 2;  // planes a transposing lane takes: ph, ph + 2
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int col = lane & 15;  // B column (coordinate within a block of 16) / A row (query, digit)
-  const int kc = lane >> 4;   // k-chunk: 16 keys of a k-block; also the query whose sums this lane receives
-  const int chunk = blockIdx.x, group = blockIdx.y, q0 = blockIdx.z * 4;
-  unsigned char* const wd = dyn_s + wave * (4 * 4 * AT_WAVE_KEYS);
-  uint32_t* const xch = reinterpret_cast<uint32_t*>(dyn_s + AT_WD_BYTES) + wave * (8 * 64);  // + plane * 8 * 8 * 64
-  float* const red_s = reinterpret_cast<float*>(dyn_s + AT_WD_BYTES + VB * AT_XCH_BYTES);     // [3][8][4]
-  float* const fsum_s = reinterpret_cast<float*>(dyn_s + AT_WD_BYTES);  // [8][4][128], over the exchange area
-
-  const int64_t gbase = (int64_t)group * a.n;
-  const int64_t key_base = (int64_t)chunk * AT_CHUNK;
-  // transposing role: block kb of 16 keys, coordinate group tg, planes ph and ph + 2
-  const int kb = lane & 7, tg = (lane >> 3) & 3, ph = lane >> 5;
-
-  uint32_t vw[ROUNDS][16];
-  auto load_codes = [&](int ps) {
-    const int64_t k0 = key_base + ps * (8 * AT_WAVE_KEYS) + wave * AT_WAVE_KEYS + 16 * kb;
-#pragma unroll
-    for (int r = 0; r < ROUNDS; ++r) {
-      const int plane = ph + 2 * r;
-      const bool have = plane < VB;  // odd VB: the last round has work for half the lanes only
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int64_t key = k0 + i;
-        const int64_t row = gbase + (key < a.n ? key : a.n - 1);  // clamped: such keys have weight 0
-        vw[r][i] = have ? a.idx[row * (4 * VB) + tg * VB + plane] : 0u;
-      }
-    }
-  };
-  load_codes(0);
-
-  // ---- logits of this wavefront's keys (2 per lane and pass), value norms --------------------
-  float lg[AT_PASSES][4][2], nu[AT_PASSES][2];
-#pragma unroll
-  for (int ps = 0; ps < AT_PASSES; ++ps) {
-    const int64_t k0 = key_base + ps * (8 * AT_WAVE_KEYS) + wave * AT_WAVE_KEYS + 2 * lane;
-#pragma unroll
-    for (int e = 0; e < 2; ++e) nu[ps][e] = k0 + e < a.n ? a.norm[gbase + k0 + e] : 0.f;
-#pragma unroll
-    for (int qi = 0; qi < 4; ++qi) {
-      const int64_t qrow = (int64_t)group * a.q_per_group + (q0 + qi < a.q_per_group ? q0 + qi : q0);
-      const float* srow = a.scores + qrow * a.lds;
-      if (k0 + 1 < a.n) {
-        const float2 v = *reinterpret_cast<const float2*>(srow + k0);  // lds % 4 == 0, k0 even
-        lg[ps][qi][0] = a.scale * v.x;
-        lg[ps][qi][1] = a.scale * v.y;
-      } else {
-        lg[ps][qi][0] = k0 < a.n ? a.scale * srow[k0] : -INFINITY;
-        lg[ps][qi][1] = -INFINITY;
-      }
-    }
-  }
-
-  // ---- the expansion table ----------------------------------------------------------------------
-  {
-    const uint32_t lo = (((uint32_t)tid >> 5) * 0x00204081u) & 0x01010101u;  // bit i of the nibble -> byte i
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const uint32_t hi = ((uint32_t)i * 0x00204081u) & 0x01010101u;
-      expand_s[tid + 512 * i] = make_uint2(lo, hi);
-    }
-  }
-
-  // ---- chunk maxima: logits per query, value norm ---------------------------------------------
-  {
-    float numax = 0.f;
-#pragma unroll
-    for (int ps = 0; ps < AT_PASSES; ++ps) numax = fmaxf(numax, fmaxf(nu[ps][0], nu[ps][1]));
-    numax = wave_max(numax);
-    float mx[4];
-#pragma unroll
-    for (int qi = 0; qi < 4; ++qi) {
-      float v = -INFINITY;
-#pragma unroll
-      for (int ps = 0; ps < AT_PASSES; ++ps) v = fmaxf(v, fmaxf(lg[ps][qi][0], lg[ps][qi][1]));
-      mx[qi] = wave_max(v);
-    }
-    if (lane < 4) red_s[wave * 4 + lane] = lane == 0 ? mx[0] : lane == 1 ? mx[1] : lane == 2 ? mx[2] : mx[3];
-    if (lane == 4) red_s[32 + wave * 4] = numax;
-  }
-  __syncthreads();
-  float m[4], numax = 0.f;
-#pragma unroll
-  for (int qi = 0; qi < 4; ++qi) {
-    m[qi] = -INFINITY;
-#pragma unroll
-    for (int w = 0; w < 8; ++w) m[qi] = fmaxf(m[qi], red_s[w * 4 + qi]);
-  }
-#pragma unroll
-  for (int w = 0; w < 8; ++w) numax = fmaxf(numax, red_s[32 + w * 4]);
-  int enu = 0;
-  if (numax > 0.f) (void)frexpf(numax, &enu);  // numax = f * 2^enu, f in [0.5, 1)
-  const float wscale = ldexpf(1.f, 26 - enu);  // weights exp(logit - m) * nu * wscale <= 2^26
-
-  const uint32_t copy_off = (uint32_t)(lane & (I8_COPIES - 1)) * 8u;
-  const char* const table = reinterpret_cast<const char*>(expand_s);
-  auto expand16 = [&](uint32_t w, int h) -> v4i {  // bits [16 h, 16 h + 16) of w -> 16 bytes of 0/1
-    const uint32_t o0 = __builtin_amdgcn_perm(w, copy_off, h ? 0x0c0c0600u : 0x0c0c0400u);
-    const uint32_t o1 = __builtin_amdgcn_perm(w, copy_off, h ? 0x0c0c0700u : 0x0c0c0500u);
-    const uint2 lo = *reinterpret_cast<const uint2*>(table + o0);
-    const uint2 hi = *reinterpret_cast<const uint2*>(table + o1);
-    return v4i{(int)lo.x, (int)lo.y, (int)hi.x, (int)hi.y};
-  };
-  auto digits_sum = [&](const v4i& acc) -> float {  // D0 + 2^7 D1 + 2^14 D2 + 2^21 D3
-    return fmaf((float)acc[3], 2097152.f, (float)(acc[0] + acc[1] * 128 + acc[2] * 16384));
-  };
-
-  float f[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};  // coordinate 16 cb + col of query kc
-  float ftot = 0.f;                                         // sum of the integer weights of query kc
-  float lsum[4] = {0.f, 0.f, 0.f, 0.f};
-  const v4i ones = v4i{0x01010101, 0x01010101, 0x01010101, 0x01010101};
-
-#pragma unroll
-  for (int ps = 0; ps < AT_PASSES; ++ps) {
-    // weights of this lane's two keys -> digits
-#pragma unroll
-    for (int qi = 0; qi < 4; ++qi) {
-      int dg[2][4];
-#pragma unroll
-      for (int e = 0; e < 2; ++e) {
-        const float p = expf(lg[ps][qi][e] - m[qi]);  // 0 for keys past the end (logit -inf)
-        lsum[qi] += p;
-        const int Q = __float2int_rn(p * nu[ps][e] * wscale);
-        const int d0 = ((Q + 64) & 127) - 64;
-        const int Q1 = (Q - d0) >> 7;
-        const int d1 = ((Q1 + 64) & 127) - 64;
-        const int Q2 = (Q1 - d1) >> 7;
-        const int d2 = ((Q2 + 64) & 127) - 64;
-        dg[e][0] = d0; dg[e][1] = d1; dg[e][2] = d2; dg[e][3] = (Q2 - d2) >> 7;
-      }
-#pragma unroll
-      for (int t = 0; t < 4; ++t)
-        *reinterpret_cast<unsigned short*>(wd + (qi * 4 + t) * AT_WAVE_KEYS + 2 * lane) =
-            (unsigned short)((dg[0][t] & 0xff) | ((dg[1][t] & 0xff) << 8));
-    }
-    // value code words: 16 keys x 32 coordinates -> 32 coordinates x 16 keys
-#pragma unroll
-    for (int r = 0; r < ROUNDS; ++r) {
-      const int plane = ph + 2 * r;
-      transpose16x32(vw[r]);
-      if (plane < VB) {
-        // word c: low half = coordinate 32 tg + c, high half = coordinate 32 tg + 16 + c.  Odd key blocks swap
-        // the halves of a row of 32 words, which keeps the reads below free of bank conflicts.
-        uint4* dst = reinterpret_cast<uint4*>(xch + plane * (8 * 8 * 64) + kb * 64 + ((tg ^ (kb & 1)) * 16));
-#pragma unroll
-        for (int c = 0; c < 4; ++c) dst[c] = make_uint4(vw[r][4 * c], vw[r][4 * c + 1], vw[r][4 * c + 2], vw[r][4 * c + 3]);
-      }
-    }
-    if (ps + 1 < AT_PASSES) load_codes(ps + 1);
-    __syncthreads();
-
-    v4i aop[2];
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk) aop[kk] = *reinterpret_cast<const v4i*>(wd + col * AT_WAVE_KEYS + kk * 64 + kc * 16);
-    {
-      v4i tot = v4i{0, 0, 0, 0};
-#pragma unroll
-      for (int kk = 0; kk < 2; ++kk) tot = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[kk], ones, tot, 0, 0, 0);
-      ftot += digits_sum(tot);
-    }
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      uint32_t pw[2][VB];
-#pragma unroll
-      for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-        for (int pl = 0; pl < VB; ++pl)
-          pw[kk][pl] = xch[pl * (8 * 8 * 64) + (4 * kk + kc) * 64 + ((g ^ (kc & 1)) * 16) + col];
-#pragma unroll
-      for (int mset = 1; mset < (1 << VB); ++mset) {
-        if (!i8_term(mset)) continue;
-        uint32_t mk[2] = {0u, 0u};
-#pragma unroll
-        for (int pl = 0; pl < VB; ++pl)
-          if (mset & (1 << pl)) {
-            mk[0] ^= pw[0][pl];
-            mk[1] ^= pw[1][pl];
-          }
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          v4i acc = v4i{0, 0, 0, 0};
-#pragma unroll
-          for (int kk = 0; kk < 2; ++kk) acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[kk], expand16(mk[kk], h), acc, 0, 0, 0);
-          f[2 * g + h] = fmaf(cf.c[mset], digits_sum(acc), f[2 * g + h]);
-        }
-      }
-    }
-    __syncthreads();  // the digit and exchange areas are rewritten by the next pass / the final sums
-  }
-
-  // ---- join the wavefronts ------------------------------------------------------------------------
-#pragma unroll
-  for (int qi = 0; qi < 4; ++qi) lsum[qi] = wave_sum_f(lsum[qi]);
-  if (lane < 4) red_s[64 + wave * 4 + lane] = lane == 0 ? lsum[0] : lane == 1 ? lsum[1] : lane == 2 ? lsum[2] : lsum[3];
-#pragma unroll
-  for (int cb = 0; cb < 8; ++cb) fsum_s[(wave * 4 + kc) * 128 + 16 * cb + col] = fmaf(cf.c[0], ftot, f[cb]);
-  __syncthreads();
-  const int qi = tid >> 7, j = tid & 127;
-  if (q0 + qi < a.q_per_group) {
-    float acc = 0.f;
-#pragma unroll
-    for (int w = 0; w < 8; ++w) acc += fsum_s[(w * 4 + qi) * 128 + j];
-    float* o = a.part + (((int64_t)group * a.q_per_group + q0 + qi) * a.nchunks + chunk) * attend_part_stride(128);
-    o[4 + j] = acc * ldexpf(1.f, enu - 26);
-    o[4 + 128 + j] = 0.f;
-    if (j == 0) {
-      float l = 0.f;
-#pragma unroll
-      for (int w = 0; w < 8; ++w) l += red_s[64 + w * 4 + qi];
-      o[0] = m[qi];
-      o[1] = l;
-    }
-  }
-}
-
-template <int VB>
-hipError_t launch_vb(const AttendArgs& a, const Coefs& cf, int n_groups, hipStream_t s) {
-  constexpr int lds = attend128_lds(VB);
-  static bool attr_done = false;  // per instantiation: the limit has to be raised once
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend128_kernel<VB>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
-  const dim3 grid(a.nchunks, n_groups, (a.q_per_group + 3) / 4);
-  hipLaunchKernelGGL(attend128_kernel<VB>, grid, dim3(512), lds, s, a, cf);
-  return hipGetLastError();
-}
-
-}  // namespace
 
 int attend128_chunks(int64_t n) { return (int)((n + AT_CHUNK - 1) / AT_CHUNK); }
 
@@ -315,15 +14,21 @@ bool attend128_applicable(int d, bool prod, const Codebook& cb) {
   return d == 128 && !prod && cb.bits >= 1 && cb.bits <= 4 && i8_coefficients(cb.bits, cb, coef);
 }
 
-hipError_t launch_attend128(const AttendArgs& a, int n_groups, hipStream_t s) {
+// ka == nullptr: logits from a.scores; otherwise the scoring body runs in the same kernel on key codes of
+// kb index bits (kprod: with the sign sketch)
+hipError_t launch_attend128(int kb, bool kprod, const ScoreI8Args* ka, const AttendArgs& a, int n_groups, hipStream_t s) {
   if (a.nchunks == 0 || n_groups == 0 || a.q_per_group == 0) return hipSuccess;
-  Coefs cf;
+  AttendCoefs cf;
   if (a.d != 128 || !i8_coefficients(a.cb.bits, a.cb, cf.c)) return hipErrorInvalidValue;
+  ScoreI8Args none;
+  std::memset(&none, 0, sizeof(none));
+  const ScoreI8Args& k = ka != nullptr ? *ka : none;
+  if (ka == nullptr) kb = -1;
   switch (a.cb.bits) {
-    case 1: return launch_vb<1>(a, cf, n_groups, s);
-    case 2: return launch_vb<2>(a, cf, n_groups, s);
-    case 3: return launch_vb<3>(a, cf, n_groups, s);
-    case 4: return launch_vb<4>(a, cf, n_groups, s);
+    case 1: return launch_attend128_v1(kb, kprod, k, a, cf, n_groups, s);
+    case 2: return launch_attend128_v2(kb, kprod, k, a, cf, n_groups, s);
+    case 3: return launch_attend128_v3(kb, kprod, k, a, cf, n_groups, s);
+    case 4: return launch_attend128_v4(kb, kprod, k, a, cf, n_groups, s);
     default: return hipErrorInvalidValue;
   }
 }

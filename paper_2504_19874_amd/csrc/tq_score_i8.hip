@@ -45,6 +45,8 @@
 // therefore replicated 32 times, copy c = lane % 32 living in banks 2c, 2c+1
 // (entry e of copy c at dword 64 e + 2 c): every lookup is conflict free.  The
 // 64 KB table is filled while the code words are in flight.
+#include <cstring>
+
 #include "tq_score_i8.h"
 
 #include <type_traits>
@@ -467,6 +469,21 @@ bool score_i8_applicable(int bits, int d, const Codebook& cb) {
   for (int sset = 1; sset < (1 << bits); ++sset)
     if (!i8_term(sset) && w[sset] != 0.0) return false;  // not symmetric about zero
   return true;
+}
+
+// Arguments of the single-kernel d = 128 path (tq_score_i8_128_body.h) for callers that run it inside a
+// kernel of their own; false when that path does not take these codes.
+bool score128_args(int bits, bool prod, const float* PiT, const float* ST, const float* q, int64_t ldq,
+                   const uint32_t* idx, const uint32_t* qjl, const float* gamma, const float* norm, int64_t n,
+                   int n_groups, int q_per_group, float kappa, const Codebook& cb, ScoreI8Args* a) {
+  const auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
+  if (bits < 0 || bits > 4 || !(bits > 0 || prod)) return false;
+  if (bits > 0 && (PiT == nullptr || idx == nullptr || !al16(idx))) return false;
+  if (prod && (ST == nullptr || qjl == nullptr || gamma == nullptr || !al16(qjl))) return false;
+  std::memset(a, 0, sizeof(*a));
+  a->PiT = PiT; a->ST = ST; a->x = q; a->ldx = ldq; a->idx = idx; a->qjl = qjl; a->gamma = gamma; a->norm = norm;
+  a->n = n; a->total_rows = (int64_t)n_groups * n; a->d = 128; a->q_per_group = q_per_group; a->kappa = kappa;
+  return i8_coefficients(bits, cb, a->coef);
 }
 
 hipError_t launch_score_i8(int bits, bool prod, const float* Pi, const float* S, const float* PiT, const float* ST,

@@ -1,289 +1,28 @@
-// Few queries per code at d = 128 (attention logits against a quantised key
-// cache, Sec. 4.3): one kernel does everything.  The arithmetic is that of
-// tq_score_i8.hip (masked sums of fixed-point query digits on
-// v_mfma_i32_16x16x64_i8, Walsh terms of a symmetric codebook); what differs is
-// how the data gets to the matrix cores.
-//
-// Measured with cycle stamps inside the kernel: what a workgroup waits for is
-// neither HBM as such nor the MFMAs but its own loads.  A compute unit takes in
-// only 10-14 bytes per clock (outstanding misses x line size / latency), and a
-// lane that fetches its own 8-byte share of 16 different code rows makes the
-// memory pipeline touch every cache line four times on top of that.  So here
-//   * a wavefront reads the codes of its keys as plain contiguous 16-byte-per-
-//     lane loads (1 KB per instruction) and parks them in a private LDS region;
-//     the tiles later pick their words out of LDS in operand order,
-//   * the workgroup prepares its own four queries while those loads are in
-//     flight (y = Pi q and S q from the transposed matrices, column per thread,
-//     query coordinates through scalar registers; then digits into LDS).  That
-//     re-reads 128 KB of matrices per workgroup, which is cheaper than the
-//     launch-and-latency chain of a preparation kernel in front,
-//   * the 64 KB expansion table is filled in the same window.
-//
-// Workgroup = 512 threads = 8 wavefronts; a wavefront owns 256 consecutive keys
-// = 16 tiles of 16, staged ROUND tiles at a time.  grid = (ceil(n / 2048),
-// groups, ceil(queries per group / 4)).
-#include "tq_score_i8_prep.h"
-
-#include <type_traits>
+// Few queries per code at d = 128: the scoring kernel of tq_score_i8_128_body.h with the scores
+// stored to memory.
+#include "tq_score_i8_128_body.h"
 
 namespace tq {
 
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-constexpr int TILES_128 = 16;  // tiles per wavefront
-// tiles staged in LDS at a time: what fits beside the table within 160 KB
-__host__ __device__ constexpr int round_tiles(int bits) { return bits <= 3 ? 8 : 4; }
-// bytes of one wavefront's staging region: idx, qjl, gamma, norm of 16 * round_tiles rows
-__host__ __device__ constexpr int stage_bytes(int bits) { return 16 * round_tiles(bits) * (16 * bits + 16 + 4 + 4); }
-
 template <int BITS, bool PROD>
 __global__ __launch_bounds__(512) void score_i8_128_kernel(const ScoreI8Args a) {
-  __shared__ __attribute__((aligned(16))) uint2 expand_s[256 * I8_COPIES];  // [256][32]: byte -> one byte per bit
-  extern __shared__ __attribute__((aligned(16))) unsigned char dyn_s[];     // 8 staging regions, then the query preparation
-  constexpr int RT = round_tiles(BITS);
-  constexpr int ROWS = 16 * RT;               // rows staged per round
-  constexpr int ROUNDS = TILES_128 / RT;
-  constexpr int NM = (1 << BITS) - 1;
-  constexpr int NW = BITS > 0 ? BITS : 1;
-  constexpr int NI = ROWS * 16 * BITS / 1024;  // 1 KB loads per round: plane words
-  constexpr int NQ = PROD ? ROWS * 16 / 1024 : 0;  // sign words
-  constexpr int NR = ROWS / 64;                // row-per-lane loads per round: gamma, norm
-  constexpr int IDX_OFF = 0, QJL_OFF = ROWS * 16 * BITS, GAM_OFF = QJL_OFF + ROWS * 16, NRM_OFF = GAM_OFF + ROWS * 4;
-  constexpr int NT = (BITS > 0 ? (1 << (BITS > 0 ? BITS - 1 : 0)) : 0) + (PROD ? 1 : 0);  // masked sums per tile
-  constexpr int NTA = NT > 0 ? NT : 1;
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // in a scalar register: addresses built from it are uniform
-  const int col = lane & 15;   // key within a tile / row of A
-  const int kq = lane >> 4;    // k-chunk = plane-word group; also the query whose sums this lane receives
-  const int group = blockIdx.y;
-  const int q0 = blockIdx.z * 4;
-
-  unsigned char* const stage = dyn_s + wave * stage_bytes(BITS);
-  float* const part_s = reinterpret_cast<float*>(dyn_s + 8 * stage_bytes(BITS));        // [2][2][4][128]
-  signed char* const dig_s = reinterpret_cast<signed char*>(part_s + 2 * 2 * 4 * 128);  // [2][4][4][128]
-  float* const scal_s = reinterpret_cast<float*>(dig_s + 2 * 4 * 4 * 128);              // [2][4][4]
-
-  // ---- 1. this thread's column of the transposed matrix: 64 values of k ---------------------
-  I8Prep<(BITS > 0), PROD> prep;
-  prep.load(a, wave, tid);
-
-  // ---- 2. the codes of this wavefront's keys, as contiguous 16-byte pieces ---------------------
-  // Pieces past the end of the arrays are clamped onto the last one (never used: the
-  // scores of keys past the end are not stored).
-  const int64_t gbase = (int64_t)group * a.n;
-  const int64_t wave_key0 = ((int64_t)blockIdx.x * 8 + wave) * (16 * TILES_128);
-  const bool full = wave_key0 + 16 * TILES_128 <= a.n;  // uniform: no key of this wavefront is past the end
-  const int64_t wrow0 = gbase + wave_key0;
-  u32x4 ci[ROUNDS][NI > 0 ? NI : 1], cq[ROUNDS][NQ > 0 ? NQ : 1];
-  float cg[ROUNDS][NR], cn[ROUNDS][NR];
-  {
-    const u32x4* const idx16 = reinterpret_cast<const u32x4*>(a.idx);
-    const u32x4* const qjl16 = reinterpret_cast<const u32x4*>(a.qjl);
-    const int64_t idx_last = a.total_rows * BITS - 1, qjl_last = a.total_rows - 1;  // last 16-byte piece
-#pragma unroll
-    for (int r = 0; r < ROUNDS; ++r) {
-      const int64_t row0 = wrow0 + r * ROWS;
-#pragma unroll
-      for (int i = 0; i < NI; ++i) {
-        int64_t piece = row0 * BITS + i * 64 + lane;
-        if (!full) piece = piece < idx_last ? piece : idx_last;
-        ci[r][i] = idx16[piece];
-      }
-#pragma unroll
-      for (int i = 0; i < NQ; ++i) {
-        int64_t piece = row0 + i * 64 + lane;
-        if (!full) piece = piece < qjl_last ? piece : qjl_last;
-        cq[r][i] = qjl16[piece];
-      }
-#pragma unroll
-      for (int i = 0; i < NR; ++i) {
-        int64_t row = row0 + i * 64 + lane;
-        if (!full) row = row < a.total_rows - 1 ? row : a.total_rows - 1;
-        cg[r][i] = PROD ? a.gamma[row] : 0.f;
-        cn[r][i] = a.norm != nullptr ? a.norm[row] : 1.f;
-      }
-    }
-  }
-
-  // ---- 3. the expansion table, 32 bank-private copies, while all of that is in flight ------
-  // thread -> (entry tid/32 + 16 i, copy tid%32): consecutive threads write consecutive
-  // addresses; the low nibble of the entry is the thread's own, the high nibble is i
-  {
-    const uint32_t lo = (((uint32_t)tid >> 5) * 0x00204081u) & 0x01010101u;  // bit i of the nibble -> byte i
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const uint32_t hi = ((uint32_t)i * 0x00204081u) & 0x01010101u;
-      expand_s[tid + 512 * i] = make_uint2(lo, hi);
-    }
-  }
-
-  // ---- 4. rotate / sketch this workgroup's four queries, 5. fixed point --------------------------
-  prep.matvec(a, group, q0, part_s);
-  __syncthreads();
-  prep.digitise(a, q0, wave, lane, 0, part_s, dig_s, scal_s);
-  __syncthreads();  // table, digits and scalars are in LDS
-
-  // ---- 6. A operands: lane = row + 16 kq, row = 4 * query + digit ---------------------------
-  const int a_query = col >> 2, a_digit = col & 3;
-  const bool out_live = q0 + kq < a.q_per_group;
-  v4i ar[2], as_[2];
-  float r_inv = 0.f, r_sum = 0.f, s_inv = 0.f, s_sum = 0.f;
-#pragma unroll
-  for (int s = 0; s < 2; ++s) {
-    const int c0 = i8_coord0(s, kq);
-    ar[s] = v4i{0, 0, 0, 0};
-    as_[s] = v4i{0, 0, 0, 0};
-    if (BITS > 0) ar[s] = *reinterpret_cast<const v4i*>(dig_s + ((0 * 4 + a_query) * 4 + a_digit) * 128 + c0);
-    if (PROD) as_[s] = *reinterpret_cast<const v4i*>(dig_s + ((1 * 4 + a_query) * 4 + a_digit) * 128 + c0);
-  }
-  if (BITS > 0) {
-    r_inv = scal_s[(0 * 4 + kq) * 4];
-    r_sum = scal_s[(0 * 4 + kq) * 4 + 1];
-  }
-  if (PROD) {
-    s_inv = scal_s[(1 * 4 + kq) * 4];
-    s_sum = scal_s[(1 * 4 + kq) * 4 + 1];
-  }
-
-  const uint32_t copy_off = (uint32_t)(lane & (I8_COPIES - 1)) * 8u;
-  const char* const table = reinterpret_cast<const char*>(expand_s);
-  // bits [16 h, 16 h + 16) of w -> 16 bytes of 0/1.  Table offset = 256 * byte + 8 * copy: one
-  // byte permute puts byte k of w into bits 8..15 above the copy offset in bits 0..7.
-  auto expand16 = [&](uint32_t w, int h) -> v4i {
-    const uint32_t o0 = __builtin_amdgcn_perm(w, copy_off, h ? 0x0c0c0600u : 0x0c0c0400u);
-    const uint32_t o1 = __builtin_amdgcn_perm(w, copy_off, h ? 0x0c0c0700u : 0x0c0c0500u);
-    const uint2 lo = *reinterpret_cast<const uint2*>(table + o0);
-    const uint2 hi = *reinterpret_cast<const uint2*>(table + o1);
-    return v4i{(int)lo.x, (int)lo.y, (int)hi.x, (int)hi.y};
+  __shared__ __attribute__((aligned(16))) uint2 expand_s[256 * I8_COPIES];
+  extern __shared__ __attribute__((aligned(16))) unsigned char dyn_s[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int q = blockIdx.z * 4 + (lane >> 4);
+  const bool out_live = q < a.q_per_group;
+  float* const out0 = a.scores + ((int64_t)blockIdx.y * a.q_per_group + (out_live ? q : 0)) * a.lds +
+                      ((int64_t)blockIdx.x * 8 + wave) * (16 * TILES_128) + (lane & 15);
+  auto sink = [&](int t, float score, bool key_live) {
+    if (out_live && key_live) out0[t * 16] = score;
   };
-  auto digits_sum = [&](const v4i& acc) -> float {  // D0 + 2^7 D1 + 2^14 D2
-    return (float)(acc[0] + acc[1] * 128 + acc[2] * 16384);
-  };
-
-  // per-lane constants of the final combination
-  float cr[NM > 0 ? NM : 1];
-#pragma unroll
-  for (int m = 1; m <= NM; ++m) cr[m - 1] = a.coef[m] * r_inv;
-  const float base_r = a.coef[0] * r_sum;
-  const float zs = 2.f * s_inv;
-  float* const out0 = a.scores + ((int64_t)group * a.q_per_group + q0 + kq) * a.lds + wave_key0 + col;
-
-  // ---- 7. tiles ------------------------------------------------------------------------------
-  // A four-stage software pipeline written out in source order: the words of tile t+2 are
-  // fetched from the staging region, the table lookups of tile t+1 are issued, the MFMAs of
-  // tile t run and the sums of tile t-1 are combined and stored.  The staging region is
-  // private to the wavefront and LDS executes a wavefront's instructions in order, so the
-  // next round may be written as soon as the last word fetch of the current one is issued.
-  // words of four tiles in flight (ring indexed by tile % 4)
-  uint32_t wp[4][NW], wz[4];
-  float wkg[4], wnu[4];
-  auto put_round = [&](int r) {
-#pragma unroll
-    for (int i = 0; i < NI; ++i) *reinterpret_cast<u32x4*>(stage + IDX_OFF + (i * 64 + lane) * 16) = ci[r][i];
-#pragma unroll
-    for (int i = 0; i < NQ; ++i) *reinterpret_cast<u32x4*>(stage + QJL_OFF + (i * 64 + lane) * 16) = cq[r][i];
-#pragma unroll
-    for (int i = 0; i < NR; ++i) {
-      if (PROD) *reinterpret_cast<float*>(stage + GAM_OFF + (i * 64 + lane) * 4) = cg[r][i];
-      *reinterpret_cast<float*>(stage + NRM_OFF + (i * 64 + lane) * 4) = cn[r][i];
-    }
-  };
-  auto fetch = [&](int t) {
-    const int lr = (t % RT) * 16 + col;  // row within the staged round
-#pragma unroll
-    for (int pl = 0; pl < BITS; ++pl)
-      wp[t & 3][pl] = *reinterpret_cast<const uint32_t*>(stage + IDX_OFF + ((lr * 4 + kq) * BITS + pl) * 4);
-    wz[t & 3] = PROD ? *reinterpret_cast<const uint32_t*>(stage + QJL_OFF + (lr * 4 + kq) * 4) : 0u;
-    wkg[t & 3] = PROD ? *reinterpret_cast<const float*>(stage + GAM_OFF + lr * 4) : 0.f;
-    wnu[t & 3] = *reinterpret_cast<const float*>(stage + NRM_OFF + lr * 4);
-  };
-  auto lookups = [&](int t, int s, v4i (&b)[NTA]) {  // B operands of k-step s of tile t
-    int j = 0;
-#pragma unroll
-    for (int m = 1; m <= NM; ++m) {
-      if (!i8_term(m)) continue;
-      uint32_t x = 0u;
-#pragma unroll
-      for (int pl = 0; pl < BITS; ++pl)
-        if (m & (1 << pl)) x ^= wp[t & 3][pl];
-      b[j++] = expand16(x, s);
-    }
-    if (PROD) b[j] = expand16(wz[t & 3], s);
-  };
-  auto mfmas = [&](int s, const v4i (&b)[NTA], v4i (&c)[NTA]) {
-#pragma unroll
-    for (int j = 0; j < NT; ++j)
-      c[j] = __builtin_amdgcn_mfma_i32_16x16x64_i8((PROD && j == NT - 1) ? as_[s] : ar[s], b[j], c[j], 0, 0, 0);
-  };
-  // with few masked sums per tile the operands of the next tile are looked up while this
-  // tile's MFMAs run; with many there are no registers for that
-  constexpr bool PIPE = NTA <= 3;
-  auto run_tiles = [&](auto full_c) {
-    constexpr bool FULL = decltype(full_c)::value;
-    v4i bop[PIPE ? 2 : 1][2][NTA];
-    v4i acc[2][NTA];
-    auto finish = [&](int t) {
-      const v4i(&c)[NTA] = acc[t & 1];
-      float total = base_r;
-      int j = 0;
-#pragma unroll
-      for (int m = 1; m <= NM; ++m)
-        if (i8_term(m)) total = fmaf(cr[m - 1], digits_sum(c[j++]), total);
-      if (PROD) total = fmaf(a.kappa * wkg[t & 3], fmaf(zs, digits_sum(c[NT - 1]), -s_sum), total);
-      total *= wnu[t & 3];
-      if (out_live && (FULL || wave_key0 + t * 16 + col < a.n)) out0[t * 16] = total;
-    };
-    // everything needed before tile t's words can be fetched
-    auto stage_for = [&](int t) {
-      if (t % RT == 0) put_round(t / RT);
-    };
-    stage_for(0);
-    fetch(0);
-    if (PIPE) {
-      lookups(0, 0, bop[0][0]);
-      lookups(0, 1, bop[0][1]);
-    }
-    stage_for(1);
-    fetch(1);
-    // tiles that have at least one key (uniform over the wavefront)
-    const int live_tiles = FULL ? TILES_128 : (int)((a.n - wave_key0 + 15) >> 4);
-#pragma unroll
-    for (int t = 0; t < TILES_128; ++t) {
-      if (FULL || t < live_tiles) {
-        if (t + 2 < TILES_128) {
-          stage_for(t + 2);
-          fetch(t + 2);
-        }
-#pragma unroll
-        for (int j = 0; j < NTA; ++j) acc[t & 1][j] = v4i{0, 0, 0, 0};
-        if (PIPE) {
-          if (t + 1 < TILES_128) {
-            lookups(t + 1, 0, bop[(t + 1) & 1][0]);
-            lookups(t + 1, 1, bop[(t + 1) & 1][1]);
-          }
-          mfmas(0, bop[t & 1][0], acc[t & 1]);
-          mfmas(1, bop[t & 1][1], acc[t & 1]);
-        } else {
-          lookups(t, 0, bop[0][0]);
-          lookups(t, 1, bop[0][1]);
-          mfmas(0, bop[0][0], acc[t & 1]);
-          mfmas(1, bop[0][1], acc[t & 1]);
-        }
-      }
-      if (t > 0 && (FULL || t - 1 < live_tiles)) finish(t - 1);
-    }
-    if (FULL || TILES_128 - 1 < live_tiles) finish(TILES_128 - 1);
-  };
-  if (full) run_tiles(std::true_type{});
-  else run_tiles(std::false_type{});
+  score128_body<BITS, PROD>(a, expand_s, dyn_s, sink);
 }
 
 template <int BITS, bool PROD>
 static hipError_t launch_128(const ScoreI8Args& a, int n_groups, hipStream_t s) {
-  constexpr int lds = 8 * stage_bytes(BITS) + I8_PREP_BYTES;  // on top of the 64 KB table
+  constexpr int lds = score128_lds(BITS);  // on top of the 64 KB table
   static_assert(I8_TABLE_BYTES + lds <= 160 * 1024, "LDS budget");
   const int64_t per_wg = 8 * 16 * TILES_128;
   const dim3 grid((unsigned)((a.n + per_wg - 1) / per_wg), n_groups, (a.q_per_group + 3) / 4);

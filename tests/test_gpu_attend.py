@@ -87,6 +87,17 @@ CASES = [
 
 @pytest.mark.parametrize("d,kb,kprod,vb,vprod,n_groups,qpg,npg", CASES)
 def test_attend(d, kb, kprod, vb, vprod, n_groups, qpg, npg):
+    run_attend(d, kb, kprod, vb, vprod, n_groups, qpg, npg, True)
+
+
+@pytest.mark.parametrize("d,kb,kprod,vb,vprod,n_groups,qpg,npg", [c for c in CASES if c[0] == 128 and not c[4]][:4])
+def test_attend_with_scores_from_a_scoring_call(d, kb, kprod, vb, vprod, n_groups, qpg, npg):
+    """Without the transposed key matrices the keys are scored by tq_score's kernels first and the
+    read-out kernel takes the logits from memory."""
+    run_attend(d, kb, kprod, vb, vprod, n_groups, qpg, npg, False)
+
+
+def run_attend(d, kb, kprod, vb, vprod, n_groups, qpg, npg, key_transposes):
     pk, Pik, Sk, ck = setup(d, kb, kprod, 100, 200)
     pv, Piv, Sv, cv = setup(d, vb, vprod, 300, 400)
     n, nq = n_groups * npg, n_groups * qpg
@@ -101,7 +112,13 @@ def test_attend(d, kb, kprod, vb, vprod, n_groups, qpg, npg):
     p_want = np.concatenate([o.attend(q[g * qpg:(g + 1) * qpg], kt[g * npg:(g + 1) * npg], np.eye(npg), scale)
                              for g in range(n_groups)])
     out = torch.full((nq, d), float("nan"), dtype=torch.float32, device=DEV)
-    tq.tq_attend(pk, pv, dev(q), n_groups, qpg, k_dev, v_dev, npg, scale, out)
+    keep = pk.c.PiT
+    if not key_transposes:
+        pk.c.PiT = 0
+    try:
+        tq.tq_attend(pk, pv, dev(q), n_groups, qpg, k_dev, v_dev, npg, scale, out)
+    finally:
+        pk.c.PiT = keep
     check_attend(out.cpu().numpy().astype(np.float64), want, q, scale, k_codes[3], vt, p_want, d, n_groups, qpg, npg)
 
 
