@@ -100,6 +100,21 @@ __global__ __launch_bounds__(256) void attend_values_kernel(const AttendArgs a) 
   }
 }
 
+// sum_j W[j * ld] * y[j] over j in [j0, j0 + count), 16 loads in flight
+__device__ __forceinline__ float strided_dot(const float* W, int64_t ld, const float* y, int j0, int count) {
+  float acc = 0.f;
+  int j = j0;
+  for (; j + 16 <= j0 + count; j += 16) {
+    float v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) v[u] = W[(int64_t)(j + u) * ld];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) acc = fmaf(v[u], y[j + u], acc);
+  }
+  for (; j < j0 + count; ++j) acc = fmaf(W[(int64_t)j * ld], y[j], acc);
+  return acc;
+}
+
 // one workgroup per query: join the chunks, then back to the original basis
 __global__ __launch_bounds__(256) void attend_combine_kernel(const float* part, int nchunks, int d, const float* Pi,
                                                              const float* S, float kappa, float* out, int64_t ldo) {
@@ -111,11 +126,18 @@ __global__ __launch_bounds__(256) void attend_combine_kernel(const float* part, 
   const int tid = threadIdx.x;
   const int stride = attend_part_stride(d);
   const float* p = part + (int64_t)blockIdx.x * nchunks * stride;
-  float mx = -INFINITY;
-  for (int c = tid; c < nchunks; c += 256) mx = fmaxf(mx, p[(int64_t)c * stride]);
+  // thread c holds (m, l) of chunk c; the common case has no more chunks than threads
+  const float2 ml0 = tid < nchunks ? *reinterpret_cast<const float2*>(p + (int64_t)tid * stride) : make_float2(-INFINITY, 0.f);
+  float mx = ml0.x;
+  for (int c = tid + 256; c < nchunks; c += 256) mx = fmaxf(mx, p[(int64_t)c * stride]);
   const float M = block_reduce(mx, true, red_s, tid);
   float ls = 0.f;
-  for (int c = tid; c < nchunks; c += 256) {
+  if (tid < nchunks) {
+    const float e = expf(ml0.x - M);
+    e_s[tid] = e;
+    ls = e * ml0.y;
+  }
+  for (int c = tid + 256; c < nchunks; c += 256) {
     const float e = expf(p[(int64_t)c * stride] - M);
     e_s[c] = e;
     ls = fmaf(e, p[(int64_t)c * stride + 1], ls);
@@ -124,8 +146,15 @@ __global__ __launch_bounds__(256) void attend_combine_kernel(const float* part, 
   const float invL = L > 0.f ? 1.f / L : 0.f;            // no keys at all: the output is zero
   for (int j = tid; j < (S != nullptr ? 2 * d : d); j += 256) {
     float acc = 0.f;
-#pragma unroll 8
-    for (int c = 0; c < nchunks; ++c) acc = fmaf(e_s[c], p[(int64_t)c * stride + 4 + j], acc);
+    int c = 0;
+    for (; c + 32 <= nchunks; c += 32) {  // 32 loads in flight
+      float v[32];
+#pragma unroll
+      for (int u = 0; u < 32; ++u) v[u] = p[(int64_t)(c + u) * stride + 4 + j];
+#pragma unroll
+      for (int u = 0; u < 32; ++u) acc = fmaf(e_s[c + u], v[u], acc);
+    }
+    for (; c < nchunks; ++c) acc = fmaf(e_s[c], p[(int64_t)c * stride + 4 + j], acc);
     y_s[j] = acc * invL;
   }
   __syncthreads();
@@ -137,12 +166,8 @@ __global__ __launch_bounds__(256) void attend_combine_kernel(const float* part, 
     float o = 0.f, oz = 0.f;
     if (k < d && part_ < parts) {
       const int j0 = part_ * span;
-#pragma unroll 8
-      for (int j = j0; j < j0 + span; ++j) o = fmaf(Pi[(int64_t)j * d + k], y_s[j], o);
-      if (S != nullptr) {
-#pragma unroll 8
-        for (int j = j0; j < j0 + span; ++j) oz = fmaf(S[(int64_t)j * d + k], y_s[d + j], oz);
-      }
+      o = strided_dot(Pi + k, d, y_s, j0, span);
+      if (S != nullptr) oz = strided_dot(S + k, d, y_s + d, j0, span);
     }
     o = fmaf(kappa, oz, o);
     if (parts > 1) {

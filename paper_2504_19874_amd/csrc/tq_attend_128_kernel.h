@@ -6,7 +6,7 @@
 // every query q and coordinate j
 //     sum_i w_qi c[idx_ij] = coef[0] * sum_i w_qi + sum_S coef[S] * sum_i w_qi x_S(idx_ij):
 // sums of weights over the KEYS selected by a bit mask.  The weights w_qi = exp(logit - m) * nu_i
-// are scaled by a power of two to 26-bit integers and split into four balanced base-128 digits;
+// are scaled by a power of two to 26-bit integers and split into four base-128 digits (0..127);
 // one v_mfma_i32_16x16x64_i8 multiplies the 16 rows (4 queries x 4 digits) with 64 keys x 16
 // coordinates of 0/1 bytes.
 //
@@ -123,27 +123,6 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
     }
   };
 
-  // ---- logits: lane (kc, col) holds those of (query q0 + kc, key wave_key0 + 16 t + col), t < 16 ----
-  float lg[16];
-#pragma unroll
-  for (int t = 0; t < 16; ++t) lg[t] = -INFINITY;
-  if (FUSED) {
-    auto sink = [&](int t, float score, bool key_live) { lg[t] = key_live ? a.scale * score : -INFINITY; };
-    score128_body<KB, KPROD>(ka, expand_s, dyn_s, sink);
-  } else {
-    const int64_t qrow = (int64_t)group * a.q_per_group + (q0 + kc < a.q_per_group ? q0 + kc : q0);
-    const float* srow = a.scores + qrow * a.lds + wave_key0 + col;
-#pragma unroll
-    for (int t = 0; t < 16; ++t)
-      if (wave_key0 + 16 * t + col < a.n) lg[t] = a.scale * srow[16 * t];
-    const uint32_t lo = (((uint32_t)tid >> 5) * 0x00204081u) & 0x01010101u;  // the expansion table
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const uint32_t hi = ((uint32_t)i * 0x00204081u) & 0x01010101u;
-      expand_s[tid + 512 * i] = make_uint2(lo, hi);
-    }
-  }
-  load_codes(0);
   // value norms: lane L holds those of keys L, L + 64, L + 128, L + 192 of the wavefront
   float nuv[4];
 #pragma unroll
@@ -151,6 +130,33 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
     const int64_t key = wave_key0 + 64 * e + lane;
     nuv[e] = key < a.n ? a.norm[gbase + key] : 0.f;
   }
+  // the first pass's value codes travel while the keys are scored, where the registers allow it
+  constexpr bool EARLY = !FUSED || KB + (KPROD ? 1 : 0) <= 4;
+  if (EARLY) load_codes(0);
+
+  // ---- logits: lane (kc, col) holds those of (query q0 + kc, key wave_key0 + 16 t + col), t < 16 ----
+  // (kept in units of log 2, so that the weights are one v_exp_f32 each)
+  float lg[16];
+  const float scale2 = a.scale * 1.44269504088896341f;
+#pragma unroll
+  for (int t = 0; t < 16; ++t) lg[t] = -INFINITY;
+  if (FUSED) {
+    auto sink = [&](int t, float score, bool key_live) { lg[t] = key_live ? scale2 * score : -INFINITY; };
+    score128_body<KB, KPROD>(ka, expand_s, dyn_s, sink);
+  } else {
+    const int64_t qrow = (int64_t)group * a.q_per_group + (q0 + kc < a.q_per_group ? q0 + kc : q0);
+    const float* srow = a.scores + qrow * a.lds + wave_key0 + col;
+#pragma unroll
+    for (int t = 0; t < 16; ++t)
+      if (wave_key0 + 16 * t + col < a.n) lg[t] = scale2 * srow[16 * t];
+    const uint32_t lo = (((uint32_t)tid >> 5) * 0x00204081u) & 0x01010101u;  // the expansion table
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const uint32_t hi = ((uint32_t)i * 0x00204081u) & 0x01010101u;
+      expand_s[tid + 512 * i] = make_uint2(lo, hi);
+    }
+  }
+  if (!EARLY) load_codes(0);
 
   // ---- chunk maxima: logits per query, value norm ---------------------------------------------
   {
@@ -193,24 +199,20 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
 
 #pragma unroll
   for (int ps = 0; ps < AT_PASSES; ++ps) {
-    // weights of this lane's (query, key) pairs -> four balanced base-128 digits
+    // weights of this lane's (query, key) pairs -> four base-128 digits
 #pragma unroll
     for (int tt = 0; tt < 8; ++tt) {
       const int t = 8 * ps + tt;
       const float nu = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (16 * (t & 3) + col), __float_as_int(nuv[t >> 2])));
-      const float p = expf(lg[t] - m);  // 0 for keys past the end (logit -inf)
+      const float p = __builtin_amdgcn_exp2f(lg[t] - m);  // 0 for keys past the end (logit -inf)
       lsum += p;
-      const int Q = __float2int_rn(p * nu * wscale);
-      const int d0 = ((Q + 64) & 127) - 64;
-      const int Q1 = (Q - d0) >> 7;
-      const int d1 = ((Q1 + 64) & 127) - 64;
-      const int Q2 = (Q1 - d1) >> 7;
-      const int d2 = ((Q2 + 64) & 127) - 64;
+      // the weight is not negative: plain base-128 digits 0..127 fit the signed bytes of the operand
+      const uint32_t Q = (uint32_t)__float2int_rn(p * nu * wscale);
       unsigned char* o = wd + (kc * 4) * AT_PASS_KEYS + 16 * tt + col;
-      o[0] = (unsigned char)d0;
-      o[AT_PASS_KEYS] = (unsigned char)d1;
-      o[2 * AT_PASS_KEYS] = (unsigned char)d2;
-      o[3 * AT_PASS_KEYS] = (unsigned char)((Q2 - d2) >> 7);
+      o[0] = (unsigned char)(Q & 127u);
+      o[AT_PASS_KEYS] = (unsigned char)((Q >> 7) & 127u);
+      o[2 * AT_PASS_KEYS] = (unsigned char)((Q >> 14) & 127u);
+      o[3 * AT_PASS_KEYS] = (unsigned char)(Q >> 21);
     }
     // value code words: 16 keys x 32 coordinates -> 32 coordinates x 16 keys
 #pragma unroll
@@ -288,7 +290,7 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
         l += red_s[64 + w * 4 + qi];
         mq = fmaxf(mq, red_s[w * 4 + qi]);
       }
-      o[0] = mq;
+      o[0] = mq * 0.693147180559945309f;  // back to natural units
       o[1] = l;
     }
   }
