@@ -100,16 +100,16 @@ __global__ __launch_bounds__(256) void attend_values_kernel(const AttendArgs a) 
   }
 }
 
-// sum_j W[j * ld] * y[j] over j in [j0, j0 + count), 16 loads in flight
+// sum_j W[j * ld] * y[j] over j in [j0, j0 + count), 32 loads in flight
 __device__ __forceinline__ float strided_dot(const float* W, int64_t ld, const float* y, int j0, int count) {
   float acc = 0.f;
   int j = j0;
-  for (; j + 16 <= j0 + count; j += 16) {
-    float v[16];
+  for (; j + 32 <= j0 + count; j += 32) {
+    float v[32];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) v[u] = W[(int64_t)(j + u) * ld];
+    for (int u = 0; u < 32; ++u) v[u] = W[(int64_t)(j + u) * ld];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) acc = fmaf(v[u], y[j + u], acc);
+    for (int u = 0; u < 32; ++u) acc = fmaf(v[u], y[j + u], acc);
   }
   for (; j < j0 + count; ++j) acc = fmaf(W[(int64_t)j * ld], y[j], acc);
   return acc;
@@ -126,36 +126,63 @@ __global__ __launch_bounds__(256) void attend_combine_kernel(const float* part, 
   const int tid = threadIdx.x;
   const int stride = attend_part_stride(d);
   const float* p = part + (int64_t)blockIdx.x * nchunks * stride;
-  // thread c holds (m, l) of chunk c; the common case has no more chunks than threads
-  const float2 ml0 = tid < nchunks ? *reinterpret_cast<const float2*>(p + (int64_t)tid * stride) : make_float2(-INFINITY, 0.f);
-  float mx = ml0.x;
-  for (int c = tid + 256; c < nchunks; c += 256) mx = fmaxf(mx, p[(int64_t)c * stride]);
-  const float M = block_reduce(mx, true, red_s, tid);
-  float ls = 0.f;
-  if (tid < nchunks) {
-    const float e = expf(ml0.x - M);
-    e_s[tid] = e;
-    ls = e * ml0.y;
-  }
-  for (int c = tid + 256; c < nchunks; c += 256) {
-    const float e = expf(p[(int64_t)c * stride] - M);
-    e_s[c] = e;
-    ls = fmaf(e, p[(int64_t)c * stride + 1], ls);
-  }
-  const float L = block_reduce(ls, false, red_s, tid);  // its barriers also publish e_s
-  const float invL = L > 0.f ? 1.f / L : 0.f;            // no keys at all: the output is zero
-  for (int j = tid; j < (S != nullptr ? 2 * d : d); j += 256) {
-    float acc = 0.f;
-    int c = 0;
-    for (; c + 32 <= nchunks; c += 32) {  // 32 loads in flight
-      float v[32];
+  const int jmax = S != nullptr ? 2 * d : d;
+  if (nchunks == 0) {
+    for (int j = tid; j < jmax; j += 256) y_s[j] = 0.f;  // no keys at all: the output is zero
+  } else if (nchunks <= 32) {
+    // the common case: every load of the joining step is issued at once (the chunk maxima and sums through
+    // scalar registers), and every thread derives M and L for itself
+    for (int j0 = 0; j0 < jmax; j0 += 256) {
+      const int j = j0 + tid, jc = j < jmax ? j : jmax - 1;
+      float v[32], mc[32], lc[32];
 #pragma unroll
-      for (int u = 0; u < 32; ++u) v[u] = p[(int64_t)(c + u) * stride + 4 + j];
+      for (int u = 0; u < 32; ++u) {  // unconditional loads (clamped), selected afterwards
+        const int64_t base = (int64_t)(u < nchunks ? u : nchunks - 1) * stride;
+        v[u] = p[base + 4 + jc];
+        mc[u] = p[base];
+        lc[u] = p[base + 1];
+      }
 #pragma unroll
-      for (int u = 0; u < 32; ++u) acc = fmaf(e_s[c + u], v[u], acc);
+      for (int u = 0; u < 32; ++u)
+        if (u >= nchunks) mc[u] = -INFINITY;
+      float M = mc[0];
+#pragma unroll
+      for (int u = 1; u < 32; ++u) M = fmaxf(M, mc[u]);
+      float L = 0.f, acc = 0.f;
+#pragma unroll
+      for (int u = 0; u < 32; ++u) {
+        const float e = expf(mc[u] - M);  // 0 past the last chunk
+        L = fmaf(e, lc[u], L);
+        acc = fmaf(e, v[u], acc);
+      }
+      if (j < jmax) y_s[j] = acc / L;
     }
-    for (; c < nchunks; ++c) acc = fmaf(e_s[c], p[(int64_t)c * stride + 4 + j], acc);
-    y_s[j] = acc * invL;
+  } else {
+    // thread c holds (m, l) of chunk c, c + 256, ...
+    float mx = -INFINITY;
+    for (int c = tid; c < nchunks; c += 256) mx = fmaxf(mx, p[(int64_t)c * stride]);
+    const float M = block_reduce(mx, true, red_s, tid);
+    float ls = 0.f;
+    for (int c = tid; c < nchunks; c += 256) {
+      const float e = expf(p[(int64_t)c * stride] - M);
+      e_s[c] = e;
+      ls = fmaf(e, p[(int64_t)c * stride + 1], ls);
+    }
+    const float L = block_reduce(ls, false, red_s, tid);  // its barriers also publish e_s
+    const float invL = L > 0.f ? 1.f / L : 0.f;
+    for (int j = tid; j < jmax; j += 256) {
+      float acc = 0.f;
+      int c = 0;
+      for (; c + 32 <= nchunks; c += 32) {  // 32 loads in flight
+        float v[32];
+#pragma unroll
+        for (int u = 0; u < 32; ++u) v[u] = p[(int64_t)(c + u) * stride + 4 + j];
+#pragma unroll
+        for (int u = 0; u < 32; ++u) acc = fmaf(e_s[c + u], v[u], acc);
+      }
+      for (; c < nchunks; ++c) acc = fmaf(e_s[c], p[(int64_t)c * stride + 4 + j], acc);
+      y_s[j] = acc * invL;
+    }
   }
   __syncthreads();
   // out[k] = sum_j Pi[j][k] y[j] + kappa sum_j S[j][k] z[j]; for small d the j range is split over the threads
