@@ -441,9 +441,10 @@ size_t tq_attend_workspace_bytes(const tq_params* pk, const tq_params* pv, int32
                                  int64_t n_per_group) {
   if (pk == nullptr || pv == nullptr || pk->d <= 0 || pv->d <= 0 || n_groups < 0 || q_per_group < 0 || n_per_group < 0)
     return 0;
-  // sized for the kernel with the shorter chunks, whichever the call then takes
+  // whichever kind of value code the call then brings
   const AttendPlan pl = attend_plan(pk, pv, true, (int64_t)n_groups * q_per_group, n_per_group);
-  return pl.scores_bytes + pl.part_bytes + pl.score_ws_bytes + 512;
+  const AttendPlan pm = attend_plan(pk, pv, false, (int64_t)n_groups * q_per_group, n_per_group);
+  return pl.scores_bytes + (pl.part_bytes > pm.part_bytes ? pl.part_bytes : pm.part_bytes) + pl.score_ws_bytes + 512;
 }
 
 tq_status tq_attend(const tq_params* pk, const tq_params* pv, const float* q, int64_t ldq, int32_t n_groups,
@@ -484,7 +485,7 @@ tq_status tq_attend(const tq_params* pk, const tq_params* pv, const float* q, in
                        score128_args(pk->bits_mse, k_prod, pk->PiT, pk->ST, q, ldq, k_idx, k_qjl, k_gamma, k_norm,
                                      n_per_group, n_groups, q_per_group, kappa_of(128), make_codebook(pk), &ka);
     if (fused) {
-      if (launch_attend128(pk->bits_mse, k_prod, &ka, a, n_groups, s) != hipSuccess) return TQ_ERR_HIP;
+      if (launch_attend128(pk->bits_mse, k_prod, &ka, v_prod, a, n_groups, s) != hipSuccess) return TQ_ERR_HIP;
     } else {
       tq_params pk_inner = *pk;  // the scoring call carves its own needs from what is left
       pk_inner.workspace = rest;
@@ -492,7 +493,7 @@ tq_status tq_attend(const tq_params* pk, const tq_params* pv, const float* q, in
       st = tq_score(&pk_inner, q, ldq, n_groups, q_per_group, k_idx, k_qjl, k_gamma, k_norm, n_per_group, scores,
                     pl.ld_scores, 0, nullptr, nullptr, stream);
       if (st != TQ_OK) return st;
-      if ((pl.fast ? launch_attend128(0, false, nullptr, a, n_groups, s) : launch_attend_values(v_prod, a, n_groups, s)) !=
+      if ((pl.fast ? launch_attend128(0, false, nullptr, v_prod, a, n_groups, s) : launch_attend_values(v_prod, a, n_groups, s)) !=
           hipSuccess)
         return TQ_ERR_HIP;
     }

@@ -29,7 +29,8 @@ struct AttendArgs {
 int attend128_chunks(int64_t n);
 bool attend128_applicable(int d, bool prod, const Codebook& cb);
 struct ScoreI8Args;
-hipError_t launch_attend128(int kb, bool kprod, const ScoreI8Args* ka, const AttendArgs& a, int n_groups, hipStream_t s);
+hipError_t launch_attend128(int kb, bool kprod, const ScoreI8Args* ka, bool vprod, const AttendArgs& a, int n_groups,
+                            hipStream_t s);
 
 int attend_simple_chunks(int64_t n);
 hipError_t launch_attend_values(bool prod, const AttendArgs& a, int n_groups, hipStream_t s);

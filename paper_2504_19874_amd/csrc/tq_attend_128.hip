@@ -8,15 +8,17 @@ namespace tq {
 
 int attend128_chunks(int64_t n) { return (int)((n + AT_CHUNK - 1) / AT_CHUNK); }
 
-// value codes the kernel covers: d = 128, MSE codes of 1..4 bits, table symmetric about zero
+// value codes the kernel covers: d = 128, table symmetric about zero; codes of Alg. 1 with 1..4 index bits or
+// codes of Alg. 2 with 0..2
 bool attend128_applicable(int d, bool prod, const Codebook& cb) {
   float coef[16];
-  return d == 128 && !prod && cb.bits >= 1 && cb.bits <= 4 && i8_coefficients(cb.bits, cb, coef);
+  return d == 128 && cb.bits >= (prod ? 0 : 1) && cb.bits <= (prod ? 2 : 4) && i8_coefficients(cb.bits, cb, coef);
 }
 
 // ka == nullptr: logits from a.scores; otherwise the scoring body runs in the same kernel on key codes of
 // kb index bits (kprod: with the sign sketch)
-hipError_t launch_attend128(int kb, bool kprod, const ScoreI8Args* ka, const AttendArgs& a, int n_groups, hipStream_t s) {
+hipError_t launch_attend128(int kb, bool kprod, const ScoreI8Args* ka, bool vprod, const AttendArgs& a, int n_groups,
+                            hipStream_t s) {
   if (a.nchunks == 0 || n_groups == 0 || a.q_per_group == 0) return hipSuccess;
   AttendCoefs cf;
   if (a.d != 128 || !i8_coefficients(a.cb.bits, a.cb, cf.c)) return hipErrorInvalidValue;
@@ -24,6 +26,14 @@ hipError_t launch_attend128(int kb, bool kprod, const ScoreI8Args* ka, const Att
   std::memset(&none, 0, sizeof(none));
   const ScoreI8Args& k = ka != nullptr ? *ka : none;
   if (ka == nullptr) kb = -1;
+  if (vprod) {
+    switch (a.cb.bits) {
+      case 0: return launch_attend128_p0(kb, kprod, k, a, cf, n_groups, s);
+      case 1: return launch_attend128_p1(kb, kprod, k, a, cf, n_groups, s);
+      case 2: return launch_attend128_p2(kb, kprod, k, a, cf, n_groups, s);
+      default: return hipErrorInvalidValue;
+    }
+  }
   switch (a.cb.bits) {
     case 1: return launch_attend128_v1(kb, kprod, k, a, cf, n_groups, s);
     case 2: return launch_attend128_v2(kb, kprod, k, a, cf, n_groups, s);

@@ -5,7 +5,8 @@
 // subsets S of coef[S] * x_S(idx), x_S = XOR of the index bits in S (tq_score_i8.hip).  So for
 // every query q and coordinate j
 //     sum_i w_qi c[idx_ij] = coef[0] * sum_i w_qi + sum_S coef[S] * sum_i w_qi x_S(idx_ij):
-// sums of weights over the KEYS selected by a bit mask.  The weights w_qi = exp(logit - m) * nu_i
+// sums of weights over the KEYS selected by a bit mask.  The sign term of Alg. 2 is one more
+// such sum, over the sign bits with the weights exp(logit - m) * nu_i * gamma_i (VPROD).  The weights w_qi = exp(logit - m) * nu_i
 // are scaled by a power of two to 26-bit integers and split into four base-128 digits (0..127);
 // one v_mfma_i32_16x16x64_i8 multiplies the 16 rows (4 queries x 4 digits) with 64 keys x 16
 // coordinates of 0/1 bytes.
@@ -37,16 +38,17 @@ constexpr int AT_PASSES = AT_WAVE_KEYS / AT_PASS_KEYS;
 constexpr int AT_CHUNK = 8 * AT_WAVE_KEYS;
 constexpr int AT_WD_BYTES = 8 * 4 * 4 * AT_PASS_KEYS;  // weight digits [wave][query][digit][key]
 constexpr int AT_XCH_BYTES = 8 * 8 * 64 * 4;            // per plane: [wave][block of 16 keys][64 words]
-constexpr int AT_RED_FLOATS = 3 * 8 * 4;
+constexpr int AT_RED_FLOATS = 3 * 8 * 4;  // [maxima | norm maxima | sums][wave][4]
 
 // dynamic LDS: digits, exchange area (or, before them in time, what the scoring body needs), then the
 // reduction scratch, which is written while other wavefronts may still be scoring
-__host__ __device__ constexpr int attend128_work_bytes(int kb, int vb, bool fused) {
-  const int own = AT_WD_BYTES + vb * AT_XCH_BYTES;
+// (vprod: a second set of weight digits and the sign plane of the value codes)
+__host__ __device__ constexpr int attend128_work_bytes(int kb, int vb, bool vprod, bool fused) {
+  const int own = (vprod ? 2 : 1) * AT_WD_BYTES + (vb + (vprod ? 1 : 0)) * AT_XCH_BYTES;
   return fused && score128_lds(kb) > own ? score128_lds(kb) : own;
 }
-__host__ __device__ constexpr int attend128_lds(int kb, int vb, bool fused) {
-  return attend128_work_bytes(kb, vb, fused) + AT_RED_FLOATS * 4;
+__host__ __device__ constexpr int attend128_lds(int kb, int vb, bool vprod, bool fused) {
+  return attend128_work_bytes(kb, vb, vprod, fused) + AT_RED_FLOATS * 4;
 }
 
 struct AttendCoefs {
@@ -86,21 +88,25 @@ __device__ __forceinline__ void transpose16x32(uint32_t (&x)[16]) {
 }
 
 // ka: arguments of the scoring body (FUSED only); a: value codes, partial results, and with !FUSED the score matrix
-template <int KB, bool KPROD, int VB, bool FUSED>
+template <int KB, bool KPROD, int VB, bool VPROD, bool FUSED>
 __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, const AttendArgs a, const AttendCoefs cf) {
   __shared__ __attribute__((aligned(16))) uint2 expand_s[256 * I8_COPIES];  // byte -> one byte per bit, 32 copies
   extern __shared__ __attribute__((aligned(16))) unsigned char dyn_s[];
-  constexpr int ROUNDS = (VB + 1) / 2;  // planes a transposing lane takes: ph, ph + 2
+  constexpr int NPL = VB + (VPROD ? 1 : 0);  // bit planes of a value code: index planes, then the signs of Alg. 2
+  constexpr int NVB = VB > 0 ? VB : 1;
+  constexpr int ROUNDS = (NPL + 1) / 2;       // planes a transposing lane takes: ph, ph + 2
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = lane & 15;  // key within a tile; B column (coordinate within a block of 16); A row (query, digit)
   const int kc = lane >> 4;   // query of this lane's logits and sums; k-chunk (16 keys of a k-block)
   const int chunk = blockIdx.x, group = blockIdx.y, q0 = blockIdx.z * 4;
-  unsigned char* const wd = dyn_s + wave * (4 * 4 * AT_PASS_KEYS);
-  uint32_t* const xch = reinterpret_cast<uint32_t*>(dyn_s + AT_WD_BYTES) + wave * (8 * 64);  // + plane * 8 * 8 * 64
-  float* const fsum_s = reinterpret_cast<float*>(dyn_s + AT_WD_BYTES);  // [8][4][128], over the exchange area
-  float* const red_s = reinterpret_cast<float*>(dyn_s + attend128_work_bytes(KB, VB, FUSED));  // [3][8][4]
+  constexpr int WD_ALL = (VPROD ? 2 : 1) * AT_WD_BYTES;
+  unsigned char* const wd = dyn_s + wave * (4 * 4 * AT_PASS_KEYS);  // digits of exp(.) nu; + AT_WD_BYTES: of exp(.) nu gamma
+  uint32_t* const xch = reinterpret_cast<uint32_t*>(dyn_s + WD_ALL) + wave * (8 * 64);  // + plane * 8 * 8 * 64
+  float* const fsum_s = reinterpret_cast<float*>(dyn_s + WD_ALL);  // [8][4][128], over the exchange area
+  float* const fsumz_s = reinterpret_cast<float*>(dyn_s);          // the same for the sign sums, over the digits
+  float* const red_s = reinterpret_cast<float*>(dyn_s + attend128_work_bytes(KB, VB, VPROD, FUSED));  // [3][8][4]
 
   const int64_t gbase = (int64_t)group * a.n;
   const int64_t wave_key0 = ((int64_t)chunk * 8 + wave) * AT_WAVE_KEYS;
@@ -113,22 +119,24 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
 #pragma unroll
     for (int r = 0; r < ROUNDS; ++r) {
       const int plane = ph + 2 * r;
-      const bool have = plane < VB;  // odd VB: the last round has work for half the lanes only
+      // an odd number of planes: the last round has work for half the lanes only
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int64_t key = k0 + i;
         const int64_t row = gbase + (key < a.n ? key : a.n - 1);  // clamped: such keys have weight 0
-        vw[r][i] = have ? a.idx[row * (4 * VB) + tg * VB + plane] : 0u;
+        vw[r][i] = plane < VB ? a.idx[row * (4 * VB) + tg * VB + plane] : (VPROD && plane == VB) ? a.qjl[row * 4 + tg] : 0u;
       }
     }
   };
 
   // value norms: lane L holds those of keys L, L + 64, L + 128, L + 192 of the wavefront
-  float nuv[4];
+  // (and nu gamma, the factor of the sign term of Alg. 2)
+  float nuv[4], ngv[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     const int64_t key = wave_key0 + 64 * e + lane;
     nuv[e] = key < a.n ? a.norm[gbase + key] : 0.f;
+    ngv[e] = VPROD && key < a.n ? nuv[e] * a.gamma[gbase + key] : 0.f;
   }
   // the first pass's value codes travel while the keys are scored, where the registers allow it
   constexpr bool EARLY = !FUSED || KB + (KPROD ? 1 : 0) <= 4;
@@ -167,17 +175,24 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
     if (col == 0) red_s[wave * 4 + kc] = v;
     const float nm = wave_max(fmaxf(fmaxf(nuv[0], nuv[1]), fmaxf(nuv[2], nuv[3])));
     if (lane == 1) red_s[32 + wave * 4] = nm;
+    if (VPROD) {
+      const float gm = wave_max(fmaxf(fmaxf(ngv[0], ngv[1]), fmaxf(ngv[2], ngv[3])));
+      if (lane == 2) red_s[32 + wave * 4 + 1] = gm;
+    }
   }
   __syncthreads();  // also: every wavefront is done with the scoring body's LDS
-  float m = -INFINITY, numax = 0.f;
+  float m = -INFINITY, numax = 0.f, ngmax = 0.f;
 #pragma unroll
   for (int w = 0; w < 8; ++w) {
     m = fmaxf(m, red_s[w * 4 + kc]);
     numax = fmaxf(numax, red_s[32 + w * 4]);
+    if (VPROD) ngmax = fmaxf(ngmax, red_s[32 + w * 4 + 1]);
   }
-  int enu = 0;
+  int enu = 0, eng = 0;
   if (numax > 0.f) (void)frexpf(numax, &enu);  // numax = f * 2^enu, f in [0.5, 1)
+  if (ngmax > 0.f) (void)frexpf(ngmax, &eng);
   const float wscale = ldexpf(1.f, 26 - enu);  // weights exp(logit - m) * nu * wscale <= 2^26
+  const float zscale = ldexpf(1.f, 26 - eng);
 
   const uint32_t copy_off = (uint32_t)(lane & (I8_COPIES - 1)) * 8u;
   const char* const table = reinterpret_cast<const char*>(expand_s);
@@ -194,6 +209,8 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
 
   float f[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};  // coordinate 16 cb + col of query kc
   float ftot = 0.f;                                         // sum of the integer weights of query kc
+  float fz[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};  // VPROD: the same two for the weights of the sign term
+  float fztot = 0.f;
   float lsum = 0.f;
   const v4i ones = v4i{0x01010101, 0x01010101, 0x01010101, 0x01010101};
 
@@ -213,13 +230,21 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
       o[AT_PASS_KEYS] = (unsigned char)((Q >> 7) & 127u);
       o[2 * AT_PASS_KEYS] = (unsigned char)((Q >> 14) & 127u);
       o[3 * AT_PASS_KEYS] = (unsigned char)(Q >> 21);
+      if (VPROD) {
+        const float ng = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (16 * (t & 3) + col), __float_as_int(ngv[t >> 2])));
+        const uint32_t Z = (uint32_t)__float2int_rn(p * ng * zscale);
+        o[AT_WD_BYTES] = (unsigned char)(Z & 127u);
+        o[AT_WD_BYTES + AT_PASS_KEYS] = (unsigned char)((Z >> 7) & 127u);
+        o[AT_WD_BYTES + 2 * AT_PASS_KEYS] = (unsigned char)((Z >> 14) & 127u);
+        o[AT_WD_BYTES + 3 * AT_PASS_KEYS] = (unsigned char)(Z >> 21);
+      }
     }
     // value code words: 16 keys x 32 coordinates -> 32 coordinates x 16 keys
 #pragma unroll
     for (int r = 0; r < ROUNDS; ++r) {
       const int plane = ph + 2 * r;
       transpose16x32(vw[r]);
-      if (plane < VB) {
+      if (plane < NPL) {
         // word c: low half = coordinate 32 tg + c, high half = coordinate 32 tg + 16 + c.  Odd key blocks swap
         // the halves of a row of 32 words, which keeps the reads below free of bank conflicts.
         uint4* dst = reinterpret_cast<uint4*>(xch + plane * (8 * 8 * 64) + kb * 64 + ((tg ^ (kb & 1)) * 16));
@@ -230,23 +255,32 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
     if (ps + 1 < AT_PASSES) load_codes(ps + 1);
     __syncthreads();
 
-    v4i aop[2];
+    v4i aop[2], zop[2];
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk) aop[kk] = *reinterpret_cast<const v4i*>(wd + col * AT_PASS_KEYS + kk * 64 + kc * 16);
+    for (int kk = 0; kk < 2; ++kk) {
+      aop[kk] = *reinterpret_cast<const v4i*>(wd + col * AT_PASS_KEYS + kk * 64 + kc * 16);
+      if (VPROD) zop[kk] = *reinterpret_cast<const v4i*>(wd + AT_WD_BYTES + col * AT_PASS_KEYS + kk * 64 + kc * 16);
+    }
     {
-      v4i tot = v4i{0, 0, 0, 0};
+      v4i tot = v4i{0, 0, 0, 0}, ztot = v4i{0, 0, 0, 0};
 #pragma unroll
-      for (int kk = 0; kk < 2; ++kk) tot = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[kk], ones, tot, 0, 0, 0);
+      for (int kk = 0; kk < 2; ++kk) {
+        tot = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[kk], ones, tot, 0, 0, 0);
+        if (VPROD) ztot = __builtin_amdgcn_mfma_i32_16x16x64_i8(zop[kk], ones, ztot, 0, 0, 0);
+      }
       ftot += digits_sum(tot);
+      if (VPROD) fztot += digits_sum(ztot);
     }
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      uint32_t pw[2][VB];
+      uint32_t pw[2][NVB], pz[2] = {0u, 0u};
 #pragma unroll
-      for (int kk = 0; kk < 2; ++kk)
+      for (int kk = 0; kk < 2; ++kk) {
 #pragma unroll
         for (int pl = 0; pl < VB; ++pl)
           pw[kk][pl] = xch[pl * (8 * 8 * 64) + (4 * kk + kc) * 64 + ((g ^ (kc & 1)) * 16) + col];
+        if (VPROD) pz[kk] = xch[VB * (8 * 8 * 64) + (4 * kk + kc) * 64 + ((g ^ (kc & 1)) * 16) + col];
+      }
 #pragma unroll
       for (int mset = 1; mset < (1 << VB); ++mset) {
         if (!i8_term(mset)) continue;
@@ -265,6 +299,15 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
           f[2 * g + h] = fmaf(cf.c[mset], digits_sum(acc), f[2 * g + h]);
         }
       }
+      if (VPROD) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          v4i acc = v4i{0, 0, 0, 0};
+#pragma unroll
+          for (int kk = 0; kk < 2; ++kk) acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(zop[kk], expand16(pz[kk], h), acc, 0, 0, 0);
+          fz[2 * g + h] += digits_sum(acc);
+        }
+      }
     }
     __syncthreads();  // the digit and exchange areas are rewritten by the next pass / the final sums
   }
@@ -273,16 +316,23 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
   lsum = row_sum(lsum);
   if (col == 0) red_s[64 + wave * 4 + kc] = lsum;
 #pragma unroll
-  for (int cb = 0; cb < 8; ++cb) fsum_s[(wave * 4 + kc) * 128 + 16 * cb + col] = fmaf(cf.c[0], ftot, f[cb]);
+  for (int cb = 0; cb < 8; ++cb) {
+    fsum_s[(wave * 4 + kc) * 128 + 16 * cb + col] = fmaf(cf.c[0], ftot, f[cb]);
+    // sum of w z over the keys, z = +-1 from the sign bits: twice the masked sum minus the sum of the weights
+    if (VPROD) fsumz_s[(wave * 4 + kc) * 128 + 16 * cb + col] = fmaf(2.f, fz[cb], -fztot);
+  }
   __syncthreads();
   const int qi = tid >> 7, j = tid & 127;
   if (q0 + qi < a.q_per_group) {
-    float acc = 0.f;
+    float acc = 0.f, accz = 0.f;
 #pragma unroll
-    for (int w = 0; w < 8; ++w) acc += fsum_s[(w * 4 + qi) * 128 + j];
+    for (int w = 0; w < 8; ++w) {
+      acc += fsum_s[(w * 4 + qi) * 128 + j];
+      if (VPROD) accz += fsumz_s[(w * 4 + qi) * 128 + j];
+    }
     float* o = a.part + (((int64_t)group * a.q_per_group + q0 + qi) * a.nchunks + chunk) * attend_part_stride(128);
     o[4 + j] = acc * ldexpf(1.f, enu - 26);
-    o[4 + 128 + j] = 0.f;
+    o[4 + 128 + j] = accz * ldexpf(1.f, eng - 26);
     if (j == 0) {
       float l = 0.f, mq = -INFINITY;
 #pragma unroll
@@ -296,46 +346,53 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
   }
 }
 
-template <int KB, bool KPROD, int VB, bool FUSED>
+template <int KB, bool KPROD, int VB, bool VPROD, bool FUSED>
 hipError_t launch_attend128_one(const ScoreI8Args& ka, const AttendArgs& a, const AttendCoefs& cf, int n_groups,
                                 hipStream_t s) {
-  constexpr int lds = attend128_lds(KB, VB, FUSED);
+  constexpr int lds = attend128_lds(KB, VB, VPROD, FUSED);
   static_assert(I8_TABLE_BYTES + lds <= 160 * 1024, "LDS budget");
   static bool attr_done = false;  // per instantiation: the limit has to be raised once
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend128_kernel<KB, KPROD, VB, FUSED>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend128_kernel<KB, KPROD, VB, VPROD, FUSED>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   const dim3 grid(a.nchunks, n_groups, (a.q_per_group + 3) / 4);
-  hipLaunchKernelGGL((attend128_kernel<KB, KPROD, VB, FUSED>), grid, dim3(512), lds, s, ka, a, cf);
+  hipLaunchKernelGGL((attend128_kernel<KB, KPROD, VB, VPROD, FUSED>), grid, dim3(512), lds, s, ka, a, cf);
   return hipGetLastError();
 }
 
-// all key variants for one width of the value codes; kb < 0: logits from a.scores
-template <int VB>
+// all key variants for one kind of value code; kb < 0: logits from a.scores
+template <int VB, bool VPROD>
 hipError_t launch_attend128_vb(int kb, bool kprod, const ScoreI8Args& ka, const AttendArgs& a, const AttendCoefs& cf,
                                int n_groups, hipStream_t s) {
-  if (kb < 0) return launch_attend128_one<0, false, VB, false>(ka, a, cf, n_groups, s);
+  if (kb < 0) return launch_attend128_one<0, false, VB, VPROD, false>(ka, a, cf, n_groups, s);
   switch (kb * 2 + (kprod ? 1 : 0)) {
-    case 1: return launch_attend128_one<0, true, VB, true>(ka, a, cf, n_groups, s);
-    case 2: return launch_attend128_one<1, false, VB, true>(ka, a, cf, n_groups, s);
-    case 3: return launch_attend128_one<1, true, VB, true>(ka, a, cf, n_groups, s);
-    case 4: return launch_attend128_one<2, false, VB, true>(ka, a, cf, n_groups, s);
-    case 5: return launch_attend128_one<2, true, VB, true>(ka, a, cf, n_groups, s);
-    case 6: return launch_attend128_one<3, false, VB, true>(ka, a, cf, n_groups, s);
-    case 7: return launch_attend128_one<3, true, VB, true>(ka, a, cf, n_groups, s);
-    case 8: return launch_attend128_one<4, false, VB, true>(ka, a, cf, n_groups, s);
-    case 9: return launch_attend128_one<4, true, VB, true>(ka, a, cf, n_groups, s);
+    case 1: return launch_attend128_one<0, true, VB, VPROD, true>(ka, a, cf, n_groups, s);
+    case 2: return launch_attend128_one<1, false, VB, VPROD, true>(ka, a, cf, n_groups, s);
+    case 3: return launch_attend128_one<1, true, VB, VPROD, true>(ka, a, cf, n_groups, s);
+    case 4: return launch_attend128_one<2, false, VB, VPROD, true>(ka, a, cf, n_groups, s);
+    case 5: return launch_attend128_one<2, true, VB, VPROD, true>(ka, a, cf, n_groups, s);
+    case 6: return launch_attend128_one<3, false, VB, VPROD, true>(ka, a, cf, n_groups, s);
+    case 7: return launch_attend128_one<3, true, VB, VPROD, true>(ka, a, cf, n_groups, s);
+    case 8: return launch_attend128_one<4, false, VB, VPROD, true>(ka, a, cf, n_groups, s);
+    case 9: return launch_attend128_one<4, true, VB, VPROD, true>(ka, a, cf, n_groups, s);
     default: return hipErrorInvalidValue;
   }
 }
 
-// one translation unit per width (tq_attend_128_v*.hip)
-hipError_t launch_attend128_v1(int kb, bool kprod, const ScoreI8Args& ka, const AttendArgs& a, const AttendCoefs& cf, int n_groups, hipStream_t s);
-hipError_t launch_attend128_v2(int kb, bool kprod, const ScoreI8Args& ka, const AttendArgs& a, const AttendCoefs& cf, int n_groups, hipStream_t s);
-hipError_t launch_attend128_v3(int kb, bool kprod, const ScoreI8Args& ka, const AttendArgs& a, const AttendCoefs& cf, int n_groups, hipStream_t s);
-hipError_t launch_attend128_v4(int kb, bool kprod, const ScoreI8Args& ka, const AttendArgs& a, const AttendCoefs& cf, int n_groups, hipStream_t s);
+// one translation unit per kind of value code (tq_attend_128_v*.hip: MSE codes of 1..4 bits; tq_attend_128_p*.hip:
+// codes of Alg. 2 with 0..2 index bits, which is what fits LDS beside the second set of weights)
+#define TQ_ATTEND128_DECL(NAME)                                                                                  \
+  hipError_t NAME(int kb, bool kprod, const ScoreI8Args& ka, const AttendArgs& a, const AttendCoefs& cf, int n_groups, \
+                  hipStream_t s)
+TQ_ATTEND128_DECL(launch_attend128_v1);
+TQ_ATTEND128_DECL(launch_attend128_v2);
+TQ_ATTEND128_DECL(launch_attend128_v3);
+TQ_ATTEND128_DECL(launch_attend128_v4);
+TQ_ATTEND128_DECL(launch_attend128_p0);
+TQ_ATTEND128_DECL(launch_attend128_p1);
+TQ_ATTEND128_DECL(launch_attend128_p2);
 
 }  // namespace tq

@@ -82,6 +82,8 @@ CASES = [
     (128, 2, True, 2, False, 8, 4, 4100),
     (128, 3, True, 1, False, 2, 7, 2048),
     (128, 0, True, 3, False, 1, 4, 6200),
+    (128, 2, True, 2, True, 2, 4, 2500),
+    (128, 3, False, 3, True, 1, 4, 900),
 ]
 
 
@@ -90,7 +92,7 @@ def test_attend(d, kb, kprod, vb, vprod, n_groups, qpg, npg):
     run_attend(d, kb, kprod, vb, vprod, n_groups, qpg, npg, True)
 
 
-@pytest.mark.parametrize("d,kb,kprod,vb,vprod,n_groups,qpg,npg", [c for c in CASES if c[0] == 128 and not c[4]][:4])
+@pytest.mark.parametrize("d,kb,kprod,vb,vprod,n_groups,qpg,npg", [c for c in CASES if c[0] == 128][:5])
 def test_attend_with_scores_from_a_scoring_call(d, kb, kprod, vb, vprod, n_groups, qpg, npg):
     """Without the transposed key matrices the keys are scored by tq_score's kernels first and the
     read-out kernel takes the logits from memory."""
