@@ -3,6 +3,7 @@ search of Sec. 4.4 and the distortions of Sec. 4.1 against Theorems 1-3.
 
     python -m paper_2504_19874_amd.recall --d 1536 --n 100000 --nq 1000 --bits 2 4 [--kind mse prod] [--data gaussian]
     python -m paper_2504_19874_amd.recall --distortion --d 1536 --n 20000 --bits 1 2 3 4
+    python -m paper_2504_19874_amd.recall --entropy --d 1536 --n 20000 --bits 2 3 4
 
 Recall 1@k (Sec. 4.4): the fraction of queries whose true maximum-inner-product
 database vector is among the k best of the estimated scores.  The database is
@@ -17,6 +18,12 @@ Distortion (Sec. 4.1, Fig. 3): D_mse = E||x - x~||^2 of unit vectors and
 D_prod = E|<y,x> - est|^2 for unit-norm queries y, next to the upper bounds
 of Theorems 1 and 2 and the lower bound of Theorem 3.  One JSON line per
 setting.
+
+Entropy (Sec. 3.1, the remark on entropy coding the indices): the empirical
+entropy of the stored indices in bits per coordinate, i.e. what a prefix code
+over the bucket probabilities could reach instead of b.  The library stores
+plain b-bit indices, as the paper's own implementation does; this is the
+measurement only.
 """
 from __future__ import annotations
 
@@ -106,6 +113,22 @@ def distortion(tq, torch, W, d, n, nq, bits, kind, seed_x=4, seed_q=5):
             "lower_mse": 4.0 ** -bits, "lower_prod": 4.0 ** -bits / d}
 
 
+def index_entropy(tq, torch, W, d, n, bits, seed_x=4):
+    """Histogram of the indices the library stores for unit vectors -> entropy in bits per coordinate."""
+    p = _params(tq, W, d, bits, "mse").reserve(n, 0, 0)
+    x = torch.from_numpy(W.unit_gaussian_rows(n, d, seed_x)).cuda()
+    idx, _, _, _ = _quantize(tq, torch, p, x, False)
+    words = idx.view(n, d // 32, bits).to(torch.int64) & 0xFFFFFFFF  # [vector][group][plane]
+    lanes = torch.arange(32, device="cuda")
+    level = torch.zeros((n, d // 32, 32), dtype=torch.int64, device="cuda")
+    for pl in range(bits):
+        level |= ((words[:, :, pl, None] >> lanes) & 1) << pl
+    freq = torch.bincount(level.reshape(-1), minlength=1 << bits).double() / level.numel()
+    nz = freq[freq > 0]
+    h = float(-(nz * torch.log2(nz)).sum())
+    return {"entropy_bits": h, "saving": 1.0 - h / bits, "freq": [round(float(f), 5) for f in freq]}
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--d", type=int, default=1536)
@@ -114,6 +137,7 @@ def main():
     ap.add_argument("--bits", type=int, nargs="+", default=[2, 4])
     ap.add_argument("--kind", nargs="+", default=["mse", "prod"])
     ap.add_argument("--distortion", action="store_true")
+    ap.add_argument("--entropy", action="store_true")
     ap.add_argument("--data", choices=["mixture", "gaussian"], default="mixture")
     args = ap.parse_args()
 
@@ -122,6 +146,12 @@ def main():
     import paper_2504_19874_amd as tq
     import workloads as W
 
+    if args.entropy:
+        for bits in args.bits:
+            out = {"d": args.d, "n": args.n, "bits": bits}
+            out.update(index_entropy(tq, torch, W, args.d, args.n, bits))
+            print(json.dumps(out), flush=True)
+        return
     for kind in args.kind:
         for bits in args.bits:
             out = {"d": args.d, "n": args.n, "nq": args.nq, "bits": bits, "kind": kind}

@@ -36,6 +36,18 @@ def test_distortions_match_theorems_1_and_2(d):
             assert abs(m["slope"] - 2 / math.pi) < 0.01
 
 
+def test_entropy_of_the_stored_indices():
+    """Sec. 3.1: at b = 4 the indices carry about 3.8 bits each (a 5 % saving for an entropy coder);
+    the histogram of what the library stores must be the codebook's bucket probabilities."""
+    d, n, bits = 1536, 4000, 4
+    got = R.index_entropy(tq, torch, W, d, n, bits)
+    c, _, _ = o.lloyd_max_codebook(d, bits)
+    p = o.bucket_masses(c, d)
+    assert np.max(np.abs(np.array(got["freq"]) - p)) < 2e-3
+    assert abs(got["entropy_bits"] - float(-np.sum(p * np.log2(p)))) < 0.01
+    assert abs(got["entropy_bits"] - 3.8) < 0.05 and abs(got["saving"] - 0.05) < 0.01
+
+
 def test_recall_harness_agrees_with_the_oracle():
     d, n, nq, bits = 128, 3000, 60, 3
     got = R.recall_at_k(tq, torch, W, d, n, nq, bits, "prod", "gaussian")
