@@ -124,6 +124,39 @@ def run_attend(d, kb, kprod, vb, vprod, n_groups, qpg, npg, key_transposes):
     check_attend(out.cpu().numpy().astype(np.float64), want, q, scale, k_codes[3], vt, p_want, d, n_groups, qpg, npg)
 
 
+def test_attend_at_the_decode_configuration_full_size():
+    """The decode configuration (32 query heads on 8 KV heads, 65536 cached tokens per head, keys b = 3 of Alg. 2)
+    with a value cache of the same shape, in the launch configuration the timing harness uses; the oracle
+    recomputes two of the eight KV heads."""
+    cfg = W.CONFIGS["C3"]
+    d, n_groups, qpg, npg = cfg.d, cfg.n_groups, cfg.q_per_group, cfg.n
+    pk, Pik, Sk, ck = setup(d, cfg.bits_mse, True, 100, 200)
+    pv, Piv, Sv, cv = setup(d, 2, False, 300, 400)
+    n, nq = n_groups * npg, n_groups * qpg
+    rng = np.random.default_rng(77)
+    k_codes, k_dev = random_codes(rng, n, d, cfg.bits_mse, True, 0.3)
+    v_codes, v_dev = random_codes(rng, n, d, 2, False, 1.0)
+    q = W.gaussian_queries(nq, d, cfg.seed_q, unit=False)
+    scale = 1.0 / math.sqrt(d)
+    out = torch.full((nq, d), float("nan"), dtype=torch.float32, device=DEV)
+    tq.tq_attend(pk, pv, dev(q), n_groups, qpg, k_dev, v_dev, npg, scale, out)
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    for g in (0, 5):
+        rows, toks = slice(g * qpg, (g + 1) * qpg), slice(g * npg, (g + 1) * npg)
+        kt = dequant(tuple(None if a is None else a[toks] for a in k_codes), Pik, Sk, ck)
+        vt = dequant(tuple(None if a is None else a[toks] for a in v_codes), Piv, Sv, cv)
+        want = o.attend(q[rows], kt, vt, scale)
+        # sum_i p_i |v~_i| without the npg x npg identity: attend with |v~| as the values
+        size = o.attend(q[rows], kt, np.abs(vt), scale)
+        qn = np.linalg.norm(q[rows].astype(np.float64), axis=1)
+        e = 1e-4 * scale * qn * float(k_codes[3][toks].max())
+        lim = (P.REL_TOL + np.expm1(2 * e))[:, None] * (size + np.abs(want))
+        err = np.abs(got[rows] - want)
+        worst = float((err / lim).max())
+        assert worst <= 1.0, f"attend, KV head {g}: error {worst:.3f}x the tolerance"
+
+
 def test_attend_sharp_softmax_and_padded_rows():
     """A scale large enough that a handful of tokens carry the weight; output rows wider than d."""
     d, n_groups, qpg, npg = 128, 2, 4, 2500
