@@ -389,6 +389,11 @@ tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_gr
     if (launch_score_small(p->bits_mse, prod, qr, qs, idx, qjl, gamma, norm, scores, ld_scores, n_per_group,
                            d, n_groups, q_per_group, kappa_of(d), make_codebook(p), s) != hipSuccess)
       return TQ_ERR_HIP;
+  } else if (n_per_group > 0 && score_bf3_applicable(p->bits_mse, prod, d, n_per_group, n_groups, q_per_group, make_codebook(p))) {
+    // many queries per code: dense contraction on the bf16 matrix cores, every fp32 factor as three bf16 pieces
+    if (launch_score_bf3(p->bits_mse, prod, qr, qs, q_per_group, d, idx, qjl, gamma, norm, n_per_group, n_groups, scores,
+                         ld_scores, kappa_of(d), make_codebook(p), s) != hipSuccess)
+      return TQ_ERR_HIP;
   } else if (n_per_group > 0) {
     GemmArgs a;
     std::memset(&a, 0, sizeof(a));

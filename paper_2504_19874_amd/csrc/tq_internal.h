@@ -108,6 +108,12 @@ hipError_t launch_score_i8(int bits, bool prod, const float* Pi, const float* S,
                            const float* norm, float* scores, int64_t lds, int64_t n, int d, int n_groups,
                            int q_per_group, float kappa, const Codebook& cb, hipStream_t stream);
 
+// many queries per code on the bf16 matrix cores, fp32 factors as three bf16 pieces (tq_score_bf3.hip)
+bool score_bf3_applicable(int bits, bool prod, int d, int64_t n, int n_groups, int q_per_group, const Codebook& cb);
+hipError_t launch_score_bf3(int bits, bool prod, const float* qr, const float* qs, int q_per_group, int d,
+                            const uint32_t* idx, const uint32_t* qjl, const float* gamma, const float* norm, int64_t n,
+                            int n_groups, float* out, int64_t ldo, float kappa, const Codebook& cb, hipStream_t s);
+
 // codec stages
 hipError_t launch_stage_pack(const Codebook& cb, int d, const float* y, int64_t n, uint32_t* idx,
                              hipStream_t stream);

@@ -1,0 +1,345 @@
+// Many queries per code (nearest-neighbour search, Sec. 4.4): the estimator of Sec. 3.2 for a block of
+// queries against a block of codes is a dense contraction whose code-side operand takes few values,
+//     score[m][i] = nu_i * ( sum_j qr[m][j] c[idx_ij]  +  kappa gamma_i sum_j qs[m][j] z_ij ).
+// It runs on the bf16 matrix cores (16 x the fp32 rate) without giving up fp32 accuracy: every fp32 factor
+// is split into three bf16 pieces, x = x1 + x2 + x3 exactly (8 + 8 + 8 mantissa bits), a product of two
+// pieces is exact in fp32, and the MFMA accumulates in fp32.  Of the nine piece products the six with
+// combined weight >= 2^-16 are kept,
+//     q c ~ q1 c1 + q1 c2 + q2 c1 + q1 c3 + q2 c2 + q3 c1,
+// the dropped ones are below 2^-24 |q| |c|, the rounding an fp32 multiply has anyway.  Sign operands need
+// one piece: z = +-1 is a bf16 value, and a 1-bit codebook is +-c_1 with c_1 applied after the sum; those
+// products take three MFMAs (q1, q2, q3).
+//
+// Workgroup = 512 threads = 8 wavefronts, tile 128 queries x 256 codes, k in steps of 16 (one
+// v_mfma_f32_32x32x16_bf16 per piece product and 32 x 32 sub-tile), operands through two LDS buffers with a
+// 48-byte row stride (conflict-free 16-byte reads).  Queries are split into pieces while they are staged
+// (read as fp32: 4 bytes per element instead of 6); codes are decoded into pieces while they are staged
+// (bit planes -> bucket number -> 3-piece table in LDS, or straight to +-1).  Wavefront (wm, wn) owns rows
+// 64 wm .. and columns 64 wn .. of the tile: 2 x 2 sub-tiles, one accumulator set per segment (the sign
+// segment is scaled per code by kappa gamma, so it cannot share the accumulator of the first).
+#include "tq_internal.h"
+
+namespace tq {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int TM = 128, TN = 256, KT = 16;
+constexpr int LDK = 24;      // bf16 per LDS row: 16 used + 8 padding = 48 bytes
+constexpr int SPAN = 4;      // coordinate groups (of 32) whose plane words a thread holds at a time
+
+template <int BITS, bool PROD>
+struct Cfg {
+  static constexpr int PC = BITS == 0 ? 0 : BITS == 1 ? 1 : 3;  // pieces of a decoded centroid
+  static constexpr int SEGS = (BITS > 0 ? 1 : 0) + (PROD ? 1 : 0);
+  static constexpr int A_ELEMS = SEGS * 3 * TM * LDK;
+  static constexpr int B_ELEMS = (PC + (PROD ? 1 : 0)) * TN * LDK;
+  static constexpr int BUF_ELEMS = A_ELEMS + B_ELEMS;
+  static constexpr int LDS_BYTES = 2 * BUF_ELEMS * 2 + 16 * 8;  // two buffers, then the piece table
+  static constexpr bool FITS = LDS_BYTES <= 156 * 1024;
+};
+
+struct Bf3Args {
+  const float* qr;  // [groups * M][d] rotated queries
+  const float* qs;  // [groups * M][d] sketched queries (PROD)
+  int M;            // queries per group
+  int d;
+  const uint32_t* idx;
+  const uint32_t* qjl;
+  const float* gamma;
+  const float* norm;  // nullable: unit-norm codes
+  int64_t n;          // codes per group
+  float* out;         // [groups * M][ldo]
+  int64_t ldo;
+  float kappa;
+  Codebook cb;
+};
+
+__device__ __forceinline__ uint32_t bf16_bits(float x) {  // round to nearest even
+  const __bf16 h = (__bf16)x;
+  return (uint32_t) * reinterpret_cast<const unsigned short*>(&h);
+}
+
+// x -> (x1, x2, x3), three bf16 values with x1 + x2 + x3 == x
+__device__ __forceinline__ void split3(float x, uint32_t& p1, uint32_t& p2, uint32_t& p3) {
+  p1 = bf16_bits(x);
+  const float r1 = x - __uint_as_float(p1 << 16);
+  p2 = bf16_bits(r1);
+  const float r2 = r1 - __uint_as_float(p2 << 16);
+  p3 = bf16_bits(r2);
+}
+
+template <int BITS, bool PROD>
+__global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
+  using C = Cfg<BITS, PROD>;
+  constexpr int PC = C::PC;
+  constexpr int NB = BITS > 0 ? BITS : 1;
+  extern __shared__ __attribute__((aligned(16))) unsigned short lds_s[];
+  uint2* const table_s = reinterpret_cast<uint2*>(lds_s + 2 * C::BUF_ELEMS);  // [16]: pieces of centroid k
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave & 1, wn = wave >> 1;
+  const int group = blockIdx.z;
+  const int64_t n0 = (int64_t)blockIdx.x * TN;
+  const int m0 = blockIdx.y * TM;
+  const int gw = a.d >> 5;  // coordinate groups per code
+
+  if (PC == 3 && tid < 16) {
+    uint32_t p1, p2, p3;
+    split3(a.cb.c[tid], p1, p2, p3);
+    table_s[tid] = make_uint2(p1 | (p2 << 16), p3);
+  }
+
+  // ---- staging roles --------------------------------------------------------------------------------
+  // A: thread = (row tid / 4, four consecutive k at 4 (tid % 4)) of each segment
+  const int a_row = tid >> 2, a_k = (tid & 3) * 4;
+  const int a_src_row = m0 + a_row < a.M ? m0 + a_row : a.M - 1;  // clamped: such rows are not stored
+  const float* const a_src0 = a.qr + ((int64_t)group * a.M + a_src_row) * a.d + a_k;
+  const float* const a_src1 = PROD ? a.qs + ((int64_t)group * a.M + a_src_row) * a.d + a_k : nullptr;
+  // B: thread = (code tid % 256, eight consecutive k at 8 (tid / 256))
+  const int b_col = tid & 255, b_half = tid >> 8;
+  const int64_t b_row = (int64_t)group * a.n + (n0 + b_col < a.n ? n0 + b_col : a.n - 1);
+  const uint32_t* const b_idx = a.idx + b_row * ((int64_t)gw * BITS);
+  const uint32_t* const b_qjl = PROD ? a.qjl + b_row * gw : nullptr;
+
+  f32x4 areg[2];
+  uint32_t wcur[SPAN][NB], zcur[SPAN], wnxt[SPAN][NB], znxt[SPAN];
+  auto load_a = [&](int step) {
+    if (BITS > 0) areg[0] = *reinterpret_cast<const f32x4*>(a_src0 + step * KT);
+    if (PROD) areg[1] = *reinterpret_cast<const f32x4*>(a_src1 + step * KT);
+  };
+  auto load_words = [&](int span) {  // plane words of coordinate groups [SPAN span, SPAN span + SPAN)
+#pragma unroll
+    for (int g = 0; g < SPAN; ++g) {
+      const int gg = SPAN * span + g < gw ? SPAN * span + g : gw - 1;  // clamped: never decoded
+#pragma unroll
+      for (int pl = 0; pl < BITS; ++pl) wnxt[g][pl] = b_idx[gg * BITS + pl];
+      znxt[g] = PROD ? b_qjl[gg] : 0u;
+    }
+  };
+  auto store_a = [&](unsigned short* buf) {
+    int seg = 0;
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      if (s == 0 ? BITS == 0 : !PROD) continue;
+      uint32_t p[3][4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) split3(areg[s][e], p[0][e], p[1][e], p[2][e]);
+#pragma unroll
+      for (int pc = 0; pc < 3; ++pc)
+        *reinterpret_cast<uint2*>(buf + ((seg * 3 + pc) * TM + a_row) * LDK + a_k) =
+            make_uint2(p[pc][0] | (p[pc][1] << 16), p[pc][2] | (p[pc][3] << 16));
+      ++seg;
+    }
+  };
+  // eight sign bits -> eight bf16 values +-1 (bit set: +1)
+  auto signs8 = [&](uint32_t b8) -> u32x4 {
+    u32x4 v;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      v[e] = 0xBF80BF80u ^ (((b8 >> (2 * e)) & 1u) << 15) ^ (((b8 >> (2 * e + 1)) & 1u) << 31);
+    return v;
+  };
+  auto store_b = [&](unsigned short* buf, int j) {  // j: step within its span of 2 SPAN steps (a constant at every call)
+    unsigned short* const bb = buf + C::A_ELEMS;
+    const int g = j >> 1, off = (j & 1) * 16 + 8 * b_half;  // word of the span, first bit
+    if (PC == 1) {
+      *reinterpret_cast<u32x4*>(bb + b_col * LDK + 8 * b_half) = signs8((wcur[g][0] >> off) & 0xFFu);
+    } else if (PC == 3) {
+      uint32_t lv[2] = {0u, 0u};  // bucket numbers of 4 coordinates, one per byte
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int pl = 0; pl < BITS; ++pl)
+          lv[h] |= ((((wcur[g][pl] >> (off + 4 * h)) & 0xFu) * 0x00204081u) & 0x01010101u) << pl;
+      uint2 e[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) e[u] = table_s[(lv[u >> 2] >> (8 * (u & 3))) & 0xFFu];
+      u32x4 v1, v2, v3;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        v1[u] = __builtin_amdgcn_perm(e[2 * u + 1].x, e[2 * u].x, 0x05040100u);  // low halves: first pieces
+        v2[u] = __builtin_amdgcn_perm(e[2 * u + 1].x, e[2 * u].x, 0x07060302u);  // high halves: second pieces
+        v3[u] = __builtin_amdgcn_perm(e[2 * u + 1].y, e[2 * u].y, 0x05040100u);
+      }
+      *reinterpret_cast<u32x4*>(bb + (0 * TN + b_col) * LDK + 8 * b_half) = v1;
+      *reinterpret_cast<u32x4*>(bb + (1 * TN + b_col) * LDK + 8 * b_half) = v2;
+      *reinterpret_cast<u32x4*>(bb + (2 * TN + b_col) * LDK + 8 * b_half) = v3;
+    }
+    if (PROD) *reinterpret_cast<u32x4*>(bb + (PC * TN + b_col) * LDK + 8 * b_half) = signs8((zcur[g] >> off) & 0xFFu);
+  };
+  auto take_words = [&]() {
+#pragma unroll
+    for (int g = 0; g < SPAN; ++g) {
+#pragma unroll
+      for (int pl = 0; pl < BITS; ++pl) wcur[g][pl] = wnxt[g][pl];
+      zcur[g] = znxt[g];
+    }
+  };
+
+  floatx16 acc1[2][2], acc2[2][2];
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        acc1[rt][ct][r] = 0.f;
+        acc2[rt][ct][r] = 0.f;
+      }
+
+  const int f_row = lane & 31, f_k = (lane >> 5) * 8;  // fragment: row / column within a sub-tile, first k
+  auto compute = [&](const unsigned short* buf) {
+    const unsigned short* const bb = buf + C::A_ELEMS;
+    auto frag = [&](const unsigned short* base, int row) -> bf16x8 {
+      return *reinterpret_cast<const bf16x8*>(base + row * LDK + f_k);
+    };
+    int seg = 0;
+    if (BITS > 0) {
+      bf16x8 af[2][3], bf[2][PC > 0 ? PC : 1];
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int pc = 0; pc < 3; ++pc) af[rt][pc] = frag(buf + (seg * 3 + pc) * TM * LDK, 64 * wm + 32 * rt + f_row);
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+        for (int pc = 0; pc < PC; ++pc) bf[ct][pc] = frag(bb + pc * TN * LDK, 64 * wn + 32 * ct + f_row);
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct) {
+          if (PC == 1) {
+#pragma unroll
+            for (int pc = 0; pc < 3; ++pc)
+              acc1[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rt][pc], bf[ct][0], acc1[rt][ct], 0, 0, 0);
+          } else {
+            // smallest products first
+            acc1[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rt][2], bf[ct][0], acc1[rt][ct], 0, 0, 0);
+            acc1[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rt][1], bf[ct][PC >= 3 ? 1 : 0], acc1[rt][ct], 0, 0, 0);
+            acc1[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rt][0], bf[ct][PC >= 3 ? 2 : 0], acc1[rt][ct], 0, 0, 0);
+            acc1[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rt][1], bf[ct][0], acc1[rt][ct], 0, 0, 0);
+            acc1[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rt][0], bf[ct][PC >= 3 ? 1 : 0], acc1[rt][ct], 0, 0, 0);
+            acc1[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rt][0], bf[ct][0], acc1[rt][ct], 0, 0, 0);
+          }
+        }
+      ++seg;
+    }
+    if (PROD) {
+      bf16x8 af[2][3], bf[2];
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int pc = 0; pc < 3; ++pc) af[rt][pc] = frag(buf + (seg * 3 + pc) * TM * LDK, 64 * wm + 32 * rt + f_row);
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct) bf[ct] = frag(bb + PC * TN * LDK, 64 * wn + 32 * ct + f_row);
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+          for (int pc = 2; pc >= 0; --pc)
+            acc2[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rt][pc], bf[ct], acc2[rt][ct], 0, 0, 0);
+    }
+  };
+
+  // ---- k loop: one barrier per step ----------------------------------------------------------------
+  unsigned short* const buf0 = lds_s;
+  unsigned short* const buf1 = lds_s + C::BUF_ELEMS;
+  const int steps = a.d / KT;
+  load_a(0);
+  load_words(0);
+  take_words();
+  __syncthreads();  // the piece table
+  store_a(buf0);
+  store_b(buf0, 0);
+  __syncthreads();
+  for (int sp = 0; sp * (2 * SPAN) < steps; ++sp) {
+#pragma unroll
+    for (int j = 0; j < 2 * SPAN; ++j) {  // unrolled, so that the plane words are picked by constant indices
+      const int s = sp * (2 * SPAN) + j;
+      if (s < steps) {                    // uniform
+        const bool more = s + 1 < steps;
+        if (more) load_a(s + 1);
+        if (j == 0 && more) load_words(sp + 1);  // requested a span ahead
+        compute((j & 1) ? buf1 : buf0);
+        if (more) {
+          if (j == 2 * SPAN - 1) take_words();
+          store_a((j & 1) ? buf0 : buf1);
+          store_b((j & 1) ? buf0 : buf1, (j + 1) & (2 * SPAN - 1));
+        }
+        __syncthreads();
+      }
+    }
+  }
+
+  // ---- epilogue: per-code factors, store -----------------------------------------------------------
+  const float c1 = BITS == 1 ? a.cb.c[1] : 1.f;
+#pragma unroll
+  for (int ct = 0; ct < 2; ++ct) {
+    const int64_t col = n0 + 64 * wn + 32 * ct + f_row;
+    const bool col_live = col < a.n;
+    const int64_t crow = (int64_t)group * a.n + (col_live ? col : a.n - 1);
+    const float nu = a.norm != nullptr ? a.norm[crow] : 1.f;
+    const float kg = PROD ? a.kappa * a.gamma[crow] : 0.f;
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + 64 * wm + 32 * rt + 8 * (r >> 2) + (r & 3) + 4 * (lane >> 5);
+        const float v = nu * fmaf(kg, acc2[rt][ct][r], c1 * acc1[rt][ct][r]);
+        if (col_live && row < a.M) a.out[((int64_t)group * a.M + row) * a.ldo + col] = v;
+      }
+  }
+}
+
+template <int BITS, bool PROD>
+hipError_t launch_one(const Bf3Args& a, int n_groups, hipStream_t s) {
+  using C = Cfg<BITS, PROD>;
+  if (!C::FITS) return hipErrorInvalidValue;
+  static bool attr_done = false;  // per instantiation: the limit has to be raised once
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_bf3_kernel<BITS, PROD>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const dim3 grid((unsigned)((a.n + TN - 1) / TN), (unsigned)((a.M + TM - 1) / TM), n_groups);
+  hipLaunchKernelGGL((score_bf3_kernel<BITS, PROD>), grid, dim3(512), C::LDS_BYTES, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// what the kernel takes: both LDS buffers must fit, and the 1-bit codebook must be +-c
+bool score_bf3_applicable(int bits, bool prod, int d, int64_t n, int n_groups, int q_per_group, const Codebook& cb) {
+  if (d % 32 != 0 || n <= 0 || q_per_group <= 0 || n_groups > 65535 || (q_per_group + TM - 1) / TM > 65535) return false;
+  if (bits == 0) return prod;
+  if (bits == 1) return cb.c[0] == -cb.c[1];
+  return bits <= 4 && !prod;  // wider codes with the sign segment do not fit two buffers
+}
+
+hipError_t launch_score_bf3(int bits, bool prod, const float* qr, const float* qs, int q_per_group, int d,
+                            const uint32_t* idx, const uint32_t* qjl, const float* gamma, const float* norm, int64_t n,
+                            int n_groups, float* out, int64_t ldo, float kappa, const Codebook& cb, hipStream_t s) {
+  Bf3Args a;
+  a.qr = qr; a.qs = qs; a.M = q_per_group; a.d = d; a.idx = idx; a.qjl = qjl; a.gamma = gamma; a.norm = norm;
+  a.n = n; a.out = out; a.ldo = ldo; a.kappa = kappa; a.cb = cb;
+  switch (bits * 2 + (prod ? 1 : 0)) {
+    case 1: return launch_one<0, true>(a, n_groups, s);
+    case 2: return launch_one<1, false>(a, n_groups, s);
+    case 3: return launch_one<1, true>(a, n_groups, s);
+    case 4: return launch_one<2, false>(a, n_groups, s);
+    case 6: return launch_one<3, false>(a, n_groups, s);
+    case 8: return launch_one<4, false>(a, n_groups, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace tq

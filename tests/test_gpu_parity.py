@@ -267,6 +267,11 @@ def test_dequantize(d, bits_mse, n, prod, with_norm):
     # workgroups, query blocks that are not multiples of 4, a handful of keys
     (128, 1, False, 3, 5, 2048, 0), (128, 3, False, 1, 4, 4100, 0), (128, 4, False, 2, 2, 2049, 3),
     (128, 0, True, 2, 4, 2300, 0), (128, 1, True, 1, 1, 5, 0), (128, 3, True, 1, 9, 6000, 0),
+    # many queries per code: the bf16-piece contraction (mse any width, prod up to one index bit); tiles of
+    # 128 queries x 256 codes with ragged edges on both sides, several groups, d that is not a multiple of 128
+    (3072, 1, True, 1, 100, 700, 10), (128, 0, True, 1, 70, 300, 0), (160, 3, False, 2, 129, 513, 4),
+    (1536, 2, False, 1, 200, 300, 0), (96, 1, False, 1, 65, 1000, 0), (1536, 4, False, 1, 257, 1025, 10),
+    (128, 1, True, 3, 33, 257, 0),
     # d = 256..512: preparation kernel + int8 scoring kernel
     (256, 2, True, 2, 4, 1500, 0), (256, 4, True, 1, 3, 600, 0), (512, 1, False, 1, 8, 700, 0),
     (384, 3, True, 1, 2, 300, 0), (512, 4, False, 1, 4, 1100, 5),
