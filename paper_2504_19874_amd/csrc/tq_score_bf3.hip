@@ -28,12 +28,14 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int TM = 128, TN = 256, KT = 16;
+constexpr int TN = 256, KT = 16;  // codes per tile, k per step; queries per tile: 128 or 256 (template parameter)
 constexpr int LDK = 24;      // bf16 per LDS row: 16 used + 8 padding = 48 bytes
 constexpr int SPAN = 4;      // coordinate groups (of 32) whose plane words a thread holds at a time
 
-template <int BITS, bool PROD>
+template <int BITS, bool PROD, int TM>
 struct Cfg {
+  static constexpr int WM = TM / 64, WN = 8 / WM;  // wavefronts along the queries / the codes
+  static constexpr int CT = TN / (32 * WN);        // 32-column sub-tiles of a wavefront (2 row sub-tiles always)
   static constexpr int PC = BITS == 0 ? 0 : BITS == 1 ? 1 : 3;  // pieces of a decoded centroid
   static constexpr int SEGS = (BITS > 0 ? 1 : 0) + (PROD ? 1 : 0);
   static constexpr int A_ELEMS = SEGS * 3 * TM * LDK;
@@ -73,10 +75,12 @@ __device__ __forceinline__ void split3(float x, uint32_t& p1, uint32_t& p2, uint
   p3 = bf16_bits(r2);
 }
 
-template <int BITS, bool PROD>
+template <int BITS, bool PROD, int TM>
 __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
-  using C = Cfg<BITS, PROD>;
+  using C = Cfg<BITS, PROD, TM>;
   constexpr int PC = C::PC;
+  constexpr int CT = C::CT;
+  constexpr int AR = TM / 128;  // 16-byte pieces of a query tile row set a thread stages per segment
   constexpr int NB = BITS > 0 ? BITS : 1;
   extern __shared__ __attribute__((aligned(16))) unsigned short lds_s[];
   uint2* const table_s = reinterpret_cast<uint2*>(lds_s + 2 * C::BUF_ELEMS);  // [16]: pieces of centroid k
@@ -84,7 +88,7 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave & 1, wn = wave >> 1;
+  const int wm = wave % C::WM, wn = wave / C::WM;
   const int group = blockIdx.z;
   const int64_t n0 = (int64_t)blockIdx.x * TN;
   const int m0 = blockIdx.y * TM;
@@ -98,21 +102,30 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
 
   // ---- staging roles --------------------------------------------------------------------------------
   // A: thread = (row tid / 4, four consecutive k at 4 (tid % 4)) of each segment
+  // (and of row + 128 when the tile has 256 rows)
   const int a_row = tid >> 2, a_k = (tid & 3) * 4;
-  const int a_src_row = m0 + a_row < a.M ? m0 + a_row : a.M - 1;  // clamped: such rows are not stored
-  const float* const a_src0 = a.qr + ((int64_t)group * a.M + a_src_row) * a.d + a_k;
-  const float* const a_src1 = PROD ? a.qs + ((int64_t)group * a.M + a_src_row) * a.d + a_k : nullptr;
+  const float* a_src0[AR];
+  const float* a_src1[AR];
+#pragma unroll
+  for (int i = 0; i < AR; ++i) {
+    const int r = m0 + a_row + 128 * i < a.M ? m0 + a_row + 128 * i : a.M - 1;  // clamped: such rows are not stored
+    a_src0[i] = a.qr + ((int64_t)group * a.M + r) * a.d + a_k;
+    a_src1[i] = PROD ? a.qs + ((int64_t)group * a.M + r) * a.d + a_k : nullptr;
+  }
   // B: thread = (code tid % 256, eight consecutive k at 8 (tid / 256))
   const int b_col = tid & 255, b_half = tid >> 8;
   const int64_t b_row = (int64_t)group * a.n + (n0 + b_col < a.n ? n0 + b_col : a.n - 1);
   const uint32_t* const b_idx = a.idx + b_row * ((int64_t)gw * BITS);
   const uint32_t* const b_qjl = PROD ? a.qjl + b_row * gw : nullptr;
 
-  f32x4 areg[2];
+  f32x4 areg[2][AR];
   uint32_t wcur[SPAN][NB], zcur[SPAN], wnxt[SPAN][NB], znxt[SPAN];
   auto load_a = [&](int step) {
-    if (BITS > 0) areg[0] = *reinterpret_cast<const f32x4*>(a_src0 + step * KT);
-    if (PROD) areg[1] = *reinterpret_cast<const f32x4*>(a_src1 + step * KT);
+#pragma unroll
+    for (int i = 0; i < AR; ++i) {
+      if (BITS > 0) areg[0][i] = *reinterpret_cast<const f32x4*>(a_src0[i] + step * KT);
+      if (PROD) areg[1][i] = *reinterpret_cast<const f32x4*>(a_src1[i] + step * KT);
+    }
   };
   auto load_words = [&](int span) {  // plane words of coordinate groups [SPAN span, SPAN span + SPAN)
 #pragma unroll
@@ -128,13 +141,16 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
       if (s == 0 ? BITS == 0 : !PROD) continue;
-      uint32_t p[3][4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) split3(areg[s][e], p[0][e], p[1][e], p[2][e]);
+      for (int i = 0; i < AR; ++i) {
+        uint32_t p[3][4];
 #pragma unroll
-      for (int pc = 0; pc < 3; ++pc)
-        *reinterpret_cast<uint2*>(buf + ((seg * 3 + pc) * TM + a_row) * LDK + a_k) =
-            make_uint2(p[pc][0] | (p[pc][1] << 16), p[pc][2] | (p[pc][3] << 16));
+        for (int e = 0; e < 4; ++e) split3(areg[s][i][e], p[0][e], p[1][e], p[2][e]);
+#pragma unroll
+        for (int pc = 0; pc < 3; ++pc)
+          *reinterpret_cast<uint2*>(buf + ((seg * 3 + pc) * TM + a_row + 128 * i) * LDK + a_k) =
+              make_uint2(p[pc][0] | (p[pc][1] << 16), p[pc][2] | (p[pc][3] << 16));
+      }
       ++seg;
     }
   };
@@ -183,15 +199,15 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
     }
   };
 
-  floatx16 acc1[2][2], acc2[2][2];
+  floatx16 acc1[2][CT], acc2[2][PROD ? CT : 1];
 #pragma unroll
   for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-    for (int ct = 0; ct < 2; ++ct)
+    for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         acc1[rt][ct][r] = 0.f;
-        acc2[rt][ct][r] = 0.f;
+        if (PROD) acc2[rt][ct][r] = 0.f;
       }
 
   const int f_row = lane & 31, f_k = (lane >> 5) * 8;  // fragment: row / column within a sub-tile, first k
@@ -202,49 +218,43 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
     };
     int seg = 0;
     if (BITS > 0) {
-      bf16x8 af[2][3], bf[2][PC > 0 ? PC : 1];
+      bf16x8 af[2][3], bf[CT][PC > 0 ? PC : 1];
 #pragma unroll
       for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
         for (int pc = 0; pc < 3; ++pc) af[rt][pc] = frag(buf + (seg * 3 + pc) * TM * LDK, 64 * wm + 32 * rt + f_row);
 #pragma unroll
-      for (int ct = 0; ct < 2; ++ct)
+      for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
-        for (int pc = 0; pc < PC; ++pc) bf[ct][pc] = frag(bb + pc * TN * LDK, 64 * wn + 32 * ct + f_row);
+        for (int pc = 0; pc < PC; ++pc) bf[ct][pc] = frag(bb + pc * TN * LDK, 32 * CT * wn + 32 * ct + f_row);
+      // piece products outermost: consecutive MFMAs go to different accumulators; smallest products first
+      constexpr int NTERM = PC == 1 ? 3 : 6;
+      constexpr int TA[6] = {2, 1, 0, 1, 0, 0};                 // query piece of each product
+      constexpr int TB[6] = {0, 1, 2, 0, 1, 0};                 // centroid piece
 #pragma unroll
-      for (int rt = 0; rt < 2; ++rt)
+      for (int t = 0; t < NTERM; ++t)
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct) {
-          if (PC == 1) {
+        for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-            for (int pc = 0; pc < 3; ++pc)
-              acc1[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rt][pc], bf[ct][0], acc1[rt][ct], 0, 0, 0);
-          } else {
-            // smallest products first
-            acc1[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rt][2], bf[ct][0], acc1[rt][ct], 0, 0, 0);
-            acc1[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rt][1], bf[ct][PC >= 3 ? 1 : 0], acc1[rt][ct], 0, 0, 0);
-            acc1[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rt][0], bf[ct][PC >= 3 ? 2 : 0], acc1[rt][ct], 0, 0, 0);
-            acc1[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rt][1], bf[ct][0], acc1[rt][ct], 0, 0, 0);
-            acc1[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rt][0], bf[ct][PC >= 3 ? 1 : 0], acc1[rt][ct], 0, 0, 0);
-            acc1[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rt][0], bf[ct][0], acc1[rt][ct], 0, 0, 0);
-          }
-        }
+          for (int ct = 0; ct < CT; ++ct)
+            acc1[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rt][PC == 1 ? 2 - t : TA[t]], bf[ct][PC == 1 ? 0 : TB[t]],
+                                                                   acc1[rt][ct], 0, 0, 0);
       ++seg;
     }
     if (PROD) {
-      bf16x8 af[2][3], bf[2];
+      bf16x8 af[2][3], bf[CT];
 #pragma unroll
       for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
         for (int pc = 0; pc < 3; ++pc) af[rt][pc] = frag(buf + (seg * 3 + pc) * TM * LDK, 64 * wm + 32 * rt + f_row);
 #pragma unroll
-      for (int ct = 0; ct < 2; ++ct) bf[ct] = frag(bb + PC * TN * LDK, 64 * wn + 32 * ct + f_row);
+      for (int ct = 0; ct < CT; ++ct) bf[ct] = frag(bb + PC * TN * LDK, 32 * CT * wn + 32 * ct + f_row);
 #pragma unroll
-      for (int rt = 0; rt < 2; ++rt)
+      for (int pc = 2; pc >= 0; --pc)
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
+        for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-          for (int pc = 2; pc >= 0; --pc)
+          for (int ct = 0; ct < CT; ++ct)
             acc2[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rt][pc], bf[ct], acc2[rt][ct], 0, 0, 0);
     }
   };
@@ -260,14 +270,30 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
   store_a(buf0);
   store_b(buf0, 0);
   __syncthreads();
-  for (int sp = 0; sp * (2 * SPAN) < steps; ++sp) {
+  const int spans = steps / (2 * SPAN);
+  // whole spans: no branch inside a step; after the last step the same step is staged once more, unused
+  for (int sp = 0; sp < spans; ++sp) {
 #pragma unroll
     for (int j = 0; j < 2 * SPAN; ++j) {  // unrolled, so that the plane words are picked by constant indices
       const int s = sp * (2 * SPAN) + j;
-      if (s < steps) {                    // uniform
+      load_a(s + 1 < steps ? s + 1 : s);
+      if (j == 0) load_words(sp + 1);  // requested a span ahead (clamped past the end)
+      compute((j & 1) ? buf1 : buf0);
+      if (j == 2 * SPAN - 1) take_words();
+      store_a((j & 1) ? buf0 : buf1);
+      store_b((j & 1) ? buf0 : buf1, (j + 1) & (2 * SPAN - 1));
+      __syncthreads();
+    }
+  }
+  // the steps of an incomplete last span (d not a multiple of 128)
+  for (int sp = spans; sp * (2 * SPAN) < steps; ++sp) {
+#pragma unroll
+    for (int j = 0; j < 2 * SPAN; ++j) {
+      const int s = sp * (2 * SPAN) + j;
+      if (s < steps) {  // uniform
         const bool more = s + 1 < steps;
         if (more) load_a(s + 1);
-        if (j == 0 && more) load_words(sp + 1);  // requested a span ahead
+        if (j == 0 && more) load_words(sp + 1);
         compute((j & 1) ? buf1 : buf0);
         if (more) {
           if (j == 2 * SPAN - 1) take_words();
@@ -282,8 +308,8 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
   // ---- epilogue: per-code factors, store -----------------------------------------------------------
   const float c1 = BITS == 1 ? a.cb.c[1] : 1.f;
 #pragma unroll
-  for (int ct = 0; ct < 2; ++ct) {
-    const int64_t col = n0 + 64 * wn + 32 * ct + f_row;
+  for (int ct = 0; ct < CT; ++ct) {
+    const int64_t col = n0 + 32 * CT * wn + 32 * ct + f_row;
     const bool col_live = col < a.n;
     const int64_t crow = (int64_t)group * a.n + (col_live ? col : a.n - 1);
     const float nu = a.norm != nullptr ? a.norm[crow] : 1.f;
@@ -293,33 +319,41 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = m0 + 64 * wm + 32 * rt + 8 * (r >> 2) + (r & 3) + 4 * (lane >> 5);
-        const float v = nu * fmaf(kg, acc2[rt][ct][r], c1 * acc1[rt][ct][r]);
+        const float v = nu * fmaf(kg, PROD ? acc2[rt][ct][r] : 0.f, c1 * acc1[rt][ct][r]);
         if (col_live && row < a.M) a.out[((int64_t)group * a.M + row) * a.ldo + col] = v;
       }
   }
 }
 
-template <int BITS, bool PROD>
-hipError_t launch_one(const Bf3Args& a, int n_groups, hipStream_t s) {
-  using C = Cfg<BITS, PROD>;
+template <int BITS, bool PROD, int TM>
+hipError_t launch_tile(const Bf3Args& a, int n_groups, hipStream_t s) {
+  using C = Cfg<BITS, PROD, TM>;
   if (!C::FITS) return hipErrorInvalidValue;
   static bool attr_done = false;  // per instantiation: the limit has to be raised once
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_bf3_kernel<BITS, PROD>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_bf3_kernel<BITS, PROD, TM>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   const dim3 grid((unsigned)((a.n + TN - 1) / TN), (unsigned)((a.M + TM - 1) / TM), n_groups);
-  hipLaunchKernelGGL((score_bf3_kernel<BITS, PROD>), grid, dim3(512), C::LDS_BYTES, s, a);
+  hipLaunchKernelGGL((score_bf3_kernel<BITS, PROD, TM>), grid, dim3(512), C::LDS_BYTES, s, a);
   return hipGetLastError();
+}
+
+// 256 queries per tile halve the LDS reads per MFMA (a wavefront's sub-tiles share fragments), which is what
+// bounds the 128-row tile; the accumulators of two segments do not fit that shape
+template <int BITS, bool PROD>
+hipError_t launch_one(const Bf3Args& a, int n_groups, hipStream_t s) {
+  if (!PROD && a.M > 128) return launch_tile<BITS, PROD, PROD ? 128 : 256>(a, n_groups, s);
+  return launch_tile<BITS, PROD, 128>(a, n_groups, s);
 }
 
 }  // namespace
 
 // what the kernel takes: both LDS buffers must fit, and the 1-bit codebook must be +-c
 bool score_bf3_applicable(int bits, bool prod, int d, int64_t n, int n_groups, int q_per_group, const Codebook& cb) {
-  if (d % 32 != 0 || n <= 0 || q_per_group <= 0 || n_groups > 65535 || (q_per_group + TM - 1) / TM > 65535) return false;
+  if (d % 32 != 0 || n <= 0 || q_per_group <= 0 || n_groups > 65535 || (q_per_group + 127) / 128 > 65535) return false;
   if (bits == 0) return prod;
   if (bits == 1) return cb.c[0] == -cb.c[1];
   return bits <= 4 && !prod;  // wider codes with the sign segment do not fit two buffers
