@@ -75,6 +75,22 @@ __device__ __forceinline__ void split3(float x, uint32_t& p1, uint32_t& p2, uint
   p3 = bf16_bits(r2);
 }
 
+// the same for two values at once: word k holds piece k of x[0] (low half) and of x[1] (high half); one
+// packed conversion per piece
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t bf16_pair(f32x2 x) {
+  const bf16x2 h = __builtin_convertvector(x, bf16x2);
+  return *reinterpret_cast<const uint32_t*>(&h);
+}
+__device__ __forceinline__ void split3_pair(f32x2 x, uint32_t& w1, uint32_t& w2, uint32_t& w3) {
+  w1 = bf16_pair(x);
+  const f32x2 r1 = {x[0] - __uint_as_float(w1 << 16), x[1] - __uint_as_float(w1 & 0xffff0000u)};
+  w2 = bf16_pair(r1);
+  const f32x2 r2 = {r1[0] - __uint_as_float(w2 << 16), r1[1] - __uint_as_float(w2 & 0xffff0000u)};
+  w3 = bf16_pair(r2);
+}
+
 template <int BITS, bool PROD, int TM>
 __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
   using C = Cfg<BITS, PROD, TM>;
@@ -143,13 +159,12 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
       if (s == 0 ? BITS == 0 : !PROD) continue;
 #pragma unroll
       for (int i = 0; i < AR; ++i) {
-        uint32_t p[3][4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) split3(areg[s][i][e], p[0][e], p[1][e], p[2][e]);
+        uint32_t lo[3], hi[3];
+        split3_pair(f32x2{areg[s][i][0], areg[s][i][1]}, lo[0], lo[1], lo[2]);
+        split3_pair(f32x2{areg[s][i][2], areg[s][i][3]}, hi[0], hi[1], hi[2]);
 #pragma unroll
         for (int pc = 0; pc < 3; ++pc)
-          *reinterpret_cast<uint2*>(buf + ((seg * 3 + pc) * TM + a_row + 128 * i) * LDK + a_k) =
-              make_uint2(p[pc][0] | (p[pc][1] << 16), p[pc][2] | (p[pc][3] << 16));
+          *reinterpret_cast<uint2*>(buf + ((seg * 3 + pc) * TM + a_row + 128 * i) * LDK + a_k) = make_uint2(lo[pc], hi[pc]);
       }
       ++seg;
     }
