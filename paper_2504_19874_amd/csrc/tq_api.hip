@@ -263,6 +263,11 @@ tq_status tq_dequantize(const tq_params* p, const uint32_t* idx, const uint32_t*
                                       kappa_of(p->d), make_codebook(p), 0, 0.f, make_codebook(p),
                                       static_cast<hipStream_t>(stream)));
   }
+  // x~_i[k] = <e_k, DeQuant(code i)>: the scoring contraction with the rows of Pi^T (and S^T) as the queries,
+  // stored one row per code; on the bf16 matrix cores where that kernel takes the codes
+  if (score_bf3_applicable(p->bits_mse, prod, p->d, n, 1, p->d, make_codebook(p)))
+    return from_hip(launch_score_bf3(p->bits_mse, prod, p->PiT, p->ST, p->d, p->d, idx, qjl, gamma, norm, n, 1, x_out, ldo,
+                                     true, kappa_of(p->d), make_codebook(p), static_cast<hipStream_t>(stream)));
   GemmArgs a;
   std::memset(&a, 0, sizeof(a));
   a.W1 = p->PiT;  // x~[k] = sum_j Pi[j][k] y~[j]: rows of Pi^T against the decoded code
@@ -392,7 +397,7 @@ tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_gr
   } else if (n_per_group > 0 && score_bf3_applicable(p->bits_mse, prod, d, n_per_group, n_groups, q_per_group, make_codebook(p))) {
     // many queries per code: dense contraction on the bf16 matrix cores, every fp32 factor as three bf16 pieces
     if (launch_score_bf3(p->bits_mse, prod, qr, qs, q_per_group, d, idx, qjl, gamma, norm, n_per_group, n_groups, scores,
-                         ld_scores, kappa_of(d), make_codebook(p), s) != hipSuccess)
+                         ld_scores, false, kappa_of(d), make_codebook(p), s) != hipSuccess)
       return TQ_ERR_HIP;
   } else if (n_per_group > 0) {
     GemmArgs a;

@@ -112,7 +112,8 @@ hipError_t launch_score_i8(int bits, bool prod, const float* Pi, const float* S,
 bool score_bf3_applicable(int bits, bool prod, int d, int64_t n, int n_groups, int q_per_group, const Codebook& cb);
 hipError_t launch_score_bf3(int bits, bool prod, const float* qr, const float* qs, int q_per_group, int d,
                             const uint32_t* idx, const uint32_t* qjl, const float* gamma, const float* norm, int64_t n,
-                            int n_groups, float* out, int64_t ldo, float kappa, const Codebook& cb, hipStream_t s);
+                            int n_groups, float* out, int64_t ldo, bool transposed, float kappa, const Codebook& cb,
+                            hipStream_t s);  // transposed: out[code][query] (queries = rows of Pi^T: dequantisation)
 
 // codec stages
 hipError_t launch_stage_pack(const Codebook& cb, int d, const float* y, int64_t n, uint32_t* idx,

@@ -55,8 +55,9 @@ struct Bf3Args {
   const float* gamma;
   const float* norm;  // nullable: unit-norm codes
   int64_t n;          // codes per group
-  float* out;         // [groups * M][ldo]
+  float* out;         // [groups * M][ldo]; transposed: [groups * n][ldo], M values per code
   int64_t ldo;
+  int transposed;
   float kappa;
   Codebook cb;
 };
@@ -329,6 +330,29 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
     const int64_t crow = (int64_t)group * a.n + (col_live ? col : a.n - 1);
     const float nu = a.norm != nullptr ? a.norm[crow] : 1.f;
     const float kg = PROD ? a.kappa * a.gamma[crow] : 0.f;
+    if (a.transposed) {
+      // one row per code (dequantisation: the "queries" are the rows of Pi^T, the result is x~): a lane owns
+      // four consecutive values of its code's row per accumulator quad
+      float* const orow = a.out + crow * a.ldo;
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+          const int row = m0 + 64 * wm + 32 * rt + 8 * qd + 4 * (lane >> 5);
+          f32x4 v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            v[e] = nu * fmaf(kg, PROD ? acc2[rt][ct][4 * qd + e] : 0.f, c1 * acc1[rt][ct][4 * qd + e]);
+          if (col_live && row + 3 < a.M) {
+            *reinterpret_cast<f32x4*>(orow + row) = v;
+          } else if (col_live) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (row + e < a.M) orow[row + e] = v[e];
+          }
+        }
+      continue;
+    }
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
@@ -376,8 +400,10 @@ bool score_bf3_applicable(int bits, bool prod, int d, int64_t n, int n_groups, i
 
 hipError_t launch_score_bf3(int bits, bool prod, const float* qr, const float* qs, int q_per_group, int d,
                             const uint32_t* idx, const uint32_t* qjl, const float* gamma, const float* norm, int64_t n,
-                            int n_groups, float* out, int64_t ldo, float kappa, const Codebook& cb, hipStream_t s) {
+                            int n_groups, float* out, int64_t ldo, bool transposed, float kappa, const Codebook& cb,
+                            hipStream_t s) {
   Bf3Args a;
+  a.transposed = transposed ? 1 : 0;
   a.qr = qr; a.qs = qs; a.M = q_per_group; a.d = d; a.idx = idx; a.qjl = qjl; a.gamma = gamma; a.norm = norm;
   a.n = n; a.out = out; a.ldo = ldo; a.kappa = kappa; a.cb = cb;
   switch (bits * 2 + (prod ? 1 : 0)) {
