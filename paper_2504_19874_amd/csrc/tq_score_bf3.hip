@@ -10,7 +10,7 @@
 // one piece: z = +-1 is a bf16 value, and a 1-bit codebook is +-c_1 with c_1 applied after the sum; those
 // products take three MFMAs (q1, q2, q3).
 //
-// Workgroup = 512 threads = 8 wavefronts, tile 128 queries x 256 codes, k in steps of 16 (one
+// Workgroup = 512 threads = 8 wavefronts, tile 128 or 256 queries x 256 or 128 codes, k in steps of 16 (one
 // v_mfma_f32_32x32x16_bf16 per piece product and 32 x 32 sub-tile), operands through two LDS buffers with a
 // 48-byte row stride (conflict-free 16-byte reads).  Queries are split into pieces while they are staged
 // (read as fp32: 4 bytes per element instead of 6); codes are decoded into pieces while they are staged
@@ -28,11 +28,11 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int TN = 256, KT = 16;  // codes per tile, k per step; queries per tile: 128 or 256 (template parameter)
+constexpr int KT = 16;  // k per step; queries per tile TM: 128 or 256, codes per tile TN: 256 or 128 (template parameters)
 constexpr int LDK = 24;      // bf16 per LDS row: 16 used + 8 padding = 48 bytes
 constexpr int SPAN = 4;      // coordinate groups (of 32) whose plane words a thread holds at a time
 
-template <int BITS, bool PROD, int TM>
+template <int BITS, bool PROD, int TM, int TN>
 struct Cfg {
   static constexpr int WM = TM / 64, WN = 8 / WM;  // wavefronts along the queries / the codes
   static constexpr int CT = TN / (32 * WN);        // 32-column sub-tiles of a wavefront (2 row sub-tiles always)
@@ -92,9 +92,10 @@ __device__ __forceinline__ void split3_pair(f32x2 x, uint32_t& w1, uint32_t& w2,
   w3 = bf16_pair(r2);
 }
 
-template <int BITS, bool PROD, int TM>
+template <int BITS, bool PROD, int TM, int TN>
 __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
-  using C = Cfg<BITS, PROD, TM>;
+  using C = Cfg<BITS, PROD, TM, TN>;
+  constexpr int CP = TN / 32;  // coordinates of one code a thread decodes per step: 8 or 4
   constexpr int PC = C::PC;
   constexpr int CT = C::CT;
   constexpr int AR = TM / 128;  // 16-byte pieces of a query tile row set a thread stages per segment
@@ -129,8 +130,8 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
     a_src0[i] = a.qr + ((int64_t)group * a.M + r) * a.d + a_k;
     a_src1[i] = PROD ? a.qs + ((int64_t)group * a.M + r) * a.d + a_k : nullptr;
   }
-  // B: thread = (code tid % 256, eight consecutive k at 8 (tid / 256))
-  const int b_col = tid & 255, b_half = tid >> 8;
+  // B: thread = (code tid % TN, CP consecutive k at CP (tid / TN))
+  const int b_col = tid % TN, b_part = tid / TN;
   const int64_t b_row = (int64_t)group * a.n + (n0 + b_col < a.n ? n0 + b_col : a.n - 1);
   const uint32_t* const b_idx = a.idx + b_row * ((int64_t)gw * BITS);
   const uint32_t* const b_qjl = PROD ? a.qjl + b_row * gw : nullptr;
@@ -170,41 +171,51 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
       ++seg;
     }
   };
-  // eight sign bits -> eight bf16 values +-1 (bit set: +1)
-  auto signs8 = [&](uint32_t b8) -> u32x4 {
-    u32x4 v;
+  // CP sign bits -> CP bf16 values +-1 (bit set: +1), two per word
+  auto signs = [&](uint32_t bits, uint32_t (&v)[CP / 2]) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e)
-      v[e] = 0xBF80BF80u ^ (((b8 >> (2 * e)) & 1u) << 15) ^ (((b8 >> (2 * e + 1)) & 1u) << 31);
-    return v;
+    for (int e = 0; e < CP / 2; ++e)
+      v[e] = 0xBF80BF80u ^ (((bits >> (2 * e)) & 1u) << 15) ^ (((bits >> (2 * e + 1)) & 1u) << 31);
+  };
+  auto put = [&](unsigned short* dst, const uint32_t (&v)[CP / 2]) {  // CP bf16 values: 16 or 8 bytes
+    if (CP == 8) *reinterpret_cast<u32x4*>(dst) = u32x4{v[0], v[1], v[CP / 2 - 2], v[CP / 2 - 1]};
+    else *reinterpret_cast<uint2*>(dst) = make_uint2(v[0], v[1]);
   };
   auto store_b = [&](unsigned short* buf, int j) {  // j: step within its span of 2 SPAN steps (a constant at every call)
     unsigned short* const bb = buf + C::A_ELEMS;
-    const int g = j >> 1, off = (j & 1) * 16 + 8 * b_half;  // word of the span, first bit
+    const int g = j >> 1, off = (j & 1) * 16 + CP * b_part;  // word of the span, first bit
     if (PC == 1) {
-      *reinterpret_cast<u32x4*>(bb + b_col * LDK + 8 * b_half) = signs8((wcur[g][0] >> off) & 0xFFu);
+      uint32_t v[CP / 2];
+      signs(wcur[g][0] >> off, v);
+      put(bb + b_col * LDK + CP * b_part, v);
     } else if (PC == 3) {
-      uint32_t lv[2] = {0u, 0u};  // bucket numbers of 4 coordinates, one per byte
+      uint32_t lv[CP / 4];  // bucket numbers of 4 coordinates, one per byte
 #pragma unroll
-      for (int h = 0; h < 2; ++h)
+      for (int h = 0; h < CP / 4; ++h) {
+        lv[h] = 0u;
 #pragma unroll
         for (int pl = 0; pl < BITS; ++pl)
           lv[h] |= ((((wcur[g][pl] >> (off + 4 * h)) & 0xFu) * 0x00204081u) & 0x01010101u) << pl;
-      uint2 e[8];
+      }
+      uint2 e[CP];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) e[u] = table_s[(lv[u >> 2] >> (8 * (u & 3))) & 0xFFu];
-      u32x4 v1, v2, v3;
+      for (int u = 0; u < CP; ++u) e[u] = table_s[(lv[u >> 2] >> (8 * (u & 3))) & 0xFFu];
+      uint32_t v1[CP / 2], v2[CP / 2], v3[CP / 2];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < CP / 2; ++u) {
         v1[u] = __builtin_amdgcn_perm(e[2 * u + 1].x, e[2 * u].x, 0x05040100u);  // low halves: first pieces
         v2[u] = __builtin_amdgcn_perm(e[2 * u + 1].x, e[2 * u].x, 0x07060302u);  // high halves: second pieces
         v3[u] = __builtin_amdgcn_perm(e[2 * u + 1].y, e[2 * u].y, 0x05040100u);
       }
-      *reinterpret_cast<u32x4*>(bb + (0 * TN + b_col) * LDK + 8 * b_half) = v1;
-      *reinterpret_cast<u32x4*>(bb + (1 * TN + b_col) * LDK + 8 * b_half) = v2;
-      *reinterpret_cast<u32x4*>(bb + (2 * TN + b_col) * LDK + 8 * b_half) = v3;
+      put(bb + (0 * TN + b_col) * LDK + CP * b_part, v1);
+      put(bb + (1 * TN + b_col) * LDK + CP * b_part, v2);
+      put(bb + (2 * TN + b_col) * LDK + CP * b_part, v3);
     }
-    if (PROD) *reinterpret_cast<u32x4*>(bb + (PC * TN + b_col) * LDK + 8 * b_half) = signs8((zcur[g] >> off) & 0xFFu);
+    if (PROD) {
+      uint32_t v[CP / 2];
+      signs(zcur[g] >> off, v);
+      put(bb + (PC * TN + b_col) * LDK + CP * b_part, v);
+    }
   };
   auto take_words = [&]() {
 #pragma unroll
@@ -364,28 +375,31 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
   }
 }
 
-template <int BITS, bool PROD, int TM>
+template <int BITS, bool PROD, int TM, int TN>
 hipError_t launch_tile(const Bf3Args& a, int n_groups, hipStream_t s) {
-  using C = Cfg<BITS, PROD, TM>;
+  using C = Cfg<BITS, PROD, TM, TN>;
   if (!C::FITS) return hipErrorInvalidValue;
   static bool attr_done = false;  // per instantiation: the limit has to be raised once
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_bf3_kernel<BITS, PROD, TM>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_bf3_kernel<BITS, PROD, TM, TN>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   const dim3 grid((unsigned)((a.n + TN - 1) / TN), (unsigned)((a.M + TM - 1) / TM), n_groups);
-  hipLaunchKernelGGL((score_bf3_kernel<BITS, PROD, TM>), grid, dim3(512), C::LDS_BYTES, s, a);
+  hipLaunchKernelGGL((score_bf3_kernel<BITS, PROD, TM, TN>), grid, dim3(512), C::LDS_BYTES, s, a);
   return hipGetLastError();
 }
 
 // 256 queries per tile halve the LDS reads per MFMA (a wavefront's sub-tiles share fragments), which is what
 // bounds the 128-row tile; the accumulators of two segments do not fit that shape
+// Two-stage codes with more than one index bit need four code-side operands (three centroid pieces and the
+// signs): 128 codes per tile, so that two buffers still fit.
 template <int BITS, bool PROD>
 hipError_t launch_one(const Bf3Args& a, int n_groups, hipStream_t s) {
-  if (!PROD && a.M > 128) return launch_tile<BITS, PROD, PROD ? 128 : 256>(a, n_groups, s);
-  return launch_tile<BITS, PROD, 128>(a, n_groups, s);
+  if (PROD && BITS >= 2) return launch_tile<BITS, PROD, 128, 128>(a, n_groups, s);
+  if (!PROD && a.M > 128) return launch_tile<BITS, PROD, PROD ? 128 : 256, 256>(a, n_groups, s);
+  return launch_tile<BITS, PROD, 128, (PROD && BITS >= 2) ? 128 : 256>(a, n_groups, s);
 }
 
 }  // namespace
@@ -395,7 +409,7 @@ bool score_bf3_applicable(int bits, bool prod, int d, int64_t n, int n_groups, i
   if (d % 32 != 0 || n <= 0 || q_per_group <= 0 || n_groups > 65535 || (q_per_group + 127) / 128 > 65535) return false;
   if (bits == 0) return prod;
   if (bits == 1) return cb.c[0] == -cb.c[1];
-  return bits <= 4 && !prod;  // wider codes with the sign segment do not fit two buffers
+  return bits <= 4;
 }
 
 hipError_t launch_score_bf3(int bits, bool prod, const float* qr, const float* qs, int q_per_group, int d,
@@ -411,8 +425,11 @@ hipError_t launch_score_bf3(int bits, bool prod, const float* qr, const float* q
     case 2: return launch_one<1, false>(a, n_groups, s);
     case 3: return launch_one<1, true>(a, n_groups, s);
     case 4: return launch_one<2, false>(a, n_groups, s);
+    case 5: return launch_one<2, true>(a, n_groups, s);
     case 6: return launch_one<3, false>(a, n_groups, s);
+    case 7: return launch_one<3, true>(a, n_groups, s);
     case 8: return launch_one<4, false>(a, n_groups, s);
+    case 9: return launch_one<4, true>(a, n_groups, s);
     default: return hipErrorInvalidValue;
   }
 }

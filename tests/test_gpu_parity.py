@@ -131,7 +131,7 @@ def _quant_inputs(n, d, kind, seed):
     (128, 2, 4096, "unit"), (128, 1, 300, "f32"), (128, 3, 129, "bf16"), (128, 4, 1, "f32"),
     (256, 4, 515, "unit"), (96, 2, 257, "f32"), (1536, 4, 300, "unit"), (3072, 1, 140, "bf16"),
     (64, 0, 40, "f32"),
-    # d = 128 above the small-batch threshold: the streaming kernel
+    # d = 128 above the small-batch threshold: the bf16-piece contraction (rows of Pi^T as queries)
     (128, 1, 30000, "f32"), (128, 4, 25000, "unit"), (128, 3, 40000, "bf16"),
 ])
 def test_quantize_mse(d, bits, n, kind):
@@ -179,7 +179,7 @@ def _check_prod(p, Pi, S, c32, t32, x_or, normalise, idx, qjl, gamma, norm):
 @pytest.mark.parametrize("d,bits_mse,n,kind", [
     (128, 2, 2000, "bf16"), (128, 3, 129, "f32"), (128, 1, 4096, "unit"), (128, 0, 100, "f32"),
     (256, 2, 300, "unit"), (1536, 1, 200, "unit"), (96, 4, 130, "f32"),
-    # d = 128 above the small-batch threshold: the streaming kernel
+    # d = 128 above the small-batch threshold: the bf16-piece contraction (rows of Pi^T as queries)
     (128, 0, 26000, "f32"), (128, 1, 33000, "unit"), (128, 4, 25001, "bf16"),
 ])
 def test_quantize_prod(d, bits_mse, n, kind):
@@ -235,7 +235,7 @@ def test_empty_and_error_paths():
 @pytest.mark.parametrize("d,bits_mse,n,prod,with_norm", [
     (128, 2, 1000, True, True), (128, 4, 129, False, False), (256, 3, 260, True, False),
     (1536, 4, 150, False, True), (128, 0, 64, True, True), (96, 1, 131, True, True),
-    # d = 128 above the small-batch threshold: the streaming kernel
+    # d = 128 above the small-batch threshold: the bf16-piece contraction (rows of Pi^T as queries)
     (128, 2, 30000, True, True), (128, 3, 25000, False, False), (128, 0, 26001, True, True), (128, 4, 24600, False, True),
 ])
 def test_dequantize(d, bits_mse, n, prod, with_norm):
@@ -271,7 +271,8 @@ def test_dequantize(d, bits_mse, n, prod, with_norm):
     # 128 queries x 256 codes with ragged edges on both sides, several groups, d that is not a multiple of 128
     (3072, 1, True, 1, 100, 700, 10), (128, 0, True, 1, 70, 300, 0), (160, 3, False, 2, 129, 513, 4),
     (1536, 2, False, 1, 200, 300, 0), (96, 1, False, 1, 65, 1000, 0), (1536, 4, False, 1, 257, 1025, 10),
-    (128, 1, True, 3, 33, 257, 0),
+    (128, 1, True, 3, 33, 257, 0), (1536, 2, True, 1, 150, 700, 0), (128, 2, True, 1, 200, 3000, 6),
+    (256, 4, True, 2, 70, 130, 0),
     # d = 256..512: preparation kernel + int8 scoring kernel
     (256, 2, True, 2, 4, 1500, 0), (256, 4, True, 1, 3, 600, 0), (512, 1, False, 1, 8, 700, 0),
     (384, 3, True, 1, 2, 300, 0), (512, 4, False, 1, 4, 1100, 5),
