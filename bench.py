@@ -247,6 +247,10 @@ def main():
         "quantize_vectors_per_s": n / (per_call_ms[0] * 1e-3),
         "scores_per_s": float(cfg.nq) * cfg.n / (per_call_ms[2] * 1e-3),
         "roofline": roof,
+        # what each call multiplies in; every result meets the fp32 tolerances of the parity tests
+        "arithmetic": {"quantize": "fp32 MFMA (rotation and sketch), fp32 bucket decision",
+                       "dequantize": "bf16 MFMA on exact three-piece splits of the fp32 factors, fp32 accumulation",
+                       "score": "int8 MFMA on exact base-128 digits of 2^-19-scaled rotated queries, fp32 combination"},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, host_x, q)
