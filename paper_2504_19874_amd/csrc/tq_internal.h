@@ -83,6 +83,12 @@ hipError_t launch_dequant128(int bits, bool prod, const uint32_t* idx, const uin
                              float* out, int64_t ldo, int64_t n, float kappa, const Codebook& cb,
                              int gs_hi, float kappa_hi, const Codebook& cb_hi, hipStream_t s);
 
+// d = 128, large batches, bf16 matrix cores at fp32 accuracy (tq_d128_bf3.hip)
+bool dequant128_bf3_applicable(int bits, bool prod, const Codebook& cb);
+hipError_t launch_dequant128_bf3(int bits, bool prod, const uint32_t* idx, const uint32_t* qjl, const float* gamma,
+                                 const float* norm, const float* PiT, const float* ST, float* out, int64_t ldo, int64_t n,
+                                 float kappa, const Codebook& cb, hipStream_t s);
+
 // few queries per code (tq_score_small.hip)
 hipError_t launch_matvec_small(int d, int nq, const float* W0, const float* W1, const float* x,
                                int64_t ldx, float* out0, float* out1, hipStream_t stream);

@@ -17,16 +17,12 @@
 // (bit planes -> bucket number -> 3-piece table in LDS, or straight to +-1).  Wavefront (wm, wn) owns rows
 // 64 wm .. and columns 64 wn .. of the tile: 2 x 2 sub-tiles, one accumulator set per segment (the sign
 // segment is scaled per code by kappa gamma, so it cannot share the accumulator of the first).
-#include "tq_internal.h"
+#include "tq_bf3.h"
 
 namespace tq {
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int KT = 16;  // k per step; queries per tile TM: 128 or 256, codes per tile TN: 256 or 128 (template parameters)
 constexpr int LDK = 24;      // bf16 per LDS row: 16 used + 8 padding = 48 bytes
@@ -61,36 +57,6 @@ struct Bf3Args {
   float kappa;
   Codebook cb;
 };
-
-__device__ __forceinline__ uint32_t bf16_bits(float x) {  // round to nearest even
-  const __bf16 h = (__bf16)x;
-  return (uint32_t) * reinterpret_cast<const unsigned short*>(&h);
-}
-
-// x -> (x1, x2, x3), three bf16 values with x1 + x2 + x3 == x
-__device__ __forceinline__ void split3(float x, uint32_t& p1, uint32_t& p2, uint32_t& p3) {
-  p1 = bf16_bits(x);
-  const float r1 = x - __uint_as_float(p1 << 16);
-  p2 = bf16_bits(r1);
-  const float r2 = r1 - __uint_as_float(p2 << 16);
-  p3 = bf16_bits(r2);
-}
-
-// the same for two values at once: word k holds piece k of x[0] (low half) and of x[1] (high half); one
-// packed conversion per piece
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ uint32_t bf16_pair(f32x2 x) {
-  const bf16x2 h = __builtin_convertvector(x, bf16x2);
-  return *reinterpret_cast<const uint32_t*>(&h);
-}
-__device__ __forceinline__ void split3_pair(f32x2 x, uint32_t& w1, uint32_t& w2, uint32_t& w3) {
-  w1 = bf16_pair(x);
-  const f32x2 r1 = {x[0] - __uint_as_float(w1 << 16), x[1] - __uint_as_float(w1 & 0xffff0000u)};
-  w2 = bf16_pair(r1);
-  const f32x2 r2 = {r1[0] - __uint_as_float(w2 << 16), r1[1] - __uint_as_float(w2 & 0xffff0000u)};
-  w3 = bf16_pair(r2);
-}
 
 template <int BITS, bool PROD, int TM, int TN>
 __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
