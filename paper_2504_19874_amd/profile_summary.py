@@ -19,12 +19,15 @@ import collections
 import csv
 import glob
 import json
+import re
 import os
 import sys
 
 COPY_KIB = 256 * 1024  # what bench.py --calibration-copy reads and writes
 # kernel name prefix -> entry point whose dominant kernel it is
 ENTRY_OF = (("tq::quant128_kernel", "tq_quantize_prod"), ("tq::dequant128_kernel", "tq_dequantize"),
+            ("tq::(anonymous namespace)::dequant128_bf3_kernel", "tq_dequantize"),
+            ("tq::(anonymous namespace)::score_bf3_kernel", "tq_score"),
             ("tq::score_i8_128_kernel", "tq_score"), ("tq::score_i8_kernel", "tq_score"),
             ("tq::score_small_kernel", "tq_score"), ("tq::gemm_kernel<0, 2", "tq_quantize"),
             ("tq::gemm_kernel<1, 2", "tq_quantize"), ("tq::gemm_kernel<2, 0", "tq_dequantize"),
@@ -82,7 +85,7 @@ def traffic(fetch_dir, write_dir, workload, json_path):
         total = (f * f_scale + w * w_scale) * 1024
         print(f"| {entry} | `{short(k, 70)}` | {len(fetch[k])} | {f:.1f} | {w:.1f} | {total / 1e6:.2f} MB |")
         if entry and len(fetch[k]) > 2:
-            table[entry] = {"kernel": name.split("(")[0], "fetch_kib_raw": round(f, 1), "write_kib_raw": round(w, 1),
+            table[entry] = {"kernel": re.match(r"(.*?kernel(?:<[^>]*>)?)", name).group(1) if "kernel" in name else name.split("(")[0], "fetch_kib_raw": round(f, 1), "write_kib_raw": round(w, 1),
                             "fetch_scale": round(f_scale, 4), "write_scale": round(w_scale, 4),
                             "traffic_bytes": int(total), "launches_averaged": len(fetch[k])}
     if json_path:
