@@ -77,7 +77,8 @@ hipError_t launch_dequant128_small(int bits, bool prod, const uint32_t* idx, con
                                    const float* gamma, const float* norm, const float* Pi, const float* S,
                                    float* out, int64_t ldo, int64_t n, float kappa, const Codebook& cb,
                                    int gs_hi, float kappa_hi, const Codebook& cb_hi, hipStream_t s);
-constexpr int64_t kSmallDequantRows = 24576;
+constexpr int64_t kSmallDequantRows = 24576;  // crossover of the two fp32 kernels
+constexpr int64_t kBf3DequantRows = 8192;     // above this the bf16-piece kernel wins (12 us at 32768 against 37)
 hipError_t launch_dequant128(int bits, bool prod, const uint32_t* idx, const uint32_t* qjl,
                              const float* gamma, const float* norm, const float* Pi, const float* S,
                              float* out, int64_t ldo, int64_t n, float kappa, const Codebook& cb,

@@ -237,6 +237,7 @@ def test_empty_and_error_paths():
     (1536, 4, 150, False, True), (128, 0, 64, True, True), (96, 1, 131, True, True),
     # d = 128 above the small-batch threshold: the bf16-piece contraction (rows of Pi^T as queries)
     (128, 2, 30000, True, True), (128, 3, 25000, False, False), (128, 0, 26001, True, True), (128, 4, 24600, False, True),
+    (128, 1, 8200, True, True), (128, 1, 9000, False, False), (128, 2, 8193, True, False),
 ])
 def test_dequantize(d, bits_mse, n, prod, with_norm):
     p, Pi, S, c32, t32 = setup(d, bits_mse, prod)
