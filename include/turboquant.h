@@ -185,8 +185,11 @@ tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_gr
  * ever written.
  *   pk, pv    parameters of the key and of the value codes (they may be the
  *             same object).  Key codes: anything tq_score accepts, including
- *             the two-instance split.  Value codes: one instance (d_hi == 0),
- *             bits_mse >= 0; v_qjl/v_gamma NULL for an MSE value cache.
+ *             the two-instance split.  Value codes: one instance with
+ *             bits_mse >= 0 (v_qjl/v_gamma NULL for an MSE value cache), or two
+ *             instances of the MSE quantiser at d = 128 with 1 + 2 or 2 + 3 index
+ *             bits (v_norm then holds two floats per token, as tq_quantize_mse
+ *             writes them).
  *   k_*, v_*  device, codes of n_groups*n_per_group tokens, layouts as above.
  *   out       device out [n_groups*q_per_group][ldo], pv->d floats per row;
  *             zero rows when n_per_group == 0.

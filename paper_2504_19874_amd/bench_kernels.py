@@ -64,6 +64,8 @@ def main():
     ap.add_argument("--only", default="")
     ap.add_argument("--value-bits", type=int, default=2, help="attend: bits of the MSE stage of the value codes")
     ap.add_argument("--value-prod", action="store_true", help="attend: value codes from TurboQuant_prod")
+    ap.add_argument("--value-split", type=int, default=0, metavar="D_HI",
+                    help="attend: value codes in two MSE instances, D_HI outlier channels with one more bit")
     args = ap.parse_args()
 
     import numpy as np
@@ -172,15 +174,21 @@ def main():
     if on("attend") and not cfg.topk and cfg.q_per_group <= 32 and not big:
         # attention read-out: the key codes above plus a value cache of the same shape
         vprod = args.value_prod
-        pv = tq.make_params(d, args.value_bits, W.gaussian_matrix(d, cfg.seed_pi + 7),
-                            W.sketch_matrix(d, cfg.seed_s + 7) if vprod else None).reserve(n, nq, 0)
+        if args.value_split:
+            vhi = W.kv_hi_channels(cfg.n_groups, d, cfg.seed_x + 9, args.value_split)
+            pv = tq.make_mixed_params(d, vhi, args.value_bits + 1, args.value_bits,
+                                      W.gaussian_matrix(args.value_split, cfg.seed_pi + 7),
+                                      W.gaussian_matrix(d - args.value_split, cfg.seed_pi + 8), None, None).reserve(n, nq, 0)
+        else:
+            pv = tq.make_params(d, args.value_bits, W.gaussian_matrix(d, cfg.seed_pi + 7),
+                                W.sketch_matrix(d, cfg.seed_s + 7) if vprod else None).reserve(n, nq, 0)
         vsets = []
         for s in range(sets):
             v = torch.from_numpy(W.unit_gaussian_rows(n, d, cfg.seed_x + 500 + s)).cuda() * 2.0
             vc = dict(idx=torch.zeros((n, max(1, pv.idx_words)), dtype=torch.int32, device="cuda"),
                       qjl=torch.zeros((n, pv.qjl_words), dtype=torch.int32, device="cuda") if vprod else None,
                       gamma=torch.zeros(n, dtype=torch.float32, device="cuda") if vprod else None,
-                      norm=torch.zeros(n, dtype=torch.float32, device="cuda"))
+                      norm=torch.zeros((n, pv.scalars_per_vector), dtype=torch.float32, device="cuda"))
             if vprod:
                 tq.tq_quantize_prod(pv, v, vc["idx"], vc["qjl"], vc["gamma"], vc["norm"])
             else:
@@ -196,8 +204,10 @@ def main():
                          (vc["idx"], vc["qjl"], vc["gamma"], vc["norm"]), cfg.n, 1.0 / d ** 0.5, outs[r % len(outs)])
 
         pairs = float(nq) * cfg.n
-        vcode_b = 4 * pv.idx_words + 4 + (d / 8 + 4 if vprod else 0)
-        report(f"attend(v{'prod' if vprod else 'mse'}{args.value_bits})", cfg, timed(attend, reps),
+        vcode_b = 4 * pv.idx_words + 4 * pv.scalars_per_vector + (d / 8 + 4 if vprod else 0)
+        vname = f"split{args.value_split}:{args.value_bits + 1}+{args.value_bits}" if args.value_split else \
+            f"{'prod' if vprod else 'mse'}{args.value_bits}"
+        report(f"attend(v{vname})", cfg, timed(attend, reps),
                2.0 * pairs * d * ((2 if prod else 1) + (2 if vprod else 1)), n * (code_b + vcode_b) + 8 * nq * d,
                {"pairs": pairs}, bound="hbm")  # the contractions run on the int8 cores; the codes are read once
 

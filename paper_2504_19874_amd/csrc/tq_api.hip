@@ -441,7 +441,9 @@ struct AttendPlan {
 };
 AttendPlan attend_plan(const tq_params* pk, const tq_params* pv, bool v_prod, int64_t nq, int64_t n_per_group) {
   AttendPlan pl;
-  pl.fast = pv->centroids != nullptr && attend128_applicable(pv->d, v_prod, make_codebook(pv));
+  const Codebook v_hi = make_codebook_hi(pv);
+  pl.fast = pv->centroids != nullptr && (pv->d_hi == 0 || pv->centroids_hi != nullptr) &&
+            attend128_applicable(pv->d, v_prod, make_codebook(pv), pv->d_hi != 0 ? &v_hi : nullptr);
   pl.nchunks = pl.fast ? attend128_chunks(n_per_group) : attend_simple_chunks(n_per_group);
   pl.ld_scores = (n_per_group + 3) / 4 * 4;
   pl.scores_bytes = round_up((size_t)nq * pl.ld_scores * sizeof(float), 256);
@@ -476,10 +478,12 @@ tq_status tq_attend(const tq_params* pk, const tq_params* pv, const float* q, in
   if (out == nullptr || pv->Pi == nullptr || (v_prod && (v_gamma == nullptr || pv->S == nullptr)))
     return TQ_ERR_INVALID_ARG;
   if (n_per_group > 0 && (v_norm == nullptr || (pv->bits_mse > 0 && v_idx == nullptr))) return TQ_ERR_INVALID_ARG;
-  if (pv->d_hi != 0 || pv->d > 4096 || n_groups > 65535 || q_per_group > 4 * 65535) return TQ_ERR_UNSUPPORTED;
+  if (pv->d > 4096 || n_groups > 65535 || q_per_group > 4 * 65535) return TQ_ERR_UNSUPPORTED;
   hipStream_t s = static_cast<hipStream_t>(stream);
 
   const AttendPlan pl = attend_plan(pk, pv, v_prod, nq, n_per_group);
+  // value codes of two instances: the d = 128 kernel or nothing
+  if (pv->d_hi != 0 && !pl.fast) return TQ_ERR_UNSUPPORTED;
   if (pl.nchunks > 4096) return TQ_ERR_UNSUPPORTED;  // the joining kernel keeps one factor per chunk in LDS
   Workspace ws{static_cast<char*>(pk->workspace), pk->workspace_bytes, 0};
   float* scores = static_cast<float*>(ws.take(pl.scores_bytes));
@@ -491,7 +495,7 @@ tq_status tq_attend(const tq_params* pk, const tq_params* pv, const float* q, in
     a.scores = scores; a.lds = pl.ld_scores;
     a.idx = v_idx; a.qjl = v_qjl; a.gamma = v_gamma; a.norm = v_norm;
     a.part = part; a.nchunks = pl.nchunks; a.n = n_per_group; a.d = pv->d; a.q_per_group = q_per_group;
-    a.scale = scale; a.cb = make_codebook(pv);
+    a.scale = scale; a.cb = make_codebook(pv); a.gs_hi = pv->d_hi / 32; a.cb_hi = make_codebook_hi(pv);
     // keys the single-kernel d = 128 scoring path takes are scored inside the read-out kernel
     const bool k_prod = k_qjl != nullptr;
     ScoreI8Args ka;

@@ -22,12 +22,14 @@ struct AttendArgs {
   int d;
   int q_per_group;
   float scale;
-  Codebook cb;          // of the value codes
+  Codebook cb;          // of the value codes (two instances: of instance lo)
+  int gs_hi;            // two instances: coordinate groups of instance hi (0: one instance); norm is [n][2] then
+  Codebook cb_hi;
 };
 
 // d = 128 on the integer matrix cores (tq_attend_128.hip)
 int attend128_chunks(int64_t n);
-bool attend128_applicable(int d, bool prod, const Codebook& cb);
+bool attend128_applicable(int d, bool prod, const Codebook& cb, const Codebook* cb_hi);
 struct ScoreI8Args;
 hipError_t launch_attend128(int kb, bool kprod, const ScoreI8Args* ka, bool vprod, const AttendArgs& a, int n_groups,
                             hipStream_t s);

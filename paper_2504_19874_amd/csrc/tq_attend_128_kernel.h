@@ -30,6 +30,8 @@
 #include "tq_attend.h"
 #include "tq_score_i8_128_body.h"
 
+#include <type_traits>
+
 namespace tq {
 
 constexpr int AT_WAVE_KEYS = 256;                    // keys a wavefront owns
@@ -42,13 +44,13 @@ constexpr int AT_RED_FLOATS = 3 * 8 * 4;  // [maxima | norm maxima | sums][wave]
 
 // dynamic LDS: digits, exchange area (or, before them in time, what the scoring body needs), then the
 // reduction scratch, which is written while other wavefronts may still be scoring
-// (vprod: a second set of weight digits and the sign plane of the value codes)
-__host__ __device__ constexpr int attend128_work_bytes(int kb, int vb, bool vprod, bool fused) {
-  const int own = (vprod ? 2 : 1) * AT_WD_BYTES + (vb + (vprod ? 1 : 0)) * AT_XCH_BYTES;
+// (two: a second set of weight digits and one more plane: the signs of Alg. 2, or the top plane of instance hi)
+__host__ __device__ constexpr int attend128_work_bytes(int kb, int vb, bool two, bool fused) {
+  const int own = (two ? 2 : 1) * AT_WD_BYTES + (vb + (two ? 1 : 0)) * AT_XCH_BYTES;
   return fused && score128_lds(kb) > own ? score128_lds(kb) : own;
 }
-__host__ __device__ constexpr int attend128_lds(int kb, int vb, bool vprod, bool fused) {
-  return attend128_work_bytes(kb, vb, vprod, fused) + AT_RED_FLOATS * 4;
+__host__ __device__ constexpr int attend128_lds(int kb, int vb, bool two, bool fused) {
+  return attend128_work_bytes(kb, vb, two, fused) + AT_RED_FLOATS * 4;
 }
 
 struct AttendCoefs {
@@ -88,11 +90,16 @@ __device__ __forceinline__ void transpose16x32(uint32_t (&x)[16]) {
 }
 
 // ka: arguments of the scoring body (FUSED only); a: value codes, partial results, and with !FUSED the score matrix
-template <int KB, bool KPROD, int VB, bool VPROD, bool FUSED>
-__global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, const AttendArgs a, const AttendCoefs cf) {
+// VKIND, the kind of value code: 0 = Alg. 1; 1 = Alg. 2 (one more plane: the signs, with weights ... * gamma);
+// 2 = two instances of Alg. 1 over a split of the coordinates (Sec. 4.3): groups g < a.gs_hi have VB + 1 index
+// planes, the table cfh and the weights exp(.) * nu_hi, the others VB planes, cf and exp(.) * nu_lo.
+template <int KB, bool KPROD, int VB, int VKIND, bool FUSED>
+__global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, const AttendArgs a, const AttendCoefs cf,
+                                                        const AttendCoefs cfh) {
+  constexpr bool VPROD = VKIND == 1, VSPLIT = VKIND == 2, TWO = VKIND != 0;  // TWO: a second set of weights
   __shared__ __attribute__((aligned(16))) uint2 expand_s[256 * I8_COPIES];  // byte -> one byte per bit, 32 copies
   extern __shared__ __attribute__((aligned(16))) unsigned char dyn_s[];
-  constexpr int NPL = VB + (VPROD ? 1 : 0);  // bit planes of a value code: index planes, then the signs of Alg. 2
+  constexpr int NPL = VB + (TWO ? 1 : 0);  // bit planes of a value code: index planes, then the signs of Alg. 2 / the top plane of instance hi
   constexpr int NVB = VB > 0 ? VB : 1;
   constexpr int ROUNDS = (NPL + 1) / 2;       // planes a transposing lane takes: ph, ph + 2
   const int tid = threadIdx.x;
@@ -101,12 +108,12 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
   const int col = lane & 15;  // key within a tile; B column (coordinate within a block of 16); A row (query, digit)
   const int kc = lane >> 4;   // query of this lane's logits and sums; k-chunk (16 keys of a k-block)
   const int chunk = blockIdx.x, group = blockIdx.y, q0 = blockIdx.z * 4;
-  constexpr int WD_ALL = (VPROD ? 2 : 1) * AT_WD_BYTES;
+  constexpr int WD_ALL = (TWO ? 2 : 1) * AT_WD_BYTES;
   unsigned char* const wd = dyn_s + wave * (4 * 4 * AT_PASS_KEYS);  // digits of exp(.) nu; + AT_WD_BYTES: of exp(.) nu gamma
   uint32_t* const xch = reinterpret_cast<uint32_t*>(dyn_s + WD_ALL) + wave * (8 * 64);  // + plane * 8 * 8 * 64
   float* const fsum_s = reinterpret_cast<float*>(dyn_s + WD_ALL);  // [8][4][128], over the exchange area
   float* const fsumz_s = reinterpret_cast<float*>(dyn_s);          // the same for the sign sums, over the digits
-  float* const red_s = reinterpret_cast<float*>(dyn_s + attend128_work_bytes(KB, VB, VPROD, FUSED));  // [3][8][4]
+  float* const red_s = reinterpret_cast<float*>(dyn_s + attend128_work_bytes(KB, VB, TWO, FUSED));  // [3][8][4]
 
   const int64_t gbase = (int64_t)group * a.n;
   const int64_t wave_key0 = ((int64_t)chunk * 8 + wave) * AT_WAVE_KEYS;
@@ -124,7 +131,13 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
       for (int i = 0; i < 16; ++i) {
         const int64_t key = k0 + i;
         const int64_t row = gbase + (key < a.n ? key : a.n - 1);  // clamped: such keys have weight 0
-        vw[r][i] = plane < VB ? a.idx[row * (4 * VB) + tg * VB + plane] : (VPROD && plane == VB) ? a.qjl[row * 4 + tg] : 0u;
+        if (VSPLIT) {
+          const bool thi = tg < a.gs_hi;
+          const int wpr = 4 * VB + a.gs_hi, woff = thi ? tg * (VB + 1) : a.gs_hi + tg * VB;
+          vw[r][i] = plane < VB + (thi ? 1 : 0) ? a.idx[row * wpr + woff + plane] : 0u;  // no such plane: all-zero mask
+        } else {
+          vw[r][i] = plane < VB ? a.idx[row * (4 * VB) + tg * VB + plane] : (VPROD && plane == VB) ? a.qjl[row * 4 + tg] : 0u;
+        }
       }
     }
   };
@@ -135,8 +148,13 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     const int64_t key = wave_key0 + 64 * e + lane;
-    nuv[e] = key < a.n ? a.norm[gbase + key] : 0.f;
-    ngv[e] = VPROD && key < a.n ? nuv[e] * a.gamma[gbase + key] : 0.f;
+    if (VSPLIT) {  // (nu_hi, nu_lo) per token
+      nuv[e] = key < a.n ? a.norm[2 * (gbase + key) + 1] : 0.f;
+      ngv[e] = key < a.n ? a.norm[2 * (gbase + key)] : 0.f;
+    } else {
+      nuv[e] = key < a.n ? a.norm[gbase + key] : 0.f;
+      ngv[e] = VPROD && key < a.n ? nuv[e] * a.gamma[gbase + key] : 0.f;
+    }
   }
   // the first pass's value codes travel while the keys are scored, where the registers allow it
   constexpr bool EARLY = !FUSED || KB + (KPROD ? 1 : 0) <= 4;
@@ -175,7 +193,7 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
     if (col == 0) red_s[wave * 4 + kc] = v;
     const float nm = wave_max(fmaxf(fmaxf(nuv[0], nuv[1]), fmaxf(nuv[2], nuv[3])));
     if (lane == 1) red_s[32 + wave * 4] = nm;
-    if (VPROD) {
+    if (TWO) {
       const float gm = wave_max(fmaxf(fmaxf(ngv[0], ngv[1]), fmaxf(ngv[2], ngv[3])));
       if (lane == 2) red_s[32 + wave * 4 + 1] = gm;
     }
@@ -186,7 +204,7 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
   for (int w = 0; w < 8; ++w) {
     m = fmaxf(m, red_s[w * 4 + kc]);
     numax = fmaxf(numax, red_s[32 + w * 4]);
-    if (VPROD) ngmax = fmaxf(ngmax, red_s[32 + w * 4 + 1]);
+    if (TWO) ngmax = fmaxf(ngmax, red_s[32 + w * 4 + 1]);
   }
   int enu = 0, eng = 0;
   if (numax > 0.f) (void)frexpf(numax, &enu);  // numax = f * 2^enu, f in [0.5, 1)
@@ -230,7 +248,7 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
       o[AT_PASS_KEYS] = (unsigned char)((Q >> 7) & 127u);
       o[2 * AT_PASS_KEYS] = (unsigned char)((Q >> 14) & 127u);
       o[3 * AT_PASS_KEYS] = (unsigned char)(Q >> 21);
-      if (VPROD) {
+      if (TWO) {
         const float ng = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (16 * (t & 3) + col), __float_as_int(ngv[t >> 2])));
         const uint32_t Z = (uint32_t)__float2int_rn(p * ng * zscale);
         o[AT_WD_BYTES] = (unsigned char)(Z & 127u);
@@ -259,46 +277,53 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) {
       aop[kk] = *reinterpret_cast<const v4i*>(wd + col * AT_PASS_KEYS + kk * 64 + kc * 16);
-      if (VPROD) zop[kk] = *reinterpret_cast<const v4i*>(wd + AT_WD_BYTES + col * AT_PASS_KEYS + kk * 64 + kc * 16);
+      if (TWO) zop[kk] = *reinterpret_cast<const v4i*>(wd + AT_WD_BYTES + col * AT_PASS_KEYS + kk * 64 + kc * 16);
     }
     {
       v4i tot = v4i{0, 0, 0, 0}, ztot = v4i{0, 0, 0, 0};
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk) {
         tot = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[kk], ones, tot, 0, 0, 0);
-        if (VPROD) ztot = __builtin_amdgcn_mfma_i32_16x16x64_i8(zop[kk], ones, ztot, 0, 0, 0);
+        if (TWO) ztot = __builtin_amdgcn_mfma_i32_16x16x64_i8(zop[kk], ones, ztot, 0, 0, 0);
       }
       ftot += digits_sum(tot);
-      if (VPROD) fztot += digits_sum(ztot);
+      if (TWO) fztot += digits_sum(ztot);
     }
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      uint32_t pw[2][NVB], pz[2] = {0u, 0u};
+      constexpr int NPW = VSPLIT ? VB + 1 : NVB;  // index planes read (instance lo: the top one is all zero)
+      uint32_t pw[2][NPW], pz[2] = {0u, 0u};
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk) {
 #pragma unroll
-        for (int pl = 0; pl < VB; ++pl)
+        for (int pl = 0; pl < (VSPLIT ? VB + 1 : VB); ++pl)
           pw[kk][pl] = xch[pl * (8 * 8 * 64) + (4 * kk + kc) * 64 + ((g ^ (kc & 1)) * 16) + col];
         if (VPROD) pz[kk] = xch[VB * (8 * 8 * 64) + (4 * kk + kc) * 64 + ((g ^ (kc & 1)) * 16) + col];
       }
+      // masked sums of one coordinate group: plane subsets of odd size, weights and table of the group's instance
+      auto terms = [&](auto planes_c, const v4i (&wop)[2], const AttendCoefs& tab) {
+        constexpr int NP = decltype(planes_c)::value;
 #pragma unroll
-      for (int mset = 1; mset < (1 << VB); ++mset) {
-        if (!i8_term(mset)) continue;
-        uint32_t mk[2] = {0u, 0u};
+        for (int mset = 1; mset < (1 << NP); ++mset) {
+          if (!i8_term(mset)) continue;
+          uint32_t mk[2] = {0u, 0u};
 #pragma unroll
-        for (int pl = 0; pl < VB; ++pl)
-          if (mset & (1 << pl)) {
-            mk[0] ^= pw[0][pl];
-            mk[1] ^= pw[1][pl];
+          for (int pl = 0; pl < NP; ++pl)
+            if (mset & (1 << pl)) {
+              mk[0] ^= pw[0][pl];
+              mk[1] ^= pw[1][pl];
+            }
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            v4i acc = v4i{0, 0, 0, 0};
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(wop[kk], expand16(mk[kk], h), acc, 0, 0, 0);
+            f[2 * g + h] = fmaf(tab.c[mset], digits_sum(acc), f[2 * g + h]);
           }
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          v4i acc = v4i{0, 0, 0, 0};
-#pragma unroll
-          for (int kk = 0; kk < 2; ++kk) acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop[kk], expand16(mk[kk], h), acc, 0, 0, 0);
-          f[2 * g + h] = fmaf(cf.c[mset], digits_sum(acc), f[2 * g + h]);
         }
-      }
+      };
+      if (VSPLIT && g < a.gs_hi) terms(std::integral_constant<int, VB + 1>{}, zop, cfh);  // uniform
+      else terms(std::integral_constant<int, VB>{}, aop, cf);
       if (VPROD) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -317,7 +342,11 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
   if (col == 0) red_s[64 + wave * 4 + kc] = lsum;
 #pragma unroll
   for (int cb = 0; cb < 8; ++cb) {
-    fsum_s[(wave * 4 + kc) * 128 + 16 * cb + col] = fmaf(cf.c[0], ftot, f[cb]);
+    if (VSPLIT)  // each instance has its own table, weight total and weight scale
+      fsum_s[(wave * 4 + kc) * 128 + 16 * cb + col] = (cb >> 1) < a.gs_hi ? fmaf(cfh.c[0], fztot, f[cb]) * ldexpf(1.f, eng - 26)
+                                                                           : fmaf(cf.c[0], ftot, f[cb]) * ldexpf(1.f, enu - 26);
+    else
+      fsum_s[(wave * 4 + kc) * 128 + 16 * cb + col] = fmaf(cf.c[0], ftot, f[cb]);
     // sum of w z over the keys, z = +-1 from the sign bits: twice the masked sum minus the sum of the weights
     if (VPROD) fsumz_s[(wave * 4 + kc) * 128 + 16 * cb + col] = fmaf(2.f, fz[cb], -fztot);
   }
@@ -331,8 +360,8 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
       if (VPROD) accz += fsumz_s[(w * 4 + qi) * 128 + j];
     }
     float* o = a.part + (((int64_t)group * a.q_per_group + q0 + qi) * a.nchunks + chunk) * attend_part_stride(128);
-    o[4 + j] = acc * ldexpf(1.f, enu - 26);
-    o[4 + 128 + j] = accz * ldexpf(1.f, eng - 26);
+    o[4 + j] = VSPLIT ? acc : acc * ldexpf(1.f, enu - 26);
+    o[4 + 128 + j] = VPROD ? accz * ldexpf(1.f, eng - 26) : 0.f;
     if (j == 0) {
       float l = 0.f, mq = -INFINITY;
 #pragma unroll
@@ -346,47 +375,48 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
   }
 }
 
-template <int KB, bool KPROD, int VB, bool VPROD, bool FUSED>
-hipError_t launch_attend128_one(const ScoreI8Args& ka, const AttendArgs& a, const AttendCoefs& cf, int n_groups,
-                                hipStream_t s) {
-  constexpr int lds = attend128_lds(KB, VB, VPROD, FUSED);
+template <int KB, bool KPROD, int VB, int VKIND, bool FUSED>
+hipError_t launch_attend128_one(const ScoreI8Args& ka, const AttendArgs& a, const AttendCoefs& cf, const AttendCoefs& cfh,
+                                int n_groups, hipStream_t s) {
+  constexpr int lds = attend128_lds(KB, VB, VKIND != 0, FUSED);
   static_assert(I8_TABLE_BYTES + lds <= 160 * 1024, "LDS budget");
   static bool attr_done = false;  // per instantiation: the limit has to be raised once
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend128_kernel<KB, KPROD, VB, VPROD, FUSED>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend128_kernel<KB, KPROD, VB, VKIND, FUSED>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   const dim3 grid(a.nchunks, n_groups, (a.q_per_group + 3) / 4);
-  hipLaunchKernelGGL((attend128_kernel<KB, KPROD, VB, VPROD, FUSED>), grid, dim3(512), lds, s, ka, a, cf);
+  hipLaunchKernelGGL((attend128_kernel<KB, KPROD, VB, VKIND, FUSED>), grid, dim3(512), lds, s, ka, a, cf, cfh);
   return hipGetLastError();
 }
 
 // all key variants for one kind of value code; kb < 0: logits from a.scores
-template <int VB, bool VPROD>
+template <int VB, int VKIND>
 hipError_t launch_attend128_vb(int kb, bool kprod, const ScoreI8Args& ka, const AttendArgs& a, const AttendCoefs& cf,
-                               int n_groups, hipStream_t s) {
-  if (kb < 0) return launch_attend128_one<0, false, VB, VPROD, false>(ka, a, cf, n_groups, s);
+                               const AttendCoefs& cfh, int n_groups, hipStream_t s) {
+  if (kb < 0) return launch_attend128_one<0, false, VB, VKIND, false>(ka, a, cf, cfh, n_groups, s);
   switch (kb * 2 + (kprod ? 1 : 0)) {
-    case 1: return launch_attend128_one<0, true, VB, VPROD, true>(ka, a, cf, n_groups, s);
-    case 2: return launch_attend128_one<1, false, VB, VPROD, true>(ka, a, cf, n_groups, s);
-    case 3: return launch_attend128_one<1, true, VB, VPROD, true>(ka, a, cf, n_groups, s);
-    case 4: return launch_attend128_one<2, false, VB, VPROD, true>(ka, a, cf, n_groups, s);
-    case 5: return launch_attend128_one<2, true, VB, VPROD, true>(ka, a, cf, n_groups, s);
-    case 6: return launch_attend128_one<3, false, VB, VPROD, true>(ka, a, cf, n_groups, s);
-    case 7: return launch_attend128_one<3, true, VB, VPROD, true>(ka, a, cf, n_groups, s);
-    case 8: return launch_attend128_one<4, false, VB, VPROD, true>(ka, a, cf, n_groups, s);
-    case 9: return launch_attend128_one<4, true, VB, VPROD, true>(ka, a, cf, n_groups, s);
+    case 1: return launch_attend128_one<0, true, VB, VKIND, true>(ka, a, cf, cfh, n_groups, s);
+    case 2: return launch_attend128_one<1, false, VB, VKIND, true>(ka, a, cf, cfh, n_groups, s);
+    case 3: return launch_attend128_one<1, true, VB, VKIND, true>(ka, a, cf, cfh, n_groups, s);
+    case 4: return launch_attend128_one<2, false, VB, VKIND, true>(ka, a, cf, cfh, n_groups, s);
+    case 5: return launch_attend128_one<2, true, VB, VKIND, true>(ka, a, cf, cfh, n_groups, s);
+    case 6: return launch_attend128_one<3, false, VB, VKIND, true>(ka, a, cf, cfh, n_groups, s);
+    case 7: return launch_attend128_one<3, true, VB, VKIND, true>(ka, a, cf, cfh, n_groups, s);
+    case 8: return launch_attend128_one<4, false, VB, VKIND, true>(ka, a, cf, cfh, n_groups, s);
+    case 9: return launch_attend128_one<4, true, VB, VKIND, true>(ka, a, cf, cfh, n_groups, s);
     default: return hipErrorInvalidValue;
   }
 }
 
 // one translation unit per kind of value code (tq_attend_128_v*.hip: MSE codes of 1..4 bits; tq_attend_128_p*.hip:
-// codes of Alg. 2 with 0..2 index bits, which is what fits LDS beside the second set of weights)
-#define TQ_ATTEND128_DECL(NAME)                                                                                  \
-  hipError_t NAME(int kb, bool kprod, const ScoreI8Args& ka, const AttendArgs& a, const AttendCoefs& cf, int n_groups, \
-                  hipStream_t s)
+// codes of Alg. 2 with 0..2 index bits; tq_attend_128_s*.hip: two instances with 1 + 2 or 2 + 3 index bits: what fits
+// LDS beside the second set of weights)
+#define TQ_ATTEND128_DECL(NAME)                                                                  \
+  hipError_t NAME(int kb, bool kprod, const ScoreI8Args& ka, const AttendArgs& a, const AttendCoefs& cf, \
+                  const AttendCoefs& cfh, int n_groups, hipStream_t s)
 TQ_ATTEND128_DECL(launch_attend128_v1);
 TQ_ATTEND128_DECL(launch_attend128_v2);
 TQ_ATTEND128_DECL(launch_attend128_v3);
@@ -394,5 +424,7 @@ TQ_ATTEND128_DECL(launch_attend128_v4);
 TQ_ATTEND128_DECL(launch_attend128_p0);
 TQ_ATTEND128_DECL(launch_attend128_p1);
 TQ_ATTEND128_DECL(launch_attend128_p2);
+TQ_ATTEND128_DECL(launch_attend128_s1);
+TQ_ATTEND128_DECL(launch_attend128_s2);
 
 }  // namespace tq

@@ -4,6 +4,6 @@
 
 namespace tq {
 
-TQ_ATTEND128_DECL(launch_attend128_p0) { return launch_attend128_vb<0, true>(kb, kprod, ka, a, cf, n_groups, s); }
+TQ_ATTEND128_DECL(launch_attend128_p0) { return launch_attend128_vb<0, 1>(kb, kprod, ka, a, cf, cfh, n_groups, s); }
 
 }  // namespace tq

@@ -257,3 +257,65 @@ def test_c3m_full_size():
         xt = o.dequant_split(D, hi_ch, rh, rl, ihi, ilo, True)
         qsl = slice(g * cfg.q_per_group, (g + 1) * cfg.q_per_group)
         P.check_close(s_gpu[qsl], o.score(q[qsl], xt), qs_n[qsl] @ nu_np[rows].T, f"C3m logits, head {g}")
+
+
+@pytest.mark.parametrize("d_hi,vbits_lo,kd_hi,n_groups,qpg,npg", [
+    (64, 2, 0, 2, 4, 2500),    # the 2.5-bit value cache, ordinary keys (scored inside the read-out kernel)
+    (32, 2, 64, 1, 4, 4100),   # keys in two instances as well (scored by tq_score first)
+    (96, 1, 0, 1, 5, 700),     # 1 + 2 bits
+    (64, 2, 0, 3, 1, 1),       # one token
+])
+def test_attend_with_values_in_two_instances(d_hi, vbits_lo, kd_hi, n_groups, qpg, npg):
+    """tq_attend with a value cache quantised as two instances (outlier channels one bit wider): softmax of the
+    key scores times the oracle's dequantised split values.  Tolerance as in tests/test_gpu_attend.py."""
+    v_ch, vhi, vlo, pv = instances(d_hi, vbits_lo, False, seed=500)
+    n, nq = n_groups * npg, n_groups * qpg
+    vres, v_idx, _, _, v_norm = random_codes(pv, vhi, vlo, d_hi, n, False, seed=31)
+    vt = o.dequant_split(D, v_ch, vres[0], vres[1], vhi, vlo, False)
+    if kd_hi:
+        k_ch, khi, klo, pk = instances(kd_hi, 1, True, seed=600)
+        kres, k_idx, k_qjl, k_gamma, k_norm = random_codes(pk, khi, klo, kd_hi, n, True, seed=32)
+        k_norm = (k_norm * 0.3).astype(np.float32)
+        for r, col in ((kres[0], 0), (kres[1], 1)):
+            r["norm"] = k_norm[:, col]
+        kt = o.dequant_split(D, k_ch, kres[0], kres[1], khi, klo, True)
+        k_dev = (dev(k_idx.view(np.int32)), dev(k_qjl.view(np.int32)), dev(k_gamma), dev(k_norm))
+        k_norm_max = float(np.sqrt((k_norm.astype(np.float64) ** 2).sum(axis=1)).max())
+    else:
+        Pi = o.rotation_from_gaussian(W.gaussian_matrix(D, 700))
+        S = W.sketch_matrix(D, 701)
+        c32, t32, _ = o.codebook_fp32(D, 2)
+        pk = tq.Params(D, 2, torch.from_numpy(Pi), torch.from_numpy(S), c32, t32)
+        rng = np.random.default_rng(33)
+        idx = rng.integers(0, 4, size=(n, D)).astype(np.int32)
+        z = rng.integers(0, 2, size=(n, D)).astype(bool)
+        gamma = rng.uniform(0.05, 0.6, size=n).astype(np.float32)
+        knorm = np.exp(rng.normal(0, 0.3, size=n)).astype(np.float32)
+        kt = o.dequant_prod(idx, z, gamma, Pi, S, c32, knorm)
+        k_dev = (dev(o.pack_planes(idx, 2).view(np.int32)), dev(o.pack_signs(z).view(np.int32)), dev(gamma), dev(knorm))
+        k_norm_max = float(knorm.max())
+    q = W.gaussian_queries(nq, D, 3, unit=False)
+    scale = 1.0 / math.sqrt(D)
+    out = torch.full((nq, D), float("nan"), dtype=torch.float32, device=DEV)
+    tq.tq_attend(pk, pv, dev(q), n_groups, qpg, k_dev, (dev(v_idx.view(np.int32)), None, None, dev(v_norm)), npg, scale, out)
+    got = out.cpu().numpy().astype(np.float64)
+    qn = np.linalg.norm(q.astype(np.float64), axis=1)
+    for g in range(n_groups):
+        rows, toks = slice(g * qpg, (g + 1) * qpg), slice(g * npg, (g + 1) * npg)
+        want = o.attend(q[rows], kt[toks], vt[toks], scale)
+        size = o.attend(q[rows], kt[toks], np.abs(vt[toks]), scale)
+        e = 1e-4 * scale * qn[rows] * k_norm_max
+        lim = (P.REL_TOL + np.expm1(2 * e))[:, None] * (size + np.abs(want))
+        worst = float((np.abs(got[rows] - want) / np.maximum(lim, 1e-300)).max())
+        assert worst <= 1.0, f"attend with split values, group {g}: error {worst:.3f}x the tolerance"
+
+
+def test_attend_rejects_value_codes_it_does_not_cover():
+    """3 + 4 index bits do not fit the kernel's LDS: a clear status, no launch."""
+    _, _, _, pv = instances(64, 3, False, seed=510)
+    _, _, _, pk = instances(64, 1, True, seed=600)
+    with pytest.raises(tq.TurboQuantError, match="UNSUPPORTED|unsupported|outside"):
+        z32 = torch.zeros((8, 64), dtype=torch.int32, device=DEV)
+        f2 = torch.ones((8, 2), dtype=torch.float32, device=DEV)
+        tq.tq_attend(pk, pv, torch.zeros((4, D), device=DEV), 1, 4, (z32, z32, f2, f2), (z32, None, None, f2), 8, 1.0,
+                     torch.zeros((4, D), device=DEV))
