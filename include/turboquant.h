@@ -42,7 +42,17 @@
  *    gamma[2i], gamma[2i+1] = residual norms of the two instances
  * and the sketch scale of Def. 1 is sqrt(pi/2)/d_hi resp. sqrt(pi/2)/(d-d_hi).
  * Covered for d = 128 with d_hi in {32, 64, 96}: tq_quantize_*, tq_dequantize,
- * and tq_score with at most 32 queries per group.
+ * tq_score with at most 32 queries per group, and tq_attend (keys: any width;
+ * values: MSE codes with 1 + 2 or 2 + 3 index bits).
+ *
+ * Arithmetic.  The rotation y = Pi x and the sketch S r of the quantisers are
+ * fp32 contractions (fp32 matrix instructions), and the bucket decision is an
+ * fp32 comparison.  Dequantisation and scoring multiply an fp32 factor (an
+ * entry of Pi or S, a rotated query coordinate) with a quantity that takes few
+ * values (a centroid, a sign); they run on the bf16 or int8 matrix cores with
+ * the fp32 factor split exactly into pieces (three bf16 pieces, or base-128
+ * digits of a fixed-point value with 2^-19 relative spacing) and fp32 / int32
+ * accumulation, and meet the same tolerances as an fp32 evaluation.
  */
 #ifndef TURBOQUANT_H
 #define TURBOQUANT_H
