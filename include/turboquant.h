@@ -216,6 +216,38 @@ tq_status tq_attend(const tq_params* pk, const tq_params* pv, const float* q, in
                     void* stream);
 
 /*
+ * The same read-out over a cache that is still growing: every group owns
+ * group_stride token slots (its capacity) of which the first n_per_group are
+ * filled, so code row g*group_stride + i holds token i of group g.  With
+ * group_stride == n_per_group this is tq_attend.  Otherwise TQ_ERR_UNSUPPORTED
+ * unless pk->d == pv->d == 128, the key codes are of one instance with at most
+ * 32 queries per group, pk->PiT (and pk->ST for prod keys) are set, the
+ * codebooks are symmetric about zero (what tq_build_codebook produces), and the
+ * value codes are among: MSE with 1..4 bits, prod with 0..2, or the two-instance
+ * MSE codes above.  Workspace: tq_attend_workspace_bytes() as for tq_attend.
+ */
+tq_status tq_attend_cache(const tq_params* pk, const tq_params* pv, const float* q, int64_t ldq,
+                          int32_t n_groups, int32_t q_per_group, const uint32_t* k_idx,
+                          const uint32_t* k_qjl, const float* k_gamma, const float* k_norm,
+                          const uint32_t* v_idx, const uint32_t* v_qjl, const float* v_gamma,
+                          const float* v_norm, int64_t n_per_group, int64_t group_stride,
+                          float scale, float* out, int64_t ldo, void* stream);
+
+/*
+ * Quantise n new vectors straight into such a cache (Sec. 4.3: tokens are
+ * quantised as they are generated): tq_quantize_mse (qjl == NULL) or
+ * tq_quantize_prod of row i of x, written to code row first_row + i*row_step of
+ * idx / qjl / gamma / norm.  One new token for each of H heads of a cache laid
+ * out [head][capacity] is n = H, first_row = tokens so far, row_step = capacity.
+ * first_row >= 0, row_step >= 1; the caller guarantees the target rows exist.
+ * d = 128 (one or two instances) and n <= 24576, else TQ_ERR_UNSUPPORTED; x
+ * 16-byte aligned with row stride a multiple of 16 bytes.  No workspace.
+ */
+tq_status tq_append(const tq_params* p, const void* x, tq_dtype dtype, int64_t n, int64_t ldx,
+                    uint32_t* idx, uint32_t* qjl, float* gamma, float* norm, int64_t first_row,
+                    int64_t row_step, void* stream);
+
+/*
  * Codec stages on their own (HBM-bound; they are also what the bit-exactness
  * tests drive): the decision idx_j = argmin_k |y_j - c_k| of Alg. 1 plus
  * packing for given rotated coordinates y[n][d]; the sign packing of Alg. 2

@@ -45,6 +45,9 @@ SIGNATURES = {
     "tq_attend_workspace_bytes": (C.c_size_t, [_P, _P, _i32, _i32, _i64]),
     "tq_attend": (C.c_int, [_P, _P, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, C.c_float, _vp,
                             _i64, _vp]),
+    "tq_attend_cache": (C.c_int, [_P, _P, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64,
+                                  C.c_float, _vp, _i64, _vp]),
+    "tq_append": (C.c_int, [_P, _vp, C.c_int, _i64, _i64, _vp, _vp, _vp, _vp, _i64, _i64, _vp]),
     "tq_stage_pack": (C.c_int, [_P, _vp, _i64, _vp, _vp]),
     "tq_stage_sign_pack": (C.c_int, [_i32, _vp, _i64, _vp, _vp]),
     "tq_stage_unpack": (C.c_int, [_P, _vp, _i64, _vp, _vp]),

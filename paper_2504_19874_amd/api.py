@@ -179,15 +179,30 @@ def tq_attend_workspace_bytes(pk: Params, pv: Params, n_groups: int, q_per_group
                                                      n_per_group))
 
 
+def tq_append(p: Params, x: torch.Tensor, idx, qjl, gamma, norm, first_row: int, row_step: int):
+    """Quantise the rows of x into code rows first_row + i * row_step of a cache (qjl None: the MSE quantiser)."""
+    n = x.shape[0]
+    _check(_lib.load().tq_append(C.byref(p.c), _ptr_rows(x), _dtype_of(x), n, x.stride(0) if n else p.d, _ptr(idx),
+                                 _ptr(qjl), _ptr(gamma), _ptr(norm), first_row, row_step, _stream()), "tq_append")
+
+
 def tq_attend(pk: Params, pv: Params, q: torch.Tensor, n_groups: int, q_per_group: int, k_codes, v_codes,
-              n_per_group: int, scale: float, out: torch.Tensor):
+              n_per_group: int, scale: float, out: torch.Tensor, group_stride: int | None = None):
     """k_codes, v_codes: (idx, qjl, gamma, norm) tensors, None where the quantiser has no such output.
+    group_stride: token slots per group when the cache holds more than n_per_group (tq_attend_cache).
     Sizes pk's workspace for the call when it is too small."""
     need = tq_attend_workspace_bytes(pk, pv, n_groups, q_per_group, n_per_group)
     if pk.workspace is None or pk.workspace.numel() < need:
         pk.workspace = torch.empty(need, dtype=torch.uint8, device=pk.device)
         pk.c.workspace = pk.workspace.data_ptr()
         pk.c.workspace_bytes = pk.workspace.numel()
+    if group_stride is not None:
+        _check(_lib.load().tq_attend_cache(C.byref(pk.c), C.byref(pv.c), _ptr_rows(q), q.stride(0) if q.shape[0] else pk.d,
+                                           n_groups, q_per_group, *[_ptr(t) for t in k_codes],
+                                           *[_ptr(t) for t in v_codes], n_per_group, group_stride, C.c_float(scale),
+                                           _ptr_rows(out), out.stride(0) if out.shape[0] else pv.d, _stream()),
+               "tq_attend_cache")
+        return
     _check(_lib.load().tq_attend(C.byref(pk.c), C.byref(pv.c), _ptr_rows(q), q.stride(0) if q.shape[0] else pk.d,
                                  n_groups, q_per_group, *[_ptr(t) for t in k_codes], *[_ptr(t) for t in v_codes],
                                  n_per_group, C.c_float(scale), _ptr_rows(out), out.stride(0) if out.shape[0] else pv.d,

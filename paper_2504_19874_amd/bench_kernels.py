@@ -211,6 +211,25 @@ def main():
                2.0 * pairs * d * ((2 if prod else 1) + (2 if vprod else 1)), n * (code_b + vcode_b) + 8 * nq * d,
                {"pairs": pairs}, bound="hbm")  # the contractions run on the int8 cores; the codes are read once
 
+        if d == 128 and not cfg.d_hi and p.PiT is not None:
+            # one decoding step on a cache laid out [head][capacity = n]: the last slot of every head is
+            # rewritten with a new key and a new value, then the queries read the whole cache
+            newk = torch.randn((cfg.n_groups, d), dtype=torch.float32, device="cuda")
+            newv = torch.randn((cfg.n_groups, d), dtype=torch.float32, device="cuda")
+
+            def decode_step(r):
+                c, vc = codes[r % sets], vsets[r % sets]
+                kn = knorm[r % sets]
+                tq.tq_append(p, newk, c["idx"], c["qjl"], c["gamma"], kn, cfg.n - 1, cfg.n)
+                tq.tq_append(pv, newv, vc["idx"], vc["qjl"], vc["gamma"], vc["norm"], cfg.n - 1, cfg.n)
+                tq.tq_attend(p, pv, q, cfg.n_groups, cfg.q_per_group, (c["idx"], c["qjl"], c["gamma"], kn),
+                             (vc["idx"], vc["qjl"], vc["gamma"], vc["norm"]), cfg.n, 1.0 / d ** 0.5, outs[r % len(outs)],
+                             group_stride=cfg.n)
+
+            report(f"decode_step(v{vname})", cfg, timed(decode_step, reps),
+                   2.0 * pairs * d * ((2 if prod else 1) + (2 if vprod else 1)), n * (code_b + vcode_b) + 8 * nq * d,
+                   {"pairs": pairs}, bound="hbm")
+
     if on("stage") and cfg.bits_mse > 0 and not cfg.d_hi:
         # codec stages on rotated coordinates of the same shape
         rows = n if not big else min(n, 1 << 20)

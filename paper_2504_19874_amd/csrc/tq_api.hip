@@ -74,7 +74,7 @@ struct Workspace {
 
 tq_status quantize_common(const tq_params* p, const void* x, tq_dtype dtype, int64_t n, int64_t ldx,
                           uint32_t* idx, uint32_t* qjl, float* gamma, float* norm, bool prod,
-                          hipStream_t stream) {
+                          hipStream_t stream, int64_t out_first = 0, int64_t out_step = 1, bool scattered = false) {
   tq_status st = check_params(p, true);
   if (st != TQ_OK) return st;
   if (n < 0 || ldx < p->d) return TQ_ERR_INVALID_ARG;
@@ -90,6 +90,16 @@ tq_status quantize_common(const tq_params* p, const void* x, tq_dtype dtype, int
   const int d = p->d;
   const size_t esz = dtype == TQ_F32 ? 4 : 2;
   const int words_per_row = (d / 32) * p->bits_mse;
+
+  if (scattered) {
+    // rows scattered into a larger store (tq_append): the short-chain d = 128 kernel only
+    if (d != 128 || n > kSmallQuantRows || !aligned16(x) || (ldx * esz) % 16 != 0) return TQ_ERR_UNSUPPORTED;
+    if (p->d_hi != 0 && norm == nullptr) return TQ_ERR_INVALID_ARG;
+    return from_hip(launch_quant128_small(p->bits_mse, prod, dtype == TQ_BF16, x, ldx, n, p->Pi,
+                                          prod ? p->SPiT : nullptr, idx, qjl, gamma, norm, make_codebook(p),
+                                          p->d_hi / 32, p->d_hi != 0 ? make_codebook_hi(p) : make_codebook(p), stream,
+                                          out_first, out_step));
+  }
 
   if (p->d_hi != 0) {
     // two instances: the d = 128 kernels; both norms are always stored
@@ -235,6 +245,15 @@ tq_status tq_quantize_prod(const tq_params* p, const void* x, tq_dtype dtype, in
                            uint32_t* idx, uint32_t* qjl, float* gamma, float* norm, void* stream) {
   return quantize_common(p, x, dtype, n, ldx, idx, qjl, gamma, norm, true,
                          static_cast<hipStream_t>(stream));
+}
+
+tq_status tq_append(const tq_params* p, const void* x, tq_dtype dtype, int64_t n, int64_t ldx, uint32_t* idx,
+                    uint32_t* qjl, float* gamma, float* norm, int64_t first_row, int64_t row_step, void* stream) {
+  if (first_row < 0 || row_step < 1) return TQ_ERR_INVALID_ARG;
+  if (p != nullptr && p->d != 128) return TQ_ERR_UNSUPPORTED;
+  if (n > kSmallQuantRows) return TQ_ERR_UNSUPPORTED;
+  return quantize_common(p, x, dtype, n, ldx, idx, qjl, gamma, norm, qjl != nullptr, static_cast<hipStream_t>(stream),
+                         first_row, row_step, true);
 }
 
 tq_status tq_dequantize(const tq_params* p, const uint32_t* idx, const uint32_t* qjl,
@@ -467,11 +486,20 @@ tq_status tq_attend(const tq_params* pk, const tq_params* pv, const float* q, in
                     int32_t q_per_group, const uint32_t* k_idx, const uint32_t* k_qjl, const float* k_gamma,
                     const float* k_norm, const uint32_t* v_idx, const uint32_t* v_qjl, const float* v_gamma,
                     const float* v_norm, int64_t n_per_group, float scale, float* out, int64_t ldo, void* stream) {
+  return tq_attend_cache(pk, pv, q, ldq, n_groups, q_per_group, k_idx, k_qjl, k_gamma, k_norm, v_idx, v_qjl, v_gamma, v_norm,
+                         n_per_group, n_per_group, scale, out, ldo, stream);
+}
+
+tq_status tq_attend_cache(const tq_params* pk, const tq_params* pv, const float* q, int64_t ldq, int32_t n_groups,
+                          int32_t q_per_group, const uint32_t* k_idx, const uint32_t* k_qjl, const float* k_gamma,
+                          const float* k_norm, const uint32_t* v_idx, const uint32_t* v_qjl, const float* v_gamma,
+                          const float* v_norm, int64_t n_per_group, int64_t group_stride, float scale, float* out,
+                          int64_t ldo, void* stream) {
   tq_status st = check_params(pk, true);
   if (st != TQ_OK) return st;
   st = check_params(pv, true);
   if (st != TQ_OK) return st;
-  if (n_groups < 0 || q_per_group < 0 || n_per_group < 0 || ldo < pv->d) return TQ_ERR_INVALID_ARG;
+  if (n_groups < 0 || q_per_group < 0 || n_per_group < 0 || ldo < pv->d || group_stride < n_per_group) return TQ_ERR_INVALID_ARG;
   const int64_t nq = (int64_t)n_groups * q_per_group;
   if (nq == 0) return TQ_OK;
   const bool v_prod = v_qjl != nullptr;
@@ -494,17 +522,19 @@ tq_status tq_attend(const tq_params* pk, const tq_params* pv, const float* q, in
     AttendArgs a;
     a.scores = scores; a.lds = pl.ld_scores;
     a.idx = v_idx; a.qjl = v_qjl; a.gamma = v_gamma; a.norm = v_norm;
-    a.part = part; a.nchunks = pl.nchunks; a.n = n_per_group; a.d = pv->d; a.q_per_group = q_per_group;
+    a.part = part; a.nchunks = pl.nchunks; a.n = n_per_group; a.group_stride = group_stride; a.d = pv->d; a.q_per_group = q_per_group;
     a.scale = scale; a.cb = make_codebook(pv); a.gs_hi = pv->d_hi / 32; a.cb_hi = make_codebook_hi(pv);
     // keys the single-kernel d = 128 scoring path takes are scored inside the read-out kernel
     const bool k_prod = k_qjl != nullptr;
     ScoreI8Args ka;
     const bool fused = pl.fast && pk->d == 128 && pk->d_hi == 0 && q != nullptr && ldq >= 128 &&
                        score128_args(pk->bits_mse, k_prod, pk->PiT, pk->ST, q, ldq, k_idx, k_qjl, k_gamma, k_norm,
-                                     n_per_group, n_groups, q_per_group, kappa_of(128), make_codebook(pk), &ka);
+                                     n_per_group, n_groups, q_per_group, kappa_of(128), make_codebook(pk), group_stride, &ka);
     if (fused) {
       if (launch_attend128(pk->bits_mse, k_prod, &ka, v_prod, a, n_groups, s) != hipSuccess) return TQ_ERR_HIP;
     } else {
+      // tq_score knows densely stored groups only
+      if (group_stride != n_per_group) return TQ_ERR_UNSUPPORTED;
       tq_params pk_inner = *pk;  // the scoring call carves its own needs from what is left
       pk_inner.workspace = rest;
       pk_inner.workspace_bytes = pl.score_ws_bytes;

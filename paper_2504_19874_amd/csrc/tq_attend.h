@@ -19,6 +19,7 @@ struct AttendArgs {
   float* part;          // [n_groups * q_per_group][nchunks][attend_part_stride(d)]
   int nchunks;
   int64_t n;            // keys per group
+  int64_t group_stride; // value code rows between the first tokens of consecutive groups (>= n)
   int d;
   int q_per_group;
   float scale;

@@ -44,7 +44,7 @@ __global__ __launch_bounds__(256) void attend_values_kernel(const AttendArgs a) 
   const int chunk = blockIdx.x, group = blockIdx.y, q0 = blockIdx.z * 4;
   const int64_t key0 = (int64_t)chunk * SIMPLE_CHUNK;
   const int nk = (int)(a.n - key0 < SIMPLE_CHUNK ? a.n - key0 : SIMPLE_CHUNK);
-  const int64_t row0 = (int64_t)group * a.n + key0;
+  const int64_t row0 = (int64_t)group * a.group_stride + key0;
   if (tid < 16) cent_s[tid] = a.cb.c[tid];
 
   float m[4], l[4];

@@ -115,7 +115,7 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
   float* const fsumz_s = reinterpret_cast<float*>(dyn_s);          // the same for the sign sums, over the digits
   float* const red_s = reinterpret_cast<float*>(dyn_s + attend128_work_bytes(KB, VB, TWO, FUSED));  // [3][8][4]
 
-  const int64_t gbase = (int64_t)group * a.n;
+  const int64_t gbase = (int64_t)group * a.group_stride;
   const int64_t wave_key0 = ((int64_t)chunk * 8 + wave) * AT_WAVE_KEYS;
   // transposing role: block kb of 16 keys, coordinate group tg, planes ph and ph + 2
   const int kb = lane & 7, tg = (lane >> 3) & 3, ph = lane >> 5;

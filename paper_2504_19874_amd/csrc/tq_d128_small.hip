@@ -34,6 +34,7 @@ struct QuantSmallArgs {
   uint32_t* qjl;
   float* gamma;
   float* norm;
+  int64_t out_first, out_step;  // vector i is written as code row out_first + i * out_step
   int normalise;
   int gs_hi;  // two instances (MIXED): coordinate groups [0, gs_hi) belong to instance hi
   Codebook cb;
@@ -90,6 +91,7 @@ __global__ __launch_bounds__(512) void quant128_small_kernel(const QuantSmallArg
   for (int64_t blk = blockIdx.x; blk < n_blocks; blk += gridDim.x) {
     const int64_t i = blk * 32 + l32;
     const bool valid = i < a.n;
+    const int64_t oi = a.out_first + i * a.out_step;  // code row
     float xb[32];
     if (BF16IN) {
 #pragma unroll
@@ -183,16 +185,16 @@ __global__ __launch_bounds__(512) void quant128_small_kernel(const QuantSmallArg
       if (hi) g2 = quantise_tile<(BITS < 4 ? BITS + 1 : 4)>(acc, inv, a.cb_hi, h, word);
       else g2 = quantise_tile<BITS>(acc, inv, a.cb, h, word);
       if (valid && h == 0) {
-        uint32_t* dst = a.idx + i * wpr + woff;
+        uint32_t* dst = a.idx + oi * wpr + woff;
 #pragma unroll
         for (int pl = 0; pl < BITS + (MIXED ? 1 : 0); ++pl)
           if (pl < BITS || hi) dst[pl] = word[pl];
         if (mt == 0 && a.norm != nullptr) {
           if (MIXED) {
-            a.norm[2 * i] = nu;  // tile 0 always belongs to instance hi
-            a.norm[2 * i + 1] = nu_other;
+            a.norm[2 * oi] = nu;  // tile 0 always belongs to instance hi
+            a.norm[2 * oi + 1] = nu_other;
           } else {
-            a.norm[i] = nu;
+            a.norm[oi] = nu;
           }
         }
       }
@@ -241,7 +243,7 @@ __global__ __launch_bounds__(512) void quant128_small_kernel(const QuantSmallArg
       uint32_t w = (nb[0] | (nb[1] << 8) | (nb[2] << 16) | (nb[3] << 24)) << (4 * h);
       w |= (uint32_t)__shfl_xor((int)w, 32);
       if (valid && h == 0) {
-        a.qjl[i * 4 + mt] = w;
+        a.qjl[oi * 4 + mt] = w;
         if (mt == 0) {
           if (MIXED) {
             float g_hi = 0.f, g_lo = 0.f;
@@ -251,10 +253,10 @@ __global__ __launch_bounds__(512) void quant128_small_kernel(const QuantSmallArg
               g_hi += t < gs ? v : 0.f;
               g_lo += t < gs ? 0.f : v;
             }
-            a.gamma[2 * i] = sqrtf(g_hi);
-            a.gamma[2 * i + 1] = sqrtf(g_lo);
+            a.gamma[2 * oi] = sqrtf(g_hi);
+            a.gamma[2 * oi + 1] = sqrtf(g_lo);
           } else {
-            a.gamma[i] = sqrtf((g2_s[0][l32] + g2_s[1][l32]) + (g2_s[2][l32] + g2_s[3][l32]));
+            a.gamma[oi] = sqrtf((g2_s[0][l32] + g2_s[1][l32]) + (g2_s[2][l32] + g2_s[3][l32]));
           }
         }
       }
@@ -290,12 +292,13 @@ static hipError_t launch_bits(const QuantSmallArgs& a, bool prod, bool bf16, hip
 hipError_t launch_quant128_small(int bits, bool prod, bool bf16, const void* X, int64_t ldx, int64_t n,
                                  const float* Pi, const float* SPiT, uint32_t* idx, uint32_t* qjl,
                                  float* gamma, float* norm, const Codebook& cb, int gs_hi,
-                                 const Codebook& cb_hi, hipStream_t s) {
+                                 const Codebook& cb_hi, hipStream_t s, int64_t out_first, int64_t out_step) {
   if (n == 0) return hipSuccess;
   if (gs_hi < 0 || gs_hi > 3 || (gs_hi > 0 && (cb_hi.bits != bits + 1 || norm == nullptr))) return hipErrorInvalidValue;
   QuantSmallArgs a;
   a.X = X; a.ldx = ldx; a.n = n; a.Pi = Pi; a.SPiT = SPiT; a.idx = idx; a.qjl = qjl; a.gamma = gamma;
   a.norm = norm; a.normalise = norm != nullptr; a.gs_hi = gs_hi; a.cb = cb; a.cb_hi = cb_hi;
+  a.out_first = out_first; a.out_step = out_step;
   switch (bits) {
     case 0: return launch_bits<0>(a, prod, bf16, s);
     case 1: return launch_bits<1>(a, prod, bf16, s);

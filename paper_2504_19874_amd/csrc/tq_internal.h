@@ -72,7 +72,7 @@ constexpr int64_t kSmallQuantRows = 24576;
 hipError_t launch_quant128_small(int bits, bool prod, bool bf16, const void* X, int64_t ldx, int64_t n,
                                  const float* Pi, const float* SPiT, uint32_t* idx, uint32_t* qjl,
                                  float* gamma, float* norm, const Codebook& cb, int gs_hi,
-                                 const Codebook& cb_hi, hipStream_t s);
+                                 const Codebook& cb_hi, hipStream_t s, int64_t out_first = 0, int64_t out_step = 1);
 hipError_t launch_dequant128_small(int bits, bool prod, const uint32_t* idx, const uint32_t* qjl,
                                    const float* gamma, const float* norm, const float* Pi, const float* S,
                                    float* out, int64_t ldo, int64_t n, float kappa, const Codebook& cb,

@@ -31,6 +31,7 @@ struct ScoreI8Args {
   int64_t lds;
   int64_t n;
   int64_t total_rows;  // rows in the code arrays (all groups)
+  int64_t group_stride;  // single-kernel d = 128 path: code rows between the first keys of consecutive groups (>= n)
   int d;
   int q_per_group;
   float kappa;
@@ -49,7 +50,7 @@ constexpr int I8_TABLE_BYTES = 256 * I8_COPIES * 8;
 hipError_t launch_score_i8_128(int bits, bool prod, const ScoreI8Args& a, int n_groups, hipStream_t stream);
 bool score128_args(int bits, bool prod, const float* PiT, const float* ST, const float* q, int64_t ldq,
                    const uint32_t* idx, const uint32_t* qjl, const float* gamma, const float* norm, int64_t n,
-                   int n_groups, int q_per_group, float kappa, const Codebook& cb, ScoreI8Args* a);
+                   int n_groups, int q_per_group, float kappa, const Codebook& cb, int64_t group_stride, ScoreI8Args* a);
 bool i8_coefficients(int bits, const Codebook& cb, float* coef);  // factors of the masked sums (tq_score_i8.hip)
 void i8_walsh(int bits, const Codebook& cb, double* w);  // Walsh coefficients of a centroid table (tq_score_i8.hip)
 hipError_t launch_prep_i8_128(int d_hi, const float* Pi, const float* S, const float* q, int64_t ldq, int64_t nq,

@@ -475,14 +475,14 @@ bool score_i8_applicable(int bits, int d, const Codebook& cb) {
 // kernel of their own; false when that path does not take these codes.
 bool score128_args(int bits, bool prod, const float* PiT, const float* ST, const float* q, int64_t ldq,
                    const uint32_t* idx, const uint32_t* qjl, const float* gamma, const float* norm, int64_t n,
-                   int n_groups, int q_per_group, float kappa, const Codebook& cb, ScoreI8Args* a) {
+                   int n_groups, int q_per_group, float kappa, const Codebook& cb, int64_t group_stride, ScoreI8Args* a) {
   const auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
   if (bits < 0 || bits > 4 || !(bits > 0 || prod)) return false;
   if (bits > 0 && (PiT == nullptr || idx == nullptr || !al16(idx))) return false;
   if (prod && (ST == nullptr || qjl == nullptr || gamma == nullptr || !al16(qjl))) return false;
   std::memset(a, 0, sizeof(*a));
   a->PiT = PiT; a->ST = ST; a->x = q; a->ldx = ldq; a->idx = idx; a->qjl = qjl; a->gamma = gamma; a->norm = norm;
-  a->n = n; a->total_rows = (int64_t)n_groups * n; a->d = 128; a->q_per_group = q_per_group; a->kappa = kappa;
+  a->n = n; a->group_stride = group_stride; a->total_rows = (int64_t)(n_groups - 1) * group_stride + n; a->d = 128; a->q_per_group = q_per_group; a->kappa = kappa;
   return i8_coefficients(bits, cb, a->coef);
 }
 
@@ -499,7 +499,7 @@ hipError_t launch_score_i8(int bits, bool prod, const float* Pi, const float* S,
   if (n == 0) return hipSuccess;
   ScoreI8Args a;
   a.img = img; a.scal = scal; a.PiT = PiT; a.ST = ST; a.x = q; a.ldx = ldq; a.idx = idx; a.qjl = qjl; a.gamma = gamma; a.norm = norm;
-  a.scores = scores; a.lds = lds; a.n = n; a.total_rows = (int64_t)n_groups * n; a.d = d; a.q_per_group = q_per_group; a.kappa = kappa;
+  a.scores = scores; a.lds = lds; a.n = n; a.total_rows = (int64_t)n_groups * n; a.group_stride = n; a.d = d; a.q_per_group = q_per_group; a.kappa = kappa;
   if (!i8_coefficients(bits, cb, a.coef)) return hipErrorInvalidValue;  // see score_i8_applicable
   // d = 128 with the transposed matrices at hand and 16-byte aligned codes: one kernel does it all
   const auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };

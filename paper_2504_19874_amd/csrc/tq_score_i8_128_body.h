@@ -80,7 +80,7 @@ __device__ __forceinline__ void score128_body(const ScoreI8Args& a, uint2* expan
   // ---- 2. the codes of this wavefront's keys, as contiguous 16-byte pieces ---------------------
   // Pieces past the end of the arrays are clamped onto the last one (never used: the
   // scores of keys past the end are not stored).
-  const int64_t gbase = (int64_t)group * a.n;
+  const int64_t gbase = (int64_t)group * a.group_stride;
   const int64_t wave_key0 = ((int64_t)blockIdx.x * 8 + wave) * (16 * TILES_128);
   const bool full = wave_key0 + 16 * TILES_128 <= a.n;  // uniform: no key of this wavefront is past the end
   const int64_t wrow0 = gbase + wave_key0;

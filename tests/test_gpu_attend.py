@@ -221,3 +221,98 @@ def test_attend_equals_softmax_of_scores_times_dequantized_values():
     tq.tq_attend(pk, pv, q, n_groups, qpg, (ki, kz, kg, kn), (vi, None, None, vn), npg, scale, out)
     size = torch.cat([p[g * qpg:(g + 1) * qpg] @ vt[g * npg:(g + 1) * npg].double().abs() for g in range(n_groups)])
     assert ((out.double() - want).abs() <= 1e-4 * (size + want.abs())).all()
+
+
+def _empty_cache(p, rows, prod):
+    """Code arrays of `rows` token slots filled with a pattern no quantiser call writes."""
+    idx = torch.full((rows, p.idx_words), -1, dtype=torch.int32, device=DEV) if p.idx_words else None
+    qjl = torch.full((rows, p.qjl_words), -1, dtype=torch.int32, device=DEV) if prod else None
+    gamma = torch.full((rows,), float("nan"), dtype=torch.float32, device=DEV) if prod else None
+    norm = torch.full((rows,), float("nan"), dtype=torch.float32, device=DEV)
+    return idx, qjl, gamma, norm
+
+
+def _quantize_dense(p, x, prod):
+    idx, qjl, gamma, norm = _empty_cache(p, x.shape[0], prod)
+    if prod:
+        tq.tq_quantize_prod(p, x, idx, qjl, gamma, norm)
+    else:
+        tq.tq_quantize_mse(p, x, idx, norm)
+    return idx, qjl, gamma, norm
+
+
+@pytest.mark.parametrize("kb,kprod,vb,vprod", [(2, True, 2, False), (3, True, 1, True), (2, False, 4, False)])
+def test_cache_growth_append_then_attend(kb, kprod, vb, vprod):
+    """A cache laid out [head][capacity] grows the way decoding grows it (Sec. 4.3: tokens are quantised as
+    they arrive): a prefill of each head, then one token for every head per step.  The code rows must be
+    bit-identical to quantising the same vectors densely, untouched slots must stay untouched, and the
+    read-out over the strided cache must match the oracle on the filled part."""
+    d, heads, qpg, cap, prefill, steps = 128, 4, 4, 2600, 2100, 3
+    pk, Pik, Sk, ck = setup(d, kb, kprod, 100, 200)
+    pv, Piv, Sv, cv = setup(d, vb, vprod, 300, 400)
+    rng = np.random.default_rng(5)
+    filled = prefill + steps
+    keys = (rng.standard_normal((heads, filled, d)) * np.exp(rng.normal(0, 0.3, (heads, filled, 1)))).astype(np.float32)
+    vals = (rng.standard_normal((heads, filled, d)) * np.exp(rng.normal(0, 1.0, (heads, filled, 1)))).astype(np.float32)
+    kc, vc = _empty_cache(pk, heads * cap, kprod), _empty_cache(pv, heads * cap, vprod)
+    for h in range(heads):  # prefill: a run of consecutive slots per head
+        tq.tq_append(pk, dev(keys[h, :prefill]), *kc, h * cap, 1)
+        tq.tq_append(pv, dev(vals[h, :prefill]), *vc, h * cap, 1)
+    for t in range(prefill, filled):  # decode: one token for every head
+        tq.tq_append(pk, dev(keys[:, t]), *kc, t, cap)
+        tq.tq_append(pv, dev(vals[:, t]), *vc, t, cap)
+    torch.cuda.synchronize()
+
+    # the codes: equal to a dense quantiser call on the same vectors, and nothing else written
+    for p, x, prod, cache in ((pk, keys, kprod, kc), (pv, vals, vprod, vc)):
+        dense = _quantize_dense(p, dev(x.reshape(heads * filled, d)), prod)
+        for name, got, want in zip(("idx", "qjl", "gamma", "norm"), cache, dense):
+            if got is None:
+                continue
+            got = got.reshape(heads, cap, -1)
+            assert torch.equal(got[:, :filled], want.reshape(heads, filled, -1)), f"{name}: appended rows differ"
+            rest = got[:, filled:]
+            untouched = torch.isnan(rest).all() if rest.dtype == torch.float32 else (rest == -1).all()
+            assert bool(untouched), f"{name}: a slot past the filled part was written"
+
+    # the read-out, against the oracle on the codes the cache holds
+    def host_codes(p, cache, prod):
+        idx, qjl, gamma, norm = [None if t is None else t.reshape(heads, cap, -1)[:, :filled].reshape(heads * filled, -1).cpu().numpy()
+                                 for t in cache]
+        i = o.unpack_planes(idx.view(np.uint32), p.bits_mse, d) if p.bits_mse else np.zeros((heads * filled, d), np.int32)
+        z = o.unpack_signs(qjl.view(np.uint32), d) if prod else None
+        return i, z, None if gamma is None else gamma[:, 0], norm[:, 0]
+
+    k_codes, v_codes = host_codes(pk, kc, kprod), host_codes(pv, vc, vprod)
+    kt, vt = dequant(k_codes, Pik, Sk, ck), dequant(v_codes, Piv, Sv, cv)
+    nq = heads * qpg
+    q = W.gaussian_queries(nq, d, 9, unit=False)
+    scale = 1.0 / math.sqrt(d)
+    sl = lambda a, g: a[g * filled:(g + 1) * filled]
+    want = np.concatenate([o.attend(q[g * qpg:(g + 1) * qpg], sl(kt, g), sl(vt, g), scale) for g in range(heads)])
+    p_want = np.concatenate([o.attend(q[g * qpg:(g + 1) * qpg], sl(kt, g), np.eye(filled), scale) for g in range(heads)])
+    out = torch.full((nq, d), float("nan"), dtype=torch.float32, device=DEV)
+    tq.tq_attend(pk, pv, dev(q), heads, qpg, kc, vc, filled, scale, out, group_stride=cap)
+    check_attend(out.cpu().numpy().astype(np.float64), want, q, scale, k_codes[3], vt, p_want, d, heads, qpg, filled)
+
+
+def test_cache_calls_reject_what_they_do_not_cover():
+    p64, *_ = setup(64, 2, True, 100, 200)
+    x = torch.zeros((4, 64), dtype=torch.float32, device=DEV)
+    cache = _empty_cache(p64, 16, True)
+    with pytest.raises(tq.TurboQuantError):
+        tq.tq_append(p64, x, *cache, 0, 4)  # d != 128
+    p, *_ = setup(128, 2, True, 100, 200)
+    x = torch.zeros((4, 128), dtype=torch.float32, device=DEV)
+    cache = _empty_cache(p, 16, True)
+    with pytest.raises(tq.TurboQuantError):
+        tq.tq_append(p, x, *cache, -1, 4)
+    with pytest.raises(tq.TurboQuantError):
+        tq.tq_append(p, x, *cache, 0, 0)
+    out = torch.zeros((4, 64), dtype=torch.float32, device=DEV)
+    q = torch.zeros((4, 64), dtype=torch.float32, device=DEV)
+    with pytest.raises(tq.TurboQuantError):  # strided groups need the d = 128 kernel
+        tq.tq_attend(p64, p64, q, 1, 4, cache, cache, 8, 1.0, out, group_stride=16)
+    with pytest.raises(tq.TurboQuantError):  # fewer slots than tokens
+        tq.tq_attend(p, p, torch.zeros((4, 128), device=DEV), 1, 4, cache, cache, 8, 1.0,
+                     torch.zeros((4, 128), device=DEV), group_stride=4)

@@ -96,6 +96,39 @@ def test_quantize_split(d_hi, bits_lo, prod, n, bf16):
             P.check_signs(z_part, u_or, s_norm[None, :] * gamma_or[:, None])
 
 
+@pytest.mark.parametrize("d_hi,bits_lo,prod", [(32, 2, True), (64, 1, False)])
+def test_append_split_equals_the_dense_call(d_hi, bits_lo, prod):
+    """tq_append with two instances: rows scattered into a larger cache hold exactly what the dense quantiser
+    call (checked against the oracle above) writes for the same vectors, and no other slot is touched."""
+    hi_ch, _, _, p = instances(d_hi, bits_lo, prod)
+    n, first, step = 37, 11, 3
+    rows = first + n * step + 5
+    _, x_dev = keys(n, hi_ch, bf16=True)
+
+    def arrays(r, fill):
+        idx = torch.full((r, p.idx_words), fill, dtype=torch.int32, device=DEV)
+        norm = torch.full((r, 2), float("nan"), dtype=torch.float32, device=DEV)
+        qjl = torch.full((r, p.qjl_words), fill, dtype=torch.int32, device=DEV) if prod else None
+        gamma = torch.full((r, 2), float("nan"), dtype=torch.float32, device=DEV) if prod else None
+        return idx, qjl, gamma, norm
+
+    dense, cache = arrays(n, 0), arrays(rows, -1)
+    if prod:
+        tq.tq_quantize_prod(p, x_dev, *dense)
+    else:
+        tq.tq_quantize_mse(p, x_dev, dense[0], dense[3])
+    tq.tq_append(p, x_dev, *cache, first, step)
+    sel = torch.arange(n, device=DEV) * step + first
+    rest = torch.ones(rows, dtype=torch.bool, device=DEV)
+    rest[sel] = False
+    for name, got, want in zip(("idx", "qjl", "gamma", "norm"), cache, dense):
+        if got is None:
+            continue
+        assert torch.equal(got[sel], want), f"{name}: appended rows differ from the dense call"
+        other = got[rest]
+        assert bool(torch.isnan(other).all() if other.dtype == torch.float32 else (other == -1).all()), f"{name}: stray write"
+
+
 def random_codes(p, ihi, ilo, d_hi, n, prod, seed=21):
     """Random codes of both instances, in the oracle's form and packed in the split layout."""
     rng = np.random.default_rng(seed)
