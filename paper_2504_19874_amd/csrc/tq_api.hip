@@ -110,6 +110,12 @@ tq_status quantize_common(const tq_params* p, const void* x, tq_dtype dtype, int
                                     p->d_hi / 32, make_codebook_hi(p), stream));
   }
 
+  // head dimension 128, a large batch of bf16 vectors: the contractions on the bf16 matrix cores
+  if (d == 128 && dtype == TQ_BF16 && n >= kBf3QuantRows && quant128_bf3_applicable(p->bits_mse, prod, x, ldx) &&
+      (p->bits_mse == 0 || aligned16(idx)) && (!prod || aligned16(qjl)))
+    return from_hip(launch_quant128_bf3(p->bits_mse, prod, x, ldx, n, p->Pi, prod ? p->SPiT : nullptr, idx, qjl, gamma,
+                                        norm, make_codebook(p), stream));
+
   // head dimension 128: one fused kernel, parameters resident in LDS
   if (d == 128 && aligned16(x) && (ldx * esz) % 16 == 0) {
     return from_hip(launch_quant128(p->bits_mse, prod, dtype == TQ_BF16, x, ldx, n, p->Pi,

@@ -42,4 +42,11 @@ __device__ __forceinline__ void split3_pair(f32x2 x, uint32_t& w1, uint32_t& w2,
   w3 = bf16_pair(r2);
 }
 
+// the two leading pieces only: x1 + x2 == x up to 2^-17 |x|
+__device__ __forceinline__ void split2_pair(f32x2 x, uint32_t& w1, uint32_t& w2) {
+  w1 = bf16_pair(x);
+  const f32x2 r1 = {x[0] - __uint_as_float(w1 << 16), x[1] - __uint_as_float(w1 & 0xffff0000u)};
+  w2 = bf16_pair(r1);
+}
+
 }  // namespace tq

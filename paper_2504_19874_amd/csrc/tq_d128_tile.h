@@ -6,6 +6,14 @@ namespace tq {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
+// nib = 2 nib + bit as ONE add-with-carry whose carry-in is the compare mask itself (written as a select and a
+// shift-or otherwise)
+__device__ __forceinline__ uint32_t shift_in(uint32_t nib, uint64_t mask) {
+  uint64_t carry_out;
+  asm("v_addc_co_u32 %0, %1, %2, %2, %3" : "=v"(nib), "=s"(carry_out) : "v"(nib), "s"(mask));
+  return nib;
+}
+
 // One output tile (32 coordinates x 32 vectors, 16 coordinates per lane) through the decision
 // of Alg. 1: nearest centroid, packing, residual (in place).  Bit p of the bucket number is the
 // XOR of the compare masks at positions k = 2^p - 1 (mod 2^p); a 4-bit nibble of a plane is
@@ -24,26 +32,27 @@ __device__ __forceinline__ float quantise_tile(floatx16& acc, const float inv, c
     for (int r = 3; r >= 0; --r) {
       const float y = acc[4 * k + r] * inv;
       float yt = cb.c[0];
-      bool bit[B > 0 ? B : 1];
+      uint64_t bit[B > 0 ? B : 1];  // lane masks, combined on the scalar unit
 #pragma unroll
-      for (int pl = 0; pl < (B > 0 ? B : 1); ++pl) bit[pl] = false;
+      for (int pl = 0; pl < (B > 0 ? B : 1); ++pl) bit[pl] = 0;
 #pragma unroll
       for (int j = 0; j < (1 << B) - 1; ++j) {
-        const bool ge = y >= cb.t[j];
-        yt = ge ? cb.c[j + 1] : yt;
+        // both table values are read before the select: a read inside one arm of the conditional can be
+        // merged by the compiler into ONE indexed load from the table's memory, a round trip per coordinate
+        const float tj = cb.t[j], cj = cb.c[j + 1];
+        const bool ge = y >= tj;
+        yt = ge ? cj : yt;
+        const uint64_t gem = __builtin_amdgcn_ballot_w64(ge);
 #pragma unroll
         for (int pl = 0; pl < B; ++pl)
-          if ((j & ((1 << pl) - 1)) == (1 << pl) - 1) bit[pl] = bit[pl] != ge;
+          if ((j & ((1 << pl) - 1)) == (1 << pl) - 1) bit[pl] ^= gem;
       }
       float e = y - yt;
       asm volatile("" : "+v"(e));  // keep the residual here: sunk later it would need the masks again
       g2 = fmaf(e, e, g2);
       acc[4 * k + r] = e;
 #pragma unroll
-      for (int pl = 0; pl < B; ++pl) {
-        nib[k][pl] = nib[k][pl] + nib[k][pl] + (bit[pl] ? 1u : 0u);
-        asm volatile("" : "+v"(nib[k][pl]));  // consume this element's masks now (scalar registers)
-      }
+      for (int pl = 0; pl < B; ++pl) nib[k][pl] = shift_in(nib[k][pl], bit[pl]);
     }
   }
 #pragma unroll

@@ -1,0 +1,317 @@
+// Quant_mse / Quant_prod (Alg. 1 / Alg. 2) at d = 128 for large batches of bf16 vectors, on the bf16 matrix
+// cores at fp32 accuracy (exact bf16 pieces of every fp32 factor, see tq_bf3.h).
+//
+//   stage 1   y^T = Pi x^T.  A bf16 input IS a single piece, so the rotation takes three piece products
+//             (x times the three pieces of Pi).  The vector is the COLUMN of the MFMA: a lane loads 8
+//             consecutive bf16 of its vector's row from HBM and that register is the B operand as it
+//             stands; the A operand is a piece of Pi, resident in LDS for the life of the workgroup.
+//   decision  the accumulator tile holds 16 coordinates of one vector per lane: scale by 1 / ||x||, nearest
+//             centroid, packing, residual e = y - c[idx] in place (quantise_tile), gamma = ||e||.
+//   stage 2   u^T = (S Pi^T) e^T, of which only the signs are kept.  The residual registers, split into their
+//             two leading pieces (e to 2^-17 |e| per coordinate: u to about 4e-7 |S_j| |e|, against the 1e-5
+//             inside which a sign may differ from the exact one), are directly the B operand (the order in
+//             which they enumerate the contraction index is a fixed permutation inside every run of 16, which
+//             the LDS image of S Pi^T follows); five piece products with the three pieces of S Pi^T.  The three
+//             pieces of Pi and of S Pi^T together exceed the LDS, so S Pi^T is held one half of its rows
+//             (= output coordinates, two of the four sign words) at a time: a block of vectors is finished
+//             for the resident half, the other half is brought in (its fp32 values were fetched during the
+//             first half), and the next block starts with the half that is already there.
+//
+// Workgroup = 4 wavefronts (one per SIMD, the register file to itself); a wavefront takes 64 vectors per
+// block, so every LDS read of an A operand feeds at least two MFMAs.
+#include "tq_bf3.h"
+#include "tq_d128_tile.h"
+
+namespace tq {
+
+namespace {
+
+constexpr int LDJ = 136;  // bf16 per LDS row: 128 values + 8 padding (272 bytes: conflict-free 16-byte reads)
+constexpr int PI_ELEMS = 3 * 128 * LDJ;
+constexpr int W_ELEMS = 3 * 64 * LDJ;
+
+struct Q128Args {
+  const unsigned short* X;  // bf16
+  int64_t ldx;
+  int64_t n;
+  const float* Pi;
+  const float* SPiT;
+  uint32_t* idx;
+  uint32_t* qjl;
+  float* gamma;
+  float* norm;  // nullable: no normalisation then
+  Codebook cb;
+};
+
+// sum of the squares of two bf16 values (exact products, fp32 sum) added to acc
+__device__ __forceinline__ float square_pair(uint32_t w, float acc) {
+  const float lo = __uint_as_float(w << 16), hi = __uint_as_float(w & 0xffff0000u);
+  return fmaf(hi, hi, fmaf(lo, lo, acc));
+}
+
+template <int BITS, bool PROD>
+__global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
+  constexpr int NB = BITS > 0 ? BITS : 1;
+  extern __shared__ __attribute__((aligned(16))) unsigned short lds_s[];
+  unsigned short* const Pi_s = lds_s;            // [piece][row j][LDJ]
+  unsigned short* const W_s = lds_s + PI_ELEMS;  // [piece][row j' of the resident half][LDJ], columns permuted
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int vi = lane & 31, g = lane >> 5;
+
+  // position of column j inside its run of 16 in the image of S Pi^T: the two middle groups of four change
+  // places (see stage 2)
+  auto w_col = [](int j) { return (j & ~12) | ((j & 4) << 1) | ((j & 8) >> 1); };
+  // 64 x 128 fp32 values -> three pieces in LDS; 8 x 16 bytes per thread
+  auto split_to_lds = [&](const f32x4 (&v)[8], unsigned short* dst, bool permute) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int e = (i * 256 + tid) * 4;
+      const int row = e >> 7, j = e & 127;
+      uint32_t lo[3], hi[3];
+      split3_pair(f32x2{v[i][0], v[i][1]}, lo[0], lo[1], lo[2]);
+      split3_pair(f32x2{v[i][2], v[i][3]}, hi[0], hi[1], hi[2]);
+      const int col = permute ? w_col(j) : j;
+#pragma unroll
+      for (int pc = 0; pc < 3; ++pc)
+        *reinterpret_cast<uint2*>(dst + (pc * (permute ? 64 : 128) + row) * LDJ + col) = make_uint2(lo[pc], hi[pc]);
+    }
+  };
+  auto fetch64 = [&](const float* src, f32x4 (&v)[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const f32x4*>(src + (i * 256 + tid) * 4);
+  };
+
+  f32x4 wpre[8];
+  {
+    f32x4 lo[8], hi[8];
+    fetch64(a.Pi, lo);
+    fetch64(a.Pi + 64 * 128, hi);
+    if (PROD) fetch64(a.SPiT, wpre);
+    split_to_lds(lo, Pi_s, false);
+    split_to_lds(hi, Pi_s + 64 * LDJ, false);
+    if (PROD) split_to_lds(wpre, W_s, true);
+  }
+  __syncthreads();
+  int resident = 0;  // which half of the rows of S Pi^T is in LDS
+
+  const int64_t blocks = (a.n + 255) / 256;
+  const bool normalise = a.norm != nullptr;
+  u32x4 xop[2][8];
+  auto load_x = [&](int64_t blk) {
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+      const int64_t v = blk * 256 + wave * 64 + 32 * nt + vi;
+      const int64_t row = v < a.n ? v : a.n - 1;  // clamped: such vectors are not stored
+      const unsigned short* src = a.X + row * a.ldx + 8 * g;
+#pragma unroll
+      for (int s = 0; s < 8; ++s) xop[nt][s] = *reinterpret_cast<const u32x4*>(src + 16 * s);
+    }
+  };
+  load_x(blockIdx.x);
+
+  for (int64_t blk = blockIdx.x; blk < blocks; blk += gridDim.x) {
+    // ---- norms: a lane and its partner in the other half-wave hold one vector between them --------------
+    float nu[2] = {1.f, 1.f}, inv[2] = {1.f, 1.f};
+    if (normalise) {
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt) {
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+          s0 = square_pair(xop[nt][s][0], s0);
+          s1 = square_pair(xop[nt][s][1], s1);
+          s0 = square_pair(xop[nt][s][2], s0);
+          s1 = square_pair(xop[nt][s][3], s1);
+        }
+        float ss = s0 + s1;
+        ss += __shfl_xor(ss, 32);
+        nu[nt] = sqrtf(ss);
+        inv[nt] = nu[nt] > 0.f ? 1.f / nu[nt] : 0.f;
+      }
+    }
+
+    // ---- stage 1: y^T = Pi x^T, three piece products ----------------------------------------------------
+    floatx16 acc[2][4];
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[nt][t][r] = 0.f;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+#pragma unroll
+      for (int pc = 2; pc >= 0; --pc) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const bf16x8 pa = *reinterpret_cast<const bf16x8*>(Pi_s + (pc * 128 + 32 * t + vi) * LDJ + 16 * s + 8 * g);
+#pragma unroll
+          for (int nt = 0; nt < 2; ++nt)
+            acc[nt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa, *reinterpret_cast<const bf16x8*>(&xop[nt][s]),
+                                                                 acc[nt][t], 0, 0, 0);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+
+    // ---- decision: indices, packing, residual in place; the residual's pieces ---------------------------
+    // register 4 k + r of tile t holds coordinate j = 32 t + 8 k + 4 g + r of the lane's vector
+    uint32_t word[2][4][NB];
+    float g2[2] = {0.f, 0.f};
+    u32x4 rp[2][2][8];  // [piece][nt][step of stage 2]
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        uint32_t wd[4] = {0u, 0u, 0u, 0u};
+        g2[nt] += quantise_tile<BITS>(acc[nt][t], inv[nt], a.cb, g, wd);
+#pragma unroll
+        for (int pl = 0; pl < BITS; ++pl) word[nt][t][pl] = wd[pl];
+        if (PROD) {
+#pragma unroll
+          for (int p = 0; p < 2; ++p)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              uint32_t w1, w2;
+              split2_pair(f32x2{acc[nt][t][8 * p + 2 * e], acc[nt][t][8 * p + 2 * e + 1]}, w1, w2);
+              rp[0][nt][2 * t + p][e] = w1;
+              rp[1][nt][2 * t + p][e] = w2;
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+
+    // the next block's vectors, and the other half of S Pi^T, travel while this block is finished
+    const int64_t v_mine = blk * 256 + wave * 64 + 32 * g + vi;  // the vector this lane stores for: tile nt = g
+    load_x(blk + gridDim.x);
+    if (PROD) fetch64(a.SPiT + (1 - resident) * 64 * 128, wpre);
+
+    // ---- the codes of Alg. 1: lane (vi, g) writes the row of vector 32 g + vi ----------------------------
+    if (v_mine < a.n) {
+      if (BITS > 0) {
+        uint32_t* dst = a.idx + v_mine * (4 * BITS);
+        uint32_t row[4 * NB];
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+          for (int pl = 0; pl < BITS; ++pl)  // word[g][t][pl], selected with a mask (an indexed array would live in scratch memory)
+            row[t * BITS + pl] = word[0][t][pl] ^ ((word[0][t][pl] ^ word[1][t][pl]) & (0u - (uint32_t)g));
+#pragma unroll
+        for (int q = 0; q < BITS; ++q)
+          *reinterpret_cast<u32x4*>(dst + 4 * q) = u32x4{row[4 * q], row[4 * q + 1], row[4 * q + 2], row[4 * q + 3]};
+      }
+      if (normalise) a.norm[v_mine] = g ? nu[1] : nu[0];
+    }
+
+    if (PROD) {
+      // ---- stage 2: u^T = (S Pi^T) e^T, six piece products, one half of the output coordinates at a time ----
+      uint32_t sw[2][4];  // [nt][sign word]
+#pragma unroll
+      for (int pass = 0; pass < 2; ++pass) {
+        if (pass == 1) {
+          __syncthreads();  // every wavefront is done with the resident half
+          split_to_lds(wpre, W_s, true);
+          resident = 1 - resident;
+          __syncthreads();
+        }
+        floatx16 u[2][2];
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) u[nt][mt][r] = 0.f;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+#pragma unroll
+          for (int pa = 2; pa >= 0; --pa) {  // piece of S Pi^T; smallest products first
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) {
+              const bf16x8 wa = *reinterpret_cast<const bf16x8*>(W_s + (pa * 64 + 32 * mt + vi) * LDJ + 16 * s + 8 * g);
+#pragma unroll
+              for (int pb = pa < 2 ? 1 : 0; pb >= 0; --pb)
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
+                  u[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, *reinterpret_cast<const bf16x8*>(&rp[pb][nt][s]),
+                                                                      u[nt][mt], 0, 0, 0);
+            }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        // signs: register 4 k + r of tile mt is coordinate 64 resident + 32 mt + 8 k + 4 g + r
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt) {
+            uint32_t nib[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+              nib[k] = 0u;
+#pragma unroll
+              for (int r = 3; r >= 0; --r) nib[k] = shift_in(nib[k], __builtin_amdgcn_ballot_w64(u[nt][mt][4 * k + r] >= 0.f));
+            }
+            const uint32_t w = (nib[0] | (nib[1] << 8) | (nib[2] << 16) | (nib[3] << 24)) << (4 * g);
+            const uint32_t both = w | (uint32_t)__shfl_xor((int)w, 32);
+            // resident is uniform; written without a runtime register index
+            if (resident == 0) sw[nt][mt] = both; else sw[nt][2 + mt] = both;
+          }
+      }
+      g2[0] += __shfl_xor(g2[0], 32);
+      g2[1] += __shfl_xor(g2[1], 32);
+      if (v_mine < a.n) {
+        *reinterpret_cast<u32x4*>(a.qjl + v_mine * 4) =
+            g ? u32x4{sw[1][0], sw[1][1], sw[1][2], sw[1][3]} : u32x4{sw[0][0], sw[0][1], sw[0][2], sw[0][3]};
+        a.gamma[v_mine] = sqrtf(g ? g2[1] : g2[0]);
+      }
+    }
+  }
+}
+
+template <int BITS, bool PROD>
+hipError_t launch_one(const Q128Args& a, hipStream_t s) {
+  constexpr int lds = (PI_ELEMS + (PROD ? W_ELEMS : 0)) * 2;
+  static bool attr_done = false;  // per instantiation: the limit has to be raised once
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant128_bf3_kernel<BITS, PROD>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int64_t blocks = (a.n + 255) / 256;
+  hipLaunchKernelGGL((quant128_bf3_kernel<BITS, PROD>), dim3((unsigned)(blocks < 256 ? blocks : 256)), dim3(256), lds, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// bf16 rows of 128 values, 16-byte aligned with a row stride that keeps them so
+bool quant128_bf3_applicable(int bits, bool prod, const void* X, int64_t ldx) {
+  if (bits < 0 || bits > 4 || (bits == 0 && !prod)) return false;
+  return (reinterpret_cast<uintptr_t>(X) & 15u) == 0 && ldx % 8 == 0;
+}
+
+hipError_t launch_quant128_bf3(int bits, bool prod, const void* X, int64_t ldx, int64_t n, const float* Pi,
+                               const float* SPiT, uint32_t* idx, uint32_t* qjl, float* gamma, float* norm,
+                               const Codebook& cb, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  Q128Args a;
+  a.X = static_cast<const unsigned short*>(X); a.ldx = ldx; a.n = n; a.Pi = Pi; a.SPiT = SPiT; a.idx = idx; a.qjl = qjl;
+  a.gamma = gamma; a.norm = norm; a.cb = cb;
+  switch (bits * 2 + (prod ? 1 : 0)) {
+    case 1: return launch_one<0, true>(a, s);
+    case 2: return launch_one<1, false>(a, s);
+    case 3: return launch_one<1, true>(a, s);
+    case 4: return launch_one<2, false>(a, s);
+    case 5: return launch_one<2, true>(a, s);
+    case 6: return launch_one<3, false>(a, s);
+    case 7: return launch_one<3, true>(a, s);
+    case 8: return launch_one<4, false>(a, s);
+    case 9: return launch_one<4, true>(a, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace tq

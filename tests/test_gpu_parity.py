@@ -118,6 +118,9 @@ def _quant_inputs(n, d, kind, seed):
     x = W.unit_gaussian_rows(n, d, seed)
     if kind == "unit":
         return x, dev(x), False
+    if kind == "bf16unit":  # bf16 rows taken as they are (no normalisation, no norm stored)
+        bits16 = W.f32_to_bf16_bits(x)
+        return o.bf16_bits_to_f64(bits16), bf16_tensor(bits16), False
     x = (x.astype(np.float64) * np.exp(np.random.default_rng(seed).normal(0, 1.5, size=(n, 1)))).astype(np.float32)
     if n > 3:
         x[3] = 0.0  # a zero vector
@@ -133,6 +136,8 @@ def _quant_inputs(n, d, kind, seed):
     (64, 0, 40, "f32"),
     # d = 128 above the small-batch threshold: the bf16-piece contraction (rows of Pi^T as queries)
     (128, 1, 30000, "f32"), (128, 4, 25000, "unit"), (128, 3, 40000, "bf16"),
+    # large batches of bf16 vectors: the kernel on the bf16 matrix cores (blocks of 256 vectors, ragged tails)
+    (128, 1, 33000, "bf16"), (128, 2, 32845, "bf16unit"), (128, 4, 70001, "bf16"),
 ])
 def test_quantize_mse(d, bits, n, kind):
     p, Pi, _, c32, t32 = setup(d, bits, False)
@@ -181,6 +186,9 @@ def _check_prod(p, Pi, S, c32, t32, x_or, normalise, idx, qjl, gamma, norm):
     (256, 2, 300, "unit"), (1536, 1, 200, "unit"), (96, 4, 130, "f32"),
     # d = 128 above the small-batch threshold: the bf16-piece contraction (rows of Pi^T as queries)
     (128, 0, 26000, "f32"), (128, 1, 33000, "unit"), (128, 4, 25001, "bf16"),
+    # large batches of bf16 vectors: the kernel on the bf16 matrix cores (blocks of 256 vectors, ragged tails)
+    (128, 0, 33000, "bf16"), (128, 1, 40001, "bf16"), (128, 2, 66000, "bf16"), (128, 3, 32768, "bf16unit"),
+    (128, 4, 33333, "bf16"),
 ])
 def test_quantize_prod(d, bits_mse, n, kind):
     p, Pi, S, c32, t32 = setup(d, bits_mse, True)
