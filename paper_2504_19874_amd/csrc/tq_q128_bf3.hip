@@ -8,14 +8,14 @@
 //   decision  the accumulator tile holds 16 coordinates of one vector per lane: scale by 1 / ||x||, nearest
 //             centroid, packing, residual e = y - c[idx] in place (quantise_tile), gamma = ||e||.
 //   stage 2   u^T = (S Pi^T) e^T, of which only the signs are kept.  The residual registers, split into their
-//             two leading pieces (e to 2^-17 |e| per coordinate: u to about 4e-7 |S_j| |e|, against the 1e-5
-//             inside which a sign may differ from the exact one), are directly the B operand (the order in
-//             which they enumerate the contraction index is a fixed permutation inside every run of 16, which
-//             the LDS image of S Pi^T follows); five piece products with the three pieces of S Pi^T.  The three
-//             pieces of Pi and of S Pi^T together exceed the LDS, so S Pi^T is held one half of its rows
-//             (= output coordinates, two of the four sign words) at a time: a block of vectors is finished
-//             for the resident half, the other half is brought in (its fp32 values were fetched during the
-//             first half), and the next block starts with the half that is already there.
+//             two leading pieces, are directly the B operand (the order in which they enumerate the
+//             contraction index is a fixed permutation inside every run of 16, which the LDS image of
+//             S Pi^T follows).  S Pi^T is held as its two leading pieces as well, and the three products of
+//             combined weight >= 2^-9 are taken: what is left out is below 3 * 2^-18 per term, about
+//             5e-7 |S_j| |e| in u, against the 1e-5 |S_j| |e| inside which a sign may differ from the exact one.
+//   LDS       three pieces of Pi and two of S Pi^T, 128 x 128 bf16 each, are exactly the 160 KB of a compute
+//             unit: rows are stored without padding, the 16-byte chunks of a row rotated by the row number
+//             (conflict-free 16-byte reads along a column of chunks).
 //
 // Workgroup = 4 wavefronts (one per SIMD, the register file to itself); a wavefront takes 64 vectors per
 // block, so every LDS read of an A operand feeds at least two MFMAs.
@@ -26,9 +26,12 @@ namespace tq {
 
 namespace {
 
-constexpr int LDJ = 136;  // bf16 per LDS row: 128 values + 8 padding (272 bytes: conflict-free 16-byte reads)
-constexpr int PI_ELEMS = 3 * 128 * LDJ;
-constexpr int W_ELEMS = 3 * 64 * LDJ;
+constexpr int MAT_ELEMS = 128 * 128;  // one piece of one matrix
+constexpr int PI_ELEMS = 3 * MAT_ELEMS;
+constexpr int W_ELEMS = 2 * MAT_ELEMS;
+
+// element offset of column col (a multiple of 4) of row `row` inside a piece: chunk (col / 8) xor (row % 16)
+__device__ __forceinline__ int lds_at(int row, int col) { return row * 128 + ((((col >> 3) ^ row) & 15) << 3) + (col & 7); }
 
 struct Q128Args {
   const unsigned short* X;  // bf16
@@ -53,8 +56,8 @@ template <int BITS, bool PROD>
 __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
   constexpr int NB = BITS > 0 ? BITS : 1;
   extern __shared__ __attribute__((aligned(16))) unsigned short lds_s[];
-  unsigned short* const Pi_s = lds_s;            // [piece][row j][LDJ]
-  unsigned short* const W_s = lds_s + PI_ELEMS;  // [piece][row j' of the resident half][LDJ], columns permuted
+  unsigned short* const Pi_s = lds_s;            // [piece][row j][128], see lds_at
+  unsigned short* const W_s = lds_s + PI_ELEMS;  // [piece][row j'][128], columns permuted
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -63,19 +66,19 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
   // position of column j inside its run of 16 in the image of S Pi^T: the two middle groups of four change
   // places (see stage 2)
   auto w_col = [](int j) { return (j & ~12) | ((j & 4) << 1) | ((j & 8) >> 1); };
-  // 64 x 128 fp32 values -> three pieces in LDS; 8 x 16 bytes per thread
-  auto split_to_lds = [&](const f32x4 (&v)[8], unsigned short* dst, bool permute) {
+  // rows [row0, row0 + 64) of a 128 x 128 fp32 matrix -> its leading `pieces` pieces in LDS; 8 x 16 bytes per thread
+  auto split_to_lds = [&](const f32x4 (&v)[8], unsigned short* dst, int row0, int pieces, bool permute) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int e = (i * 256 + tid) * 4;
-      const int row = e >> 7, j = e & 127;
+      const int row = row0 + (e >> 7), j = e & 127;
       uint32_t lo[3], hi[3];
       split3_pair(f32x2{v[i][0], v[i][1]}, lo[0], lo[1], lo[2]);
       split3_pair(f32x2{v[i][2], v[i][3]}, hi[0], hi[1], hi[2]);
-      const int col = permute ? w_col(j) : j;
+      const int at = lds_at(row, permute ? w_col(j) : j);
 #pragma unroll
       for (int pc = 0; pc < 3; ++pc)
-        *reinterpret_cast<uint2*>(dst + (pc * (permute ? 64 : 128) + row) * LDJ + col) = make_uint2(lo[pc], hi[pc]);
+        if (pc < pieces) *reinterpret_cast<uint2*>(dst + pc * MAT_ELEMS + at) = make_uint2(lo[pc], hi[pc]);
     }
   };
   auto fetch64 = [&](const float* src, f32x4 (&v)[8]) {
@@ -83,33 +86,34 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
     for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const f32x4*>(src + (i * 256 + tid) * 4);
   };
 
-  f32x4 wpre[8];
   {
     f32x4 lo[8], hi[8];
     fetch64(a.Pi, lo);
     fetch64(a.Pi + 64 * 128, hi);
-    if (PROD) fetch64(a.SPiT, wpre);
-    split_to_lds(lo, Pi_s, false);
-    split_to_lds(hi, Pi_s + 64 * LDJ, false);
-    if (PROD) split_to_lds(wpre, W_s, true);
+    split_to_lds(lo, Pi_s, 0, 3, false);
+    split_to_lds(hi, Pi_s, 64, 3, false);
+    if (PROD) {
+      fetch64(a.SPiT, lo);
+      fetch64(a.SPiT + 64 * 128, hi);
+      split_to_lds(lo, W_s, 0, 2, true);
+      split_to_lds(hi, W_s, 64, 2, true);
+    }
   }
   __syncthreads();
-  int resident = 0;  // which half of the rows of S Pi^T is in LDS
 
   const int64_t blocks = (a.n + 255) / 256;
   const bool normalise = a.norm != nullptr;
   u32x4 xop[2][8];
-  auto load_x = [&](int64_t blk) {
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-      const int64_t v = blk * 256 + wave * 64 + 32 * nt + vi;
-      const int64_t row = v < a.n ? v : a.n - 1;  // clamped: such vectors are not stored
-      const unsigned short* src = a.X + row * a.ldx + 8 * g;
-#pragma unroll
-      for (int s = 0; s < 8; ++s) xop[nt][s] = *reinterpret_cast<const u32x4*>(src + 16 * s);
-    }
+  auto x_row = [&](int64_t blk, int nt) {  // this lane's 8 values of step 0
+    const int64_t v = blk * 256 + wave * 64 + 32 * nt + vi;
+    return a.X + (v < a.n ? v : a.n - 1) * a.ldx + 8 * g;  // clamped: such vectors are not stored
   };
-  load_x(blockIdx.x);
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt) {
+    const unsigned short* src = x_row(blockIdx.x, nt);
+#pragma unroll
+    for (int s = 0; s < 8; ++s) xop[nt][s] = *reinterpret_cast<const u32x4*>(src + 16 * s);
+  }
 
   for (int64_t blk = blockIdx.x; blk < blocks; blk += gridDim.x) {
     // ---- norms: a lane and its partner in the other half-wave hold one vector between them --------------
@@ -146,7 +150,7 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
       for (int pc = 2; pc >= 0; --pc) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-          const bf16x8 pa = *reinterpret_cast<const bf16x8*>(Pi_s + (pc * 128 + 32 * t + vi) * LDJ + 16 * s + 8 * g);
+          const bf16x8 pa = *reinterpret_cast<const bf16x8*>(Pi_s + pc * MAT_ELEMS + lds_at(32 * t + vi, 16 * s + 8 * g));
 #pragma unroll
           for (int nt = 0; nt < 2; ++nt)
             acc[nt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa, *reinterpret_cast<const bf16x8*>(&xop[nt][s]),
@@ -184,10 +188,15 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
       }
     }
 
-    // the next block's vectors, and the other half of S Pi^T, travel while this block is finished
     const int64_t v_mine = blk * 256 + wave * 64 + 32 * g + vi;  // the vector this lane stores for: tile nt = g
-    load_x(blk + gridDim.x);
-    if (PROD) fetch64(a.SPiT + (1 - resident) * 64 * 128, wpre);
+    // the next block's vectors are fetched while this block is finished: one load per step of stage 2
+    const unsigned short* const next_x[2] = {x_row(blk + gridDim.x, 0), x_row(blk + gridDim.x, 1)};
+    if (!PROD) {
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int s = 0; s < 8; ++s) xop[nt][s] = *reinterpret_cast<const u32x4*>(next_x[nt] + 16 * s);
+    }
 
     // ---- the codes of Alg. 1: lane (vi, g) writes the row of vector 32 g + vi ----------------------------
     if (v_mine < a.n) {
@@ -207,16 +216,10 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
     }
 
     if (PROD) {
-      // ---- stage 2: u^T = (S Pi^T) e^T, six piece products, one half of the output coordinates at a time ----
+      // ---- stage 2: u^T = (S Pi^T) e^T, three piece products, one half of the output coordinates at a time ----
       uint32_t sw[2][4];  // [nt][sign word]
 #pragma unroll
       for (int pass = 0; pass < 2; ++pass) {
-        if (pass == 1) {
-          __syncthreads();  // every wavefront is done with the resident half
-          split_to_lds(wpre, W_s, true);
-          resident = 1 - resident;
-          __syncthreads();
-        }
         floatx16 u[2][2];
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
@@ -227,21 +230,23 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
 #pragma unroll
-          for (int pa = 2; pa >= 0; --pa) {  // piece of S Pi^T; smallest products first
+          for (int pa = 1; pa >= 0; --pa) {  // piece of S Pi^T; smallest products first
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt) {
-              const bf16x8 wa = *reinterpret_cast<const bf16x8*>(W_s + (pa * 64 + 32 * mt + vi) * LDJ + 16 * s + 8 * g);
+              const bf16x8 wa = *reinterpret_cast<const bf16x8*>(W_s + pa * MAT_ELEMS +
+                                                                 lds_at(64 * pass + 32 * mt + vi, 16 * s + 8 * g));
 #pragma unroll
-              for (int pb = pa < 2 ? 1 : 0; pb >= 0; --pb)
+              for (int pb = 1 - pa; pb >= 0; --pb)
 #pragma unroll
                 for (int nt = 0; nt < 2; ++nt)
                   u[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, *reinterpret_cast<const bf16x8*>(&rp[pb][nt][s]),
                                                                       u[nt][mt], 0, 0, 0);
             }
           }
+          xop[pass][s] = *reinterpret_cast<const u32x4*>(next_x[pass] + 16 * s);
           __builtin_amdgcn_sched_barrier(0);
         }
-        // signs: register 4 k + r of tile mt is coordinate 64 resident + 32 mt + 8 k + 4 g + r
+        // signs: register 4 k + r of tile mt is coordinate 64 pass + 32 mt + 8 k + 4 g + r
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
@@ -254,9 +259,7 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
               for (int r = 3; r >= 0; --r) nib[k] = shift_in(nib[k], __builtin_amdgcn_ballot_w64(u[nt][mt][4 * k + r] >= 0.f));
             }
             const uint32_t w = (nib[0] | (nib[1] << 8) | (nib[2] << 16) | (nib[3] << 24)) << (4 * g);
-            const uint32_t both = w | (uint32_t)__shfl_xor((int)w, 32);
-            // resident is uniform; written without a runtime register index
-            if (resident == 0) sw[nt][mt] = both; else sw[nt][2 + mt] = both;
+            sw[nt][2 * pass + mt] = w | (uint32_t)__shfl_xor((int)w, 32);
           }
       }
       g2[0] += __shfl_xor(g2[0], 32);
