@@ -6,6 +6,17 @@ namespace tq {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
+// Lane l and lane l ^ 32 exchange a register inside the vector unit (no LDS round trip): the pair
+// (own value, partner's value) in an order that depends on the half-wave; for commutative merges.
+__device__ __forceinline__ uint32_t or_across_halves(uint32_t w) {
+  const auto r = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+  return r[0] | r[1];
+}
+__device__ __forceinline__ float add_across_halves(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // nib = 2 nib + bit as ONE add-with-carry whose carry-in is the compare mask itself (written as a select and a
 // shift-or otherwise)
 __device__ __forceinline__ uint32_t shift_in(uint32_t nib, uint64_t mask) {
@@ -58,7 +69,7 @@ __device__ __forceinline__ float quantise_tile(floatx16& acc, const float inv, c
 #pragma unroll
   for (int pl = 0; pl < B; ++pl) {
     const uint32_t w = (nib[0][pl] | (nib[1][pl] << 8) | (nib[2][pl] << 16) | (nib[3][pl] << 24)) << (4 * h);
-    word[pl] = w | (uint32_t)__shfl_xor((int)w, 32);
+    word[pl] = or_across_halves(w);
   }
   return g2;
 }

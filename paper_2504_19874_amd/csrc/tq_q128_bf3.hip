@@ -29,6 +29,7 @@ namespace {
 constexpr int MAT_ELEMS = 128 * 128;  // one piece of one matrix
 constexpr int PI_ELEMS = 3 * MAT_ELEMS;
 constexpr int W_ELEMS = 2 * MAT_ELEMS;
+constexpr int RING = 4;  // A operands in flight
 
 // element offset of column col (a multiple of 4) of row `row` inside a piece: chunk (col / 8) xor (row % 16)
 __device__ __forceinline__ int lds_at(int row, int col) { return row * 128 + ((((col >> 3) ^ row) & 15) << 3) + (col & 7); }
@@ -129,9 +130,7 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
           s0 = square_pair(xop[nt][s][2], s0);
           s1 = square_pair(xop[nt][s][3], s1);
         }
-        float ss = s0 + s1;
-        ss += __shfl_xor(ss, 32);
-        nu[nt] = sqrtf(ss);
+        nu[nt] = sqrtf(add_across_halves(s0 + s1));
         inv[nt] = nu[nt] > 0.f ? 1.f / nu[nt] : 0.f;
       }
     }
@@ -144,20 +143,25 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
       for (int t = 0; t < 4; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[nt][t][r] = 0.f;
+    {
+      // the A operands travel through a ring of RING registers, read RING MFMA pairs ahead of their use: left to
+      // itself the compiler reuses two registers and every group of MFMAs waits for a full LDS round trip
+      auto pi_piece = [&](int i) {  // read i of 96: step i / 12, pieces 2, 1, 0 (smallest products first), tile i % 4
+        return *reinterpret_cast<const bf16x8*>(Pi_s + (2 - (i >> 2) % 3) * MAT_ELEMS + lds_at(32 * (i & 3) + vi, 16 * (i / 12) + 8 * g));
+      };
+      bf16x8 ring[RING];
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
+      for (int i = 0; i < RING; ++i) ring[i] = pi_piece(i);
 #pragma unroll
-      for (int pc = 2; pc >= 0; --pc) {
+      for (int i = 0; i < 96; ++i) {
+        const int s = i / 12, t = i & 3;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const bf16x8 pa = *reinterpret_cast<const bf16x8*>(Pi_s + pc * MAT_ELEMS + lds_at(32 * t + vi, 16 * s + 8 * g));
-#pragma unroll
-          for (int nt = 0; nt < 2; ++nt)
-            acc[nt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa, *reinterpret_cast<const bf16x8*>(&xop[nt][s]),
-                                                                 acc[nt][t], 0, 0, 0);
-        }
+        for (int nt = 0; nt < 2; ++nt)
+          acc[nt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i % RING], *reinterpret_cast<const bf16x8*>(&xop[nt][s]),
+                                                               acc[nt][t], 0, 0, 0);
+        if (i + RING < 96) ring[i % RING] = pi_piece(i + RING);
+        __builtin_amdgcn_sched_barrier(0);
       }
-      __builtin_amdgcn_sched_barrier(0);
     }
 
     // ---- decision: indices, packing, residual in place; the residual's pieces ---------------------------
@@ -227,24 +231,28 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
           for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) u[nt][mt][r] = 0.f;
+        {
+          auto w_piece = [&](int i) {  // read i of 32: step i / 4, pieces 1, 0, tile i % 2
+            return *reinterpret_cast<const bf16x8*>(W_s + (1 - ((i >> 1) & 1)) * MAT_ELEMS +
+                                                    lds_at(64 * pass + 32 * (i & 1) + vi, 16 * (i >> 2) + 8 * g));
+          };
+          bf16x8 ring[RING];
 #pragma unroll
-        for (int s = 0; s < 8; ++s) {
+          for (int i = 0; i < RING; ++i) ring[i] = w_piece(i);
 #pragma unroll
-          for (int pa = 1; pa >= 0; --pa) {  // piece of S Pi^T; smallest products first
+          for (int i = 0; i < 32; ++i) {
+            const int s = i >> 2, pa = 1 - ((i >> 1) & 1), mt = i & 1;
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
-              const bf16x8 wa = *reinterpret_cast<const bf16x8*>(W_s + pa * MAT_ELEMS +
-                                                                 lds_at(64 * pass + 32 * mt + vi, 16 * s + 8 * g));
+            for (int pb = 1 - pa; pb >= 0; --pb)
 #pragma unroll
-              for (int pb = 1 - pa; pb >= 0; --pb)
-#pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
-                  u[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, *reinterpret_cast<const bf16x8*>(&rp[pb][nt][s]),
-                                                                      u[nt][mt], 0, 0, 0);
-            }
+              for (int nt = 0; nt < 2; ++nt)
+                u[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i % RING], *reinterpret_cast<const bf16x8*>(&rp[pb][nt][s]),
+                                                                    u[nt][mt], 0, 0, 0);
+            if (i + RING < 32) ring[i % RING] = w_piece(i + RING);
+            // the next block's vectors: all sixteen loads during the first pass
+            if (pass == 0 && (i & 1)) xop[(i >> 1) & 1][s] = *reinterpret_cast<const u32x4*>(next_x[(i >> 1) & 1] + 16 * s);
+            __builtin_amdgcn_sched_barrier(0);
           }
-          xop[pass][s] = *reinterpret_cast<const u32x4*>(next_x[pass] + 16 * s);
-          __builtin_amdgcn_sched_barrier(0);
         }
         // signs: register 4 k + r of tile mt is coordinate 64 pass + 32 mt + 8 k + 4 g + r
 #pragma unroll
@@ -259,11 +267,11 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
               for (int r = 3; r >= 0; --r) nib[k] = shift_in(nib[k], __builtin_amdgcn_ballot_w64(u[nt][mt][4 * k + r] >= 0.f));
             }
             const uint32_t w = (nib[0] | (nib[1] << 8) | (nib[2] << 16) | (nib[3] << 24)) << (4 * g);
-            sw[nt][2 * pass + mt] = w | (uint32_t)__shfl_xor((int)w, 32);
+            sw[nt][2 * pass + mt] = or_across_halves(w);
           }
       }
-      g2[0] += __shfl_xor(g2[0], 32);
-      g2[1] += __shfl_xor(g2[1], 32);
+      g2[0] = add_across_halves(g2[0]);
+      g2[1] = add_across_halves(g2[1]);
       if (v_mine < a.n) {
         *reinterpret_cast<u32x4*>(a.qjl + v_mine * 4) =
             g ? u32x4{sw[1][0], sw[1][1], sw[1][2], sw[1][3]} : u32x4{sw[0][0], sw[0][1], sw[0][2], sw[0][3]};
