@@ -27,6 +27,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3
+PEAK_BF16_MFMA_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 
 
@@ -85,6 +86,23 @@ def make_calls(tq, cfg, p, b):
                     b["topk_val"] if cfg.topk else None)
 
     return [("quantize", quantize), ("dequantize", dequantize), ("score", score)]
+
+
+def piece_products(cfg, call: str):
+    """bf16 piece products the library executes per fp32 contraction of `call`, or 0 when the call runs on the
+    fp32 matrix cores.  Mirrors the library's routing (d = 128, one instance): large bf16 batches are quantised
+    with x as one piece against three pieces of Pi, and the residual's two pieces against two of S Pi^T (three
+    products each); DeQuant takes six products for the centroid part (three for a 1-bit table) and three for
+    the sign part."""
+    n, prod = cfg.n * cfg.n_groups, cfg.kind == "prod"
+    if cfg.d != 128 or getattr(cfg, "d_hi", 0):
+        return 0.0
+    if call == "quantize" and cfg.in_dtype == "bf16" and n >= 32768:
+        return 3.0
+    if call == "dequantize" and n > 8192:
+        pi = 0 if cfg.bits_mse == 0 else 3 if cfg.bits_mse == 1 else 6
+        return (pi + (3 if prod else 0)) / ((1 if cfg.bits_mse else 0) + (1 if prod else 0))
+    return 0.0
 
 
 def algorithmic_work(cfg, call: str):
@@ -215,7 +233,17 @@ def main():
     flops, nbytes = algorithmic_work(cfg, dom_name)
     dom_s = per_call_ms[dom] * 1e-3
     mfma_bound = flops / (PEAK_FP32_MFMA_TFLOPS * 1e12) >= nbytes / (PEAK_HBM_GBS * 1e9)
-    if mfma_bound:
+    pieces = piece_products(cfg, dom_name)
+    if mfma_bound and pieces:
+        # the fp32 contraction is executed as `pieces` bf16 products per fp32 product: priced against the bf16
+        # matrix cores on the flops they execute; the fp32-equivalent rate is given beside it
+        ach = flops * pieces / dom_s / 1e12
+        roof = {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / PEAK_BF16_MFMA_TFLOPS, "traffic": None, "dtype": "bf16 pieces of fp32 factors",
+                "piece_products_per_fp32_product": pieces,
+                "fp32_equivalent": {"achieved": flops / dom_s / 1e12, "unit": "TFLOP/s",
+                                    "of_fp32_mfma_peak": flops / dom_s / 1e12 / PEAK_FP32_MFMA_TFLOPS}}
+    elif mfma_bound:
         ach = flops / dom_s / 1e12
         roof = {"bound": "mfma", "achieved": ach, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                 "frac": ach / PEAK_FP32_MFMA_TFLOPS, "traffic": None}
@@ -248,7 +276,9 @@ def main():
         "scores_per_s": float(cfg.nq) * cfg.n / (per_call_ms[2] * 1e-3),
         "roofline": roof,
         # what each call multiplies in; every result meets the fp32 tolerances of the parity tests
-        "arithmetic": {"quantize": "fp32 MFMA (rotation and sketch), fp32 bucket decision",
+        "arithmetic": {"quantize": ("bf16 MFMA on exact pieces: bf16 input x three pieces of Pi (rotation), two pieces of the "
+                                    "residual x two of S Pi^T (signs only); fp32 accumulation and bucket decision")
+                       if piece_products(cfg, "quantize") else "fp32 MFMA (rotation and sketch), fp32 bucket decision",
                        "dequantize": "bf16 MFMA on exact three-piece splits of the fp32 factors, fp32 accumulation",
                        "score": "int8 MFMA on exact base-128 digits of 2^-19-scaled rotated queries, fp32 combination"},
     }

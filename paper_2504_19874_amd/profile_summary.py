@@ -25,7 +25,7 @@ import sys
 
 COPY_KIB = 256 * 1024  # what bench.py --calibration-copy reads and writes
 # kernel name prefix -> entry point whose dominant kernel it is
-ENTRY_OF = (("tq::quant128_kernel", "tq_quantize_prod"), ("tq::dequant128_kernel", "tq_dequantize"),
+ENTRY_OF = (("tq::quant128_kernel", "tq_quantize_prod"), ("tq::(anonymous namespace)::quant128_bf3_kernel", "tq_quantize_prod"), ("tq::dequant128_kernel", "tq_dequantize"),
             ("tq::(anonymous namespace)::dequant128_bf3_kernel", "tq_dequantize"),
             ("tq::(anonymous namespace)::score_bf3_kernel", "tq_score"),
             ("tq::score_i8_128_kernel", "tq_score"), ("tq::score_i8_kernel", "tq_score"),
