@@ -283,7 +283,7 @@ tq_status tq_dequantize(const tq_params* p, const uint32_t* idx, const uint32_t*
                                       kappa_of(p->d_hi), make_codebook_hi(p), static_cast<hipStream_t>(stream)));
   }
   // large batches at d = 128: decoded codes straight into bf16 MFMA operands, pieces of Pi^T / S^T in LDS
-  if (p->d == 128 && n > kBf3DequantRows && dequant128_bf3_applicable(p->bits_mse, prod, make_codebook(p)))
+  if (p->d == 128 && n > kBf3DequantRows && dequant128_bf3_applicable(p->bits_mse, prod, make_codebook(p), x_out, ldo))
     return from_hip(launch_dequant128_bf3(p->bits_mse, prod, idx, qjl, gamma, norm, p->PiT, p->ST, x_out, ldo, n,
                                           kappa_of(128), make_codebook(p), static_cast<hipStream_t>(stream)));
   if (p->d == 128 && p->Pi != nullptr && aligned16(p->Pi) && (!prod || (p->S != nullptr && aligned16(p->S))) &&

@@ -1,23 +1,32 @@
-// DeQuant (Alg. 1 / Alg. 2) at d = 128 for large batches, on the bf16 matrix cores at fp32 accuracy
-// (three exact bf16 pieces per fp32 factor, see tq_bf3.h):
+// DeQuant (Alg. 1 / Alg. 2) at d = 128 for large batches, on the bf16 matrix cores (bf16 pieces of the fp32
+// factors, see tq_bf3.h; fp32 accumulation):
 //     x~_i[k] = nu_i ( sum_j c[idx_ij] Pi[j][k]  +  kappa gamma_i sum_j z_ij S[j][k] ).
 // The VECTOR is the row of the MFMA and the output coordinate the column, so
 //   * the A operand (lane = vector, 8 consecutive j) is exactly what decoding 8 coordinates of one code
 //     yields: a lane decodes its code's bit planes straight into the operand registers, no staging;
 //   * the B operand is a piece of Pi^T / S^T (row k, 8 consecutive j), resident in LDS for the life of the
-//     workgroup.  The three pieces of both matrices take 6 x 32 KB, so a workgroup holds the rows of HALF the
-//     output coordinates (blockIdx.y) and every code is decoded by two workgroups;
-//   * D[vector][k] is stored as 128 contiguous bytes per vector and half-wave.
-// Workgroup = 8 wavefronts; a wavefront takes 32 vectors per round (all of k = 0..127 in 8 steps of 16, two
-// 32-column sub-tiles), workgroups stride over the blocks of 256 vectors.
+//     workgroup;
+//   * D[vector][k]: output tile t holds the columns k = 4 l + t of lane l, so a lane owns 16 contiguous bytes
+//     of its vector's row and a half-wave stores one whole row per instruction.
+// Pieces: a centroid and an entry of Pi^T are taken as their two leading bf16 pieces and the three products
+// of combined weight >= 2^-9 are summed (what is left out is below 3 * 2^-18 per term: about 5e-6 of a
+// coordinate's typical size, against the 1e-4 the output has to meet).  The sign part is folded into the same
+// accumulator: its operand is +-(kappa gamma_i), the two leading pieces of kappa gamma_i with the sign bit of
+// z_ij, against two pieces of S^T, again three products.  A 1-bit table is +-c_1: the pieces of c_1 with a sign.
+// Workgroup = 4 wavefronts, one per SIMD; a wavefront takes 64 vectors per block (every LDS read of a B operand
+// feeds at least two MFMAs), workgroups stride over the blocks of 256 vectors.
 #include "tq_bf3.h"
 
 namespace tq {
 
 namespace {
 
-constexpr int LDJ = 136;  // bf16 per LDS row: 128 values of j + 8 padding (272 bytes: conflict-free 16-byte reads)
-constexpr int MAT_ELEMS = 3 * 64 * LDJ;
+constexpr int MAT_ELEMS = 128 * 128;  // one piece of one matrix
+constexpr int RING = 4;               // B operands in flight
+
+// element offset of column j (a multiple of 4) of row k inside a piece: the 16-byte chunks of a row are
+// rotated by k / 4, so the rows 4 l + t that the lanes l of one read touch fall into different banks
+__device__ __forceinline__ int lds_at(int k, int j) { return k * 128 + ((((j >> 3) ^ (k >> 2)) & 15) << 3) + (j & 7); }
 
 struct Dq128Args {
   const uint32_t* idx;
@@ -34,167 +43,216 @@ struct Dq128Args {
 };
 
 template <int BITS, bool PROD>
-__global__ __launch_bounds__(512) void dequant128_bf3_kernel(const Dq128Args a) {
-  constexpr int PC = BITS == 0 ? 0 : BITS == 1 ? 1 : 3;  // pieces of a decoded centroid (1 bit: +-c_1, c_1 applied at the end)
+__global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) {
+  constexpr bool TABLE = BITS >= 2;  // centroid pieces looked up in LDS (1 bit: the pieces of c_1 with a sign)
   constexpr int NB = BITS > 0 ? BITS : 1;
   constexpr int MATS = (BITS > 0 ? 1 : 0) + (PROD ? 1 : 0);
-  extern __shared__ __attribute__((aligned(16))) unsigned short lds_s[];  // [matrix][piece][k 64][LDJ], then the table
-  uint2* const table_s = reinterpret_cast<uint2*>(lds_s + MATS * MAT_ELEMS);
+  constexpr int READS = 4 * 2 * MATS;  // B operands per step: 4 tiles x 2 pieces x matrices
+  extern __shared__ __attribute__((aligned(16))) unsigned short lds_s[];  // [matrix][piece][k][128], then the table
+  uint32_t* const table_s = reinterpret_cast<uint32_t*>(lds_s + MATS * 2 * MAT_ELEMS);
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int half = blockIdx.y;  // output coordinates [64 half, 64 half + 64)
 
-  // ---- the rows of Pi^T (and S^T) of this half, split into pieces ---------------------------------
+  // ---- Pi^T (and S^T), two leading pieces each -----------------------------------------------------
   {
     int m = 0;
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
       if (s == 0 ? BITS == 0 : !PROD) continue;
-      const float* W = (s == 0 ? a.PiT : a.ST) + (int64_t)(64 * half) * 128;
+      const float* W = s == 0 ? a.PiT : a.ST;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int e = (i * 512 + tid) * 4;  // element of the 64 x 128 block
-        const int k = e >> 7, j = e & 127;
-        const f32x4 v = *reinterpret_cast<const f32x4*>(W + e);
-        uint32_t lo[3], hi[3];
-        split3_pair(f32x2{v[0], v[1]}, lo[0], lo[1], lo[2]);
-        split3_pair(f32x2{v[2], v[3]}, hi[0], hi[1], hi[2]);
+      for (int half = 0; half < 2; ++half) {
+        f32x4 v[8];
 #pragma unroll
-        for (int pc = 0; pc < 3; ++pc)
-          *reinterpret_cast<uint2*>(lds_s + m * MAT_ELEMS + (pc * 64 + k) * LDJ + j) = make_uint2(lo[pc], hi[pc]);
+        for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const f32x4*>(W + half * 8192 + (i * 256 + tid) * 4);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int e = half * 8192 + (i * 256 + tid) * 4;
+          const int k = e >> 7, j = e & 127;
+          uint32_t lo[2], hi[2];
+          split2_pair(f32x2{v[i][0], v[i][1]}, lo[0], lo[1]);
+          split2_pair(f32x2{v[i][2], v[i][3]}, hi[0], hi[1]);
+#pragma unroll
+          for (int pc = 0; pc < 2; ++pc)
+            *reinterpret_cast<uint2*>(lds_s + (m * 2 + pc) * MAT_ELEMS + lds_at(k, j)) = make_uint2(lo[pc], hi[pc]);
+        }
       }
       ++m;
     }
-    if (PC == 3 && tid < 16) {
+    if (TABLE && tid < 16) {
       uint32_t p1, p2, p3;
       split3(a.cb.c[tid], p1, p2, p3);
-      table_s[tid] = make_uint2(p1 | (p2 << 16), p3);
+      table_s[tid] = p1 | (p2 << 16);
     }
   }
   __syncthreads();
 
-  const int vi = lane & 31, jg = lane >> 5;  // A: vector within the round, which 8 of the 16 values of j
-  const float c1 = BITS == 1 ? a.cb.c[1] : 1.f;
+  const int vi = lane & 31, jg = lane >> 5;  // A: vector within the tile, which 8 of the 16 values of j
+  uint32_t c1p[2] = {0u, 0u};  // 1 bit: the two pieces of c_1, each twice in a word
+  if (BITS == 1) {
+    uint32_t p1, p2, p3;
+    split3(a.cb.c[1], p1, p2, p3);
+    c1p[0] = p1 * 0x00010001u;
+    c1p[1] = p2 * 0x00010001u;
+  }
   const int64_t blocks = (a.n + 255) / 256;
 
-  uint32_t w[4][NB], z[4], wn[4][NB], zn[4];
-  float nu = 0.f, kg = 0.f, nun = 0.f, kgn = 0.f;
+  uint32_t w[2][4][NB], z[2][4], wn[2][4][NB], zn[2][4];
+  float nu[2], kg[2], nun[2], kgn[2];
   auto load_code = [&](int64_t blk) {  // into the "next" registers
-    const int64_t v = blk * 256 + wave * 32 + vi;
-    const int64_t row = v < a.n ? v : a.n - 1;  // clamped: such rows are not stored
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
+    for (int mt = 0; mt < 2; ++mt) {
+      const int64_t v = blk * 256 + wave * 64 + 32 * mt + vi;
+      const int64_t row = v < a.n ? v : a.n - 1;  // clamped: such rows are not stored
 #pragma unroll
-      for (int pl = 0; pl < BITS; ++pl) wn[g][pl] = a.idx[row * (4 * BITS) + g * BITS + pl];
-      zn[g] = PROD ? a.qjl[row * 4 + g] : 0u;
+      for (int g = 0; g < 4; ++g) {
+#pragma unroll
+        for (int pl = 0; pl < BITS; ++pl) wn[mt][g][pl] = a.idx[row * (4 * BITS) + g * BITS + pl];
+        zn[mt][g] = PROD ? a.qjl[row * 4 + g] : 0u;
+      }
+      nun[mt] = a.norm != nullptr ? a.norm[row] : 1.f;
+      kgn[mt] = PROD ? a.kappa * a.gamma[row] : 0.f;
     }
-    nun = a.norm != nullptr ? a.norm[row] : 1.f;
-    kgn = PROD ? a.kappa * a.gamma[row] : 0.f;
+  };
+
+  // B operand r of a step: tile r % 4 (columns k = 4 l + tile), then piece 1 before piece 0 of Pi^T, then of S^T
+  auto b_piece = [&](int s, int r) {
+    const int ct = r & 3, q = r >> 2;  // q: (matrix, piece) in the order (0, 1), (0, 0), (1, 1), (1, 0)
+    const int m = q >> 1, pc = 1 - (q & 1);
+    return *reinterpret_cast<const bf16x8*>(lds_s + (m * 2 + pc) * MAT_ELEMS + lds_at(4 * vi + ct, 16 * s + 8 * jg));
   };
 
   load_code(blockIdx.x);
   for (int64_t blk = blockIdx.x; blk < blocks; blk += gridDim.x) {
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
+    for (int mt = 0; mt < 2; ++mt) {
 #pragma unroll
-      for (int pl = 0; pl < BITS; ++pl) w[g][pl] = wn[g][pl];
-      z[g] = zn[g];
-    }
-    nu = nun;
-    kg = kgn;
-    load_code(blk + gridDim.x);  // the next round's code travels during this round (clamped past the end)
-    floatx16 acc1[2], acc2[2];
+      for (int g = 0; g < 4; ++g) {
 #pragma unroll
-    for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        acc1[ct][r] = 0.f;
-        acc2[ct][r] = 0.f;
+        for (int pl = 0; pl < BITS; ++pl) w[mt][g][pl] = wn[mt][g][pl];
+        z[mt][g] = zn[mt][g];
       }
+      nu[mt] = nun[mt];
+      kg[mt] = kgn[mt];
+    }
+    load_code(blk + gridDim.x);  // the next block's codes travel during this block (clamped past the end)
+    floatx16 acc[2][4];  // [vector tile][column tile]
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      const int g = s >> 1, off = (s & 1) * 16 + 8 * jg;  // word of the code, first bit
-      const int j0 = 16 * s + 8 * jg;
-      // ---- A operands: this lane's 8 coordinates decoded into pieces --------------------------------
-      bf16x8 ca[PC > 0 ? PC : 1], za;
-      if (PC == 1) {
-        u32x4 v;
+    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-          v[e] = 0xBF80BF80u ^ (((w[g][0] >> (off + 2 * e)) & 1u) << 15) ^ (((w[g][0] >> (off + 2 * e + 1)) & 1u) << 31);
-        ca[0] = *reinterpret_cast<const bf16x8*>(&v);
-      } else if (PC == 3) {
+      for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[mt][ct][r] = 0.f;
+    uint32_t kgp[2][2];  // the two pieces of kappa gamma of this lane's vectors, each twice in a word
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+      uint32_t p1, p2, p3;
+      split3(kg[mt], p1, p2, p3);
+      kgp[mt][0] = p1 * 0x00010001u;
+      kgp[mt][1] = p2 * 0x00010001u;
+    }
+    bf16x8 ring[RING];
+#pragma unroll
+    for (int r = 0; r < RING; ++r) ring[r] = b_piece(0, r);
+    // table entries of the coordinates of one step, looked up one step ahead: they travel during the MFMAs
+    uint32_t te[2][8];
+    auto look_up = [&](int s) {
+      const int g = s >> 1, off = (s & 1) * 16 + 8 * jg;
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt) {
         uint32_t lv[2] = {0u, 0u};  // bucket numbers of 4 coordinates, one per byte
 #pragma unroll
         for (int h = 0; h < 2; ++h)
 #pragma unroll
           for (int pl = 0; pl < BITS; ++pl)
-            lv[h] |= ((((w[g][pl] >> (off + 4 * h)) & 0xFu) * 0x00204081u) & 0x01010101u) << pl;
-        uint2 e[8];
+            lv[h] |= ((((w[mt][g][pl] >> (off + 4 * h)) & 0xFu) * 0x00204081u) & 0x01010101u) << pl;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) e[u] = table_s[(lv[u >> 2] >> (8 * (u & 3))) & 0xFFu];
-        u32x4 v1, v2, v3;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          v1[u] = __builtin_amdgcn_perm(e[2 * u + 1].x, e[2 * u].x, 0x05040100u);
-          v2[u] = __builtin_amdgcn_perm(e[2 * u + 1].x, e[2 * u].x, 0x07060302u);
-          v3[u] = __builtin_amdgcn_perm(e[2 * u + 1].y, e[2 * u].y, 0x05040100u);
-        }
-        ca[0] = *reinterpret_cast<const bf16x8*>(&v1);
-        ca[PC >= 3 ? 1 : 0] = *reinterpret_cast<const bf16x8*>(&v2);
-        ca[PC >= 3 ? 2 : 0] = *reinterpret_cast<const bf16x8*>(&v3);
+        for (int u = 0; u < 8; ++u) te[mt][u] = table_s[(lv[u >> 2] >> (8 * (u & 3))) & 0xFFu];
       }
-      if (PROD) {
-        u32x4 v;
+    };
+    if (TABLE) look_up(0);
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-          v[e] = 0xBF80BF80u ^ (((z[g] >> (off + 2 * e)) & 1u) << 15) ^ (((z[g] >> (off + 2 * e + 1)) & 1u) << 31);
-        za = *reinterpret_cast<const bf16x8*>(&v);
-      }
-      // ---- B operands from LDS, MFMAs -------------------------------------------------------------
+    for (int s = 0; s < 8; ++s) {
+      const int g = s >> 1, off = (s & 1) * 16 + 8 * jg;  // word of the code, first bit
+      // ---- A operands: this lane's 8 coordinates of two vectors decoded into pieces ----------------------
+      bf16x8 ca[2][2], za[2][2];
 #pragma unroll
-      for (int ct = 0; ct < 2; ++ct) {
-        const unsigned short* const brow = lds_s + (32 * ct + vi) * LDJ + j0;  // row k = 32 ct + lane % 32 of a piece
-        int m = 0;
-        if (BITS > 0) {
-          bf16x8 pb[3];
+      for (int mt = 0; mt < 2; ++mt) {
+        if (BITS == 1) {
+          u32x4 v1, v2;
 #pragma unroll
-          for (int pc = 0; pc < 3; ++pc) pb[pc] = *reinterpret_cast<const bf16x8*>(brow + m * MAT_ELEMS + pc * 64 * LDJ);
-          if (PC == 1) {
-#pragma unroll
-            for (int pc = 2; pc >= 0; --pc) acc1[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ca[0], pb[pc], acc1[ct], 0, 0, 0);
-          } else {
-            constexpr int TA[6] = {2, 1, 0, 1, 0, 0};  // centroid piece; smallest products first
-            constexpr int TB[6] = {0, 1, 2, 0, 1, 0};  // matrix piece
-#pragma unroll
-            for (int t = 0; t < 6; ++t)
-              acc1[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ca[PC >= 3 ? TA[t] : 0], pb[TB[t]], acc1[ct], 0, 0, 0);
+          for (int e = 0; e < 4; ++e) {  // bit 1 = +c_1: the sign bit is set where the code bit is 0
+            const uint32_t sg = ((((w[mt][g][0] >> (off + 2 * e)) & 1u) << 15) | (((w[mt][g][0] >> (off + 2 * e + 1)) & 1u) << 31)) ^ 0x80008000u;
+            v1[e] = c1p[0] ^ sg;
+            v2[e] = c1p[1] ^ sg;
           }
-          ++m;
+          ca[mt][0] = *reinterpret_cast<const bf16x8*>(&v1);
+          ca[mt][1] = *reinterpret_cast<const bf16x8*>(&v2);
+        } else if (TABLE) {
+          u32x4 v1, v2;
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            v1[u] = __builtin_amdgcn_perm(te[mt][2 * u + 1], te[mt][2 * u], 0x05040100u);
+            v2[u] = __builtin_amdgcn_perm(te[mt][2 * u + 1], te[mt][2 * u], 0x07060302u);
+          }
+          ca[mt][0] = *reinterpret_cast<const bf16x8*>(&v1);
+          ca[mt][1] = *reinterpret_cast<const bf16x8*>(&v2);
         }
         if (PROD) {
+          u32x4 v1, v2;
 #pragma unroll
-          for (int pc = 2; pc >= 0; --pc) {
-            const bf16x8 pb = *reinterpret_cast<const bf16x8*>(brow + m * MAT_ELEMS + pc * 64 * LDJ);
-            acc2[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(za, pb, acc2[ct], 0, 0, 0);
+          for (int e = 0; e < 4; ++e) {  // bit 1 = +1
+            const uint32_t sg = ((((z[mt][g] >> (off + 2 * e)) & 1u) << 15) | (((z[mt][g] >> (off + 2 * e + 1)) & 1u) << 31)) ^ 0x80008000u;
+            v1[e] = kgp[mt][0] ^ sg;
+            v2[e] = kgp[mt][1] ^ sg;
           }
+          za[mt][0] = *reinterpret_cast<const bf16x8*>(&v1);
+          za[mt][1] = *reinterpret_cast<const bf16x8*>(&v2);
         }
       }
-      // keep the steps apart: hoisting every step's operand reads to the top costs more registers than there are
       __builtin_amdgcn_sched_barrier(0);
+      if (TABLE && s + 1 < 8) look_up(s + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      // ---- B operands through the ring, MFMAs ----------------------------------------------------------
+#pragma unroll
+      for (int r = 0; r < READS; ++r) {
+        const int ct = r & 3, q = r >> 2;
+        const bool sign_part = BITS == 0 || q >= 2;  // which matrix this operand belongs to
+        const int pc = 1 - (q & 1);
+        const bf16x8 b = ring[(s * READS + r) % RING];
+        // piece pc of the matrix meets the pieces a of the decoded operand with a + pc <= 1; the two MFMAs on
+        // one accumulator are kept apart by the other vector tile's
+        if (pc == 0) {
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt)
+            acc[mt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sign_part ? za[mt][1] : ca[mt][1], b, acc[mt][ct], 0, 0, 0);
+        }
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+          acc[mt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sign_part ? za[mt][0] : ca[mt][0], b, acc[mt][ct], 0, 0, 0);
+        const int nxt = s * READS + r + RING;  // the read that takes this slot
+        if (nxt < 8 * READS) ring[nxt % RING] = b_piece(nxt / READS, nxt % READS);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
     // ---- epilogue: D[vector][k]; the factors of a row's vector sit in the lane with that number --------
-    const int64_t v0 = blk * 256 + wave * 32;
+    const int64_t v0 = blk * 256 + wave * 64;
+    const bool full = v0 + 64 <= a.n;  // uniform: no vector of this wavefront is past the end
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int row = 8 * (r >> 2) + (r & 3) + 4 * (lane >> 5);
-      const float rnu = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * row, __float_as_int(nu)));
-      const float rkg = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * row, __float_as_int(kg)));
-      if (v0 + row < a.n) {
-        float* o = a.out + (v0 + row) * a.ldo + 64 * half + vi;
+    for (int mt = 0; mt < 2; ++mt) {
+      // every row's norm first (one LDS round trip for all of them), then the arithmetic and the stores
+      float rnu[16];
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct) o[32 * ct] = rnu * fmaf(rkg, acc2[ct][r], c1 * acc1[ct][r]);
+      for (int r = 0; r < 16; ++r)
+        rnu[r] = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (8 * (r >> 2) + (r & 3) + 4 * (lane >> 5)), __float_as_int(nu[mt])));
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t v = v0 + 32 * mt + 8 * (r >> 2) + (r & 3) + 4 * (lane >> 5);
+        f32x4 o;
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) o[ct] = rnu[r] * acc[mt][ct][r];
+        if (full || v < a.n) *reinterpret_cast<f32x4*>(a.out + v * a.ldo + 4 * vi) = o;
       }
     }
   }
@@ -203,7 +261,7 @@ __global__ __launch_bounds__(512) void dequant128_bf3_kernel(const Dq128Args a) 
 template <int BITS, bool PROD>
 hipError_t launch_one(const Dq128Args& a, hipStream_t s) {
   constexpr int MATS = (BITS > 0 ? 1 : 0) + (PROD ? 1 : 0);
-  constexpr int lds = MATS * MAT_ELEMS * 2 + 16 * 8;
+  constexpr int lds = MATS * 2 * MAT_ELEMS * 2 + 16 * 4;
   static bool attr_done = false;  // per instantiation: the limit has to be raised once
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dequant128_bf3_kernel<BITS, PROD>),
@@ -212,16 +270,16 @@ hipError_t launch_one(const Dq128Args& a, hipStream_t s) {
     attr_done = true;
   }
   const int64_t blocks = (a.n + 255) / 256;
-  const dim3 grid((unsigned)(blocks < 128 ? blocks : 128), 2);  // one workgroup per compute unit
-  hipLaunchKernelGGL((dequant128_bf3_kernel<BITS, PROD>), grid, dim3(512), lds, s, a);
+  hipLaunchKernelGGL((dequant128_bf3_kernel<BITS, PROD>), dim3((unsigned)(blocks < 256 ? blocks : 256)), dim3(256), lds, s, a);
   return hipGetLastError();
 }
 
 }  // namespace
 
-// d = 128, one instance; a 1-bit table must be +-c
-bool dequant128_bf3_applicable(int bits, bool prod, const Codebook& cb) {
+// d = 128, one instance; a 1-bit table must be +-c; rows of the output 16-byte aligned
+bool dequant128_bf3_applicable(int bits, bool prod, const Codebook& cb, const float* out, int64_t ldo) {
   if (bits < 0 || bits > 4 || (bits == 0 && !prod)) return false;
+  if ((reinterpret_cast<uintptr_t>(out) & 15u) != 0 || ldo % 4 != 0) return false;
   return bits != 1 || cb.c[0] == -cb.c[1];
 }
 
