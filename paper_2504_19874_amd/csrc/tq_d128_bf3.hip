@@ -252,7 +252,7 @@ __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) 
         f32x4 o;
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct) o[ct] = rnu[r] * acc[mt][ct][r];
-        if (full || v < a.n) *reinterpret_cast<f32x4*>(a.out + v * a.ldo + 4 * vi) = o;
+        if (full || v < a.n) __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(a.out + v * a.ldo + 4 * vi));
       }
     }
   }
