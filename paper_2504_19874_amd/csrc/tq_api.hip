@@ -2,6 +2,7 @@
 // No allocation, no synchronisation; everything is enqueued on the caller's
 // stream.
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 
 #include "tq_attend.h"
@@ -58,6 +59,12 @@ Codebook make_codebook(const tq_params* p) {
 
 float kappa_of(int d) { return (float)(std::sqrt(1.5707963267948966) / (double)d); }
 
+// TQ_FP32_MFMA=1 in the environment keeps every contraction on the fp32 matrix cores (read at each call)
+bool fp32_mfma_only() {
+  const char* v = std::getenv("TQ_FP32_MFMA");
+  return v != nullptr && v[0] == '1';
+}
+
 tq_status from_hip(hipError_t e) { return e == hipSuccess ? TQ_OK : TQ_ERR_HIP; }
 
 struct Workspace {
@@ -111,7 +118,7 @@ tq_status quantize_common(const tq_params* p, const void* x, tq_dtype dtype, int
   }
 
   // head dimension 128, a large batch of bf16 vectors: the contractions on the bf16 matrix cores
-  if (d == 128 && dtype == TQ_BF16 && n >= kBf3QuantRows && quant128_bf3_applicable(p->bits_mse, prod, x, ldx) &&
+  if (d == 128 && dtype == TQ_BF16 && n >= kBf3QuantRows && !fp32_mfma_only() && quant128_bf3_applicable(p->bits_mse, prod, x, ldx) &&
       (p->bits_mse == 0 || aligned16(idx)) && (!prod || aligned16(qjl)))
     return from_hip(launch_quant128_bf3(p->bits_mse, prod, x, ldx, n, p->Pi, prod ? p->SPiT : nullptr, idx, qjl, gamma,
                                         norm, make_codebook(p), stream));
@@ -283,7 +290,7 @@ tq_status tq_dequantize(const tq_params* p, const uint32_t* idx, const uint32_t*
                                       kappa_of(p->d_hi), make_codebook_hi(p), static_cast<hipStream_t>(stream)));
   }
   // large batches at d = 128: decoded codes straight into bf16 MFMA operands, pieces of Pi^T / S^T in LDS
-  if (p->d == 128 && n > kBf3DequantRows && dequant128_bf3_applicable(p->bits_mse, prod, make_codebook(p), x_out, ldo))
+  if (p->d == 128 && n > kBf3DequantRows && !fp32_mfma_only() && dequant128_bf3_applicable(p->bits_mse, prod, make_codebook(p), x_out, ldo))
     return from_hip(launch_dequant128_bf3(p->bits_mse, prod, idx, qjl, gamma, norm, p->PiT, p->ST, x_out, ldo, n,
                                           kappa_of(128), make_codebook(p), static_cast<hipStream_t>(stream)));
   if (p->d == 128 && p->Pi != nullptr && aligned16(p->Pi) && (!prod || (p->S != nullptr && aligned16(p->S))) &&
@@ -294,7 +301,7 @@ tq_status tq_dequantize(const tq_params* p, const uint32_t* idx, const uint32_t*
   }
   // x~_i[k] = <e_k, DeQuant(code i)>: the scoring contraction with the rows of Pi^T (and S^T) as the queries,
   // stored one row per code; on the bf16 matrix cores where that kernel takes the codes
-  if (score_bf3_applicable(p->bits_mse, prod, p->d, n, 1, p->d, make_codebook(p)))
+  if (!fp32_mfma_only() && score_bf3_applicable(p->bits_mse, prod, p->d, n, 1, p->d, make_codebook(p)))
     return from_hip(launch_score_bf3(p->bits_mse, prod, p->PiT, p->ST, p->d, p->d, idx, qjl, gamma, norm, n, 1, x_out, ldo,
                                      true, kappa_of(p->d), make_codebook(p), static_cast<hipStream_t>(stream)));
   GemmArgs a;
@@ -423,7 +430,7 @@ tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_gr
     if (launch_score_small(p->bits_mse, prod, qr, qs, idx, qjl, gamma, norm, scores, ld_scores, n_per_group,
                            d, n_groups, q_per_group, kappa_of(d), make_codebook(p), s) != hipSuccess)
       return TQ_ERR_HIP;
-  } else if (n_per_group > 0 && score_bf3_applicable(p->bits_mse, prod, d, n_per_group, n_groups, q_per_group, make_codebook(p))) {
+  } else if (n_per_group > 0 && !fp32_mfma_only() && score_bf3_applicable(p->bits_mse, prod, d, n_per_group, n_groups, q_per_group, make_codebook(p))) {
     // many queries per code: dense contraction on the bf16 matrix cores, every fp32 factor as three bf16 pieces
     if (launch_score_bf3(p->bits_mse, prod, qr, qs, q_per_group, d, idx, qjl, gamma, norm, n_per_group, n_groups, scores,
                          ld_scores, false, kappa_of(d), make_codebook(p), s) != hipSuccess)

@@ -197,6 +197,29 @@ def test_quantize_prod(d, bits_mse, n, kind):
     _check_prod(p, Pi, S, c32, t32, x_or, normalise, *out)
 
 
+def test_both_arithmetic_paths_of_large_bf16_batches(monkeypatch):
+    """Large bf16 batches at d = 128 run on the bf16 matrix cores (exact pieces); TQ_FP32_MFMA=1 keeps them on the
+    fp32 matrix instructions.  Both must meet the oracle, and they must agree with each other on nearly every
+    index and sign."""
+    d, bits_mse, n = 128, 2, 34000
+    p, Pi, S, c32, t32 = setup(d, bits_mse, True)
+    x_or, x_dev, normalise = _quant_inputs(n, d, "bf16", 77)
+    pieces = _run_prod(p, x_dev, n, normalise)
+    _check_prod(p, Pi, S, c32, t32, x_or, normalise, *pieces)
+    monkeypatch.setenv("TQ_FP32_MFMA", "1")
+    plain = _run_prod(p, x_dev, n, normalise)
+    _check_prod(p, Pi, S, c32, t32, x_or, normalise, *plain)
+    same_idx = (words(pieces[0]) == words(plain[0])).mean()
+    same_qjl = (words(pieces[1]) == words(plain[1])).mean()
+    assert same_idx >= 0.9999 and same_qjl >= 0.999, (same_idx, same_qjl)
+    xt = [torch.zeros((n, d), dtype=torch.float32, device=DEV) for _ in range(2)]
+    tq.tq_dequantize(p, *plain, xt[0])
+    monkeypatch.delenv("TQ_FP32_MFMA")
+    tq.tq_dequantize(p, *plain, xt[1])
+    nu = plain[3].cpu().numpy().astype(np.float64)
+    P.check_close(xt[1].cpu().numpy(), xt[0].cpu().numpy().astype(np.float64), nu[:, None] / np.sqrt(d), "dequantize, pieces vs fp32")
+
+
 def test_quantize_is_deterministic_and_respects_row_stride():
     d, n = 128, 1000
     p, Pi, S, c32, t32 = setup(d, 2, True)
