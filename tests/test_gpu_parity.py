@@ -220,6 +220,31 @@ def test_both_arithmetic_paths_of_large_bf16_batches(monkeypatch):
     P.check_close(xt[1].cpu().numpy(), xt[0].cpu().numpy().astype(np.float64), nu[:, None] / np.sqrt(d), "dequantize, pieces vs fp32")
 
 
+def test_large_batches_respect_row_strides_and_leave_the_tail_alone():
+    """The large-batch kernels at d = 128 with padded input and output rows, a batch that ends inside a block of
+    256, and guard rows behind every output that must stay untouched."""
+    d, bits_mse, n, pad = 128, 2, 32768 + 300, 5
+    p, Pi, S, c32, t32 = setup(d, bits_mse, True)
+    x_or, x_dev, normalise = _quant_inputs(n, d, "bf16", 78)
+    dense = _run_prod(p, x_dev, n, normalise)
+    wide = torch.full((n, d + 64), 7.0, dtype=torch.bfloat16, device=DEV)
+    wide[:, :d] = x_dev
+    idx = torch.full((n + pad, p.idx_words), -1, dtype=torch.int32, device=DEV)
+    qjl = torch.full((n + pad, p.qjl_words), -1, dtype=torch.int32, device=DEV)
+    gamma = torch.full((n + pad,), -2.0, dtype=torch.float32, device=DEV)
+    norm = torch.full((n + pad,), -2.0, dtype=torch.float32, device=DEV)
+    tq.tq_quantize_prod(p, wide[:, :d], idx[:n], qjl[:n], gamma[:n], norm[:n])
+    for got, want, fill in ((idx, dense[0], -1), (qjl, dense[1], -1), (gamma, dense[2], -2.0), (norm, dense[3], -2.0)):
+        assert torch.equal(got[:n], want), "padded input rows change the codes"
+        assert bool((got[n:] == fill).all()), "rows past the batch were written"
+    out = torch.full((n + pad, d + 32), -3.0, dtype=torch.float32, device=DEV)
+    ref = torch.zeros((n, d), dtype=torch.float32, device=DEV)
+    tq.tq_dequantize(p, *dense, ref)
+    tq.tq_dequantize(p, *dense, out[:n, :d])
+    assert torch.equal(out[:n, :d], ref), "padded output rows change the values"
+    assert bool((out[:n, d:] == -3.0).all()) and bool((out[n:] == -3.0).all()), "bytes outside the rows were written"
+
+
 def test_quantize_is_deterministic_and_respects_row_stride():
     d, n = 128, 1000
     p, Pi, S, c32, t32 = setup(d, 2, True)
