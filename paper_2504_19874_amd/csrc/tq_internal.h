@@ -90,7 +90,7 @@ constexpr int64_t kBf3QuantRows = 32768;  // bf16 input: from here on the bf16-p
 bool quant128_bf3_applicable(int bits, bool prod, const void* X, int64_t ldx);
 hipError_t launch_quant128_bf3(int bits, bool prod, const void* X, int64_t ldx, int64_t n, const float* Pi,
                                const float* SPiT, uint32_t* idx, uint32_t* qjl, float* gamma, float* norm,
-                               const Codebook& cb, hipStream_t s);
+                               const Codebook& cb, int gs_hi, const Codebook& cb_hi, hipStream_t s);
 hipError_t launch_dequant128_bf3(int bits, bool prod, const uint32_t* idx, const uint32_t* qjl, const float* gamma,
                                  const float* norm, const float* PiT, const float* ST, float* out, int64_t ldo, int64_t n,
                                  float kappa, const Codebook& cb, hipStream_t s);

@@ -45,6 +45,11 @@ struct Q128Args {
   float* gamma;
   float* norm;  // nullable: no normalisation then
   Codebook cb;
+  // two instances over a split of the rotated coordinates (MIXED, Sec. 4.3): coordinate groups (= output tiles)
+  // [0, gs_hi) are quantised with BITS + 1 bits and cb_hi, each instance normalised by the norm of its own rotated
+  // coordinates; idx rows then hold 4 BITS + gs_hi words, gamma and norm two floats per vector (hi, lo)
+  int gs_hi;
+  Codebook cb_hi;
 };
 
 // sum of the squares of two bf16 values (exact products, fp32 sum) added to acc
@@ -53,9 +58,10 @@ __device__ __forceinline__ float square_pair(uint32_t w, float acc) {
   return fmaf(hi, hi, fmaf(lo, lo, acc));
 }
 
-template <int BITS, bool PROD>
+template <int BITS, bool PROD, bool MIXED>
 __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
-  constexpr int NB = BITS > 0 ? BITS : 1;
+  constexpr int NB = (BITS > 0 ? BITS : 1) + (MIXED ? 1 : 0);  // plane words per tile, at most
+  constexpr int BH = BITS < 4 ? BITS + 1 : 4;                  // bits of instance hi
   extern __shared__ __attribute__((aligned(16))) unsigned short lds_s[];
   unsigned short* const Pi_s = lds_s;            // [piece][row j][128], see lds_at
   unsigned short* const W_s = lds_s + PI_ELEMS;  // [piece][row j'][128], columns permuted
@@ -103,7 +109,7 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
   __syncthreads();
 
   const int64_t blocks = (a.n + 255) / 256;
-  const bool normalise = a.norm != nullptr;
+  const bool normalise = !MIXED && a.norm != nullptr;
   u32x4 xop[2][8];
   auto x_row = [&](int64_t blk, int nt) {  // this lane's 8 values of step 0
     const int64_t v = blk * 256 + wave * 64 + 32 * nt + vi;
@@ -167,16 +173,40 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
     // ---- decision: indices, packing, residual in place; the residual's pieces ---------------------------
     // register 4 k + r of tile t holds coordinate j = 32 t + 8 k + 4 g + r of the lane's vector
     uint32_t word[2][4][NB];
-    float g2[2] = {0.f, 0.f};
+    float g2[2] = {0.f, 0.f}, g2h[2] = {0.f, 0.f}, nuh[2] = {0.f, 0.f};  // MIXED: g2 / nu belong to instance lo
     u32x4 rp[2][2][8];  // [piece][nt][step of stage 2]
+    const int gs = MIXED ? a.gs_hi : 0;
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
+      float inv_hi = 0.f;
+      if (MIXED) {
+        // the norms of the two instances from the rotated coordinates (the rotation is block diagonal)
+        float s_hi = 0.f, s_lo = 0.f;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+          for (int r = 0; r < 16; r += 2) {
+            s0 = fmaf(acc[nt][t][r], acc[nt][t][r], s0);
+            s1 = fmaf(acc[nt][t][r + 1], acc[nt][t][r + 1], s1);
+          }
+          s_hi += t < gs ? s0 + s1 : 0.f;
+          s_lo += t < gs ? 0.f : s0 + s1;
+        }
+        nuh[nt] = sqrtf(add_across_halves(s_hi));
+        nu[nt] = sqrtf(add_across_halves(s_lo));
+        inv_hi = nuh[nt] > 0.f ? 1.f / nuh[nt] : 0.f;
+        inv[nt] = nu[nt] > 0.f ? 1.f / nu[nt] : 0.f;
+      }
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
         uint32_t wd[4] = {0u, 0u, 0u, 0u};
-        g2[nt] += quantise_tile<BITS>(acc[nt][t], inv[nt], a.cb, g, wd);
+        if (MIXED && t < gs)  // uniform
+          g2h[nt] += quantise_tile<BH>(acc[nt][t], inv_hi, a.cb_hi, g, wd);
+        else
+          g2[nt] += quantise_tile<BITS>(acc[nt][t], inv[nt], a.cb, g, wd);
 #pragma unroll
-        for (int pl = 0; pl < BITS; ++pl) word[nt][t][pl] = wd[pl];
+        for (int pl = 0; pl < NB; ++pl) word[nt][t][pl] = wd[pl];
         if (PROD) {
 #pragma unroll
           for (int p = 0; p < 2; ++p)
@@ -203,20 +233,34 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
     }
 
     // ---- the codes of Alg. 1: lane (vi, g) writes the row of vector 32 g + vi ----------------------------
+    const uint32_t mine = 0u - (uint32_t)g;  // all ones in the half-wave that stores tile nt = 1
     if (v_mine < a.n) {
-      if (BITS > 0) {
-        uint32_t* dst = a.idx + v_mine * (4 * BITS);
-        uint32_t row[4 * NB];
+      // word[g][t][pl], selected with a mask (an indexed array would live in scratch memory)
+      if (MIXED) {
+        uint32_t* dst = a.idx + v_mine * (4 * BITS + gs);
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
+        for (int t = 0; t < 4; ++t) {
+          const bool thi = t < gs;
 #pragma unroll
-          for (int pl = 0; pl < BITS; ++pl)  // word[g][t][pl], selected with a mask (an indexed array would live in scratch memory)
-            row[t * BITS + pl] = word[0][t][pl] ^ ((word[0][t][pl] ^ word[1][t][pl]) & (0u - (uint32_t)g));
+          for (int pl = 0; pl < BITS + 1; ++pl)
+            if (pl < BITS || thi) dst[pl] = word[0][t][pl] ^ ((word[0][t][pl] ^ word[1][t][pl]) & mine);
+          dst += thi ? BITS + 1 : BITS;
+        }
+        *reinterpret_cast<float2*>(a.norm + 2 * v_mine) = make_float2(g ? nuh[1] : nuh[0], g ? nu[1] : nu[0]);
+      } else {
+        if (BITS > 0) {
+          uint32_t* dst = a.idx + v_mine * (4 * BITS);
+          uint32_t row[4 * NB];
 #pragma unroll
-        for (int q = 0; q < BITS; ++q)
-          *reinterpret_cast<u32x4*>(dst + 4 * q) = u32x4{row[4 * q], row[4 * q + 1], row[4 * q + 2], row[4 * q + 3]};
+          for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int pl = 0; pl < BITS; ++pl) row[t * BITS + pl] = word[0][t][pl] ^ ((word[0][t][pl] ^ word[1][t][pl]) & mine);
+#pragma unroll
+          for (int q = 0; q < BITS; ++q)
+            *reinterpret_cast<u32x4*>(dst + 4 * q) = u32x4{row[4 * q], row[4 * q + 1], row[4 * q + 2], row[4 * q + 3]};
+        }
+        if (normalise) a.norm[v_mine] = g ? nu[1] : nu[0];
       }
-      if (normalise) a.norm[v_mine] = g ? nu[1] : nu[0];
     }
 
     if (PROD) {
@@ -275,24 +319,30 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
       if (v_mine < a.n) {
         *reinterpret_cast<u32x4*>(a.qjl + v_mine * 4) =
             g ? u32x4{sw[1][0], sw[1][1], sw[1][2], sw[1][3]} : u32x4{sw[0][0], sw[0][1], sw[0][2], sw[0][3]};
-        a.gamma[v_mine] = sqrtf(g ? g2[1] : g2[0]);
+        if (MIXED) {
+          g2h[0] = add_across_halves(g2h[0]);
+          g2h[1] = add_across_halves(g2h[1]);
+          *reinterpret_cast<float2*>(a.gamma + 2 * v_mine) = make_float2(sqrtf(g ? g2h[1] : g2h[0]), sqrtf(g ? g2[1] : g2[0]));
+        } else {
+          a.gamma[v_mine] = sqrtf(g ? g2[1] : g2[0]);
+        }
       }
     }
   }
 }
 
-template <int BITS, bool PROD>
+template <int BITS, bool PROD, bool MIXED>
 hipError_t launch_one(const Q128Args& a, hipStream_t s) {
   constexpr int lds = (PI_ELEMS + (PROD ? W_ELEMS : 0)) * 2;
   static bool attr_done = false;  // per instantiation: the limit has to be raised once
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant128_bf3_kernel<BITS, PROD>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant128_bf3_kernel<BITS, PROD, MIXED>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   const int64_t blocks = (a.n + 255) / 256;
-  hipLaunchKernelGGL((quant128_bf3_kernel<BITS, PROD>), dim3((unsigned)(blocks < 256 ? blocks : 256)), dim3(256), lds, s, a);
+  hipLaunchKernelGGL((quant128_bf3_kernel<BITS, PROD, MIXED>), dim3((unsigned)(blocks < 256 ? blocks : 256)), dim3(256), lds, s, a);
   return hipGetLastError();
 }
 
@@ -304,23 +354,36 @@ bool quant128_bf3_applicable(int bits, bool prod, const void* X, int64_t ldx) {
   return (reinterpret_cast<uintptr_t>(X) & 15u) == 0 && ldx % 8 == 0;
 }
 
+// gs_hi > 0: two instances (cb_hi with bits + 1 bits for the first gs_hi coordinate groups); norm is required then
 hipError_t launch_quant128_bf3(int bits, bool prod, const void* X, int64_t ldx, int64_t n, const float* Pi,
                                const float* SPiT, uint32_t* idx, uint32_t* qjl, float* gamma, float* norm,
-                               const Codebook& cb, hipStream_t s) {
+                               const Codebook& cb, int gs_hi, const Codebook& cb_hi, hipStream_t s) {
   if (n <= 0) return hipSuccess;
+  if (gs_hi < 0 || gs_hi > 3 || (gs_hi > 0 && (bits > 2 || cb_hi.bits != bits + 1 || norm == nullptr))) return hipErrorInvalidValue;
   Q128Args a;
   a.X = static_cast<const unsigned short*>(X); a.ldx = ldx; a.n = n; a.Pi = Pi; a.SPiT = SPiT; a.idx = idx; a.qjl = qjl;
-  a.gamma = gamma; a.norm = norm; a.cb = cb;
+  a.gamma = gamma; a.norm = norm; a.cb = cb; a.gs_hi = gs_hi; a.cb_hi = cb_hi;
+  if (gs_hi > 0) {
+    switch (bits * 2 + (prod ? 1 : 0)) {
+      case 0: return launch_one<0, false, true>(a, s);
+      case 1: return launch_one<0, true, true>(a, s);
+      case 2: return launch_one<1, false, true>(a, s);
+      case 3: return launch_one<1, true, true>(a, s);
+      case 4: return launch_one<2, false, true>(a, s);
+      case 5: return launch_one<2, true, true>(a, s);
+      default: return hipErrorInvalidValue;  // 3 + 4 bits: the compiler keeps that body's arrays in scratch memory
+    }
+  }
   switch (bits * 2 + (prod ? 1 : 0)) {
-    case 1: return launch_one<0, true>(a, s);
-    case 2: return launch_one<1, false>(a, s);
-    case 3: return launch_one<1, true>(a, s);
-    case 4: return launch_one<2, false>(a, s);
-    case 5: return launch_one<2, true>(a, s);
-    case 6: return launch_one<3, false>(a, s);
-    case 7: return launch_one<3, true>(a, s);
-    case 8: return launch_one<4, false>(a, s);
-    case 9: return launch_one<4, true>(a, s);
+    case 1: return launch_one<0, true, false>(a, s);
+    case 2: return launch_one<1, false, false>(a, s);
+    case 3: return launch_one<1, true, false>(a, s);
+    case 4: return launch_one<2, false, false>(a, s);
+    case 5: return launch_one<2, true, false>(a, s);
+    case 6: return launch_one<3, false, false>(a, s);
+    case 7: return launch_one<3, true, false>(a, s);
+    case 8: return launch_one<4, false, false>(a, s);
+    case 9: return launch_one<4, true, false>(a, s);
     default: return hipErrorInvalidValue;
   }
 }

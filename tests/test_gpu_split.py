@@ -64,6 +64,8 @@ def keys(n, hi_ch, seed=9, bf16=True):
 @pytest.mark.parametrize("d_hi,bits_lo,prod,n,bf16", [
     (32, 1, True, 3000, True), (64, 1, True, 257, False), (32, 2, True, 40000, True), (96, 2, False, 130, False),
     (32, 0, True, 65, False), (64, 3, False, 1000, True),
+    # large bf16 batches: the kernel on the bf16 matrix cores (up to 2 + 3 bits), ragged tails
+    (64, 1, True, 33000, True), (96, 2, False, 32773, True), (32, 0, True, 34000, True), (64, 3, True, 33000, True),
 ])
 def test_quantize_split(d_hi, bits_lo, prod, n, bf16):
     hi_ch, ihi, ilo, p = instances(d_hi, bits_lo, prod)
