@@ -314,14 +314,17 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
             sw[nt][2 * pass + mt] = or_across_halves(w);
           }
       }
+      // (exchanges between the half-waves stay outside the guarded stores: every lane takes part)
       g2[0] = add_across_halves(g2[0]);
       g2[1] = add_across_halves(g2[1]);
+      if (MIXED) {
+        g2h[0] = add_across_halves(g2h[0]);
+        g2h[1] = add_across_halves(g2h[1]);
+      }
       if (v_mine < a.n) {
         *reinterpret_cast<u32x4*>(a.qjl + v_mine * 4) =
             g ? u32x4{sw[1][0], sw[1][1], sw[1][2], sw[1][3]} : u32x4{sw[0][0], sw[0][1], sw[0][2], sw[0][3]};
         if (MIXED) {
-          g2h[0] = add_across_halves(g2h[0]);
-          g2h[1] = add_across_halves(g2h[1]);
           *reinterpret_cast<float2*>(a.gamma + 2 * v_mine) = make_float2(sqrtf(g ? g2h[1] : g2h[0]), sqrtf(g ? g2[1] : g2[0]));
         } else {
           a.gamma[v_mine] = sqrtf(g ? g2[1] : g2[0]);
