@@ -288,6 +288,10 @@ tq_status tq_dequantize(const tq_params* p, const uint32_t* idx, const uint32_t*
     // two instances: d = 128 kernel only; idx rows are not 16-byte multiples there
     if (norm == nullptr || idx == nullptr || p->Pi == nullptr || (prod && p->S == nullptr)) return TQ_ERR_INVALID_ARG;
     if (!aligned16(p->Pi) || (prod && (!aligned16(p->S) || !aligned16(qjl)))) return TQ_ERR_UNSUPPORTED;
+    if (n > kBf3DequantRows && !fp32_mfma_only() && p->PiT != nullptr && (!prod || p->ST != nullptr))
+      return from_hip(launch_dequant128_bf3(p->bits_mse, prod, idx, qjl, gamma, norm, p->PiT, p->ST, x_out, ldo, n,
+                                            kappa_of(p->d - p->d_hi), make_codebook(p), p->d_hi / 32, kappa_of(p->d_hi),
+                                            make_codebook_hi(p), static_cast<hipStream_t>(stream)));
     return from_hip(launch_dequant128(p->bits_mse, prod, idx, qjl, gamma, norm, p->Pi, p->S, x_out, ldo, n,
                                       kappa_of(p->d - p->d_hi), make_codebook(p), p->d_hi / 32,
                                       kappa_of(p->d_hi), make_codebook_hi(p), static_cast<hipStream_t>(stream)));
@@ -295,7 +299,7 @@ tq_status tq_dequantize(const tq_params* p, const uint32_t* idx, const uint32_t*
   // large batches at d = 128: decoded codes straight into bf16 MFMA operands, pieces of Pi^T / S^T in LDS
   if (p->d == 128 && n > kBf3DequantRows && !fp32_mfma_only() && dequant128_bf3_applicable(p->bits_mse, prod, make_codebook(p), x_out, ldo))
     return from_hip(launch_dequant128_bf3(p->bits_mse, prod, idx, qjl, gamma, norm, p->PiT, p->ST, x_out, ldo, n,
-                                          kappa_of(128), make_codebook(p), static_cast<hipStream_t>(stream)));
+                                          kappa_of(128), make_codebook(p), 0, 0.f, make_codebook(p), static_cast<hipStream_t>(stream)));
   if (p->d == 128 && p->Pi != nullptr && aligned16(p->Pi) && (!prod || (p->S != nullptr && aligned16(p->S))) &&
       aligned16(idx) && (!prod || aligned16(qjl))) {
     return from_hip(launch_dequant128(p->bits_mse, prod, idx, qjl, gamma, norm, p->Pi, p->S, x_out, ldo, n,

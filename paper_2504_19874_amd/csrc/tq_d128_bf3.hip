@@ -40,13 +40,20 @@ struct Dq128Args {
   int64_t n;
   float kappa;
   Codebook cb;
+  // two instances over a split of the rotated coordinates (MIXED, Sec. 4.3): coordinate groups [0, gs_hi) belong to
+  // instance hi with BITS + 1 planes, codebook cb_hi and sketch scale kappa_hi; idx rows hold 4 BITS + gs_hi words,
+  // gamma and norm two floats per vector (hi, lo)
+  int gs_hi;
+  float kappa_hi;
+  Codebook cb_hi;
 };
 
-template <int BITS, bool PROD>
+template <int BITS, bool PROD, bool MIXED>
 __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) {
-  constexpr bool TABLE = BITS >= 2;  // centroid pieces looked up in LDS (1 bit: the pieces of c_1 with a sign)
-  constexpr int NB = BITS > 0 ? BITS : 1;
-  constexpr int MATS = (BITS > 0 ? 1 : 0) + (PROD ? 1 : 0);
+  constexpr bool TABLE = BITS >= 2 || MIXED;  // centroid pieces looked up in LDS (1 bit: the pieces of c_1 with a sign)
+  constexpr int NB = (BITS > 0 ? BITS : 1) + (MIXED ? 1 : 0);  // plane words per coordinate group, at most
+  constexpr int MATS = (BITS > 0 || MIXED ? 1 : 0) + (PROD ? 1 : 0);
+  constexpr bool PI = BITS > 0 || MIXED;  // there is a centroid part
   constexpr int READS = 4 * 2 * MATS;  // B operands per step: 4 tiles x 2 pieces x matrices
   extern __shared__ __attribute__((aligned(16))) unsigned short lds_s[];  // [matrix][piece][k][128], then the table
   uint32_t* const table_s = reinterpret_cast<uint32_t*>(lds_s + MATS * 2 * MAT_ELEMS);
@@ -59,7 +66,7 @@ __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) 
     int m = 0;
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
-      if (s == 0 ? BITS == 0 : !PROD) continue;
+      if (s == 0 ? !PI : !PROD) continue;
       const float* W = s == 0 ? a.PiT : a.ST;
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
@@ -80,9 +87,9 @@ __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) 
       }
       ++m;
     }
-    if (TABLE && tid < 16) {
+    if (TABLE && tid < (MIXED ? 32 : 16)) {  // MIXED: entries 16.. are instance hi's
       uint32_t p1, p2, p3;
-      split3(a.cb.c[tid], p1, p2, p3);
+      split3(tid < 16 ? a.cb.c[tid] : a.cb_hi.c[tid - 16], p1, p2, p3);
       table_s[tid] = p1 | (p2 << 16);
     }
   }
@@ -97,9 +104,29 @@ __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) 
     c1p[1] = p2 * 0x00010001u;
   }
   const int64_t blocks = (a.n + 255) / 256;
+  const int gs = MIXED ? a.gs_hi : 0;
+  // MIXED: which of this lane's four output columns belong to instance hi.  The matrices are block diagonal up to a
+  // permutation of the channels, so column k belongs to hi exactly when row k of the transposed matrix has an
+  // entry among the first 32 gs_hi.
+  uint32_t hi_cols = 0u;
+  if (MIXED) {
+    // thread t scans one half of the range for row t / 2; the flags go through LDS (behind the table)
+    uint32_t* const flag_s = table_s + 32;
+    const float* row = (PROD ? a.ST : a.PiT) + (tid >> 1) * 128;
+    bool any = false;
+    for (int j = 16 * gs * (tid & 1); j < 16 * gs * ((tid & 1) + 1); j += 4) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(row + j);
+      any = any || v[0] != 0.f || v[1] != 0.f || v[2] != 0.f || v[3] != 0.f;
+    }
+    flag_s[tid] = any ? 1u : 0u;
+    __syncthreads();
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) hi_cols |= (flag_s[2 * (4 * vi + ct)] | flag_s[2 * (4 * vi + ct) + 1]) << ct;
+  }
 
+  // MIXED: nu / kg are instance lo's, nuh / kgh instance hi's
   uint32_t w[2][4][NB], z[2][4], wn[2][4][NB], zn[2][4];
-  float nu[2], kg[2], nun[2], kgn[2];
+  float nu[2], kg[2], nun[2], kgn[2], nuh[2] = {0.f, 0.f}, kgh[2] = {0.f, 0.f}, nuhn[2] = {0.f, 0.f}, kghn[2] = {0.f, 0.f};
   auto load_code = [&](int64_t blk) {  // into the "next" registers
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
@@ -107,12 +134,25 @@ __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) 
       const int64_t row = v < a.n ? v : a.n - 1;  // clamped: such rows are not stored
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
+        if (MIXED) {  // group g: BITS (+ 1 below gs) planes, the groups back to back
+          const uint32_t* src = a.idx + row * (4 * BITS + gs) + g * BITS + (g < gs ? g : gs);
 #pragma unroll
-        for (int pl = 0; pl < BITS; ++pl) wn[mt][g][pl] = a.idx[row * (4 * BITS) + g * BITS + pl];
+          for (int pl = 0; pl < BITS + 1; ++pl) wn[mt][g][pl] = (pl < BITS || g < gs) ? src[pl < BITS || g < gs ? pl : 0] : 0u;
+        } else {
+#pragma unroll
+          for (int pl = 0; pl < BITS; ++pl) wn[mt][g][pl] = a.idx[row * (4 * BITS) + g * BITS + pl];
+        }
         zn[mt][g] = PROD ? a.qjl[row * 4 + g] : 0u;
       }
-      nun[mt] = a.norm != nullptr ? a.norm[row] : 1.f;
-      kgn[mt] = PROD ? a.kappa * a.gamma[row] : 0.f;
+      if (MIXED) {
+        nuhn[mt] = a.norm[2 * row];
+        nun[mt] = a.norm[2 * row + 1];
+        kghn[mt] = PROD ? a.kappa_hi * a.gamma[2 * row] : 0.f;
+        kgn[mt] = PROD ? a.kappa * a.gamma[2 * row + 1] : 0.f;
+      } else {
+        nun[mt] = a.norm != nullptr ? a.norm[row] : 1.f;
+        kgn[mt] = PROD ? a.kappa * a.gamma[row] : 0.f;
+      }
     }
   };
 
@@ -130,11 +170,13 @@ __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) 
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
 #pragma unroll
-        for (int pl = 0; pl < BITS; ++pl) w[mt][g][pl] = wn[mt][g][pl];
+        for (int pl = 0; pl < (MIXED ? BITS + 1 : BITS); ++pl) w[mt][g][pl] = wn[mt][g][pl];
         z[mt][g] = zn[mt][g];
       }
       nu[mt] = nun[mt];
       kg[mt] = kgn[mt];
+      nuh[mt] = nuhn[mt];
+      kgh[mt] = kghn[mt];
     }
     load_code(blk + gridDim.x);  // the next block's codes travel during this block (clamped past the end)
     floatx16 acc[2][4];  // [vector tile][column tile]
@@ -144,13 +186,16 @@ __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) 
       for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[mt][ct][r] = 0.f;
-    uint32_t kgp[2][2];  // the two pieces of kappa gamma of this lane's vectors, each twice in a word
+    uint32_t kgp[2][2], kghp[2][2];  // the two pieces of kappa gamma of this lane's vectors, each twice in a word
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
       uint32_t p1, p2, p3;
       split3(kg[mt], p1, p2, p3);
       kgp[mt][0] = p1 * 0x00010001u;
       kgp[mt][1] = p2 * 0x00010001u;
+      split3(kgh[mt], p1, p2, p3);
+      kghp[mt][0] = p1 * 0x00010001u;
+      kghp[mt][1] = p2 * 0x00010001u;
     }
     bf16x8 ring[RING];
 #pragma unroll
@@ -165,10 +210,11 @@ __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) 
 #pragma unroll
         for (int h = 0; h < 2; ++h)
 #pragma unroll
-          for (int pl = 0; pl < BITS; ++pl)
+          for (int pl = 0; pl < (MIXED ? BITS + 1 : BITS); ++pl)  // a missing plane was loaded as zero
             lv[h] |= ((((w[mt][g][pl] >> (off + 4 * h)) & 0xFu) * 0x00204081u) & 0x01010101u) << pl;
+        const uint32_t* const tab = table_s + (MIXED && g < gs ? 16 : 0);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) te[mt][u] = table_s[(lv[u >> 2] >> (8 * (u & 3))) & 0xFFu];
+        for (int u = 0; u < 8; ++u) te[mt][u] = tab[(lv[u >> 2] >> (8 * (u & 3))) & 0xFFu];
       }
     };
     if (TABLE) look_up(0);
@@ -179,7 +225,7 @@ __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) 
       bf16x8 ca[2][2], za[2][2];
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt) {
-        if (BITS == 1) {
+        if (BITS == 1 && !MIXED) {
           u32x4 v1, v2;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {  // bit 1 = +c_1: the sign bit is set where the code bit is 0
@@ -204,8 +250,8 @@ __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) 
 #pragma unroll
           for (int e = 0; e < 4; ++e) {  // bit 1 = +1
             const uint32_t sg = ((((z[mt][g] >> (off + 2 * e)) & 1u) << 15) | (((z[mt][g] >> (off + 2 * e + 1)) & 1u) << 31)) ^ 0x80008000u;
-            v1[e] = kgp[mt][0] ^ sg;
-            v2[e] = kgp[mt][1] ^ sg;
+            v1[e] = (MIXED && g < gs ? kghp[mt][0] : kgp[mt][0]) ^ sg;
+            v2[e] = (MIXED && g < gs ? kghp[mt][1] : kgp[mt][1]) ^ sg;
           }
           za[mt][0] = *reinterpret_cast<const bf16x8*>(&v1);
           za[mt][1] = *reinterpret_cast<const bf16x8*>(&v2);
@@ -218,7 +264,7 @@ __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) 
 #pragma unroll
       for (int r = 0; r < READS; ++r) {
         const int ct = r & 3, q = r >> 2;
-        const bool sign_part = BITS == 0 || q >= 2;  // which matrix this operand belongs to
+        const bool sign_part = !PI || q >= 2;  // which matrix this operand belongs to
         const int pc = 1 - (q & 1);
         const bf16x8 b = ring[(s * READS + r) % RING];
         // piece pc of the matrix meets the pieces a of the decoded operand with a + pc <= 1; the two MFMAs on
@@ -242,64 +288,84 @@ __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) 
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
       // every row's norm first (one LDS round trip for all of them), then the arithmetic and the stores
-      float rnu[16];
+      float rnu[16], rnuh[MIXED ? 16 : 1];
 #pragma unroll
-      for (int r = 0; r < 16; ++r)
+      for (int r = 0; r < 16; ++r) {
         rnu[r] = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (8 * (r >> 2) + (r & 3) + 4 * (lane >> 5)), __float_as_int(nu[mt])));
+        if (MIXED)
+          rnuh[r] = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (8 * (r >> 2) + (r & 3) + 4 * (lane >> 5)), __float_as_int(nuh[mt])));
+      }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int64_t v = v0 + 32 * mt + 8 * (r >> 2) + (r & 3) + 4 * (lane >> 5);
         f32x4 o;
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct) o[ct] = rnu[r] * acc[mt][ct][r];
+        for (int ct = 0; ct < 4; ++ct) o[ct] = (MIXED && ((hi_cols >> ct) & 1u) ? rnuh[MIXED ? r : 0] : rnu[r]) * acc[mt][ct][r];
         if (full || v < a.n) __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(a.out + v * a.ldo + 4 * vi));
       }
     }
   }
 }
 
-template <int BITS, bool PROD>
+template <int BITS, bool PROD, bool MIXED>
 hipError_t launch_one(const Dq128Args& a, hipStream_t s) {
-  constexpr int MATS = (BITS > 0 ? 1 : 0) + (PROD ? 1 : 0);
-  constexpr int lds = MATS * 2 * MAT_ELEMS * 2 + 16 * 4;
+  constexpr int MATS = (BITS > 0 || MIXED ? 1 : 0) + (PROD ? 1 : 0);
+  constexpr int lds = MATS * 2 * MAT_ELEMS * 2 + (32 + 256) * 4;  // matrices, centroid tables, column flags
   static bool attr_done = false;  // per instantiation: the limit has to be raised once
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dequant128_bf3_kernel<BITS, PROD>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dequant128_bf3_kernel<BITS, PROD, MIXED>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   const int64_t blocks = (a.n + 255) / 256;
-  hipLaunchKernelGGL((dequant128_bf3_kernel<BITS, PROD>), dim3((unsigned)(blocks < 256 ? blocks : 256)), dim3(256), lds, s, a);
+  hipLaunchKernelGGL((dequant128_bf3_kernel<BITS, PROD, MIXED>), dim3((unsigned)(blocks < 256 ? blocks : 256)), dim3(256), lds, s, a);
   return hipGetLastError();
 }
 
 }  // namespace
 
-// d = 128, one instance; a 1-bit table must be +-c; rows of the output 16-byte aligned
+// d = 128; a 1-bit table of one instance must be +-c; rows of the output 16-byte aligned
 bool dequant128_bf3_applicable(int bits, bool prod, const Codebook& cb, const float* out, int64_t ldo) {
   if (bits < 0 || bits > 4 || (bits == 0 && !prod)) return false;
   if ((reinterpret_cast<uintptr_t>(out) & 15u) != 0 || ldo % 4 != 0) return false;
   return bits != 1 || cb.c[0] == -cb.c[1];
 }
 
+// gs_hi > 0: two instances (cb_hi with bits + 1 bits and kappa_hi for the first gs_hi coordinate groups; norm and
+// gamma hold two floats per vector)
 hipError_t launch_dequant128_bf3(int bits, bool prod, const uint32_t* idx, const uint32_t* qjl, const float* gamma,
                                  const float* norm, const float* PiT, const float* ST, float* out, int64_t ldo, int64_t n,
-                                 float kappa, const Codebook& cb, hipStream_t s) {
+                                 float kappa, const Codebook& cb, int gs_hi, float kappa_hi, const Codebook& cb_hi,
+                                 hipStream_t s) {
   if (n <= 0) return hipSuccess;
+  if (gs_hi < 0 || gs_hi > 3 || (gs_hi > 0 && (bits > 3 || cb_hi.bits != bits + 1 || norm == nullptr))) return hipErrorInvalidValue;
   Dq128Args a;
   a.idx = idx; a.qjl = qjl; a.gamma = gamma; a.norm = norm; a.PiT = PiT; a.ST = ST; a.out = out; a.ldo = ldo; a.n = n;
-  a.kappa = kappa; a.cb = cb;
+  a.kappa = kappa; a.cb = cb; a.gs_hi = gs_hi; a.kappa_hi = kappa_hi; a.cb_hi = cb_hi;
+  if (gs_hi > 0) {
+    switch (bits * 2 + (prod ? 1 : 0)) {
+      case 0: return launch_one<0, false, true>(a, s);
+      case 1: return launch_one<0, true, true>(a, s);
+      case 2: return launch_one<1, false, true>(a, s);
+      case 3: return launch_one<1, true, true>(a, s);
+      case 4: return launch_one<2, false, true>(a, s);
+      case 5: return launch_one<2, true, true>(a, s);
+      case 6: return launch_one<3, false, true>(a, s);
+      case 7: return launch_one<3, true, true>(a, s);
+      default: return hipErrorInvalidValue;
+    }
+  }
   switch (bits * 2 + (prod ? 1 : 0)) {
-    case 1: return launch_one<0, true>(a, s);
-    case 2: return launch_one<1, false>(a, s);
-    case 3: return launch_one<1, true>(a, s);
-    case 4: return launch_one<2, false>(a, s);
-    case 5: return launch_one<2, true>(a, s);
-    case 6: return launch_one<3, false>(a, s);
-    case 7: return launch_one<3, true>(a, s);
-    case 8: return launch_one<4, false>(a, s);
-    case 9: return launch_one<4, true>(a, s);
+    case 1: return launch_one<0, true, false>(a, s);
+    case 2: return launch_one<1, false, false>(a, s);
+    case 3: return launch_one<1, true, false>(a, s);
+    case 4: return launch_one<2, false, false>(a, s);
+    case 5: return launch_one<2, true, false>(a, s);
+    case 6: return launch_one<3, false, false>(a, s);
+    case 7: return launch_one<3, true, false>(a, s);
+    case 8: return launch_one<4, false, false>(a, s);
+    case 9: return launch_one<4, true, false>(a, s);
     default: return hipErrorInvalidValue;
   }
 }

@@ -93,7 +93,8 @@ hipError_t launch_quant128_bf3(int bits, bool prod, const void* X, int64_t ldx, 
                                const Codebook& cb, int gs_hi, const Codebook& cb_hi, hipStream_t s);
 hipError_t launch_dequant128_bf3(int bits, bool prod, const uint32_t* idx, const uint32_t* qjl, const float* gamma,
                                  const float* norm, const float* PiT, const float* ST, float* out, int64_t ldo, int64_t n,
-                                 float kappa, const Codebook& cb, hipStream_t s);
+                                 float kappa, const Codebook& cb, int gs_hi, float kappa_hi, const Codebook& cb_hi,
+                                 hipStream_t s);
 
 // few queries per code (tq_score_small.hip)
 hipError_t launch_matvec_small(int d, int nq, const float* W0, const float* W1, const float* x,

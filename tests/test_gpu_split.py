@@ -155,7 +155,10 @@ def random_codes(p, ihi, ilo, d_hi, n, prod, seed=21):
 
 
 @pytest.mark.parametrize("d_hi,bits_lo,prod,n", [(32, 1, True, 777), (64, 2, True, 130), (96, 1, False, 65), (32, 3, False, 300),
-                                                (32, 0, True, 40)])
+                                                (32, 0, True, 40),
+                                                # above 8192 vectors: the kernel on the bf16 matrix cores
+                                                (32, 1, True, 9000), (64, 2, True, 8200), (96, 1, False, 8500),
+                                                (32, 3, False, 9001), (64, 0, True, 8300), (64, 3, True, 8193)])
 def test_dequantize_split(d_hi, bits_lo, prod, n):
     hi_ch, ihi, ilo, p = instances(d_hi, bits_lo, prod)
     res, idx_w, qjl_w, gamma, norm = random_codes(p, ihi, ilo, d_hi, n, prod)
