@@ -94,7 +94,14 @@ def piece_products(cfg, call: str):
     with x as one piece against three pieces of Pi, and the residual's two pieces against two of S Pi^T (three
     products each); DeQuant takes three products for the centroid part and three for the sign part."""
     n, prod = cfg.n * cfg.n_groups, cfg.kind == "prod"
-    if cfg.d != 128 or getattr(cfg, "d_hi", 0):
+    if cfg.d != 128:
+        # the generic kernel: rotation with three pieces of both factors (six products, three for a bf16 input),
+        # the sketch with two (three products)
+        if call == "quantize":
+            rot = 3.0 if cfg.in_dtype == "bf16" else 6.0
+            return (rot + 3.0) / 2 if prod else rot
+        return 0.0
+    if getattr(cfg, "d_hi", 0):
         return 0.0
     if call == "quantize" and cfg.in_dtype == "bf16" and n >= 32768:
         return 3.0

@@ -50,16 +50,16 @@
  * the fp32 factors are fed to the bf16 or int8 matrix cores as exact pieces
  * (bf16 pieces of 8 significant bits each, or base-128 digits of a fixed-point
  * value with 2^-19 relative spacing):
- *   quantise, large bf16 batches at d = 128: x (one exact piece) against the
- *     three pieces of Pi, i.e. the rotation to fp32 accuracy; the sketch, of
- *     which only signs are kept, from two pieces of the residual and two of
- *     S Pi^T (a sign can differ from the exact one only where
- *     |<S_j, r>| < 1e-6 |S_j| |r|);
+ *   quantise, large bf16 batches at d = 128 and every d other than 128: the
+ *     rotation from three pieces of Pi and three of x (a bf16 x is one piece),
+ *     i.e. to fp32 accuracy; the sketch, of which only signs are kept, from
+ *     two pieces of the residual and two of S Pi^T (a sign can differ from the
+ *     exact one only where |<S_j, r>| < 1e-6 |S_j| |r|);
  *   dequantise, large batches at d = 128: two pieces of each factor (error
  *     below 3e-5 of a coordinate's typical size); other d: three pieces;
  *   scoring: three bf16 pieces (many queries) or int8 digits (few queries).
- * fp32 inputs, smaller batches and two-instance codes run on the fp32 matrix
- * instructions.  All paths meet the same tolerances (indices equal to an fp32
+ * At d = 128, fp32 inputs, smaller batches and 3 + 4-bit two-instance codes run
+ * on the fp32 matrix instructions.  All paths meet the same tolerances (indices equal to an fp32
  * evaluation except within 1e-5 of a cell boundary; values and scores within
  * 1e-4 relative).  With TQ_FP32_MFMA=1 in the environment every contraction of
  * tq_quantize_*, tq_dequantize and many-query tq_score stays on the fp32 matrix

@@ -19,25 +19,32 @@
 // epilogues work per lane: a lane holds 16 coordinates of ONE vector per tile,
 // builds its share of the packed words locally and merges with the other
 // half-wave through one cross-lane exchange.
-#include "tq_internal.h"
+//
+// Pieces (NP > 0).  The same contraction can run on the bf16 matrix cores: both fp32 operands are split
+// into NP exact bf16 pieces while they are staged into LDS (a bf16 input is one piece as it stands) and the
+// piece products of combined weight >= 2^(-8 (NP - 1)) are summed in the fp32 accumulator with
+// v_mfma_f32_32x32x16_bf16, whose D layout is the one above, so the epilogues do not change.  NP = 3
+// reproduces the fp32 product to 2^-24 (six products, three for a bf16 input); NP = 2 (three products) is
+// used where only signs are kept.
+#include "tq_bf3.h"
 
+#include <cstdlib>
 #include <type_traits>
 
 namespace tq {
 
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int TM = 128;      // rows of W per workgroup
 constexpr int TN = 128;      // vectors per workgroup
 constexpr int BK = 32;       // k per LDS stage
 constexpr int LDS_LD = 36;   // padded row stride (floats)
+constexpr int P_LD = 104;    // pieces: bf16 per staged row, [piece][32 k] + 8 padding (208 bytes: conflict-free 16-byte reads)
 constexpr int XCDS = 8;
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-template <int NKIND, int EKIND, int BITS>
+template <int NKIND, int EKIND, int BITS, int NP>
 __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const int tiles_m,
                                                    const int tiles_n, const int per_xcd) {
   // two staging buffers of [TM + TN][LDS_LD] floats: one is read by the MFMAs while the next
@@ -146,6 +153,35 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
   // registers -> staging buffer (decoding packed codes on the way)
   auto store_tiles = [&](auto seg_c, float* Ws, float* Ns) {
     constexpr int SEG = decltype(seg_c)::value;
+    if constexpr (NP > 0) {
+      // both tiles as bf16 pieces, [row][piece][k]
+      unsigned short* const Wp = reinterpret_cast<unsigned short*>(Ws);
+      unsigned short* const Xp = reinterpret_cast<unsigned short*>(Ns);
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        uint32_t lo[3], hi[3];
+        split3_pair(f32x2{wreg[p][0], wreg[p][1]}, lo[0], lo[1], lo[2]);
+        split3_pair(f32x2{wreg[p][2], wreg[p][3]}, hi[0], hi[1], hi[2]);
+#pragma unroll
+        for (int pc = 0; pc < NP; ++pc)
+          *reinterpret_cast<uint2*>(Wp + (srow + 32 * p) * P_LD + pc * 32 + scol) = make_uint2(lo[pc], hi[pc]);
+        if (NKIND == N_BF16) {
+          const float x0 = bf16_lo(nreg[4 * p]), x1 = bf16_hi(nreg[4 * p]), x2 = bf16_lo(nreg[4 * p + 1]), x3 = bf16_hi(nreg[4 * p + 1]);
+          ss[p] += x0 * x0 + x1 * x1 + x2 * x2 + x3 * x3;
+          *reinterpret_cast<uint2*>(Xp + (srow + 32 * p) * P_LD + scol) = make_uint2(nreg[4 * p], nreg[4 * p + 1]);
+        } else {
+          const float x0 = __uint_as_float(nreg[4 * p]), x1 = __uint_as_float(nreg[4 * p + 1]);
+          const float x2 = __uint_as_float(nreg[4 * p + 2]), x3 = __uint_as_float(nreg[4 * p + 3]);
+          ss[p] += x0 * x0 + x1 * x1 + x2 * x2 + x3 * x3;
+          split3_pair(f32x2{x0, x1}, lo[0], lo[1], lo[2]);
+          split3_pair(f32x2{x2, x3}, hi[0], hi[1], hi[2]);
+#pragma unroll
+          for (int pc = 0; pc < NP; ++pc)
+            *reinterpret_cast<uint2*>(Xp + (srow + 32 * p) * P_LD + pc * 32 + scol) = make_uint2(lo[pc], hi[pc]);
+        }
+      }
+      return;
+    }
 #pragma unroll
     for (int p = 0; p < 4; ++p)
       *reinterpret_cast<f32x4*>(&Ws[(srow + 32 * p) * LDS_LD + scol]) = wreg[p];
@@ -195,8 +231,41 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  constexpr int BUF = (TM + TN) * LDS_LD;
+  constexpr int BUF = NP > 0 ? (TM + TN) * P_LD / 2 : (TM + TN) * LDS_LD;  // floats per staging buffer
+  constexpr int W_PART = NP > 0 ? TM * P_LD / 2 : TM * LDS_LD;           // floats of its W tile
   auto mfma_tile = [&](const float* Ws, const float* Ns) {
+    if constexpr (NP > 0) {
+      const unsigned short* const Wp = reinterpret_cast<const unsigned short*>(Ws);
+      const unsigned short* const Xp = reinterpret_cast<const unsigned short*>(Ns);
+      constexpr int NPX = NKIND == N_BF16 ? 1 : NP;  // pieces of the streamed operand
+#pragma unroll
+      for (int s = 0; s < 2; ++s) {  // 16 values of k per step: lane half h holds k = 16 s + 8 h + 0..7
+        bf16x8 av[2][NP], bv[2][NPX];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+#pragma unroll
+          for (int pc = 0; pc < NP; ++pc)
+            av[t][pc] = *reinterpret_cast<const bf16x8*>(Wp + (wm * 64 + t * 32 + l32) * P_LD + pc * 32 + 16 * s + 8 * h);
+#pragma unroll
+          for (int pc = 0; pc < NPX; ++pc)
+            bv[t][pc] = *reinterpret_cast<const bf16x8*>(Xp + (wn * 64 + t * 32 + l32) * P_LD + pc * 32 + 16 * s + 8 * h);
+        }
+        // products of pieces pa, pb with pa + pb < NP, smallest first; the four accumulators in turn
+#pragma unroll
+        for (int w = NP - 1; w >= 0; --w)
+#pragma unroll
+          for (int pb = 0; pb < NPX; ++pb) {
+            const int pa = w - pb;
+            if (pa < 0) continue;
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+              for (int j = 0; j < 2; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i][pa], bv[j][pb], acc[i][j], 0, 0, 0);
+          }
+      }
+      return;
+    }
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       float4 av[2], bv[2];
@@ -221,12 +290,24 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
   // kt-1 read, k-tile kt+2 (segment SF) is requested, and the MFMAs run on k-tile kt.  The
   // barrier that ends the step both publishes the new buffer and retires the old one.
   auto steps = [&](int kt_begin, int kt_end, auto sn_c, auto sf_c) {
+    if constexpr (NP > 0) {
+      // pieces: ONE staging buffer (two would leave room for a single workgroup per compute unit, and the second
+      // workgroup hides more than the second buffer does): MFMAs, barrier, refill, barrier
+      for (int kt = kt_begin; kt < kt_end; ++kt) {
+        mfma_tile(stage_s, stage_s + W_PART);
+        __syncthreads();
+        if (kt + 1 < n_kt) store_tiles(sn_c, stage_s, stage_s + W_PART);
+        if (kt + 2 < n_kt) load_tiles(sf_c, kt + 2);
+        __syncthreads();
+      }
+      return;
+    }
     for (int kt = kt_begin; kt < kt_end; ++kt) {
       float* const cur = stage_s + (kt & 1) * BUF;
       float* const nxt = stage_s + ((kt + 1) & 1) * BUF;
-      if (kt + 1 < n_kt) store_tiles(sn_c, nxt, nxt + TM * LDS_LD);
+      if (kt + 1 < n_kt) store_tiles(sn_c, nxt, nxt + W_PART);
       if (kt + 2 < n_kt) load_tiles(sf_c, kt + 2);
-      mfma_tile(cur, cur + TM * LDS_LD);
+      mfma_tile(cur, cur + W_PART);
       __syncthreads();
     }
   };
@@ -235,7 +316,7 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
 
   load_tiles(S0{}, 0);
   __syncthreads();  // cent_s visible before the first decode
-  store_tiles(S0{}, stage_s, stage_s + TM * LDS_LD);
+  store_tiles(S0{}, stage_s, stage_s + W_PART);
   if (NKIND == N_CODE && a.segs > 1) {
     if (n_kt > 1) {
       if (kt_per_seg > 1) load_tiles(S0{}, 1);
@@ -418,7 +499,12 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
   }
 }
 
-template <int NKIND, int EKIND, int BITS>
+static bool gemm_uses_pieces() {
+  const char* const env = std::getenv("TQ_FP32_MFMA");
+  return !(env != nullptr && env[0] == '1');
+}
+
+template <int NKIND, int EKIND, int BITS, int NP = 0>
 static hipError_t launch_one(const GemmArgs& a, int n_groups, hipStream_t stream) {
   const int tiles_m = (a.M + TM - 1) / TM;
   const int64_t tiles_n64 = (a.n + TN - 1) / TN;
@@ -428,27 +514,27 @@ static hipError_t launch_one(const GemmArgs& a, int n_groups, hipStream_t stream
   if (total == 0 || n_groups == 0) return hipSuccess;
   const int per_xcd = (total + XCDS - 1) / XCDS;
   dim3 grid(per_xcd * XCDS, n_groups, 1);
-  constexpr int lds_bytes = 2 * (TM + TN) * LDS_LD * (int)sizeof(float);  // above the 64 KB default limit
+  constexpr int lds_bytes = NP > 0 ? (TM + TN) * P_LD * 2 : 2 * (TM + TN) * LDS_LD * (int)sizeof(float);  // above the 64 KB default limit
   static bool attr_done = false;  // per instantiation: the limit has to be raised once
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<NKIND, EKIND, BITS>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<NKIND, EKIND, BITS, NP>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL((gemm_kernel<NKIND, EKIND, BITS>), grid, dim3(256), lds_bytes, stream, a, tiles_m,
+  hipLaunchKernelGGL((gemm_kernel<NKIND, EKIND, BITS, NP>), grid, dim3(256), lds_bytes, stream, a, tiles_m,
                      tiles_n, per_xcd);
   return hipGetLastError();
 }
 
-template <int NKIND, int EKIND>
+template <int NKIND, int EKIND, int NP = 0>
 static hipError_t launch_bits(int bits, const GemmArgs& a, int g, hipStream_t s) {
   switch (bits) {
-    case 0: return launch_one<NKIND, EKIND, 0>(a, g, s);
-    case 1: return launch_one<NKIND, EKIND, 1>(a, g, s);
-    case 2: return launch_one<NKIND, EKIND, 2>(a, g, s);
-    case 3: return launch_one<NKIND, EKIND, 3>(a, g, s);
-    case 4: return launch_one<NKIND, EKIND, 4>(a, g, s);
+    case 0: return launch_one<NKIND, EKIND, 0, NP>(a, g, s);
+    case 1: return launch_one<NKIND, EKIND, 1, NP>(a, g, s);
+    case 2: return launch_one<NKIND, EKIND, 2, NP>(a, g, s);
+    case 3: return launch_one<NKIND, EKIND, 3, NP>(a, g, s);
+    case 4: return launch_one<NKIND, EKIND, 4, NP>(a, g, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -456,6 +542,12 @@ static hipError_t launch_bits(int bits, const GemmArgs& a, int g, hipStream_t s)
 hipError_t launch_gemm(NKind nk, EKind ek, int bits, const GemmArgs& a, int n_groups,
                        hipStream_t stream) {
   // only the combinations the library uses are instantiated
+  // the quantiser's two contractions on the bf16 matrix cores unless TQ_FP32_MFMA=1: the rotation with three
+  // pieces (fp32 accuracy), the sketch (signs only) with two
+  const bool pieces = gemm_uses_pieces();
+  if (pieces && nk == N_F32 && ek == E_QUANT) return launch_bits<N_F32, E_QUANT, 3>(bits, a, n_groups, stream);
+  if (pieces && nk == N_BF16 && ek == E_QUANT) return launch_bits<N_BF16, E_QUANT, 3>(bits, a, n_groups, stream);
+  if (pieces && nk == N_F32 && ek == E_SIGN) return launch_one<N_F32, E_SIGN, 0, 2>(a, n_groups, stream);
   if (nk == N_F32 && ek == E_QUANT) return launch_bits<N_F32, E_QUANT>(bits, a, n_groups, stream);
   if (nk == N_BF16 && ek == E_QUANT) return launch_bits<N_BF16, E_QUANT>(bits, a, n_groups, stream);
   if (nk == N_F32 && ek == E_SIGN) return launch_one<N_F32, E_SIGN, 0>(a, n_groups, stream);
