@@ -110,6 +110,24 @@ def piece_products(cfg, call: str):
     return 0.0
 
 
+def arithmetic(cfg):
+    """What each call of this workload multiplies in (every result meets the fp32 tolerances of the parity tests)."""
+    if cfg.d == 128:
+        q = ("bf16 MFMA on exact pieces: bf16 input x three pieces of Pi (rotation), two pieces of the residual x two "
+             "of S Pi^T (signs only); fp32 accumulation and bucket decision") if piece_products(cfg, "quantize") else \
+            "fp32 MFMA (rotation and sketch), fp32 bucket decision"
+        dq = "bf16 MFMA on two-piece splits of the fp32 factors (error < 3e-5 of a coordinate), fp32 accumulation" \
+            if piece_products(cfg, "dequantize") else "fp32 MFMA"
+    else:
+        q = ("bf16 MFMA on exact pieces: three pieces of Pi x three of x (rotation; a bf16 x is one piece), two x two for "
+             "the sketch (signs only); fp32 accumulation and bucket decision")
+        dq = "bf16 MFMA on exact three-piece splits of the fp32 factors (the scoring kernel with the rows of Pi^T as queries)"
+    few = cfg.q_per_group <= 32 and cfg.d <= 512
+    sc = "int8 MFMA on exact base-128 digits of 2^-19-scaled rotated queries, fp32 combination" if few else \
+        "bf16 MFMA on exact three-piece splits of the rotated queries, fp32 accumulation"
+    return {"quantize": q, "dequantize": dq, "score": sc}
+
+
 def algorithmic_work(cfg, call: str):
     """(flops, bytes) of one call, counting only what the method needs."""
     n, d, nq = cfg.n * cfg.n_groups, cfg.d, cfg.nq
@@ -281,12 +299,7 @@ def main():
         "scores_per_s": float(cfg.nq) * cfg.n / (per_call_ms[2] * 1e-3),
         "roofline": roof,
         # what each call multiplies in; every result meets the fp32 tolerances of the parity tests
-        "arithmetic": {"quantize": ("bf16 MFMA on exact pieces: bf16 input x three pieces of Pi (rotation), two pieces of the "
-                                    "residual x two of S Pi^T (signs only); fp32 accumulation and bucket decision")
-                       if piece_products(cfg, "quantize") else "fp32 MFMA (rotation and sketch), fp32 bucket decision",
-                       "dequantize": "bf16 MFMA on two-piece splits of the fp32 factors (error < 3e-5 of a coordinate), fp32 accumulation"
-                       if piece_products(cfg, "dequantize") else "fp32 MFMA",
-                       "score": "int8 MFMA on exact base-128 digits of 2^-19-scaled rotated queries, fp32 combination"},
+        "arithmetic": arithmetic(cfg),
     }
     if any(piece_products(cfg, name) for name, _ in calls):
         # the same calls with every contraction kept on the fp32 matrix instructions (TQ_FP32_MFMA=1): the
