@@ -203,13 +203,13 @@ def unit_normalise(x, normalise: bool = True):
 
 
 def rotate(xh, Pi):
-    """y = Pi x for every row x of xh, rounded to fp32 (Alg. 1, Quant line 1)."""
+    """y = Pi x for every row x of xh, rounded to fp32 (Alg. 1, Quant: the rotation step)."""
     P = np.asarray(Pi, dtype=np.float32).astype(np.float64)
     return (np.asarray(xh, dtype=np.float64) @ P.T).astype(np.float32)
 
 
 def nearest_centroid(y32, bounds32):
-    """idx_j = argmin_k |y_j - c_k| (Alg. 1, Quant line 2), evaluated as the
+    """idx_j = argmin_k |y_j - c_k| (Alg. 1, Quant: the nearest-centroid step), evaluated as the
     number of cell boundaries that y_j is >= to, in fp32."""
     y32 = np.asarray(y32, dtype=np.float32)
     b = np.asarray(bounds32, dtype=np.float32)

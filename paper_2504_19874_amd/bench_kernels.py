@@ -1,5 +1,5 @@
 """Per-entry-point timings against the MFMA / HBM rooflines for the five
-benchmark configurations (the table in the design doc comes from this).
+benchmark configurations.
 
     python -m paper_2504_19874_amd.bench_kernels --config C2 [--reps 50]
 
