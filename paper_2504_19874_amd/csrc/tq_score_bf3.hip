@@ -1,20 +1,22 @@
 // Many queries per code (nearest-neighbour search, Sec. 4.4): the estimator of Sec. 3.2 for a block of
 // queries against a block of codes is a dense contraction whose code-side operand takes few values,
 //     score[m][i] = nu_i * ( sum_j qr[m][j] c[idx_ij]  +  kappa gamma_i sum_j qs[m][j] z_ij ).
-// It runs on the bf16 matrix cores (16 x the fp32 rate) without giving up fp32 accuracy: every fp32 factor
-// is split into three bf16 pieces, x = x1 + x2 + x3 exactly (8 + 8 + 8 mantissa bits), a product of two
-// pieces is exact in fp32, and the MFMA accumulates in fp32.  Of the nine piece products the six with
-// combined weight >= 2^-16 are kept,
-//     q c ~ q1 c1 + q1 c2 + q2 c1 + q1 c3 + q2 c2 + q3 c1,
-// the dropped ones are below 2^-24 |q| |c|, the rounding an fp32 multiply has anyway.  Sign operands need
-// one piece: z = +-1 is a bf16 value, and a 1-bit codebook is +-c_1 with c_1 applied after the sum; those
-// products take three MFMAs (q1, q2, q3).
+// It runs on the bf16 matrix cores (16 x the fp32 rate): every fp32 factor is taken as its two leading bf16
+// pieces, x ~ x1 + x2 (8 + 8 significant bits, what is left is below 2^-18 |x|), a product of two pieces is
+// exact in fp32, and the MFMA accumulates in fp32.  The three piece products of combined weight >= 2^-9 are
+// kept,
+//     q c ~ q1 c1 + q1 c2 + q2 c1,
+// so a term is off by less than 3 * 2^-18 |q| |c|.  Over the d terms of a score these errors average out: the
+// scores are within about 2e-7 |q| nu of the exact ones; a single dequantised coordinate (the transposed mode,
+// one term per coordinate and query) within about 2e-5 of its typical size.  Sign operands need one piece:
+// z = +-1 is a bf16 value, and a 1-bit codebook is +-c_1 with c_1 applied after the sum; those products take
+// two MFMAs (q1, q2).
 //
 // Workgroup = 512 threads = 8 wavefronts, tile 128 or 256 queries x 256 or 128 codes, k in steps of 16 (one
 // v_mfma_f32_32x32x16_bf16 per piece product and 32 x 32 sub-tile), operands through two LDS buffers with a
 // 48-byte row stride (conflict-free 16-byte reads).  Queries are split into pieces while they are staged
 // (read as fp32: 4 bytes per element instead of 6); codes are decoded into pieces while they are staged
-// (bit planes -> bucket number -> 3-piece table in LDS, or straight to +-1).  Wavefront (wm, wn) owns rows
+// (bit planes -> bucket number -> table of pieces in LDS, or straight to +-1).  Wavefront (wm, wn) owns rows
 // 64 wm .. and columns 64 wn .. of the tile: 2 x 2 sub-tiles, one accumulator set per segment (the sign
 // segment is scaled per code by kappa gamma, so it cannot share the accumulator of the first).
 #include "tq_bf3.h"
@@ -27,14 +29,15 @@ namespace {
 constexpr int KT = 16;  // k per step; queries per tile TM: 128 or 256, codes per tile TN: 256 or 128 (template parameters)
 constexpr int LDK = 24;      // bf16 per LDS row: 16 used + 8 padding = 48 bytes
 constexpr int SPAN = 4;      // coordinate groups (of 32) whose plane words a thread holds at a time
+constexpr int QP = 2;        // leading bf16 pieces kept of a query coordinate (and of a centroid)
 
 template <int BITS, bool PROD, int TM, int TN>
 struct Cfg {
   static constexpr int WM = TM / 64, WN = 8 / WM;  // wavefronts along the queries / the codes
   static constexpr int CT = TN / (32 * WN);        // 32-column sub-tiles of a wavefront (2 row sub-tiles always)
-  static constexpr int PC = BITS == 0 ? 0 : BITS == 1 ? 1 : 3;  // pieces of a decoded centroid
+  static constexpr int PC = BITS == 0 ? 0 : BITS == 1 ? 1 : QP;  // pieces of a decoded centroid
   static constexpr int SEGS = (BITS > 0 ? 1 : 0) + (PROD ? 1 : 0);
-  static constexpr int A_ELEMS = SEGS * 3 * TM * LDK;
+  static constexpr int A_ELEMS = SEGS * QP * TM * LDK;
   static constexpr int B_ELEMS = (PC + (PROD ? 1 : 0)) * TN * LDK;
   static constexpr int BUF_ELEMS = A_ELEMS + B_ELEMS;
   static constexpr int LDS_BYTES = 2 * BUF_ELEMS * 2 + 16 * 8;  // two buffers, then the piece table
@@ -78,7 +81,7 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
   const int m0 = blockIdx.y * TM;
   const int gw = a.d >> 5;  // coordinate groups per code
 
-  if (PC == 3 && tid < 16) {
+  if (PC == QP && tid < 16) {
     uint32_t p1, p2, p3;
     split3(a.cb.c[tid], p1, p2, p3);
     table_s[tid] = make_uint2(p1 | (p2 << 16), p3);
@@ -131,8 +134,8 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
         split3_pair(f32x2{areg[s][i][0], areg[s][i][1]}, lo[0], lo[1], lo[2]);
         split3_pair(f32x2{areg[s][i][2], areg[s][i][3]}, hi[0], hi[1], hi[2]);
 #pragma unroll
-        for (int pc = 0; pc < 3; ++pc)
-          *reinterpret_cast<uint2*>(buf + ((seg * 3 + pc) * TM + a_row + 128 * i) * LDK + a_k) = make_uint2(lo[pc], hi[pc]);
+        for (int pc = 0; pc < QP; ++pc)
+          *reinterpret_cast<uint2*>(buf + ((seg * QP + pc) * TM + a_row + 128 * i) * LDK + a_k) = make_uint2(lo[pc], hi[pc]);
       }
       ++seg;
     }
@@ -154,7 +157,7 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
       uint32_t v[CP / 2];
       signs(wcur[g][0] >> off, v);
       put(bb + b_col * LDK + CP * b_part, v);
-    } else if (PC == 3) {
+    } else if (PC == QP) {
       uint32_t lv[CP / 4];  // bucket numbers of 4 coordinates, one per byte
 #pragma unroll
       for (int h = 0; h < CP / 4; ++h) {
@@ -166,16 +169,14 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
       uint2 e[CP];
 #pragma unroll
       for (int u = 0; u < CP; ++u) e[u] = table_s[(lv[u >> 2] >> (8 * (u & 3))) & 0xFFu];
-      uint32_t v1[CP / 2], v2[CP / 2], v3[CP / 2];
+      uint32_t v1[CP / 2], v2[CP / 2];
 #pragma unroll
       for (int u = 0; u < CP / 2; ++u) {
         v1[u] = __builtin_amdgcn_perm(e[2 * u + 1].x, e[2 * u].x, 0x05040100u);  // low halves: first pieces
         v2[u] = __builtin_amdgcn_perm(e[2 * u + 1].x, e[2 * u].x, 0x07060302u);  // high halves: second pieces
-        v3[u] = __builtin_amdgcn_perm(e[2 * u + 1].y, e[2 * u].y, 0x05040100u);
       }
       put(bb + (0 * TN + b_col) * LDK + CP * b_part, v1);
       put(bb + (1 * TN + b_col) * LDK + CP * b_part, v2);
-      put(bb + (2 * TN + b_col) * LDK + CP * b_part, v3);
     }
     if (PROD) {
       uint32_t v[CP / 2];
@@ -211,39 +212,39 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
     };
     int seg = 0;
     if (BITS > 0) {
-      bf16x8 af[2][3], bf[CT][PC > 0 ? PC : 1];
+      bf16x8 af[2][QP], bf[CT][PC > 0 ? PC : 1];
 #pragma unroll
       for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-        for (int pc = 0; pc < 3; ++pc) af[rt][pc] = frag(buf + (seg * 3 + pc) * TM * LDK, 64 * wm + 32 * rt + f_row);
+        for (int pc = 0; pc < QP; ++pc) af[rt][pc] = frag(buf + (seg * QP + pc) * TM * LDK, 64 * wm + 32 * rt + f_row);
 #pragma unroll
       for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
         for (int pc = 0; pc < PC; ++pc) bf[ct][pc] = frag(bb + pc * TN * LDK, 32 * CT * wn + 32 * ct + f_row);
       // piece products outermost: consecutive MFMAs go to different accumulators; smallest products first
-      constexpr int NTERM = PC == 1 ? 3 : 6;
-      constexpr int TA[6] = {2, 1, 0, 1, 0, 0};                 // query piece of each product
-      constexpr int TB[6] = {0, 1, 2, 0, 1, 0};                 // centroid piece
+      constexpr int NTERM = PC == 1 ? QP : 3;
+      constexpr int TA[3] = {1, 0, 0};                          // query piece of each product
+      constexpr int TB[3] = {0, 1, 0};                          // centroid piece
 #pragma unroll
       for (int t = 0; t < NTERM; ++t)
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
           for (int ct = 0; ct < CT; ++ct)
-            acc1[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rt][PC == 1 ? 2 - t : TA[t]], bf[ct][PC == 1 ? 0 : TB[t]],
+            acc1[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rt][PC == 1 ? QP - 1 - t : TA[t]], bf[ct][PC == 1 ? 0 : TB[t]],
                                                                    acc1[rt][ct], 0, 0, 0);
       ++seg;
     }
     if (PROD) {
-      bf16x8 af[2][3], bf[CT];
+      bf16x8 af[2][QP], bf[CT];
 #pragma unroll
       for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-        for (int pc = 0; pc < 3; ++pc) af[rt][pc] = frag(buf + (seg * 3 + pc) * TM * LDK, 64 * wm + 32 * rt + f_row);
+        for (int pc = 0; pc < QP; ++pc) af[rt][pc] = frag(buf + (seg * QP + pc) * TM * LDK, 64 * wm + 32 * rt + f_row);
 #pragma unroll
       for (int ct = 0; ct < CT; ++ct) bf[ct] = frag(bb + PC * TN * LDK, 32 * CT * wn + 32 * ct + f_row);
 #pragma unroll
-      for (int pc = 2; pc >= 0; --pc)
+      for (int pc = QP - 1; pc >= 0; --pc)
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
