@@ -121,10 +121,10 @@ def arithmetic(cfg):
     else:
         q = ("bf16 MFMA on exact pieces: three pieces of Pi x three of x (rotation; a bf16 x is one piece), two x two for "
              "the sketch (signs only); fp32 accumulation and bucket decision")
-        dq = "bf16 MFMA on exact three-piece splits of the fp32 factors (the scoring kernel with the rows of Pi^T as queries)"
+        dq = "bf16 MFMA on two-piece splits of the fp32 factors (the scoring kernel with the rows of Pi^T as queries), fp32 accumulation"
     few = cfg.q_per_group <= 32 and cfg.d <= 512
     sc = "int8 MFMA on exact base-128 digits of 2^-19-scaled rotated queries, fp32 combination" if few else \
-        "bf16 MFMA on exact three-piece splits of the rotated queries, fp32 accumulation"
+        "bf16 MFMA on two-piece splits of the rotated queries and centroids (scores within 3e-6 |q| norm), fp32 accumulation"
     return {"quantize": q, "dequantize": dq, "score": sc}
 
 

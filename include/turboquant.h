@@ -55,9 +55,10 @@
  *     i.e. to fp32 accuracy; the sketch, of which only signs are kept, from
  *     two pieces of the residual and two of S Pi^T (a sign can differ from the
  *     exact one only where |<S_j, r>| < 1e-6 |S_j| |r|);
- *   dequantise, large batches at d = 128: two pieces of each factor (error
- *     below 3e-5 of a coordinate's typical size); other d: three pieces;
- *   scoring: three bf16 pieces (many queries) or int8 digits (few queries).
+ *   dequantise, large batches: two pieces of each factor (error
+ *     below 4e-5 of a coordinate's typical size), at every d;
+ *   scoring: two bf16 pieces of each factor (many queries; scores within
+ *     3e-6 |q| norm of the exact ones) or int8 digits (few queries).
  * At d = 128, fp32 inputs, smaller batches and 3 + 4-bit two-instance codes run
  * on the fp32 matrix instructions.  All paths meet the same tolerances (indices equal to an fp32
  * evaluation except within 1e-5 of a cell boundary; values and scores within
