@@ -203,6 +203,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C3b4", "C4", "C5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-fp32-reference", action="store_true",
+                    help="skip the TQ_FP32_MFMA=1 leg (profiler runs that should see one kernel per call)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -301,7 +303,7 @@ def main():
         # what each call multiplies in; every result meets the fp32 tolerances of the parity tests
         "arithmetic": arithmetic(cfg),
     }
-    if any(piece_products(cfg, name) for name, _ in calls):
+    if not args.no_fp32_reference and any(piece_products(cfg, name) for name, _ in calls):
         # the same calls with every contraction kept on the fp32 matrix instructions (TQ_FP32_MFMA=1): the
         # figure the fp32 MFMA peak applies to directly.  Outside the timed region, not part of `value`.
         os.environ["TQ_FP32_MFMA"] = "1"
