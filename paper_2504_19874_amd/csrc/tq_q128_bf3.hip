@@ -314,6 +314,13 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
             sw[nt][2 * pass + mt] = or_across_halves(w);
           }
       }
+      // The next block's vectors are waited for HERE, before the last stores of this block are issued: the wait the
+      // compiler places in front of their first use covers every older memory operation, and at the top of the
+      // next block that would include these stores (a round trip to memory per block).
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int s = 0; s < 8; ++s) asm volatile("" ::"v"(xop[nt][s]));
       // (exchanges between the half-waves stay outside the guarded stores: every lane takes part)
       g2[0] = add_across_halves(g2[0]);
       g2[1] = add_across_halves(g2[1]);
