@@ -164,6 +164,18 @@ __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) 
   };
 
   load_code(blockIdx.x);
+  // (waited for before the loop as well as at the end of every block, see below: no path into the loop's head may
+  // have these loads pending)
+#pragma unroll
+  for (int mt = 0; mt < 2; ++mt) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+#pragma unroll
+      for (int pl = 0; pl < NB; ++pl) asm volatile("" ::"v"(wn[mt][g][pl]));
+      asm volatile("" ::"v"(zn[mt][g]));
+    }
+    asm volatile("" ::"v"(nun[mt]), "v"(kgn[mt]), "v"(nuhn[mt]), "v"(kghn[mt]));
+  }
   for (int64_t blk = blockIdx.x; blk < blocks; blk += gridDim.x) {
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {

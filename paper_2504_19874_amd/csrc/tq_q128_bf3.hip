@@ -122,6 +122,12 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
     for (int s = 0; s < 8; ++s) xop[nt][s] = *reinterpret_cast<const u32x4*>(src + 16 * s);
   }
 
+  // (waited for before the loop as well, so that no path into the loop's head has these loads pending: otherwise the
+  // wait sits at the top of every block, behind the stores of the block before)
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+    for (int s = 0; s < 8; ++s) asm volatile("" ::"v"(xop[nt][s]));
   for (int64_t blk = blockIdx.x; blk < blocks; blk += gridDim.x) {
     // ---- norms: a lane and its partner in the other half-wave hold one vector between them --------------
     float nu[2] = {1.f, 1.f}, inv[2] = {1.f, 1.f};
