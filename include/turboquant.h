@@ -59,8 +59,8 @@
  *     below 4e-5 of a coordinate's typical size), at every d;
  *   scoring: two bf16 pieces of each factor (many queries; scores within
  *     3e-6 |q| norm of the exact ones) or int8 digits (few queries).
- * At d = 128, fp32 inputs, smaller batches and 3 + 4-bit two-instance codes run
- * on the fp32 matrix instructions.  All paths meet the same tolerances (indices equal to an fp32
+ * At d = 128, fp32 inputs and smaller batches run on the fp32 matrix
+ * instructions.  All paths meet the same tolerances (indices equal to an fp32
  * evaluation except within 1e-5 of a cell boundary; values and scores within
  * 1e-4 relative).  With TQ_FP32_MFMA=1 in the environment every contraction of
  * tq_quantize_*, tq_dequantize and many-query tq_score stays on the fp32 matrix

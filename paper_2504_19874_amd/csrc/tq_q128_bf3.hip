@@ -19,6 +19,8 @@
 //
 // Workgroup = 4 wavefronts (one per SIMD, the register file to itself); a wavefront takes 64 vectors per
 // block, so every LDS read of an A operand feeds at least two MFMAs.
+#include <type_traits>
+
 #include "tq_bf3.h"
 #include "tq_d128_tile.h"
 
@@ -182,9 +184,9 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
     float g2[2] = {0.f, 0.f}, g2h[2] = {0.f, 0.f}, nuh[2] = {0.f, 0.f};  // MIXED: g2 / nu belong to instance lo
     u32x4 rp[2][2][8];  // [piece][nt][step of stage 2]
     const int gs = MIXED ? a.gs_hi : 0;
+    float inv_hi[2] = {0.f, 0.f};
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
-      float inv_hi = 0.f;
       if (MIXED) {
         // the norms of the two instances from the rotated coordinates (the rotation is block diagonal)
         float s_hi = 0.f, s_lo = 0.f;
@@ -201,14 +203,19 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
         }
         nuh[nt] = sqrtf(add_across_halves(s_hi));
         nu[nt] = sqrtf(add_across_halves(s_lo));
-        inv_hi = nuh[nt] > 0.f ? 1.f / nuh[nt] : 0.f;
+        inv_hi[nt] = nuh[nt] > 0.f ? 1.f / nuh[nt] : 0.f;
         inv[nt] = nu[nt] > 0.f ? 1.f / nu[nt] : 0.f;
       }
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
+    }
+    {
+      // one tile; nt and t arrive as types so that every register index below is a constant whatever the compiler
+      // decides about unrolling (left as loops, the two-instance body with 15 compares was not unrolled and its
+      // arrays went to scratch memory)
+      auto tile = [&](auto nt_c, auto t_c) {
+        constexpr int nt = decltype(nt_c)::value, t = decltype(t_c)::value;
         uint32_t wd[4] = {0u, 0u, 0u, 0u};
         if (MIXED && t < gs)  // uniform
-          g2h[nt] += quantise_tile<BH>(acc[nt][t], inv_hi, a.cb_hi, g, wd);
+          g2h[nt] += quantise_tile<BH>(acc[nt][t], inv_hi[nt], a.cb_hi, g, wd);
         else
           g2[nt] += quantise_tile<BITS>(acc[nt][t], inv[nt], a.cb, g, wd);
 #pragma unroll
@@ -225,7 +232,13 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
             }
         }
         __builtin_amdgcn_sched_barrier(0);
-      }
+      };
+      using I0 = std::integral_constant<int, 0>;
+      using I1 = std::integral_constant<int, 1>;
+      using I2 = std::integral_constant<int, 2>;
+      using I3 = std::integral_constant<int, 3>;
+      tile(I0{}, I0{}); tile(I0{}, I1{}); tile(I0{}, I2{}); tile(I0{}, I3{});
+      tile(I1{}, I0{}); tile(I1{}, I1{}); tile(I1{}, I2{}); tile(I1{}, I3{});
     }
 
     const int64_t v_mine = blk * 256 + wave * 64 + 32 * g + vi;  // the vector this lane stores for: tile nt = g
@@ -375,7 +388,7 @@ hipError_t launch_quant128_bf3(int bits, bool prod, const void* X, int64_t ldx, 
                                const float* SPiT, uint32_t* idx, uint32_t* qjl, float* gamma, float* norm,
                                const Codebook& cb, int gs_hi, const Codebook& cb_hi, hipStream_t s) {
   if (n <= 0) return hipSuccess;
-  if (gs_hi < 0 || gs_hi > 3 || (gs_hi > 0 && (bits > 2 || cb_hi.bits != bits + 1 || norm == nullptr))) return hipErrorInvalidValue;
+  if (gs_hi < 0 || gs_hi > 3 || (gs_hi > 0 && (bits > 3 || cb_hi.bits != bits + 1 || norm == nullptr))) return hipErrorInvalidValue;
   Q128Args a;
   a.X = static_cast<const unsigned short*>(X); a.ldx = ldx; a.n = n; a.Pi = Pi; a.SPiT = SPiT; a.idx = idx; a.qjl = qjl;
   a.gamma = gamma; a.norm = norm; a.cb = cb; a.gs_hi = gs_hi; a.cb_hi = cb_hi;
@@ -387,7 +400,9 @@ hipError_t launch_quant128_bf3(int bits, bool prod, const void* X, int64_t ldx, 
       case 3: return launch_one<1, true, true>(a, s);
       case 4: return launch_one<2, false, true>(a, s);
       case 5: return launch_one<2, true, true>(a, s);
-      default: return hipErrorInvalidValue;  // 3 + 4 bits: the compiler keeps that body's arrays in scratch memory
+      case 6: return launch_one<3, false, true>(a, s);
+      case 7: return launch_one<3, true, true>(a, s);
+      default: return hipErrorInvalidValue;
     }
   }
   switch (bits * 2 + (prod ? 1 : 0)) {
