@@ -164,18 +164,6 @@ __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) 
   };
 
   load_code(blockIdx.x);
-  // (waited for before the loop as well as at the end of every block, see below: no path into the loop's head may
-  // have these loads pending)
-#pragma unroll
-  for (int mt = 0; mt < 2; ++mt) {
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-#pragma unroll
-      for (int pl = 0; pl < NB; ++pl) asm volatile("" ::"v"(wn[mt][g][pl]));
-      asm volatile("" ::"v"(zn[mt][g]));
-    }
-    asm volatile("" ::"v"(nun[mt]), "v"(kgn[mt]), "v"(nuhn[mt]), "v"(kghn[mt]));
-  }
   for (int64_t blk = blockIdx.x; blk < blocks; blk += gridDim.x) {
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
@@ -293,19 +281,6 @@ __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) 
         if (nxt < 8 * READS) ring[nxt % RING] = b_piece(nxt / READS, nxt % READS);
         __builtin_amdgcn_sched_barrier(0);
       }
-    }
-    // The next block's codes (requested at the top of this block) are waited for HERE, before the output stores
-    // are issued: the wait the compiler places in front of their first use covers every older memory operation,
-    // and at the top of the next block that would include these 32 stores per lane.
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-#pragma unroll
-        for (int pl = 0; pl < NB; ++pl) asm volatile("" ::"v"(wn[mt][g][pl]));
-        asm volatile("" ::"v"(zn[mt][g]));
-      }
-      asm volatile("" ::"v"(nun[mt]), "v"(kgn[mt]), "v"(nuhn[mt]), "v"(kghn[mt]));
     }
     // ---- epilogue: D[vector][k]; the factors of a row's vector sit in the lane with that number --------
     const int64_t v0 = blk * 256 + wave * 64;

@@ -124,12 +124,6 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
     for (int s = 0; s < 8; ++s) xop[nt][s] = *reinterpret_cast<const u32x4*>(src + 16 * s);
   }
 
-  // (waited for before the loop as well, so that no path into the loop's head has these loads pending: otherwise the
-  // wait sits at the top of every block, behind the stores of the block before)
-#pragma unroll
-  for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-    for (int s = 0; s < 8; ++s) asm volatile("" ::"v"(xop[nt][s]));
   for (int64_t blk = blockIdx.x; blk < blocks; blk += gridDim.x) {
     // ---- norms: a lane and its partner in the other half-wave hold one vector between them --------------
     float nu[2] = {1.f, 1.f}, inv[2] = {1.f, 1.f};
@@ -333,13 +327,6 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
             sw[nt][2 * pass + mt] = or_across_halves(w);
           }
       }
-      // The next block's vectors are waited for HERE, before the last stores of this block are issued: the wait the
-      // compiler places in front of their first use covers every older memory operation, and at the top of the
-      // next block that would include these stores (a round trip to memory per block).
-#pragma unroll
-      for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-        for (int s = 0; s < 8; ++s) asm volatile("" ::"v"(xop[nt][s]));
       // (exchanges between the half-waves stay outside the guarded stores: every lane takes part)
       g2[0] = add_across_halves(g2[0]);
       g2[1] = add_across_halves(g2[1]);
