@@ -103,7 +103,7 @@ def piece_products(cfg, call: str):
         return 0.0
     if getattr(cfg, "d_hi", 0):
         return 0.0
-    if call == "quantize" and cfg.in_dtype == "bf16" and n >= 32768:
+    if call == "quantize" and cfg.in_dtype == "bf16" and n > 8192:
         return 3.0
     if call == "dequantize" and n > 8192:
         return 3.0  # two pieces of each factor, three products, for the centroid part and for the sign part alike

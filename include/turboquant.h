@@ -50,7 +50,8 @@
  * the fp32 factors are fed to the bf16 or int8 matrix cores as exact pieces
  * (bf16 pieces of 8 significant bits each, or base-128 digits of a fixed-point
  * value with 2^-19 relative spacing):
- *   quantise, large bf16 batches at d = 128 and every d other than 128: the
+ *   quantise, bf16 batches above 8192 vectors at d = 128 and every d other
+ *     than 128: the
  *     rotation from three pieces of Pi and three of x (a bf16 x is one piece),
  *     i.e. to fp32 accuracy; the sketch, of which only signs are kept, from
  *     two pieces of the residual and two of S Pi^T (a sign can differ from the
