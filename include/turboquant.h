@@ -51,9 +51,9 @@
  * (bf16 pieces of 8 significant bits each, or base-128 digits of a fixed-point
  * value with 2^-19 relative spacing):
  *   quantise, bf16 batches above 8192 vectors at d = 128 and every d other
- *     than 128: the
- *     rotation from three pieces of Pi and three of x (a bf16 x is one piece),
- *     i.e. to fp32 accuracy; the sketch, of which only signs are kept, from
+ *     than 128: the rotation from three pieces of Pi and three of x (a bf16
+ *     x is one piece), i.e. to fp32 accuracy; the sketch, of which only signs
+ *     are kept, from
  *     two pieces of the residual and two of S Pi^T (a sign can differ from the
  *     exact one only where |<S_j, r>| < 1e-6 |S_j| |r|);
  *   dequantise, large batches: two pieces of each factor (error
