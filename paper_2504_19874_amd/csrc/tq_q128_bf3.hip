@@ -1,5 +1,6 @@
-// Quant_mse / Quant_prod (Alg. 1 / Alg. 2) at d = 128 for large batches of bf16 vectors, on the bf16 matrix
-// cores at fp32 accuracy (exact bf16 pieces of every fp32 factor, see tq_bf3.h).
+// Quant_mse / Quant_prod (Alg. 1 / Alg. 2) at d = 128 for batches of bf16 vectors beyond what one round of the
+// small-batch kernel covers, on the bf16 matrix cores (exact bf16 pieces of the fp32 factors, see tq_bf3.h): the
+// rotation to fp32 accuracy, the sketch as far as its signs need.
 //
 //   stage 1   y^T = Pi x^T.  A bf16 input IS a single piece, so the rotation takes three piece products
 //             (x times the three pieces of Pi).  The vector is the COLUMN of the MFMA: a lane loads 8
@@ -236,7 +237,7 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
     }
 
     const int64_t v_mine = blk * 256 + wave * 64 + 32 * g + vi;  // the vector this lane stores for: tile nt = g
-    // the next block's vectors are fetched while this block is finished: one load per step of stage 2
+    // the next block's vectors are fetched while this block is finished: spread over the first pass of stage 2
     const unsigned short* const next_x[2] = {x_row(blk + gridDim.x, 0), x_row(blk + gridDim.x, 1)};
     if (!PROD) {
 #pragma unroll
