@@ -100,6 +100,11 @@ def piece_products(cfg, call: str):
         if call == "quantize":
             rot = 3.0 if cfg.in_dtype == "bf16" else 6.0
             return (rot + 3.0) / 2 if prod else rot
+        if call == "dequantize" or cfg.q_per_group > 32 or cfg.d > 512:
+            # the many-query scoring kernel (also DeQuant, with the rows of Pi^T as queries): two pieces of a query
+            # coordinate against two of a centroid (three products; two for a 1-bit table) or against a sign (two)
+            cen = 0 if cfg.bits_mse == 0 else 2 if cfg.bits_mse == 1 else 3
+            return (cen + (2 if prod else 0)) / ((1 if cfg.bits_mse else 0) + (1 if prod else 0))
         return 0.0
     if getattr(cfg, "d_hi", 0):
         return 0.0
