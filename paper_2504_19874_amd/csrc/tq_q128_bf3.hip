@@ -210,9 +210,9 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
         constexpr int nt = decltype(nt_c)::value, t = decltype(t_c)::value;
         uint32_t wd[4] = {0u, 0u, 0u, 0u};
         if (MIXED && t < gs)  // uniform
-          g2h[nt] += quantise_tile<BH>(acc[nt][t], inv_hi[nt], a.cb_hi, g, wd);
+          g2h[nt] += quantise_tile_best<BH>(acc[nt][t], inv_hi[nt], a.cb_hi, g, wd);
         else
-          g2[nt] += quantise_tile<BITS>(acc[nt][t], inv[nt], a.cb, g, wd);
+          g2[nt] += quantise_tile_best<BITS>(acc[nt][t], inv[nt], a.cb, g, wd);
 #pragma unroll
         for (int pl = 0; pl < NB; ++pl) word[nt][t][pl] = wd[pl];
         if (PROD) {
@@ -365,9 +365,11 @@ hipError_t launch_one(const Q128Args& a, hipStream_t s) {
 
 }  // namespace
 
-// bf16 rows of 128 values, 16-byte aligned with a row stride that keeps them so
-bool quant128_bf3_applicable(int bits, bool prod, const void* X, int64_t ldx) {
-  if (bits < 0 || bits > 4 || (bits == 0 && !prod)) return false;
+// bf16 rows of 128 values, 16-byte aligned with a row stride that keeps them so; symmetric tables
+bool quant128_bf3_applicable(int bits, bool prod, const void* X, int64_t ldx, const Codebook& cb, const Codebook* cb_hi) {
+  if (bits < 0 || bits > (cb_hi != nullptr ? 3 : 4) || (bits == 0 && !prod && cb_hi == nullptr)) return false;
+  // from 3 bits on the decision is taken on |y|: tables symmetric about zero (what tq_build_codebook produces)
+  if (!codebook_symmetric(cb, bits) || (cb_hi != nullptr && !codebook_symmetric(*cb_hi, bits + 1))) return false;
   return (reinterpret_cast<uintptr_t>(X) & 15u) == 0 && ldx % 8 == 0;
 }
 
@@ -377,6 +379,7 @@ hipError_t launch_quant128_bf3(int bits, bool prod, const void* X, int64_t ldx, 
                                const Codebook& cb, int gs_hi, const Codebook& cb_hi, hipStream_t s) {
   if (n <= 0) return hipSuccess;
   if (gs_hi < 0 || gs_hi > 3 || (gs_hi > 0 && (bits > 3 || cb_hi.bits != bits + 1 || norm == nullptr))) return hipErrorInvalidValue;
+  if (!codebook_symmetric(cb, bits) || (gs_hi > 0 && !codebook_symmetric(cb_hi, bits + 1))) return hipErrorInvalidValue;
   Q128Args a;
   a.X = static_cast<const unsigned short*>(X); a.ldx = ldx; a.n = n; a.Pi = Pi; a.SPiT = SPiT; a.idx = idx; a.qjl = qjl;
   a.gamma = gamma; a.norm = norm; a.cb = cb; a.gs_hi = gs_hi; a.cb_hi = cb_hi;
