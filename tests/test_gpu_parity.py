@@ -220,6 +220,43 @@ def test_both_arithmetic_paths_of_large_bf16_batches(monkeypatch):
     P.check_close(xt[1].cpu().numpy(), xt[0].cpu().numpy().astype(np.float64), nu[:, None] / np.sqrt(d), "dequantize, pieces vs fp32")
 
 
+@pytest.mark.parametrize("d,bits_mse,n,kind", [(256, 2, 3000, "f32"), (512, 4, 1500, "unit"), (96, 1, 2500, "bf16")])
+def test_both_arithmetic_paths_at_other_dimensions(monkeypatch, d, bits_mse, n, kind):
+    """Every d other than 128 runs the quantiser's contractions, many-query scoring and dequantisation on the bf16
+    matrix cores (pieces); TQ_FP32_MFMA=1 keeps them on the fp32 matrix instructions.  Both must meet the oracle
+    and agree with each other."""
+    p, Pi, S, c32, t32 = setup(d, bits_mse, True)
+    x_or, x_dev, normalise = _quant_inputs(n, d, kind, 91)
+    nq = 40  # more than 32 queries per group: the many-query kernel
+    q = W.gaussian_queries(nq, d, 5, unit=False)
+    p.reserve(n, nq, 0)
+
+    def run():
+        codes = _run_prod(p, x_dev, n, normalise)
+        _check_prod(p, Pi, S, c32, t32, x_or, normalise, *codes)
+        xt = torch.zeros((n, d), dtype=torch.float32, device=DEV)
+        tq.tq_dequantize(p, *codes, xt)
+        sc = torch.zeros((nq, n), dtype=torch.float32, device=DEV)
+        tq.tq_score(p, dev(q), 1, nq, *codes, n, sc)
+        return codes, xt, sc
+
+    pieces = run()
+    monkeypatch.setenv("TQ_FP32_MFMA", "1")
+    plain = run()
+    monkeypatch.delenv("TQ_FP32_MFMA")
+    assert (words(pieces[0][0]) == words(plain[0][0])).mean() >= 0.9999
+    assert (words(pieces[0][1]) == words(plain[0][1])).mean() >= 0.999
+    # the same codes through both arithmetic paths
+    xt2 = torch.zeros((n, d), dtype=torch.float32, device=DEV)
+    sc2 = torch.zeros((nq, n), dtype=torch.float32, device=DEV)
+    tq.tq_dequantize(p, *plain[0], xt2)
+    tq.tq_score(p, dev(q), 1, nq, *plain[0], n, sc2)
+    nu = plain[0][3].cpu().numpy().astype(np.float64) if normalise else np.ones(n)
+    P.check_close(xt2.cpu().numpy(), plain[1].cpu().numpy().astype(np.float64), nu[:, None] / np.sqrt(d), "dequantize, pieces vs fp32")
+    qn = np.linalg.norm(q.astype(np.float64), axis=1)
+    P.check_close(sc2.cpu().numpy(), plain[2].cpu().numpy().astype(np.float64), qn[:, None] * nu[None, :], "scores, pieces vs fp32")
+
+
 def test_large_batches_respect_row_strides_and_leave_the_tail_alone():
     """The large-batch kernels at d = 128 with padded input and output rows, a batch that ends inside a block of
     256, and guard rows behind every output that must stay untouched."""
