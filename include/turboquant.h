@@ -196,6 +196,30 @@ tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_gr
                    int64_t lds, int32_t topk, int32_t* topk_idx, float* topk_val, void* stream);
 
 /*
+ * tq_score for callers that cannot allocate device memory or carry a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, results and error codes as tq_score,
+ * but p->workspace is ignored: the scratch memory (rotated queries or their
+ * int8 digit images, and the score matrix when scores == NULL) is a static
+ * device array inside the library, tq_score_static_scratch_bytes() bytes
+ * (16 MiB) on every GPU the library has run on, held until the process ends.
+ * The call allocates and frees nothing and calls no allocating routine.
+ *   TQ_ERR_WORKSPACE  the call needs more than the array holds:
+ *                     tq_workspace_bytes(p, 0, nq, 0), plus nq*(n_per_group+3)*4
+ *                     bytes when scores == NULL, must not exceed it.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on
+ * one GPU (two streams, two threads) race on it; serialise them.  Nothing in
+ * the array has to survive between calls and nothing is read before the call
+ * itself has written it.
+ */
+size_t tq_score_static_scratch_bytes(void);
+tq_status tq_score_static(const tq_params* p, const float* q, int64_t ldq, int32_t n_groups,
+                          int32_t q_per_group, const uint32_t* idx, const uint32_t* qjl,
+                          const float* gamma, const float* norm, int64_t n_per_group, float* scores,
+                          int64_t lds, int32_t topk, int32_t* topk_idx, float* topk_val,
+                          void* stream);
+
+/*
  * Attention read-out of a few queries over a quantised key/value cache
  * (Sec. 4.3: keys and values of past tokens are kept as codes; the paper gives
  * the value side nothing beyond DeQuant, so this is the usual read-out on the

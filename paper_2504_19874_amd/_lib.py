@@ -42,6 +42,8 @@ SIGNATURES = {
     "tq_quantize_prod": (C.c_int, [_P, _vp, C.c_int, _i64, _i64, _vp, _vp, _vp, _vp, _vp]),
     "tq_dequantize": (C.c_int, [_P, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _vp]),
     "tq_score": (C.c_int, [_P, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _i32, _vp, _vp, _vp]),
+    "tq_score_static_scratch_bytes": (C.c_size_t, []),
+    "tq_score_static": (C.c_int, [_P, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _i32, _vp, _vp, _vp]),
     "tq_attend_workspace_bytes": (C.c_size_t, [_P, _P, _i32, _i32, _i64]),
     "tq_attend": (C.c_int, [_P, _P, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, C.c_float, _vp,
                             _i64, _vp]),

@@ -174,6 +174,21 @@ def tq_score(p: Params, q: torch.Tensor, n_groups: int, q_per_group: int, idx, q
            "tq_score")
 
 
+def tq_score_static(p: Params, q: torch.Tensor, n_groups: int, q_per_group: int, idx, qjl, gamma, norm,
+                    n_per_group: int, scores: torch.Tensor | None, topk: int = 0,
+                    topk_idx: torch.Tensor | None = None, topk_val: torch.Tensor | None = None):
+    """tq_score on the library's static scratch array: p's workspace is not used and nothing is allocated."""
+    lds = scores.stride(0) if scores is not None and scores.shape[0] else n_per_group
+    _check(_lib.load().tq_score_static(C.byref(p.c), _ptr_rows(q), q.stride(0) if q.shape[0] else p.d, n_groups,
+                                       q_per_group, _ptr(idx), _ptr(qjl), _ptr(gamma), _ptr(norm), n_per_group,
+                                       _ptr_rows(scores), lds, topk, _ptr(topk_idx), _ptr(topk_val), _stream()),
+           "tq_score_static")
+
+
+def tq_score_static_scratch_bytes() -> int:
+    return int(_lib.load().tq_score_static_scratch_bytes())
+
+
 def tq_attend_workspace_bytes(pk: Params, pv: Params, n_groups: int, q_per_group: int, n_per_group: int) -> int:
     return int(_lib.load().tq_attend_workspace_bytes(C.byref(pk.c), C.byref(pv.c), n_groups, q_per_group,
                                                      n_per_group))

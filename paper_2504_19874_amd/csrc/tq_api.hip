@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "tq_attend.h"
 #include "tq_score_i8.h"
@@ -333,10 +334,15 @@ tq_status tq_dequantize(const tq_params* p, const uint32_t* idx, const uint32_t*
   return from_hip(launch_gemm(N_CODE, E_STORE_T, p->bits_mse, a, 1, static_cast<hipStream_t>(stream)));
 }
 
-tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_groups,
-                   int32_t q_per_group, const uint32_t* idx, const uint32_t* qjl, const float* gamma,
-                   const float* norm, int64_t n_per_group, float* scores, int64_t lds, int32_t topk,
-                   int32_t* topk_idx, float* topk_val, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// tq_score with the scratch memory given explicitly (the caller's workspace, or this library's static array)
+tq_status score_impl(const tq_params* p, Workspace ws, const float* q, int64_t ldq, int32_t n_groups,
+                     int32_t q_per_group, const uint32_t* idx, const uint32_t* qjl, const float* gamma,
+                     const float* norm, int64_t n_per_group, float* scores, int64_t lds, int32_t topk,
+                     int32_t* topk_idx, float* topk_val, void* stream) {
   tq_status st = check_params(p, true);
   if (st != TQ_OK) return st;
   if (n_groups < 0 || q_per_group < 0 || n_per_group < 0 || ldq < p->d || topk < 0) return TQ_ERR_INVALID_ARG;
@@ -354,7 +360,6 @@ tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_gr
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int d = p->d;
 
-  Workspace ws{static_cast<char*>(p->workspace), p->workspace_bytes, 0};
   int64_t ld_scores = lds;
   if (p->d_hi != 0) {
     // two instances over a split of the coordinates: few queries per code at d = 128 only
@@ -473,6 +478,62 @@ tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_gr
   return TQ_OK;
 }
 
+// Scratch memory of tq_score_static: one copy per GPU the library runs on, held until the process ends.
+constexpr size_t kStaticScratchBytes = size_t(16) << 20;
+__device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device, once asked for
+
+// The array's name is only a host-side handle: its address in the current device's memory has to be asked for.
+tq_status static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return TQ_ERR_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return TQ_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return TQ_ERR_HIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return TQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_groups,
+                   int32_t q_per_group, const uint32_t* idx, const uint32_t* qjl, const float* gamma,
+                   const float* norm, int64_t n_per_group, float* scores, int64_t lds, int32_t topk,
+                   int32_t* topk_idx, float* topk_val, void* stream) {
+  if (p == nullptr) return TQ_ERR_INVALID_ARG;
+  return score_impl(p, Workspace{static_cast<char*>(p->workspace), p->workspace_bytes, 0}, q, ldq, n_groups, q_per_group,
+                    idx, qjl, gamma, norm, n_per_group, scores, lds, topk, topk_idx, topk_val, stream);
+}
+
+size_t tq_score_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+tq_status tq_score_static(const tq_params* p, const float* q, int64_t ldq, int32_t n_groups,
+                          int32_t q_per_group, const uint32_t* idx, const uint32_t* qjl, const float* gamma,
+                          const float* norm, int64_t n_per_group, float* scores, int64_t lds, int32_t topk,
+                          int32_t* topk_idx, float* topk_val, void* stream) {
+  if (p == nullptr || n_groups < 0 || q_per_group < 0 || n_per_group < 0) return TQ_ERR_INVALID_ARG;
+  // the whole need of the call must fit the static array: the same sum tq_workspace_bytes gives the caller
+  const size_t need = tq_workspace_bytes(p, 0, (int64_t)n_groups * q_per_group, 0) +
+                      (scores == nullptr ? round_up((size_t)n_groups * q_per_group * (size_t)(n_per_group + 3) * sizeof(float), 256) : 0);
+  if (need > kStaticScratchBytes) return TQ_ERR_WORKSPACE;
+  void* base = nullptr;
+  const tq_status st = static_scratch(&base);
+  if (st != TQ_OK) return st;
+  return score_impl(p, Workspace{static_cast<char*>(base), kStaticScratchBytes, 0}, q, ldq, n_groups, q_per_group, idx, qjl,
+                    gamma, norm, n_per_group, scores, lds, topk, topk_idx, topk_val, stream);
+}
+
+}  // extern "C"
+
 namespace {
 struct AttendPlan {
   bool fast;  // the d = 128 kernel on the integer matrix cores takes the value codes
@@ -493,6 +554,8 @@ AttendPlan attend_plan(const tq_params* pk, const tq_params* pv, bool v_prod, in
   return pl;
 }
 }  // namespace
+
+extern "C" {
 
 size_t tq_attend_workspace_bytes(const tq_params* pk, const tq_params* pv, int32_t n_groups, int32_t q_per_group,
                                  int64_t n_per_group) {
