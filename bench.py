@@ -64,7 +64,7 @@ def build_workload(name: str):
         topk_idx=torch.zeros((cfg.nq, max(1, cfg.topk)), dtype=torch.int32, device="cuda"),
         topk_val=torch.zeros((cfg.nq, max(1, cfg.topk)), dtype=torch.float32, device="cuda"),
     )
-    p.reserve(n, cfg.nq, cfg.topk)
+    p.reserve(n, cfg.nq, 0).reserve_score(cfg.n_groups, cfg.q_per_group, cfg.n, prod, cfg.topk == 0, cfg.topk)
     return cfg, p, bufs, host_x, q
 
 

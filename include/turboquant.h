@@ -63,7 +63,7 @@
  * At d = 128, fp32 inputs and smaller batches run on the fp32 matrix
  * instructions.  All paths meet the same tolerances (indices equal to an fp32
  * evaluation except within 1e-5 of a cell boundary; values and scores within
- * 1e-4 relative).  With TQ_FP32_MFMA=1 in the environment every contraction of
+ * 1e-4 relative).  With TQ_FLAG_FP32_MFMA in params.flags every contraction of
  * tq_quantize_*, tq_dequantize and many-query tq_score stays on the fp32 matrix
  * instructions.
  */
@@ -85,6 +85,8 @@ typedef enum {
   TQ_ERR_WORKSPACE = 4    /* params.workspace is NULL or too small for the call  */
 } tq_status;
 
+/* Element type of input vectors; passed as int32_t so that any value a caller
+ * sends is rejected by a check instead of being undefined. */
 typedef enum { TQ_F32 = 0, TQ_BF16 = 1 } tq_dtype;
 
 /* Human-readable name of a status (static storage). */
@@ -103,6 +105,33 @@ const char* tq_status_string(tq_status s);
  */
 tq_status tq_build_codebook(int32_t d, int32_t bits, float* centroids, float* bounds,
                             double* cost_per_coord);
+
+/*
+ * The random rotation of Sec. 3.1: the orthogonal factor Q of a QR
+ * decomposition of a d x d matrix with i.i.d. N(0,1) entries, made unique (and
+ * Haar distributed) by negating column j of Q where R[j][j] < 0, so that R has
+ * a positive diagonal.  Host only: Householder reflections in fp64 on up to 16
+ * threads, result rounded to fp32 once.
+ *   gaussian  host, d*d doubles, row-major (the caller draws them).
+ *   Pi        host out, d*d floats, row-major; y = Pi x rotates a vector.
+ *   d in [1, 16384].
+ */
+tq_status tq_build_rotation(int32_t d, const double* gaussian, float* Pi);
+
+/*
+ * Parameter matrix of two instances over a channel split (Sec. 4.3: outlier
+ * channels form an instance of their own): out = blockdiag(block_hi, block_lo)
+ * * P, where P lists the d_hi channels in hi_channels first and the others
+ * after them, both in ascending order.  Used for Pi (blocks = the two
+ * rotations) and for S (blocks = the two sketch matrices); rotated coordinates
+ * [0, d_hi) then belong to instance hi while x keeps its channel order.  Host
+ * only, pure data movement.
+ *   hi_channels host, d_hi ascending distinct channel numbers in [0, d).
+ *   block_hi    host, d_hi*d_hi floats;  block_lo host, (d-d_hi)^2 floats.
+ *   out         host out, d*d floats, row-major.
+ */
+tq_status tq_compose_split(int32_t d, int32_t d_hi, const int32_t* hi_channels, const float* block_hi,
+                           const float* block_lo, float* out);
 
 /*
  * Global parameters of Alg. 1 / Alg. 2 for one (d, bits_mse).
@@ -126,7 +155,16 @@ typedef struct tq_params {
   const float* centroids_hi;  /* host, 2^bits_mse_hi floats: codebook of dimension d_hi */
   const float* bounds_hi;     /* host, 2^bits_mse_hi - 1 floats; `centroids`/`bounds`   */
                               /* are then the codebook of dimension d - d_hi            */
+  uint32_t flags;             /* TQ_FLAG_* bits, 0 = the library's own choice           */
 } tq_params;
+
+/* Keep every contraction of tq_quantize_*, tq_dequantize and many-query
+ * tq_score on the fp32 matrix instructions (v_mfma_f32_32x32x2_f32) instead
+ * of feeding them to the bf16 matrix cores as pieces (see "Arithmetic" at the
+ * head of this file).  Same results within the stated tolerances, about half
+ * the speed; meant for measurements against the fp32 peak and for callers who
+ * want the plain fp32 evaluation. */
+#define TQ_FLAG_FP32_MFMA 1u
 
 /*
  * Fill the derived matrices from Pi and S on the device: PiT = Pi^T,
@@ -139,20 +177,22 @@ tq_status tq_derive_params(int32_t d, const float* Pi, const float* S, float* Pi
                            float* SPiT, void* stream);
 
 /* Device scratch large enough for any call with up to n vectors (per call),
- * nq queries and this topk under these params. */
+ * nq queries and this topk under these params: an upper bound that counts a
+ * score matrix [nq][n] whenever topk > 0.  tq_score_workspace_bytes gives the
+ * (often far smaller) exact need of one tq_score call. */
 size_t tq_workspace_bytes(const tq_params* p, int64_t n, int64_t nq, int32_t topk);
 
 /*
  * Quant_mse of Alg. 1 for n vectors.
- *   x     device, n rows of d values (fp32, or bf16 bit patterns), row stride
- *         ldx elements.
+ *   x     device, n rows of d values (dtype TQ_F32: fp32, TQ_BF16: bf16 bit
+ *         patterns), row stride ldx elements.
  *   idx   device out, n * (bits_mse*d/32) words.
  *   norm  device out, n floats, or NULL.  Non-NULL: each row is divided by its
  *         L2 norm before rotation and the norm is stored (a zero row stays
  *         zero with norm 0).  NULL: rows are taken as unit-norm as given.
  * A coordinate exactly on a cell boundary goes to the upper cell.
  */
-tq_status tq_quantize_mse(const tq_params* p, const void* x, tq_dtype dtype, int64_t n,
+tq_status tq_quantize_mse(const tq_params* p, const void* x, int32_t dtype, int64_t n,
                           int64_t ldx, uint32_t* idx, float* norm, void* stream);
 
 /*
@@ -162,7 +202,7 @@ tq_status tq_quantize_mse(const tq_params* p, const void* x, tq_dtype dtype, int
  * fused d = 128 kernel applies, workspace.
  *   qjl   device out, n * (d/32) words.   gamma device out, n floats.
  */
-tq_status tq_quantize_prod(const tq_params* p, const void* x, tq_dtype dtype, int64_t n,
+tq_status tq_quantize_prod(const tq_params* p, const void* x, int32_t dtype, int64_t n,
                            int64_t ldx, uint32_t* idx, uint32_t* qjl, float* gamma, float* norm,
                            void* stream);
 
@@ -187,9 +227,20 @@ tq_status tq_dequantize(const tq_params* p, const uint32_t* idx, const uint32_t*
  *   topk     0, or 1..64: also return, per query, the indices (within the
  *            group, int32) and values of the topk largest scores, descending,
  *            equal scores ordered by lower index.  topk_idx/topk_val: device
- *            out [n_groups*q_per_group][topk]; topk_val nullable.
- * Uses workspace for the rotated queries (and for scores when scores==NULL).
+ *            out [n_groups*q_per_group][topk]; topk_val nullable.  Where
+ *            topk > n_per_group the surplus entries are index -1, value -inf.
+ *            NaN scores are never returned.
+ * Workspace (tq_score_workspace_bytes gives the exact need of a call): the
+ * rotated queries or their int8 digit images, and for top-k without a score
+ * buffer either nothing more than topk candidates per query and per range of
+ * codes (many queries per code, topk <= 16: the selection runs inside the
+ * scoring kernel and no score matrix exists anywhere) or a score matrix
+ * [nq][n_per_group] (other cases).
+ * n_groups <= 65535 and q_per_group <= 262140, else TQ_ERR_UNSUPPORTED.
  */
+size_t tq_score_workspace_bytes(const tq_params* p, int32_t n_groups, int32_t q_per_group,
+                                int64_t n_per_group, int32_t prod /* qjl will be given */,
+                                int32_t scores_given /* scores != NULL */, int32_t topk);
 tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_groups,
                    int32_t q_per_group, const uint32_t* idx, const uint32_t* qjl,
                    const float* gamma, const float* norm, int64_t n_per_group, float* scores,
@@ -280,7 +331,7 @@ tq_status tq_attend_cache(const tq_params* pk, const tq_params* pv, const float*
  * d = 128 (one or two instances) and n <= 24576, else TQ_ERR_UNSUPPORTED; x
  * 16-byte aligned with row stride a multiple of 16 bytes.  No workspace.
  */
-tq_status tq_append(const tq_params* p, const void* x, tq_dtype dtype, int64_t n, int64_t ldx,
+tq_status tq_append(const tq_params* p, const void* x, int32_t dtype, int64_t n, int64_t ldx,
                     uint32_t* idx, uint32_t* qjl, float* gamma, float* norm, int64_t first_row,
                     int64_t row_step, void* stream);
 

@@ -26,7 +26,10 @@ class TqParams(C.Structure):
         ("bits_mse_hi", C.c_int32),
         ("centroids_hi", C.c_void_p),
         ("bounds_hi", C.c_void_p),
+        ("flags", C.c_uint32),
     ]
+
+TQ_FLAG_FP32_MFMA = 1
 
 
 _P = C.POINTER(TqParams)
@@ -36,12 +39,15 @@ _vp, _i32, _i64 = C.c_void_p, C.c_int32, C.c_int64
 SIGNATURES = {
     "tq_status_string": (C.c_char_p, [C.c_int]),
     "tq_build_codebook": (C.c_int, [_i32, _i32, _vp, _vp, C.POINTER(C.c_double)]),
+    "tq_build_rotation": (C.c_int, [_i32, _vp, _vp]),
+    "tq_compose_split": (C.c_int, [_i32, _i32, _vp, _vp, _vp, _vp]),
     "tq_derive_params": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "tq_workspace_bytes": (C.c_size_t, [_P, _i64, _i64, _i32]),
     "tq_quantize_mse": (C.c_int, [_P, _vp, C.c_int, _i64, _i64, _vp, _vp, _vp]),
     "tq_quantize_prod": (C.c_int, [_P, _vp, C.c_int, _i64, _i64, _vp, _vp, _vp, _vp, _vp]),
     "tq_dequantize": (C.c_int, [_P, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _vp]),
     "tq_score": (C.c_int, [_P, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _i32, _vp, _vp, _vp]),
+    "tq_score_workspace_bytes": (C.c_size_t, [_P, _i32, _i32, _i64, _i32, _i32, _i32]),
     "tq_score_static_scratch_bytes": (C.c_size_t, []),
     "tq_score_static": (C.c_int, [_P, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _i32, _vp, _vp, _vp]),
     "tq_attend_workspace_bytes": (C.c_size_t, [_P, _P, _i32, _i32, _i64]),

@@ -97,6 +97,7 @@ class Params:
         self.c.workspace, self.c.workspace_bytes = 0, 0
         self.d_hi, self.bits_mse_hi = int(d_hi), int(bits_mse_hi)
         self.c.d_hi, self.c.bits_mse_hi, self.c.centroids_hi, self.c.bounds_hi = 0, 0, 0, 0
+        self.c.flags = 0
         if self.d_hi:
             self.centroids_hi = np.ascontiguousarray(centroids_hi, dtype=np.float32)
             self.bounds_hi = np.ascontiguousarray(bounds_hi, dtype=np.float32)
@@ -111,12 +112,33 @@ class Params:
 
     def reserve(self, n: int, nq: int = 0, topk: int = 0):
         """Size the device workspace for calls with up to n vectors / nq queries."""
-        need = tq_workspace_bytes(self, n, nq, topk)
+        return self.reserve_bytes(tq_workspace_bytes(self, n, nq, topk))
+
+    def reserve_bytes(self, need: int):
+        """Make the device workspace at least `need` bytes."""
         if self.workspace is None or self.workspace.numel() < need:
             self.workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
             self.c.workspace = self.workspace.data_ptr()
             self.c.workspace_bytes = self.workspace.numel()
         return self
+
+    def reserve_score(self, n_groups: int, q_per_group: int, n_per_group: int, prod: bool, scores_given: bool,
+                      topk: int = 0):
+        """Size the workspace for exactly one kind of tq_score call (tq_score_workspace_bytes)."""
+        need = int(_lib.load().tq_score_workspace_bytes(C.byref(self.c), n_groups, q_per_group, n_per_group, int(prod),
+                                                        int(scores_given), topk))
+        if need == 0:
+            raise TurboQuantError("tq_score_workspace_bytes: invalid arguments")
+        return self.reserve_bytes(need)
+
+    @property
+    def fp32_mfma(self) -> bool:
+        """TQ_FLAG_FP32_MFMA of the struct: every contraction on the fp32 matrix instructions."""
+        return bool(self.c.flags & _lib.TQ_FLAG_FP32_MFMA)
+
+    @fp32_mfma.setter
+    def fp32_mfma(self, on: bool):
+        self.c.flags = (self.c.flags | _lib.TQ_FLAG_FP32_MFMA) if on else (self.c.flags & ~_lib.TQ_FLAG_FP32_MFMA)
 
     @property
     def idx_words(self) -> int:

@@ -85,10 +85,13 @@ def main():
         p = tq.make_mixed_params(d, hi, cfg.bits_mse + 1, cfg.bits_mse, W.gaussian_matrix(cfg.d_hi, cfg.seed_pi),
                                  W.gaussian_matrix(d - cfg.d_hi, cfg.seed_pi + 1),
                                  W.sketch_matrix(cfg.d_hi, cfg.seed_s) if prod else None,
-                                 W.sketch_matrix(d - cfg.d_hi, cfg.seed_s + 1) if prod else None).reserve(n, nq, cfg.topk)
+                                 W.sketch_matrix(d - cfg.d_hi, cfg.seed_s + 1) if prod else None)
     else:
         S = W.sketch_matrix(d, cfg.seed_s) if prod else None
-        p = tq.make_params(d, cfg.bits_mse, W.gaussian_matrix(d, cfg.seed_pi), S).reserve(n, nq, cfg.topk)
+        p = tq.make_params(d, cfg.bits_mse, W.gaussian_matrix(d, cfg.seed_pi), S)
+    # quantisation scratch, then exactly what this configuration's scoring call takes (no score matrix
+    # where the top-k selection runs inside the scoring kernel)
+    p.reserve(n, nq, 0).reserve_score(cfg.n_groups, cfg.q_per_group, cfg.n, prod, not cfg.topk, cfg.topk)
     spv = p.scalars_per_vector
 
     # input sets: rotate through several when the working set would sit in cache

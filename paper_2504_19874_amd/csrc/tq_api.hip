@@ -2,7 +2,6 @@
 // No allocation, no synchronisation; everything is enqueued on the caller's
 // stream.
 #include <cmath>
-#include <cstdlib>
 #include <cstring>
 #include <mutex>
 
@@ -10,6 +9,22 @@
 #include "tq_score_i8.h"
 
 using namespace tq;
+
+namespace tq {
+int device_cu_count() {
+  static std::mutex m;
+  static int count[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+  std::lock_guard<std::mutex> lock(m);
+  if (count[dev] == 0) {
+    int v = 0;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+    count[dev] = v;
+  }
+  return count[dev];
+}
+}  // namespace tq
 
 namespace {
 
@@ -60,11 +75,8 @@ Codebook make_codebook(const tq_params* p) {
 
 float kappa_of(int d) { return (float)(std::sqrt(1.5707963267948966) / (double)d); }
 
-// TQ_FP32_MFMA=1 in the environment keeps every contraction on the fp32 matrix cores (read at each call)
-bool fp32_mfma_only() {
-  const char* v = std::getenv("TQ_FP32_MFMA");
-  return v != nullptr && v[0] == '1';
-}
+// TQ_FLAG_FP32_MFMA keeps every contraction of the call on the fp32 matrix instructions
+bool fp32_mfma_only(const tq_params* p) { return (p->flags & TQ_FLAG_FP32_MFMA) != 0; }
 
 tq_status from_hip(hipError_t e) { return e == hipSuccess ? TQ_OK : TQ_ERR_HIP; }
 
@@ -80,7 +92,7 @@ struct Workspace {
   }
 };
 
-tq_status quantize_common(const tq_params* p, const void* x, tq_dtype dtype, int64_t n, int64_t ldx,
+tq_status quantize_common(const tq_params* p, const void* x, int32_t dtype, int64_t n, int64_t ldx,
                           uint32_t* idx, uint32_t* qjl, float* gamma, float* norm, bool prod,
                           hipStream_t stream, int64_t out_first = 0, int64_t out_step = 1, bool scattered = false) {
   tq_status st = check_params(p, true);
@@ -114,7 +126,7 @@ tq_status quantize_common(const tq_params* p, const void* x, tq_dtype dtype, int
     if (norm == nullptr) return TQ_ERR_INVALID_ARG;
     if (!aligned16(x) || (ldx * esz) % 16 != 0) return TQ_ERR_UNSUPPORTED;
     const Codebook cb_hi = make_codebook_hi(p);
-    if (dtype == TQ_BF16 && n >= kBf3QuantRows && !fp32_mfma_only() && (!prod || aligned16(qjl)) &&
+    if (dtype == TQ_BF16 && n >= kBf3QuantRows && !fp32_mfma_only(p) && (!prod || aligned16(qjl)) &&
         quant128_bf3_applicable(p->bits_mse, prod, x, ldx, make_codebook(p), &cb_hi))
       return from_hip(launch_quant128_bf3(p->bits_mse, prod, x, ldx, n, p->Pi, prod ? p->SPiT : nullptr, idx, qjl, gamma,
                                           norm, make_codebook(p), p->d_hi / 32, make_codebook_hi(p), stream));
@@ -124,7 +136,7 @@ tq_status quantize_common(const tq_params* p, const void* x, tq_dtype dtype, int
   }
 
   // head dimension 128, a large batch of bf16 vectors: the contractions on the bf16 matrix cores
-  if (d == 128 && dtype == TQ_BF16 && n >= kBf3QuantRows && !fp32_mfma_only() && quant128_bf3_applicable(p->bits_mse, prod, x, ldx, make_codebook(p), nullptr) &&
+  if (d == 128 && dtype == TQ_BF16 && n >= kBf3QuantRows && !fp32_mfma_only(p) && quant128_bf3_applicable(p->bits_mse, prod, x, ldx, make_codebook(p), nullptr) &&
       (p->bits_mse == 0 || aligned16(idx)) && (!prod || aligned16(qjl)))
     return from_hip(launch_quant128_bf3(p->bits_mse, prod, x, ldx, n, p->Pi, prod ? p->SPiT : nullptr, idx, qjl, gamma,
                                         norm, make_codebook(p), 0, make_codebook(p), stream));
@@ -147,6 +159,7 @@ tq_status quantize_common(const tq_params* p, const void* x, tq_dtype dtype, int
   a.normalise = norm != nullptr;
   a.kappa = kappa_of(d);
   a.cb = make_codebook(p);
+  a.pieces = !fp32_mfma_only(p);
   const NKind nk = dtype == TQ_F32 ? N_F32 : N_BF16;
 
   if (!prod) {
@@ -193,6 +206,7 @@ tq_status quantize_common(const tq_params* p, const void* x, tq_dtype dtype, int
     a2.n = rows;
     a2.rownorm_out = gamma + r0;
     a2.words_out = qjl + r0 * (d / 32);
+    a2.pieces = a.pieces;
     e = launch_gemm(N_F32, E_SIGN, 0, a2, 1, stream);
     if (e != hipSuccess) return TQ_ERR_HIP;
   }
@@ -254,19 +268,19 @@ size_t tq_workspace_bytes(const tq_params* p, int64_t n, int64_t nq, int32_t top
   return bytes + 256;
 }
 
-tq_status tq_quantize_mse(const tq_params* p, const void* x, tq_dtype dtype, int64_t n, int64_t ldx,
+tq_status tq_quantize_mse(const tq_params* p, const void* x, int32_t dtype, int64_t n, int64_t ldx,
                           uint32_t* idx, float* norm, void* stream) {
   return quantize_common(p, x, dtype, n, ldx, idx, nullptr, nullptr, norm, false,
                          static_cast<hipStream_t>(stream));
 }
 
-tq_status tq_quantize_prod(const tq_params* p, const void* x, tq_dtype dtype, int64_t n, int64_t ldx,
+tq_status tq_quantize_prod(const tq_params* p, const void* x, int32_t dtype, int64_t n, int64_t ldx,
                            uint32_t* idx, uint32_t* qjl, float* gamma, float* norm, void* stream) {
   return quantize_common(p, x, dtype, n, ldx, idx, qjl, gamma, norm, true,
                          static_cast<hipStream_t>(stream));
 }
 
-tq_status tq_append(const tq_params* p, const void* x, tq_dtype dtype, int64_t n, int64_t ldx, uint32_t* idx,
+tq_status tq_append(const tq_params* p, const void* x, int32_t dtype, int64_t n, int64_t ldx, uint32_t* idx,
                     uint32_t* qjl, float* gamma, float* norm, int64_t first_row, int64_t row_step, void* stream) {
   if (first_row < 0 || row_step < 1) return TQ_ERR_INVALID_ARG;
   if (p != nullptr && p->d != 128) return TQ_ERR_UNSUPPORTED;
@@ -291,7 +305,7 @@ tq_status tq_dequantize(const tq_params* p, const uint32_t* idx, const uint32_t*
     // two instances: d = 128 kernel only; idx rows are not 16-byte multiples there
     if (norm == nullptr || idx == nullptr || p->Pi == nullptr || (prod && p->S == nullptr)) return TQ_ERR_INVALID_ARG;
     if (!aligned16(p->Pi) || (prod && (!aligned16(p->S) || !aligned16(qjl)))) return TQ_ERR_UNSUPPORTED;
-    if (n > kBf3DequantRows && !fp32_mfma_only() && p->PiT != nullptr && (!prod || p->ST != nullptr))
+    if (n > kBf3DequantRows && !fp32_mfma_only(p) && p->PiT != nullptr && (!prod || p->ST != nullptr))
       return from_hip(launch_dequant128_bf3(p->bits_mse, prod, idx, qjl, gamma, norm, p->PiT, p->ST, x_out, ldo, n,
                                             kappa_of(p->d - p->d_hi), make_codebook(p), p->d_hi / 32, kappa_of(p->d_hi),
                                             make_codebook_hi(p), static_cast<hipStream_t>(stream)));
@@ -300,7 +314,7 @@ tq_status tq_dequantize(const tq_params* p, const uint32_t* idx, const uint32_t*
                                       kappa_of(p->d_hi), make_codebook_hi(p), static_cast<hipStream_t>(stream)));
   }
   // large batches at d = 128: decoded codes straight into bf16 MFMA operands, pieces of Pi^T / S^T in LDS
-  if (p->d == 128 && n > kBf3DequantRows && !fp32_mfma_only() && dequant128_bf3_applicable(p->bits_mse, prod, make_codebook(p), x_out, ldo))
+  if (p->d == 128 && n > kBf3DequantRows && !fp32_mfma_only(p) && dequant128_bf3_applicable(p->bits_mse, prod, make_codebook(p), x_out, ldo))
     return from_hip(launch_dequant128_bf3(p->bits_mse, prod, idx, qjl, gamma, norm, p->PiT, p->ST, x_out, ldo, n,
                                           kappa_of(128), make_codebook(p), 0, 0.f, make_codebook(p), static_cast<hipStream_t>(stream)));
   if (p->d == 128 && p->Pi != nullptr && aligned16(p->Pi) && (!prod || (p->S != nullptr && aligned16(p->S))) &&
@@ -311,7 +325,7 @@ tq_status tq_dequantize(const tq_params* p, const uint32_t* idx, const uint32_t*
   }
   // x~_i[k] = <e_k, DeQuant(code i)>: the scoring contraction with the rows of Pi^T (and S^T) as the queries,
   // stored one row per code; on the bf16 matrix cores where that kernel takes the codes
-  if (!fp32_mfma_only() && score_bf3_applicable(p->bits_mse, prod, p->d, n, 1, p->d, make_codebook(p)))
+  if (!fp32_mfma_only(p) && score_bf3_applicable(p->bits_mse, prod, p->d, n, 1, p->d, make_codebook(p)))
     return from_hip(launch_score_bf3(p->bits_mse, prod, p->PiT, p->ST, p->d, p->d, idx, qjl, gamma, norm, n, 1, x_out, ldo,
                                      true, kappa_of(p->d), make_codebook(p), static_cast<hipStream_t>(stream)));
   GemmArgs a;
@@ -338,6 +352,69 @@ tq_status tq_dequantize(const tq_params* p, const uint32_t* idx, const uint32_t*
 
 namespace {
 
+// How one tq_score call is carried out and what scratch memory it takes.  tq_score follows it and
+// tq_score_workspace_bytes reports it, so the two cannot drift apart.
+struct ScorePlan {
+  enum Route { R_SPLIT_I8, R_I8, R_SMALL, R_BF3, R_GEMM } route;
+  size_t img_bytes;     // int8 digit images of the rotated queries (R_SPLIT_I8, R_I8)
+  size_t q_bytes;       // one [nq][d] fp32 matrix of rotated queries (other routes; a second one for prod)
+  int64_t ld_scores;    // row stride of a score matrix in scratch memory
+  size_t scores_bytes;  // that matrix: only when scores == NULL and top-k is not taken inside the scoring kernel
+  int ranges;           // > 0: top-k inside the scoring kernel, this many partial lists per query
+  size_t part_bytes;    // one array [nq][ranges][topk] (values; indices take the same again)
+  bool prod;
+  size_t total() const {
+    const size_t a = 256;
+    size_t t = round_up(img_bytes, a) + (q_bytes ? round_up(q_bytes, a) * (prod ? 2 : 1) : 0) + round_up(scores_bytes, a) +
+               2 * round_up(part_bytes, a);
+    return t + a;
+  }
+};
+
+ScorePlan plan_score(const tq_params* p, bool prod, int n_groups, int q_per_group, int64_t n_per_group, bool scores_given,
+                     int topk, bool codes_aligned) {
+  ScorePlan pl;
+  std::memset(&pl, 0, sizeof(pl));
+  pl.prod = prod;
+  const int d = p->d;
+  const int64_t nq = (int64_t)n_groups * q_per_group;
+  pl.ld_scores = (n_per_group + 3) / 4 * 4;
+  const size_t scratch_scores = scores_given ? 0 : (size_t)nq * pl.ld_scores * sizeof(float);
+  if (p->d_hi != 0) {
+    pl.route = ScorePlan::R_SPLIT_I8;
+    pl.img_bytes = score_i8_workspace_bytes(d, nq);
+    pl.scores_bytes = scratch_scores;
+    return pl;
+  }
+  // few queries per code; with a short code list also a few more (every block of 4 queries re-reads the
+  // codes, which costs less than the launches of the contraction path while the list is short)
+  if ((q_per_group <= 32 || (q_per_group <= 64 && n_per_group <= 16384)) && score_i8_applicable(p->bits_mse, d, make_codebook(p))) {
+    pl.route = ScorePlan::R_I8;
+    pl.img_bytes = score_i8_workspace_bytes(d, nq);
+    pl.scores_bytes = scratch_scores;
+    return pl;
+  }
+  pl.q_bytes = (size_t)nq * d * sizeof(float);
+  if (q_per_group <= 32 && d % 128 == 0 && d <= 1024 && codes_aligned) {
+    pl.route = ScorePlan::R_SMALL;
+    pl.scores_bytes = scratch_scores;
+    return pl;
+  }
+  if (n_per_group > 0 && !fp32_mfma_only(p) &&
+      score_bf3_applicable(p->bits_mse, prod, d, n_per_group, n_groups, q_per_group, make_codebook(p))) {
+    pl.route = ScorePlan::R_BF3;
+    pl.ranges = topk > 0 ? score_bf3_topk_ranges(p->bits_mse, prod, n_per_group, n_groups, q_per_group, topk) : 0;
+    if (pl.ranges > 0)
+      pl.part_bytes = (size_t)nq * pl.ranges * topk * sizeof(float);
+    else
+      pl.scores_bytes = scratch_scores;
+    return pl;
+  }
+  pl.route = ScorePlan::R_GEMM;
+  pl.scores_bytes = scratch_scores;
+  return pl;
+}
+
 // tq_score with the scratch memory given explicitly (the caller's workspace, or this library's static array)
 tq_status score_impl(const tq_params* p, Workspace ws, const float* q, int64_t ldq, int32_t n_groups,
                      int32_t q_per_group, const uint32_t* idx, const uint32_t* qjl, const float* gamma,
@@ -346,7 +423,8 @@ tq_status score_impl(const tq_params* p, Workspace ws, const float* q, int64_t l
   tq_status st = check_params(p, true);
   if (st != TQ_OK) return st;
   if (n_groups < 0 || q_per_group < 0 || n_per_group < 0 || ldq < p->d || topk < 0) return TQ_ERR_INVALID_ARG;
-  if (topk > 64 || n_per_group > 0x7fffffff) return TQ_ERR_UNSUPPORTED;
+  // groups and blocks of four queries are grid dimensions of the few-query kernels
+  if (topk > 64 || n_per_group > 0x7fffffff || n_groups > 65535 || q_per_group > 4 * 65535) return TQ_ERR_UNSUPPORTED;
   const int64_t nq = (int64_t)n_groups * q_per_group;
   if (nq == 0) return TQ_OK;
   const bool prod = qjl != nullptr;
@@ -357,124 +435,107 @@ tq_status score_impl(const tq_params* p, Workspace ws, const float* q, int64_t l
   if (scores != nullptr && lds < n_per_group) return TQ_ERR_INVALID_ARG;
   if (topk > 0 && topk_idx == nullptr) return TQ_ERR_INVALID_ARG;
   if (ldq % 4 != 0 || !aligned16(q) || !aligned16(p->Pi) || (prod && !aligned16(p->S))) return TQ_ERR_UNSUPPORTED;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  const int d = p->d;
-
-  int64_t ld_scores = lds;
   if (p->d_hi != 0) {
     // two instances over a split of the coordinates: few queries per code at d = 128 only
-    if (norm == nullptr || (n_per_group > 0 && idx == nullptr)) return TQ_ERR_INVALID_ARG;
+    if (norm == nullptr) return TQ_ERR_INVALID_ARG;
     if (q_per_group > 32 || !score_i8_split_applicable(p->bits_mse, make_codebook(p), make_codebook_hi(p)))
       return TQ_ERR_UNSUPPORTED;
-    void* img = ws.take(score_i8_workspace_bytes(d, nq));
-    if (img == nullptr) return TQ_ERR_WORKSPACE;
-    if (scores == nullptr) {
-      ld_scores = (n_per_group + 3) / 4 * 4;
-      scores = static_cast<float*>(ws.take((size_t)nq * ld_scores * sizeof(float)));
-      if (scores == nullptr) return TQ_ERR_WORKSPACE;
-    }
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int d = p->d;
+  const ScorePlan pl = plan_score(p, prod, n_groups, q_per_group, n_per_group, scores != nullptr, topk,
+                                  aligned16(idx) && (!prod || aligned16(qjl)));
+
+  // all scratch memory is taken before the first launch
+  void* img = pl.img_bytes ? ws.take(pl.img_bytes) : nullptr;
+  float* qr = pl.q_bytes ? static_cast<float*>(ws.take(pl.q_bytes)) : nullptr;
+  float* qs = pl.q_bytes && prod ? static_cast<float*>(ws.take(pl.q_bytes)) : nullptr;
+  int64_t ld_scores = lds;
+  if (scores == nullptr && pl.scores_bytes) {
+    ld_scores = pl.ld_scores;
+    scores = static_cast<float*>(ws.take(pl.scores_bytes));
+    if (scores == nullptr) return TQ_ERR_WORKSPACE;
+  }
+  float* part_val = pl.part_bytes ? static_cast<float*>(ws.take(pl.part_bytes)) : nullptr;
+  int32_t* part_idx = pl.part_bytes ? static_cast<int32_t*>(ws.take(pl.part_bytes)) : nullptr;
+  if ((pl.img_bytes && img == nullptr) || (pl.q_bytes && (qr == nullptr || (prod && qs == nullptr))) ||
+      (pl.part_bytes && (part_val == nullptr || part_idx == nullptr)))
+    return TQ_ERR_WORKSPACE;
+
+  if (pl.route == ScorePlan::R_SPLIT_I8) {
     if (launch_score_i8_split(p->bits_mse, prod, p->Pi, p->S, p->PiT, p->ST, q, ldq, img, idx, qjl, gamma, norm, scores, ld_scores,
                               n_per_group, n_groups, q_per_group, p->d_hi / 32, kappa_of(d - p->d_hi),
                               kappa_of(p->d_hi), make_codebook(p), make_codebook_hi(p), s) != hipSuccess)
       return TQ_ERR_HIP;
-    if (topk > 0 &&
-        launch_topk(scores, nq, n_per_group, ld_scores, topk, topk_idx, topk_val, s) != hipSuccess)
-      return TQ_ERR_HIP;
-    return TQ_OK;
-  }
-  // few queries per code; with a short code list also a few more (every block of 4 queries re-reads the
-  // codes, which costs less than the launches of the contraction path while the list is short)
-  const bool small_i8 = (q_per_group <= 32 || (q_per_group <= 64 && n_per_group <= 16384)) &&
-                        score_i8_applicable(p->bits_mse, d, make_codebook(p));
-  if (small_i8) {
-    // few queries per code: masked sums of fixed-point query digits on the int8 matrix cores (at
-    // d = 128 one kernel; otherwise a preparation kernel rotates the queries and writes their digits)
-    void* img = ws.take(score_i8_workspace_bytes(d, nq));
-    if (img == nullptr) return TQ_ERR_WORKSPACE;
-    if (scores == nullptr) {
-      ld_scores = (n_per_group + 3) / 4 * 4;
-      scores = static_cast<float*>(ws.take((size_t)nq * ld_scores * sizeof(float)));
-      if (scores == nullptr) return TQ_ERR_WORKSPACE;
-    }
+  } else if (pl.route == ScorePlan::R_I8) {
+    // masked sums of fixed-point query digits on the int8 matrix cores (at d = 128 one kernel; otherwise a
+    // preparation kernel rotates the queries and writes their digits)
     if (launch_score_i8(p->bits_mse, prod, p->Pi, p->S, p->PiT, p->ST, q, ldq, img, idx, qjl, gamma, norm, scores, ld_scores,
                         n_per_group, d, n_groups, q_per_group, kappa_of(d), make_codebook(p), s) != hipSuccess)
       return TQ_ERR_HIP;
-    if (topk > 0 &&
-        launch_topk(scores, nq, n_per_group, ld_scores, topk, topk_idx, topk_val, s) != hipSuccess)
-      return TQ_ERR_HIP;
-    return TQ_OK;
-  }
-  float* qr = static_cast<float*>(ws.take((size_t)nq * d * sizeof(float)));
-  float* qs = prod ? static_cast<float*>(ws.take((size_t)nq * d * sizeof(float))) : nullptr;
-  if (qr == nullptr || (prod && qs == nullptr)) return TQ_ERR_WORKSPACE;
-  if (scores == nullptr) {
-    ld_scores = (n_per_group + 3) / 4 * 4;
-    scores = static_cast<float*>(ws.take((size_t)nq * ld_scores * sizeof(float)));
-    if (scores == nullptr) return TQ_ERR_WORKSPACE;
-  }
-
-  // queries into the rotated basis and the sketch basis: Pi q and S q
-  if (nq <= 64 && d <= 4096) {
-    if (launch_matvec_small(d, (int)nq, p->Pi, prod ? p->S : nullptr, q, ldq, qr, qs, s) != hipSuccess)
-      return TQ_ERR_HIP;
   } else {
-    GemmArgs a;
-    std::memset(&a, 0, sizeof(a));
-    a.W1 = p->Pi;
-    a.ldw = d;
-    a.M = d;
-    a.d = d;
-    a.segs = 1;
-    a.X = q;
-    a.ldx = ldq;
-    a.n = nq;
-    a.out = qr;
-    a.ldo = d;
-    if (launch_gemm(N_F32, E_STORE_T, 0, a, 1, s) != hipSuccess) return TQ_ERR_HIP;
-    if (prod) {
-      a.W1 = p->S;
-      a.out = qs;
+    // queries into the rotated basis and the sketch basis: Pi q and S q
+    if (nq <= 64 && d <= 4096) {
+      if (launch_matvec_small(d, (int)nq, p->Pi, prod ? p->S : nullptr, q, ldq, qr, qs, s) != hipSuccess)
+        return TQ_ERR_HIP;
+    } else {
+      GemmArgs a;
+      std::memset(&a, 0, sizeof(a));
+      a.W1 = p->Pi;
+      a.ldw = d;
+      a.M = d;
+      a.d = d;
+      a.segs = 1;
+      a.X = q;
+      a.ldx = ldq;
+      a.n = nq;
+      a.out = qr;
+      a.ldo = d;
       if (launch_gemm(N_F32, E_STORE_T, 0, a, 1, s) != hipSuccess) return TQ_ERR_HIP;
+      if (prod) {
+        a.W1 = p->S;
+        a.out = qs;
+        if (launch_gemm(N_F32, E_STORE_T, 0, a, 1, s) != hipSuccess) return TQ_ERR_HIP;
+      }
+    }
+    if (n_per_group > 0 && pl.route == ScorePlan::R_SMALL) {
+      // few queries per code: stream the codes once, lane = key
+      if (launch_score_small(p->bits_mse, prod, qr, qs, idx, qjl, gamma, norm, scores, ld_scores, n_per_group,
+                             d, n_groups, q_per_group, kappa_of(d), make_codebook(p), s) != hipSuccess)
+        return TQ_ERR_HIP;
+    } else if (pl.route == ScorePlan::R_BF3) {
+      // many queries per code: dense contraction on the bf16 matrix cores, every fp32 factor as two bf16 pieces;
+      // with top-k wanted the kernel keeps the k best pairs of every query itself and a small kernel joins them
+      if (launch_score_bf3(p->bits_mse, prod, qr, qs, q_per_group, d, idx, qjl, gamma, norm, n_per_group, n_groups, scores,
+                           ld_scores, false, kappa_of(d), make_codebook(p), s, pl.ranges > 0 ? topk : 0, part_val,
+                           part_idx) != hipSuccess)
+        return TQ_ERR_HIP;
+      if (pl.ranges > 0)
+        return from_hip(launch_topk_merge(part_val, part_idx, nq, pl.ranges, topk, topk_idx, topk_val, s));
+    } else if (n_per_group > 0) {
+      GemmArgs a;
+      std::memset(&a, 0, sizeof(a));
+      a.W1 = qr;
+      a.W2 = qs;
+      a.ldw = d;
+      a.w_group_stride = (int64_t)q_per_group * d;
+      a.M = q_per_group;
+      a.d = d;
+      a.segs = prod ? 2 : 1;
+      a.n = n_per_group;
+      a.idx = idx;
+      a.qjl = qjl;
+      a.gamma = gamma;
+      a.scale_in = norm;
+      a.out = scores;
+      a.ldo = ld_scores;
+      a.out_group_stride = (int64_t)q_per_group * ld_scores;
+      a.kappa = kappa_of(d);
+      a.cb = make_codebook(p);
+      if (launch_gemm(N_CODE, E_STORE_N, p->bits_mse, a, n_groups, s) != hipSuccess) return TQ_ERR_HIP;
     }
   }
-  const bool small = q_per_group <= 32 && d % 128 == 0 && d <= 1024 && aligned16(idx) &&
-                     (!prod || aligned16(qjl));
-  if (n_per_group > 0 && small) {
-    // few queries per code: stream the codes once, lane = key
-    if (launch_score_small(p->bits_mse, prod, qr, qs, idx, qjl, gamma, norm, scores, ld_scores, n_per_group,
-                           d, n_groups, q_per_group, kappa_of(d), make_codebook(p), s) != hipSuccess)
-      return TQ_ERR_HIP;
-  } else if (n_per_group > 0 && !fp32_mfma_only() && score_bf3_applicable(p->bits_mse, prod, d, n_per_group, n_groups, q_per_group, make_codebook(p))) {
-    // many queries per code: dense contraction on the bf16 matrix cores, every fp32 factor as three bf16 pieces
-    if (launch_score_bf3(p->bits_mse, prod, qr, qs, q_per_group, d, idx, qjl, gamma, norm, n_per_group, n_groups, scores,
-                         ld_scores, false, kappa_of(d), make_codebook(p), s) != hipSuccess)
-      return TQ_ERR_HIP;
-  } else if (n_per_group > 0) {
-    GemmArgs a;
-    std::memset(&a, 0, sizeof(a));
-    a.W1 = qr;
-    a.W2 = qs;
-    a.ldw = d;
-    a.w_group_stride = (int64_t)q_per_group * d;
-    a.M = q_per_group;
-    a.d = d;
-    a.segs = prod ? 2 : 1;
-    a.n = n_per_group;
-    a.idx = idx;
-    a.qjl = qjl;
-    a.gamma = gamma;
-    a.scale_in = norm;
-    a.out = scores;
-    a.ldo = ld_scores;
-    a.out_group_stride = (int64_t)q_per_group * ld_scores;
-    a.kappa = kappa_of(d);
-    a.cb = make_codebook(p);
-    if (launch_gemm(N_CODE, E_STORE_N, p->bits_mse, a, n_groups, s) != hipSuccess) return TQ_ERR_HIP;
-  }
-  if (topk > 0) {
-    if (launch_topk(scores, nq, n_per_group, ld_scores, topk, topk_idx, topk_val, s) != hipSuccess)
-      return TQ_ERR_HIP;
-  }
+  if (topk > 0) return from_hip(launch_topk(scores, nq, n_per_group, ld_scores, topk, topk_idx, topk_val, s));
   return TQ_OK;
 }
 
@@ -482,7 +543,6 @@ tq_status score_impl(const tq_params* p, Workspace ws, const float* q, int64_t l
 constexpr size_t kStaticScratchBytes = size_t(16) << 20;
 __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
-constexpr int kMaxDevices = 64;
 std::mutex g_scratch_mutex;
 void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device, once asked for
 
@@ -514,6 +574,17 @@ tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_gr
                     idx, qjl, gamma, norm, n_per_group, scores, lds, topk, topk_idx, topk_val, stream);
 }
 
+size_t tq_score_workspace_bytes(const tq_params* p, int32_t n_groups, int32_t q_per_group, int64_t n_per_group,
+                                int32_t prod, int32_t scores_given, int32_t topk) {
+  if (p == nullptr || p->d <= 0 || p->bits_mse < 0 || p->bits_mse > 4 || n_groups < 0 || q_per_group < 0 || n_per_group < 0 ||
+      topk < 0 || topk > 64 || p->centroids == nullptr || (p->bits_mse > 0 && p->bounds == nullptr))
+    return 0;
+  // codes that are not 16-byte aligned can take a route with the smaller need; report the larger
+  const size_t a = plan_score(p, prod != 0, n_groups, q_per_group, n_per_group, scores_given != 0, topk, true).total();
+  const size_t b = plan_score(p, prod != 0, n_groups, q_per_group, n_per_group, scores_given != 0, topk, false).total();
+  return a > b ? a : b;
+}
+
 size_t tq_score_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 tq_status tq_score_static(const tq_params* p, const float* q, int64_t ldq, int32_t n_groups,
@@ -521,9 +592,9 @@ tq_status tq_score_static(const tq_params* p, const float* q, int64_t ldq, int32
                           const float* norm, int64_t n_per_group, float* scores, int64_t lds, int32_t topk,
                           int32_t* topk_idx, float* topk_val, void* stream) {
   if (p == nullptr || n_groups < 0 || q_per_group < 0 || n_per_group < 0) return TQ_ERR_INVALID_ARG;
-  // the whole need of the call must fit the static array: the same sum tq_workspace_bytes gives the caller
-  const size_t need = tq_workspace_bytes(p, 0, (int64_t)n_groups * q_per_group, 0) +
-                      (scores == nullptr ? round_up((size_t)n_groups * q_per_group * (size_t)(n_per_group + 3) * sizeof(float), 256) : 0);
+  // the whole need of the call must fit the static array
+  const size_t need = tq_score_workspace_bytes(p, n_groups, q_per_group, n_per_group, qjl != nullptr, scores != nullptr, topk);
+  if (need == 0) return TQ_ERR_INVALID_ARG;
   if (need > kStaticScratchBytes) return TQ_ERR_WORKSPACE;
   void* base = nullptr;
   const tq_status st = static_scratch(&base);

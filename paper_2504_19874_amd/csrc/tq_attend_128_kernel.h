@@ -380,13 +380,8 @@ hipError_t launch_attend128_one(const ScoreI8Args& ka, const AttendArgs& a, cons
                                 int n_groups, hipStream_t s) {
   constexpr int lds = attend128_lds(KB, VB, VKIND != 0, FUSED);
   static_assert(I8_TABLE_BYTES + lds <= 160 * 1024, "LDS budget");
-  static bool attr_done = false;  // per instantiation: the limit has to be raised once
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend128_kernel<KB, KPROD, VB, VKIND, FUSED>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static LdsLimit lds_limit;  // per instantiation: the limit is raised once per device
+  if (const hipError_t e = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&attend128_kernel<KB, KPROD, VB, VKIND, FUSED>), lds); e != hipSuccess) return e;
   const dim3 grid(a.nchunks, n_groups, (a.q_per_group + 3) / 4);
   hipLaunchKernelGGL((attend128_kernel<KB, KPROD, VB, VKIND, FUSED>), grid, dim3(512), lds, s, ka, a, cf, cfh);
   return hipGetLastError();

@@ -451,20 +451,16 @@ __global__ __launch_bounds__(512) void dequant128_kernel(const Dequant128Args a)
 static int grid_128(int64_t n) {
   const int64_t blocks = (n + 31) / 32;
   int64_t g = (blocks + 7) / 8;
-  if (g > 256) g = 256;  // one workgroup per compute unit
+  const int64_t cus = device_cu_count();
+  if (g > cus) g = cus;  // one workgroup per compute unit
   return (int)(g < 1 ? 1 : g);
 }
 
 template <int BITS, bool PROD, bool BF16IN, bool MIXED>
 static hipError_t launch_q(const Quant128Args& a, hipStream_t s) {
   const size_t smem = (size_t)(PROD ? 2 : 1) * D * PAD_LD * sizeof(float);
-  static bool attr_done = false;  // per instantiation
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant128_kernel<BITS, PROD, BF16IN, MIXED>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static LdsLimit lds_limit;  // per instantiation: the limit is raised once per device
+  if (const hipError_t e = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&quant128_kernel<BITS, PROD, BF16IN, MIXED>), (int)smem); e != hipSuccess) return e;
   hipLaunchKernelGGL((quant128_kernel<BITS, PROD, BF16IN, MIXED>), dim3(grid_128(a.n)), dim3(512), smem, s, a);
   return hipGetLastError();
 }
@@ -509,13 +505,8 @@ hipError_t launch_quant128(int bits, bool prod, bool bf16, const void* X, int64_
 template <int BITS, bool PROD, bool MIXED>
 static hipError_t launch_dm(const Dequant128Args& a, hipStream_t s) {
   const size_t smem = (size_t)(PROD ? 2 : 1) * D * D * sizeof(float);
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dequant128_kernel<BITS, PROD, MIXED>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static LdsLimit lds_limit;  // per instantiation: the limit is raised once per device
+  if (const hipError_t e = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&dequant128_kernel<BITS, PROD, MIXED>), (int)smem); e != hipSuccess) return e;
   hipLaunchKernelGGL((dequant128_kernel<BITS, PROD, MIXED>), dim3(grid_128(a.n)), dim3(512), smem, s, a);
   return hipGetLastError();
 }

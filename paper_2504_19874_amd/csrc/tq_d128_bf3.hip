@@ -311,15 +311,10 @@ template <int BITS, bool PROD, bool MIXED>
 hipError_t launch_one(const Dq128Args& a, hipStream_t s) {
   constexpr int MATS = (BITS > 0 || MIXED ? 1 : 0) + (PROD ? 1 : 0);
   constexpr int lds = MATS * 2 * MAT_ELEMS * 2 + (32 + 256) * 4;  // matrices, centroid tables, column flags
-  static bool attr_done = false;  // per instantiation: the limit has to be raised once
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dequant128_bf3_kernel<BITS, PROD, MIXED>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
-  const int64_t blocks = (a.n + 255) / 256;
-  hipLaunchKernelGGL((dequant128_bf3_kernel<BITS, PROD, MIXED>), dim3((unsigned)(blocks < 256 ? blocks : 256)), dim3(256), lds, s, a);
+  static LdsLimit lds_limit;  // per instantiation: the limit is raised once per device
+  if (const hipError_t e = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&dequant128_bf3_kernel<BITS, PROD, MIXED>), lds); e != hipSuccess) return e;
+  const int64_t blocks = (a.n + 255) / 256, cus = device_cu_count();  // one workgroup per compute unit
+  hipLaunchKernelGGL((dequant128_bf3_kernel<BITS, PROD, MIXED>), dim3((unsigned)(blocks < cus ? blocks : cus)), dim3(256), lds, s, a);
   return hipGetLastError();
 }
 

@@ -153,13 +153,8 @@ __global__ __launch_bounds__(512) void dequant128_small_kernel(const DequantSmal
 template <int BITS, bool PROD, bool MIXED>
 static hipError_t launch_one(const DequantSmallArgs& a, hipStream_t s) {
   constexpr int lds = 4 * 64 * 64 * (int)sizeof(float);  // with the static tables just above the 64 KB default limit
-  static bool attr_done = false;  // per instantiation
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dequant128_small_kernel<BITS, PROD, MIXED>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static LdsLimit lds_limit;  // per instantiation: the limit is raised once per device
+  if (const hipError_t e = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&dequant128_small_kernel<BITS, PROD, MIXED>), lds); e != hipSuccess) return e;
   hipLaunchKernelGGL((dequant128_small_kernel<BITS, PROD, MIXED>), dim3((unsigned)((a.n + 31) / 32)), dim3(512), lds, s, a);
   return hipGetLastError();
 }

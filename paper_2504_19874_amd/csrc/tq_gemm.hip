@@ -499,11 +499,6 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
   }
 }
 
-static bool gemm_uses_pieces() {
-  const char* const env = std::getenv("TQ_FP32_MFMA");
-  return !(env != nullptr && env[0] == '1');
-}
-
 template <int NKIND, int EKIND, int BITS, int NP = 0>
 static hipError_t launch_one(const GemmArgs& a, int n_groups, hipStream_t stream) {
   const int tiles_m = (a.M + TM - 1) / TM;
@@ -515,13 +510,8 @@ static hipError_t launch_one(const GemmArgs& a, int n_groups, hipStream_t stream
   const int per_xcd = (total + XCDS - 1) / XCDS;
   dim3 grid(per_xcd * XCDS, n_groups, 1);
   constexpr int lds_bytes = NP > 0 ? (TM + TN) * P_LD * 2 : 2 * (TM + TN) * LDS_LD * (int)sizeof(float);  // above the 64 KB default limit
-  static bool attr_done = false;  // per instantiation: the limit has to be raised once
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<NKIND, EKIND, BITS, NP>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static LdsLimit lds_limit;  // per instantiation: the limit is raised once per device
+  if (const hipError_t e = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&gemm_kernel<NKIND, EKIND, BITS, NP>), lds_bytes); e != hipSuccess) return e;
   hipLaunchKernelGGL((gemm_kernel<NKIND, EKIND, BITS, NP>), grid, dim3(256), lds_bytes, stream, a, tiles_m,
                      tiles_n, per_xcd);
   return hipGetLastError();
@@ -542,9 +532,9 @@ static hipError_t launch_bits(int bits, const GemmArgs& a, int g, hipStream_t s)
 hipError_t launch_gemm(NKind nk, EKind ek, int bits, const GemmArgs& a, int n_groups,
                        hipStream_t stream) {
   // only the combinations the library uses are instantiated
-  // the quantiser's two contractions on the bf16 matrix cores unless TQ_FP32_MFMA=1: the rotation with three
-  // pieces (fp32 accuracy), the sketch (signs only) with two
-  const bool pieces = gemm_uses_pieces();
+  // the quantiser's two contractions on the bf16 matrix cores when the caller asks for pieces: the rotation with
+  // three pieces (fp32 accuracy), the sketch (signs only) with two
+  const bool pieces = a.pieces != 0;
   if (pieces && nk == N_F32 && ek == E_QUANT) return launch_bits<N_F32, E_QUANT, 3>(bits, a, n_groups, stream);
   if (pieces && nk == N_BF16 && ek == E_QUANT) return launch_bits<N_BF16, E_QUANT, 3>(bits, a, n_groups, stream);
   if (pieces && nk == N_F32 && ek == E_SIGN) return launch_one<N_F32, E_SIGN, 0, 2>(a, n_groups, stream);

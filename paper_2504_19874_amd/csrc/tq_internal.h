@@ -5,9 +5,31 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "../../include/turboquant.h"
 
 namespace tq {
+
+constexpr int kMaxDevices = 64;
+
+// Compute units of the current device (asked once per device; 256 when the query fails).
+int device_cu_count();
+
+// A kernel that needs more dynamic LDS than the default limit has the limit raised once per
+// device and instantiation; concurrent first calls from several host threads are serialised.
+struct LdsLimit {
+  std::once_flag once[kMaxDevices];
+  hipError_t err[kMaxDevices];
+};
+inline hipError_t raise_lds_limit(LdsLimit& st, const void* kernel, int bytes) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::call_once(st.once[dev], [&] {
+    st.err[dev] = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  });
+  return st.err[dev];
+}
 
 // Codebook of Alg. 1 passed to kernels by value (lives in scalar registers).
 struct Codebook {
@@ -57,6 +79,7 @@ struct GemmArgs {
   uint32_t* words_out;
   float* resid_out;  // E_QUANT: y - c[idx], n rows of d floats, nullable
   float kappa;       // sqrt(pi/2)/d
+  int pieces;        // E_QUANT / E_SIGN: multiply bf16 pieces of the fp32 factors instead of the fp32 values
   Codebook cb;
 };
 
@@ -121,12 +144,19 @@ hipError_t launch_score_i8(int bits, bool prod, const float* Pi, const float* S,
                            const float* norm, float* scores, int64_t lds, int64_t n, int d, int n_groups,
                            int q_per_group, float kappa, const Codebook& cb, hipStream_t stream);
 
-// many queries per code on the bf16 matrix cores, fp32 factors as three bf16 pieces (tq_score_bf3.hip)
+// many queries per code on the bf16 matrix cores, fp32 factors as two bf16 pieces (tq_score_bf3.hip)
 bool score_bf3_applicable(int bits, bool prod, int d, int64_t n, int n_groups, int q_per_group, const Codebook& cb);
 hipError_t launch_score_bf3(int bits, bool prod, const float* qr, const float* qs, int q_per_group, int d,
                             const uint32_t* idx, const uint32_t* qjl, const float* gamma, const float* norm, int64_t n,
                             int n_groups, float* out, int64_t ldo, bool transposed, float kappa, const Codebook& cb,
-                            hipStream_t s);  // transposed: out[code][query] (queries = rows of Pi^T: dequantisation)
+                            hipStream_t s, int topk = 0, float* part_val = nullptr, int32_t* part_idx = nullptr);
+// transposed: out[code][query] (queries = rows of Pi^T: dequantisation).  topk in 1..16 (not transposed): the
+// kernel also keeps the topk best (score, index) pairs of every query per range of code tiles and writes them
+// to part_val / part_idx [n_groups * q_per_group][ranges][topk], ranges = score_bf3_topk_ranges(...); out may
+// then be NULL.  launch_topk_merge joins the ranges (descending, equal scores by lower index, -1 past n).
+int score_bf3_topk_ranges(int bits, bool prod, int64_t n, int n_groups, int q_per_group, int topk);
+hipError_t launch_topk_merge(const float* part_val, const int32_t* part_idx, int64_t rows, int ranges, int k,
+                             int32_t* out_idx, float* out_val, hipStream_t s);
 
 // codec stages
 hipError_t launch_stage_pack(const Codebook& cb, int d, const float* y, int64_t n, uint32_t* idx,

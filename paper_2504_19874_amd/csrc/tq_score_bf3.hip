@@ -19,11 +19,31 @@
 // (bit planes -> bucket number -> table of pieces in LDS, or straight to +-1).  Wavefront (wm, wn) owns rows
 // 64 wm .. and columns 64 wn .. of the tile: 2 x 2 sub-tiles, one accumulator set per segment (the sign
 // segment is scaled per code by kappa gamma, so it cannot share the accumulator of the first).
+//
+// Top-k without a score matrix (TOPK): a workgroup owns one block of queries and a contiguous range of code
+// tiles, which it walks with the k-loop above; the k best (score, index) pairs of every query row so far live
+// in LDS, sorted.  After a tile, a score enters the selection only if it reaches the row's k-th best: one
+// compare per score in the steady state.  The few that do are queued, per 32 x 32 sub-tile, in the (idle)
+// staging buffers, four queues per wavefront by row class, and a group of 16 lanes per queue inserts them
+// one by one: lane j of the group rewrites slot j of the row's sorted list from slots j - 1 and j, so an
+// insertion is two reads and a write with no reduction.  Wavefronts that share query rows take turns.  The
+// lists of all ranges are then joined by topk_merge_kernel.  Order everywhere: larger score first, equal
+// scores by lower index, so the result is the one a full sort of the score matrix gives.
+#include <cstring>
+
 #include "tq_bf3.h"
 
 namespace tq {
 
 namespace {
+
+constexpr int KL = 16;       // list slots per query row in the fused top-k (k <= KL): one lane of a group each
+constexpr int QCAP = 256;    // entries per candidate queue: 8 rows x 32 columns of a sub-tile
+constexpr int QBYTES = 4 * QCAP * 8;  // a wavefront's four queues
+
+__device__ __forceinline__ bool better(float va, int ia, float vb, int ib) {
+  return va > vb || (va == vb && ia < ib);
+}
 
 
 constexpr int KT = 16;  // k per step; queries per tile TM: 128 or 256, codes per tile TN: 256 or 128 (template parameters)
@@ -41,7 +61,11 @@ struct Cfg {
   static constexpr int B_ELEMS = (PC + (PROD ? 1 : 0)) * TN * LDK;
   static constexpr int BUF_ELEMS = A_ELEMS + B_ELEMS;
   static constexpr int LDS_BYTES = 2 * BUF_ELEMS * 2 + 16 * 8;  // two buffers, then the piece table
-  static constexpr bool FITS = LDS_BYTES <= 156 * 1024;
+  // fused top-k: the candidate queues share the staging buffers' space (made large enough for them), then the
+  // piece table, then per query row KL (score, index) slots
+  static constexpr int STAGE_BYTES_TOPK = 2 * BUF_ELEMS * 2 > 8 * QBYTES ? 2 * BUF_ELEMS * 2 : 8 * QBYTES;
+  static constexpr int LDS_BYTES_TOPK = STAGE_BYTES_TOPK + 16 * 8 + TM * KL * 8;
+  static constexpr bool FITS = LDS_BYTES_TOPK <= 156 * 1024;
 };
 
 struct Bf3Args {
@@ -59,9 +83,18 @@ struct Bf3Args {
   int transposed;
   float kappa;
   Codebook cb;
+  // fused top-k (TOPK kernels): workgroup w of a 1-D grid owns query block w_qb and code tiles [t0, t1) of range w_r
+  int topk;          // 1..KL
+  int groups;
+  int ranges;        // code-tile ranges per query block
+  int qblocks;       // query blocks per group
+  int tiles_n;       // code tiles per group
+  int xcd_split;     // > 0: query block from the workgroup's XCD residue (see launch_tile)
+  float* part_val;   // [groups * M][ranges][topk]
+  int32_t* part_idx;
 };
 
-template <int BITS, bool PROD, int TM, int TN>
+template <int BITS, bool PROD, int TM, int TN, bool TOPK>
 __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
   using C = Cfg<BITS, PROD, TM, TN>;
   constexpr int CP = TN / 32;  // coordinates of one code a thread decodes per step: 8 or 4
@@ -70,16 +103,46 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
   constexpr int AR = TM / 128;  // 16-byte pieces of a query tile row set a thread stages per segment
   constexpr int NB = BITS > 0 ? BITS : 1;
   extern __shared__ __attribute__((aligned(16))) unsigned short lds_s[];
-  uint2* const table_s = reinterpret_cast<uint2*>(lds_s + 2 * C::BUF_ELEMS);  // [16]: pieces of centroid k
+  constexpr int STAGE_ELEMS = TOPK ? C::STAGE_BYTES_TOPK / 2 : 2 * C::BUF_ELEMS;
+  uint2* const table_s = reinterpret_cast<uint2*>(lds_s + STAGE_ELEMS);  // [16]: pieces of centroid k
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave % C::WM, wn = wave / C::WM;
-  const int group = blockIdx.z;
-  const int64_t n0 = (int64_t)blockIdx.x * TN;
-  const int m0 = blockIdx.y * TM;
   const int gw = a.d >> 5;  // coordinate groups per code
+  int group, m0, range = 0;
+  int64_t tile_begin, tile_end;
+  if (TOPK) {
+    // workgroup -> (query block, range).  Workgroups are dealt to the 8 XCDs in turn; with xcd_split the
+    // query block follows the XCD residue, so the workgroups that share an L2 share their queries
+    const int w = blockIdx.x;
+    const int nqb = a.qblocks * a.groups;
+    int qb;
+    if (a.xcd_split > 0) {
+      qb = (w % 8) % nqb;
+      range = (w / 8) * a.xcd_split + (w % 8) / nqb;
+    } else {
+      qb = w % nqb;
+      range = w / nqb;
+    }
+    group = qb / a.qblocks;
+    m0 = (qb % a.qblocks) * TM;
+    tile_begin = (int64_t)range * a.tiles_n / a.ranges;
+    tile_end = (int64_t)(range + 1) * a.tiles_n / a.ranges;
+  } else {
+    group = blockIdx.z;
+    m0 = blockIdx.y * TM;
+    tile_begin = blockIdx.x;
+    tile_end = tile_begin + 1;
+  }
+  // fused top-k state, behind the staging buffers and the piece table
+  // [TM][KL] (score bits, index), every row sorted, best first
+  uint2* const list = reinterpret_cast<uint2*>(lds_s + STAGE_ELEMS + 64);
+  const float NEG = -__builtin_inff();
+  if (TOPK) {
+    for (int e = tid; e < TM * KL; e += 512) list[e] = make_uint2(__float_as_uint(NEG), 0x7fffffffu);  // "no entry": worse than any score
+  }
 
   if (PC == QP && tid < 16) {
     uint32_t p1, p2, p3;
@@ -99,11 +162,10 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
     a_src0[i] = a.qr + ((int64_t)group * a.M + r) * a.d + a_k;
     a_src1[i] = PROD ? a.qs + ((int64_t)group * a.M + r) * a.d + a_k : nullptr;
   }
-  // B: thread = (code tid % TN, CP consecutive k at CP (tid / TN))
+  // B: thread = (code tid % TN, CP consecutive k at CP (tid / TN)); the code changes with the tile
   const int b_col = tid % TN, b_part = tid / TN;
-  const int64_t b_row = (int64_t)group * a.n + (n0 + b_col < a.n ? n0 + b_col : a.n - 1);
-  const uint32_t* const b_idx = a.idx + b_row * ((int64_t)gw * BITS);
-  const uint32_t* const b_qjl = PROD ? a.qjl + b_row * gw : nullptr;
+  const uint32_t* b_idx = nullptr;
+  const uint32_t* b_qjl = nullptr;
 
   f32x4 areg[2][AR];
   uint32_t wcur[SPAN][NB], zcur[SPAN], wnxt[SPAN][NB], znxt[SPAN];
@@ -193,6 +255,19 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
     }
   };
 
+  const int f_row = lane & 31, f_k = (lane >> 5) * 8;  // fragment: row / column within a sub-tile, first k
+  unsigned short* const buf0 = lds_s;
+  unsigned short* const buf1 = lds_s + C::BUF_ELEMS;
+  const int steps = a.d / KT;
+  const int spans = steps / (2 * SPAN);
+
+  for (int64_t tile = tile_begin; tile < tile_end; ++tile) {
+  const int64_t n0 = tile * TN;
+  {
+    const int64_t b_row = (int64_t)group * a.n + (n0 + b_col < a.n ? n0 + b_col : a.n - 1);
+    b_idx = a.idx + b_row * ((int64_t)gw * BITS);
+    b_qjl = PROD ? a.qjl + b_row * gw : nullptr;
+  }
   floatx16 acc1[2][CT], acc2[2][PROD ? CT : 1];
 #pragma unroll
   for (int rt = 0; rt < 2; ++rt)
@@ -204,7 +279,6 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
         if (PROD) acc2[rt][ct][r] = 0.f;
       }
 
-  const int f_row = lane & 31, f_k = (lane >> 5) * 8;  // fragment: row / column within a sub-tile, first k
   auto compute = [&](const unsigned short* buf) {
     const unsigned short* const bb = buf + C::A_ELEMS;
     auto frag = [&](const unsigned short* base, int row) -> bf16x8 {
@@ -254,17 +328,13 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
   };
 
   // ---- k loop: one barrier per step ----------------------------------------------------------------
-  unsigned short* const buf0 = lds_s;
-  unsigned short* const buf1 = lds_s + C::BUF_ELEMS;
-  const int steps = a.d / KT;
   load_a(0);
   load_words(0);
   take_words();
-  __syncthreads();  // the piece table
+  __syncthreads();  // the piece table (and, from the second tile on, the end of the previous tile's selection)
   store_a(buf0);
   store_b(buf0, 0);
   __syncthreads();
-  const int spans = steps / (2 * SPAN);
   // whole spans: no branch inside a step; after the last step the same step is staged once more, unused
   for (int sp = 0; sp < spans; ++sp) {
 #pragma unroll
@@ -301,9 +371,13 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
 
   // ---- epilogue: per-code factors, store -----------------------------------------------------------
   const float c1 = BITS == 1 ? a.cb.c[1] : 1.f;
+  // in the tile loop of the fused top-k the epilogue's addresses must not be computed ahead of the loop (they
+  // would be carried through it in registers the k-loop needs): lane-derived values are re-made per tile
+  int e_row = f_row, e_half = lane >> 5;
+  if (TOPK) asm volatile("" : "+v"(e_row), "+v"(e_half));
 #pragma unroll
   for (int ct = 0; ct < CT; ++ct) {
-    const int64_t col = n0 + 32 * CT * wn + 32 * ct + f_row;
+    const int64_t col = n0 + 32 * CT * wn + 32 * ct + e_row;
     const bool col_live = col < a.n;
     const int64_t crow = (int64_t)group * a.n + (col_live ? col : a.n - 1);
     const float nu = a.norm != nullptr ? a.norm[crow] : 1.f;
@@ -316,7 +390,7 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
       for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd) {
-          const int row = m0 + 64 * wm + 32 * rt + 8 * qd + 4 * (lane >> 5);
+          const int row = m0 + 64 * wm + 32 * rt + 8 * qd + 4 * e_half;
           f32x4 v;
 #pragma unroll
           for (int e = 0; e < 4; ++e)
@@ -335,26 +409,193 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
     for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int row = m0 + 64 * wm + 32 * rt + 8 * (r >> 2) + (r & 3) + 4 * (lane >> 5);
+        const int row = m0 + 64 * wm + 32 * rt + 8 * (r >> 2) + (r & 3) + 4 * e_half;
         const float v = nu * fmaf(kg, PROD ? acc2[rt][ct][r] : 0.f, c1 * acc1[rt][ct][r]);
-        if (col_live && row < a.M) a.out[((int64_t)group * a.M + row) * a.ldo + col] = v;
+        const bool live = col_live && row < a.M;
+        if (live && (!TOPK || a.out != nullptr)) a.out[((int64_t)group * a.M + row) * a.ldo + col] = v;
+        // the selection below reads the finished scores from the accumulator registers; what is not a
+        // score becomes NaN, which no comparison lets in
+        if (TOPK) acc1[rt][ct][r] = live ? v : __builtin_nanf("");
       }
+  }
+
+  // ---- selection: the tile's scores against the k best of every query row so far ----------------------
+  if (TOPK) {
+    uint2* const qu = reinterpret_cast<uint2*>(reinterpret_cast<unsigned char*>(lds_s) + wave * QBYTES);  // [4][QCAP]
+    const int half = e_half;
+    const int grp = lane >> 4, gj = lane & 15;  // insertion: group = queue, lane of the group = list slot
+    const int kk = a.topk;
+#pragma unroll 1
+    for (int ph = 0; ph < C::WN; ++ph) {  // the wavefronts that share query rows take turns
+      if (wn == ph) {
+        // every row's k-th best score, fetched in batches of 16 (a fetch per compare would leave each compare
+        // waiting for LDS) and again after insertions into those rows
+        float bar[2][16];
+        auto fetch_bars = [&](int rt) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            bar[rt][r] = __uint_as_float(list[(64 * wm + 32 * rt + 8 * (r >> 2) + (r & 3) + 4 * half) * KL + kk - 1].x);
+        };
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) {
+          fetch_bars(rt);
+#pragma unroll
+          for (int ct = 0; ct < CT; ++ct) {
+            // queue every score of this 32 x 32 sub-tile that reaches its row's k-th best; queue = row class
+            // (accumulator register parity, half-wave), so a queue's rows belong to no other queue
+            int cnt[4] = {0, 0, 0, 0};
+            const int lcol = 32 * CT * wn + 32 * ct + e_row;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int lrow = 64 * wm + 32 * rt + 8 * (r >> 2) + (r & 3) + 4 * half;
+              const float v = acc1[rt][ct][r];
+              const bool pass = v >= bar[rt][r];
+              const unsigned long long m = __ballot(pass);
+              if (m != 0ull) {  // uniform
+                const uint32_t lo = (uint32_t)m, hi = (uint32_t)(m >> 32);
+                const int pos = half ? (int)__builtin_amdgcn_mbcnt_hi(hi, 0u) : (int)__builtin_amdgcn_mbcnt_lo(lo, 0u);
+                const int c0 = (r & 1) * 2;
+                const int base = half ? cnt[c0 + 1] : cnt[c0];
+                if (pass) qu[(c0 + half) * QCAP + base + pos] = make_uint2(__float_as_uint(v), ((uint32_t)lrow << 8) | (uint32_t)lcol);
+                cnt[c0] += __builtin_popcount(lo);
+                cnt[c0 + 1] += __builtin_popcount(hi);
+              }
+            }
+            const int most = max(max(cnt[0], cnt[1]), max(cnt[2], cnt[3]));
+            if (most == 0) continue;  // uniform: the steady state
+            __builtin_amdgcn_wave_barrier();
+            const int mine = grp == 0 ? cnt[0] : grp == 1 ? cnt[1] : grp == 2 ? cnt[2] : cnt[3];
+            const uint2* const myq = qu + grp * QCAP;
+            const int gp = gj > 0 ? gj - 1 : 0;
+            uint2 nxt = myq[0];
+#pragma unroll 1
+            for (int e = 0; e < most; ++e) {
+              const bool act = e < mine;
+              const uint2 ent = nxt;
+              nxt = myq[e + 1 < QCAP ? e + 1 : e];  // requested an entry ahead
+              const float v = __uint_as_float(ent.x);
+              const int col = (int)n0 + (int)(ent.y & 255u);
+              uint2* const row = list + (act ? (int)(ent.y >> 8) : 0) * KL;
+              // one batch of reads: the row's k-th best (an earlier entry of the same row may have raised the
+              // bar), this lane's slot and the slot ahead of it
+              const uint2 last = row[kk - 1], own = row[gj], prev = row[gp];
+              const bool ins = act && gj < kk && better(v, col, __uint_as_float(last.x), (int)last.y);
+              const bool keep = better(__uint_as_float(own.x), (int)own.y, v, col);  // slot gj is ahead of the new pair: it stays
+              const bool here = gj == 0 || better(__uint_as_float(prev.x), (int)prev.y, v, col);  // the slot ahead is: the pair lands here
+              const uint2 put = keep ? own : here ? make_uint2(ent.x, (uint32_t)col) : prev;
+              __builtin_amdgcn_wave_barrier();  // every lane has read before any lane writes
+              if (ins) row[gj] = put;
+              __builtin_amdgcn_wave_barrier();
+            }
+            if (ct + 1 < CT) fetch_bars(rt);
+          }
+        }
+      }
+      __syncthreads();
+    }
+  }
+  }  // tiles
+
+  if (TOPK) {
+    // the lists of this range (unordered; unused slots hold -inf / INT_MAX): joined by topk_merge_kernel
+    for (int e = tid; e < TM * a.topk; e += 512) {
+      const int row = e / a.topk, j = e - row * a.topk;
+      if (m0 + row < a.M) {
+        const int64_t o = ((((int64_t)group * a.M + m0 + row) * a.ranges) + range) * a.topk + j;
+        a.part_val[o] = __uint_as_float(list[row * KL + j].x);
+        a.part_idx[o] = (int)list[row * KL + j].y;
+      }
+    }
   }
 }
 
+// One wavefront per query: the ranges * k (score, index) pairs of the row, k rounds of arg-best.
+__global__ __launch_bounds__(64) void topk_merge_kernel(const float* __restrict__ part_val, const int32_t* __restrict__ part_idx,
+                                                        const int cands, const int k, int32_t* __restrict__ out_idx,
+                                                        float* __restrict__ out_val) {
+  constexpr int PER = 64;  // pairs per lane: ranges <= 256 and k <= KL give at most 4096 pairs
+  const int lane = threadIdx.x;
+  const int64_t row = blockIdx.x;
+  const float NEG = -__builtin_inff();
+  float v[PER];
+  int id[PER];
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    const int c = e * 64 + lane;
+    v[e] = c < cands ? part_val[row * cands + c] : NEG;
+    id[e] = c < cands ? part_idx[row * cands + c] : 0x7fffffff;
+  }
+  for (int r = 0; r < k; ++r) {
+    float bv = NEG;
+    int bi = 0x7fffffff;
+#pragma unroll
+    for (int e = 0; e < PER; ++e)
+      if (e * 64 < cands && better(v[e], id[e], bv, bi)) {
+        bv = v[e];
+        bi = id[e];
+      }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      const float ov = __shfl_xor(bv, off);
+      const int oi = __shfl_xor(bi, off);
+      if (better(ov, oi, bv, bi)) {
+        bv = ov;
+        bi = oi;
+      }
+    }
+    // the winner leaves the set (indices of real pairs are distinct)
+#pragma unroll
+    for (int e = 0; e < PER; ++e)
+      if (id[e] == bi && bi != 0x7fffffff) {
+        v[e] = NEG;
+        id[e] = 0x7fffffff;
+      }
+    if (lane == 0) {
+      out_idx[row * k + r] = bi == 0x7fffffff ? -1 : bi;
+      if (out_val != nullptr) out_val[row * k + r] = bv;
+    }
+  }
+}
+
+// Ranges of code tiles per query block for the fused top-k: about one workgroup per compute unit in all
+// (the kernel's LDS admits one), every range at least one tile; with few query blocks the count is kept a
+// multiple of 8 / blocks so that the XCD residue of a workgroup can pick its query block.
+int plan_ranges(int64_t tiles_n, int nqb, int* xcd_split) {
+  int64_t r = device_cu_count() / nqb;
+  if (r > tiles_n) r = tiles_n;
+  if (r > 256) r = 256;
+  if (r < 1) r = 1;
+  *xcd_split = 0;
+  if (nqb <= 8 && 8 % nqb == 0) {
+    const int xs = 8 / nqb;
+    if (r >= xs) {
+      r -= r % xs;
+      *xcd_split = xs;
+    }
+  }
+  return (int)r;
+}
+
 template <int BITS, bool PROD, int TM, int TN>
-hipError_t launch_tile(const Bf3Args& a, int n_groups, hipStream_t s) {
+hipError_t launch_tile(const Bf3Args& a0, int n_groups, hipStream_t s) {
   using C = Cfg<BITS, PROD, TM, TN>;
   if (!C::FITS) return hipErrorInvalidValue;
-  static bool attr_done = false;  // per instantiation: the limit has to be raised once
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_bf3_kernel<BITS, PROD, TM, TN>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_done = true;
+  if (a0.topk > 0) {
+    Bf3Args a = a0;
+    a.groups = n_groups;
+    a.tiles_n = (int)((a.n + TN - 1) / TN);
+    a.qblocks = (a.M + TM - 1) / TM;
+    a.ranges = plan_ranges(a.tiles_n, a.qblocks * n_groups, &a.xcd_split);
+    static LdsLimit lds_limit;  // per instantiation: the limit is raised once per device
+    if (const hipError_t e = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&score_bf3_kernel<BITS, PROD, TM, TN, true>), C::LDS_BYTES_TOPK); e != hipSuccess) return e;
+    hipLaunchKernelGGL((score_bf3_kernel<BITS, PROD, TM, TN, true>), dim3((unsigned)(a.qblocks * n_groups * a.ranges)), dim3(512),
+                       C::LDS_BYTES_TOPK, s, a);
+    return hipGetLastError();
   }
-  const dim3 grid((unsigned)((a.n + TN - 1) / TN), (unsigned)((a.M + TM - 1) / TM), n_groups);
-  hipLaunchKernelGGL((score_bf3_kernel<BITS, PROD, TM, TN>), grid, dim3(512), C::LDS_BYTES, s, a);
+  static LdsLimit lds_limit;  // per instantiation: the limit is raised once per device
+  if (const hipError_t e = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&score_bf3_kernel<BITS, PROD, TM, TN, false>), C::LDS_BYTES); e != hipSuccess) return e;
+  const dim3 grid((unsigned)((a0.n + TN - 1) / TN), (unsigned)((a0.M + TM - 1) / TM), n_groups);
+  hipLaunchKernelGGL((score_bf3_kernel<BITS, PROD, TM, TN, false>), grid, dim3(512), C::LDS_BYTES, s, a0);
   return hipGetLastError();
 }
 
@@ -379,11 +620,32 @@ bool score_bf3_applicable(int bits, bool prod, int d, int64_t n, int n_groups, i
   return bits <= 4;
 }
 
+// the tile launch_one picks, and with it the fused top-k's ranges
+int score_bf3_topk_ranges(int bits, bool prod, int64_t n, int n_groups, int q_per_group, int topk) {
+  if (topk < 1 || topk > KL || n <= 0 || n_groups <= 0 || q_per_group <= 0) return 0;
+  const int tm = (!prod && q_per_group > 128) ? 256 : 128, tn = (prod && bits >= 2) ? 128 : 256;
+  const int64_t nqb = (int64_t)((q_per_group + tm - 1) / tm) * n_groups;
+  if (nqb > 0x7fffffff / 256) return 0;
+  int xs;
+  return plan_ranges((n + tn - 1) / tn, (int)nqb, &xs);
+}
+
+hipError_t launch_topk_merge(const float* part_val, const int32_t* part_idx, int64_t rows, int ranges, int k,
+                             int32_t* out_idx, float* out_val, hipStream_t s) {
+  if (rows == 0) return hipSuccess;
+  if (ranges < 1 || ranges > 256 || k < 1 || k > KL || rows > 0x7fffffff) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(topk_merge_kernel, dim3((unsigned)rows), dim3(64), 0, s, part_val, part_idx, ranges * k, k, out_idx, out_val);
+  return hipGetLastError();
+}
+
 hipError_t launch_score_bf3(int bits, bool prod, const float* qr, const float* qs, int q_per_group, int d,
                             const uint32_t* idx, const uint32_t* qjl, const float* gamma, const float* norm, int64_t n,
                             int n_groups, float* out, int64_t ldo, bool transposed, float kappa, const Codebook& cb,
-                            hipStream_t s) {
+                            hipStream_t s, int topk, float* part_val, int32_t* part_idx) {
   Bf3Args a;
+  std::memset(&a, 0, sizeof(a));
+  if (topk > 0 && (transposed || topk > KL || part_val == nullptr || part_idx == nullptr)) return hipErrorInvalidValue;
+  a.topk = topk; a.part_val = part_val; a.part_idx = part_idx;
   a.transposed = transposed ? 1 : 0;
   a.qr = qr; a.qs = qs; a.M = q_per_group; a.d = d; a.idx = idx; a.qjl = qjl; a.gamma = gamma; a.norm = norm;
   a.n = n; a.out = out; a.ldo = ldo; a.kappa = kappa; a.cb = cb;

@@ -26,13 +26,8 @@ static hipError_t launch_128(const ScoreI8Args& a, int n_groups, hipStream_t s) 
   static_assert(I8_TABLE_BYTES + lds <= 160 * 1024, "LDS budget");
   const int64_t per_wg = 8 * 16 * TILES_128;
   const dim3 grid((unsigned)((a.n + per_wg - 1) / per_wg), n_groups, (a.q_per_group + 3) / 4);
-  static bool attr_done = false;  // per instantiation: the limit has to be raised once
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_i8_128_kernel<BITS, PROD>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static LdsLimit lds_limit;  // per instantiation: the limit is raised once per device
+  if (const hipError_t e = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&score_i8_128_kernel<BITS, PROD>), lds); e != hipSuccess) return e;
   hipLaunchKernelGGL((score_i8_128_kernel<BITS, PROD>), grid, dim3(512), lds, s, a);
   return hipGetLastError();
 }

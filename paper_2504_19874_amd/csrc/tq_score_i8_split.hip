@@ -210,13 +210,8 @@ static hipError_t launch_split_one(const ScoreI8Args& a, const SplitArgs& sp, in
   const int64_t per_wg = 8 * 16 * SPLIT_TILES;
   const dim3 grid((unsigned)((a.n + per_wg - 1) / per_wg), n_groups, (a.q_per_group + 3) / 4);
   constexpr int lds = FUSED ? I8_PREP_BYTES : 0;  // on top of the 64 KB table
-  static bool attr_done = false;  // per instantiation: the limit has to be raised once
-  if (FUSED && !attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_i8_split_kernel<BITS, PROD, FUSED>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static LdsLimit lds_limit;  // per instantiation: the limit is raised once per device
+  if (FUSED) if (const hipError_t e = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&score_i8_split_kernel<BITS, PROD, FUSED>), lds); e != hipSuccess) return e;
   hipLaunchKernelGGL((score_i8_split_kernel<BITS, PROD, FUSED>), grid, dim3(512), lds, s, a, sp);
   return hipGetLastError();
 }

@@ -73,6 +73,7 @@ __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ sco
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
+        if (i0 + 256 * u >= n4) break;  // padding of the last round: no element, no index
         const int id = (int)((i0 + 256 * u) << 2);
         consider(v[u].x, id);
         consider(v[u].y, id + 1);

@@ -41,8 +41,9 @@ def test_every_declared_symbol_is_exported_and_bound(lib):
 
 def test_params_struct_matches_header_layout():
     from paper_2504_19874_amd import _lib
-    # int32 x2, 9 pointer-sized fields, then the split: int32 x2 and two pointers
-    assert C.sizeof(_lib.TqParams) == 8 + 9 * 8 + 8 + 2 * 8
+    # int32 x2, 9 pointer-sized fields, then the split: int32 x2 and two pointers, then the flags word (padded)
+    assert C.sizeof(_lib.TqParams) == 8 + 9 * 8 + 8 + 2 * 8 + 8
+    assert _lib.TqParams.flags.offset == 104
     assert _lib.TqParams.Pi.offset == 8 and _lib.TqParams.workspace_bytes.offset == 72
     assert _lib.TqParams.d_hi.offset == 80 and _lib.TqParams.bits_mse_hi.offset == 84
     assert _lib.TqParams.centroids_hi.offset == 88 and _lib.TqParams.bounds_hi.offset == 96
@@ -139,3 +140,56 @@ def test_workload_generators_are_seeded_and_shaped():
     m2 = W.mixture_chunk(0, 50, 64, 4, c)
     assert np.allclose(np.linalg.norm(m1, axis=1), 1, atol=1e-6) and m1.dtype == np.float32
     assert W.CONFIGS["C5"].bits_mse == 1 and W.CONFIGS["C4"].bits_mse == 4
+
+
+def test_split_composer_places_blocks_on_their_channels(lib):
+    import paper_2504_19874_amd as tq
+    from paper_2504_19874_amd import params
+    d, hi = 12, [7, 2, 9]
+    rng = np.random.default_rng(5)
+    a = rng.standard_normal((3, 3)).astype(np.float32)
+    b = rng.standard_normal((9, 9)).astype(np.float32)
+    got = params.compose_split(d, hi, a, b).numpy()
+    x = rng.standard_normal(d).astype(np.float32)
+    hi_sorted = sorted(hi)
+    lo = [c for c in range(d) if c not in hi]
+    # the composed matrix applies block a to the hi channels and block b to the others, each in ascending order
+    want = np.concatenate([a @ x[hi_sorted], b @ x[lo]])
+    assert np.allclose(got @ x, want, atol=1e-6)
+    assert np.count_nonzero(got) <= 9 + 81
+
+
+def test_host_code_under_address_and_undefined_sanitizers(lib, tmp_path):
+    """The library's CPU code (codebook solver, rotation builder, split composer, and the argument checks of
+    every entry point) compiled with -fsanitize=address,undefined on the host side and driven by
+    tests/host/sanitize_driver.cpp; device code objects are linked in as built, nothing touches a GPU."""
+    import glob
+    import shutil
+    import subprocess
+    from paper_2504_19874_amd import build
+    if shutil.which("hipcc") is None:
+        pytest.skip("no hipcc")
+    objs = [f for f in glob.glob(os.path.join(build.OBJ, "*.o"))
+            if os.path.basename(f) not in ("tq_api.o", "tq_codebook.o", "tq_rotation.o")]
+    if len(objs) < len(build.SOURCES) - 3:
+        build.build_library(verbose=False)
+        objs = [f for f in glob.glob(os.path.join(build.OBJ, "*.o"))
+                if os.path.basename(f) not in ("tq_api.o", "tq_codebook.o", "tq_rotation.o")]
+    san = ["-fsanitize=address,undefined", "-fno-sanitize-recover=undefined"]
+    host = ["hipcc", "-O1", "-g", "-std=c++17", "-x", "c++", *san, "-c"]
+    made = []
+    for src in (os.path.join(build.CSRC, "tq_codebook.cpp"), os.path.join(build.CSRC, "tq_rotation.cpp"),
+                os.path.join(ROOT, "tests", "host", "sanitize_driver.cpp")):
+        out = str(tmp_path / (os.path.basename(src) + ".o"))
+        subprocess.run([*host, src, "-o", out], check=True, capture_output=True)
+        made.append(out)
+    api_o = str(tmp_path / "tq_api.o")
+    xh = [f for s in san for f in ("-Xarch_host", s)]
+    subprocess.run(["hipcc", *[f for f in build.HIP_FLAGS if f != "-O3"], "-O1", "-g", *xh, "-c",
+                    os.path.join(build.CSRC, "tq_api.hip"), "-o", api_o], check=True, capture_output=True)
+    exe = str(tmp_path / "sanitize_driver")
+    subprocess.run(["hipcc", "--offload-arch=gfx950", *san, "-o", exe, *made, api_o, *objs], check=True,
+                   capture_output=True)
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "argument checks ok" in r.stdout and "runtime error" not in r.stderr and "AddressSanitizer" not in r.stderr

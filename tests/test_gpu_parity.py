@@ -197,8 +197,8 @@ def test_quantize_prod(d, bits_mse, n, kind):
     _check_prod(p, Pi, S, c32, t32, x_or, normalise, *out)
 
 
-def test_both_arithmetic_paths_of_large_bf16_batches(monkeypatch):
-    """Large bf16 batches at d = 128 run on the bf16 matrix cores (exact pieces); TQ_FP32_MFMA=1 keeps them on the
+def test_both_arithmetic_paths_of_large_bf16_batches():
+    """Large bf16 batches at d = 128 run on the bf16 matrix cores (exact pieces); TQ_FLAG_FP32_MFMA in the parameters keeps them on the
     fp32 matrix instructions.  Both must meet the oracle, and they must agree with each other on nearly every
     index and sign."""
     d, bits_mse, n = 128, 2, 34000
@@ -206,24 +206,26 @@ def test_both_arithmetic_paths_of_large_bf16_batches(monkeypatch):
     x_or, x_dev, normalise = _quant_inputs(n, d, "bf16", 77)
     pieces = _run_prod(p, x_dev, n, normalise)
     _check_prod(p, Pi, S, c32, t32, x_or, normalise, *pieces)
-    monkeypatch.setenv("TQ_FP32_MFMA", "1")
-    plain = _run_prod(p, x_dev, n, normalise)
+    xt = [torch.zeros((n, d), dtype=torch.float32, device=DEV) for _ in range(2)]
+    p.fp32_mfma = True
+    try:
+        plain = _run_prod(p, x_dev, n, normalise)
+        tq.tq_dequantize(p, *plain, xt[0])
+    finally:
+        p.fp32_mfma = False  # the parameter object is shared with other tests
     _check_prod(p, Pi, S, c32, t32, x_or, normalise, *plain)
     same_idx = (words(pieces[0]) == words(plain[0])).mean()
     same_qjl = (words(pieces[1]) == words(plain[1])).mean()
     assert same_idx >= 0.9999 and same_qjl >= 0.999, (same_idx, same_qjl)
-    xt = [torch.zeros((n, d), dtype=torch.float32, device=DEV) for _ in range(2)]
-    tq.tq_dequantize(p, *plain, xt[0])
-    monkeypatch.delenv("TQ_FP32_MFMA")
     tq.tq_dequantize(p, *plain, xt[1])
     nu = plain[3].cpu().numpy().astype(np.float64)
     P.check_close(xt[1].cpu().numpy(), xt[0].cpu().numpy().astype(np.float64), nu[:, None] / np.sqrt(d), "dequantize, pieces vs fp32")
 
 
 @pytest.mark.parametrize("d,bits_mse,n,kind", [(256, 2, 3000, "f32"), (512, 4, 1500, "unit"), (96, 1, 2500, "bf16")])
-def test_both_arithmetic_paths_at_other_dimensions(monkeypatch, d, bits_mse, n, kind):
+def test_both_arithmetic_paths_at_other_dimensions(d, bits_mse, n, kind):
     """Every d other than 128 runs the quantiser's contractions, many-query scoring and dequantisation on the bf16
-    matrix cores (pieces); TQ_FP32_MFMA=1 keeps them on the fp32 matrix instructions.  Both must meet the oracle
+    matrix cores (pieces); TQ_FLAG_FP32_MFMA in the parameters keeps them on the fp32 matrix instructions.  Both must meet the oracle
     and agree with each other."""
     p, Pi, S, c32, t32 = setup(d, bits_mse, True)
     x_or, x_dev, normalise = _quant_inputs(n, d, kind, 91)
@@ -241,9 +243,11 @@ def test_both_arithmetic_paths_at_other_dimensions(monkeypatch, d, bits_mse, n, 
         return codes, xt, sc
 
     pieces = run()
-    monkeypatch.setenv("TQ_FP32_MFMA", "1")
-    plain = run()
-    monkeypatch.delenv("TQ_FP32_MFMA")
+    p.fp32_mfma = True
+    try:
+        plain = run()
+    finally:
+        p.fp32_mfma = False  # the parameter object is shared with other tests
     assert (words(pieces[0][0]) == words(plain[0][0])).mean() >= 0.9999
     assert (words(pieces[0][1]) == words(plain[0][1])).mean() >= 0.999
     # the same codes through both arithmetic paths
@@ -446,3 +450,80 @@ def test_score_equals_inner_product_with_dequantized_vectors():
     want = q.double().cpu().numpy() @ xt.double().cpu().numpy().T
     scale = np.linalg.norm(q.cpu().numpy(), axis=1)[:, None] * norm.cpu().numpy()[None, :]
     P.check_close(s.cpu().numpy(), want, scale, "score vs <q, dequantized>")
+
+
+def _random_codes(p, d, bits_mse, prod, n, seed):
+    rng = np.random.default_rng(seed)
+    idx = rng.integers(0, 1 << bits_mse, size=(n, d)).astype(np.int32)
+    z = rng.integers(0, 2, size=(n, d)).astype(bool)
+    return dict(idx=dev(o.pack_planes(idx, bits_mse).view(np.int32)) if bits_mse else None,
+                qjl=dev(o.pack_signs(z).view(np.int32)) if prod else None,
+                gamma=dev(rng.uniform(0.05, 0.6, size=n).astype(np.float32)) if prod else None,
+                norm=dev(np.exp(rng.normal(0, 1, size=n)).astype(np.float32)))
+
+
+def _topk_both_ways(p, q, n_groups, qpg, c, npg, topk):
+    """tq_score with a score buffer and top-k, and top-k alone: the indices and values must be the stable
+    descending sort of the score matrix the same call wrote (equal scores by lower index)."""
+    nq = n_groups * qpg
+    prod = c["qjl"] is not None
+    scores = torch.zeros((nq, npg), dtype=torch.float32, device=DEV)
+    ti = torch.full((nq, topk), -5, dtype=torch.int32, device=DEV)
+    tv = torch.full((nq, topk), float("nan"), dtype=torch.float32, device=DEV)
+    p.reserve_score(n_groups, qpg, npg, prod, True, topk)
+    tq.tq_score(p, q, n_groups, qpg, c["idx"], c["qjl"], c["gamma"], c["norm"], npg, scores, topk, ti, tv)
+    got = scores.cpu().numpy()
+    k_real = min(topk, npg)
+    ref = o.topk(got, k_real)
+    assert np.array_equal(ti.cpu().numpy()[:, :k_real], ref)
+    assert np.array_equal(tv.cpu().numpy()[:, :k_real], np.take_along_axis(got, ref, axis=1))
+    if k_real < topk:  # more wanted than there are codes
+        assert np.all(ti.cpu().numpy()[:, k_real:] == -1) and np.all(np.isneginf(tv.cpu().numpy()[:, k_real:]))
+    # no score buffer: a workspace sized for exactly this call (no score matrix where the selection is fused)
+    ti2 = torch.full_like(ti, -5)
+    tv2 = torch.full_like(tv, float("nan"))
+    p.workspace, p.c.workspace, p.c.workspace_bytes = None, 0, 0
+    p.reserve_score(n_groups, qpg, npg, prod, False, topk)
+    tq.tq_score(p, q, n_groups, qpg, c["idx"], c["qjl"], c["gamma"], c["norm"], npg, None, topk, ti2, tv2)
+    assert torch.equal(ti, ti2) and torch.equal(tv, tv2)
+    return got, p.workspace.numel()
+
+
+@pytest.mark.parametrize("d,bits_mse,prod,n_groups,qpg,npg,topk", [
+    (128, 2, False, 1, 300, 200000, 10),   # two query blocks x 128 ranges of several 256-code tiles
+    (128, 1, True, 1, 130, 150001, 16),    # the list length limit; a ragged last tile
+    (96, 3, True, 3, 70, 5000, 7),         # three groups (query blocks do not divide the XCD count), 128-code tiles
+    (256, 4, False, 2, 257, 3000, 1),      # k = 1; query blocks with a ragged tail
+    (128, 2, False, 1, 100, 5, 10),        # more wanted than there are codes
+    (128, 3, False, 1, 90, 70000, 17),     # above the list length: the separate top-k kernel over a score matrix
+])
+def test_topk_inside_the_scoring_kernel(d, bits_mse, prod, n_groups, qpg, npg, topk):
+    p, Pi, S, c32, t32 = setup(d, bits_mse, prod)
+    n, nq = n_groups * npg, n_groups * qpg
+    c = _random_codes(p, d, bits_mse, prod, n, d + npg)
+    q = dev(W.gaussian_queries(nq, d, 3, unit=False))
+    _, ws = _topk_both_ways(p, q, n_groups, qpg, c, npg, topk)
+    if topk <= 16 and npg >= 5000:
+        assert ws < nq * npg  # far below a score matrix (4 bytes per pair)
+
+
+def test_topk_inside_the_scoring_kernel_on_adversarial_orders():
+    """Every tile beats the previous one (scores grow with the code index), and every score equal (the k
+    lowest indices win): the selection must not depend on the order in which tiles and ranges are met."""
+    d, bits_mse, nq, n, topk = 128, 2, 140, 90000, 10
+    p, Pi, S, c32, t32 = setup(d, bits_mse, False)
+    one = np.random.default_rng(1).integers(0, 4, size=(1, d)).astype(np.int32)
+    words1 = o.pack_planes(one, bits_mse).view(np.int32)
+    idx = dev(np.repeat(words1, n, axis=0))
+    q = dev(W.gaussian_queries(nq, d, 9, unit=False))
+    grow = dict(idx=idx, qjl=None, gamma=None, norm=dev(np.linspace(1.0, 2.0, n).astype(np.float32)))
+    got, _ = _topk_both_ways(p, q, 1, nq, grow, n, topk)
+    assert (got[:, -1] > got[:, 0]).any() and (got[:, -1] < got[:, 0]).any()  # rising rows and falling rows
+    flat = dict(idx=idx, qjl=None, gamma=None, norm=dev(np.ones(n, dtype=np.float32)))
+    got, _ = _topk_both_ways(p, q, 1, nq, flat, n, topk)
+    assert np.all(got == got[:, :1])
+    # a block of exact ties that straddles tiles and ranges, in the middle of random codes
+    c = _random_codes(p, d, bits_mse, False, n, 77)
+    c["idx"][30000:52000] = idx[30000:52000]
+    c["norm"][30000:52000] = 50.0
+    _topk_both_ways(p, q, 1, nq, c, n, topk)
