@@ -21,14 +21,15 @@
 // segment is scaled per code by kappa gamma, so it cannot share the accumulator of the first).
 //
 // Top-k without a score matrix (TOPK): a workgroup owns one block of queries and a contiguous range of code
-// tiles, which it walks with the k-loop above; the k best (score, index) pairs of every query row so far live
-// in LDS, sorted.  After a tile, a score enters the selection only if it reaches the row's k-th best: one
-// compare per score in the steady state.  The few that do are queued, per 32 x 32 sub-tile, in the (idle)
-// staging buffers, four queues per wavefront by row class, and a group of 16 lanes per queue inserts them
-// one by one: lane j of the group rewrites slot j of the row's sorted list from slots j - 1 and j, so an
-// insertion is two reads and a write with no reduction.  Wavefronts that share query rows take turns.  The
-// lists of all ranges are then joined by topk_merge_kernel.  Order everywhere: larger score first, equal
-// scores by lower index, so the result is the one a full sort of the score matrix gives.
+// tiles, which it walks with the k-loop above.  Every query row has RS (score, index) slots in LDS: the k best
+// pairs so far, sorted, and behind them an append area with a counter.  After a tile, a score that reaches its
+// row's k-th best is appended (one LDS atomic for the position; all wavefronts at once); in the steady state
+// that is one compare per score and a handful of appends per tile.  Then the half-waves share out the rows:
+// a row with appended pairs has each of its <= 32 pairs ranked against the others by one lane each, and the
+// pairs of rank < k written to their slots, which also gives the row's new bar.  Scores that found the append
+// area full stay in their registers and the round is repeated with the raised bars (only the first tiles of a
+// range need that).  The lists of all ranges are then joined by topk_merge_kernel.  Order everywhere: larger
+// score first, equal scores by lower index, so the result is the one a full sort of the score matrix gives.
 #include <cstring>
 
 #include "tq_bf3.h"
@@ -37,9 +38,7 @@ namespace tq {
 
 namespace {
 
-constexpr int KL = 16;       // list slots per query row in the fused top-k (k <= KL): one lane of a group each
-constexpr int QCAP = 256;    // entries per candidate queue: 8 rows x 32 columns of a sub-tile
-constexpr int QBYTES = 4 * QCAP * 8;  // a wavefront's four queues
+constexpr int KL = 16;       // largest k of the fused top-k
 
 __device__ __forceinline__ bool better(float va, int ia, float vb, int ib) {
   return va > vb || (va == vb && ia < ib);
@@ -61,10 +60,10 @@ struct Cfg {
   static constexpr int B_ELEMS = (PC + (PROD ? 1 : 0)) * TN * LDK;
   static constexpr int BUF_ELEMS = A_ELEMS + B_ELEMS;
   static constexpr int LDS_BYTES = 2 * BUF_ELEMS * 2 + 16 * 8;  // two buffers, then the piece table
-  // fused top-k: the candidate queues share the staging buffers' space (made large enough for them), then the
-  // piece table, then per query row KL (score, index) slots
-  static constexpr int STAGE_BYTES_TOPK = 2 * BUF_ELEMS * 2 > 8 * QBYTES ? 2 * BUF_ELEMS * 2 : 8 * QBYTES;
-  static constexpr int LDS_BYTES_TOPK = STAGE_BYTES_TOPK + 16 * 8 + TM * KL * 8;
+  // fused top-k: per query row RS (score, index) slots (the sorted k best, then the append area), a counter per
+  // row, and the two "some score is still waiting" flags
+  static constexpr int RS = TM == 256 ? 26 : 32;  // at most 32: one lane of a half-wave per pair when a row is ranked
+  static constexpr int LDS_BYTES_TOPK = LDS_BYTES + TM * RS * 8 + TM * 4 + 16;
   static constexpr bool FITS = LDS_BYTES_TOPK <= 156 * 1024;
 };
 
@@ -103,7 +102,7 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
   constexpr int AR = TM / 128;  // 16-byte pieces of a query tile row set a thread stages per segment
   constexpr int NB = BITS > 0 ? BITS : 1;
   extern __shared__ __attribute__((aligned(16))) unsigned short lds_s[];
-  constexpr int STAGE_ELEMS = TOPK ? C::STAGE_BYTES_TOPK / 2 : 2 * C::BUF_ELEMS;
+  constexpr int STAGE_ELEMS = 2 * C::BUF_ELEMS;
   uint2* const table_s = reinterpret_cast<uint2*>(lds_s + STAGE_ELEMS);  // [16]: pieces of centroid k
 
   const int tid = threadIdx.x;
@@ -137,11 +136,16 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
     tile_end = tile_begin + 1;
   }
   // fused top-k state, behind the staging buffers and the piece table
-  // [TM][KL] (score bits, index), every row sorted, best first
+  // [TM][RS] (score bits, index): slots [0, k) sorted, best first; slots [k, RS) appended since the last ranking
+  constexpr int RS = C::RS;
   uint2* const list = reinterpret_cast<uint2*>(lds_s + STAGE_ELEMS + 64);
+  int* const cnt_s = reinterpret_cast<int*>(list + TM * RS);  // [TM] pairs appended (may count past the area's end)
+  int* const wait_s = cnt_s + TM;                             // [2] a score found its row's area full (by round parity)
   const float NEG = -__builtin_inff();
+  const uint2 NONE = make_uint2(__float_as_uint(NEG), 0x7fffffffu);  // "no pair": worse than any score
   if (TOPK) {
-    for (int e = tid; e < TM * KL; e += 512) list[e] = make_uint2(__float_as_uint(NEG), 0x7fffffffu);  // "no entry": worse than any score
+    for (int e = tid; e < TM * RS; e += 512) list[e] = NONE;
+    for (int e = tid; e < TM + 2; e += 512) cnt_s[e] = 0;
   }
 
   if (PC == QP && tid < 16) {
@@ -371,6 +375,13 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
 
   // ---- epilogue: per-code factors, store -----------------------------------------------------------
   const float c1 = BITS == 1 ? a.cb.c[1] : 1.f;
+  // Where the selection keeps the finished scores.  With 128-row tiles there is room for registers of their
+  // own (the accumulators' life then ends with this epilogue); the 256-row tile has none to spare and keeps
+  // them in the accumulator registers, which the selection then only reads (marking appended scores there
+  // would carry the accumulators through the selection's rounds and cost copies in the k-loop).  Measured,
+  // each tile shape is 10-15 % slower with the other choice.
+  constexpr bool SEL_COPY = TOPK && TM == 128;
+  float sv[SEL_COPY ? 2 : 1][SEL_COPY ? CT : 1][SEL_COPY ? 16 : 1];
   // in the tile loop of the fused top-k the epilogue's addresses must not be computed ahead of the loop (they
   // would be carried through it in registers the k-loop needs): lane-derived values are re-made per tile
   int e_row = f_row, e_half = lane >> 5;
@@ -413,86 +424,96 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
         const float v = nu * fmaf(kg, PROD ? acc2[rt][ct][r] : 0.f, c1 * acc1[rt][ct][r]);
         const bool live = col_live && row < a.M;
         if (live && (!TOPK || a.out != nullptr)) a.out[((int64_t)group * a.M + row) * a.ldo + col] = v;
-        // the selection below reads the finished scores from the accumulator registers; what is not a
-        // score becomes NaN, which no comparison lets in
-        if (TOPK) acc1[rt][ct][r] = live ? v : __builtin_nanf("");
+        // what is not a score becomes NaN, which no comparison lets in
+        if (SEL_COPY) sv[SEL_COPY ? rt : 0][SEL_COPY ? ct : 0][SEL_COPY ? r : 0] = live ? v : __builtin_nanf("");
+        else if (TOPK) acc1[rt][ct][r] = live ? v : __builtin_nanf("");
       }
   }
 
   // ---- selection: the tile's scores against the k best of every query row so far ----------------------
   if (TOPK) {
-    uint2* const qu = reinterpret_cast<uint2*>(reinterpret_cast<unsigned char*>(lds_s) + wave * QBYTES);  // [4][QCAP]
     const int half = e_half;
-    const int grp = lane >> 4, gj = lane & 15;  // insertion: group = queue, lane of the group = list slot
     const int kk = a.topk;
-#pragma unroll 1
-    for (int ph = 0; ph < C::WN; ++ph) {  // the wavefronts that share query rows take turns
-      if (wn == ph) {
-        // every row's k-th best score, fetched in batches of 16 (a fetch per compare would leave each compare
-        // waiting for LDS) and again after insertions into those rows
-        float bar[2][16];
-        auto fetch_bars = [&](int rt) {
+    const int area = RS - kk;  // append slots per row
+    const bool last_tile = tile + 1 == tile_end;
+    int round = 0;
+    bool again;
+    // scores that have been appended: NaN in their own registers, or (scores in the accumulators) bit
+    // 16 (ct % 2) + r of word [rt][ct / 2]
+    uint32_t done[2][(CT + 1) / 2];
 #pragma unroll
-          for (int r = 0; r < 16; ++r)
-            bar[rt][r] = __uint_as_float(list[(64 * wm + 32 * rt + 8 * (r >> 2) + (r & 3) + 4 * half) * KL + kk - 1].x);
-        };
+    for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-        for (int rt = 0; rt < 2; ++rt) {
-          fetch_bars(rt);
+      for (int w = 0; w < (CT + 1) / 2; ++w) done[rt][w] = 0u;
+    do {
+      // every row's k-th best score, fetched in one batch (a fetch per compare would leave each compare
+      // waiting for LDS)
+      float bar[2][16];
 #pragma unroll
-          for (int ct = 0; ct < CT; ++ct) {
-            // queue every score of this 32 x 32 sub-tile that reaches its row's k-th best; queue = row class
-            // (accumulator register parity, half-wave), so a queue's rows belong to no other queue
-            int cnt[4] = {0, 0, 0, 0};
-            const int lcol = 32 * CT * wn + 32 * ct + e_row;
+      for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
+        for (int r = 0; r < 16; ++r)
+          bar[rt][r] = __uint_as_float(list[(64 * wm + 32 * rt + 8 * (r >> 2) + (r & 3) + 4 * half) * RS + kk - 1].x);
+      bool waiting = false;
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+          const int col = (int)n0 + 32 * CT * wn + 32 * ct + e_row;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float v = SEL_COPY ? sv[SEL_COPY ? rt : 0][SEL_COPY ? ct : 0][SEL_COPY ? r : 0] : acc1[rt][ct][r];
+            const uint32_t bit = 1u << (16 * (ct & 1) + r);
+            if (v >= bar[rt][r] && (SEL_COPY || (done[rt][ct >> 1] & bit) == 0u)) {  // NaN never passes
               const int lrow = 64 * wm + 32 * rt + 8 * (r >> 2) + (r & 3) + 4 * half;
-              const float v = acc1[rt][ct][r];
-              const bool pass = v >= bar[rt][r];
-              const unsigned long long m = __ballot(pass);
-              if (m != 0ull) {  // uniform
-                const uint32_t lo = (uint32_t)m, hi = (uint32_t)(m >> 32);
-                const int pos = half ? (int)__builtin_amdgcn_mbcnt_hi(hi, 0u) : (int)__builtin_amdgcn_mbcnt_lo(lo, 0u);
-                const int c0 = (r & 1) * 2;
-                const int base = half ? cnt[c0 + 1] : cnt[c0];
-                if (pass) qu[(c0 + half) * QCAP + base + pos] = make_uint2(__float_as_uint(v), ((uint32_t)lrow << 8) | (uint32_t)lcol);
-                cnt[c0] += __builtin_popcount(lo);
-                cnt[c0 + 1] += __builtin_popcount(hi);
+              const int pos = atomicAdd(&cnt_s[lrow], 1);
+              if (pos < area) {
+                list[lrow * RS + kk + pos] = make_uint2(__float_as_uint(v), (uint32_t)col);
+                if (SEL_COPY) sv[SEL_COPY ? rt : 0][SEL_COPY ? ct : 0][SEL_COPY ? r : 0] = __builtin_nanf("");
+                else done[rt][ct >> 1] |= bit;
+              } else {
+                waiting = true;  // kept for the next round, when the row's bar is higher
               }
             }
-            const int most = max(max(cnt[0], cnt[1]), max(cnt[2], cnt[3]));
-            if (most == 0) continue;  // uniform: the steady state
-            __builtin_amdgcn_wave_barrier();
-            const int mine = grp == 0 ? cnt[0] : grp == 1 ? cnt[1] : grp == 2 ? cnt[2] : cnt[3];
-            const uint2* const myq = qu + grp * QCAP;
-            const int gp = gj > 0 ? gj - 1 : 0;
-            uint2 nxt = myq[0];
-#pragma unroll 1
-            for (int e = 0; e < most; ++e) {
-              const bool act = e < mine;
-              const uint2 ent = nxt;
-              nxt = myq[e + 1 < QCAP ? e + 1 : e];  // requested an entry ahead
-              const float v = __uint_as_float(ent.x);
-              const int col = (int)n0 + (int)(ent.y & 255u);
-              uint2* const row = list + (act ? (int)(ent.y >> 8) : 0) * KL;
-              // one batch of reads: the row's k-th best (an earlier entry of the same row may have raised the
-              // bar), this lane's slot and the slot ahead of it
-              const uint2 last = row[kk - 1], own = row[gj], prev = row[gp];
-              const bool ins = act && gj < kk && better(v, col, __uint_as_float(last.x), (int)last.y);
-              const bool keep = better(__uint_as_float(own.x), (int)own.y, v, col);  // slot gj is ahead of the new pair: it stays
-              const bool here = gj == 0 || better(__uint_as_float(prev.x), (int)prev.y, v, col);  // the slot ahead is: the pair lands here
-              const uint2 put = keep ? own : here ? make_uint2(ent.x, (uint32_t)col) : prev;
-              __builtin_amdgcn_wave_barrier();  // every lane has read before any lane writes
-              if (ins) row[gj] = put;
-              __builtin_amdgcn_wave_barrier();
-            }
-            if (ct + 1 < CT) fetch_bars(rt);
           }
         }
-      }
+      if (waiting) wait_s[round & 1] = 1;
       __syncthreads();
-    }
+      // ranking: half-wave hw takes rows hw, hw + 16, ...; lane l of the half-wave is pair l of the row
+      {
+        const int hw = 2 * wave + half, l = lane & 31;
+        int pend[TM / 16];
+#pragma unroll
+        for (int i = 0; i < TM / 16; ++i) pend[i] = cnt_s[hw + 16 * i];
+#pragma unroll 1
+        for (int i = 0; i < TM / 16; ++i) {
+          int c = 0;
+#pragma unroll
+          for (int i2 = 0; i2 < TM / 16; ++i2) c = i2 == i ? pend[i2] : c;
+          c = c < area ? c : area;
+          // a row is ranked once its area is half full (its bar is stale until then, which only lets a few more
+          // scores in), and at the end of the range
+          if (2 * c < area && !last_tile) c = 0;
+          if (__ballot(c > 0) == 0) continue;  // uniform
+          uint2* const row = list + (hw + 16 * i) * RS;
+          const int n_ent = c > 0 ? kk + c : 0;
+          const uint2 mine = l < n_ent ? row[l] : NONE;
+          int rank = 0;
+#pragma unroll
+          for (int m = 0; m < RS; ++m) {
+            const uint2 o = row[m];  // the same address across the half-wave: a broadcast
+            rank += (m < n_ent && better(__uint_as_float(o.x), (int)o.y, __uint_as_float(mine.x), (int)mine.y)) ? 1 : 0;
+          }
+          __builtin_amdgcn_wave_barrier();  // every lane has read before any lane writes
+          if (l < n_ent && rank < kk) row[rank] = mine;
+          if (l == 0 && c > 0) cnt_s[hw + 16 * i] = 0;
+        }
+        if (tid == 0) wait_s[(round + 1) & 1] = 0;
+      }
+      again = wait_s[round & 1] != 0;
+      ++round;
+      __syncthreads();
+    } while (again);
   }
   }  // tiles
 
@@ -502,8 +523,8 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
       const int row = e / a.topk, j = e - row * a.topk;
       if (m0 + row < a.M) {
         const int64_t o = ((((int64_t)group * a.M + m0 + row) * a.ranges) + range) * a.topk + j;
-        a.part_val[o] = __uint_as_float(list[row * KL + j].x);
-        a.part_idx[o] = (int)list[row * KL + j].y;
+        a.part_val[o] = __uint_as_float(list[row * RS + j].x);
+        a.part_idx[o] = (int)list[row * RS + j].y;
       }
     }
   }

@@ -97,9 +97,15 @@ def test_static_scratch_rejects_what_does_not_fit():
     q = torch.zeros((nq, 128), dtype=torch.float32, device="cuda")
     s = torch.zeros((nq, 64), dtype=torch.float32, device="cuda")
     assert _raw_call(lib.tq_score_static, p, q, 1, nq, t, 64, s, 0, None, None) == 4  # TQ_ERR_WORKSPACE
-    # top-k without a score buffer whose score matrix does not fit
-    ti = torch.zeros((64, 4), dtype=torch.int32, device="cuda")
-    p2, t2, _, _ = _codes(128, 2, False, 70000, 4)
+    # top-k without a score buffer on a route that keeps a score matrix in scratch memory (few queries per
+    # code): 32 x 200000 floats do not fit
+    ti = torch.zeros((32, 4), dtype=torch.int32, device="cuda")
+    p2, t2, _, _ = _codes(128, 2, False, 200000, 4)
     p2.c.workspace, p2.c.workspace_bytes = 0, 0
-    assert _raw_call(lib.tq_score_static, p2, q[:64], 1, 64, t2, 70000, None, 4, ti, None) == 4
+    assert _raw_call(lib.tq_score_static, p2, q[:32], 1, 32, t2, 200000, None, 4, ti, None) == 4
+    # the same request with many queries per code selects inside the scoring kernel and fits
+    ti = torch.zeros((64, 4), dtype=torch.int32, device="cuda")
+    assert _raw_call(lib.tq_score_static, p2, q[:64], 1, 64, t2, 200000, None, 4, ti, None) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(ti.cpu(), torch.arange(4, dtype=torch.int32).repeat(64, 1))  # zero queries: all scores 0, ties by index
     assert lib.tq_status_string(4) == b"TQ_ERR_WORKSPACE"
