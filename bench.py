@@ -9,10 +9,19 @@ KV-cache configuration (8 KV heads x 16384 bf16 keys, d = 128, b = 3 =
 2-bit MSE stage + 1-bit QJL, 32 query heads, GQA 4:1).
 
 Prints ONE JSON line.  `value` is vectors quantised per second through the
-whole step.  `roofline` describes the call that takes the largest share of
-the step, timed with HIP events on the launch stream inside the timed
-region.  `cpu_baseline` is the CPU oracle on a bounded sample of the same
-workload (a reported baseline, not a target).
+whole step.  `rooflines` prices every call of the step against the roofline
+that bounds it, from its ALGORITHMIC flops or bytes and its HIP-event time on
+the launch stream inside the timed region; `roofline` is the entry of the call
+that takes the largest share of the step.  A contraction that the library
+feeds to the bf16 matrix cores as pieces of its fp32 factors is priced
+against the bf16 peak on its algorithmic flops (`frac`); the share of the
+peak that the executed piece products reach (`executed_frac`) and the
+fp32-equivalent rate are given beside it, and `fp32_mfma_reference` times the
+same calls with TQ_FLAG_FP32_MFMA (every contraction on fp32 MFMA).
+`d1536` is the same step on the d = 1536 configuration (C4: 10^6 database
+vectors, 1000 queries, top-10), a few timed steps after the headline region.
+`cpu_baseline` is the CPU oracle on a bounded sample of the headline workload
+(a reported baseline, not a target).
 """
 from __future__ import annotations
 
@@ -201,6 +210,94 @@ def cpu_baseline(cfg, host_x, q, budget_s=20.0):
                       f"against {qs.shape[0]} queries, {elapsed:.2f} s"}
 
 
+def call_roofline(cfg, name: str, ms: float):
+    """Roofline entry of one call from its algorithmic work and its measured time."""
+    flops, nbytes = algorithmic_work(cfg, name)
+    sec = ms * 1e-3
+    pieces = piece_products(cfg, name)
+    few_q = name == "score" and not pieces  # few queries per code: integer digits or fp32 lanes, graded against HBM
+    peak_tf = PEAK_BF16_MFMA_TFLOPS if pieces else PEAK_FP32_MFMA_TFLOPS
+    t_mfma, t_hbm = flops / (peak_tf * 1e12), nbytes / (PEAK_HBM_GBS * 1e9)
+    kernel = f"tq_{name}" + ("_prod" if name == "quantize" and cfg.kind == "prod" else "_mse" if name == "quantize" else "")
+    if few_q or t_hbm > t_mfma and not pieces:
+        r = {"bound": "hbm", "achieved": nbytes / sec / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+             "frac": nbytes / sec / 1e9 / PEAK_HBM_GBS}
+    else:
+        r = {"bound": "mfma", "achieved": flops / sec / 1e12, "peak": peak_tf, "unit": "TFLOP/s",
+             "frac": flops / sec / 1e12 / peak_tf,
+             "dtype": "bf16 pieces of fp32 factors, fp32 accumulate" if pieces else "f32"}
+        if pieces:
+            r["piece_products_per_fp32_product"] = pieces
+            r["executed_frac"] = flops * pieces / sec / 1e12 / PEAK_BF16_MFMA_TFLOPS
+            r["of_fp32_mfma_peak"] = flops / sec / 1e12 / PEAK_FP32_MFMA_TFLOPS
+        r["hbm_frac"] = nbytes / sec / 1e9 / PEAK_HBM_GBS
+    r.update({"kernel": kernel, "avg_ms": ms, "algorithmic_flops": flops, "algorithmic_bytes": nbytes,
+              "traffic": measured_traffic(cfg.name, kernel)})
+    return r
+
+
+def path_dtype(cfg):
+    """The arithmetic type the step computes in, from the library's routing for this workload."""
+    parts = []
+    for name in ("quantize", "dequantize", "score"):
+        pc = piece_products(cfg, name)
+        if pc:
+            parts.append(f"{name}: bf16 pieces of fp32 factors ({pc:g} products per fp32 product), f32 accumulate")
+        elif name == "score" and cfg.q_per_group <= 32 and cfg.d <= 512:
+            parts.append("score: i8 digits of a 2^-19 fixed-point query, i32 accumulate")
+        else:
+            parts.append(f"{name}: f32")
+    return "; ".join(parts)
+
+
+def time_step(calls, steps, warmup):
+    """W untimed steps, then exactly `steps` timed ones between device synchronisations; per-call times from
+    events on torch's current stream, which is the stream every launch uses."""
+    import torch
+    for _ in range(warmup):
+        for _, fn in calls:
+            fn()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        ev[s][0].record()
+        for k, (_, fn) in enumerate(calls):
+            fn()
+            ev[s][k + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per_call = [sum(ev[s][k].elapsed_time(ev[s][k + 1]) for s in range(steps)) / steps for k in range(len(calls))]
+    return wall * 1e3 / steps, per_call
+
+
+def workload_label(cfg):
+    return (f"{cfg.name}: TurboQuant_{cfg.kind} b={cfg.bits} d={cfg.d}, {cfg.n_groups}x{cfg.n} {cfg.in_dtype} vectors, "
+            f"{cfg.nq} queries ({cfg.q_per_group} per group)" + (f", top-{cfg.topk}" if cfg.topk else ""))
+
+
+def second_config_record(name: str, steps: int, warmup: int):
+    """The same step on another configuration (the d = 1536 half of the metric), timed after the headline region."""
+    import torch
+
+    import paper_2504_19874_amd as tq
+    cfg, p, bufs, _, _ = build_workload(name)
+    calls = make_calls(tq, cfg, p, bufs)
+    ms_per_step, per_call = time_step(calls, steps, warmup)
+    n = cfg.n * cfg.n_groups
+    rec = {"workload": workload_label(cfg), "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
+           "vectors_per_s_whole_step": n / (ms_per_step * 1e-3),
+           "per_call_ms": {nm: per_call[k] for k, (nm, _) in enumerate(calls)},
+           "quantize_vectors_per_s": n / (per_call[0] * 1e-3),
+           "scores_per_s": float(cfg.nq) * cfg.n / (per_call[2] * 1e-3),
+           "dtype": path_dtype(cfg),
+           "rooflines": {nm: call_roofline(cfg, nm, per_call[k]) for k, (nm, _) in enumerate(calls)}}
+    del bufs, p, calls
+    torch.cuda.empty_cache()
+    return rec
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -209,7 +306,9 @@ def main():
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C3b4", "C4", "C5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fp32-reference", action="store_true",
-                    help="skip the TQ_FP32_MFMA=1 leg (profiler runs that should see one kernel per call)")
+                    help="skip the TQ_FLAG_FP32_MFMA leg (profiler runs that should see one kernel per call)")
+    ap.add_argument("--no-d1536", action="store_true", help="skip the d = 1536 record (C4)")
+    ap.add_argument("--d1536-steps", type=int, default=3)
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -237,53 +336,9 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
-        for _, fn in calls:
-            fn()
-    torch.cuda.synchronize()
-
-    # events on torch's current stream, which is the stream every launch uses
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for s in range(args.steps):
-        ev[s][0].record()
-        for k, (_, fn) in enumerate(calls):
-            fn()
-            ev[s][k + 1].record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-
-    ms_per_step = wall * 1e3 / args.steps
-    per_call_ms = []
-    for k in range(len(calls)):
-        per_call_ms.append(sum(ev[s][k].elapsed_time(ev[s][k + 1]) for s in range(args.steps)) / args.steps)
-    dom = max(range(len(calls)), key=lambda k: per_call_ms[k])
-    dom_name = calls[dom][0]
-    flops, nbytes = algorithmic_work(cfg, dom_name)
-    dom_s = per_call_ms[dom] * 1e-3
-    mfma_bound = flops / (PEAK_FP32_MFMA_TFLOPS * 1e12) >= nbytes / (PEAK_HBM_GBS * 1e9)
-    pieces = piece_products(cfg, dom_name)
-    if mfma_bound and pieces:
-        # the fp32 contraction is executed as `pieces` bf16 products per fp32 product: priced against the bf16
-        # matrix cores on the flops they execute; the fp32-equivalent rate is given beside it
-        ach = flops * pieces / dom_s / 1e12
-        roof = {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / PEAK_BF16_MFMA_TFLOPS, "traffic": None, "dtype": "bf16 pieces of fp32 factors",
-                "piece_products_per_fp32_product": pieces,
-                "fp32_equivalent": {"achieved": flops / dom_s / 1e12, "unit": "TFLOP/s",
-                                    "of_fp32_mfma_peak": flops / dom_s / 1e12 / PEAK_FP32_MFMA_TFLOPS}}
-    elif mfma_bound:
-        ach = flops / dom_s / 1e12
-        roof = {"bound": "mfma", "achieved": ach, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / PEAK_FP32_MFMA_TFLOPS, "traffic": None}
-    else:
-        ach = nbytes / dom_s / 1e9
-        roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": ach / PEAK_HBM_GBS, "traffic": None}
-    roof["kernel"] = f"tq_{dom_name}" + ("_prod" if dom_name == "quantize" and cfg.kind == "prod" else "")
-    roof["avg_ms"] = per_call_ms[dom]
-    roof["traffic"] = measured_traffic(cfg.name, roof["kernel"])
+    ms_per_step, per_call_ms = time_step(calls, args.steps, args.warmup)
+    rooflines = {name: call_roofline(cfg, name, per_call_ms[k]) for k, (name, _) in enumerate(calls)}
+    dom_name = max(rooflines, key=lambda k: rooflines[k]["avg_ms"])
 
     out = {
         "metric": "vectors quantized/s through quantize+dequantize+score (one GPU)",
@@ -296,29 +351,31 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": path_dtype(cfg),
         "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: TurboQuant_{cfg.kind} b={cfg.bits} d={cfg.d}, "
-                               f"{cfg.n_groups}x{cfg.n} {cfg.in_dtype} vectors, {cfg.nq} queries "
-                               f"({cfg.q_per_group} per group)" + (f", top-{cfg.topk}" if cfg.topk else "")},
+        "config": {"workload": workload_label(cfg)},
         "per_call_ms": {name: per_call_ms[k] for k, (name, _) in enumerate(calls)},
         "quantize_vectors_per_s": n / (per_call_ms[0] * 1e-3),
         "scores_per_s": float(cfg.nq) * cfg.n / (per_call_ms[2] * 1e-3),
-        "roofline": roof,
+        "roofline": rooflines[dom_name],
+        "rooflines": rooflines,
         # what each call multiplies in; every result meets the fp32 tolerances of the parity tests
         "arithmetic": arithmetic(cfg),
     }
     if not args.no_fp32_reference and any(piece_products(cfg, name) for name, _ in calls):
-        # the same calls with every contraction kept on the fp32 matrix instructions (TQ_FP32_MFMA=1): the
-        # figure the fp32 MFMA peak applies to directly.  Outside the timed region, not part of `value`.
-        os.environ["TQ_FP32_MFMA"] = "1"
+        # the same calls with every contraction kept on the fp32 matrix instructions (TQ_FLAG_FP32_MFMA in the
+        # parameters): the figure the fp32 MFMA peak applies to directly.  Outside the timed region, not part
+        # of `value`.
+        p.fp32_mfma = True
         try:
-            reps = max(20, args.steps // 4)
+            # without a score buffer the fp32 route keeps a score matrix in the workspace
+            p.reserve_score(cfg.n_groups, cfg.q_per_group, cfg.n, cfg.kind == "prod", cfg.topk == 0, cfg.topk)
+            reps = max(20, args.steps // 4) if n * cfg.d < (1 << 30) else 2
             ref = {}
             for name, fn in calls:
                 if not piece_products(cfg, name):
                     continue
-                for _ in range(5):
+                for _ in range(5 if reps > 2 else 1):
                     fn()
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
@@ -332,9 +389,13 @@ def main():
                              "frac_of_fp32_mfma_peak": fl / (ms * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS}
             out["fp32_mfma_reference"] = ref
         finally:
-            del os.environ["TQ_FP32_MFMA"]
+            p.fp32_mfma = False
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, host_x, q)
+    if not args.no_d1536 and args.workload != "C4":
+        del bufs, calls, host_x
+        torch.cuda.empty_cache()
+        out["d1536"] = second_config_record("C4", args.d1536_steps, 1)
     print(json.dumps(out))
 
 
