@@ -62,6 +62,8 @@ def main():
     ap.add_argument("--reps", type=int, default=0)
     ap.add_argument("--warm", action="store_true")
     ap.add_argument("--only", default="")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     ap.add_argument("--value-bits", type=int, default=2, help="attend: bits of the MSE stage of the value codes")
     ap.add_argument("--value-prod", action="store_true", help="attend: value codes from TurboQuant_prod")
     ap.add_argument("--value-split", type=int, default=0, metavar="D_HI",
@@ -73,6 +75,14 @@ def main():
 
     import paper_2504_19874_amd as tq
     import workloads as W
+
+    if args.calibration_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)  # 256 MiB read + 256 MiB written
+        torch.cuda.synchronize()
+        del src, dst
 
     cfg = W.CONFIGS[args.config]
     prod = cfg.kind == "prod"

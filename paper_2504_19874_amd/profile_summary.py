@@ -4,8 +4,18 @@
     python -m paper_2504_19874_amd.profile_summary traffic <FETCH_SIZE dir> <WRITE_SIZE dir> \
            --workload C2 [--json profiles/traffic.json]
 
+    python -m paper_2504_19874_amd.profile_summary counters <dir of a --pmc run>
+
 `stats` prints a markdown table of the per-kernel durations (rocprofv3
---kernel-trace --stats --output-format csv).  `traffic` reads the two
+--kernel-trace --stats --output-format csv).  `counters` prints, per kernel,
+the averages of whatever counters the run collected and, when the run has
+SQ_VALU_MFMA_BUSY_CYCLES, SQ_ACTIVE_INST_VALU, SQ_WAIT_INST_ANY,
+SQ_WAVE_CYCLES and GRBM_GUI_ACTIVE, three shares:
+    MFMA busy  = SQ_VALU_MFMA_BUSY_CYCLES / (4 SIMDs x 256 CUs x GRBM_GUI_ACTIVE / 8 XCDs)
+    VALU busy  = 4 x SQ_ACTIVE_INST_VALU  / (the same denominator)
+    waiting    = SQ_WAIT_INST_ANY / SQ_WAVE_CYCLES   (share of wavefront cycles)
+(rocprofv3 sums GRBM_GUI_ACTIVE over the chip's 8 XCDs and the SQ counters over
+all SIMDs; SQ_ACTIVE_INST_VALU counts units of 4 cycles).  `traffic` reads the two
 --pmc runs (FETCH_SIZE in one, WRITE_SIZE in the other; both made with
 bench.py --calibration-copy so that a plain 256 MiB device copy is in the same
 trace), derives the scale factor of each counter from that copy, prints the
@@ -31,7 +41,9 @@ ENTRY_OF = (("tq::quant128_kernel", "tq_quantize_prod"), ("tq::(anonymous namesp
             ("tq::score_i8_128_kernel", "tq_score"), ("tq::score_i8_kernel", "tq_score"),
             ("tq::score_small_kernel", "tq_score"), ("tq::gemm_kernel<0, 2", "tq_quantize"),
             ("tq::gemm_kernel<1, 2", "tq_quantize"), ("tq::gemm_kernel<2, 0", "tq_dequantize"),
-            ("tq::gemm_kernel<2, 1", "tq_score"))
+            ("tq::gemm_kernel<2, 1", "tq_score"), ("tq::stage_pack_kernel", "tq_stage_pack"),
+            ("tq::stage_unpack_kernel", "tq_stage_unpack"), ("tq::stage_sign_pack_kernel", "tq_stage_sign_pack"),
+            ("tq::(anonymous namespace)::stage_", "tq_stage"))
 
 
 def find(dirname, suffix):
@@ -53,6 +65,26 @@ def stats(dirname):
     for r in rows:
         print(f"| `{short(r['Name'])}` | {r['Calls']} | {float(r['AverageNs']):.0f} | {r['MinNs']} | {r['MaxNs']} | "
               f"{float(r['Percentage']):.2f} |")
+
+
+def counters(dirname, cus=256, xcds=8):
+    acc = collections.defaultdict(lambda: collections.defaultdict(list))
+    for r in csv.DictReader(open(find(dirname, "counter_collection.csv"))):
+        name = r["Kernel_Name"].replace("void ", "")
+        if name.startswith("tq::"):
+            acc[name][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    names = sorted({c for v in acc.values() for c in v})
+    print("| kernel | launches | " + " | ".join(names) + " | MFMA busy | VALU busy | waiting |")
+    print("|---|---|" + "---|" * (len(names) + 3))
+    for k in sorted(acc):
+        v = {c: sum(x) / len(x) for c, x in acc[k].items()}
+        n = max(len(x) for x in acc[k].values())
+        den = 4.0 * cus * v["GRBM_GUI_ACTIVE"] / xcds if v.get("GRBM_GUI_ACTIVE") else 0.0
+        mfma = f"{100 * v['SQ_VALU_MFMA_BUSY_CYCLES'] / den:.1f} %" if den and "SQ_VALU_MFMA_BUSY_CYCLES" in v else ""
+        valu = f"{100 * 4 * v['SQ_ACTIVE_INST_VALU'] / den:.1f} %" if den and "SQ_ACTIVE_INST_VALU" in v else ""
+        wait = f"{100 * v['SQ_WAIT_INST_ANY'] / v['SQ_WAVE_CYCLES']:.1f} %" if v.get("SQ_WAVE_CYCLES") and "SQ_WAIT_INST_ANY" in v else ""
+        print(f"| `{short(k, 80)}` | {n} | " + " | ".join(f"{v[c]:.4g}" if c in v else "" for c in names) +
+              f" | {mfma} | {valu} | {wait} |")
 
 
 def per_kernel(dirname, counter):
@@ -105,6 +137,8 @@ def main():
     sub = ap.add_subparsers(dest="cmd", required=True)
     s = sub.add_parser("stats")
     s.add_argument("dir")
+    c = sub.add_parser("counters")
+    c.add_argument("dir")
     t = sub.add_parser("traffic")
     t.add_argument("fetch_dir")
     t.add_argument("write_dir")
@@ -113,6 +147,8 @@ def main():
     args = ap.parse_args()
     if args.cmd == "stats":
         stats(args.dir)
+    elif args.cmd == "counters":
+        counters(args.dir)
     else:
         traffic(args.fetch_dir, args.write_dir, args.workload, args.json)
 

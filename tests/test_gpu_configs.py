@@ -1,8 +1,10 @@
 """The five benchmark configurations at their full sizes, in the launch
 configuration the benchmark uses.  Small ones are compared in full with the
-oracle; the million-vector ones on sampled rows and sampled (query, code)
-pairs that the oracle computes one by one, plus properties that hold at any
-size (top-k of the GPU's own score matrix)."""
+oracle; the million-vector ones on their first 131072 rows in full (indices,
+residual norms, signs, every score of every query, and the top-10 of every
+query within that subset ranked on the oracle's scores), on sampled rows and
+sampled (query, code) pairs from the whole set, plus properties that hold at
+any size (top-k of the GPU's own score matrix)."""
 import math
 
 import numpy as np
@@ -117,10 +119,14 @@ def test_c3_decode_scoring_full(name):
     assert abs(err.mean()) < 5 * err.std() / math.sqrt(cfg.n)
 
 
+HEAD = 131072  # rows of the million-vector sets that the oracle takes in full
+
+
 def _ann_database(cfg, p, prod):
-    """Generate on the host in chunks, upload, quantise everything; keep a
-    sample of rows on the host for the oracle."""
+    """Generate on the host in chunks, upload, quantise everything; keep the
+    first HEAD rows and a sample of the others on the host for the oracle."""
     n, d = cfg.n, cfg.d
+    x_head = np.empty((HEAD, d), dtype=np.float32)
     x_dev = torch.empty((n, d), dtype=torch.float32, device=DEV)
     rng = np.random.default_rng(99)
     sample = np.unique(np.concatenate([np.arange(0, 300), np.arange(n - 300, n),
@@ -131,16 +137,20 @@ def _ann_database(cfg, p, prod):
         sel = sample[(sample >= start) & (sample < start + blk.shape[0])]
         for i in sel:
             kept[int(i)] = blk[i - start].copy()
+        if start < HEAD:
+            x_head[start:min(HEAD, start + blk.shape[0])] = blk[:HEAD - start]
     x_s = np.stack([kept[int(i)] for i in sample])
     idx, qjl, gamma = alloc_codes(p, n, prod)
-    p.reserve(n, cfg.nq, cfg.topk)
+    # quantisation scratch, and exactly what the top-k call takes (no score matrix: the selection is fused)
+    p.reserve(n, cfg.nq, 0).reserve_score(1, cfg.nq, n, prod, False, cfg.topk)
+    assert p.workspace.numel() < (1 << 30)
     if prod:
         tq.tq_quantize_prod(p, x_dev, idx, qjl, gamma, None)
     else:
         tq.tq_quantize_mse(p, x_dev, idx, None)
     torch.cuda.synchronize()
     del x_dev
-    return sample, x_s, idx, qjl, gamma
+    return sample, x_s, idx, qjl, gamma, x_head
 
 
 def _ann_score_checks(cfg, p, Pi, S, c32, idx, qjl, gamma, prod):
@@ -154,6 +164,7 @@ def _ann_score_checks(cfg, p, Pi, S, c32, idx, qjl, gamma, prod):
     # a slice of queries with the score matrix materialised
     nqs = 48
     s = torch.zeros((nqs, n), dtype=torch.float32, device=DEV)
+    p.reserve_score(1, nqs, n, prod, True, 0)
     tq.tq_score(p, qd[:nqs], 1, nqs, idx, qjl, gamma, None, n, s)
     # the two calls rotate the queries with different kernels (few vs many queries), so the
     # scores agree to rounding, not bit for bit: compare the top-k with the tolerance rule
@@ -172,24 +183,60 @@ def _ann_score_checks(cfg, p, Pi, S, c32, idx, qjl, gamma, prod):
         xt = o.dequant_mse(got_idx, Pi, c32)
     want = o.score(q[:nqs], xt)
     P.check_close(s[:, cd].cpu().numpy(), want, 1.0, f"{cfg.name} sampled scores")
+    del s
     return q, ti
+
+
+def _ann_head_checks(cfg, p, Pi, S, c32, q, idx, qjl, gamma, got_head, z_head, prod):
+    """Every query against the first HEAD codes: all HEAD x nq scores against the oracle (fed the GPU's own
+    codes), and the top-10 within that subset, selected by the library without a score buffer, judged on
+    the ORACLE's scores."""
+    d = cfg.d
+    g_head = gamma[:HEAD].cpu().numpy() if prod else None
+    xt = o.dequant_prod(got_head, z_head, g_head, Pi, S, c32) if prod else o.dequant_mse(got_head, Pi, c32)
+    want = o.score(q, xt)  # [nq, HEAD] fp64
+    del xt
+    qd = dev(q)
+    sub = (idx[:HEAD], qjl[:HEAD] if prod else None, gamma[:HEAD] if prod else None)
+    s = torch.zeros((cfg.nq, HEAD), dtype=torch.float32, device=DEV)
+    p.reserve_score(1, cfg.nq, HEAD, prod, True, 0)
+    tq.tq_score(p, qd, 1, cfg.nq, *sub, None, HEAD, s)
+    worst = P.check_close(s.cpu().numpy(), want, 1.0, f"{cfg.name} scores of the first {HEAD} codes")
+    del s
+    ti = torch.zeros((cfg.nq, cfg.topk), dtype=torch.int32, device=DEV)
+    tv = torch.zeros((cfg.nq, cfg.topk), dtype=torch.float32, device=DEV)
+    p.reserve_score(1, cfg.nq, HEAD, prod, False, cfg.topk)
+    tq.tq_score(p, qd, 1, cfg.nq, *sub, None, HEAD, None, cfg.topk, ti, tv)
+    ti_np = ti.cpu().numpy()
+    P.check_topk(ti_np, want, cfg.topk, np.ones(cfg.nq))
+    P.check_close(tv.cpu().numpy(), np.take_along_axis(want, ti_np.astype(np.int64), axis=1), 1.0,
+                  f"{cfg.name} top-{cfg.topk} values")
+    print(f"{cfg.name}: {cfg.nq} x {HEAD} scores within {worst:.3f} of the tolerance; top-{cfg.topk} of every query "
+          f"agrees with the oracle's ranking")
 
 
 def test_c4_ann_mse_b4_d1536_full():
     cfg = W.CONFIGS["C4"]
     p, Pi, _, c32, t32 = params_for(cfg)
-    sample, x_s, idx, _, _ = _ann_database(cfg, p, False)
+    sample, x_s, idx, _, _, x_head = _ann_database(cfg, p, False)
     idx_or, _, y_or = o.quant_mse(x_s, Pi, t32, normalise=False)
     got = o.unpack_planes(words(idx[torch.as_tensor(sample, device=DEV)]), cfg.bits_mse, cfg.d)
     frac = P.check_indices(got, idx_or, y_or, t32)
     print(f"C4 index agreement on {sample.size} sampled rows {frac:.7f}")
-    _ann_score_checks(cfg, p, Pi, None, c32, idx, None, None, False)
+    # the first HEAD rows in full
+    idx_or, _, y_or = o.quant_mse(x_head, Pi, t32, normalise=False)
+    got_head = o.unpack_planes(words(idx[:HEAD]), cfg.bits_mse, cfg.d)
+    frac = P.check_indices(got_head, idx_or, y_or, t32)
+    print(f"C4 index agreement on the first {HEAD} rows {frac:.7f}")
+    del idx_or, y_or, x_head
+    q, _ = _ann_score_checks(cfg, p, Pi, None, c32, idx, None, None, False)
+    _ann_head_checks(cfg, p, Pi, None, c32, q, idx, None, None, got_head, None, False)
 
 
 def test_c5_ann_prod_b2_d3072_full():
     cfg = W.CONFIGS["C5"]
     p, Pi, S, c32, t32 = params_for(cfg)
-    sample, x_s, idx, qjl, gamma = _ann_database(cfg, p, True)
+    sample, x_s, idx, qjl, gamma, x_head = _ann_database(cfg, p, True)
     sd = torch.as_tensor(sample, device=DEV)
     xh, _ = o.unit_normalise(x_s, False)
     y_or = o.rotate(xh, Pi)
@@ -201,4 +248,20 @@ def test_c5_ann_prod_b2_d3072_full():
     s_norm = np.linalg.norm(S.astype(np.float64), axis=1)
     fs = P.check_signs(o.unpack_signs(words(qjl[sd]), cfg.d), u_or, s_norm[None, :] * gamma_or[:, None])
     print(f"C5 index agreement {frac:.7f}, sign agreement {fs:.7f} on {sample.size} sampled rows")
-    _ann_score_checks(cfg, p, Pi, S, c32, idx, qjl, gamma, True)
+    # the first HEAD rows in full
+    xh, _ = o.unit_normalise(x_head, False)
+    del x_head
+    y_or = o.rotate(xh, Pi)
+    idx_or = o.nearest_centroid(y_or, t32)
+    got_head = o.unpack_planes(words(idx[:HEAD]), cfg.bits_mse, cfg.d)
+    frac = P.check_indices(got_head, idx_or, y_or, t32)
+    del y_or, idx_or
+    _, gamma_or, u_or = o.residual_and_sketch(xh, got_head, Pi, S, c32)
+    del xh
+    P.check_close(gamma[:HEAD].cpu().numpy(), gamma_or, 0.0, "C5 gamma", rel=1e-5)
+    z_head = o.unpack_signs(words(qjl[:HEAD]), cfg.d)
+    fs = P.check_signs(z_head, u_or, s_norm[None, :] * gamma_or[:, None])
+    del u_or
+    print(f"C5 index agreement {frac:.7f}, sign agreement {fs:.7f} on the first {HEAD} rows")
+    q, _ = _ann_score_checks(cfg, p, Pi, S, c32, idx, qjl, gamma, True)
+    _ann_head_checks(cfg, p, Pi, S, c32, q, idx, qjl, gamma, got_head, z_head, True)
