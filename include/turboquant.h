@@ -107,6 +107,45 @@ tq_status tq_build_codebook(int32_t d, int32_t bits, float* centroids, float* bo
                             double* cost_per_coord);
 
 /*
+ * Probability of every codebook index (Sec. 3.1, entropy-coding paragraph):
+ * p[l] = mass of the coordinate law f_X of Lemma 1 in the Voronoi cell of
+ * centroid l.  Host only.  centroids: host, 2^bits ascending floats;
+ * p: host out, 2^bits doubles summing to 1.
+ */
+tq_status tq_bucket_masses(int32_t d, int32_t bits, const float* centroids, double* p);
+
+/*
+ * Entropy coding of stored indices (Sec. 3.1, entropy-coding paragraph: an
+ * optimal prefix code for {p_l} lowers the average bit-width towards the
+ * entropy of the index distribution, by about 5 % at b = 4; the paper leaves it
+ * out of the method, and so do the GPU kernels: this is an optional host-side
+ * codec for codes at rest).  All pointers are host memory.
+ *
+ * tq_prefix_code_build: Huffman code lengths for probabilities p[0..K), K <=
+ *   256, and the canonical codewords for them (symbols ordered by (length,
+ *   symbol) take consecutive binary numbers).  lengths: out, K bytes;
+ *   codewords: out, K words (right-aligned); mean_bits: out, nullable, sum p*len.
+ *   TQ_ERR_UNSUPPORTED when a codeword would exceed 32 bits.
+ * tq_entropy_encode: the codewords of coordinates 0..d-1 of each of n vectors,
+ *   most significant bit first, vectors back to back, the last byte padded with
+ *   zero bits.  idx: n * (bits*d/32) words in the packed layout above.
+ *   out_capacity bytes are available at out (n*d*4 is always enough for codes
+ *   made by tq_prefix_code_build with bits <= 4); TQ_ERR_WORKSPACE when they do
+ *   not suffice.  out_bytes: out, bytes written.  row_bit_offsets: out,
+ *   nullable, n + 1 values: the bit at which each vector starts, and the end.
+ * tq_entropy_decode: n vectors starting at bit first_bit of the stream back
+ *   into the packed layout.  TQ_ERR_INVALID_ARG when the stream ends early or
+ *   holds a bit pattern that is no codeword.
+ */
+tq_status tq_prefix_code_build(int32_t K, const double* p, uint8_t* lengths, uint32_t* codewords,
+                               double* mean_bits);
+tq_status tq_entropy_encode(int32_t d, int32_t bits, const uint8_t* lengths, const uint32_t* codewords,
+                            const uint32_t* idx, int64_t n, uint8_t* out, size_t out_capacity,
+                            size_t* out_bytes, uint64_t* row_bit_offsets);
+tq_status tq_entropy_decode(int32_t d, int32_t bits, const uint8_t* lengths, const uint8_t* in,
+                            size_t in_bytes, uint64_t first_bit, int64_t n, uint32_t* idx);
+
+/*
  * The random rotation of Sec. 3.1: the orthogonal factor Q of a QR
  * decomposition of a d x d matrix with i.i.d. N(0,1) entries, made unique (and
  * Haar distributed) by negating column j of Q where R[j][j] < 0, so that R has

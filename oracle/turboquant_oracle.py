@@ -30,6 +30,11 @@ scores times the dequantised values; pinned in tests/test_oracle_attend.py by a
 scalar-loop brute force and by the cases with a known answer (equal logits, one
 dominant key, a common shift of the logits, a single key).
 
+The optimal prefix code for the indices (Sec. 3.1, last paragraph) is Huffman's
+construction; pinned in tests/test_oracle_entropy.py by Kraft's equality, exact
+lengths for dyadic laws, brute force over every complete code of small
+alphabets, and the paper's two figures for b = 4.
+
 Pinned by tests/test_oracle_*.py (closed forms, the paper's printed values,
 brute force).  The only part with no external pin is the exact index vector
 of one particular input under one particular Pi ("parity unpinned" for that
@@ -394,3 +399,85 @@ def pack_signs(qjl):
 
 def unpack_signs(words, d: int):
     return unpack_planes(words, 1, d).astype(bool)
+
+
+# --------------------------------------------------------------------------
+# entropy coding of the indices (Sec. 3.1, last paragraph): an optimal prefix
+# code for the bucket probabilities p_l.  The paper names the technique and
+# its gain and declines to use it; the bit stream below is this build's
+# choice: the codewords of coordinates 0..d-1 of a vector, most significant
+# bit first, vectors back to back.
+# --------------------------------------------------------------------------
+
+
+def index_entropy(p):
+    """Entropy in bits of the index distribution {p_l}."""
+    p = np.asarray(p, dtype=np.float64)
+    nz = p[p > 0]
+    return float(-(nz * np.log2(nz)).sum())
+
+
+def huffman_lengths(p):
+    """Codeword lengths of an optimal prefix code for probabilities p
+    (Huffman's construction: merge the two least probable nodes until one
+    is left; every merge makes the codewords below it one bit longer).
+    Ties go to the node that was made first / has the lower symbol."""
+    p = [float(v) for v in p]
+    K = len(p)
+    if K == 1:
+        return np.zeros(1, dtype=np.int64)
+    nodes = [(p[s], s, [s]) for s in range(K)]  # (probability, age, symbols below)
+    lengths = np.zeros(K, dtype=np.int64)
+    age = K
+    while len(nodes) > 1:
+        nodes.sort(key=lambda t: (t[0], t[1]))
+        a, b = nodes[0], nodes[1]
+        for s in a[2] + b[2]:
+            lengths[s] += 1
+        nodes = nodes[2:] + [(a[0] + b[0], age, a[2] + b[2])]
+        age += 1
+    return lengths
+
+
+def canonical_codewords(lengths):
+    """Codewords of the canonical prefix code with the given lengths:
+    symbols ordered by (length, symbol) take consecutive binary numbers,
+    shifted left whenever the length grows."""
+    lengths = np.asarray(lengths, dtype=np.int64)
+    code = np.zeros(lengths.size, dtype=np.int64)
+    nxt, prev = 0, 0
+    for s in sorted(range(lengths.size), key=lambda s: (lengths[s], s)):
+        nxt <<= int(lengths[s] - prev)
+        code[s] = nxt
+        nxt += 1
+        prev = int(lengths[s])
+    return code
+
+
+def prefix_encode(idx, lengths, codewords):
+    """Bit list of the rows of idx (one codeword per coordinate, most
+    significant bit first) and the bit offset at which every row starts."""
+    bits, starts = [], []
+    for row in np.asarray(idx):
+        starts.append(len(bits))
+        for v in row:
+            L, c = int(lengths[v]), int(codewords[v])
+            bits.extend((c >> (L - 1 - k)) & 1 for k in range(L))
+    starts.append(len(bits))
+    return bits, starts
+
+
+def prefix_decode(bits, lengths, codewords, n: int, d: int):
+    """Inverse of prefix_encode by matching codewords bit by bit."""
+    table = {(int(lengths[s]), int(codewords[s])): s for s in range(len(lengths))}
+    out = np.zeros((n, d), dtype=np.int32)
+    pos = 0
+    for i in range(n):
+        for j in range(d):
+            L, c = 0, 0
+            while (L, c) not in table:
+                c = (c << 1) | bits[pos]
+                pos += 1
+                L += 1
+            out[i, j] = table[(L, c)]
+    return out

@@ -39,6 +39,10 @@ _vp, _i32, _i64 = C.c_void_p, C.c_int32, C.c_int64
 SIGNATURES = {
     "tq_status_string": (C.c_char_p, [C.c_int]),
     "tq_build_codebook": (C.c_int, [_i32, _i32, _vp, _vp, C.POINTER(C.c_double)]),
+    "tq_bucket_masses": (C.c_int, [_i32, _i32, _vp, _vp]),
+    "tq_prefix_code_build": (C.c_int, [_i32, _vp, _vp, _vp, C.POINTER(C.c_double)]),
+    "tq_entropy_encode": (C.c_int, [_i32, _i32, _vp, _vp, _vp, _i64, _vp, C.c_size_t, C.POINTER(C.c_size_t), _vp]),
+    "tq_entropy_decode": (C.c_int, [_i32, _i32, _vp, _vp, C.c_size_t, C.c_uint64, _i64, _vp]),
     "tq_build_rotation": (C.c_int, [_i32, _vp, _vp]),
     "tq_compose_split": (C.c_int, [_i32, _i32, _vp, _vp, _vp, _vp]),
     "tq_derive_params": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _vp, _vp]),

@@ -48,6 +48,24 @@ def _ptr_rows(t):
     return C.c_void_p(t.data_ptr())
 
 
+def _need(t, dtype, numel, what):
+    """A code array must have the dtype the library writes and at least `numel` elements: the library only
+    sees an address, so a short or mistyped tensor would be read or written past its end."""
+    if t is None:
+        return
+    if t.dtype != dtype:
+        raise TurboQuantError(f"{what}: expected {dtype}, got {t.dtype}")
+    if t.numel() < numel:
+        raise TurboQuantError(f"{what}: {t.numel()} elements where the call covers {numel}")
+
+
+def _check_codes(p, rows, idx, qjl, gamma, norm):
+    _need(idx, torch.int32, rows * p.idx_words, "idx")
+    _need(qjl, torch.int32, rows * p.qjl_words, "qjl")
+    _need(gamma, torch.float32, rows * p.scalars_per_vector, "gamma")
+    _need(norm, torch.float32, rows * p.scalars_per_vector, "norm")
+
+
 def _stream():
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
 
@@ -168,6 +186,7 @@ def _dtype_of(x: torch.Tensor) -> int:
 
 def tq_quantize_mse(p: Params, x: torch.Tensor, idx: torch.Tensor, norm: torch.Tensor | None):
     n = x.shape[0]
+    _check_codes(p, n, idx, None, None, norm)
     _check(_lib.load().tq_quantize_mse(C.byref(p.c), _ptr_rows(x), _dtype_of(x), n, x.stride(0) if n else p.d,
                                        _ptr(idx), _ptr(norm), _stream()), "tq_quantize_mse")
 
@@ -175,6 +194,7 @@ def tq_quantize_mse(p: Params, x: torch.Tensor, idx: torch.Tensor, norm: torch.T
 def tq_quantize_prod(p: Params, x: torch.Tensor, idx: torch.Tensor, qjl: torch.Tensor,
                      gamma: torch.Tensor, norm: torch.Tensor | None):
     n = x.shape[0]
+    _check_codes(p, n, idx, qjl, gamma, norm)
     _check(_lib.load().tq_quantize_prod(C.byref(p.c), _ptr_rows(x), _dtype_of(x), n, x.stride(0) if n else p.d,
                                         _ptr(idx), _ptr(qjl), _ptr(gamma), _ptr(norm), _stream()),
            "tq_quantize_prod")
@@ -182,14 +202,31 @@ def tq_quantize_prod(p: Params, x: torch.Tensor, idx: torch.Tensor, qjl: torch.T
 
 def tq_dequantize(p: Params, idx, qjl, gamma, norm, x_out: torch.Tensor):
     n = x_out.shape[0]
+    _check_codes(p, n, idx, qjl, gamma, norm)
+    _need(x_out, torch.float32, 0, "x_out")
     _check(_lib.load().tq_dequantize(C.byref(p.c), _ptr(idx), _ptr(qjl), _ptr(gamma), _ptr(norm), n,
                                      _ptr_rows(x_out), x_out.stride(0) if n else p.d, _stream()), "tq_dequantize")
+
+
+def _check_score_args(p, q, n_groups, q_per_group, idx, qjl, gamma, norm, n_per_group, scores, topk, topk_idx, topk_val):
+    nq = n_groups * q_per_group
+    _check_codes(p, n_groups * n_per_group, idx, qjl, gamma, norm)
+    _need(q, torch.float32, 0, "q")
+    if q.shape[0] < nq:
+        raise TurboQuantError(f"q: {q.shape[0]} rows for {nq} queries")
+    if scores is not None:
+        _need(scores, torch.float32, 0, "scores")
+        if scores.shape[0] < nq or scores.shape[1] < n_per_group:
+            raise TurboQuantError(f"scores: {tuple(scores.shape)} where the call writes {nq} x {n_per_group}")
+    _need(topk_idx, torch.int32, nq * topk, "topk_idx")
+    _need(topk_val, torch.float32, nq * topk, "topk_val")
 
 
 def tq_score(p: Params, q: torch.Tensor, n_groups: int, q_per_group: int, idx, qjl, gamma, norm,
              n_per_group: int, scores: torch.Tensor | None, topk: int = 0,
              topk_idx: torch.Tensor | None = None, topk_val: torch.Tensor | None = None):
     lds = scores.stride(0) if scores is not None and scores.shape[0] else n_per_group
+    _check_score_args(p, q, n_groups, q_per_group, idx, qjl, gamma, norm, n_per_group, scores, topk, topk_idx, topk_val)
     _check(_lib.load().tq_score(C.byref(p.c), _ptr_rows(q), q.stride(0) if q.shape[0] else p.d, n_groups,
                                 q_per_group, _ptr(idx), _ptr(qjl), _ptr(gamma), _ptr(norm), n_per_group,
                                 _ptr_rows(scores), lds, topk, _ptr(topk_idx), _ptr(topk_val), _stream()),
@@ -201,6 +238,7 @@ def tq_score_static(p: Params, q: torch.Tensor, n_groups: int, q_per_group: int,
                     topk_idx: torch.Tensor | None = None, topk_val: torch.Tensor | None = None):
     """tq_score on the library's static scratch array: p's workspace is not used and nothing is allocated."""
     lds = scores.stride(0) if scores is not None and scores.shape[0] else n_per_group
+    _check_score_args(p, q, n_groups, q_per_group, idx, qjl, gamma, norm, n_per_group, scores, topk, topk_idx, topk_val)
     _check(_lib.load().tq_score_static(C.byref(p.c), _ptr_rows(q), q.stride(0) if q.shape[0] else p.d, n_groups,
                                        q_per_group, _ptr(idx), _ptr(qjl), _ptr(gamma), _ptr(norm), n_per_group,
                                        _ptr_rows(scores), lds, topk, _ptr(topk_idx), _ptr(topk_val), _stream()),
@@ -219,6 +257,8 @@ def tq_attend_workspace_bytes(pk: Params, pv: Params, n_groups: int, q_per_group
 def tq_append(p: Params, x: torch.Tensor, idx, qjl, gamma, norm, first_row: int, row_step: int):
     """Quantise the rows of x into code rows first_row + i * row_step of a cache (qjl None: the MSE quantiser)."""
     n = x.shape[0]
+    if n:
+        _check_codes(p, first_row + (n - 1) * row_step + 1, idx, qjl, gamma, norm)
     _check(_lib.load().tq_append(C.byref(p.c), _ptr_rows(x), _dtype_of(x), n, x.stride(0) if n else p.d, _ptr(idx),
                                  _ptr(qjl), _ptr(gamma), _ptr(norm), first_row, row_step, _stream()), "tq_append")
 

@@ -18,7 +18,7 @@ LIB = os.path.join(HERE, "libturboquant.so")
 OBJ = os.path.join(HERE, "_build")
 
 SOURCES = ["tq_api.hip", "tq_gemm.hip", "tq_d128.hip", "tq_d128_small.hip", "tq_d128_small_dq.hip", "tq_score_small.hip", "tq_score_i8.hip", "tq_score_i8_128.hip", "tq_score_i8_split.hip", "tq_score_bf3.hip", "tq_d128_bf3.hip", "tq_q128_bf3.hip", "tq_stage.hip", "tq_attend.hip", "tq_attend_128.hip", "tq_attend_128_v1.hip", "tq_attend_128_v2.hip", "tq_attend_128_v3.hip", "tq_attend_128_v4.hip", "tq_attend_128_p0.hip", "tq_attend_128_p1.hip", "tq_attend_128_p2.hip", "tq_attend_128_s1.hip", "tq_attend_128_s2.hip", "tq_topk.hip",
-           "tq_codebook.cpp", "tq_rotation.cpp"]
+           "tq_codebook.cpp", "tq_rotation.cpp", "tq_entropy.cpp"]
 HIP_FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -162,3 +162,20 @@ extern "C" tq_status tq_build_codebook(int32_t d, int32_t bits, float* centroids
   if (cost_per_coord) *cost_per_coord = cost;
   return TQ_OK;
 }
+
+extern "C" tq_status tq_bucket_masses(int32_t d, int32_t bits, const float* centroids, double* p) {
+  if (d < 3 || bits < 0 || bits > 8 || centroids == nullptr || p == nullptr) return TQ_ERR_INVALID_ARG;
+  const int K = 1 << bits;
+  const CoordLaw law(d);
+  double total = 0.0;
+  for (int k = 0; k < K; ++k) {
+    if (k > 0 && !(centroids[k] > centroids[k - 1])) return TQ_ERR_INVALID_ARG;
+    const double lo = k == 0 ? -1.0 : 0.5 * ((double)centroids[k - 1] + (double)centroids[k]);
+    const double hi = k == K - 1 ? 1.0 : 0.5 * ((double)centroids[k] + (double)centroids[k + 1]);
+    double m2;
+    law.moments02(lo, hi, &p[k], &m2);
+    total += p[k];
+  }
+  for (int k = 0; k < K; ++k) p[k] /= total;  // the quadrature leaves 1e-15; the clipped far tails 1e-40
+  return TQ_OK;
+}

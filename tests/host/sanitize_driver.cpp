@@ -86,6 +86,36 @@ int main() {
   }
   std::puts("compose ok");
 
+  // entropy codec: bucket masses, code construction, a round trip, a truncated stream
+  {
+    float c16[16], t15[15];
+    EXPECT(tq_build_codebook(128, 4, c16, t15, nullptr) == TQ_OK);
+    double p[16], sum = 0.0, mean = 0.0;
+    EXPECT(tq_bucket_masses(128, 4, c16, p) == TQ_OK);
+    for (double v : p) sum += v;
+    EXPECT(std::fabs(sum - 1.0) < 1e-12);
+    uint8_t len[16];
+    uint32_t cw[16];
+    EXPECT(tq_prefix_code_build(16, p, len, cw, &mean) == TQ_OK);
+    EXPECT(mean > 3.7 && mean < 3.9);
+    const int d = 96, n = 37, words = d / 32 * 4;
+    std::vector<uint32_t> idx((size_t)n * words), back((size_t)n * words, 0xffffffffu);
+    for (auto& w : idx) w = (uint32_t)rng();
+    std::vector<uint8_t> stream((size_t)n * d * 4);
+    std::vector<uint64_t> offs((size_t)n + 1);
+    size_t used = 0;
+    EXPECT(tq_entropy_encode(d, 4, len, cw, idx.data(), n, stream.data(), stream.size(), &used, offs.data()) == TQ_OK);
+    EXPECT(used == (offs[(size_t)n] + 7) / 8);
+    std::vector<uint8_t> exact(stream.begin(), stream.begin() + (long)used);  // no slack behind the stream
+    EXPECT(tq_entropy_decode(d, 4, len, exact.data(), exact.size(), 0, n, back.data()) == TQ_OK);
+    EXPECT(back == idx);
+    EXPECT(tq_entropy_decode(d, 4, len, exact.data(), exact.size(), offs[20], 1, back.data()) == TQ_OK);
+    for (int w = 0; w < words; ++w) EXPECT(back[(size_t)w] == idx[(size_t)20 * words + w]);
+    EXPECT(tq_entropy_decode(d, 4, len, exact.data(), exact.size() - 3, 0, n, back.data()) == TQ_ERR_INVALID_ARG);
+    EXPECT(tq_entropy_encode(d, 4, len, cw, idx.data(), n, stream.data(), 10, &used, nullptr) == TQ_ERR_WORKSPACE);
+  }
+  std::puts("entropy codec ok");
+
   // argument checks of the GPU entry points: all answered on the host
   float c4[4] = {-1.5f, -0.5f, 0.5f, 1.5f}, t3[3] = {-1.f, 0.f, 1.f};
   tq_params p{};

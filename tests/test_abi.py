@@ -160,7 +160,7 @@ def test_split_composer_places_blocks_on_their_channels(lib):
 
 
 def test_host_code_under_address_and_undefined_sanitizers(lib, tmp_path):
-    """The library's CPU code (codebook solver, rotation builder, split composer, and the argument checks of
+    """The library's CPU code (codebook solver, rotation builder, split composer, entropy codec, and the argument checks of
     every entry point) compiled with -fsanitize=address,undefined on the host side and driven by
     tests/host/sanitize_driver.cpp; device code objects are linked in as built, nothing touches a GPU."""
     import glob
@@ -170,15 +170,16 @@ def test_host_code_under_address_and_undefined_sanitizers(lib, tmp_path):
     if shutil.which("hipcc") is None:
         pytest.skip("no hipcc")
     objs = [f for f in glob.glob(os.path.join(build.OBJ, "*.o"))
-            if os.path.basename(f) not in ("tq_api.o", "tq_codebook.o", "tq_rotation.o")]
-    if len(objs) < len(build.SOURCES) - 3:
+            if os.path.basename(f) not in ("tq_api.o", "tq_codebook.o", "tq_rotation.o", "tq_entropy.o")]
+    if len(objs) < len(build.SOURCES) - 4:
         build.build_library(verbose=False)
         objs = [f for f in glob.glob(os.path.join(build.OBJ, "*.o"))
-                if os.path.basename(f) not in ("tq_api.o", "tq_codebook.o", "tq_rotation.o")]
+                if os.path.basename(f) not in ("tq_api.o", "tq_codebook.o", "tq_rotation.o", "tq_entropy.o")]
     san = ["-fsanitize=address,undefined", "-fno-sanitize-recover=undefined"]
     host = ["hipcc", "-O1", "-g", "-std=c++17", "-x", "c++", *san, "-c"]
     made = []
     for src in (os.path.join(build.CSRC, "tq_codebook.cpp"), os.path.join(build.CSRC, "tq_rotation.cpp"),
+                os.path.join(build.CSRC, "tq_entropy.cpp"),
                 os.path.join(ROOT, "tests", "host", "sanitize_driver.cpp")):
         out = str(tmp_path / (os.path.basename(src) + ".o"))
         subprocess.run([*host, src, "-o", out], check=True, capture_output=True)
@@ -193,3 +194,30 @@ def test_host_code_under_address_and_undefined_sanitizers(lib, tmp_path):
     r = subprocess.run([exe], capture_output=True, text=True, timeout=600)
     assert r.returncode == 0, r.stdout + r.stderr
     assert "argument checks ok" in r.stdout and "runtime error" not in r.stderr and "AddressSanitizer" not in r.stderr
+
+
+def test_binding_rejects_short_or_mistyped_code_tensors():
+    """The library sees addresses only; the binding checks every code tensor against the call's sizes."""
+    import torch
+    from paper_2504_19874_amd import api
+
+    class Shape:
+        idx_words, qjl_words, scalars_per_vector = 8, 4, 1
+
+    good = dict(idx=torch.zeros(80, dtype=torch.int32), qjl=torch.zeros(40, dtype=torch.int32),
+                gamma=torch.zeros(10), norm=torch.zeros(10))
+    api._check_codes(Shape, 10, **good)
+    for key, bad in [("idx", torch.zeros(79, dtype=torch.int32)), ("idx", torch.zeros(80, dtype=torch.int64)),
+                     ("qjl", torch.zeros(39, dtype=torch.int32)), ("gamma", torch.zeros(9)),
+                     ("norm", torch.zeros(10, dtype=torch.float64))]:
+        with pytest.raises(api.TurboQuantError, match=key):
+            api._check_codes(Shape, 10, **{**good, key: bad})
+    q = torch.zeros((8, 128))
+    with pytest.raises(api.TurboQuantError, match="scores"):
+        api._check_score_args(Shape, q, 2, 4, good["idx"], None, None, None, 5, torch.zeros((8, 4)), 0, None, None)
+    with pytest.raises(api.TurboQuantError, match="topk_idx"):
+        api._check_score_args(Shape, q, 2, 4, good["idx"], None, None, None, 5, None, 3,
+                              torch.zeros(23, dtype=torch.int32), None)
+    with pytest.raises(api.TurboQuantError, match="q:"):
+        api._check_score_args(Shape, q[:7], 2, 4, good["idx"], None, None, None, 5, None, 3,
+                              torch.zeros(24, dtype=torch.int32), None)

@@ -496,6 +496,8 @@ def _topk_both_ways(p, q, n_groups, qpg, c, npg, topk):
     (256, 4, False, 2, 257, 3000, 1),      # k = 1; query blocks with a ragged tail
     (128, 2, False, 1, 100, 5, 10),        # more wanted than there are codes
     (128, 3, False, 1, 90, 70000, 17),     # above the list length: the separate top-k kernel over a score matrix
+    (128, 3, False, 1, 90, 8, 17),         # that kernel with more wanted than there are codes (a 16-byte aligned row)
+    (128, 2, True, 2, 4, 6, 9),            # the same on the few-query route
 ])
 def test_topk_inside_the_scoring_kernel(d, bits_mse, prod, n_groups, qpg, npg, topk):
     p, Pi, S, c32, t32 = setup(d, bits_mse, prod)
