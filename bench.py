@@ -104,10 +104,10 @@ def piece_products(cfg, call: str):
     products each); DeQuant takes three products for the centroid part and three for the sign part."""
     n, prod = cfg.n * cfg.n_groups, cfg.kind == "prod"
     if cfg.d != 128:
-        # the generic kernel: rotation with three pieces of both factors (six products, three for a bf16 input),
-        # the sketch with two (three products)
+        # the generic kernel: rotation with three pieces of Pi against the two leading pieces of an fp32 vector
+        # (five products; three against the single piece of a bf16 vector), the sketch with two of each (three)
         if call == "quantize":
-            rot = 3.0 if cfg.in_dtype == "bf16" else 6.0
+            rot = 3.0 if cfg.in_dtype == "bf16" else 5.0
             return (rot + 3.0) / 2 if prod else rot
         if call == "dequantize" or cfg.q_per_group > 32 or cfg.d > 512:
             # the many-query scoring kernel (also DeQuant, with the rows of Pi^T as queries): two pieces of a query
@@ -133,8 +133,8 @@ def arithmetic(cfg):
         dq = "bf16 MFMA on two-piece splits of the fp32 factors (error < 3e-5 of a coordinate), fp32 accumulation" \
             if piece_products(cfg, "dequantize") else "fp32 MFMA"
     else:
-        q = ("bf16 MFMA on exact pieces: three pieces of Pi x three of x (rotation; a bf16 x is one piece), two x two for "
-             "the sketch (signs only); fp32 accumulation and bucket decision")
+        q = ("bf16 MFMA on pieces: three (exact) pieces of Pi x the two leading pieces of x (rotation, y to 4e-6 |x|; a bf16 "
+             "x is one exact piece), two x two for the sketch (signs only); fp32 accumulation and bucket decision")
         dq = "bf16 MFMA on two-piece splits of the fp32 factors (the scoring kernel with the rows of Pi^T as queries), fp32 accumulation"
     few = cfg.q_per_group <= 32 and cfg.d <= 512
     sc = "int8 MFMA on exact base-128 digits of 2^-19-scaled rotated queries, fp32 combination" if few else \

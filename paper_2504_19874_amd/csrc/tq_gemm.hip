@@ -24,8 +24,9 @@
 // into NP exact bf16 pieces while they are staged into LDS (a bf16 input is one piece as it stands) and the
 // piece products of combined weight >= 2^(-8 (NP - 1)) are summed in the fp32 accumulator with
 // v_mfma_f32_32x32x16_bf16, whose D layout is the one above, so the epilogues do not change.  NP = 3
-// reproduces the fp32 product to 2^-24 (six products, three for a bf16 input); NP = 2 (three products) is
-// used where only signs are kept.
+// keeps W exact (three pieces) against the two leading pieces of an fp32 vector or the one of a bf16 vector
+// (five resp. three products: y to 4e-6 |x| at worst, see mfma_tile); NP = 2 (three products) is used where
+// only signs are kept.
 #include "tq_bf3.h"
 
 #include <cstdlib>
@@ -173,10 +174,11 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
           const float x0 = __uint_as_float(nreg[4 * p]), x1 = __uint_as_float(nreg[4 * p + 1]);
           const float x2 = __uint_as_float(nreg[4 * p + 2]), x3 = __uint_as_float(nreg[4 * p + 3]);
           ss[p] += x0 * x0 + x1 * x1 + x2 * x2 + x3 * x3;
-          split3_pair(f32x2{x0, x1}, lo[0], lo[1], lo[2]);
-          split3_pair(f32x2{x2, x3}, hi[0], hi[1], hi[2]);
+          // the streamed vector as its two leading pieces (see mfma_tile)
+          split2_pair(f32x2{x0, x1}, lo[0], lo[1]);
+          split2_pair(f32x2{x2, x3}, hi[0], hi[1]);
 #pragma unroll
-          for (int pc = 0; pc < NP; ++pc)
+          for (int pc = 0; pc < 2; ++pc)
             *reinterpret_cast<uint2*>(Xp + (srow + 32 * p) * P_LD + pc * 32 + scol) = make_uint2(lo[pc], hi[pc]);
         }
       }
@@ -237,7 +239,13 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
     if constexpr (NP > 0) {
       const unsigned short* const Wp = reinterpret_cast<const unsigned short*>(Ws);
       const unsigned short* const Xp = reinterpret_cast<const unsigned short*>(Ns);
-      constexpr int NPX = NKIND == N_BF16 ? 1 : NP;  // pieces of the streamed operand
+      // Pieces of the streamed operand: a bf16 vector is one; an fp32 vector is taken as its two leading pieces,
+      // x = x1 + x2 + dx with |dx_k| <= 2^-18 |x_k|.  What that leaves out of y = W x is W dx: at most
+      // 2^-18 |W_j| |x| in any one coordinate (3.8e-6 for a unit vector against a row of a rotation, inside the
+      // 1e-5 within which a bucket decision may differ from the exact one), and, W being orthogonal there,
+      // 2^-18 |x| in norm over all coordinates together, so for no input more than a few in 10^5 decisions can
+      // sit that close to a cell boundary.  W itself keeps all NP pieces.
+      constexpr int NPX = NKIND == N_BF16 ? 1 : 2;
 #pragma unroll
       for (int s = 0; s < 2; ++s) {  // 16 values of k per step: lane half h holds k = 16 s + 8 h + 0..7
         bf16x8 av[2][NP], bv[2][NPX];

@@ -248,8 +248,14 @@ def test_both_arithmetic_paths_at_other_dimensions(d, bits_mse, n, kind):
         plain = run()
     finally:
         p.fp32_mfma = False  # the parameter object is shared with other tests
-    assert (words(pieces[0][0]) == words(plain[0][0])).mean() >= 0.9999
-    assert (words(pieces[0][1]) == words(plain[0][1])).mean() >= 0.999
+    # coordinate by coordinate (a word holds 32 of them): the two paths round differently, so a coordinate within
+    # rounding of a cell boundary, or a sketch entry within rounding of zero, may fall on either side
+    same = o.unpack_planes(words(pieces[0][0]), bits_mse, d) == o.unpack_planes(words(plain[0][0]), bits_mse, d)
+    assert same.mean() >= 0.99999, same.mean()
+    # signs only where the whole index vector agrees: one differing index changes that vector's residual
+    rows = same.all(axis=1)
+    assert rows.mean() > 0.99
+    assert (o.unpack_signs(words(pieces[0][1]), d) == o.unpack_signs(words(plain[0][1]), d))[rows].mean() >= 0.9999
     # the same codes through both arithmetic paths
     xt2 = torch.zeros((n, d), dtype=torch.float32, device=DEV)
     sc2 = torch.zeros((nq, n), dtype=torch.float32, device=DEV)
