@@ -154,10 +154,18 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
     table_s[tid] = make_uint2(p1 | (p2 << 16), p3);
   }
 
+  for (int64_t tile = tile_begin; tile < tile_end; ++tile) {
+  // In the tile loop of the fused top-k everything derived from the thread's number is made again per tile:
+  // computed once ahead of the loop, the dozens of LDS and global addresses of the k-loop would stay in
+  // registers through the epilogue and the selection, which need them for the scores.
+  int ttid = tid;
+  if (TOPK) asm volatile("" : "+v"(ttid));
+  const int tlane = ttid & 63;
+
   // ---- staging roles --------------------------------------------------------------------------------
   // A: thread = (row tid / 4, four consecutive k at 4 (tid % 4)) of each segment
   // (and of row + 128 when the tile has 256 rows)
-  const int a_row = tid >> 2, a_k = (tid & 3) * 4;
+  const int a_row = ttid >> 2, a_k = (ttid & 3) * 4;
   const float* a_src0[AR];
   const float* a_src1[AR];
 #pragma unroll
@@ -167,7 +175,7 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
     a_src1[i] = PROD ? a.qs + ((int64_t)group * a.M + r) * a.d + a_k : nullptr;
   }
   // B: thread = (code tid % TN, CP consecutive k at CP (tid / TN)); the code changes with the tile
-  const int b_col = tid % TN, b_part = tid / TN;
+  const int b_col = ttid % TN, b_part = ttid / TN;
   const uint32_t* b_idx = nullptr;
   const uint32_t* b_qjl = nullptr;
 
@@ -259,13 +267,12 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
     }
   };
 
-  const int f_row = lane & 31, f_k = (lane >> 5) * 8;  // fragment: row / column within a sub-tile, first k
+  const int f_row = tlane & 31, f_k = (tlane >> 5) * 8;  // fragment: row / column within a sub-tile, first k
   unsigned short* const buf0 = lds_s;
   unsigned short* const buf1 = lds_s + C::BUF_ELEMS;
   const int steps = a.d / KT;
   const int spans = steps / (2 * SPAN);
 
-  for (int64_t tile = tile_begin; tile < tile_end; ++tile) {
   const int64_t n0 = tile * TN;
   {
     const int64_t b_row = (int64_t)group * a.n + (n0 + b_col < a.n ? n0 + b_col : a.n - 1);
@@ -448,15 +455,13 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
     do {
       // every row's k-th best score, fetched in one batch (a fetch per compare would leave each compare
       // waiting for LDS)
-      float bar[2][16];
-#pragma unroll
-      for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          bar[rt][r] = __uint_as_float(list[(64 * wm + 32 * rt + 8 * (r >> 2) + (r & 3) + 4 * half) * RS + kk - 1].x);
       bool waiting = false;
 #pragma unroll
-      for (int rt = 0; rt < 2; ++rt)
+      for (int rt = 0; rt < 2; ++rt) {
+        float bar[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          bar[r] = __uint_as_float(list[(64 * wm + 32 * rt + 8 * (r >> 2) + (r & 3) + 4 * half) * RS + kk - 1].x);
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) {
           const int col = (int)n0 + 32 * CT * wn + 32 * ct + e_row;
@@ -464,7 +469,7 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
           for (int r = 0; r < 16; ++r) {
             const float v = SEL_COPY ? sv[SEL_COPY ? rt : 0][SEL_COPY ? ct : 0][SEL_COPY ? r : 0] : acc1[rt][ct][r];
             const uint32_t bit = 1u << (16 * (ct & 1) + r);
-            if (v >= bar[rt][r] && (SEL_COPY || (done[rt][ct >> 1] & bit) == 0u)) {  // NaN never passes
+            if (v >= bar[r] && (SEL_COPY || (done[rt][ct >> 1] & bit) == 0u)) {  // NaN never passes
               const int lrow = 64 * wm + 32 * rt + 8 * (r >> 2) + (r & 3) + 4 * half;
               const int pos = atomicAdd(&cnt_s[lrow], 1);
               if (pos < area) {
@@ -477,24 +482,25 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
             }
           }
         }
+      }
       if (waiting) wait_s[round & 1] = 1;
       __syncthreads();
-      // ranking: half-wave hw takes rows hw, hw + 16, ...; lane l of the half-wave is pair l of the row
+      // ranking: half-wave hw takes rows hw, hw + 16, ...; lane l of the half-wave is pair l of the row.  A row
+      // is ranked once its area is half full (its bar is stale until then, which only lets a few more scores
+      // in), and at the end of the range.
       {
         const int hw = 2 * wave + half, l = lane & 31;
-        int pend[TM / 16];
-#pragma unroll
-        for (int i = 0; i < TM / 16; ++i) pend[i] = cnt_s[hw + 16 * i];
-#pragma unroll 1
-        for (int i = 0; i < TM / 16; ++i) {
-          int c = 0;
-#pragma unroll
-          for (int i2 = 0; i2 < TM / 16; ++i2) c = i2 == i ? pend[i2] : c;
-          c = c < area ? c : area;
-          // a row is ranked once its area is half full (its bar is stale until then, which only lets a few more
-          // scores in), and at the end of the range
-          if (2 * c < area && !last_tile) c = 0;
-          if (__ballot(c > 0) == 0) continue;  // uniform
+        int mine_c = l < TM / 16 ? cnt_s[hw + 16 * l] : 0;  // lane l: pairs waiting in row hw + 16 l
+        mine_c = mine_c < area ? mine_c : area;
+        const bool due = mine_c > 0 && (2 * mine_c >= area || last_tile);
+        const unsigned long long due64 = __ballot(due);
+        uint32_t rows_due = ((uint32_t)due64 | (uint32_t)(due64 >> 32)) & 0xffffu;  // rows due in either half-wave
+        const uint32_t due_half = half ? (uint32_t)(due64 >> 32) : (uint32_t)due64;
+        while (rows_due != 0u) {  // uniform
+          const int i = __builtin_ctz(rows_due);
+          rows_due &= rows_due - 1u;
+          const int c_i = __shfl(mine_c, (lane & 32) + i);  // by every lane: the exchange is not to run under a mask
+          const int c = ((due_half >> i) & 1u) ? c_i : 0;
           uint2* const row = list + (hw + 16 * i) * RS;
           const int n_ent = c > 0 ? kk + c : 0;
           const uint2 mine = l < n_ent ? row[l] : NONE;
