@@ -88,7 +88,7 @@ struct Bf3Args {
   int ranges;        // code-tile ranges per query block
   int qblocks;       // query blocks per group
   int tiles_n;       // code tiles per group
-  int xcd_split;     // > 0: query block from the workgroup's XCD residue (see launch_tile)
+  int xcd_split;     // fused top-k: ranges per XCD (0: no split by XCD); plain kernel: 1 = query block fastest
   float* part_val;   // [groups * M][ranges][topk]
   int32_t* part_idx;
 };
@@ -101,6 +101,7 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
   constexpr int CT = C::CT;
   constexpr int AR = TM / 128;  // 16-byte pieces of a query tile row set a thread stages per segment
   constexpr int NB = BITS > 0 ? BITS : 1;
+  constexpr bool PIN = !(TOPK && PROD);  // see the k-loop
   extern __shared__ __attribute__((aligned(16))) unsigned short lds_s[];
   constexpr int STAGE_ELEMS = 2 * C::BUF_ELEMS;
   uint2* const table_s = reinterpret_cast<uint2*>(lds_s + STAGE_ELEMS);  // [16]: pieces of centroid k
@@ -113,26 +114,50 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
   int group, m0, range = 0;
   int64_t tile_begin, tile_end;
   if (TOPK) {
-    // workgroup -> (query block, range).  Workgroups are dealt to the 8 XCDs in turn; with xcd_split the
-    // query block follows the XCD residue, so the workgroups that share an L2 share their queries
+    // workgroup -> (query block, range).  Workgroups are dealt to the 8 XCDs in turn; with xcd_split (=
+    // ranges / 8) the query blocks that walk the same range of codes sit on one XCD and share its L2
     const int w = blockIdx.x;
     const int nqb = a.qblocks * a.groups;
     int qb;
     if (a.xcd_split > 0) {
-      qb = (w % 8) % nqb;
-      range = (w / 8) * a.xcd_split + (w % 8) / nqb;
+      // XCD w % 8 takes ranges / 8 consecutive ranges, each with all of its query blocks
+      const int slot = w / 8;
+      qb = slot % nqb;
+      range = (w % 8) * a.xcd_split + slot / nqb;
     } else {
       qb = w % nqb;
       range = w / nqb;
     }
-    group = qb / a.qblocks;
-    m0 = (qb % a.qblocks) * TM;
-    tile_begin = (int64_t)range * a.tiles_n / a.ranges;
-    tile_end = (int64_t)(range + 1) * a.tiles_n / a.ranges;
+    // (the results of integer divisions are pinned to scalar registers: the compiler takes them for per-lane
+    // values otherwise, and with them every address of the k-loop and the epilogue)
+    range = __builtin_amdgcn_readfirstlane(range);
+    group = __builtin_amdgcn_readfirstlane(qb / a.qblocks);
+    m0 = __builtin_amdgcn_readfirstlane((qb % a.qblocks) * TM);
+    tile_begin = __builtin_amdgcn_readfirstlane((int)((int64_t)range * a.tiles_n / a.ranges));
+    tile_end = __builtin_amdgcn_readfirstlane((int)((int64_t)(range + 1) * a.tiles_n / a.ranges));
   } else {
+    // workgroup -> tile.  Workgroups are dealt to the 8 XCDs in turn; every XCD gets a contiguous range of
+    // tiles.  With xcd_split the query block runs fastest, so the query blocks that read the same block of
+    // codes share one L2 and run at about the same time: dequantisation (d / TM "query" blocks per block of
+    // codes, C5: 88 -> 72 ms) and scoring with more than four query blocks (C5 shape: 29 -> 24 ms); with
+    // four 256-row blocks the order below is the faster one (C4 shape: 9.6 against 10.7 ms)
     group = blockIdx.z;
-    m0 = blockIdx.y * TM;
-    tile_begin = blockIdx.x;
+    if (a.xcd_split > 0) {
+      // (32-bit unsigned arithmetic, and the results pinned to scalar registers: a division makes the compiler
+      // treat them as per-lane values, and with them every address of the k-loop and the epilogue)
+      const uint32_t qblocks = (uint32_t)(a.M + TM - 1) / TM;
+      const uint32_t total = qblocks * (uint32_t)a.tiles_n;  // below 2^31: checked at launch
+      const uint32_t per_xcd = (total + 7u) / 8u;
+      const uint32_t logical = (blockIdx.x % 8u) * per_xcd + blockIdx.x / 8u;
+      if (logical >= total) return;  // the whole workgroup
+      m0 = __builtin_amdgcn_readfirstlane((int)(logical % qblocks) * TM);
+      tile_begin = __builtin_amdgcn_readfirstlane((int)(logical / qblocks));
+    } else {
+      // a grid of (blocks of codes, query blocks): the workgroups in flight write neighbouring pieces of the
+      // same score rows
+      m0 = blockIdx.y * TM;
+      tile_begin = blockIdx.x;
+    }
     tile_end = tile_begin + 1;
   }
   // fused top-k state, behind the staging buffers and the piece table
@@ -353,7 +378,14 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
       const int s = sp * (2 * SPAN) + j;
       load_a(s + 1 < steps ? s + 1 : s);
       if (j == 0) load_words(sp + 1);  // requested a span ahead (clamped past the end)
+      // The staging arithmetic is kept out of the MFMAs of a step (the scheduler interleaves them in most
+      // instantiations, and the same instructions then take 3-12 % longer: C5 dequantise 88 -> 79 ms).  The
+      // two-segment kernels of the fused top-k are left alone: their register pressure keeps the scheduler
+      // from interleaving anyway, and pinned they lose the overlap of a step's last MFMAs with the next
+      // step's reads (C5 score + top-10: 25.2 against 26.2 ms).
+      if (PIN) __builtin_amdgcn_sched_barrier(0);
       compute((j & 1) ? buf1 : buf0);
+      if (PIN) __builtin_amdgcn_sched_barrier(0);
       if (j == 2 * SPAN - 1) take_words();
       store_a((j & 1) ? buf0 : buf1);
       store_b((j & 1) ? buf0 : buf1, (j + 1) & (2 * SPAN - 1));
@@ -369,7 +401,9 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
         const bool more = s + 1 < steps;
         if (more) load_a(s + 1);
         if (j == 0 && more) load_words(sp + 1);
+        if (PIN) __builtin_amdgcn_sched_barrier(0);
         compute((j & 1) ? buf1 : buf0);
+        if (PIN) __builtin_amdgcn_sched_barrier(0);
         if (more) {
           if (j == 2 * SPAN - 1) take_words();
           store_a((j & 1) ? buf0 : buf1);
@@ -585,20 +619,17 @@ __global__ __launch_bounds__(64) void topk_merge_kernel(const float* __restrict_
 }
 
 // Ranges of code tiles per query block for the fused top-k: about one workgroup per compute unit in all
-// (the kernel's LDS admits one), every range at least one tile; with few query blocks the count is kept a
-// multiple of 8 / blocks so that the XCD residue of a workgroup can pick its query block.
+// (the kernel's LDS admits one), every range at least one tile; from 8 ranges on the count is kept a multiple
+// of 8 so that every XCD can take whole ranges (xcd_split = ranges per XCD, 0: no such split).
 int plan_ranges(int64_t tiles_n, int nqb, int* xcd_split) {
   int64_t r = device_cu_count() / nqb;
   if (r > tiles_n) r = tiles_n;
   if (r > 256) r = 256;
   if (r < 1) r = 1;
   *xcd_split = 0;
-  if (nqb <= 8 && 8 % nqb == 0) {
-    const int xs = 8 / nqb;
-    if (r >= xs) {
-      r -= r % xs;
-      *xcd_split = xs;
-    }
+  if (r >= 8) {
+    r -= r % 8;
+    *xcd_split = (int)(r / 8);
   }
   return (int)r;
 }
@@ -621,8 +652,14 @@ hipError_t launch_tile(const Bf3Args& a0, int n_groups, hipStream_t s) {
   }
   static LdsLimit lds_limit;  // per instantiation: the limit is raised once per device
   if (const hipError_t e = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&score_bf3_kernel<BITS, PROD, TM, TN, false>), C::LDS_BYTES); e != hipSuccess) return e;
-  const dim3 grid((unsigned)((a0.n + TN - 1) / TN), (unsigned)((a0.M + TM - 1) / TM), n_groups);
-  hipLaunchKernelGGL((score_bf3_kernel<BITS, PROD, TM, TN, false>), grid, dim3(512), C::LDS_BYTES, s, a0);
+  Bf3Args a = a0;
+  a.tiles_n = (int)((a.n + TN - 1) / TN);
+  const int64_t total = (int64_t)a.tiles_n * ((a.M + TM - 1) / TM);
+  if (total > 0x7ffffff0) return hipErrorInvalidValue;
+  a.xcd_split = (a.transposed || (a.M + TM - 1) / TM > 4) ? 1 : 0;
+  const dim3 grid = a.xcd_split ? dim3((unsigned)((total + 7) / 8 * 8), 1, n_groups)
+                                : dim3((unsigned)a.tiles_n, (unsigned)((a.M + TM - 1) / TM), n_groups);
+  hipLaunchKernelGGL((score_bf3_kernel<BITS, PROD, TM, TN, false>), grid, dim3(512), C::LDS_BYTES, s, a);
   return hipGetLastError();
 }
 
