@@ -243,10 +243,12 @@ def test_split_end_to_end_statistics():
     assert abs(np.mean(err ** 2) / np.mean(var) - 1) < 0.12
 
 
-def test_c3m_full_size():
-    """The 2.5-bit decode configuration at its full size, in the launch shapes bench_kernels times:
-    524288 bf16 keys of 8 heads quantised as two instances (64 + 64 channels), 4 queries per head."""
-    cfg = W.CONFIGS["C3m"]
+@pytest.mark.parametrize("name", ["C3m", "C3h"])
+def test_split_decode_configurations_full_size(name):
+    """The 2.5-bit and 3.5-bit decode configurations (Sec. 4.3) at their full size, in the launch shapes
+    bench_kernels times: 524288 bf16 keys of 8 heads quantised as two instances (64 + 64 channels with 3 + 2
+    resp. 4 + 3 bits), 4 queries per head."""
+    cfg = W.CONFIGS[name]
     d_hi, bits_lo = cfg.d_hi, cfg.bits_mse
     hi_ch = W.kv_hi_channels(cfg.n_groups, D, cfg.seed_x, d_hi)
     g_hi, g_lo = W.gaussian_matrix(d_hi, cfg.seed_pi), W.gaussian_matrix(D - d_hi, cfg.seed_pi + 1)
@@ -280,9 +282,9 @@ def test_c3m_full_size():
         xh, nu = o.unit_normalise(x_or[:, ch], True)
         y = o.rotate(xh, it["Pi"])
         P.check_indices(got[sample], o.nearest_centroid(y, it["t32"]), y, it["t32"])
-        P.check_close(nu_np[sample, part], nu, 0.0, "C3m norm", rel=3e-6)
+        P.check_close(nu_np[sample, part], nu, 0.0, f"{name} norm", rel=3e-6)
         _, gamma_or, u_or = o.residual_and_sketch(xh, got[sample], it["Pi"], it["S"], it["c32"])
-        P.check_close(g_np[sample, part], gamma_or, 0.0, "C3m gamma", rel=1e-5)
+        P.check_close(g_np[sample, part], gamma_or, 0.0, f"{name} gamma", rel=1e-5)
         zp = z[sample][:, :d_hi] if part == 0 else z[sample][:, d_hi:]
         P.check_signs(zp, u_or, np.linalg.norm(it["S"].astype(np.float64), axis=1)[None, :] * gamma_or[:, None])
     # scores of every head against the oracle's estimate from the GPU's own codes
@@ -294,7 +296,7 @@ def test_c3m_full_size():
         rl = dict(idx=got_lo[rows], qjl=z[rows][:, d_hi:], gamma=g_np[rows, 1], norm=nu_np[rows, 1])
         xt = o.dequant_split(D, hi_ch, rh, rl, ihi, ilo, True)
         qsl = slice(g * cfg.q_per_group, (g + 1) * cfg.q_per_group)
-        P.check_close(s_gpu[qsl], o.score(q[qsl], xt), qs_n[qsl] @ nu_np[rows].T, f"C3m logits, head {g}")
+        P.check_close(s_gpu[qsl], o.score(q[qsl], xt), qs_n[qsl] @ nu_np[rows].T, f"{name} logits, head {g}")
 
 
 @pytest.mark.parametrize("d_hi,vbits_lo,kd_hi,n_groups,qpg,npg", [

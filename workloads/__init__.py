@@ -51,6 +51,9 @@ CONFIGS = {
     # 2.5 bits per channel: 64 outlier channels at b = 3, 64 at b = 2 (shapes of C2 / C3)
     "C2m": Config("C2m", "prod", 2, 128, 16384, 8, 32, 4, "bf16", False, 0, 2, 3, 100, 200, 64),
     "C3m": Config("C3m", "prod", 2, 128, 65536, 8, 32, 4, "bf16", False, 0, 2, 3, 100, 200, 64),
+    # 3.5 bits per channel: 64 outlier channels at b = 4, 64 at b = 3
+    "C2h": Config("C2h", "prod", 3, 128, 16384, 8, 32, 4, "bf16", False, 0, 2, 3, 100, 200, 64),
+    "C3h": Config("C3h", "prod", 3, 128, 65536, 8, 32, 4, "bf16", False, 0, 2, 3, 100, 200, 64),
     "C4": Config("C4", "mse", 4, 1536, 1000000, 1, 1000, 1000, "f32", True, 10, 4, 5, 101, 201),
     "C5": Config("C5", "prod", 2, 3072, 1000000, 1, 1000, 1000, "f32", True, 10, 6, 7, 102, 202),
 }
