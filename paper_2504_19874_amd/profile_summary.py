@@ -97,14 +97,23 @@ def per_kernel(dirname, counter):
 
 def traffic(fetch_dir, write_dir, workload, json_path):
     fetch, write = per_kernel(fetch_dir, "FETCH_SIZE"), per_kernel(write_dir, "WRITE_SIZE")
-    copy = [k for k in fetch if "copyBuffer" in k or "direct_copy" in k or "CUDAFunctor" in k]
-    copy = max(copy, key=lambda k: max(fetch[k])) if copy else None
-    if copy is None or max(fetch[copy]) < COPY_KIB / 8:
+    # the calibration copy is the launch of a copy kernel that wrote 256 MiB (WRITE_SIZE counts every byte
+    # written, which the copy itself shows); other copies in the trace (inputs being laid out) have other sizes.
+    # The two runs execute the same program, so launch i of a kernel is the same launch in both.
+    copy, at = None, -1
+    for k in write:
+        if not ("copyBuffer" in k or "direct_copy" in k or "CUDAFunctor" in k) or k not in fetch:
+            continue
+        for i, w in enumerate(write[k]):
+            if abs(w - COPY_KIB) < 0.05 * COPY_KIB and i < len(fetch[k]):
+                copy, at = k, i
+    if copy is None:
         sys.exit("no calibration copy in the trace (run bench.py with --calibration-copy)")
-    f_scale = COPY_KIB / max(fetch[copy])
-    w_scale = COPY_KIB / max(write[copy])
-    print(f"calibration copy `{short(copy, 60)}`: FETCH_SIZE {max(fetch[copy]):.1f} KiB -> scale {f_scale:.4f}, "
-          f"WRITE_SIZE {max(write[copy]):.1f} KiB -> scale {w_scale:.4f}\n")
+    f_copy, w_copy = fetch[copy][at], write[copy][at]
+    f_scale = COPY_KIB / f_copy
+    w_scale = COPY_KIB / w_copy
+    print(f"calibration copy `{short(copy, 60)}`: FETCH_SIZE {f_copy:.1f} KiB -> scale {f_scale:.4f}, "
+          f"WRITE_SIZE {w_copy:.1f} KiB -> scale {w_scale:.4f}\n")
     print("| call | kernel | launches | FETCH_SIZE KiB | WRITE_SIZE KiB | HBM bytes (scaled) |")
     print("|---|---|---|---|---|---|")
     table = {}
