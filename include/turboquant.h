@@ -51,11 +51,15 @@
  * (bf16 pieces of 8 significant bits each, or base-128 digits of a fixed-point
  * value with 2^-19 relative spacing):
  *   quantise, bf16 batches above 8192 vectors at d = 128 and every d other
- *     than 128: the rotation from three pieces of Pi and three of x (a bf16
- *     x is one piece), i.e. to fp32 accuracy; the sketch, of which only signs
- *     are kept, from
- *     two pieces of the residual and two of S Pi^T (a sign can differ from the
- *     exact one only where |<S_j, r>| < 1e-6 |S_j| |r|);
+ *     than 128: the rotation from three pieces of Pi and the two leading
+ *     pieces of an fp32 x (a bf16 x is one exact piece); what is dropped of x is
+ *     below 2^-18 |x_k| per element, so a rotated coordinate moves by at most
+ *     2^-18 |Pi_j| |x| = 3.8e-6 of the unit norm and the rotated vector by that in
+ *     L2 norm: an index can differ from the fp32 evaluation only inside the
+ *     1e-5 band around a cell boundary that every path is allowed.  The sketch,
+ *     of which only signs are kept, from two pieces of the residual and two of
+ *     S Pi^T (a sign can differ from the exact one only where
+ *     |<S_j, r>| < 1e-6 |S_j| |r|);
  *   dequantise, large batches: two pieces of each factor (error
  *     below 4e-5 of a coordinate's typical size), at every d;
  *   scoring: two bf16 pieces of each factor (many queries; scores within
