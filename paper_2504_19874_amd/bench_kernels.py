@@ -13,7 +13,8 @@ inputs are rotated through several buffer sets so HBM-bound figures are not
 cache figures ("cold"); `--warm` disables that.  Inputs come from the seeded
 generators in workloads/.  Also times a plain device-to-device copy of the
 same size as the stage kernels' traffic, as the reference for what a
-streaming kernel reaches on this chip.
+streaming kernel reaches on this chip.  `--only intake` runs no entry point
+but a probe: how long one workgroup per compute unit needs to take in N KB.
 """
 from __future__ import annotations
 
@@ -62,6 +63,35 @@ def report(name, cfg, ms, flops, nbytes, extra=None, bound=None):
     print(json.dumps(out), flush=True)
 
 
+def intake_probe(torch):
+    """`--only intake`: time for one workgroup per compute unit to take in a given number of KB, part of it a
+    region all workgroups share (the parameter matrices of the few-query scoring kernel) and part its own (its
+    codes), from the probe kernel in libtqprobe.so.  Own regions are rotated through 12 buffers (cold)."""
+    import ctypes as C
+    lib = C.CDLL(os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtqprobe.so"))
+    lib.tq_probe_intake.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p]
+    lib.tq_probe_intake.restype = C.c_int
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    sets = 12
+    shared = torch.empty(128 << 10, dtype=torch.uint8, device="cuda").random_(0, 255)
+    own = [torch.empty(cus * (240 << 10), dtype=torch.uint8, device="cuda").random_(0, 255) for _ in range(sets)]
+    out = torch.empty(cus * 512, dtype=torch.int32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    for shared_kb, own_kb in ((0, 8), (0, 56), (0, 112), (0, 176), (0, 240), (64, 0), (128, 0), (32, 112), (64, 112),
+                              (128, 112), (64, 56), (128, 56)):
+        def run(r):
+            rc = lib.tq_probe_intake(shared.data_ptr(), shared_kb, own[r % sets].data_ptr(), own_kb, out.data_ptr(), cus,
+                                     stream)
+            if rc != 0:
+                raise RuntimeError(f"tq_probe_intake({shared_kb}, {own_kb}) returned {rc}")
+        avg, mn, med = timed(run, 60)
+        kb = shared_kb + own_kb
+        print(json.dumps({"probe": "intake", "workgroups": cus, "shared_kb": shared_kb, "own_kb": own_kb,
+                          "avg_us": round(avg * 1e3, 2), "min_us": round(mn * 1e3, 2), "median_us": round(med * 1e3, 2),
+                          "hbm_gbs": round(cus * own_kb * 1024 / (med * 1e-3) / 1e9, 1),
+                          "bytes_per_us_per_cu": round(kb * 1024 / (med * 1e3), 1)}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--config", default="C2")
@@ -89,6 +119,10 @@ def main():
         dst.copy_(src)  # 256 MiB read + 256 MiB written
         torch.cuda.synchronize()
         del src, dst
+
+    if args.only == "intake":
+        intake_probe(torch)
+        return
 
     cfg = W.CONFIGS[args.config]
     prod = cfg.kind == "prod"

@@ -5,10 +5,11 @@
 // how the data gets to the matrix cores.
 //
 // Measured with cycle stamps inside the kernel: what a workgroup waits for is
-// neither HBM as such nor the MFMAs but its own loads.  A compute unit takes in
-// only 10-14 bytes per clock (outstanding misses x line size / latency), and a
-// lane that fetches its own 8-byte share of 16 different code rows makes the
-// memory pipeline touch every cache line four times on top of that.  So here
+// not the MFMAs but its own loads.  When every compute unit asks for its 240 KB
+// at once they arrive over about 17 000 cycles (the chip's HBM rate shared by
+// 256 workgroups: 10-14 bytes per clock each), and a lane that fetches its own
+// 8-byte share of 16 different code rows makes the memory pipeline touch every
+// cache line four times on top of that.  So here
 //   * a wavefront reads the codes of its keys as plain contiguous 16-byte-per-
 //     lane loads (1 KB per instruction) and parks them in a private LDS region;
 //     the tiles later pick their words out of LDS in operand order,
