@@ -199,6 +199,8 @@ typedef struct tq_params {
   const float* bounds_hi;     /* host, 2^bits_mse_hi - 1 floats; `centroids`/`bounds`   */
                               /* are then the codebook of dimension d - d_hi            */
   uint32_t flags;             /* TQ_FLAG_* bits, 0 = the library's own choice           */
+  const void* images;         /* device, nullable: tq_images_bytes(d) bytes filled by
+                                 tq_build_images from THESE matrices (see there)        */
 } tq_params;
 
 /* Keep every contraction of tq_quantize_*, tq_dequantize and many-query
@@ -218,6 +220,20 @@ typedef struct tq_params {
  */
 tq_status tq_derive_params(int32_t d, const float* Pi, const float* S, float* PiT, float* ST,
                            float* SPiT, void* stream);
+
+/* Optional, once per parameter set: the matrices in the form the large-batch d = 128 kernels keep them in on-chip
+ * memory (bf16 pieces of Pi, S Pi^T, Pi^T and S^T, rows and columns in the kernels' own order), so that a
+ * kernel's prologue is a copy instead of 128 KB of fp32 loads and their splitting on every launch (Alg. 1 / Alg. 2
+ * fix the matrices "at setup"; this is that setup carried one step further).  tq_images_bytes: size of the
+ * buffer for dimension d, 0 where no kernel takes one (every d other than 128; tq_build_images then does
+ * nothing).  tq_build_images reads p->Pi, p->PiT and, when p->S is set, p->ST and p->SPiT (device, as
+ * tq_derive_params left them) and writes `images` (device, 16-byte aligned, owned by the caller) on `stream`; the
+ * caller then stores the pointer in params.images.  A null params.images is always valid and gives identical
+ * results.  The image must be rebuilt whenever one of the matrices changes: the kernels that take it do not look
+ * at the fp32 matrices again.  Errors: TQ_ERR_INVALID_ARG (null pointers, S given without ST / SPiT),
+ * TQ_ERR_UNSUPPORTED (misaligned), TQ_ERR_HIP. */
+size_t tq_images_bytes(int32_t d);
+tq_status tq_build_images(const tq_params* p, void* images, void* stream);
 
 /* Device scratch large enough for any call with up to n vectors (per call),
  * nq queries and this topk under these params: an upper bound that counts a

@@ -27,6 +27,7 @@ class TqParams(C.Structure):
         ("centroids_hi", C.c_void_p),
         ("bounds_hi", C.c_void_p),
         ("flags", C.c_uint32),
+        ("images", C.c_void_p),
     ]
 
 TQ_FLAG_FP32_MFMA = 1
@@ -40,6 +41,8 @@ SIGNATURES = {
     "tq_status_string": (C.c_char_p, [C.c_int]),
     "tq_build_codebook": (C.c_int, [_i32, _i32, _vp, _vp, C.POINTER(C.c_double)]),
     "tq_bucket_masses": (C.c_int, [_i32, _i32, _vp, _vp]),
+    "tq_images_bytes": (C.c_size_t, [_i32]),
+    "tq_build_images": (C.c_int, [_P, _vp, _vp]),
     "tq_prefix_code_build": (C.c_int, [_i32, _vp, _vp, _vp, C.POINTER(C.c_double)]),
     "tq_entropy_encode": (C.c_int, [_i32, _i32, _vp, _vp, _vp, _i64, _vp, C.c_size_t, C.POINTER(C.c_size_t), _vp]),
     "tq_entropy_decode": (C.c_int, [_i32, _i32, _vp, _vp, C.c_size_t, C.c_uint64, _i64, _vp]),

@@ -127,6 +127,22 @@ class Params:
             self.c.bounds_hi = self._bounds_hi_buf.ctypes.data
         _check(lib.tq_derive_params(self.d, _ptr(self.Pi), _ptr(self.S), _ptr(self.PiT), _ptr(self.ST),
                                     _ptr(self.SPiT), _stream()), "tq_derive_params")
+        self.c.images, self.images = 0, None
+        self.build_images()
+
+    def build_images(self):
+        """The matrices in the form the large-batch d = 128 kernels keep on chip (tq_build_images); a no-op at
+        other dimensions.  `drop_images` goes back to splitting them in every launch (same results)."""
+        need = int(_lib.load().tq_images_bytes(self.d))
+        if need:
+            self.images = torch.empty(need, dtype=torch.uint8, device=self.device)
+            _check(_lib.load().tq_build_images(C.byref(self.c), _ptr(self.images), _stream()), "tq_build_images")
+            self.c.images = self.images.data_ptr()
+        return self
+
+    def drop_images(self):
+        self.c.images, self.images = 0, None
+        return self
 
     def reserve(self, n: int, nq: int = 0, topk: int = 0):
         """Size the device workspace for calls with up to n vectors / nq queries."""
@@ -170,6 +186,10 @@ class Params:
     @property
     def qjl_words(self) -> int:
         return self.d // 32
+
+
+def tq_images_bytes(d: int) -> int:
+    return int(_lib.load().tq_images_bytes(d))
 
 
 def tq_workspace_bytes(p: Params, n: int, nq: int, topk: int) -> int:

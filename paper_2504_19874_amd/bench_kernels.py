@@ -100,6 +100,8 @@ def main():
     ap.add_argument("--only", default="")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
+    ap.add_argument("--no-images", action="store_true",
+                    help="d = 128: split the matrices in every launch instead of using the images of tq_build_images")
     ap.add_argument("--value-bits", type=int, default=2, help="attend: bits of the MSE stage of the value codes")
     ap.add_argument("--value-prod", action="store_true", help="attend: value codes from TurboQuant_prod")
     ap.add_argument("--value-split", type=int, default=0, metavar="D_HI",
@@ -139,6 +141,8 @@ def main():
     else:
         S = W.sketch_matrix(d, cfg.seed_s) if prod else None
         p = tq.make_params(d, cfg.bits_mse, W.gaussian_matrix(d, cfg.seed_pi), S)
+    if args.no_images:
+        p.drop_images()
     # quantisation scratch, then exactly what this configuration's scoring call takes (no score matrix
     # where the top-k selection runs inside the scoring kernel)
     p.reserve(n, nq, 0).reserve_score(cfg.n_groups, cfg.q_per_group, cfg.n, prod, not cfg.topk, cfg.topk)

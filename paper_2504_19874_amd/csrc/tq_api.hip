@@ -78,6 +78,12 @@ float kappa_of(int d) { return (float)(std::sqrt(1.5707963267948966) / (double)d
 // TQ_FLAG_FP32_MFMA keeps every contraction of the call on the fp32 matrix instructions
 bool fp32_mfma_only(const tq_params* p) { return (p->flags & TQ_FLAG_FP32_MFMA) != 0; }
 
+// tq_params.images: [image of the d = 128 quantisation kernel][image of the d = 128 dequantisation kernel]
+const void* quant_image(const tq_params* p) { return p->d == 128 ? p->images : nullptr; }
+const void* dequant_image(const tq_params* p) {
+  return p->d == 128 && p->images != nullptr ? static_cast<const char*>(p->images) + quant128_bf3_image_bytes() : nullptr;
+}
+
 tq_status from_hip(hipError_t e) { return e == hipSuccess ? TQ_OK : TQ_ERR_HIP; }
 
 struct Workspace {
@@ -129,7 +135,7 @@ tq_status quantize_common(const tq_params* p, const void* x, int32_t dtype, int6
     if (dtype == TQ_BF16 && n >= kBf3QuantRows && !fp32_mfma_only(p) && (!prod || aligned16(qjl)) &&
         quant128_bf3_applicable(p->bits_mse, prod, x, ldx, make_codebook(p), &cb_hi))
       return from_hip(launch_quant128_bf3(p->bits_mse, prod, x, ldx, n, p->Pi, prod ? p->SPiT : nullptr, idx, qjl, gamma,
-                                          norm, make_codebook(p), p->d_hi / 32, make_codebook_hi(p), stream));
+                                          norm, make_codebook(p), p->d_hi / 32, make_codebook_hi(p), quant_image(p), stream));
     return from_hip(launch_quant128(p->bits_mse, prod, dtype == TQ_BF16, x, ldx, n, p->Pi,
                                     prod ? p->SPiT : nullptr, idx, qjl, gamma, norm, make_codebook(p),
                                     p->d_hi / 32, make_codebook_hi(p), stream));
@@ -139,7 +145,7 @@ tq_status quantize_common(const tq_params* p, const void* x, int32_t dtype, int6
   if (d == 128 && dtype == TQ_BF16 && n >= kBf3QuantRows && !fp32_mfma_only(p) && quant128_bf3_applicable(p->bits_mse, prod, x, ldx, make_codebook(p), nullptr) &&
       (p->bits_mse == 0 || aligned16(idx)) && (!prod || aligned16(qjl)))
     return from_hip(launch_quant128_bf3(p->bits_mse, prod, x, ldx, n, p->Pi, prod ? p->SPiT : nullptr, idx, qjl, gamma,
-                                        norm, make_codebook(p), 0, make_codebook(p), stream));
+                                        norm, make_codebook(p), 0, make_codebook(p), quant_image(p), stream));
 
   // head dimension 128: one fused kernel, parameters resident in LDS
   if (d == 128 && aligned16(x) && (ldx * esz) % 16 == 0) {
@@ -228,6 +234,24 @@ const char* tq_status_string(tq_status s) {
   }
 }
 
+size_t tq_images_bytes(int32_t d) {
+  return d == 128 ? quant128_bf3_image_bytes() + dequant128_bf3_image_bytes() : 0;
+}
+
+tq_status tq_build_images(const tq_params* p, void* images, void* stream) {
+  if (p == nullptr || p->d <= 0) return TQ_ERR_INVALID_ARG;
+  if (tq_images_bytes(p->d) == 0) return TQ_OK;  // no kernel at this d takes one
+  if (images == nullptr || p->Pi == nullptr || p->PiT == nullptr) return TQ_ERR_INVALID_ARG;
+  if ((p->S == nullptr) != (p->ST == nullptr) || (p->S == nullptr) != (p->SPiT == nullptr)) return TQ_ERR_INVALID_ARG;
+  if (!aligned16(images) || !aligned16(p->Pi) || !aligned16(p->PiT) || (p->S != nullptr && (!aligned16(p->ST) || !aligned16(p->SPiT))))
+    return TQ_ERR_UNSUPPORTED;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (launch_quant128_bf3_image(p->Pi, p->SPiT, images, s) != hipSuccess) return TQ_ERR_HIP;
+  if (launch_dequant128_bf3_image(p->PiT, p->ST, static_cast<char*>(images) + quant128_bf3_image_bytes(), s) != hipSuccess)
+    return TQ_ERR_HIP;
+  return TQ_OK;
+}
+
 tq_status tq_derive_params(int32_t d, const float* Pi, const float* S, float* PiT, float* ST,
                            float* SPiT, void* stream) {
   if (d <= 0 || Pi == nullptr) return TQ_ERR_INVALID_ARG;
@@ -308,7 +332,7 @@ tq_status tq_dequantize(const tq_params* p, const uint32_t* idx, const uint32_t*
     if (n > kBf3DequantRows && !fp32_mfma_only(p) && p->PiT != nullptr && (!prod || p->ST != nullptr))
       return from_hip(launch_dequant128_bf3(p->bits_mse, prod, idx, qjl, gamma, norm, p->PiT, p->ST, x_out, ldo, n,
                                             kappa_of(p->d - p->d_hi), make_codebook(p), p->d_hi / 32, kappa_of(p->d_hi),
-                                            make_codebook_hi(p), static_cast<hipStream_t>(stream)));
+                                            make_codebook_hi(p), dequant_image(p), static_cast<hipStream_t>(stream)));
     return from_hip(launch_dequant128(p->bits_mse, prod, idx, qjl, gamma, norm, p->Pi, p->S, x_out, ldo, n,
                                       kappa_of(p->d - p->d_hi), make_codebook(p), p->d_hi / 32,
                                       kappa_of(p->d_hi), make_codebook_hi(p), static_cast<hipStream_t>(stream)));
@@ -316,7 +340,8 @@ tq_status tq_dequantize(const tq_params* p, const uint32_t* idx, const uint32_t*
   // large batches at d = 128: decoded codes straight into bf16 MFMA operands, pieces of Pi^T / S^T in LDS
   if (p->d == 128 && n > kBf3DequantRows && !fp32_mfma_only(p) && dequant128_bf3_applicable(p->bits_mse, prod, make_codebook(p), x_out, ldo))
     return from_hip(launch_dequant128_bf3(p->bits_mse, prod, idx, qjl, gamma, norm, p->PiT, p->ST, x_out, ldo, n,
-                                          kappa_of(128), make_codebook(p), 0, 0.f, make_codebook(p), static_cast<hipStream_t>(stream)));
+                                          kappa_of(128), make_codebook(p), 0, 0.f, make_codebook(p), dequant_image(p),
+                                          static_cast<hipStream_t>(stream)));
   if (p->d == 128 && p->Pi != nullptr && aligned16(p->Pi) && (!prod || (p->S != nullptr && aligned16(p->S))) &&
       aligned16(idx) && (!prod || aligned16(qjl))) {
     return from_hip(launch_dequant128(p->bits_mse, prod, idx, qjl, gamma, norm, p->Pi, p->S, x_out, ldo, n,

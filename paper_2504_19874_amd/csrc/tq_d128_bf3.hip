@@ -13,8 +13,9 @@
 // coordinate's typical size, against the 1e-4 the output has to meet).  The sign part is folded into the same
 // accumulator: its operand is +-(kappa gamma_i), the two leading pieces of kappa gamma_i with the sign bit of
 // z_ij, against two pieces of S^T, again three products.  A 1-bit table is +-c_1: the pieces of c_1 with a sign.
-// Workgroup = 4 wavefronts, one per SIMD; a wavefront takes 64 vectors per block (every LDS read of a B operand
-// feeds at least two MFMAs), workgroups stride over the blocks of 256 vectors.
+// Workgroup = 8 wavefronts, two per SIMD; a wavefront takes 32 vectors per block, workgroups stride over the
+// blocks of 256 vectors.  (Four wavefronts of 64 vectors halve the LDS reads per MFMA but leave every SIMD idle
+// while its one wavefront pushes out the block's stores: 13-20 % slower.)
 #include "tq_bf3.h"
 
 namespace tq {
@@ -35,6 +36,7 @@ struct Dq128Args {
   const float* norm;  // nullable
   const float* PiT;
   const float* ST;
+  const u32x4* image;  // nullable: Pi^T and S^T as the kernel's LDS image, made ahead of time by dq128_image_kernel
   float* out;
   int64_t ldo;
   int64_t n;
@@ -48,8 +50,41 @@ struct Dq128Args {
   Codebook cb_hi;
 };
 
-template <int BITS, bool PROD, bool MIXED>
-__global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) {
+// One 128 x 128 fp32 matrix as its two leading pieces at dst ([piece][k][128], chunk rotation of lds_at), by 256
+// threads.  dst is LDS in the dequantisation kernel and device memory in dq128_image_kernel.
+__device__ __forceinline__ void dq128_split_matrix(const float* W, unsigned short* dst, int tid) {
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    f32x4 v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const f32x4*>(W + half * 8192 + (i * 256 + tid) * 4);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int e = half * 8192 + (i * 256 + tid) * 4;
+      const int k = e >> 7, j = e & 127;
+      uint32_t lo[2], hi[2];
+      split2_pair(f32x2{v[i][0], v[i][1]}, lo[0], lo[1]);
+      split2_pair(f32x2{v[i][2], v[i][3]}, hi[0], hi[1]);
+#pragma unroll
+      for (int pc = 0; pc < 2; ++pc)
+        *reinterpret_cast<uint2*>(dst + pc * MAT_ELEMS + lds_at(k, j)) = make_uint2(lo[pc], hi[pc]);
+    }
+  }
+}
+
+// workgroup 0: Pi^T, workgroup 1: S^T, each 2 * MAT_ELEMS * 2 bytes of the image
+__global__ __launch_bounds__(256) void dq128_image_kernel(const float* PiT, const float* ST, unsigned short* image) {
+  const float* W = blockIdx.x == 0 ? PiT : ST;
+  if (W != nullptr) dq128_split_matrix(W, image + blockIdx.x * 2 * MAT_ELEMS, threadIdx.x);
+}
+
+// VT = vector tiles (of 32) per wavefront.  VT = 2: four wavefronts of 64 vectors, each LDS read of a matrix
+// operand feeds both tiles.  VT = 1: eight wavefronts of 32 vectors, two per SIMD, so that one can issue MFMAs
+// while the other sits in the burst of stores that ends its block; every variant stays within the 256 registers
+// that leaves a wavefront.  VT = 1 is what is launched.
+template <int BITS, bool PROD, bool MIXED, int VT>
+__global__ __launch_bounds__(512 / VT) void dequant128_bf3_kernel(const Dq128Args a) {
+  constexpr int NT = 512 / VT;  // threads
   constexpr bool TABLE = BITS >= 2 || MIXED;  // centroid pieces looked up in LDS (1 bit: the pieces of c_1 with a sign)
   constexpr int NB = (BITS > 0 ? BITS : 1) + (MIXED ? 1 : 0);  // plane words per coordinate group, at most
   constexpr int MATS = (BITS > 0 || MIXED ? 1 : 0) + (PROD ? 1 : 0);
@@ -67,23 +102,17 @@ __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) 
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
       if (s == 0 ? !PI : !PROD) continue;
-      const float* W = s == 0 ? a.PiT : a.ST;
+      if (a.image != nullptr) {
+        // a straight copy of the matrix's 64 KB, 16 bytes per thread and step
+        const u32x4* const src = a.image + s * (2 * MAT_ELEMS * 2 / 16);
+        u32x4* const dst = reinterpret_cast<u32x4*>(lds_s + m * 2 * MAT_ELEMS);
+        u32x4 v[4096 / NT];
 #pragma unroll
-      for (int half = 0; half < 2; ++half) {
-        f32x4 v[8];
+        for (int i = 0; i < 4096 / NT; ++i) v[i] = src[i * NT + tid];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const f32x4*>(W + half * 8192 + (i * 256 + tid) * 4);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const int e = half * 8192 + (i * 256 + tid) * 4;
-          const int k = e >> 7, j = e & 127;
-          uint32_t lo[2], hi[2];
-          split2_pair(f32x2{v[i][0], v[i][1]}, lo[0], lo[1]);
-          split2_pair(f32x2{v[i][2], v[i][3]}, hi[0], hi[1]);
-#pragma unroll
-          for (int pc = 0; pc < 2; ++pc)
-            *reinterpret_cast<uint2*>(lds_s + (m * 2 + pc) * MAT_ELEMS + lds_at(k, j)) = make_uint2(lo[pc], hi[pc]);
-        }
+        for (int i = 0; i < 4096 / NT; ++i) dst[i * NT + tid] = v[i];
+      } else {
+        if (tid < 256) dq128_split_matrix(s == 0 ? a.PiT : a.ST, lds_s + m * 2 * MAT_ELEMS, tid);
       }
       ++m;
     }
@@ -112,25 +141,27 @@ __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) 
   if (MIXED) {
     // thread t scans one half of the range for row t / 2; the flags go through LDS (behind the table)
     uint32_t* const flag_s = table_s + 32;
-    const float* row = (PROD ? a.ST : a.PiT) + (tid >> 1) * 128;
-    bool any = false;
-    for (int j = 16 * gs * (tid & 1); j < 16 * gs * ((tid & 1) + 1); j += 4) {
-      const f32x4 v = *reinterpret_cast<const f32x4*>(row + j);
-      any = any || v[0] != 0.f || v[1] != 0.f || v[2] != 0.f || v[3] != 0.f;
+    if (tid < 256) {
+      const float* row = (PROD ? a.ST : a.PiT) + (tid >> 1) * 128;
+      bool any = false;
+      for (int j = 16 * gs * (tid & 1); j < 16 * gs * ((tid & 1) + 1); j += 4) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(row + j);
+        any = any || v[0] != 0.f || v[1] != 0.f || v[2] != 0.f || v[3] != 0.f;
+      }
+      flag_s[tid] = any ? 1u : 0u;
     }
-    flag_s[tid] = any ? 1u : 0u;
     __syncthreads();
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct) hi_cols |= (flag_s[2 * (4 * vi + ct)] | flag_s[2 * (4 * vi + ct) + 1]) << ct;
   }
 
   // MIXED: nu / kg are instance lo's, nuh / kgh instance hi's
-  uint32_t w[2][4][NB], z[2][4], wn[2][4][NB], zn[2][4];
-  float nu[2], kg[2], nun[2], kgn[2], nuh[2] = {0.f, 0.f}, kgh[2] = {0.f, 0.f}, nuhn[2] = {0.f, 0.f}, kghn[2] = {0.f, 0.f};
+  uint32_t w[VT][4][NB], z[VT][4], wn[VT][4][NB], zn[VT][4];
+  float nu[VT], kg[VT], nun[VT], kgn[VT], nuh[VT] = {}, kgh[VT] = {}, nuhn[VT] = {}, kghn[VT] = {};
   auto load_code = [&](int64_t blk) {  // into the "next" registers
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
-      const int64_t v = blk * 256 + wave * 64 + 32 * mt + vi;
+    for (int mt = 0; mt < VT; ++mt) {
+      const int64_t v = blk * 256 + wave * (32 * VT) + 32 * mt + vi;
       const int64_t row = v < a.n ? v : a.n - 1;  // clamped: such rows are not stored
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
@@ -166,7 +197,7 @@ __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) 
   load_code(blockIdx.x);
   for (int64_t blk = blockIdx.x; blk < blocks; blk += gridDim.x) {
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
+    for (int mt = 0; mt < VT; ++mt) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
 #pragma unroll
@@ -179,16 +210,16 @@ __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) 
       kgh[mt] = kghn[mt];
     }
     load_code(blk + gridDim.x);  // the next block's codes travel during this block (clamped past the end)
-    floatx16 acc[2][4];  // [vector tile][column tile]
+    floatx16 acc[VT][4];  // [vector tile][column tile]
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+    for (int mt = 0; mt < VT; ++mt)
 #pragma unroll
       for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[mt][ct][r] = 0.f;
-    uint32_t kgp[2][2], kghp[2][2];  // the two pieces of kappa gamma of this lane's vectors, each twice in a word
+    uint32_t kgp[VT][2], kghp[VT][2];  // the two pieces of kappa gamma of this lane's vectors, each twice in a word
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
+    for (int mt = 0; mt < VT; ++mt) {
       uint32_t p1, p2, p3;
       split3(kg[mt], p1, p2, p3);
       kgp[mt][0] = p1 * 0x00010001u;
@@ -201,11 +232,11 @@ __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) 
 #pragma unroll
     for (int r = 0; r < RING; ++r) ring[r] = b_piece(0, r);
     // table entries of the coordinates of one step, looked up one step ahead: they travel during the MFMAs
-    uint32_t te[2][8];
+    uint32_t te[VT][8];
     auto look_up = [&](int s) {
       const int g = s >> 1, off = (s & 1) * 16 + 8 * jg;
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
+      for (int mt = 0; mt < VT; ++mt) {
         uint32_t lv[2] = {0u, 0u};  // bucket numbers of 4 coordinates, one per byte
 #pragma unroll
         for (int h = 0; h < 2; ++h)
@@ -222,9 +253,9 @@ __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) 
     for (int s = 0; s < 8; ++s) {
       const int g = s >> 1, off = (s & 1) * 16 + 8 * jg;  // word of the code, first bit
       // ---- A operands: this lane's 8 coordinates of two vectors decoded into pieces ----------------------
-      bf16x8 ca[2][2], za[2][2];
+      bf16x8 ca[VT][2], za[VT][2];
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
+      for (int mt = 0; mt < VT; ++mt) {
         if (BITS == 1 && !MIXED) {
           u32x4 v1, v2;
 #pragma unroll
@@ -271,11 +302,11 @@ __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) 
         // one accumulator are kept apart by the other vector tile's
         if (pc == 0) {
 #pragma unroll
-          for (int mt = 0; mt < 2; ++mt)
+          for (int mt = 0; mt < VT; ++mt)
             acc[mt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sign_part ? za[mt][1] : ca[mt][1], b, acc[mt][ct], 0, 0, 0);
         }
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
+        for (int mt = 0; mt < VT; ++mt)
           acc[mt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sign_part ? za[mt][0] : ca[mt][0], b, acc[mt][ct], 0, 0, 0);
         const int nxt = s * READS + r + RING;  // the read that takes this slot
         if (nxt < 8 * READS) ring[nxt % RING] = b_piece(nxt / READS, nxt % READS);
@@ -283,10 +314,17 @@ __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) 
       }
     }
     // ---- epilogue: D[vector][k]; the factors of a row's vector sit in the lane with that number --------
-    const int64_t v0 = blk * 256 + wave * 64;
-    const bool full = v0 + 64 <= a.n;  // uniform: no vector of this wavefront is past the end
+    // Addresses: a base that is uniform over the wavefront (scalar registers) plus a 32-bit byte offset per lane
+    // that advances by a scalar from row to row: one vector add per store.  (Written as out + v * ldo per lane,
+    // every one of the 32 stores carried its own 64-bit multiply.)
+    const int64_t v0 = blk * 256 + wave * (32 * VT);
+    const bool full = v0 + 32 * VT <= a.n;  // uniform: no vector of this wavefront is past the end
+    char* const wbase = reinterpret_cast<char*>(a.out + v0 * a.ldo);
+    const int rows_left = full ? 32 * VT : (int)(a.n - v0 > 0 ? a.n - v0 : 0);
+    const uint32_t row_bytes = (uint32_t)a.ldo * 4u;
+    const uint32_t lane_off = 4u * (uint32_t)(lane >> 5) * row_bytes + 16u * (uint32_t)vi;
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
+    for (int mt = 0; mt < VT; ++mt) {
       // every row's norm first (one LDS round trip for all of them), then the arithmetic and the stores
       float rnu[16], rnuh[MIXED ? 16 : 1];
 #pragma unroll
@@ -297,25 +335,33 @@ __global__ __launch_bounds__(256) void dequant128_bf3_kernel(const Dq128Args a) 
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int64_t v = v0 + 32 * mt + 8 * (r >> 2) + (r & 3) + 4 * (lane >> 5);
+        const int row = 32 * mt + 8 * (r >> 2) + (r & 3);  // of lanes 0..31; lanes 32..63 hold row + 4
         f32x4 o;
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct) o[ct] = (MIXED && ((hi_cols >> ct) & 1u) ? rnuh[MIXED ? r : 0] : rnu[r]) * acc[mt][ct][r];
-        if (full || v < a.n) __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(a.out + v * a.ldo + 4 * vi));
+        if (full || row + 4 * (lane >> 5) < rows_left)
+          __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(wbase + (lane_off + (uint32_t)row * row_bytes)));
       }
     }
   }
 }
 
-template <int BITS, bool PROD, bool MIXED>
-hipError_t launch_one(const Dq128Args& a, hipStream_t s) {
+template <int BITS, bool PROD, bool MIXED, int VT>
+hipError_t launch_vt(const Dq128Args& a, hipStream_t s) {
   constexpr int MATS = (BITS > 0 || MIXED ? 1 : 0) + (PROD ? 1 : 0);
   constexpr int lds = MATS * 2 * MAT_ELEMS * 2 + (32 + 256) * 4;  // matrices, centroid tables, column flags
   static LdsLimit lds_limit;  // per instantiation: the limit is raised once per device
-  if (const hipError_t e = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&dequant128_bf3_kernel<BITS, PROD, MIXED>), lds); e != hipSuccess) return e;
+  if (const hipError_t e = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&dequant128_bf3_kernel<BITS, PROD, MIXED, VT>), lds); e != hipSuccess) return e;
   const int64_t blocks = (a.n + 255) / 256, cus = device_cu_count();  // one workgroup per compute unit
-  hipLaunchKernelGGL((dequant128_bf3_kernel<BITS, PROD, MIXED>), dim3((unsigned)(blocks < cus ? blocks : cus)), dim3(256), lds, s, a);
+  hipLaunchKernelGGL((dequant128_bf3_kernel<BITS, PROD, MIXED, VT>), dim3((unsigned)(blocks < cus ? blocks : cus)), dim3(512 / VT), lds, s, a);
   return hipGetLastError();
+}
+
+// eight wavefronts of 32 vectors: measured against four of 64 (VT = 2) on the same box, 524288 vectors: 110 against
+// 127 us (two-instance codes and 4-bit codes alike), 131072 vectors: 30 against 38 us
+template <int BITS, bool PROD, bool MIXED>
+hipError_t launch_one(const Dq128Args& a, hipStream_t s) {
+  return launch_vt<BITS, PROD, MIXED, 1>(a, s);
 }
 
 }  // namespace
@@ -324,6 +370,7 @@ hipError_t launch_one(const Dq128Args& a, hipStream_t s) {
 bool dequant128_bf3_applicable(int bits, bool prod, const Codebook& cb, const float* out, int64_t ldo) {
   if (bits < 0 || bits > 4 || (bits == 0 && !prod)) return false;
   if ((reinterpret_cast<uintptr_t>(out) & 15u) != 0 || ldo % 4 != 0) return false;
+  if (ldo < 128 || ldo > (1 << 22)) return false;  // 64 rows of a wavefront are addressed with 32-bit byte offsets
   return bits != 1 || cb.c[0] == -cb.c[1];
 }
 
@@ -332,11 +379,13 @@ bool dequant128_bf3_applicable(int bits, bool prod, const Codebook& cb, const fl
 hipError_t launch_dequant128_bf3(int bits, bool prod, const uint32_t* idx, const uint32_t* qjl, const float* gamma,
                                  const float* norm, const float* PiT, const float* ST, float* out, int64_t ldo, int64_t n,
                                  float kappa, const Codebook& cb, int gs_hi, float kappa_hi, const Codebook& cb_hi,
-                                 hipStream_t s) {
+                                 const void* image, hipStream_t s) {
   if (n <= 0) return hipSuccess;
   if (gs_hi < 0 || gs_hi > 3 || (gs_hi > 0 && (bits > 3 || cb_hi.bits != bits + 1 || norm == nullptr))) return hipErrorInvalidValue;
   Dq128Args a;
   a.idx = idx; a.qjl = qjl; a.gamma = gamma; a.norm = norm; a.PiT = PiT; a.ST = ST; a.out = out; a.ldo = ldo; a.n = n;
+  a.image = static_cast<const u32x4*>(image);
+
   a.kappa = kappa; a.cb = cb; a.gs_hi = gs_hi; a.kappa_hi = kappa_hi; a.cb_hi = cb_hi;
   if (gs_hi > 0) {
     switch (bits * 2 + (prod ? 1 : 0)) {
@@ -363,6 +412,14 @@ hipError_t launch_dequant128_bf3(int bits, bool prod, const uint32_t* idx, const
     case 9: return launch_one<4, true, false>(a, s);
     default: return hipErrorInvalidValue;
   }
+}
+
+size_t dequant128_bf3_image_bytes() { return (size_t)4 * MAT_ELEMS * 2; }
+
+// ST may be null (no sketch): the second half of the image is left alone then
+hipError_t launch_dequant128_bf3_image(const float* PiT, const float* ST, void* image, hipStream_t s) {
+  hipLaunchKernelGGL(dq128_image_kernel, dim3(2), dim3(256), 0, s, PiT, ST, static_cast<unsigned short*>(image));
+  return hipGetLastError();
 }
 
 }  // namespace tq

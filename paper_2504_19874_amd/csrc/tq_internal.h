@@ -113,11 +113,17 @@ constexpr int64_t kBf3QuantRows = 8193;   // bf16 input: from here on the bf16-p
 bool quant128_bf3_applicable(int bits, bool prod, const void* X, int64_t ldx, const Codebook& cb, const Codebook* cb_hi);
 hipError_t launch_quant128_bf3(int bits, bool prod, const void* X, int64_t ldx, int64_t n, const float* Pi,
                                const float* SPiT, uint32_t* idx, uint32_t* qjl, float* gamma, float* norm,
-                               const Codebook& cb, int gs_hi, const Codebook& cb_hi, hipStream_t s);
+                               const Codebook& cb, int gs_hi, const Codebook& cb_hi, const void* image, hipStream_t s);
+// the matrices of those two kernels as they sit in LDS, made once (tq_build_images); null pointers above mean
+// "split the fp32 matrices in the kernel's prologue"
+size_t quant128_bf3_image_bytes();
+size_t dequant128_bf3_image_bytes();
+hipError_t launch_quant128_bf3_image(const float* Pi, const float* SPiT, void* image, hipStream_t s);
+hipError_t launch_dequant128_bf3_image(const float* PiT, const float* ST, void* image, hipStream_t s);
 hipError_t launch_dequant128_bf3(int bits, bool prod, const uint32_t* idx, const uint32_t* qjl, const float* gamma,
                                  const float* norm, const float* PiT, const float* ST, float* out, int64_t ldo, int64_t n,
                                  float kappa, const Codebook& cb, int gs_hi, float kappa_hi, const Codebook& cb_hi,
-                                 hipStream_t s);
+                                 const void* image, hipStream_t s);
 
 // few queries per code (tq_score_small.hip)
 hipError_t launch_matvec_small(int d, int nq, const float* W0, const float* W1, const float* x,

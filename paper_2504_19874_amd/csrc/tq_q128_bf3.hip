@@ -43,6 +43,7 @@ struct Q128Args {
   int64_t n;
   const float* Pi;
   const float* SPiT;
+  const u32x4* image;  // nullable: the LDS image below, made ahead of time by q128_image_kernel
   uint32_t* idx;
   uint32_t* qjl;
   float* gamma;
@@ -55,10 +56,56 @@ struct Q128Args {
   Codebook cb_hi;
 };
 
-// sum of the squares of two bf16 values (exact products, fp32 sum) added to acc
+// sum of the squares of two bf16 values added to acc: one two-element dot product with fp32 accumulation
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ float square_pair(uint32_t w, float acc) {
-  const float lo = __uint_as_float(w << 16), hi = __uint_as_float(w & 0xffff0000u);
-  return fmaf(hi, hi, fmaf(lo, lo, acc));
+  const bf16x2_t v = __builtin_bit_cast(bf16x2_t, w);
+  return __builtin_amdgcn_fdot2_f32_bf16(v, v, acc, false);
+}
+
+// position of column j inside its run of 16 in the image of S Pi^T: the two middle groups of four change
+// places (see stage 2)
+__device__ __forceinline__ int w_col(int j) { return (j & ~12) | ((j & 4) << 1) | ((j & 8) >> 1); }
+
+// The kernel's parameter image, by 256 threads: three pieces of Pi at dst, two of S Pi^T (columns permuted) behind
+// them, each [row][128] with the chunk rotation of lds_at.  dst is LDS in the quantisation kernel and device
+// memory in q128_image_kernel.
+__device__ __forceinline__ void q128_split_matrices(const float* Pi, const float* SPiT, unsigned short* dst, int tid) {
+  // rows [row0, row0 + 64) of a 128 x 128 fp32 matrix -> its leading `pieces` pieces; 8 x 16 bytes per thread
+  auto split_rows = [&](const f32x4 (&v)[8], unsigned short* out, int row0, int pieces, bool permute) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int e = (i * 256 + tid) * 4;
+      const int row = row0 + (e >> 7), j = e & 127;
+      uint32_t lo[3], hi[3];
+      split3_pair(f32x2{v[i][0], v[i][1]}, lo[0], lo[1], lo[2]);
+      split3_pair(f32x2{v[i][2], v[i][3]}, hi[0], hi[1], hi[2]);
+      const int at = lds_at(row, permute ? w_col(j) : j);
+#pragma unroll
+      for (int pc = 0; pc < 3; ++pc)
+        if (pc < pieces) *reinterpret_cast<uint2*>(out + pc * MAT_ELEMS + at) = make_uint2(lo[pc], hi[pc]);
+    }
+  };
+  auto fetch64 = [&](const float* src, f32x4 (&v)[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const f32x4*>(src + (i * 256 + tid) * 4);
+  };
+  f32x4 lo[8], hi[8];
+  fetch64(Pi, lo);
+  fetch64(Pi + 64 * 128, hi);
+  split_rows(lo, dst, 0, 3, false);
+  split_rows(hi, dst, 64, 3, false);
+  if (SPiT != nullptr) {
+    fetch64(SPiT, lo);
+    fetch64(SPiT + 64 * 128, hi);
+    split_rows(lo, dst + PI_ELEMS, 0, 2, true);
+    split_rows(hi, dst + PI_ELEMS, 64, 2, true);
+  }
+}
+
+// one workgroup of 256 threads: the image in device memory, (PI_ELEMS + W_ELEMS) * 2 bytes
+__global__ __launch_bounds__(256) void q128_image_kernel(const float* Pi, const float* SPiT, unsigned short* image) {
+  q128_split_matrices(Pi, SPiT, image, threadIdx.x);
 }
 
 template <int BITS, bool PROD, bool MIXED>
@@ -73,41 +120,20 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int vi = lane & 31, g = lane >> 5;
 
-  // position of column j inside its run of 16 in the image of S Pi^T: the two middle groups of four change
-  // places (see stage 2)
-  auto w_col = [](int j) { return (j & ~12) | ((j & 4) << 1) | ((j & 8) >> 1); };
-  // rows [row0, row0 + 64) of a 128 x 128 fp32 matrix -> its leading `pieces` pieces in LDS; 8 x 16 bytes per thread
-  auto split_to_lds = [&](const f32x4 (&v)[8], unsigned short* dst, int row0, int pieces, bool permute) {
+  if (a.image != nullptr) {
+    // a straight copy, 16 bytes per thread and step: 24 steps for Pi, 16 for S Pi^T
+    constexpr int STEPS = (PI_ELEMS + (PROD ? W_ELEMS : 0)) * 2 / (256 * 16);
+    u32x4* const dst = reinterpret_cast<u32x4*>(lds_s);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int e = (i * 256 + tid) * 4;
-      const int row = row0 + (e >> 7), j = e & 127;
-      uint32_t lo[3], hi[3];
-      split3_pair(f32x2{v[i][0], v[i][1]}, lo[0], lo[1], lo[2]);
-      split3_pair(f32x2{v[i][2], v[i][3]}, hi[0], hi[1], hi[2]);
-      const int at = lds_at(row, permute ? w_col(j) : j);
+    for (int half = 0; half < 2; ++half) {
+      u32x4 v[STEPS / 2];
 #pragma unroll
-      for (int pc = 0; pc < 3; ++pc)
-        if (pc < pieces) *reinterpret_cast<uint2*>(dst + pc * MAT_ELEMS + at) = make_uint2(lo[pc], hi[pc]);
+      for (int i = 0; i < STEPS / 2; ++i) v[i] = a.image[(half * (STEPS / 2) + i) * 256 + tid];
+#pragma unroll
+      for (int i = 0; i < STEPS / 2; ++i) dst[(half * (STEPS / 2) + i) * 256 + tid] = v[i];
     }
-  };
-  auto fetch64 = [&](const float* src, f32x4 (&v)[8]) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const f32x4*>(src + (i * 256 + tid) * 4);
-  };
-
-  {
-    f32x4 lo[8], hi[8];
-    fetch64(a.Pi, lo);
-    fetch64(a.Pi + 64 * 128, hi);
-    split_to_lds(lo, Pi_s, 0, 3, false);
-    split_to_lds(hi, Pi_s, 64, 3, false);
-    if (PROD) {
-      fetch64(a.SPiT, lo);
-      fetch64(a.SPiT + 64 * 128, hi);
-      split_to_lds(lo, W_s, 0, 2, true);
-      split_to_lds(hi, W_s, 64, 2, true);
-    }
+  } else {
+    q128_split_matrices(a.Pi, PROD ? a.SPiT : nullptr, lds_s, tid);
   }
   __syncthreads();
 
@@ -145,13 +171,9 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
     }
 
     // ---- stage 1: y^T = Pi x^T, three piece products ----------------------------------------------------
+    // (the first product of every accumulator takes a zero C operand: nothing is cleared)
     floatx16 acc[2][4];
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-      for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[nt][t][r] = 0.f;
+    const floatx16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     {
       // the A operands travel through a ring of RING registers, read RING MFMA pairs ahead of their use: left to
       // itself the compiler reuses two registers and every group of MFMAs waits for a full LDS round trip
@@ -167,7 +189,7 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
           acc[nt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i % RING], *reinterpret_cast<const bf16x8*>(&xop[nt][s]),
-                                                               acc[nt][t], 0, 0, 0);
+                                                               i < 4 ? zero16 : acc[nt][t], 0, 0, 0);
         if (i + RING < 96) ring[i % RING] = pi_piece(i + RING);
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -283,12 +305,6 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
 #pragma unroll
       for (int pass = 0; pass < 2; ++pass) {
         floatx16 u[2][2];
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-          for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) u[nt][mt][r] = 0.f;
         {
           auto w_piece = [&](int i) {  // read i of 32: step i / 4, pieces 1, 0, tile i % 2
             return *reinterpret_cast<const bf16x8*>(W_s + (1 - ((i >> 1) & 1)) * MAT_ELEMS +
@@ -305,14 +321,16 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
 #pragma unroll
               for (int nt = 0; nt < 2; ++nt)
                 u[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i % RING], *reinterpret_cast<const bf16x8*>(&rp[pb][nt][s]),
-                                                                    u[nt][mt], 0, 0, 0);
+                                                                    i < 2 ? zero16 : u[nt][mt], 0, 0, 0);
             if (i + RING < 32) ring[i % RING] = w_piece(i + RING);
             // the next block's vectors: all sixteen loads during the first pass
             if (pass == 0 && (i & 1)) xop[(i >> 1) & 1][s] = *reinterpret_cast<const u32x4*>(next_x[(i >> 1) & 1] + 16 * s);
             __builtin_amdgcn_sched_barrier(0);
           }
         }
-        // signs: register 4 k + r of tile mt is coordinate 64 pass + 32 mt + 8 k + 4 g + r
+        // signs: register 4 k + r of tile mt is coordinate 64 pass + 32 mt + 8 k + 4 g + r.  The bit of Def. 1 is
+        // "u >= 0", the complement of the fp32 sign bit: a sum of products accumulated from +0 is never -0 (exact
+        // cancellation rounds to +0), so the sign bits are shifted in, one instruction each, and inverted at the end.
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
@@ -322,9 +340,9 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
             for (int k = 0; k < 4; ++k) {
               nib[k] = 0u;
 #pragma unroll
-              for (int r = 3; r >= 0; --r) nib[k] = shift_in(nib[k], __builtin_amdgcn_ballot_w64(u[nt][mt][4 * k + r] >= 0.f));
+              for (int r = 3; r >= 0; --r) nib[k] = __builtin_amdgcn_alignbit(nib[k], __float_as_uint(u[nt][mt][4 * k + r]), 31);
             }
-            const uint32_t w = (nib[0] | (nib[1] << 8) | (nib[2] << 16) | (nib[3] << 24)) << (4 * g);
+            const uint32_t w = ((nib[0] | (nib[1] << 8) | (nib[2] << 16) | (nib[3] << 24)) ^ 0x0f0f0f0fu) << (4 * g);
             sw[nt][2 * pass + mt] = or_across_halves(w);
           }
       }
@@ -371,12 +389,13 @@ bool quant128_bf3_applicable(int bits, bool prod, const void* X, int64_t ldx, co
 // gs_hi > 0: two instances (cb_hi with bits + 1 bits for the first gs_hi coordinate groups); norm is required then
 hipError_t launch_quant128_bf3(int bits, bool prod, const void* X, int64_t ldx, int64_t n, const float* Pi,
                                const float* SPiT, uint32_t* idx, uint32_t* qjl, float* gamma, float* norm,
-                               const Codebook& cb, int gs_hi, const Codebook& cb_hi, hipStream_t s) {
+                               const Codebook& cb, int gs_hi, const Codebook& cb_hi, const void* image, hipStream_t s) {
   if (n <= 0) return hipSuccess;
   if (gs_hi < 0 || gs_hi > 3 || (gs_hi > 0 && (bits > 3 || cb_hi.bits != bits + 1 || norm == nullptr))) return hipErrorInvalidValue;
   if (!codebook_symmetric(cb, bits) || (gs_hi > 0 && !codebook_symmetric(cb_hi, bits + 1))) return hipErrorInvalidValue;
   Q128Args a;
   a.X = static_cast<const unsigned short*>(X); a.ldx = ldx; a.n = n; a.Pi = Pi; a.SPiT = SPiT; a.idx = idx; a.qjl = qjl;
+  a.image = static_cast<const u32x4*>(image);
   a.gamma = gamma; a.norm = norm; a.cb = cb; a.gs_hi = gs_hi; a.cb_hi = cb_hi;
   if (gs_hi > 0) {
     switch (bits * 2 + (prod ? 1 : 0)) {
@@ -403,6 +422,14 @@ hipError_t launch_quant128_bf3(int bits, bool prod, const void* X, int64_t ldx, 
     case 9: return launch_one<4, true, false>(a, s);
     default: return hipErrorInvalidValue;
   }
+}
+
+size_t quant128_bf3_image_bytes() { return (size_t)(PI_ELEMS + W_ELEMS) * 2; }
+
+// SPiT may be null (no sketch): the second part of the image is left alone then
+hipError_t launch_quant128_bf3_image(const float* Pi, const float* SPiT, void* image, hipStream_t s) {
+  hipLaunchKernelGGL(q128_image_kernel, dim3(1), dim3(256), 0, s, Pi, SPiT, static_cast<unsigned short*>(image));
+  return hipGetLastError();
 }
 
 }  // namespace tq

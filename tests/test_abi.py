@@ -42,8 +42,9 @@ def test_every_declared_symbol_is_exported_and_bound(lib):
 def test_params_struct_matches_header_layout():
     from paper_2504_19874_amd import _lib
     # int32 x2, 9 pointer-sized fields, then the split: int32 x2 and two pointers, then the flags word (padded)
-    assert C.sizeof(_lib.TqParams) == 8 + 9 * 8 + 8 + 2 * 8 + 8
-    assert _lib.TqParams.flags.offset == 104
+    # and the pointer to the parameter images
+    assert C.sizeof(_lib.TqParams) == 8 + 9 * 8 + 8 + 2 * 8 + 8 + 8
+    assert _lib.TqParams.flags.offset == 104 and _lib.TqParams.images.offset == 112
     assert _lib.TqParams.Pi.offset == 8 and _lib.TqParams.workspace_bytes.offset == 72
     assert _lib.TqParams.d_hi.offset == 80 and _lib.TqParams.bits_mse_hi.offset == 84
     assert _lib.TqParams.centroids_hi.offset == 88 and _lib.TqParams.bounds_hi.offset == 96

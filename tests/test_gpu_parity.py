@@ -222,6 +222,37 @@ def test_both_arithmetic_paths_of_large_bf16_batches():
     P.check_close(xt[1].cpu().numpy(), xt[0].cpu().numpy().astype(np.float64), nu[:, None] / np.sqrt(d), "dequantize, pieces vs fp32")
 
 
+@pytest.mark.parametrize("bits_mse,prod", [(2, True), (3, False), (1, True), (4, True)])
+def test_parameter_images_change_nothing(bits_mse, prod):
+    """tq_build_images only moves the splitting of the matrices out of the kernels' prologues: with and without
+    params.images the large-batch d = 128 kernels must write the same bits (and a kernel that ran with the image
+    must not have read a stale one: the image is rebuilt after the matrices are swapped)."""
+    d, n = 128, 20000 + 77
+    p, Pi, S, c32, t32 = setup(d, bits_mse, prod)
+    assert p.c.images != 0 and tq.tq_images_bytes(d) == p.images.numel() == (5 + 4) * 128 * 128 * 2
+    assert tq.tq_images_bytes(1536) == 0
+    x_or, x_dev, normalise = _quant_inputs(n, d, "bf16", 5)
+    out = []
+    try:
+        for with_images in (True, False):
+            if not with_images:
+                p.drop_images()
+            if prod:
+                codes = _run_prod(p, x_dev, n, normalise)
+            else:
+                idx = torch.zeros((n, p.idx_words), dtype=torch.int32, device=DEV)
+                norm = torch.zeros(n, dtype=torch.float32, device=DEV)
+                tq.tq_quantize_mse(p, x_dev, idx, norm)
+                codes = (idx, None, None, norm)
+            xt = torch.zeros((n, d), dtype=torch.float32, device=DEV)
+            tq.tq_dequantize(p, *codes, xt)
+            out.append([t.cpu().numpy() for t in (*codes, xt) if t is not None])
+    finally:
+        p.build_images()  # the parameter object is shared with other tests
+    for a, b in zip(*out):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
 @pytest.mark.parametrize("d,bits_mse,n,kind", [(256, 2, 3000, "f32"), (512, 4, 1500, "unit"), (96, 1, 2500, "bf16")])
 def test_both_arithmetic_paths_at_other_dimensions(d, bits_mse, n, kind):
     """Every d other than 128 runs the quantiser's contractions, many-query scoring and dequantisation on the bf16
