@@ -18,8 +18,10 @@
 //             unit: rows are stored without padding, the 16-byte chunks of a row rotated by the row number
 //             (conflict-free 16-byte reads along a column of chunks).
 //
-// Workgroup = 4 wavefronts (one per SIMD, the register file to itself); a wavefront takes 64 vectors per
-// block, so every LDS read of an A operand feeds at least two MFMAs.
+// Workgroup = 8 wavefronts (two per SIMD), a wavefront takes 32 vectors per block of 256.  Four wavefronts of
+// 64 vectors (VT = 2: the register file of a SIMD to one wavefront, every LDS read of an A operand feeding two
+// MFMAs) are 13-19 % slower: nothing runs on a SIMD while its one wavefront is in the decision stage's
+// dependent chains or waits for LDS.
 #include <type_traits>
 
 #include "tq_bf3.h"
@@ -108,8 +110,12 @@ __global__ __launch_bounds__(256) void q128_image_kernel(const float* Pi, const 
   q128_split_matrices(Pi, SPiT, image, threadIdx.x);
 }
 
-template <int BITS, bool PROD, bool MIXED>
-__global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
+// VT = vector tiles (of 32) per wavefront: 2 = four wavefronts of 64 vectors (one per SIMD, every LDS read of an A
+// operand feeds two MFMAs), 1 = eight wavefronts of 32 vectors (two per SIMD: while one is in its decision stage or
+// waits for LDS, the other issues MFMAs).
+template <int BITS, bool PROD, bool MIXED, int VT>
+__global__ __launch_bounds__(512 / VT) void quant128_bf3_kernel(const Q128Args a) {
+  constexpr int NT = 512 / VT;  // threads
   constexpr int NB = (BITS > 0 ? BITS : 1) + (MIXED ? 1 : 0);  // plane words per tile, at most
   constexpr int BH = BITS < 4 ? BITS + 1 : 4;                  // bits of instance hi
   extern __shared__ __attribute__((aligned(16))) unsigned short lds_s[];
@@ -122,30 +128,30 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
 
   if (a.image != nullptr) {
     // a straight copy, 16 bytes per thread and step: 24 steps for Pi, 16 for S Pi^T
-    constexpr int STEPS = (PI_ELEMS + (PROD ? W_ELEMS : 0)) * 2 / (256 * 16);
+    constexpr int STEPS = (PI_ELEMS + (PROD ? W_ELEMS : 0)) * 2 / (NT * 16);
     u32x4* const dst = reinterpret_cast<u32x4*>(lds_s);
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       u32x4 v[STEPS / 2];
 #pragma unroll
-      for (int i = 0; i < STEPS / 2; ++i) v[i] = a.image[(half * (STEPS / 2) + i) * 256 + tid];
+      for (int i = 0; i < STEPS / 2; ++i) v[i] = a.image[(half * (STEPS / 2) + i) * NT + tid];
 #pragma unroll
-      for (int i = 0; i < STEPS / 2; ++i) dst[(half * (STEPS / 2) + i) * 256 + tid] = v[i];
+      for (int i = 0; i < STEPS / 2; ++i) dst[(half * (STEPS / 2) + i) * NT + tid] = v[i];
     }
-  } else {
+  } else if (tid < 256) {
     q128_split_matrices(a.Pi, PROD ? a.SPiT : nullptr, lds_s, tid);
   }
   __syncthreads();
 
   const int64_t blocks = (a.n + 255) / 256;
   const bool normalise = !MIXED && a.norm != nullptr;
-  u32x4 xop[2][8];
+  u32x4 xop[VT][8];
   auto x_row = [&](int64_t blk, int nt) {  // this lane's 8 values of step 0
-    const int64_t v = blk * 256 + wave * 64 + 32 * nt + vi;
+    const int64_t v = blk * 256 + wave * (32 * VT) + 32 * nt + vi;
     return a.X + (v < a.n ? v : a.n - 1) * a.ldx + 8 * g;  // clamped: such vectors are not stored
   };
 #pragma unroll
-  for (int nt = 0; nt < 2; ++nt) {
+  for (int nt = 0; nt < VT; ++nt) {
     const unsigned short* src = x_row(blockIdx.x, nt);
 #pragma unroll
     for (int s = 0; s < 8; ++s) xop[nt][s] = *reinterpret_cast<const u32x4*>(src + 16 * s);
@@ -153,10 +159,12 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
 
   for (int64_t blk = blockIdx.x; blk < blocks; blk += gridDim.x) {
     // ---- norms: a lane and its partner in the other half-wave hold one vector between them --------------
-    float nu[2] = {1.f, 1.f}, inv[2] = {1.f, 1.f};
+    float nu[VT], inv[VT];
+#pragma unroll
+    for (int nt = 0; nt < VT; ++nt) nu[nt] = inv[nt] = 1.f;
     if (normalise) {
 #pragma unroll
-      for (int nt = 0; nt < 2; ++nt) {
+      for (int nt = 0; nt < VT; ++nt) {
         float s0 = 0.f, s1 = 0.f;
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
@@ -172,7 +180,7 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
 
     // ---- stage 1: y^T = Pi x^T, three piece products ----------------------------------------------------
     // (the first product of every accumulator takes a zero C operand: nothing is cleared)
-    floatx16 acc[2][4];
+    floatx16 acc[VT][4];
     const floatx16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     {
       // the A operands travel through a ring of RING registers, read RING MFMA pairs ahead of their use: left to
@@ -187,7 +195,7 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
       for (int i = 0; i < 96; ++i) {
         const int s = i / 12, t = i & 3;
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
+        for (int nt = 0; nt < VT; ++nt)
           acc[nt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i % RING], *reinterpret_cast<const bf16x8*>(&xop[nt][s]),
                                                                i < 4 ? zero16 : acc[nt][t], 0, 0, 0);
         if (i + RING < 96) ring[i % RING] = pi_piece(i + RING);
@@ -197,13 +205,13 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
 
     // ---- decision: indices, packing, residual in place; the residual's pieces ---------------------------
     // register 4 k + r of tile t holds coordinate j = 32 t + 8 k + 4 g + r of the lane's vector
-    uint32_t word[2][4][NB];
-    float g2[2] = {0.f, 0.f}, g2h[2] = {0.f, 0.f}, nuh[2] = {0.f, 0.f};  // MIXED: g2 / nu belong to instance lo
-    u32x4 rp[2][2][8];  // [piece][nt][step of stage 2]
+    uint32_t word[VT][4][NB];
+    float g2[VT] = {}, g2h[VT] = {}, nuh[VT] = {};  // MIXED: g2 / nu belong to instance lo
+    u32x4 rp[2][VT][8];  // [piece][nt][step of stage 2]
     const int gs = MIXED ? a.gs_hi : 0;
-    float inv_hi[2] = {0.f, 0.f};
+    float inv_hi[VT] = {};
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
+    for (int nt = 0; nt < VT; ++nt) {
       if (MIXED) {
         // the norms of the two instances from the rotated coordinates (the rotation is block diagonal)
         float s_hi = 0.f, s_lo = 0.f;
@@ -255,22 +263,28 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
       using I2 = std::integral_constant<int, 2>;
       using I3 = std::integral_constant<int, 3>;
       tile(I0{}, I0{}); tile(I0{}, I1{}); tile(I0{}, I2{}); tile(I0{}, I3{});
-      tile(I1{}, I0{}); tile(I1{}, I1{}); tile(I1{}, I2{}); tile(I1{}, I3{});
+      if constexpr (VT == 2) {
+        tile(I1{}, I0{}); tile(I1{}, I1{}); tile(I1{}, I2{}); tile(I1{}, I3{});
+      }
     }
 
-    const int64_t v_mine = blk * 256 + wave * 64 + 32 * g + vi;  // the vector this lane stores for: tile nt = g
+    // the vector this lane stores for.  VT = 2: tile nt = g (each half-wave writes one tile's rows); VT = 1: the one
+    // tile, by the lower half-wave (both halves hold the merged words)
+    const int64_t v_mine = VT == 2 ? blk * 256 + wave * 64 + 32 * g + vi : blk * 256 + wave * 32 + vi;
+    const bool storing = v_mine < a.n && (VT == 2 || g == 0);
+    constexpr int HI = VT - 1;  // the tile of the upper half-wave
     // the next block's vectors are fetched while this block is finished: spread over the first pass of stage 2
-    const unsigned short* const next_x[2] = {x_row(blk + gridDim.x, 0), x_row(blk + gridDim.x, 1)};
+    const unsigned short* const next_x[2] = {x_row(blk + gridDim.x, 0), x_row(blk + gridDim.x, HI)};
     if (!PROD) {
 #pragma unroll
-      for (int nt = 0; nt < 2; ++nt)
+      for (int nt = 0; nt < VT; ++nt)
 #pragma unroll
         for (int s = 0; s < 8; ++s) xop[nt][s] = *reinterpret_cast<const u32x4*>(next_x[nt] + 16 * s);
     }
 
     // ---- the codes of Alg. 1: lane (vi, g) writes the row of vector 32 g + vi ----------------------------
-    const uint32_t mine = 0u - (uint32_t)g;  // all ones in the half-wave that stores tile nt = 1
-    if (v_mine < a.n) {
+    const uint32_t mine = VT == 2 ? 0u - (uint32_t)g : 0u;  // all ones in the half-wave that stores tile nt = 1
+    if (storing) {
       // word[g][t][pl], selected with a mask (an indexed array would live in scratch memory)
       if (MIXED) {
         uint32_t* dst = a.idx + v_mine * (4 * BITS + gs);
@@ -279,10 +293,10 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
           const bool thi = t < gs;
 #pragma unroll
           for (int pl = 0; pl < BITS + 1; ++pl)
-            if (pl < BITS || thi) dst[pl] = word[0][t][pl] ^ ((word[0][t][pl] ^ word[1][t][pl]) & mine);
+            if (pl < BITS || thi) dst[pl] = word[0][t][pl] ^ ((word[0][t][pl] ^ word[HI][t][pl]) & mine);
           dst += thi ? BITS + 1 : BITS;
         }
-        *reinterpret_cast<float2*>(a.norm + 2 * v_mine) = make_float2(g ? nuh[1] : nuh[0], g ? nu[1] : nu[0]);
+        *reinterpret_cast<float2*>(a.norm + 2 * v_mine) = make_float2(g ? nuh[HI] : nuh[0], g ? nu[HI] : nu[0]);
       } else {
         if (BITS > 0) {
           uint32_t* dst = a.idx + v_mine * (4 * BITS);
@@ -290,21 +304,21 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
 #pragma unroll
           for (int t = 0; t < 4; ++t)
 #pragma unroll
-            for (int pl = 0; pl < BITS; ++pl) row[t * BITS + pl] = word[0][t][pl] ^ ((word[0][t][pl] ^ word[1][t][pl]) & mine);
+            for (int pl = 0; pl < BITS; ++pl) row[t * BITS + pl] = word[0][t][pl] ^ ((word[0][t][pl] ^ word[HI][t][pl]) & mine);
 #pragma unroll
           for (int q = 0; q < BITS; ++q)
             *reinterpret_cast<u32x4*>(dst + 4 * q) = u32x4{row[4 * q], row[4 * q + 1], row[4 * q + 2], row[4 * q + 3]};
         }
-        if (normalise) a.norm[v_mine] = g ? nu[1] : nu[0];
+        if (normalise) a.norm[v_mine] = g ? nu[HI] : nu[0];
       }
     }
 
     if (PROD) {
       // ---- stage 2: u^T = (S Pi^T) e^T, three piece products, one half of the output coordinates at a time ----
-      uint32_t sw[2][4];  // [nt][sign word]
+      uint32_t sw[VT][4];  // [nt][sign word]
 #pragma unroll
       for (int pass = 0; pass < 2; ++pass) {
-        floatx16 u[2][2];
+        floatx16 u[VT][2];
         {
           auto w_piece = [&](int i) {  // read i of 32: step i / 4, pieces 1, 0, tile i % 2
             return *reinterpret_cast<const bf16x8*>(W_s + (1 - ((i >> 1) & 1)) * MAT_ELEMS +
@@ -319,12 +333,13 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
 #pragma unroll
             for (int pb = 1 - pa; pb >= 0; --pb)
 #pragma unroll
-              for (int nt = 0; nt < 2; ++nt)
+              for (int nt = 0; nt < VT; ++nt)
                 u[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i % RING], *reinterpret_cast<const bf16x8*>(&rp[pb][nt][s]),
                                                                     i < 2 ? zero16 : u[nt][mt], 0, 0, 0);
             if (i + RING < 32) ring[i % RING] = w_piece(i + RING);
             // the next block's vectors: all sixteen loads during the first pass
-            if (pass == 0 && (i & 1)) xop[(i >> 1) & 1][s] = *reinterpret_cast<const u32x4*>(next_x[(i >> 1) & 1] + 16 * s);
+            if (pass == 0 && (i & 1) && (VT == 2 || !(i & 2)))
+              xop[(i >> 1) & HI][s] = *reinterpret_cast<const u32x4*>(next_x[(i >> 1) & 1] + 16 * s);
             __builtin_amdgcn_sched_barrier(0);
           }
         }
@@ -332,7 +347,7 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
         // "u >= 0", the complement of the fp32 sign bit: a sum of products accumulated from +0 is never -0 (exact
         // cancellation rounds to +0), so the sign bits are shifted in, one instruction each, and inverted at the end.
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
+        for (int nt = 0; nt < VT; ++nt)
 #pragma unroll
           for (int mt = 0; mt < 2; ++mt) {
             uint32_t nib[4];
@@ -347,33 +362,39 @@ __global__ __launch_bounds__(256) void quant128_bf3_kernel(const Q128Args a) {
           }
       }
       // (exchanges between the half-waves stay outside the guarded stores: every lane takes part)
-      g2[0] = add_across_halves(g2[0]);
-      g2[1] = add_across_halves(g2[1]);
-      if (MIXED) {
-        g2h[0] = add_across_halves(g2h[0]);
-        g2h[1] = add_across_halves(g2h[1]);
+#pragma unroll
+      for (int nt = 0; nt < VT; ++nt) {
+        g2[nt] = add_across_halves(g2[nt]);
+        if (MIXED) g2h[nt] = add_across_halves(g2h[nt]);
       }
-      if (v_mine < a.n) {
+      if (storing) {
         *reinterpret_cast<u32x4*>(a.qjl + v_mine * 4) =
-            g ? u32x4{sw[1][0], sw[1][1], sw[1][2], sw[1][3]} : u32x4{sw[0][0], sw[0][1], sw[0][2], sw[0][3]};
+            g ? u32x4{sw[HI][0], sw[HI][1], sw[HI][2], sw[HI][3]} : u32x4{sw[0][0], sw[0][1], sw[0][2], sw[0][3]};
         if (MIXED) {
-          *reinterpret_cast<float2*>(a.gamma + 2 * v_mine) = make_float2(sqrtf(g ? g2h[1] : g2h[0]), sqrtf(g ? g2[1] : g2[0]));
+          *reinterpret_cast<float2*>(a.gamma + 2 * v_mine) = make_float2(sqrtf(g ? g2h[HI] : g2h[0]), sqrtf(g ? g2[HI] : g2[0]));
         } else {
-          a.gamma[v_mine] = sqrtf(g ? g2[1] : g2[0]);
+          a.gamma[v_mine] = sqrtf(g ? g2[HI] : g2[0]);
         }
       }
     }
   }
 }
 
-template <int BITS, bool PROD, bool MIXED>
-hipError_t launch_one(const Q128Args& a, hipStream_t s) {
+template <int BITS, bool PROD, bool MIXED, int VT>
+hipError_t launch_vt(const Q128Args& a, hipStream_t s) {
   constexpr int lds = (PI_ELEMS + (PROD ? W_ELEMS : 0)) * 2;
   static LdsLimit lds_limit;  // per instantiation: the limit is raised once per device
-  if (const hipError_t e = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&quant128_bf3_kernel<BITS, PROD, MIXED>), lds); e != hipSuccess) return e;
+  if (const hipError_t e = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&quant128_bf3_kernel<BITS, PROD, MIXED, VT>), lds); e != hipSuccess) return e;
   const int64_t blocks = (a.n + 255) / 256, cus = device_cu_count();  // one workgroup per compute unit
-  hipLaunchKernelGGL((quant128_bf3_kernel<BITS, PROD, MIXED>), dim3((unsigned)(blocks < cus ? blocks : cus)), dim3(256), lds, s, a);
+  hipLaunchKernelGGL((quant128_bf3_kernel<BITS, PROD, MIXED, VT>), dim3((unsigned)(blocks < cus ? blocks : cus)), dim3(512 / VT), lds, s, a);
   return hipGetLastError();
+}
+
+// eight wavefronts of 32 vectors: measured against four of 64 (VT = 2) on the same box, 524288 vectors, 2 + 1 bits:
+// 109 against 125 us; 3 + 1 bits: 122 against 150; two instances: 105 against 124; 131072 vectors: 33 against 38
+template <int BITS, bool PROD, bool MIXED>
+hipError_t launch_one(const Q128Args& a, hipStream_t s) {
+  return launch_vt<BITS, PROD, MIXED, 1>(a, s);
 }
 
 }  // namespace
