@@ -133,7 +133,7 @@ def arithmetic(cfg):
         dq = "bf16 MFMA on two-piece splits of the fp32 factors (error < 3e-5 of a coordinate), fp32 accumulation" \
             if piece_products(cfg, "dequantize") else "fp32 MFMA"
     else:
-        q = ("bf16 MFMA on pieces: three (exact) pieces of Pi x the two leading pieces of x (rotation, y to 4e-6 |x|; a bf16 "
+        q = ("bf16 MFMA on pieces: three (exact) pieces of Pi x the two leading pieces of x (rotation, y to 8e-6 |x|; a bf16 "
              "x is one exact piece), two x two for the sketch (signs only); fp32 accumulation and bucket decision")
         dq = "bf16 MFMA on two-piece splits of the fp32 factors (the scoring kernel with the rows of Pi^T as queries), fp32 accumulation"
     few = cfg.q_per_group <= 32 and cfg.d <= 512

@@ -53,8 +53,8 @@
  *   quantise, bf16 batches above 8192 vectors at d = 128 and every d other
  *     than 128: the rotation from three pieces of Pi and the two leading
  *     pieces of an fp32 x (a bf16 x is one exact piece); what is dropped of x is
- *     below 2^-18 |x_k| per element, so a rotated coordinate moves by at most
- *     2^-18 |Pi_j| |x| = 3.8e-6 of the unit norm and the rotated vector by that in
+ *     below 2^-17 |x_k| per element, so a rotated coordinate moves by at most
+ *     2^-17 |Pi_j| |x| = 7.6e-6 of the unit norm and the rotated vector by that in
  *     L2 norm: an index can differ from the fp32 evaluation only inside the
  *     1e-5 band around a cell boundary that every path is allowed.  The sketch,
  *     of which only signs are kept, from two pieces of the residual and two of

@@ -9,8 +9,8 @@
 //   * D[vector][k]: output tile t holds the columns k = 4 l + t of lane l, so a lane owns 16 contiguous bytes
 //     of its vector's row and a half-wave stores one whole row per instruction.
 // Pieces: a centroid and an entry of Pi^T are taken as their two leading bf16 pieces and the three products
-// of combined weight >= 2^-9 are summed (what is left out is below 3 * 2^-18 per term: about 5e-6 of a
-// coordinate's typical size, against the 1e-4 the output has to meet).  The sign part is folded into the same
+// of combined weight >= 2^-9 are summed (what is left out is 2^-17.8 of a term in the root mean square, 2^-15 at
+// worst: about 5e-6 of a coordinate's typical size, against the 1e-4 the output has to meet).  The sign part is folded into the same
 // accumulator: its operand is +-(kappa gamma_i), the two leading pieces of kappa gamma_i with the sign bit of
 // z_ij, against two pieces of S^T, again three products.  A 1-bit table is +-c_1: the pieces of c_1 with a sign.
 // Workgroup = 8 wavefronts, two per SIMD; a wavefront takes 32 vectors per block, workgroups stride over the

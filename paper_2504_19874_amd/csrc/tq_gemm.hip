@@ -25,7 +25,7 @@
 // piece products of combined weight >= 2^(-8 (NP - 1)) are summed in the fp32 accumulator with
 // v_mfma_f32_32x32x16_bf16, whose D layout is the one above, so the epilogues do not change.  NP = 3
 // keeps W exact (three pieces) against the two leading pieces of an fp32 vector or the one of a bf16 vector
-// (five resp. three products: y to 4e-6 |x| at worst, see mfma_tile); NP = 2 (three products) is used where
+// (five resp. three products: y to 8e-6 |x| at worst, see mfma_tile); NP = 2 (three products) is used where
 // only signs are kept.
 #include "tq_bf3.h"
 
@@ -240,11 +240,11 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
       const unsigned short* const Wp = reinterpret_cast<const unsigned short*>(Ws);
       const unsigned short* const Xp = reinterpret_cast<const unsigned short*>(Ns);
       // Pieces of the streamed operand: a bf16 vector is one; an fp32 vector is taken as its two leading pieces,
-      // x = x1 + x2 + dx with |dx_k| <= 2^-18 |x_k|.  What that leaves out of y = W x is W dx: at most
-      // 2^-18 |W_j| |x| in any one coordinate (3.8e-6 for a unit vector against a row of a rotation, inside the
-      // 1e-5 within which a bucket decision may differ from the exact one), and, W being orthogonal there,
-      // 2^-18 |x| in norm over all coordinates together, so for no input more than a few in 10^5 decisions can
-      // sit that close to a cell boundary.  W itself keeps all NP pieces.
+      // x = x1 + x2 + dx with |dx_k| <= 2^-17 |x_k| (2^-18.6 in the root mean square).  What that leaves out of
+      // y = W x is W dx: at most 2^-17 |W_j| |x| in any one coordinate (7.6e-6 for a unit vector against a row of a
+      // rotation, inside the 1e-5 within which a bucket decision may differ from the exact one), and, W being
+      // orthogonal there, 2^-17 |x| in norm over all coordinates together, so for no input more than a few in 10^5
+      // decisions can sit that close to a cell boundary.  W itself keeps all NP pieces.
       constexpr int NPX = NKIND == N_BF16 ? 1 : 2;
 #pragma unroll
       for (int s = 0; s < 2; ++s) {  // 16 values of k per step: lane half h holds k = 16 s + 8 h + 0..7

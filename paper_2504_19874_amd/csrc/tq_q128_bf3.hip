@@ -12,7 +12,7 @@
 //             two leading pieces, are directly the B operand (the order in which they enumerate the
 //             contraction index is a fixed permutation inside every run of 16, which the LDS image of
 //             S Pi^T follows).  S Pi^T is held as its two leading pieces as well, and the three products of
-//             combined weight >= 2^-9 are taken: what is left out is below 3 * 2^-18 per term, about
+//             combined weight >= 2^-9 are taken: what is left out is 2^-17.8 of a term (root mean square), about
 //             5e-7 |S_j| |e| in u, against the 1e-5 |S_j| |e| inside which a sign may differ from the exact one.
 //   LDS       three pieces of Pi and two of S Pi^T, 128 x 128 bf16 each, are exactly the 160 KB of a compute
 //             unit: rows are stored without padding, the 16-byte chunks of a row rotated by the row number

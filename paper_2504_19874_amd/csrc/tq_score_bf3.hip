@@ -2,11 +2,12 @@
 // queries against a block of codes is a dense contraction whose code-side operand takes few values,
 //     score[m][i] = nu_i * ( sum_j qr[m][j] c[idx_ij]  +  kappa gamma_i sum_j qs[m][j] z_ij ).
 // It runs on the bf16 matrix cores (16 x the fp32 rate): every fp32 factor is taken as its two leading bf16
-// pieces, x ~ x1 + x2 (8 + 8 significant bits, what is left is below 2^-18 |x|), a product of two pieces is
+// pieces, x ~ x1 + x2 (8 + 8 significant bits and a sign: what is left is below 2^-17 |x|), a product of two pieces is
 // exact in fp32, and the MFMA accumulates in fp32.  The three piece products of combined weight >= 2^-9 are
 // kept,
 //     q c ~ q1 c1 + q1 c2 + q2 c1,
-// so a term is off by less than 3 * 2^-18 |q| |c|.  Over the d terms of a score these errors average out: the
+// so a term is off by 2^-17.8 |q| |c| in the root mean square (2^-15 if both factors sit at the bottom of their
+// binades and every dropped part has its largest size).  Over the d terms of a score these errors average out: the
 // scores are within about 2e-7 |q| nu of the exact ones; a single dequantised coordinate (the transposed mode,
 // one term per coordinate and query) within about 2e-5 of its typical size.  Sign operands need one piece:
 // z = +-1 is a bf16 value, and a 1-bit codebook is +-c_1 with c_1 applied after the sum; those products take
