@@ -221,17 +221,18 @@ typedef struct tq_params {
 tq_status tq_derive_params(int32_t d, const float* Pi, const float* S, float* PiT, float* ST,
                            float* SPiT, void* stream);
 
-/* Optional, once per parameter set: the matrices in the form the large-batch d = 128 kernels keep them in on-chip
- * memory (bf16 pieces of Pi, S Pi^T, Pi^T and S^T, rows and columns in the kernels' own order), so that a
- * kernel's prologue is a copy instead of 128 KB of fp32 loads and their splitting on every launch (Alg. 1 / Alg. 2
- * fix the matrices "at setup"; this is that setup carried one step further).  tq_images_bytes: size of the
- * buffer for dimension d, 0 where no kernel takes one (every d other than 128; tq_build_images then does
- * nothing).  tq_build_images reads p->Pi, p->PiT and, when p->S is set, p->ST and p->SPiT (device, as
- * tq_derive_params left them) and writes `images` (device, 16-byte aligned, owned by the caller) on `stream`; the
- * caller then stores the pointer in params.images.  A null params.images is always valid and gives identical
- * results.  The image must be rebuilt whenever one of the matrices changes: the kernels that take it do not look
- * at the fp32 matrices again.  Errors: TQ_ERR_INVALID_ARG (null pointers, S given without ST / SPiT),
- * TQ_ERR_UNSUPPORTED (misaligned), TQ_ERR_HIP. */
+/* Optional, once per parameter set: the matrices already split into the bf16 pieces the quantisation and
+ * dequantisation kernels multiply (see "Arithmetic" above), in the kernels' own order, so that no launch splits them
+ * again (Alg. 1 / Alg. 2 fix the matrices "at setup"; this is that setup carried one step further).  d = 128: Pi,
+ * S Pi^T, Pi^T and S^T as the large-batch kernels keep them in on-chip memory (their prologue becomes a copy);
+ * every other d: Pi and S Pi^T as the tiles the quantiser's workgroups stage (10 d^2 bytes).
+ * tq_images_bytes: size of the buffer for dimension d (0: none is taken at this d, tq_build_images then does
+ * nothing).  tq_build_images reads p->Pi and, when p->S is set, p->SPiT (at d = 128 also p->PiT and p->ST), device
+ * memory as tq_derive_params left it, and writes `images` (device, 16-byte aligned, owned by the caller) on
+ * `stream`; the caller then stores the pointer in params.images.  A null params.images is always valid and gives
+ * identical results.  The image must be rebuilt whenever one of the matrices changes: the kernels that take it do
+ * not look at the fp32 matrices again.  Errors: TQ_ERR_INVALID_ARG (null pointers, S given without its derived
+ * matrices), TQ_ERR_UNSUPPORTED (misaligned), TQ_ERR_HIP. */
 size_t tq_images_bytes(int32_t d);
 tq_status tq_build_images(const tq_params* p, void* images, void* stream);
 

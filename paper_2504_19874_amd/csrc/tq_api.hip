@@ -166,6 +166,7 @@ tq_status quantize_common(const tq_params* p, const void* x, int32_t dtype, int6
   a.kappa = kappa_of(d);
   a.cb = make_codebook(p);
   a.pieces = !fp32_mfma_only(p);
+  a.W1_image = a.pieces ? p->images : nullptr;
   const NKind nk = dtype == TQ_F32 ? N_F32 : N_BF16;
 
   if (!prod) {
@@ -213,6 +214,7 @@ tq_status quantize_common(const tq_params* p, const void* x, int32_t dtype, int6
     a2.rownorm_out = gamma + r0;
     a2.words_out = qjl + r0 * (d / 32);
     a2.pieces = a.pieces;
+    a2.W1_image = a.pieces && p->images != nullptr ? static_cast<const char*>(p->images) + gemm_image_bytes(d, d, 3) : nullptr;
     e = launch_gemm(N_F32, E_SIGN, 0, a2, 1, stream);
     if (e != hipSuccess) return TQ_ERR_HIP;
   }
@@ -235,13 +237,27 @@ const char* tq_status_string(tq_status s) {
 }
 
 size_t tq_images_bytes(int32_t d) {
-  return d == 128 ? quant128_bf3_image_bytes() + dequant128_bf3_image_bytes() : 0;
+  if (d == 128) return quant128_bf3_image_bytes() + dequant128_bf3_image_bytes();
+  if (d <= 0 || d % 32 != 0 || d > 16384) return 0;
+  return gemm_image_bytes(d, d, 3) + gemm_image_bytes(d, d, 2);  // Pi in three pieces, S Pi^T in two
 }
 
 tq_status tq_build_images(const tq_params* p, void* images, void* stream) {
   if (p == nullptr || p->d <= 0) return TQ_ERR_INVALID_ARG;
   if (tq_images_bytes(p->d) == 0) return TQ_OK;  // no kernel at this d takes one
-  if (images == nullptr || p->Pi == nullptr || p->PiT == nullptr) return TQ_ERR_INVALID_ARG;
+  if (images == nullptr || p->Pi == nullptr) return TQ_ERR_INVALID_ARG;
+  if (p->d != 128) {
+    // the generic quantiser: Pi, and S Pi^T when there is a sketch
+    if ((p->S == nullptr) != (p->SPiT == nullptr)) return TQ_ERR_INVALID_ARG;
+    if (!aligned16(images) || !aligned16(p->Pi) || (p->SPiT != nullptr && !aligned16(p->SPiT))) return TQ_ERR_UNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (launch_gemm_image(p->Pi, p->d, p->d, p->d, 3, images, s) != hipSuccess) return TQ_ERR_HIP;
+    if (p->SPiT != nullptr &&
+        launch_gemm_image(p->SPiT, p->d, p->d, p->d, 2, static_cast<char*>(images) + gemm_image_bytes(p->d, p->d, 3), s) != hipSuccess)
+      return TQ_ERR_HIP;
+    return TQ_OK;
+  }
+  if (p->PiT == nullptr) return TQ_ERR_INVALID_ARG;
   if ((p->S == nullptr) != (p->ST == nullptr) || (p->S == nullptr) != (p->SPiT == nullptr)) return TQ_ERR_INVALID_ARG;
   if (!aligned16(images) || !aligned16(p->Pi) || !aligned16(p->PiT) || (p->S != nullptr && (!aligned16(p->ST) || !aligned16(p->SPiT))))
     return TQ_ERR_UNSUPPORTED;

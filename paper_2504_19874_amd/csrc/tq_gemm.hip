@@ -45,7 +45,8 @@ constexpr int XCDS = 8;
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-template <int NKIND, int EKIND, int BITS, int NP>
+// IMG (pieces only): W1 comes from its image (GemmArgs::W1_image) instead of being split in every workgroup
+template <int NKIND, int EKIND, int BITS, int NP, bool IMG>
 __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const int tiles_m,
                                                    const int tiles_n, const int per_xcd) {
   // two staging buffers of [TM + TN][LDS_LD] floats: one is read by the MFMAs while the next
@@ -116,6 +117,22 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
 
   f32x4 wreg[4];  // native vectors: these stay in registers
   uint32_t nreg[16];
+  // W from its image (pieces only): a row's k-tile is NP * 64 contiguous bytes, [piece][32 k]; chunk c = i * 256 + tid
+  // of the tile's 128 * NP * 4 chunks of 16 bytes is (row c / (4 NP), piece, eight k)
+  constexpr int NCH = IMG ? 2 * NP : 1;
+  constexpr bool w_image = IMG;
+  const u32x4* const Wimg = reinterpret_cast<const u32x4*>(a.W1_image);
+  uint32_t ioff[NCH], loff[NCH];
+  u32x4 wimg[NCH];
+  if constexpr (IMG) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = i * 256 + tid, row = c / (4 * NP), within = c % (4 * NP);
+      const uint32_t rm = (uint32_t)min(row, rows_m - 1);
+      ioff[i] = ((uint32_t)(m0 + rm) * (uint32_t)kt_per_seg) * (4 * NP) + within;  // in chunks; + kt * 4 NP per k-tile
+      loff[i] = row * P_LD + (within >> 2) * 32 + (within & 3) * 8;               // in bf16 elements
+    }
+  }
   float ss[4] = {0.f, 0.f, 0.f, 0.f};
 
   // global -> registers for k-tile kt; SEG (0: rotated codebook part, 1: sign sketch part)
@@ -124,8 +141,13 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
     constexpr int SEG = decltype(seg_c)::value;
     const int g = kt - SEG * kt_per_seg;
     const float* W = (SEG ? W2 : W1) + g * BK;
+    if constexpr (IMG) {
 #pragma unroll
-    for (int p = 0; p < 4; ++p) wreg[p] = *reinterpret_cast<const f32x4*>(W + woff[p]);
+      for (int i = 0; i < NCH; ++i) wimg[i] = Wimg[ioff[i] + (uint32_t)g * (4 * NP)];
+    } else {
+#pragma unroll
+      for (int p = 0; p < 4; ++p) wreg[p] = *reinterpret_cast<const f32x4*>(W + woff[p]);
+    }
     if (NKIND == N_F32) {
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
@@ -158,14 +180,20 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
       // both tiles as bf16 pieces, [row][piece][k]
       unsigned short* const Wp = reinterpret_cast<unsigned short*>(Ws);
       unsigned short* const Xp = reinterpret_cast<unsigned short*>(Ns);
+      if constexpr (IMG) {
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) *reinterpret_cast<u32x4*>(Wp + loff[i]) = wimg[i];
+      }
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
         uint32_t lo[3], hi[3];
-        split3_pair(f32x2{wreg[p][0], wreg[p][1]}, lo[0], lo[1], lo[2]);
-        split3_pair(f32x2{wreg[p][2], wreg[p][3]}, hi[0], hi[1], hi[2]);
+        if constexpr (!IMG) {
+          split3_pair(f32x2{wreg[p][0], wreg[p][1]}, lo[0], lo[1], lo[2]);
+          split3_pair(f32x2{wreg[p][2], wreg[p][3]}, hi[0], hi[1], hi[2]);
 #pragma unroll
-        for (int pc = 0; pc < NP; ++pc)
-          *reinterpret_cast<uint2*>(Wp + (srow + 32 * p) * P_LD + pc * 32 + scol) = make_uint2(lo[pc], hi[pc]);
+          for (int pc = 0; pc < NP; ++pc)
+            *reinterpret_cast<uint2*>(Wp + (srow + 32 * p) * P_LD + pc * 32 + scol) = make_uint2(lo[pc], hi[pc]);
+        }
         if (NKIND == N_BF16) {
           const float x0 = bf16_lo(nreg[4 * p]), x1 = bf16_hi(nreg[4 * p]), x2 = bf16_lo(nreg[4 * p + 1]), x3 = bf16_hi(nreg[4 * p + 1]);
           ss[p] += x0 * x0 + x1 * x1 + x2 * x2 + x3 * x3;
@@ -507,7 +535,24 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmArgs a, const in
   }
 }
 
-template <int NKIND, int EKIND, int BITS, int NP = 0>
+// W (M rows of d fp32 values, row stride ldw) as its np leading bf16 pieces in the order the piece kernels copy
+// it: [row][k / 32][piece][32 k].  Thread = four consecutive k of one row.
+template <int NP>
+__global__ __launch_bounds__(256) void gemm_image_kernel(const float* W, int64_t ldw, int M, int d, unsigned short* out) {
+  const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (e >= (int64_t)M * d) return;
+  const int64_t row = e / d;
+  const int k = (int)(e % d);
+  const f32x4 v = *reinterpret_cast<const f32x4*>(W + row * ldw + k);
+  uint32_t lo[3], hi[3];
+  split3_pair(f32x2{v[0], v[1]}, lo[0], lo[1], lo[2]);
+  split3_pair(f32x2{v[2], v[3]}, hi[0], hi[1], hi[2]);
+  unsigned short* const dst = out + (row * (d / BK) + k / BK) * (NP * BK) + (k % BK);
+#pragma unroll
+  for (int pc = 0; pc < NP; ++pc) *reinterpret_cast<uint2*>(dst + pc * BK) = make_uint2(lo[pc], hi[pc]);
+}
+
+template <int NKIND, int EKIND, int BITS, int NP = 0, bool IMG = false>
 static hipError_t launch_one(const GemmArgs& a, int n_groups, hipStream_t stream) {
   const int tiles_m = (a.M + TM - 1) / TM;
   const int64_t tiles_n64 = (a.n + TN - 1) / TN;
@@ -519,20 +564,20 @@ static hipError_t launch_one(const GemmArgs& a, int n_groups, hipStream_t stream
   dim3 grid(per_xcd * XCDS, n_groups, 1);
   constexpr int lds_bytes = NP > 0 ? (TM + TN) * P_LD * 2 : 2 * (TM + TN) * LDS_LD * (int)sizeof(float);  // above the 64 KB default limit
   static LdsLimit lds_limit;  // per instantiation: the limit is raised once per device
-  if (const hipError_t e = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&gemm_kernel<NKIND, EKIND, BITS, NP>), lds_bytes); e != hipSuccess) return e;
-  hipLaunchKernelGGL((gemm_kernel<NKIND, EKIND, BITS, NP>), grid, dim3(256), lds_bytes, stream, a, tiles_m,
+  if (const hipError_t e = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&gemm_kernel<NKIND, EKIND, BITS, NP, IMG>), lds_bytes); e != hipSuccess) return e;
+  hipLaunchKernelGGL((gemm_kernel<NKIND, EKIND, BITS, NP, IMG>), grid, dim3(256), lds_bytes, stream, a, tiles_m,
                      tiles_n, per_xcd);
   return hipGetLastError();
 }
 
-template <int NKIND, int EKIND, int NP = 0>
+template <int NKIND, int EKIND, int NP = 0, bool IMG = false>
 static hipError_t launch_bits(int bits, const GemmArgs& a, int g, hipStream_t s) {
   switch (bits) {
-    case 0: return launch_one<NKIND, EKIND, 0, NP>(a, g, s);
-    case 1: return launch_one<NKIND, EKIND, 1, NP>(a, g, s);
-    case 2: return launch_one<NKIND, EKIND, 2, NP>(a, g, s);
-    case 3: return launch_one<NKIND, EKIND, 3, NP>(a, g, s);
-    case 4: return launch_one<NKIND, EKIND, 4, NP>(a, g, s);
+    case 0: return launch_one<NKIND, EKIND, 0, NP, IMG>(a, g, s);
+    case 1: return launch_one<NKIND, EKIND, 1, NP, IMG>(a, g, s);
+    case 2: return launch_one<NKIND, EKIND, 2, NP, IMG>(a, g, s);
+    case 3: return launch_one<NKIND, EKIND, 3, NP, IMG>(a, g, s);
+    case 4: return launch_one<NKIND, EKIND, 4, NP, IMG>(a, g, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -543,6 +588,10 @@ hipError_t launch_gemm(NKind nk, EKind ek, int bits, const GemmArgs& a, int n_gr
   // the quantiser's two contractions on the bf16 matrix cores when the caller asks for pieces: the rotation with
   // three pieces (fp32 accuracy), the sketch (signs only) with two
   const bool pieces = a.pieces != 0;
+  const bool img = pieces && a.W1_image != nullptr && n_groups == 1 && (reinterpret_cast<uintptr_t>(a.W1_image) & 15u) == 0;
+  if (img && nk == N_F32 && ek == E_QUANT) return launch_bits<N_F32, E_QUANT, 3, true>(bits, a, n_groups, stream);
+  if (img && nk == N_BF16 && ek == E_QUANT) return launch_bits<N_BF16, E_QUANT, 3, true>(bits, a, n_groups, stream);
+  if (img && nk == N_F32 && ek == E_SIGN) return launch_one<N_F32, E_SIGN, 0, 2, true>(a, n_groups, stream);
   if (pieces && nk == N_F32 && ek == E_QUANT) return launch_bits<N_F32, E_QUANT, 3>(bits, a, n_groups, stream);
   if (pieces && nk == N_BF16 && ek == E_QUANT) return launch_bits<N_BF16, E_QUANT, 3>(bits, a, n_groups, stream);
   if (pieces && nk == N_F32 && ek == E_SIGN) return launch_one<N_F32, E_SIGN, 0, 2>(a, n_groups, stream);
@@ -553,6 +602,17 @@ hipError_t launch_gemm(NKind nk, EKind ek, int bits, const GemmArgs& a, int n_gr
   if (nk == N_CODE && ek == E_STORE_T) return launch_bits<N_CODE, E_STORE_T>(bits, a, n_groups, stream);
   if (nk == N_CODE && ek == E_STORE_N) return launch_bits<N_CODE, E_STORE_N>(bits, a, n_groups, stream);
   return hipErrorInvalidValue;
+}
+
+size_t gemm_image_bytes(int M, int d, int np) { return (size_t)M * d * np * 2; }
+
+hipError_t launch_gemm_image(const float* W, int64_t ldw, int M, int d, int np, void* image, hipStream_t stream) {
+  if (M <= 0 || d <= 0 || d % BK != 0 || ldw % 4 != 0 || (np != 2 && np != 3)) return hipErrorInvalidValue;
+  const int64_t threads = (int64_t)M * d / 4;
+  const dim3 grid((unsigned)((threads + 255) / 256));
+  if (np == 3) hipLaunchKernelGGL(gemm_image_kernel<3>, grid, dim3(256), 0, stream, W, ldw, M, d, static_cast<unsigned short*>(image));
+  else hipLaunchKernelGGL(gemm_image_kernel<2>, grid, dim3(256), 0, stream, W, ldw, M, d, static_cast<unsigned short*>(image));
+  return hipGetLastError();
 }
 
 }  // namespace tq

@@ -80,8 +80,14 @@ struct GemmArgs {
   float* resid_out;  // E_QUANT: y - c[idx], n rows of d floats, nullable
   float kappa;       // sqrt(pi/2)/d
   int pieces;        // E_QUANT / E_SIGN: multiply bf16 pieces of the fp32 factors instead of the fp32 values
+  // pieces, nullable: W1 already split, [row][k / 32][piece][32 k] bf16 with 3 (E_QUANT) or 2 (E_SIGN) pieces, as
+  // launch_gemm_image writes it; the kernel then copies its W tiles instead of splitting them in every workgroup
+  const void* W1_image;
   Codebook cb;
 };
+
+size_t gemm_image_bytes(int M, int d, int np);
+hipError_t launch_gemm_image(const float* W, int64_t ldw, int M, int d, int np, void* image, hipStream_t stream);
 
 hipError_t launch_gemm(NKind nk, EKind ek, int bits, const GemmArgs& a, int n_groups,
                        hipStream_t stream);

@@ -222,16 +222,18 @@ def test_both_arithmetic_paths_of_large_bf16_batches():
     P.check_close(xt[1].cpu().numpy(), xt[0].cpu().numpy().astype(np.float64), nu[:, None] / np.sqrt(d), "dequantize, pieces vs fp32")
 
 
-@pytest.mark.parametrize("bits_mse,prod", [(2, True), (3, False), (1, True), (4, True)])
-def test_parameter_images_change_nothing(bits_mse, prod):
-    """tq_build_images only moves the splitting of the matrices out of the kernels' prologues: with and without
-    params.images the large-batch d = 128 kernels must write the same bits (and a kernel that ran with the image
-    must not have read a stale one: the image is rebuilt after the matrices are swapped)."""
-    d, n = 128, 20000 + 77
+@pytest.mark.parametrize("d,bits_mse,prod,kind,n", [(128, 2, True, "bf16", 20077), (128, 3, False, "bf16", 20077),
+                                                    (128, 1, True, "bf16", 20077), (128, 4, True, "bf16", 20077),
+                                                    (256, 2, True, "f32", 3000), (1536, 4, False, "unit", 700),
+                                                    (96, 1, True, "bf16", 2500), (512, 3, True, "bf16", 1111)])
+def test_parameter_images_change_nothing(d, bits_mse, prod, kind, n):
+    """tq_build_images only moves the splitting of the matrices out of the kernels: with and without params.images
+    the large-batch d = 128 kernels and the generic quantiser must write the same bits."""
     p, Pi, S, c32, t32 = setup(d, bits_mse, prod)
-    assert p.c.images != 0 and tq.tq_images_bytes(d) == p.images.numel() == (5 + 4) * 128 * 128 * 2
-    assert tq.tq_images_bytes(1536) == 0
-    x_or, x_dev, normalise = _quant_inputs(n, d, "bf16", 5)
+    want = (5 + 4) * 128 * 128 * 2 if d == 128 else 10 * d * d
+    assert p.c.images != 0 and tq.tq_images_bytes(d) == p.images.numel() == want
+    assert tq.tq_images_bytes(100) == 0
+    x_or, x_dev, normalise = _quant_inputs(n, d, kind, 5)
     out = []
     try:
         for with_images in (True, False):
@@ -241,7 +243,8 @@ def test_parameter_images_change_nothing(bits_mse, prod):
                 codes = _run_prod(p, x_dev, n, normalise)
             else:
                 idx = torch.zeros((n, p.idx_words), dtype=torch.int32, device=DEV)
-                norm = torch.zeros(n, dtype=torch.float32, device=DEV)
+                norm = torch.zeros(n, dtype=torch.float32, device=DEV) if normalise else None
+                p.reserve(n, 0, 0)
                 tq.tq_quantize_mse(p, x_dev, idx, norm)
                 codes = (idx, None, None, norm)
             xt = torch.zeros((n, d), dtype=torch.float32, device=DEV)
