@@ -33,7 +33,7 @@ namespace tq {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int TILES_128 = 16;  // tiles per wavefront
+constexpr int TILES_128 = 16;  // tiles per wavefront (the default; 8 or 4 where that would leave compute units idle)
 // tiles staged in LDS at a time: what fits beside the table within 160 KB
 __host__ __device__ constexpr int round_tiles(int bits) { return bits <= 3 ? 8 : 4; }
 // bytes of one wavefront's staging region: idx, qjl, gamma, norm of 16 * round_tiles rows
@@ -42,16 +42,16 @@ __host__ __device__ constexpr int stage_bytes(int bits) { return 16 * round_tile
 __host__ __device__ constexpr int score128_lds(int bits) { return 8 * stage_bytes(bits) + I8_PREP_BYTES; }
 
 // The whole kernel as a function of where a finished score goes: sink(t, score, key_live) is
-// called once per tile t (16 tiles of 16 keys per wavefront) by every lane with the score of
-// (query q0 + lane / 16, key wave_key0 + 16 t + lane % 16), wave_key0 = (8 blockIdx.x + wave) * 256.
+// called once per tile t (TILES tiles of 16 keys per wavefront) by every lane with the score of
+// (query q0 + lane / 16, key wave_key0 + 16 t + lane % 16), wave_key0 = (8 blockIdx.x + wave) * 16 TILES.
 // expand_s: the 64 KB expansion table [256][32] (filled here); dyn_s: score128_lds(BITS) bytes,
 // 8 staging regions, then the query preparation.  All of LDS may be reused after the workgroup's
 // next barrier.
-template <int BITS, bool PROD, class Sink>
+template <int BITS, bool PROD, int TILES = TILES_128, class Sink>
 __device__ __forceinline__ void score128_body(const ScoreI8Args& a, uint2* expand_s, unsigned char* dyn_s, Sink& sink) {
-  constexpr int RT = round_tiles(BITS);
+  constexpr int RT = round_tiles(BITS) < TILES ? round_tiles(BITS) : TILES;
   constexpr int ROWS = 16 * RT;               // rows staged per round
-  constexpr int ROUNDS = TILES_128 / RT;
+  constexpr int ROUNDS = TILES / RT;
   constexpr int NM = (1 << BITS) - 1;
   constexpr int NW = BITS > 0 ? BITS : 1;
   constexpr int NI = ROWS * 16 * BITS / 1024;  // 1 KB loads per round: plane words
@@ -82,8 +82,8 @@ __device__ __forceinline__ void score128_body(const ScoreI8Args& a, uint2* expan
   // Pieces past the end of the arrays are clamped onto the last one (never used: the
   // scores of keys past the end are not stored).
   const int64_t gbase = (int64_t)group * a.group_stride;
-  const int64_t wave_key0 = ((int64_t)blockIdx.x * 8 + wave) * (16 * TILES_128);
-  const bool full = wave_key0 + 16 * TILES_128 <= a.n;  // uniform: no key of this wavefront is past the end
+  const int64_t wave_key0 = ((int64_t)blockIdx.x * 8 + wave) * (16 * TILES);
+  const bool full = wave_key0 + 16 * TILES <= a.n;  // uniform: no key of this wavefront is past the end
   const int64_t wrow0 = gbase + wave_key0;
   u32x4 ci[ROUNDS][NI > 0 ? NI : 1], cq[ROUNDS][NQ > 0 ? NQ : 1];
   float cg[ROUNDS][NR], cn[ROUNDS][NR];
@@ -255,18 +255,18 @@ __device__ __forceinline__ void score128_body(const ScoreI8Args& a, uint2* expan
     stage_for(1);
     fetch(1);
     // tiles that have at least one key (uniform over the wavefront)
-    const int live_tiles = FULL ? TILES_128 : (int)((a.n - wave_key0 + 15) >> 4);
+    const int live_tiles = FULL ? TILES : (int)((a.n - wave_key0 + 15) >> 4);
 #pragma unroll
-    for (int t = 0; t < TILES_128; ++t) {
+    for (int t = 0; t < TILES; ++t) {
       if (FULL || t < live_tiles) {
-        if (t + 2 < TILES_128) {
+        if (t + 2 < TILES) {
           stage_for(t + 2);
           fetch(t + 2);
         }
 #pragma unroll
         for (int j = 0; j < NTA; ++j) acc[t & 1][j] = v4i{0, 0, 0, 0};
         if (PIPE) {
-          if (t + 1 < TILES_128) {
+          if (t + 1 < TILES) {
             lookups(t + 1, 0, bop[(t + 1) & 1][0]);
             lookups(t + 1, 1, bop[(t + 1) & 1][1]);
           }
@@ -281,7 +281,7 @@ __device__ __forceinline__ void score128_body(const ScoreI8Args& a, uint2* expan
       }
       if (t > 0 && (FULL || t - 1 < live_tiles)) finish(t - 1);
     }
-    if (FULL || TILES_128 - 1 < live_tiles) finish(TILES_128 - 1);
+    if (FULL || TILES - 1 < live_tiles) finish(TILES - 1);
   };
   if (full) run_tiles(std::true_type{});
   else run_tiles(std::false_type{});
