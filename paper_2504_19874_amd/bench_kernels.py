@@ -303,6 +303,10 @@ def main():
         dst = [torch.empty_like(y) for y in ys]
         report("plain_copy(torch)", cfg, timed(lambda r: dst[r % ysets].copy_(ys[r % ysets]), reps),
                0.0, rows * 8 * d)
+        # write-only and read-only streams of the same footprint: what stage_unpack (almost all stores) and
+        # stage_pack (almost all loads) can be held against
+        report("plain_fill(torch)", cfg, timed(lambda r: dst[r % ysets].fill_(1.0), reps), 0.0, rows * 4 * d)
+        report("plain_sum(torch)", cfg, timed(lambda r: ys[r % ysets].sum(), reps), 0.0, rows * 4 * d)
 
 
 if __name__ == "__main__":
