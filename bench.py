@@ -261,14 +261,14 @@ def time_step(calls, steps, warmup):
     """W untimed steps, then exactly `steps` timed ones between device synchronisations.  Per-call times come from
     events on torch's current stream (the stream every launch uses), recorded inside the timed region around the
     calls of every `stride`-th step: an event between two launches keeps the second from being set up behind the
-    first (about 4 us each, 15 us on the 80 us step of the d = 128 workloads), so only a sample of about 25
-    steps carries them."""
+    first (about 4 us each, 15 us on the 60 us step of the d = 128 workloads), so only a sample of the steps
+    carries them."""
     import torch
     for _ in range(warmup):
         for _, fn in calls:
             fn()
     torch.cuda.synchronize()
-    stride = max(1, steps // 25)
+    stride = max(steps // 25, 8 if steps >= 16 else 1)  # at most one step in eight, about 25 in a long run
     sampled = [s for s in range(steps) if s % stride == 0]
     ev = {s: [torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)] for s in sampled}
     torch.cuda.synchronize()

@@ -92,6 +92,14 @@ def test_entry_points_validate_before_launching(lib):
     assert lib.tq_stage_sign_pack(100, None, 1, None, None) == 2
     assert lib.tq_workspace_bytes(C.byref(p), 1000, 10, 0) >= 1000 * 128 * 4 + 2 * 10 * 128 * 4
     assert lib.tq_derive_params(128, None, None, None, None, None, None) == 1
+    # parameter images: sizes, and nothing is launched for missing matrices or dimensions that take none
+    assert lib.tq_images_bytes(128) == (5 + 4) * 128 * 128 * 2 and lib.tq_images_bytes(1536) == 10 * 1536 * 1536
+    assert lib.tq_images_bytes(100) == 0 and lib.tq_images_bytes(0) == 0
+    assert lib.tq_build_images(None, None, None) == 1
+    assert lib.tq_build_images(C.byref(p), None, None) == 1          # d = 128, no buffer and no matrices
+    q = _lib.TqParams()
+    q.d = 100
+    assert lib.tq_build_images(C.byref(q), None, None) == 0          # no image at this dimension: a no-op
     # two instances over a channel split: what is malformed, and what the kernels do not cover
     c_hi = np.zeros(8, dtype=np.float32)
     t_hi = np.zeros(7, dtype=np.float32)
