@@ -48,6 +48,37 @@ def test_entropy_of_the_stored_indices():
     assert abs(got["entropy_bits"] - 3.8) < 0.05 and abs(got["saving"] - 0.05) < 0.01
 
 
+@pytest.mark.parametrize("d,bits", [(1536, 4), (128, 3)])
+def test_prefix_code_on_what_the_gpu_stores(d, bits):
+    """Sec. 3.1, entropy-coding paragraph, end to end: indices quantised on the GPU, coded with the library's prefix
+    code for the codebook's bucket probabilities, decode to the same words; the stream has the length the oracle's
+    code lengths predict for these indices and, at b = 4, saves the 5 % the paper quotes."""
+    from paper_2504_19874_amd import entropy as E
+    n = 3000
+    c, t, _ = tq.tq_build_codebook(d, bits)
+    p = tq.make_params(d, bits, W.gaussian_matrix(d, 31))
+    x = torch.from_numpy(W.unit_gaussian_rows(n, d, 32)).cuda()
+    idx = torch.zeros((n, p.idx_words), dtype=torch.int32, device="cuda")
+    p.reserve(n, 0, 0)
+    tq.tq_quantize_mse(p, x, idx, None)
+    words = idx.cpu().numpy().view(np.uint32)
+    masses = E.bucket_masses(d, bits, c)
+    code = E.PrefixCode(masses)
+    stream, offs = code.encode(words, d)
+    assert np.array_equal(code.decode(stream, d, n), words)
+    assert np.array_equal(code.decode(stream, d, 5, first_bit=int(offs[n - 5])), words[n - 5:])  # rows decode on their own
+    # (the two middle buckets of a symmetric law tie: the lengths depend on which of them an implementation's
+    # masses make larger by 1e-9, so the oracle's construction is run on the same masses)
+    assert np.max(np.abs(masses - o.bucket_masses(o.lloyd_max_codebook(d, bits)[0], d))) < 1e-8
+    L = o.huffman_lengths(masses)
+    buckets = o.unpack_planes(words, bits, d)
+    assert int(offs[n]) == int(L[buckets].sum())
+    per_coord = int(offs[n]) / (n * d)
+    assert per_coord < bits
+    if bits == 4:
+        assert abs((1 - per_coord / bits) - 0.05) < 0.01
+
+
 def test_recall_harness_agrees_with_the_oracle():
     d, n, nq, bits = 128, 3000, 60, 3
     got = R.recall_at_k(tq, torch, W, d, n, nq, bits, "prod", "gaussian")
