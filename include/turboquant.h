@@ -42,8 +42,9 @@
  *    gamma[2i], gamma[2i+1] = residual norms of the two instances
  * and the sketch scale of Def. 1 is sqrt(pi/2)/d_hi resp. sqrt(pi/2)/(d-d_hi).
  * Covered for d = 128 with d_hi in {32, 64, 96}: tq_quantize_*, tq_dequantize,
- * tq_score with at most 32 queries per group, and tq_attend (keys: any width;
- * values: MSE codes with 1 + 2 or 2 + 3 index bits).
+ * tq_score (up to 4096 queries per group, through the kernel written for a few
+ * queries per code), and tq_attend (keys: any width; values: MSE codes with
+ * 1 + 2 or 2 + 3 index bits).
  *
  * Arithmetic.  Every contraction has fp32 operands and an fp32 (or int32)
  * accumulator; the bucket decision is an fp32 comparison.  Where it is faster

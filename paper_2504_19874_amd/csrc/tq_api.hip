@@ -477,9 +477,10 @@ tq_status score_impl(const tq_params* p, Workspace ws, const float* q, int64_t l
   if (topk > 0 && topk_idx == nullptr) return TQ_ERR_INVALID_ARG;
   if (ldq % 4 != 0 || !aligned16(q) || !aligned16(p->Pi) || (prod && !aligned16(p->S))) return TQ_ERR_UNSUPPORTED;
   if (p->d_hi != 0) {
-    // two instances over a split of the coordinates: few queries per code at d = 128 only
+    // two instances over a split of the coordinates: d = 128, the kernel written for few queries per code (every
+    // block of four queries streams the group's codes once more, so many queries are served, not served fast)
     if (norm == nullptr) return TQ_ERR_INVALID_ARG;
-    if (q_per_group > 32 || !score_i8_split_applicable(p->bits_mse, make_codebook(p), make_codebook_hi(p)))
+    if (q_per_group > 4096 || !score_i8_split_applicable(p->bits_mse, make_codebook(p), make_codebook_hi(p)))
       return TQ_ERR_UNSUPPORTED;
   }
   hipStream_t s = static_cast<hipStream_t>(stream);

@@ -176,6 +176,8 @@ def test_dequantize_split(d_hi, bits_lo, prod, n):
 @pytest.mark.parametrize("d_hi,bits_lo,prod,n_groups,qpg,npg,topk", [
     (32, 1, True, 8, 4, 1000, 0), (64, 1, True, 2, 5, 2100, 0), (32, 2, True, 1, 4, 130, 5), (96, 2, False, 2, 3, 300, 0),
     (32, 0, True, 1, 1, 77, 0), (64, 3, False, 1, 9, 1500, 4),
+    # more than 32 queries per group (served by the same kernel, a block of four queries at a time)
+    (64, 2, True, 2, 70, 900, 3),
 ])
 @pytest.mark.parametrize("own_prep", [True, False])
 def test_score_split(d_hi, bits_lo, prod, n_groups, qpg, npg, topk, own_prep):
