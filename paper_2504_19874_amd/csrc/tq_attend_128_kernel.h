@@ -168,14 +168,16 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
   for (int t = 0; t < 16; ++t) lg[t] = -INFINITY;
   if (FUSED) {
     auto sink = [&](int t, float score, bool key_live) { lg[t] = key_live ? scale2 * score : -INFINITY; };
-    score128_body<KB, KPROD>(ka, expand_s, dyn_s, sink);
+    score128_body<KB, KPROD>(ka, dyn_s, sink);
   } else {
     const int64_t qrow = (int64_t)group * a.q_per_group + (q0 + kc < a.q_per_group ? q0 + kc : q0);
     const float* srow = a.scores + qrow * a.lds + wave_key0 + col;
 #pragma unroll
     for (int t = 0; t < 16; ++t)
       if (wave_key0 + 16 * t + col < a.n) lg[t] = scale2 * srow[16 * t];
-    const uint32_t lo = (((uint32_t)tid >> 5) * 0x00204081u) & 0x01010101u;  // the expansion table
+  }
+  {
+    const uint32_t lo = (((uint32_t)tid >> 5) * 0x00204081u) & 0x01010101u;  // the expansion table of the read-out
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const uint32_t hi = ((uint32_t)i * 0x00204081u) & 0x01010101u;

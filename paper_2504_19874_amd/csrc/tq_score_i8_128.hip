@@ -6,7 +6,6 @@ namespace tq {
 
 template <int BITS, bool PROD, int TILES>
 __global__ __launch_bounds__(512) void score_i8_128_kernel(const ScoreI8Args a) {
-  __shared__ __attribute__((aligned(16))) uint2 expand_s[256 * I8_COPIES];
   extern __shared__ __attribute__((aligned(16))) unsigned char dyn_s[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -17,13 +16,13 @@ __global__ __launch_bounds__(512) void score_i8_128_kernel(const ScoreI8Args a) 
   auto sink = [&](int t, float score, bool key_live) {
     if (out_live && key_live) out0[t * 16] = score;
   };
-  score128_body<BITS, PROD, TILES>(a, expand_s, dyn_s, sink);
+  score128_body<BITS, PROD, TILES>(a, dyn_s, sink);
 }
 
 template <int BITS, bool PROD, int TILES>
 static hipError_t launch_tiles(const ScoreI8Args& a, int n_groups, hipStream_t s) {
-  constexpr int lds = score128_lds(BITS);  // on top of the 64 KB table
-  static_assert(I8_TABLE_BYTES + lds <= 160 * 1024, "LDS budget");
+  constexpr int lds = score128_lds(BITS);
+  static_assert(lds <= 160 * 1024, "LDS budget");
   const int64_t per_wg = 8 * 16 * TILES;
   const dim3 grid((unsigned)((a.n + per_wg - 1) / per_wg), n_groups, (a.q_per_group + 3) / 4);
   static LdsLimit lds_limit;  // per instantiation: the limit is raised once per device

@@ -18,7 +18,11 @@
 //     query coordinates through scalar registers; then digits into LDS).  That
 //     re-reads 128 KB of matrices per workgroup, which is cheaper than the
 //     launch-and-latency chain of a preparation kernel in front,
-//   * the 64 KB expansion table is filled in the same window.
+//   * the mask operands need no lookup: a stored word ANDed with 0x01010101 << k is already four
+//     operand bytes (bit k + 8 b of the word in byte b, worth 2^k), and the query digits are
+//     written pre-scaled by 2^(7 - k) to match (I8Prep::digitise<true>), so a tile's operands cost
+//     eight ANDs per stored word where a table in LDS cost four 8-byte reads per word and bounded
+//     the tile phase (8 x 65536 keys, 4 queries each: 3.4 of 14.3 us).
 //
 // Workgroup = 512 threads = 8 wavefronts; a wavefront owns 256 consecutive keys
 // = 16 tiles of 16, staged ROUND tiles at a time.  grid = (ceil(n / 2048),
@@ -34,7 +38,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int TILES_128 = 16;  // tiles per wavefront (the default; 8 or 4 where that would leave compute units idle)
-// tiles staged in LDS at a time: what fits beside the table within 160 KB
+// tiles staged in LDS at a time
 __host__ __device__ constexpr int round_tiles(int bits) { return bits <= 3 ? 8 : 4; }
 // bytes of one wavefront's staging region: idx, qjl, gamma, norm of 16 * round_tiles rows
 __host__ __device__ constexpr int stage_bytes(int bits) { return 16 * round_tiles(bits) * (16 * bits + 16 + 4 + 4); }
@@ -44,11 +48,10 @@ __host__ __device__ constexpr int score128_lds(int bits) { return 8 * stage_byte
 // The whole kernel as a function of where a finished score goes: sink(t, score, key_live) is
 // called once per tile t (TILES tiles of 16 keys per wavefront) by every lane with the score of
 // (query q0 + lane / 16, key wave_key0 + 16 t + lane % 16), wave_key0 = (8 blockIdx.x + wave) * 16 TILES.
-// expand_s: the 64 KB expansion table [256][32] (filled here); dyn_s: score128_lds(BITS) bytes,
-// 8 staging regions, then the query preparation.  All of LDS may be reused after the workgroup's
+// dyn_s: score128_lds(BITS) bytes, 8 staging regions, then the query preparation.  All of LDS may be reused after the workgroup's
 // next barrier.
 template <int BITS, bool PROD, int TILES = TILES_128, class Sink>
-__device__ __forceinline__ void score128_body(const ScoreI8Args& a, uint2* expand_s, unsigned char* dyn_s, Sink& sink) {
+__device__ __forceinline__ void score128_body(const ScoreI8Args& a, unsigned char* dyn_s, Sink& sink) {
   constexpr int RT = round_tiles(BITS) < TILES ? round_tiles(BITS) : TILES;
   constexpr int ROWS = 16 * RT;               // rows staged per round
   constexpr int ROUNDS = TILES / RT;
@@ -116,31 +119,19 @@ __device__ __forceinline__ void score128_body(const ScoreI8Args& a, uint2* expan
     }
   }
 
-  // ---- 3. the expansion table, 32 bank-private copies, while all of that is in flight ------
-  // thread -> (entry tid/32 + 16 i, copy tid%32): consecutive threads write consecutive
-  // addresses; the low nibble of the entry is the thread's own, the high nibble is i
-  {
-    const uint32_t lo = (((uint32_t)tid >> 5) * 0x00204081u) & 0x01010101u;  // bit i of the nibble -> byte i
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const uint32_t hi = ((uint32_t)i * 0x00204081u) & 0x01010101u;
-      expand_s[tid + 512 * i] = make_uint2(lo, hi);
-    }
-  }
-
-  // ---- 4. rotate / sketch this workgroup's four queries, 5. fixed point --------------------------
+  // ---- 3. rotate / sketch this workgroup's four queries, 4. fixed point --------------------------
   prep.matvec(a, group, q0, part_s);
   __syncthreads();
-  prep.digitise(a, q0, wave, lane, 0, part_s, dig_s, scal_s);
-  __syncthreads();  // table, digits and scalars are in LDS
+  prep.template digitise<true>(a, q0, wave, lane, 0, part_s, dig_s, scal_s);
+  __syncthreads();  // digits and scalars are in LDS
 
-  // ---- 6. A operands: lane = row + 16 kq, row = 4 * query + digit ---------------------------
+  // ---- 5. A operands: lane = row + 16 kq, row = 4 * query + digit ---------------------------
   const int a_query = col >> 2, a_digit = col & 3;
   v4i ar[2], as_[2];
   float r_inv = 0.f, r_sum = 0.f, s_inv = 0.f, s_sum = 0.f;
 #pragma unroll
   for (int s = 0; s < 2; ++s) {
-    const int c0 = i8_coord0(s, kq);
+    const int c0 = (s * 4 + kq) * 16;  // slot order of i8_shifted_slot
     ar[s] = v4i{0, 0, 0, 0};
     as_[s] = v4i{0, 0, 0, 0};
     if (BITS > 0) ar[s] = *reinterpret_cast<const v4i*>(dig_s + ((0 * 4 + a_query) * 4 + a_digit) * 128 + c0);
@@ -155,19 +146,19 @@ __device__ __forceinline__ void score128_body(const ScoreI8Args& a, uint2* expan
     s_sum = scal_s[(1 * 4 + kq) * 4 + 1];
   }
 
-  const uint32_t copy_off = (uint32_t)(lane & (I8_COPIES - 1)) * 8u;
-  const char* const table = reinterpret_cast<const char*>(expand_s);
-  // bits [16 h, 16 h + 16) of w -> 16 bytes of 0/1.  Table offset = 256 * byte + 8 * copy: one
-  // byte permute puts byte k of w into bits 8..15 above the copy offset in bits 0..7.
-  auto expand16 = [&](uint32_t w, int h) -> v4i {
-    const uint32_t o0 = __builtin_amdgcn_perm(w, copy_off, h ? 0x0c0c0600u : 0x0c0c0400u);
-    const uint32_t o1 = __builtin_amdgcn_perm(w, copy_off, h ? 0x0c0c0700u : 0x0c0c0500u);
-    const uint2 lo = *reinterpret_cast<const uint2*>(table + o0);
-    const uint2 hi = *reinterpret_cast<const uint2*>(table + o1);
-    return v4i{(int)lo.x, (int)lo.y, (int)hi.x, (int)hi.y};
+  // B operand of k-step s from the 32 stored bits w of this lane's k-chunk: dword i keeps bits
+  // 4 s + i + {0, 8, 16, 24} of w where they are, one AND each.  Byte b of it is bit
+  // k + 8 b (k = 4 s + i) times 2^k; the digits on the A side are those of the coordinate
+  // times 2^(7 - k) (negated for k = 7, where the byte reads as -128), so every product
+  // carries the same factor 128.
+  auto expand16 = [&](uint32_t w, int s) -> v4i {
+    v4i b;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) b[i] = (int)(w & (0x01010101u << (4 * s + i)));
+    return b;
   };
-  auto digits_sum = [&](const v4i& acc) -> float {  // D0 + 2^7 D1 + 2^14 D2
-    return (float)(acc[0] + acc[1] * 128 + acc[2] * 16384);
+  auto digits_sum = [&](const v4i& acc) -> float {  // (D0 + 2^7 D1 + 2^14 D2 + 2^21 D3) / 128, D0 a multiple of 128
+    return (float)((acc[0] >> 7) + acc[1] + acc[2] * 128 + acc[3] * 16384);
   };
 
   // per-lane constants of the final combination
@@ -177,9 +168,9 @@ __device__ __forceinline__ void score128_body(const ScoreI8Args& a, uint2* expan
   const float base_r = a.coef[0] * r_sum;
   const float zs = 2.f * s_inv;
 
-  // ---- 7. tiles ------------------------------------------------------------------------------
+  // ---- 6. tiles ------------------------------------------------------------------------------
   // A four-stage software pipeline written out in source order: the words of tile t+2 are
-  // fetched from the staging region, the table lookups of tile t+1 are issued, the MFMAs of
+  // fetched from the staging region, the mask operands of tile t+1 are made, the MFMAs of
   // tile t run and the sums of tile t-1 are combined and stored.  The staging region is
   // private to the wavefront and LDS executes a wavefront's instructions in order, so the
   // next round may be written as soon as the last word fetch of the current one is issued.

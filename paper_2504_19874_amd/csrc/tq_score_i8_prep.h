@@ -16,6 +16,12 @@
 
 namespace tq {
 
+// Slot of coordinate c (d = 128) among the 128 operand bytes of a digit row when the mask bytes are the stored
+// bits left in place: k-step s = bit 2 of c, k-chunk kq = c / 32, dword i = c % 4, byte b = (c / 8) % 4.
+__host__ __device__ constexpr int i8_shifted_slot(int c) {
+  return (((c >> 2) & 1) * 4 + (c >> 5)) * 16 + (c & 3) * 4 + ((c >> 3) & 3);
+}
+
 constexpr int I8_PREP_BYTES = 2 * 2 * 4 * 128 * 4 + 2 * 4 * 4 * 128 + 2 * 4 * 4 * 4;  // partial sums, digits, scalars
 
 // max / sum over the 64 lanes: four DPP steps inside each row of 16, then the four rows
@@ -79,6 +85,10 @@ struct I8Prep {
     for (int qi = 0; qi < 4; ++qi) part_s[((mat * 2 + kh) * 4 + qi) * 128 + j] = acc[qi];
   }
 
+  // SHIFTED: the digit image for operands whose mask bytes are the stored bits left in place (bit k of a byte
+  // reads as 2^k, as -128 for k = 7): coordinate c is written as Q 2^(7 - c % 8), negated where c % 8 = 7, in
+  // four digits, at slot i8_shifted_slot(c); the masked sum of the products is then 128 times that of Q.
+  template <bool SHIFTED = false>
   __device__ __forceinline__ static void digitise(const ScoreI8Args& a, int q0, int wave, int lane, int d_hi,
                                                   const float* part_s, signed char* dig_s, float* scal_s) {
     const int m = wave >> 2, qi = wave & 3;
@@ -101,16 +111,20 @@ struct I8Prep {
     const int tot_hi = wave_sum((lane < d_hi ? Q[0] : 0) + (lane + 64 < d_hi ? Q[1] : 0));
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
-      // balanced base 128: D0, D1 in [-64, 63], D2 in [-64, 64]
-      const int d0 = ((Q[u] + 64) & 127) - 64;
-      const int Q1 = (Q[u] - d0) >> 7;
+      // balanced base 128: D0, D1 in [-64, 63], D2 in [-64, 64] (SHIFTED: D2 as D1, |D3| <= 33)
+      const int c = lane + 64 * u, k = c & 7;
+      const int Qs = !SHIFTED ? Q[u] : k == 7 ? -Q[u] : Q[u] << (7 - k);
+      const int d0 = ((Qs + 64) & 127) - 64;
+      const int Q1 = (Qs - d0) >> 7;
       const int d1 = ((Q1 + 64) & 127) - 64;
-      const int d2 = (Q1 - d1) >> 7;
-      signed char* o = dig_s + (m * 4 + qi) * 4 * 128 + lane + 64 * u;
+      const int Q2 = (Q1 - d1) >> 7;
+      const int d2 = SHIFTED ? ((Q2 + 64) & 127) - 64 : Q2;
+      const int d3 = (Q2 - d2) >> 7;
+      signed char* o = dig_s + (m * 4 + qi) * 4 * 128 + (SHIFTED ? i8_shifted_slot(c) : c);
       o[0] = (signed char)d0;
       o[128] = (signed char)d1;
       o[256] = (signed char)d2;
-      o[384] = 0;
+      o[384] = (signed char)d3;
     }
     if (lane == 0) {
       const float inv = ldexpf(1.f, e - 19);
