@@ -91,6 +91,24 @@ def intake_probe(torch):
                           "hbm_gbs": round(cus * own_kb * 1024 / (med * 1e-3) / 1e9, 1),
                           "bytes_per_us_per_cu": round(kb * 1024 / (med * 1e3), 1)}), flush=True)
 
+    # when each wavefront's loads come back (own region of 112 KB per workgroup, 14 loads per thread, cold)
+    lib.tq_probe_arrival.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
+    lib.tq_probe_arrival.restype = C.c_int
+    stamps = torch.zeros(cus * 8 * 16, dtype=torch.int64, device="cuda")
+    for r in range(6):
+        rc = lib.tq_probe_arrival(own[r % sets].data_ptr(), out.data_ptr(), stamps.data_ptr(), cus, stream)
+        if rc != 0:
+            raise RuntimeError(f"tq_probe_arrival returned {rc}")
+        torch.cuda.synchronize()
+    t = stamps.cpu().numpy().reshape(cus * 8, 16)[:, :15].astype("float64")
+    t = (t - t[:, 0].min()) * 0.01  # 100 MHz clock -> microseconds after the first wavefront's start
+    import numpy as np
+    rows = {}
+    for k in (0, 1, 2, 4, 7, 10, 12, 14):
+        rows[f"after_{k}_loads" if k else "start"] = [round(float(np.percentile(t[:, k], q)), 2) for q in (5, 25, 50, 75, 95)]
+    print(json.dumps({"probe": "arrival", "workgroups": cus, "own_kb": 112, "loads_per_thread": 14,
+                      "us_percentiles_5_25_50_75_95": rows}), flush=True)
+
 
 def main():
     ap = argparse.ArgumentParser()
