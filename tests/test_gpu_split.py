@@ -361,3 +361,67 @@ def test_attend_rejects_value_codes_it_does_not_cover():
         f2 = torch.ones((8, 2), dtype=torch.float32, device=DEV)
         tq.tq_attend(pk, pv, torch.zeros((4, D), device=DEV), 1, 4, (z32, z32, f2, f2), (z32, None, None, f2), 8, 1.0,
                      torch.zeros((4, D), device=DEV))
+
+
+@pytest.mark.parametrize("d,d_hi,bits_lo,prod,n,nq", [
+    (1536, 384, 3, False, 2100, 40),   # the d = 1536 retrieval shape: a quarter of the channels at 4 bits, the rest at 3
+    (256, 64, 1, True, 1500, 6),       # few queries, inner-product codes of both instances
+    (512, 128, 2, True, 700, 70),
+])
+def test_split_at_any_dimension_by_two_instances(d, d_hi, bits_lo, prod, n, nq):
+    """Sec. 4.3's two instances at a dimension other than 128: the channels of instance hi first, each instance
+    an ordinary parameter set of its own dimension that reads its columns of x (and of q) through the row stride
+    and writes its columns of the dequantised output the same way; the estimate of <q, x> is the sum of the two
+    instances' estimates.  Every call is the library's ordinary one; the oracle's quant_split / dequant_split
+    over the same channel split is the reference."""
+    hi_ch = np.arange(d_hi)
+    dims, bits = (d_hi, d - d_hi), (bits_lo + 1, bits_lo)
+    rng = np.random.default_rng(77)
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    x[:, :8] *= 15.0  # outlier channels lie in instance hi
+    x[3] = 0.0
+    q = W.gaussian_queries(nq, d, 5, unit=False)
+    x_dev, q_dev = dev(x), dev(q)
+    xt_dev = torch.zeros((n, d), dtype=torch.float32, device=DEV)
+    total = torch.zeros((nq, n), dtype=torch.float32, device=DEV)
+    inst, res = [], []
+    col = 0
+    for part, (dd, b) in enumerate(zip(dims, bits)):
+        g = W.gaussian_matrix(dd, 500 + part)
+        s_ = W.sketch_matrix(dd, 600 + part) if prod else None
+        c32, t32, _ = o.codebook_fp32(dd, b)
+        inst.append(dict(Pi=o.rotation_from_gaussian(g), S=s_, c32=c32, t32=t32, d=dd, bits=b))
+        p = tq.make_params(dd, b, g, s_).reserve(n, nq, 0)
+        xs = x_dev[:, col:col + dd]  # a view: row stride d
+        idx = torch.zeros((n, p.idx_words), dtype=torch.int32, device=DEV)
+        norm = torch.zeros(n, dtype=torch.float32, device=DEV)
+        qjl = torch.zeros((n, p.qjl_words), dtype=torch.int32, device=DEV) if prod else None
+        gamma = torch.zeros(n, dtype=torch.float32, device=DEV) if prod else None
+        if prod:
+            tq.tq_quantize_prod(p, xs, idx, qjl, gamma, norm)
+        else:
+            tq.tq_quantize_mse(p, xs, idx, norm)
+        tq.tq_dequantize(p, idx, qjl, gamma, norm, xt_dev[:, col:col + dd])
+        part_scores = torch.zeros((nq, n), dtype=torch.float32, device=DEV)
+        tq.tq_score(p, q_dev[:, col:col + dd], 1, nq, idx, qjl, gamma, norm, n, part_scores)
+        total += part_scores
+        r = dict(idx=o.unpack_planes(words(idx), b, dd), norm=norm.cpu().numpy())
+        if prod:
+            r["qjl"] = o.unpack_signs(words(qjl), dd)
+            r["gamma"] = gamma.cpu().numpy()
+        res.append(r)
+        col += dd
+    # the quantiser of each instance against the oracle's split quantiser
+    want_hi, want_lo = o.quant_split(x.astype(np.float64), hi_ch, inst[0], inst[1], prod)
+    for r, w, i in zip(res, (want_hi, want_lo), inst):
+        P.check_close(r["norm"], w["norm"], 0.0, "norm", rel=3e-6)
+        P.check_indices(r["idx"], w["idx"], w["y"], i["t32"])
+    # dequantised vectors and scores downstream of the GPU's own codes
+    want_xt = o.dequant_split(d, hi_ch, res[0], res[1], inst[0], inst[1], prod)
+    scale = np.zeros((n, d))
+    scale[:, :d_hi] = res[0]["norm"][:, None] / math.sqrt(d_hi)
+    scale[:, d_hi:] = res[1]["norm"][:, None] / math.sqrt(d - d_hi)
+    P.check_close(xt_dev.cpu().numpy(), want_xt, scale, "dequantized coordinate")
+    bound = sum(np.linalg.norm(q[:, c], axis=1)[:, None] * r["norm"][None, :]
+                for c, r in ((slice(0, d_hi), res[0]), (slice(d_hi, d), res[1])))
+    P.check_close(total.cpu().numpy(), o.score(q, want_xt), bound, "score")
