@@ -120,6 +120,8 @@ def main():
                     help="also run one plain 256 MiB device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     ap.add_argument("--no-images", action="store_true",
                     help="d = 128: split the matrices in every launch instead of using the images of tq_build_images")
+    ap.add_argument("--f32-input", action="store_true",
+                    help="hand the vectors of a bf16 configuration to the quantiser as fp32 (same values)")
     ap.add_argument("--value-bits", type=int, default=2, help="attend: bits of the MSE stage of the value codes")
     ap.add_argument("--value-prod", action="store_true", help="attend: value codes from TurboQuant_prod")
     ap.add_argument("--value-split", type=int, default=0, metavar="D_HI",
@@ -167,13 +169,15 @@ def main():
     spv = p.scalars_per_vector
 
     # input sets: rotate through several when the working set would sit in cache
-    in_b = 2 if cfg.in_dtype == "bf16" else 4
+    in_b = 2 if cfg.in_dtype == "bf16" and not args.f32_input else 4
     sets = 1 if (big or args.warm) else max(1, min(12, int(300e6 // max(1, n * d * in_b)) + 1))
     xs = []
     for s in range(sets):
         if cfg.in_dtype == "bf16":
             keys = W.kv_keys(cfg.n_groups, cfg.n, d, cfg.seed_x + 1000 * s).reshape(n, d)
             xs.append(torch.from_numpy(keys.view(np.int16)).view(torch.bfloat16).cuda())
+            if args.f32_input:
+                xs[-1] = xs[-1].float()
         elif big:
             x = torch.empty((n, d), dtype=torch.float32, device="cuda")
             for start, blk in W.mixture_rows(n, d, cfg.seed_x, cfg.seed_x):

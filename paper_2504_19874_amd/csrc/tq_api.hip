@@ -133,18 +133,18 @@ tq_status quantize_common(const tq_params* p, const void* x, int32_t dtype, int6
     if (!aligned16(x) || (ldx * esz) % 16 != 0) return TQ_ERR_UNSUPPORTED;
     const Codebook cb_hi = make_codebook_hi(p);
     if (dtype == TQ_BF16 && n >= kBf3QuantRows && !fp32_mfma_only(p) && (!prod || aligned16(qjl)) &&
-        quant128_bf3_applicable(p->bits_mse, prod, x, ldx, make_codebook(p), &cb_hi))
-      return from_hip(launch_quant128_bf3(p->bits_mse, prod, x, ldx, n, p->Pi, prod ? p->SPiT : nullptr, idx, qjl, gamma,
+        quant128_bf3_applicable(p->bits_mse, prod, false, x, ldx, make_codebook(p), &cb_hi))
+      return from_hip(launch_quant128_bf3(p->bits_mse, prod, false, x, ldx, n, p->Pi, prod ? p->SPiT : nullptr, idx, qjl, gamma,
                                           norm, make_codebook(p), p->d_hi / 32, make_codebook_hi(p), quant_image(p), stream));
     return from_hip(launch_quant128(p->bits_mse, prod, dtype == TQ_BF16, x, ldx, n, p->Pi,
                                     prod ? p->SPiT : nullptr, idx, qjl, gamma, norm, make_codebook(p),
                                     p->d_hi / 32, make_codebook_hi(p), stream));
   }
 
-  // head dimension 128, a large batch of bf16 vectors: the contractions on the bf16 matrix cores
-  if (d == 128 && dtype == TQ_BF16 && n >= kBf3QuantRows && !fp32_mfma_only(p) && quant128_bf3_applicable(p->bits_mse, prod, x, ldx, make_codebook(p), nullptr) &&
+  // head dimension 128, a large batch of bf16 or fp32 vectors: the contractions on the bf16 matrix cores
+  if (d == 128 && n >= kBf3QuantRows && !fp32_mfma_only(p) && quant128_bf3_applicable(p->bits_mse, prod, dtype == TQ_F32, x, ldx, make_codebook(p), nullptr) &&
       (p->bits_mse == 0 || aligned16(idx)) && (!prod || aligned16(qjl)))
-    return from_hip(launch_quant128_bf3(p->bits_mse, prod, x, ldx, n, p->Pi, prod ? p->SPiT : nullptr, idx, qjl, gamma,
+    return from_hip(launch_quant128_bf3(p->bits_mse, prod, dtype == TQ_F32, x, ldx, n, p->Pi, prod ? p->SPiT : nullptr, idx, qjl, gamma,
                                         norm, make_codebook(p), 0, make_codebook(p), quant_image(p), stream));
 
   // head dimension 128: one fused kernel, parameters resident in LDS

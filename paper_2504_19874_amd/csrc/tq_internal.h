@@ -116,8 +116,8 @@ hipError_t launch_dequant128(int bits, bool prod, const uint32_t* idx, const uin
 // d = 128, large batches, bf16 matrix cores at fp32 accuracy (tq_d128_bf3.hip)
 bool dequant128_bf3_applicable(int bits, bool prod, const Codebook& cb, const float* out, int64_t ldo);
 constexpr int64_t kBf3QuantRows = 8193;   // bf16 input: from here on the bf16-piece kernel wins (17 us flat up to 65536 rows against 20 / 29 / 37)
-bool quant128_bf3_applicable(int bits, bool prod, const void* X, int64_t ldx, const Codebook& cb, const Codebook* cb_hi);
-hipError_t launch_quant128_bf3(int bits, bool prod, const void* X, int64_t ldx, int64_t n, const float* Pi,
+bool quant128_bf3_applicable(int bits, bool prod, bool f32, const void* X, int64_t ldx, const Codebook& cb, const Codebook* cb_hi);
+hipError_t launch_quant128_bf3(int bits, bool prod, bool f32, const void* X, int64_t ldx, int64_t n, const float* Pi,
                                const float* SPiT, uint32_t* idx, uint32_t* qjl, float* gamma, float* norm,
                                const Codebook& cb, int gs_hi, const Codebook& cb_hi, const void* image, hipStream_t s);
 // the matrices of those two kernels as they sit in LDS, made once (tq_build_images); null pointers above mean

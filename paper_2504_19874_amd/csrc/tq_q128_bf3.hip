@@ -40,7 +40,7 @@ constexpr int RING = 4;  // A operands in flight
 __device__ __forceinline__ int lds_at(int row, int col) { return row * 128 + ((((col >> 3) ^ row) & 15) << 3) + (col & 7); }
 
 struct Q128Args {
-  const unsigned short* X;  // bf16
+  const void* X;  // bf16, or fp32 in the F32 instantiations
   int64_t ldx;
   int64_t n;
   const float* Pi;
@@ -113,7 +113,11 @@ __global__ __launch_bounds__(256) void q128_image_kernel(const float* Pi, const 
 // VT = vector tiles (of 32) per wavefront: 2 = four wavefronts of 64 vectors (one per SIMD, every LDS read of an A
 // operand feeds two MFMAs), 1 = eight wavefronts of 32 vectors (two per SIMD: while one is in its decision stage or
 // waits for LDS, the other issues MFMAs).
-template <int BITS, bool PROD, bool MIXED, int VT>
+//
+// F32: the vectors are fp32.  A lane's 8 values of a step are two 16-byte loads, split into their two leading
+// pieces (x1 + x2 = x up to 2^-17 |x|), and the rotation takes the five piece products of weight >= 2^-16 that two
+// pieces of x have with three of Pi: every A operand read of the two leading pieces of Pi feeds two MFMAs.
+template <int BITS, bool PROD, bool MIXED, int VT, bool F32 = false>
 __global__ __launch_bounds__(512 / VT) void quant128_bf3_kernel(const Q128Args a) {
   constexpr int NT = 512 / VT;  // threads
   constexpr int NB = (BITS > 0 ? BITS : 1) + (MIXED ? 1 : 0);  // plane words per tile, at most
@@ -145,16 +149,27 @@ __global__ __launch_bounds__(512 / VT) void quant128_bf3_kernel(const Q128Args a
 
   const int64_t blocks = (a.n + 255) / 256;
   const bool normalise = !MIXED && a.norm != nullptr;
-  u32x4 xop[VT][8];
+  constexpr int ESZ = F32 ? 4 : 2;
+  u32x4 xop[VT][8];                   // the B operands of stage 1 (F32: piece 1 of x)
+  u32x4 xop2[F32 ? VT : 1][8];        // F32: piece 2
+  u32x4 xraw[F32 ? VT : 1][8][2];     // F32: the fp32 values as loaded
   auto x_row = [&](int64_t blk, int nt) {  // this lane's 8 values of step 0
     const int64_t v = blk * 256 + wave * (32 * VT) + 32 * nt + vi;
-    return a.X + (v < a.n ? v : a.n - 1) * a.ldx + 8 * g;  // clamped: such vectors are not stored
+    return static_cast<const char*>(a.X) + ((v < a.n ? v : a.n - 1) * a.ldx + 8 * g) * ESZ;  // clamped: such vectors are not stored
+  };
+  auto load_x = [&](const char* src, int nt, int s) {  // the 8 values of step s
+    if constexpr (F32) {
+      xraw[nt][s][0] = *reinterpret_cast<const u32x4*>(src + 64 * s);
+      xraw[nt][s][1] = *reinterpret_cast<const u32x4*>(src + 64 * s + 16);
+    } else {
+      xop[nt][s] = *reinterpret_cast<const u32x4*>(src + 32 * s);
+    }
   };
 #pragma unroll
   for (int nt = 0; nt < VT; ++nt) {
-    const unsigned short* src = x_row(blockIdx.x, nt);
+    const char* src = x_row(blockIdx.x, nt);
 #pragma unroll
-    for (int s = 0; s < 8; ++s) xop[nt][s] = *reinterpret_cast<const u32x4*>(src + 16 * s);
+    for (int s = 0; s < 8; ++s) load_x(src, nt, s);
   }
 
   for (int64_t blk = blockIdx.x; blk < blocks; blk += gridDim.x) {
@@ -168,17 +183,44 @@ __global__ __launch_bounds__(512 / VT) void quant128_bf3_kernel(const Q128Args a
         float s0 = 0.f, s1 = 0.f;
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
-          s0 = square_pair(xop[nt][s][0], s0);
-          s1 = square_pair(xop[nt][s][1], s1);
-          s0 = square_pair(xop[nt][s][2], s0);
-          s1 = square_pair(xop[nt][s][3], s1);
+          if constexpr (F32) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+              const f32x4 v = __builtin_bit_cast(f32x4, xraw[nt][s][h]);
+              s0 = fmaf(v[0], v[0], s0);
+              s1 = fmaf(v[1], v[1], s1);
+              s0 = fmaf(v[2], v[2], s0);
+              s1 = fmaf(v[3], v[3], s1);
+            }
+          } else {
+            s0 = square_pair(xop[nt][s][0], s0);
+            s1 = square_pair(xop[nt][s][1], s1);
+            s0 = square_pair(xop[nt][s][2], s0);
+            s1 = square_pair(xop[nt][s][3], s1);
+          }
         }
         nu[nt] = sqrtf(add_across_halves(s0 + s1));
         inv[nt] = nu[nt] > 0.f ? 1.f / nu[nt] : 0.f;
       }
     }
 
-    // ---- stage 1: y^T = Pi x^T, three piece products ----------------------------------------------------
+    if constexpr (F32) {
+      // the two leading pieces of the vectors: word j of a step's operand holds values 2 j and 2 j + 1
+#pragma unroll
+      for (int nt = 0; nt < VT; ++nt)
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const f32x4 v = __builtin_bit_cast(f32x4, xraw[nt][s][j >> 1]);
+            uint32_t w1, w2;
+            split2_pair(f32x2{v[2 * (j & 1)], v[2 * (j & 1) + 1]}, w1, w2);
+            xop[nt][s][j] = w1;
+            xop2[nt][s][j] = w2;
+          }
+    }
+
+    // ---- stage 1: y^T = Pi x^T, three piece products (F32: five) ----------------------------------------
     // (the first product of every accumulator takes a zero C operand: nothing is cleared)
     floatx16 acc[VT][4];
     const floatx16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -198,6 +240,14 @@ __global__ __launch_bounds__(512 / VT) void quant128_bf3_kernel(const Q128Args a
         for (int nt = 0; nt < VT; ++nt)
           acc[nt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i % RING], *reinterpret_cast<const bf16x8*>(&xop[nt][s]),
                                                                i < 4 ? zero16 : acc[nt][t], 0, 0, 0);
+        if constexpr (F32) {
+          if ((i >> 2) % 3 != 0) {  // pieces 1 and 0 of Pi also meet piece 2 of x
+#pragma unroll
+            for (int nt = 0; nt < VT; ++nt)
+              acc[nt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i % RING], *reinterpret_cast<const bf16x8*>(&xop2[nt][s]),
+                                                                   acc[nt][t], 0, 0, 0);
+          }
+        }
         if (i + RING < 96) ring[i % RING] = pi_piece(i + RING);
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -274,12 +324,12 @@ __global__ __launch_bounds__(512 / VT) void quant128_bf3_kernel(const Q128Args a
     const bool storing = v_mine < a.n && (VT == 2 || g == 0);
     constexpr int HI = VT - 1;  // the tile of the upper half-wave
     // the next block's vectors are fetched while this block is finished: spread over the first pass of stage 2
-    const unsigned short* const next_x[2] = {x_row(blk + gridDim.x, 0), x_row(blk + gridDim.x, HI)};
+    const char* const next_x[2] = {x_row(blk + gridDim.x, 0), x_row(blk + gridDim.x, HI)};
     if (!PROD) {
 #pragma unroll
       for (int nt = 0; nt < VT; ++nt)
 #pragma unroll
-        for (int s = 0; s < 8; ++s) xop[nt][s] = *reinterpret_cast<const u32x4*>(next_x[nt] + 16 * s);
+        for (int s = 0; s < 8; ++s) load_x(next_x[nt], nt, s);
     }
 
     // ---- the codes of Alg. 1: lane (vi, g) writes the row of vector 32 g + vi ----------------------------
@@ -339,7 +389,7 @@ __global__ __launch_bounds__(512 / VT) void quant128_bf3_kernel(const Q128Args a
             if (i + RING < 32) ring[i % RING] = w_piece(i + RING);
             // the next block's vectors: all sixteen loads during the first pass
             if (pass == 0 && (i & 1) && (VT == 2 || !(i & 2)))
-              xop[(i >> 1) & HI][s] = *reinterpret_cast<const u32x4*>(next_x[(i >> 1) & 1] + 16 * s);
+              load_x(next_x[(i >> 1) & 1], (i >> 1) & HI, s);
             __builtin_amdgcn_sched_barrier(0);
           }
         }
@@ -380,67 +430,72 @@ __global__ __launch_bounds__(512 / VT) void quant128_bf3_kernel(const Q128Args a
   }
 }
 
-template <int BITS, bool PROD, bool MIXED, int VT>
+template <int BITS, bool PROD, bool MIXED, int VT, bool F32>
 hipError_t launch_vt(const Q128Args& a, hipStream_t s) {
   constexpr int lds = (PI_ELEMS + (PROD ? W_ELEMS : 0)) * 2;
   static LdsLimit lds_limit;  // per instantiation: the limit is raised once per device
-  if (const hipError_t e = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&quant128_bf3_kernel<BITS, PROD, MIXED, VT>), lds); e != hipSuccess) return e;
+  if (const hipError_t e = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&quant128_bf3_kernel<BITS, PROD, MIXED, VT, F32>), lds); e != hipSuccess) return e;
   const int64_t blocks = (a.n + 255) / 256, cus = device_cu_count();  // one workgroup per compute unit
-  hipLaunchKernelGGL((quant128_bf3_kernel<BITS, PROD, MIXED, VT>), dim3((unsigned)(blocks < cus ? blocks : cus)), dim3(512 / VT), lds, s, a);
+  hipLaunchKernelGGL((quant128_bf3_kernel<BITS, PROD, MIXED, VT, F32>), dim3((unsigned)(blocks < cus ? blocks : cus)), dim3(512 / VT), lds, s, a);
   return hipGetLastError();
 }
 
 // eight wavefronts of 32 vectors: measured against four of 64 (VT = 2) on the same box, 524288 vectors, 2 + 1 bits:
 // 109 against 125 us; 3 + 1 bits: 122 against 150; two instances: 105 against 124; 131072 vectors: 33 against 38
 template <int BITS, bool PROD, bool MIXED>
-hipError_t launch_one(const Q128Args& a, hipStream_t s) {
-  return launch_vt<BITS, PROD, MIXED, 1>(a, s);
+hipError_t launch_one(const Q128Args& a, bool f32, hipStream_t s) {
+  if constexpr (!MIXED) {
+    if (f32) return launch_vt<BITS, PROD, MIXED, 1, true>(a, s);
+  }
+  return launch_vt<BITS, PROD, MIXED, 1, false>(a, s);
 }
 
 }  // namespace
 
-// bf16 rows of 128 values, 16-byte aligned with a row stride that keeps them so; symmetric tables
-bool quant128_bf3_applicable(int bits, bool prod, const void* X, int64_t ldx, const Codebook& cb, const Codebook* cb_hi) {
+// bf16 rows of 128 values (fp32 rows too where there is one instance), 16-byte aligned with a row stride that keeps
+// them so; symmetric tables
+bool quant128_bf3_applicable(int bits, bool prod, bool f32, const void* X, int64_t ldx, const Codebook& cb, const Codebook* cb_hi) {
+  if (f32 && cb_hi != nullptr) return false;
   if (bits < 0 || bits > (cb_hi != nullptr ? 3 : 4) || (bits == 0 && !prod && cb_hi == nullptr)) return false;
   // from 3 bits on the decision is taken on |y|: tables symmetric about zero (what tq_build_codebook produces)
   if (!codebook_symmetric(cb, bits) || (cb_hi != nullptr && !codebook_symmetric(*cb_hi, bits + 1))) return false;
-  return (reinterpret_cast<uintptr_t>(X) & 15u) == 0 && ldx % 8 == 0;
+  return (reinterpret_cast<uintptr_t>(X) & 15u) == 0 && ldx % (f32 ? 4 : 8) == 0;
 }
 
 // gs_hi > 0: two instances (cb_hi with bits + 1 bits for the first gs_hi coordinate groups); norm is required then
-hipError_t launch_quant128_bf3(int bits, bool prod, const void* X, int64_t ldx, int64_t n, const float* Pi,
+hipError_t launch_quant128_bf3(int bits, bool prod, bool f32, const void* X, int64_t ldx, int64_t n, const float* Pi,
                                const float* SPiT, uint32_t* idx, uint32_t* qjl, float* gamma, float* norm,
                                const Codebook& cb, int gs_hi, const Codebook& cb_hi, const void* image, hipStream_t s) {
   if (n <= 0) return hipSuccess;
-  if (gs_hi < 0 || gs_hi > 3 || (gs_hi > 0 && (bits > 3 || cb_hi.bits != bits + 1 || norm == nullptr))) return hipErrorInvalidValue;
+  if (gs_hi < 0 || gs_hi > 3 || (gs_hi > 0 && (f32 || bits > 3 || cb_hi.bits != bits + 1 || norm == nullptr))) return hipErrorInvalidValue;
   if (!codebook_symmetric(cb, bits) || (gs_hi > 0 && !codebook_symmetric(cb_hi, bits + 1))) return hipErrorInvalidValue;
   Q128Args a;
-  a.X = static_cast<const unsigned short*>(X); a.ldx = ldx; a.n = n; a.Pi = Pi; a.SPiT = SPiT; a.idx = idx; a.qjl = qjl;
+  a.X = X; a.ldx = ldx; a.n = n; a.Pi = Pi; a.SPiT = SPiT; a.idx = idx; a.qjl = qjl;
   a.image = static_cast<const u32x4*>(image);
   a.gamma = gamma; a.norm = norm; a.cb = cb; a.gs_hi = gs_hi; a.cb_hi = cb_hi;
   if (gs_hi > 0) {
     switch (bits * 2 + (prod ? 1 : 0)) {
-      case 0: return launch_one<0, false, true>(a, s);
-      case 1: return launch_one<0, true, true>(a, s);
-      case 2: return launch_one<1, false, true>(a, s);
-      case 3: return launch_one<1, true, true>(a, s);
-      case 4: return launch_one<2, false, true>(a, s);
-      case 5: return launch_one<2, true, true>(a, s);
-      case 6: return launch_one<3, false, true>(a, s);
-      case 7: return launch_one<3, true, true>(a, s);
+      case 0: return launch_one<0, false, true>(a, f32, s);
+      case 1: return launch_one<0, true, true>(a, f32, s);
+      case 2: return launch_one<1, false, true>(a, f32, s);
+      case 3: return launch_one<1, true, true>(a, f32, s);
+      case 4: return launch_one<2, false, true>(a, f32, s);
+      case 5: return launch_one<2, true, true>(a, f32, s);
+      case 6: return launch_one<3, false, true>(a, f32, s);
+      case 7: return launch_one<3, true, true>(a, f32, s);
       default: return hipErrorInvalidValue;
     }
   }
   switch (bits * 2 + (prod ? 1 : 0)) {
-    case 1: return launch_one<0, true, false>(a, s);
-    case 2: return launch_one<1, false, false>(a, s);
-    case 3: return launch_one<1, true, false>(a, s);
-    case 4: return launch_one<2, false, false>(a, s);
-    case 5: return launch_one<2, true, false>(a, s);
-    case 6: return launch_one<3, false, false>(a, s);
-    case 7: return launch_one<3, true, false>(a, s);
-    case 8: return launch_one<4, false, false>(a, s);
-    case 9: return launch_one<4, true, false>(a, s);
+    case 1: return launch_one<0, true, false>(a, f32, s);
+    case 2: return launch_one<1, false, false>(a, f32, s);
+    case 3: return launch_one<1, true, false>(a, f32, s);
+    case 4: return launch_one<2, false, false>(a, f32, s);
+    case 5: return launch_one<2, true, false>(a, f32, s);
+    case 6: return launch_one<3, false, false>(a, f32, s);
+    case 7: return launch_one<3, true, false>(a, f32, s);
+    case 8: return launch_one<4, false, false>(a, f32, s);
+    case 9: return launch_one<4, true, false>(a, f32, s);
     default: return hipErrorInvalidValue;
   }
 }

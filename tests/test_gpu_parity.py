@@ -138,6 +138,8 @@ def _quant_inputs(n, d, kind, seed):
     (128, 1, 30000, "f32"), (128, 4, 25000, "unit"), (128, 3, 40000, "bf16"),
     # large batches of bf16 vectors: the kernel on the bf16 matrix cores (blocks of 256 vectors, ragged tails)
     (128, 1, 33000, "bf16"), (128, 2, 32845, "bf16unit"), (128, 4, 70001, "bf16"),
+    # large batches of fp32 vectors: the same kernel on two pieces of x (five piece products)
+    (128, 2, 33001, "f32"), (128, 3, 40000, "unit"), (128, 4, 8193, "f32"),
     # just above the threshold of that kernel: one vector, and one wavefront's worth, in the last block
     (128, 2, 8193, "bf16"), (128, 3, 8225, "bf16"),
 ])
@@ -191,6 +193,8 @@ def _check_prod(p, Pi, S, c32, t32, x_or, normalise, idx, qjl, gamma, norm):
     # large batches of bf16 vectors: the kernel on the bf16 matrix cores (blocks of 256 vectors, ragged tails)
     (128, 0, 33000, "bf16"), (128, 1, 40001, "bf16"), (128, 2, 66000, "bf16"), (128, 3, 32768, "bf16unit"),
     (128, 4, 33333, "bf16"), (128, 2, 8193, "bf16"), (128, 1, 8449, "bf16"),
+    # large batches of fp32 vectors: the same kernel on two pieces of x (five piece products)
+    (128, 2, 33001, "f32"), (128, 3, 66000, "f32"), (128, 4, 9000, "unit"),
 ])
 def test_quantize_prod(d, bits_mse, n, kind):
     p, Pi, S, c32, t32 = setup(d, bits_mse, True)
