@@ -43,7 +43,8 @@ __host__ __device__ constexpr int round_tiles(int bits) { return bits <= 3 ? 8 :
 // bytes of one wavefront's staging region: idx, qjl, gamma, norm of 16 * round_tiles rows
 __host__ __device__ constexpr int stage_bytes(int bits) { return 16 * round_tiles(bits) * (16 * bits + 16 + 4 + 4); }
 
-__host__ __device__ constexpr int score128_lds(int bits) { return 8 * stage_bytes(bits) + I8_PREP_BYTES; }
+// staging regions, partial sums of the query preparation (8 KB), one 2 KB digit image per masked sum, scalars
+__host__ __device__ constexpr int score128_lds(int bits) { return 8 * stage_bytes(bits) + 2 * 2 * 4 * 128 * 4 + i8_terms(bits, true) * 2048 + 2 * 4 * 4 * 4; }
 
 // The whole kernel as a function of where a finished score goes: sink(t, score, key_live) is
 // called once per tile t (TILES tiles of 16 keys per wavefront) by every lane with the score of
@@ -74,8 +75,8 @@ __device__ __forceinline__ void score128_body(const ScoreI8Args& a, unsigned cha
 
   unsigned char* const stage = dyn_s + wave * stage_bytes(BITS);
   float* const part_s = reinterpret_cast<float*>(dyn_s + 8 * stage_bytes(BITS));        // [2][2][4][128]
-  signed char* const dig_s = reinterpret_cast<signed char*>(part_s + 2 * 2 * 4 * 128);  // [2][4][4][128]
-  float* const scal_s = reinterpret_cast<float*>(dig_s + 2 * 4 * 4 * 128);              // [2][4][4]
+  signed char* const dig_s = reinterpret_cast<signed char*>(part_s + 2 * 2 * 4 * 128);  // [term][4][4][128]
+  float* const scal_s = reinterpret_cast<float*>(dig_s + i8_terms(BITS, true) * 2048);  // [2][4][4]
 
   // ---- 1. this thread's column of the transposed matrix: 64 values of k ---------------------
   I8Prep<(BITS > 0), PROD> prep;
@@ -122,24 +123,26 @@ __device__ __forceinline__ void score128_body(const ScoreI8Args& a, unsigned cha
   // ---- 3. rotate / sketch this workgroup's four queries, 4. fixed point --------------------------
   prep.matvec(a, group, q0, part_s);
   __syncthreads();
-  prep.template digitise<true>(a, q0, wave, lane, 0, part_s, dig_s, scal_s);
+  i8_digitise_terms<BITS, PROD>(a, q0, wave, lane, part_s, dig_s, scal_s);
   __syncthreads();  // digits and scalars are in LDS
 
-  // ---- 5. A operands: lane = row + 16 kq, row = 4 * query + digit ---------------------------
+  // ---- 5. A operands: lane = row + 16 kq, row = 4 * query + digit; one image per masked sum --------
   const int a_query = col >> 2, a_digit = col & 3;
-  v4i ar[2], as_[2];
-  float r_inv = 0.f, r_sum = 0.f, s_inv = 0.f, s_sum = 0.f;
+  constexpr bool A_REGS = NTA <= 3;  // else read at every use (LDS has nothing else to do)
+  auto a_read = [&](int j, int s) -> v4i {
+    return *reinterpret_cast<const v4i*>(dig_s + ((j * 4 + a_query) * 4 + a_digit) * 128 + (s * 4 + kq) * 16);  // slot order of i8_shifted_slot
+  };
+  v4i areg[A_REGS ? NTA : 1][2];
+  if (A_REGS) {
 #pragma unroll
-  for (int s = 0; s < 2; ++s) {
-    const int c0 = (s * 4 + kq) * 16;  // slot order of i8_shifted_slot
-    ar[s] = v4i{0, 0, 0, 0};
-    as_[s] = v4i{0, 0, 0, 0};
-    if (BITS > 0) ar[s] = *reinterpret_cast<const v4i*>(dig_s + ((0 * 4 + a_query) * 4 + a_digit) * 128 + c0);
-    if (PROD) as_[s] = *reinterpret_cast<const v4i*>(dig_s + ((1 * 4 + a_query) * 4 + a_digit) * 128 + c0);
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int s = 0; s < 2; ++s) areg[j][s] = a_read(j, s);
   }
+  float r_inv = 0.f, base_r = 0.f, s_inv = 0.f, s_sum = 0.f;
   if (BITS > 0) {
     r_inv = scal_s[(0 * 4 + kq) * 4];
-    r_sum = scal_s[(0 * 4 + kq) * 4 + 1];
+    base_r = scal_s[(0 * 4 + kq) * 4 + 1];
   }
   if (PROD) {
     s_inv = scal_s[(1 * 4 + kq) * 4];
@@ -158,14 +161,9 @@ __device__ __forceinline__ void score128_body(const ScoreI8Args& a, unsigned cha
     return b;
   };
   auto digits_sum = [&](const v4i& acc) -> float {  // (D0 + 2^7 D1 + 2^14 D2 + 2^21 D3) / 128, D0 a multiple of 128
-    return (float)((acc[0] >> 7) + acc[1] + acc[2] * 128 + acc[3] * 16384);
+    return (float)((((acc[3] << 7) + acc[2]) << 7) + acc[1] + (acc[0] >> 7));
   };
 
-  // per-lane constants of the final combination
-  float cr[NM > 0 ? NM : 1];
-#pragma unroll
-  for (int m = 1; m <= NM; ++m) cr[m - 1] = a.coef[m] * r_inv;
-  const float base_r = a.coef[0] * r_sum;
   const float zs = 2.f * s_inv;
 
   // ---- 6. tiles ------------------------------------------------------------------------------
@@ -210,10 +208,14 @@ __device__ __forceinline__ void score128_body(const ScoreI8Args& a, unsigned cha
     }
     if (PROD) b[j] = expand16(wz[t & 3], s);
   };
-  auto mfmas = [&](int s, const v4i (&b)[NTA], v4i (&c)[NTA]) {
+  // all masked sums of the rotated query go to accumulator 0, the sketch's to the last one
+  constexpr int NACC = (BITS > 0 ? 1 : 0) + (PROD ? 1 : 0);
+  auto mfmas = [&](int s, const v4i (&b)[NTA], v4i (&c)[NACC]) {
 #pragma unroll
-    for (int j = 0; j < NT; ++j)
-      c[j] = __builtin_amdgcn_mfma_i32_16x16x64_i8((PROD && j == NT - 1) ? as_[s] : ar[s], b[j], c[j], 0, 0, 0);
+    for (int j = 0; j < NT; ++j) {
+      const int to = (PROD && j == NT - 1) ? NACC - 1 : 0;
+      c[to] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A_REGS ? areg[A_REGS ? j : 0][s] : a_read(j, s), b[j], c[to], 0, 0, 0);
+    }
   };
   // with few masked sums per tile the operands of the next tile are looked up while this
   // tile's MFMAs run; with many there are no registers for that
@@ -221,15 +223,11 @@ __device__ __forceinline__ void score128_body(const ScoreI8Args& a, unsigned cha
   auto run_tiles = [&](auto full_c) {
     constexpr bool FULL = decltype(full_c)::value;
     v4i bop[PIPE ? 2 : 1][2][NTA];
-    v4i acc[2][NTA];
+    v4i acc[2][NACC];
     auto finish = [&](int t) {
-      const v4i(&c)[NTA] = acc[t & 1];
-      float total = base_r;
-      int j = 0;
-#pragma unroll
-      for (int m = 1; m <= NM; ++m)
-        if (i8_term(m)) total = fmaf(cr[m - 1], digits_sum(c[j++]), total);
-      if (PROD) total = fmaf(a.kappa * wkg[t & 3], fmaf(zs, digits_sum(c[NT - 1]), -s_sum), total);
+      const v4i(&c)[NACC] = acc[t & 1];
+      float total = BITS > 0 ? fmaf(r_inv, digits_sum(c[0]), base_r) : 0.f;
+      if (PROD) total = fmaf(a.kappa * wkg[t & 3], fmaf(zs, digits_sum(c[NACC - 1]), -s_sum), total);
       total *= wnu[t & 3];
       sink(t, total, FULL || wave_key0 + t * 16 + col < a.n);
     };
@@ -255,7 +253,7 @@ __device__ __forceinline__ void score128_body(const ScoreI8Args& a, unsigned cha
           fetch(t + 2);
         }
 #pragma unroll
-        for (int j = 0; j < NTA; ++j) acc[t & 1][j] = v4i{0, 0, 0, 0};
+        for (int j = 0; j < NACC; ++j) acc[t & 1][j] = v4i{0, 0, 0, 0};
         if (PIPE) {
           if (t + 1 < TILES) {
             lookups(t + 1, 0, bop[(t + 1) & 1][0]);

@@ -136,4 +136,88 @@ struct I8Prep {
   }
 };
 
+__device__ __forceinline__ float wave_sum_f(float v) {
+  v += __int_as_float(dpp_move<0xB1>(__float_as_int(v)));
+  v += __int_as_float(dpp_move<0x4E>(__float_as_int(v)));
+  v += __int_as_float(dpp_move<0x141>(__float_as_int(v)));
+  v += __int_as_float(dpp_move<0x140>(__float_as_int(v)));
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0)) + __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16)) +
+         __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32)) + __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+}
+
+// Digit images for the d = 128 single-kernel path, one per masked sum, so that all the masked sums of the
+// rotated query share ONE accumulator: term t (the t-th plane subset of odd size, factor coef[m]) is the image of
+// Q = round(coef[m] y 2^s), s the power of two with max |coef| max |y| 2^s <= 2^19, in the shifted form of
+// I8Prep::digitise<true>; the sketch term (index 2^(BITS-1)) is that of S q as before.  Wavefront w takes
+// (matrix w / 4, query w % 4).
+//   dig_s[term][query][digit][slot]; scal_s[matrix][query][0: 2^-s, 1: matrix 0: coef[0] sum_j y_j, matrix 1:
+//   2^-s sum_j Q_j]
+__host__ __device__ constexpr int i8_terms(int bits, bool prod) { return (bits > 0 ? 1 << (bits - 1) : 0) + (prod ? 1 : 0); }
+
+template <int BITS, bool PROD>
+__device__ __forceinline__ void i8_digitise_terms(const ScoreI8Args& a, int q0, int wave, int lane, const float* part_s,
+                                                  signed char* dig_s, float* scal_s) {
+  constexpr int NM = (1 << BITS) - 1;
+  constexpr int NTM = BITS > 0 ? 1 << (BITS - 1) : 0;
+  const int m = wave >> 2, qi = wave & 3;
+  if (!(m == 0 ? BITS > 0 : PROD)) return;
+  const bool live = q0 + qi < a.q_per_group;
+  float y[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int c = lane + 64 * u;
+    y[u] = live ? part_s[((m * 2 + 0) * 4 + qi) * 128 + c] + part_s[((m * 2 + 1) * 4 + qi) * 128 + c] : 0.f;
+  }
+  auto put = [&](int term, int u, int Q) {  // four balanced base-128 digits of the shifted value
+    const int c = lane + 64 * u, k = c & 7;
+    const int Qs = k == 7 ? -Q : Q << (7 - k);
+    const int d0 = ((Qs + 64) & 127) - 64;
+    const int Q1 = (Qs - d0) >> 7;
+    const int d1 = ((Q1 + 64) & 127) - 64;
+    const int Q2 = (Q1 - d1) >> 7;
+    const int d2 = ((Q2 + 64) & 127) - 64;
+    const int d3 = (Q2 - d2) >> 7;
+    signed char* o = dig_s + (term * 4 + qi) * 4 * 128 + i8_shifted_slot(c);
+    o[0] = (signed char)d0;
+    o[128] = (signed char)d1;
+    o[256] = (signed char)d2;
+    o[384] = (signed char)d3;
+  };
+  float cmax = 1.f;
+  if (m == 0) {
+    cmax = 0.f;
+#pragma unroll
+    for (int v = 1; v <= NM; ++v)
+      if (i8_term(v)) cmax = fmaxf(cmax, fabsf(a.coef[v]));
+  }
+  const float mx = wave_max(fmaxf(fabsf(y[0]), fabsf(y[1]))) * cmax;
+  int e = 0;
+  if (mx > 0.f) (void)frexpf(mx, &e);  // mx = f * 2^e, f in [0.5, 1): |Q| <= 2^19
+  const float sc = ldexpf(1.f, 19 - e), inv = ldexpf(1.f, e - 19);
+  if (m == 1) {
+    const int Q0 = __float2int_rn(y[0] * sc), Q1 = __float2int_rn(y[1] * sc);
+    const int tot = wave_sum(Q0 + Q1);
+    put(NTM, 0, Q0);
+    put(NTM, 1, Q1);
+    if (lane == 0) {
+      scal_s[(4 + qi) * 4 + 0] = inv;
+      scal_s[(4 + qi) * 4 + 1] = (float)tot * inv;
+    }
+  } else {
+    int term = 0;
+#pragma unroll
+    for (int v = 1; v <= NM; ++v) {
+      if (!i8_term(v)) continue;
+      put(term, 0, __float2int_rn(a.coef[v] * y[0] * sc));
+      put(term, 1, __float2int_rn(a.coef[v] * y[1] * sc));
+      ++term;
+    }
+    const float ysum = wave_sum_f(y[0] + y[1]);
+    if (lane == 0) {
+      scal_s[qi * 4 + 0] = inv;
+      scal_s[qi * 4 + 1] = a.coef[0] * ysum;
+    }
+  }
+}
+
 }  // namespace tq
