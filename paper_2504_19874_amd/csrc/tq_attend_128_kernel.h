@@ -168,7 +168,7 @@ __global__ __launch_bounds__(512) void attend128_kernel(const ScoreI8Args ka, co
   for (int t = 0; t < 16; ++t) lg[t] = -INFINITY;
   if (FUSED) {
     auto sink = [&](int t, float score, bool key_live) { lg[t] = key_live ? scale2 * score : -INFINITY; };
-    score128_body<KB, KPROD>(ka, dyn_s, sink);
+    score128_body<KB, KPROD, TILES_128, SCORE128_ROUND_TILES, SCORE128_ROUNDS_AHEAD>(ka, dyn_s, sink);
   } else {
     const int64_t qrow = (int64_t)group * a.q_per_group + (q0 + kc < a.q_per_group ? q0 + kc : q0);
     const float* srow = a.scores + qrow * a.lds + wave_key0 + col;

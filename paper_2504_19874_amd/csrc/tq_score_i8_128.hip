@@ -16,7 +16,7 @@ __global__ __launch_bounds__(512) void score_i8_128_kernel(const ScoreI8Args a) 
   auto sink = [&](int t, float score, bool key_live) {
     if (out_live && key_live) out0[t * 16] = score;
   };
-  score128_body<BITS, PROD, TILES>(a, dyn_s, sink);
+  score128_body<BITS, PROD, TILES, SCORE128_ROUND_TILES, SCORE128_ROUNDS_AHEAD>(a, dyn_s, sink);
 }
 
 template <int BITS, bool PROD, int TILES>
