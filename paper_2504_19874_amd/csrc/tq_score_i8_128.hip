@@ -4,7 +4,7 @@
 
 namespace tq {
 
-template <int BITS, bool PROD, int TILES>
+template <int BITS, bool PROD, int TILES, int RTP = SCORE128_ROUND_TILES, int INFLIGHT = SCORE128_ROUNDS_AHEAD>
 __global__ __launch_bounds__(512) void score_i8_128_kernel(const ScoreI8Args a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char dyn_s[];
   const int lane = threadIdx.x & 63;
@@ -16,18 +16,18 @@ __global__ __launch_bounds__(512) void score_i8_128_kernel(const ScoreI8Args a) 
   auto sink = [&](int t, float score, bool key_live) {
     if (out_live && key_live) out0[t * 16] = score;
   };
-  score128_body<BITS, PROD, TILES, SCORE128_ROUND_TILES, SCORE128_ROUNDS_AHEAD>(a, dyn_s, sink);
+  score128_body<BITS, PROD, TILES, RTP, INFLIGHT>(a, dyn_s, sink);
 }
 
-template <int BITS, bool PROD, int TILES>
+template <int BITS, bool PROD, int TILES, int RTP = SCORE128_ROUND_TILES, int INFLIGHT = SCORE128_ROUNDS_AHEAD>
 static hipError_t launch_tiles(const ScoreI8Args& a, int n_groups, hipStream_t s) {
   constexpr int lds = score128_lds(BITS);
   static_assert(lds <= 160 * 1024, "LDS budget");
   const int64_t per_wg = 8 * 16 * TILES;
   const dim3 grid((unsigned)((a.n + per_wg - 1) / per_wg), n_groups, (a.q_per_group + 3) / 4);
   static LdsLimit lds_limit;  // per instantiation: the limit is raised once per device
-  if (const hipError_t e = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&score_i8_128_kernel<BITS, PROD, TILES>), lds); e != hipSuccess) return e;
-  hipLaunchKernelGGL((score_i8_128_kernel<BITS, PROD, TILES>), grid, dim3(512), lds, s, a);
+  if (const hipError_t e = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&score_i8_128_kernel<BITS, PROD, TILES, RTP, INFLIGHT>), lds); e != hipSuccess) return e;
+  hipLaunchKernelGGL((score_i8_128_kernel<BITS, PROD, TILES, RTP, INFLIGHT>), grid, dim3(512), lds, s, a);
   return hipGetLastError();
 }
 

@@ -40,7 +40,8 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // The codes of a wavefront are asked for a few rounds ahead of their use rather than all at once: rounds of 4 tiles
 // (64 keys, 3.5 KB at 2 + 1 bits), two in flight.  8 x 65536 keys, 4 queries each, same box: 12.8 us against 13.4
 // with everything requested up front (rounds of 8 tiles: 13.4; rounds of 4, three in flight: 13.4; rounds of 8,
-// one in flight: 13.1).
+// one in flight: 13.1; on another box 12.5 against rounds of 2 tiles with 2 / 3 / 4 / 6 in flight: 13.0 / 12.7 /
+// 12.9 / 13.7, and rounds of one tile with 5 / 8 in flight: 13.7 / 14.3).
 constexpr int SCORE128_ROUND_TILES = 4, SCORE128_ROUNDS_AHEAD = 2;
 constexpr int TILES_128 = 16;  // tiles per wavefront (the default; 8 or 4 where that would leave compute units idle)
 // tiles staged in LDS at a time
@@ -64,9 +65,12 @@ __device__ __forceinline__ void score128_body(const ScoreI8Args& a, unsigned cha
   constexpr int ROUNDS = TILES / RT;
   constexpr int NM = (1 << BITS) - 1;
   constexpr int NW = BITS > 0 ? BITS : 1;
-  constexpr int NI = ROWS * 16 * BITS / 1024;  // 1 KB loads per round: plane words
-  constexpr int NQ = PROD ? ROWS * 16 / 1024 : 0;  // sign words
-  constexpr int NR = ROWS / 64;                // row-per-lane loads per round: gamma, norm
+  // loads per round; where a round's share of an array is not a whole number of them, the lanes past its end
+  // repeat its last piece (same address, same value, in memory and in LDS)
+  constexpr int PI = ROWS * BITS;                  // 16-byte pieces of plane words per round
+  constexpr int NI = (PI + 63) / 64;               // 1 KB loads per round: plane words
+  constexpr int NQ = PROD ? (ROWS + 63) / 64 : 0;  // sign words, a 16-byte piece per row
+  constexpr int NR = (ROWS + 63) / 64;             // row-per-lane loads per round: gamma, norm
   constexpr int IDX_OFF = 0, QJL_OFF = ROWS * 16 * BITS, GAM_OFF = QJL_OFF + ROWS * 16, NRM_OFF = GAM_OFF + ROWS * 4;
   constexpr int NT = (BITS > 0 ? (1 << (BITS > 0 ? BITS - 1 : 0)) : 0) + (PROD ? 1 : 0);  // masked sums per tile
   constexpr int NTA = NT > 0 ? NT : 1;
@@ -100,23 +104,27 @@ __device__ __forceinline__ void score128_body(const ScoreI8Args& a, unsigned cha
   const u32x4* const idx16 = reinterpret_cast<const u32x4*>(a.idx);
   const u32x4* const qjl16 = reinterpret_cast<const u32x4*>(a.qjl);
   const int64_t idx_last = a.total_rows * BITS - 1, qjl_last = a.total_rows - 1;  // last 16-byte piece
+  auto in_round = [&](int i, int count) {  // piece i * 64 + lane of a round's `count` pieces, the last one repeated
+    const int p = i * 64 + lane;
+    return count % 64 == 0 ? p : (p < count ? p : count - 1);
+  };
   auto issue_round = [&](int r) {
     const int64_t row0 = wrow0 + r * ROWS;
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-      int64_t piece = row0 * BITS + i * 64 + lane;
+      int64_t piece = row0 * BITS + in_round(i, PI);
       if (!full) piece = piece < idx_last ? piece : idx_last;
       ci[r][i] = idx16[piece];
     }
 #pragma unroll
     for (int i = 0; i < NQ; ++i) {
-      int64_t piece = row0 + i * 64 + lane;
+      int64_t piece = row0 + in_round(i, ROWS);
       if (!full) piece = piece < qjl_last ? piece : qjl_last;
       cq[r][i] = qjl16[piece];
     }
 #pragma unroll
     for (int i = 0; i < NR; ++i) {
-      int64_t row = row0 + i * 64 + lane;
+      int64_t row = row0 + in_round(i, ROWS);
       if (!full) row = row < a.total_rows - 1 ? row : a.total_rows - 1;
       cg[r][i] = PROD ? a.gamma[row] : 0.f;
       cn[r][i] = a.norm != nullptr ? a.norm[row] : 1.f;
@@ -183,13 +191,13 @@ __device__ __forceinline__ void score128_body(const ScoreI8Args& a, unsigned cha
   float wkg[4], wnu[4];
   auto put_round = [&](int r) {
 #pragma unroll
-    for (int i = 0; i < NI; ++i) *reinterpret_cast<u32x4*>(stage + IDX_OFF + (i * 64 + lane) * 16) = ci[r][i];
+    for (int i = 0; i < NI; ++i) *reinterpret_cast<u32x4*>(stage + IDX_OFF + in_round(i, PI) * 16) = ci[r][i];
 #pragma unroll
-    for (int i = 0; i < NQ; ++i) *reinterpret_cast<u32x4*>(stage + QJL_OFF + (i * 64 + lane) * 16) = cq[r][i];
+    for (int i = 0; i < NQ; ++i) *reinterpret_cast<u32x4*>(stage + QJL_OFF + in_round(i, ROWS) * 16) = cq[r][i];
 #pragma unroll
     for (int i = 0; i < NR; ++i) {
-      if (PROD) *reinterpret_cast<float*>(stage + GAM_OFF + (i * 64 + lane) * 4) = cg[r][i];
-      *reinterpret_cast<float*>(stage + NRM_OFF + (i * 64 + lane) * 4) = cn[r][i];
+      if (PROD) *reinterpret_cast<float*>(stage + GAM_OFF + in_round(i, ROWS) * 4) = cg[r][i];
+      *reinterpret_cast<float*>(stage + NRM_OFF + in_round(i, ROWS) * 4) = cn[r][i];
     }
   };
   auto fetch = [&](int t) {
