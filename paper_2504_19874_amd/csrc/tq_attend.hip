@@ -127,6 +127,20 @@ __global__ __launch_bounds__(256) void attend_combine_kernel(const float* part, 
   const int stride = attend_part_stride(d);
   const float* p = part + (int64_t)blockIdx.x * nchunks * stride;
   const int jmax = S != nullptr ? 2 * d : d;
+  // d = 128: this thread's 64 + 64 matrix entries of the last step (thread = coordinate k and half of the j range)
+  // are asked for before the chunks are joined, so the call has two dependent round trips to memory, not six
+  const bool early = d == 128;
+  float wp[64], ws[64];
+  if (early) {
+    const float* Pk = Pi + (tid >> 7) * 64 * 128 + (tid & 127);
+#pragma unroll
+    for (int u = 0; u < 64; ++u) wp[u] = Pk[u * 128];
+    if (S != nullptr) {
+      const float* Sk = S + (tid >> 7) * 64 * 128 + (tid & 127);
+#pragma unroll
+      for (int u = 0; u < 64; ++u) ws[u] = Sk[u * 128];
+    }
+  }
   if (nchunks == 0) {
     for (int j = tid; j < jmax; j += 256) y_s[j] = 0.f;  // no keys at all: the output is zero
   } else if (nchunks <= 32) {
@@ -191,7 +205,15 @@ __global__ __launch_bounds__(256) void attend_combine_kernel(const float* part, 
   for (int k0 = 0; k0 < d; k0 += 256) {  // one trip unless d > 256
     const int item = k0 + tid, k = parts > 1 ? tid % d : item, part_ = parts > 1 ? tid / d : 0;
     float o = 0.f, oz = 0.f;
-    if (k < d && part_ < parts) {
+    if (early) {
+      const int j0 = part_ * span;  // 64 * (tid / 128)
+#pragma unroll
+      for (int u = 0; u < 64; ++u) o = fmaf(wp[u], y_s[j0 + u], o);
+      if (S != nullptr) {
+#pragma unroll
+        for (int u = 0; u < 64; ++u) oz = fmaf(ws[u], y_s[d + j0 + u], oz);
+      }
+    } else if (k < d && part_ < parts) {
       const int j0 = part_ * span;
       o = strided_dot(Pi + k, d, y_s, j0, span);
       if (S != nullptr) oz = strided_dot(S + k, d, y_s + d, j0, span);
