@@ -97,9 +97,64 @@ __global__ __launch_bounds__(512 / VT) void dequant128_bf3_kernel(const Dq128Arg
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
   // ---- Pi^T (and S^T), two leading pieces each -----------------------------------------------------
+  {
+    int m = 0;
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      if (s == 0 ? !PI : !PROD) continue;
+      if (a.image != nullptr) {
+        // a straight copy of the matrix's 64 KB, 16 bytes per thread and step
+        const u32x4* const src = a.image + s * (2 * MAT_ELEMS * 2 / 16);
+        u32x4* const dst = reinterpret_cast<u32x4*>(lds_s + m * 2 * MAT_ELEMS);
+        u32x4 v[4096 / NT];
+#pragma unroll
+        for (int i = 0; i < 4096 / NT; ++i) v[i] = src[i * NT + tid];
+#pragma unroll
+        for (int i = 0; i < 4096 / NT; ++i) dst[i * NT + tid] = v[i];
+      } else {
+        if (tid < 256) dq128_split_matrix(s == 0 ? a.PiT : a.ST, lds_s + m * 2 * MAT_ELEMS, tid);
+      }
+      ++m;
+    }
+    if (TABLE && tid < (MIXED ? 32 : 16)) {  // MIXED: entries 16.. are instance hi's
+      uint32_t p1, p2, p3;
+      split3(tid < 16 ? a.cb.c[tid] : a.cb_hi.c[tid - 16], p1, p2, p3);
+      table_s[tid] = p1 | (p2 << 16);
+    }
+  }
+  __syncthreads();
+
   const int vi = lane & 31, jg = lane >> 5;  // A: vector within the tile, which 8 of the 16 values of j
+  uint32_t c1p[2] = {0u, 0u};  // 1 bit: the two pieces of c_1, each twice in a word
+  if (BITS == 1) {
+    uint32_t p1, p2, p3;
+    split3(a.cb.c[1], p1, p2, p3);
+    c1p[0] = p1 * 0x00010001u;
+    c1p[1] = p2 * 0x00010001u;
+  }
   const int64_t blocks = (a.n + 255) / 256;
   const int gs = MIXED ? a.gs_hi : 0;
+  // MIXED: which of this lane's four output columns belong to instance hi.  The matrices are block diagonal up to a
+  // permutation of the channels, so column k belongs to hi exactly when row k of the transposed matrix has an
+  // entry among the first 32 gs_hi.
+  uint32_t hi_cols = 0u;
+  if (MIXED) {
+    // thread t scans one half of the range for row t / 2; the flags go through LDS (behind the table)
+    uint32_t* const flag_s = table_s + 32;
+    if (tid < 256) {
+      const float* row = (PROD ? a.ST : a.PiT) + (tid >> 1) * 128;
+      bool any = false;
+      for (int j = 16 * gs * (tid & 1); j < 16 * gs * ((tid & 1) + 1); j += 4) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(row + j);
+        any = any || v[0] != 0.f || v[1] != 0.f || v[2] != 0.f || v[3] != 0.f;
+      }
+      flag_s[tid] = any ? 1u : 0u;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) hi_cols |= (flag_s[2 * (4 * vi + ct)] | flag_s[2 * (4 * vi + ct) + 1]) << ct;
+  }
+
   // MIXED: nu / kg are instance lo's, nuh / kgh instance hi's
   uint32_t w[VT][4][NB], z[VT][4], wn[VT][4][NB], zn[VT][4];
   float nu[VT], kg[VT], nun[VT], kgn[VT], nuh[VT] = {}, kgh[VT] = {}, nuhn[VT] = {}, kghn[VT] = {};
@@ -132,64 +187,6 @@ __global__ __launch_bounds__(512 / VT) void dequant128_bf3_kernel(const Dq128Arg
     }
   };
 
-  // the first block's codes are asked for before the parameters: they are what the first MFMA waits for last
-  load_code(blockIdx.x);
-
-  {
-    int m = 0;
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-      if (s == 0 ? !PI : !PROD) continue;
-      if (a.image != nullptr) {
-        // a straight copy of the matrix's 64 KB, 16 bytes per thread and step
-        const u32x4* const src = a.image + s * (2 * MAT_ELEMS * 2 / 16);
-        u32x4* const dst = reinterpret_cast<u32x4*>(lds_s + m * 2 * MAT_ELEMS);
-        u32x4 v[4096 / NT];
-#pragma unroll
-        for (int i = 0; i < 4096 / NT; ++i) v[i] = src[i * NT + tid];
-#pragma unroll
-        for (int i = 0; i < 4096 / NT; ++i) dst[i * NT + tid] = v[i];
-      } else {
-        if (tid < 256) dq128_split_matrix(s == 0 ? a.PiT : a.ST, lds_s + m * 2 * MAT_ELEMS, tid);
-      }
-      ++m;
-    }
-    if (TABLE && tid < (MIXED ? 32 : 16)) {  // MIXED: entries 16.. are instance hi's
-      uint32_t p1, p2, p3;
-      split3(tid < 16 ? a.cb.c[tid] : a.cb_hi.c[tid - 16], p1, p2, p3);
-      table_s[tid] = p1 | (p2 << 16);
-    }
-  }
-  __syncthreads();
-
-  uint32_t c1p[2] = {0u, 0u};  // 1 bit: the two pieces of c_1, each twice in a word
-  if (BITS == 1) {
-    uint32_t p1, p2, p3;
-    split3(a.cb.c[1], p1, p2, p3);
-    c1p[0] = p1 * 0x00010001u;
-    c1p[1] = p2 * 0x00010001u;
-  }
-  // MIXED: which of this lane's four output columns belong to instance hi.  The matrices are block diagonal up to a
-  // permutation of the channels, so column k belongs to hi exactly when row k of the transposed matrix has an
-  // entry among the first 32 gs_hi.
-  uint32_t hi_cols = 0u;
-  if (MIXED) {
-    // thread t scans one half of the range for row t / 2; the flags go through LDS (behind the table)
-    uint32_t* const flag_s = table_s + 32;
-    if (tid < 256) {
-      const float* row = (PROD ? a.ST : a.PiT) + (tid >> 1) * 128;
-      bool any = false;
-      for (int j = 16 * gs * (tid & 1); j < 16 * gs * ((tid & 1) + 1); j += 4) {
-        const f32x4 v = *reinterpret_cast<const f32x4*>(row + j);
-        any = any || v[0] != 0.f || v[1] != 0.f || v[2] != 0.f || v[3] != 0.f;
-      }
-      flag_s[tid] = any ? 1u : 0u;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int ct = 0; ct < 4; ++ct) hi_cols |= (flag_s[2 * (4 * vi + ct)] | flag_s[2 * (4 * vi + ct) + 1]) << ct;
-  }
-
   // B operand r of a step: tile r % 4 (columns k = 4 l + tile), then piece 1 before piece 0 of Pi^T, then of S^T
   auto b_piece = [&](int s, int r) {
     const int ct = r & 3, q = r >> 2;  // q: (matrix, piece) in the order (0, 1), (0, 0), (1, 1), (1, 0)
@@ -197,6 +194,7 @@ __global__ __launch_bounds__(512 / VT) void dequant128_bf3_kernel(const Dq128Arg
     return *reinterpret_cast<const bf16x8*>(lds_s + (m * 2 + pc) * MAT_ELEMS + lds_at(4 * vi + ct, 16 * s + 8 * jg));
   };
 
+  load_code(blockIdx.x);
   for (int64_t blk = blockIdx.x; blk < blocks; blk += gridDim.x) {
 #pragma unroll
     for (int mt = 0; mt < VT; ++mt) {

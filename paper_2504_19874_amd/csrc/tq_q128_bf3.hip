@@ -130,7 +130,25 @@ __global__ __launch_bounds__(512 / VT) void quant128_bf3_kernel(const Q128Args a
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int vi = lane & 31, g = lane >> 5;
 
-  // the first block's vectors are asked for before the parameters: they are what the first MFMA waits for last
+  if (a.image != nullptr) {
+    // a straight copy, 16 bytes per thread and step: 24 steps for Pi, 16 for S Pi^T
+    constexpr int STEPS = (PI_ELEMS + (PROD ? W_ELEMS : 0)) * 2 / (NT * 16);
+    u32x4* const dst = reinterpret_cast<u32x4*>(lds_s);
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      u32x4 v[STEPS / 2];
+#pragma unroll
+      for (int i = 0; i < STEPS / 2; ++i) v[i] = a.image[(half * (STEPS / 2) + i) * NT + tid];
+#pragma unroll
+      for (int i = 0; i < STEPS / 2; ++i) dst[(half * (STEPS / 2) + i) * NT + tid] = v[i];
+    }
+  } else if (tid < 256) {
+    q128_split_matrices(a.Pi, PROD ? a.SPiT : nullptr, lds_s, tid);
+  }
+  __syncthreads();
+
+  const int64_t blocks = (a.n + 255) / 256;
+  const bool normalise = !MIXED && a.norm != nullptr;
   constexpr int ESZ = F32 ? 4 : 2;
   u32x4 xop[VT][8];                   // the B operands of stage 1 (F32: piece 1 of x)
   u32x4 xop2[F32 ? VT : 1][8];        // F32: piece 2
@@ -154,25 +172,6 @@ __global__ __launch_bounds__(512 / VT) void quant128_bf3_kernel(const Q128Args a
     for (int s = 0; s < 8; ++s) load_x(src, nt, s);
   }
 
-  if (a.image != nullptr) {
-    // a straight copy, 16 bytes per thread and step: 24 steps for Pi, 16 for S Pi^T
-    constexpr int STEPS = (PI_ELEMS + (PROD ? W_ELEMS : 0)) * 2 / (NT * 16);
-    u32x4* const dst = reinterpret_cast<u32x4*>(lds_s);
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      u32x4 v[STEPS / 2];
-#pragma unroll
-      for (int i = 0; i < STEPS / 2; ++i) v[i] = a.image[(half * (STEPS / 2) + i) * NT + tid];
-#pragma unroll
-      for (int i = 0; i < STEPS / 2; ++i) dst[(half * (STEPS / 2) + i) * NT + tid] = v[i];
-    }
-  } else if (tid < 256) {
-    q128_split_matrices(a.Pi, PROD ? a.SPiT : nullptr, lds_s, tid);
-  }
-  __syncthreads();
-
-  const int64_t blocks = (a.n + 255) / 256;
-  const bool normalise = !MIXED && a.norm != nullptr;
   for (int64_t blk = blockIdx.x; blk < blocks; blk += gridDim.x) {
     // ---- norms: a lane and its partner in the other half-wave hold one vector between them --------------
     float nu[VT], inv[VT];
