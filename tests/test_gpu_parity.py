@@ -420,6 +420,11 @@ def test_dequantize(d, bits_mse, n, prod, with_norm):
     # d = 256..512: preparation kernel + int8 scoring kernel
     (256, 2, True, 2, 4, 1500, 0), (256, 4, True, 1, 3, 600, 0), (512, 1, False, 1, 8, 700, 0),
     (384, 3, True, 1, 2, 300, 0), (512, 4, False, 1, 4, 1100, 5),
+    # d = 128 single-kernel path with a grid that fills the chip: 2048 keys per workgroup (33 groups x 5
+    # workgroups; codes requested rounds ahead) and 1024 (20 groups), every bit width, ragged last workgroup
+    (128, 1, False, 33, 4, 8292, 0), (128, 0, True, 33, 3, 8292, 0), (128, 3, False, 33, 4, 8200, 5),
+    (128, 4, True, 33, 2, 8292, 0), (128, 2, False, 33, 4, 8292, 0), (128, 1, True, 20, 4, 8292, 0),
+    (128, 3, True, 20, 4, 8292, 0), (128, 4, False, 20, 4, 8292, 3),
 ])
 def test_score_and_topk(d, bits_mse, prod, n_groups, qpg, npg, topk):
     p, Pi, S, c32, t32 = setup(d, bits_mse, prod)
