@@ -136,6 +136,24 @@ struct I8Prep {
   }
 };
 
+// Four balanced base-128 digits of fixed-point value Q of coordinate c, in the shifted form (Q 2^(7 - c % 8), negated
+// where c % 8 = 7) at slot i8_shifted_slot(c) of image `term`, query qi: dig_s[term][qi][digit][slot].
+__device__ __forceinline__ void i8_put_shifted(signed char* dig_s, int term, int qi, int c, int Q) {
+  const int k = c & 7;
+  const int Qs = k == 7 ? -Q : Q << (7 - k);
+  const int d0 = ((Qs + 64) & 127) - 64;
+  const int Q1 = (Qs - d0) >> 7;
+  const int d1 = ((Q1 + 64) & 127) - 64;
+  const int Q2 = (Q1 - d1) >> 7;
+  const int d2 = ((Q2 + 64) & 127) - 64;
+  const int d3 = (Q2 - d2) >> 7;
+  signed char* o = dig_s + (term * 4 + qi) * 4 * 128 + i8_shifted_slot(c);
+  o[0] = (signed char)d0;
+  o[128] = (signed char)d1;
+  o[256] = (signed char)d2;
+  o[384] = (signed char)d3;
+}
+
 __device__ __forceinline__ float wave_sum_f(float v) {
   v += __int_as_float(dpp_move<0xB1>(__float_as_int(v)));
   v += __int_as_float(dpp_move<0x4E>(__float_as_int(v)));
@@ -168,21 +186,7 @@ __device__ __forceinline__ void i8_digitise_terms(const ScoreI8Args& a, int q0, 
     const int c = lane + 64 * u;
     y[u] = live ? part_s[((m * 2 + 0) * 4 + qi) * 128 + c] + part_s[((m * 2 + 1) * 4 + qi) * 128 + c] : 0.f;
   }
-  auto put = [&](int term, int u, int Q) {  // four balanced base-128 digits of the shifted value
-    const int c = lane + 64 * u, k = c & 7;
-    const int Qs = k == 7 ? -Q : Q << (7 - k);
-    const int d0 = ((Qs + 64) & 127) - 64;
-    const int Q1 = (Qs - d0) >> 7;
-    const int d1 = ((Q1 + 64) & 127) - 64;
-    const int Q2 = (Q1 - d1) >> 7;
-    const int d2 = ((Q2 + 64) & 127) - 64;
-    const int d3 = (Q2 - d2) >> 7;
-    signed char* o = dig_s + (term * 4 + qi) * 4 * 128 + i8_shifted_slot(c);
-    o[0] = (signed char)d0;
-    o[128] = (signed char)d1;
-    o[256] = (signed char)d2;
-    o[384] = (signed char)d3;
-  };
+  auto put = [&](int term, int u, int Q) { i8_put_shifted(dig_s, term, qi, lane + 64 * u, Q); };
   float cmax = 1.f;
   if (m == 0) {
     cmax = 0.f;
