@@ -317,8 +317,8 @@ tq_status tq_score(const tq_params* p, const float* q, int64_t ldq, int32_t n_gr
  * (16 MiB) on every GPU the library has run on, held until the process ends.
  * The call allocates and frees nothing and calls no allocating routine.
  *   TQ_ERR_WORKSPACE  the call needs more than the array holds:
- *                     tq_workspace_bytes(p, 0, nq, 0), plus nq*(n_per_group+3)*4
- *                     bytes when scores == NULL, must not exceed it.
+ *                     tq_score_workspace_bytes() of the same arguments must
+ *                     not exceed tq_score_static_scratch_bytes().
  * All calls on one GPU share that GPU's array: calls that overlap in time on
  * one GPU (two streams, two threads) race on it; serialise them.  Nothing in
  * the array has to survive between calls and nothing is read before the call
