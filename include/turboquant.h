@@ -60,7 +60,10 @@
  *     1e-5 band around a cell boundary that every path is allowed.  The sketch,
  *     of which only signs are kept, from two pieces of the residual and two of
  *     S Pi^T (a sign can differ from the exact one only where
- *     |<S_j, r>| < 1e-6 |S_j| |r|);
+ *     |<S_j, r>| < 1e-6 |S_j| |r|).  tq_quantize_prod of fp32 vectors keeps the
+ *     rotation on the fp32 instructions where the residual is so small that the
+ *     part of x left out would show in gamma (4-bit MSE stage up to d = 416,
+ *     3 bits up to d = 96, 2 bits at d = 32);
  *   dequantise, large batches: two pieces of each factor (error
  *     below 4e-5 of a coordinate's typical size), at every d;
  *   scoring: two bf16 pieces of each factor (many queries; scores within

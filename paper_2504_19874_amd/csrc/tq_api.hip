@@ -86,6 +86,17 @@ const void* dequant_image(const tq_params* p) {
 
 tq_status from_hip(hipError_t e) { return e == hipSuccess ? TQ_OK : TQ_ERR_HIP; }
 
+// Quant_prod of fp32 vectors on the bf16 matrix cores keeps the two leading pieces of x: the rotated vector is off
+// by up to 2^-17 |x| in norm (2^-18.6 in the root mean square).  The indices do not notice, but the residual norm
+// gamma and the sketch signs of Alg. 2 are judged relative to gamma, which shrinks with the bit-width of the MSE
+// stage (sqrt(D_mse) of Theorem 1: 1, 0.60, 0.34, 0.18, 0.097 for 0..4 bits); the error's component along the
+// residual is about 2^-18.6 / sqrt(d).  Where that exceeds about 1e-6 gamma the rotation stays on fp32 MFMA
+// (d = 128: the 4-bit MSE stage; 3 bits below d = 128; 2 bits at d = 32).
+bool two_piece_x_serves_prod(int d, int bits_mse) {
+  static const float gamma_typ[5] = {1.f, 0.60f, 0.342f, 0.183f, 0.097f};
+  return gamma_typ[bits_mse] * std::sqrt((float)d) >= 2.f;
+}
+
 struct Workspace {
   char* base;
   size_t size;
@@ -142,7 +153,8 @@ tq_status quantize_common(const tq_params* p, const void* x, int32_t dtype, int6
   }
 
   // head dimension 128, a large batch of bf16 or fp32 vectors: the contractions on the bf16 matrix cores
-  if (d == 128 && n >= kBf3QuantRows && !fp32_mfma_only(p) && quant128_bf3_applicable(p->bits_mse, prod, dtype == TQ_F32, x, ldx, make_codebook(p), nullptr) &&
+  if (d == 128 && n >= kBf3QuantRows && !fp32_mfma_only(p) && !(prod && dtype == TQ_F32 && !two_piece_x_serves_prod(d, p->bits_mse)) &&
+      quant128_bf3_applicable(p->bits_mse, prod, dtype == TQ_F32, x, ldx, make_codebook(p), nullptr) &&
       (p->bits_mse == 0 || aligned16(idx)) && (!prod || aligned16(qjl)))
     return from_hip(launch_quant128_bf3(p->bits_mse, prod, dtype == TQ_F32, x, ldx, n, p->Pi, prod ? p->SPiT : nullptr, idx, qjl, gamma,
                                         norm, make_codebook(p), 0, make_codebook(p), quant_image(p), stream));
@@ -165,7 +177,8 @@ tq_status quantize_common(const tq_params* p, const void* x, int32_t dtype, int6
   a.normalise = norm != nullptr;
   a.kappa = kappa_of(d);
   a.cb = make_codebook(p);
-  a.pieces = !fp32_mfma_only(p);
+  const bool pieces = !fp32_mfma_only(p);
+  a.pieces = pieces && !(prod && dtype == TQ_F32 && !two_piece_x_serves_prod(d, p->bits_mse));
   a.W1_image = a.pieces ? p->images : nullptr;
   const NKind nk = dtype == TQ_F32 ? N_F32 : N_BF16;
 
@@ -213,8 +226,8 @@ tq_status quantize_common(const tq_params* p, const void* x, int32_t dtype, int6
     a2.n = rows;
     a2.rownorm_out = gamma + r0;
     a2.words_out = qjl + r0 * (d / 32);
-    a2.pieces = a.pieces;
-    a2.W1_image = a.pieces && p->images != nullptr ? static_cast<const char*>(p->images) + gemm_image_bytes(d, d, 3) : nullptr;
+    a2.pieces = pieces;  // the residual's own two pieces leave out 2^-17 of the residual: relative to gamma as it must be
+    a2.W1_image = pieces && p->images != nullptr ? static_cast<const char*>(p->images) + gemm_image_bytes(d, d, 3) : nullptr;
     e = launch_gemm(N_F32, E_SIGN, 0, a2, 1, stream);
     if (e != hipSuccess) return TQ_ERR_HIP;
   }

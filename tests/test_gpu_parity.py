@@ -195,6 +195,10 @@ def _check_prod(p, Pi, S, c32, t32, x_or, normalise, idx, qjl, gamma, norm):
     (128, 4, 33333, "bf16"), (128, 2, 8193, "bf16"), (128, 1, 8449, "bf16"),
     # large batches of fp32 vectors: the same kernel on two pieces of x (five piece products)
     (128, 2, 33001, "f32"), (128, 3, 66000, "f32"), (128, 4, 9000, "unit"),
+    # fp32 vectors and a small residual (gamma ~ 0.1 at 4 bits): two pieces of x would move gamma by more than
+    # 1e-5 of itself, so these stay on the fp32 instructions
+    (128, 4, 37512, "unit"), (128, 4, 25848, "f32"), (96, 4, 573, "unit"), (64, 4, 471, "f32"), (32, 4, 444, "f32"),
+    (32, 3, 500, "f32"), (64, 3, 700, "unit"),
 ])
 def test_quantize_prod(d, bits_mse, n, kind):
     p, Pi, S, c32, t32 = setup(d, bits_mse, True)
