@@ -179,7 +179,10 @@ tq_status quantize_common(const tq_params* p, const void* x, int32_t dtype, int6
   a.cb = make_codebook(p);
   const bool pieces = !fp32_mfma_only(p);
   a.pieces = pieces && !(prod && dtype == TQ_F32 && !two_piece_x_serves_prod(d, p->bits_mse));
-  a.W1_image = a.pieces ? p->images : nullptr;
+  // (d = 128 arrives here with bf16 rows that are only 8-byte aligned; params.images then holds the images of the
+  // d = 128 kernels, which are not this kernel's)
+  const char* const gemm_images = d != 128 ? static_cast<const char*>(p->images) : nullptr;
+  a.W1_image = a.pieces ? gemm_images : nullptr;
   const NKind nk = dtype == TQ_F32 ? N_F32 : N_BF16;
 
   if (!prod) {
@@ -227,7 +230,7 @@ tq_status quantize_common(const tq_params* p, const void* x, int32_t dtype, int6
     a2.rownorm_out = gamma + r0;
     a2.words_out = qjl + r0 * (d / 32);
     a2.pieces = pieces;  // the residual's own two pieces leave out 2^-17 of the residual: relative to gamma as it must be
-    a2.W1_image = pieces && p->images != nullptr ? static_cast<const char*>(p->images) + gemm_image_bytes(d, d, 3) : nullptr;
+    a2.W1_image = pieces && gemm_images != nullptr ? gemm_images + gemm_image_bytes(d, d, 3) : nullptr;
     e = launch_gemm(N_F32, E_SIGN, 0, a2, 1, stream);
     if (e != hipSuccess) return TQ_ERR_HIP;
   }

@@ -336,6 +336,32 @@ def test_large_batches_respect_row_strides_and_leave_the_tail_alone():
     assert bool((out[:n, d:] == -3.0).all()) and bool((out[n:] == -3.0).all()), "bytes outside the rows were written"
 
 
+@pytest.mark.parametrize("bits_mse,prod,n,offset,pad", [(2, True, 300, 4, 0), (3, False, 9000, 0, 4), (1, True, 8300, 12, 4),
+                                                        (4, False, 40, 4, 8)])
+def test_bf16_rows_that_are_only_8_byte_aligned(bits_mse, prod, n, offset, pad):
+    """bf16 rows need 8-byte alignment only; at d = 128 such rows take the kernel written for every dimension,
+    which must not be handed the parameter images of the d = 128 kernels (they are built by default)."""
+    d = 128
+    p, Pi, S, c32, t32 = setup(d, bits_mse, prod)
+    assert p.images is not None
+    x_or, x_dev, normalise = _quant_inputs(n, d, "bf16", 3 * n + bits_mse)
+    ld = d + pad
+    buf = torch.zeros(offset + n * ld + 8, dtype=torch.bfloat16, device=DEV)
+    xv = buf[offset: offset + n * ld].view(n, ld)[:, :d]
+    xv.copy_(x_dev)
+    assert xv.data_ptr() % 16 != 0 or (ld * 2) % 16 != 0
+    if prod:
+        out = _run_prod(p, xv, n, normalise)
+        _check_prod(p, Pi, S, c32, t32, x_or, normalise, *out)
+    else:
+        idx_or, nu_or, y_or = o.quant_mse(x_or, Pi, t32, normalise)
+        idx = torch.zeros((n, p.idx_words), dtype=torch.int32, device=DEV)
+        norm = torch.zeros(n, dtype=torch.float32, device=DEV)
+        tq.tq_quantize_mse(p, xv, idx, norm)
+        P.check_indices(o.unpack_planes(words(idx), bits_mse, d), idx_or, y_or, t32)
+        P.check_close(norm.cpu().numpy(), nu_or, 0.0, "norm", rel=2e-6)
+
+
 def test_quantize_is_deterministic_and_respects_row_stride():
     d, n = 128, 1000
     p, Pi, S, c32, t32 = setup(d, 2, True)
