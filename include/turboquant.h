@@ -14,7 +14,10 @@
  *    device work is enqueued on `stream` (a hipStream_t passed as void*; NULL
  *    is the default stream).
  *  - Matrices are row-major fp32.  Vectors are rows.  d must be a multiple of
- *    32 (GPU entry points), bits_mse in [0, 4].
+ *    32 (GPU entry points), bits_mse in [0, 4].  Row strides of vectors,
+ *    queries and dequantised / attention output (ldx, ldq, ldo) are at most
+ *    2^22 elements, else TQ_ERR_UNSUPPORTED; the row stride of a score matrix
+ *    (lds) is not limited.
  *  - Every failure is a return code; nothing is launched when arguments are
  *    rejected.
  *

@@ -29,6 +29,9 @@ int device_cu_count() {
 namespace {
 
 constexpr int64_t kChunkRows = 65536;  // rows per pass when a residual workspace is needed
+// Row strides of vectors (x, q) and of dequantised output: the kernels address a tile's rows with 32-bit byte
+// offsets from a 64-bit tile base (up to 256 rows of ld * 4 bytes)
+constexpr int64_t kMaxRowStride = int64_t(1) << 22;
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -115,6 +118,7 @@ tq_status quantize_common(const tq_params* p, const void* x, int32_t dtype, int6
   tq_status st = check_params(p, true);
   if (st != TQ_OK) return st;
   if (n < 0 || ldx < p->d) return TQ_ERR_INVALID_ARG;
+  if (ldx > kMaxRowStride) return TQ_ERR_UNSUPPORTED;
   if (dtype != TQ_F32 && dtype != TQ_BF16) return TQ_ERR_INVALID_ARG;
   if (n == 0) return TQ_OK;
   if (x == nullptr || p->Pi == nullptr) return TQ_ERR_INVALID_ARG;
@@ -351,6 +355,7 @@ tq_status tq_dequantize(const tq_params* p, const uint32_t* idx, const uint32_t*
   tq_status st = check_params(p, true);
   if (st != TQ_OK) return st;
   if (n < 0 || ldo < p->d) return TQ_ERR_INVALID_ARG;
+  if (ldo > kMaxRowStride) return TQ_ERR_UNSUPPORTED;
   if (n == 0) return TQ_OK;
   const bool prod = qjl != nullptr;
   if (x_out == nullptr || p->PiT == nullptr || (p->bits_mse > 0 && idx == nullptr)) return TQ_ERR_INVALID_ARG;
@@ -481,7 +486,8 @@ tq_status score_impl(const tq_params* p, Workspace ws, const float* q, int64_t l
   if (st != TQ_OK) return st;
   if (n_groups < 0 || q_per_group < 0 || n_per_group < 0 || ldq < p->d || topk < 0) return TQ_ERR_INVALID_ARG;
   // groups and blocks of four queries are grid dimensions of the few-query kernels
-  if (topk > 64 || n_per_group > 0x7fffffff || n_groups > 65535 || q_per_group > 4 * 65535) return TQ_ERR_UNSUPPORTED;
+  if (topk > 64 || n_per_group > 0x7fffffff || n_groups > 65535 || q_per_group > 4 * 65535 || ldq > kMaxRowStride)
+    return TQ_ERR_UNSUPPORTED;
   const int64_t nq = (int64_t)n_groups * q_per_group;
   if (nq == 0) return TQ_OK;
   const bool prod = qjl != nullptr;
@@ -720,7 +726,8 @@ tq_status tq_attend_cache(const tq_params* pk, const tq_params* pv, const float*
   if (out == nullptr || pv->Pi == nullptr || (v_prod && (v_gamma == nullptr || pv->S == nullptr)))
     return TQ_ERR_INVALID_ARG;
   if (n_per_group > 0 && (v_norm == nullptr || (pv->bits_mse > 0 && v_idx == nullptr))) return TQ_ERR_INVALID_ARG;
-  if (pv->d > 4096 || n_groups > 65535 || q_per_group > 4 * 65535) return TQ_ERR_UNSUPPORTED;
+  if (pv->d > 4096 || n_groups > 65535 || q_per_group > 4 * 65535 || ldq > kMaxRowStride || ldo > kMaxRowStride)
+    return TQ_ERR_UNSUPPORTED;
   hipStream_t s = static_cast<hipStream_t>(stream);
 
   const AttendPlan pl = attend_plan(pk, pv, v_prod, nq, n_per_group);

@@ -130,6 +130,11 @@ int main() {
   EXPECT(tq_quantize_mse(&p, nullptr, TQ_F32, -1, 128, nullptr, nullptr, nullptr) == TQ_ERR_INVALID_ARG);
   EXPECT(tq_quantize_mse(&p, nullptr, 7, 4, 128, nullptr, nullptr, nullptr) == TQ_ERR_INVALID_ARG);
   EXPECT(tq_quantize_mse(&p, nullptr, TQ_F32, 0, 128, nullptr, nullptr, nullptr) == TQ_OK);
+  // row strides beyond what the kernels' 32-bit row offsets cover
+  EXPECT(tq_quantize_mse(&p, nullptr, TQ_F32, 4, (int64_t(1) << 22) + 4, nullptr, nullptr, nullptr) == TQ_ERR_UNSUPPORTED);
+  EXPECT(tq_dequantize(&p, nullptr, nullptr, nullptr, nullptr, 1, nullptr, (int64_t(1) << 22) + 4, nullptr) == TQ_ERR_UNSUPPORTED);
+  EXPECT(tq_score(&p, nullptr, (int64_t(1) << 22) + 4, 1, 1, nullptr, nullptr, nullptr, nullptr, 10, nullptr, 10, 0, nullptr, nullptr,
+                  nullptr) == TQ_ERR_UNSUPPORTED);
   EXPECT(tq_quantize_prod(&p, nullptr, TQ_BF16, 4, 64, nullptr, nullptr, nullptr, nullptr, nullptr) == TQ_ERR_INVALID_ARG);
   EXPECT(tq_append(&p, nullptr, TQ_F32, 4, 128, nullptr, nullptr, nullptr, nullptr, -1, 1, nullptr) == TQ_ERR_INVALID_ARG);
   EXPECT(tq_append(&p, nullptr, TQ_F32, 1 << 20, 128, nullptr, nullptr, nullptr, nullptr, 0, 1, nullptr) == TQ_ERR_UNSUPPORTED);
@@ -171,6 +176,11 @@ int main() {
   EXPECT(tq_quantize_mse(&p, nullptr, TQ_F32, 4, 128, nullptr, nullptr, nullptr) == TQ_ERR_UNSUPPORTED);
   p.bits_mse_hi = 3;
   EXPECT(tq_quantize_mse(&p, nullptr, TQ_F32, 0, 128, nullptr, nullptr, nullptr) == TQ_OK);
+  // row strides beyond what the kernels' 32-bit row offsets cover
+  EXPECT(tq_quantize_mse(&p, nullptr, TQ_F32, 4, (int64_t(1) << 22) + 4, nullptr, nullptr, nullptr) == TQ_ERR_UNSUPPORTED);
+  EXPECT(tq_dequantize(&p, nullptr, nullptr, nullptr, nullptr, 1, nullptr, (int64_t(1) << 22) + 4, nullptr) == TQ_ERR_UNSUPPORTED);
+  EXPECT(tq_score(&p, nullptr, (int64_t(1) << 22) + 4, 1, 1, nullptr, nullptr, nullptr, nullptr, 10, nullptr, 10, 0, nullptr, nullptr,
+                  nullptr) == TQ_ERR_UNSUPPORTED);
   EXPECT(tq_stage_pack(&p, nullptr, 4, nullptr, nullptr) == TQ_ERR_UNSUPPORTED);
   for (int s = 0; s <= 5; ++s) EXPECT(tq_status_string((tq_status)s) != nullptr);
   std::puts("argument checks ok");
