@@ -325,6 +325,8 @@ size_t tq_workspace_bytes(const tq_params* p, int64_t n, int64_t nq, int32_t top
   bytes += 2 * round_up((size_t)nq * d * sizeof(float), 256);      // rotated / sketched queries
   bytes += round_up(score_i8_workspace_bytes(p->d, nq), 256);      // or their int8 digit images
   if (topk > 0) bytes += round_up((size_t)nq * (size_t)(n + 3) * sizeof(float), 256);  // scores when not returned
+  // partial top-k lists of a few long rows: at most 4096 (score, index) pairs for each of at most 128 rows
+  if (topk > 0) bytes += 2 * round_up((size_t)(nq < 128 ? nq : 128) * 4096 * sizeof(float), 256);
   return bytes + 256;
 }
 
@@ -423,7 +425,8 @@ struct ScorePlan {
   int64_t ld_scores;    // row stride of a score matrix in scratch memory
   size_t scores_bytes;  // that matrix: only when scores == NULL and top-k is not taken inside the scoring kernel
   int ranges;           // > 0: top-k inside the scoring kernel, this many partial lists per query
-  size_t part_bytes;    // one array [nq][ranges][topk] (values; indices take the same again)
+  int topk_chunks;      // > 0: top-k over a score matrix of few long rows, this many chunks (partial lists) per row
+  size_t part_bytes;    // one array [nq][ranges or topk_chunks][topk] (values; indices take the same again)
   bool prod;
   size_t total() const {
     const size_t a = 256;
@@ -433,7 +436,22 @@ struct ScorePlan {
   }
 };
 
+ScorePlan plan_route(const tq_params* p, bool prod, int n_groups, int q_per_group, int64_t n_per_group, bool scores_given,
+                     int topk, bool codes_aligned);
+
 ScorePlan plan_score(const tq_params* p, bool prod, int n_groups, int q_per_group, int64_t n_per_group, bool scores_given,
+                     int topk, bool codes_aligned) {
+  ScorePlan pl = plan_route(p, prod, n_groups, q_per_group, n_per_group, scores_given, topk, codes_aligned);
+  // top-k over a score matrix: a few long rows are cut into chunks so that the selection fills the chip
+  if (topk > 0 && pl.ranges == 0) {
+    const int64_t nq = (int64_t)n_groups * q_per_group;
+    pl.topk_chunks = topk_chunks(nq, n_per_group, topk);
+    if (pl.topk_chunks > 0) pl.part_bytes = (size_t)nq * pl.topk_chunks * topk * sizeof(float);
+  }
+  return pl;
+}
+
+ScorePlan plan_route(const tq_params* p, bool prod, int n_groups, int q_per_group, int64_t n_per_group, bool scores_given,
                      int topk, bool codes_aligned) {
   ScorePlan pl;
   std::memset(&pl, 0, sizeof(pl));
@@ -450,7 +468,10 @@ ScorePlan plan_score(const tq_params* p, bool prod, int n_groups, int q_per_grou
   }
   // few queries per code; with a short code list also a few more (every block of 4 queries re-reads the
   // codes, which costs less than the launches of the contraction path while the list is short)
-  if ((q_per_group <= 32 || (q_per_group <= 64 && n_per_group <= 16384)) && score_i8_applicable(p->bits_mse, d, make_codebook(p))) {
+  // (beyond 512 coordinates that kernel takes one launch per 512 and a matrix-vector kernel rotates the queries:
+  // up to 16 queries per group, where the dense contraction would run on tiles that are mostly padding)
+  if ((d <= 512 ? (q_per_group <= 32 || (q_per_group <= 64 && n_per_group <= 16384)) : (q_per_group <= 16 && nq <= 64)) &&
+      score_i8_applicable(p->bits_mse, d, make_codebook(p))) {
     pl.route = ScorePlan::R_I8;
     pl.img_bytes = score_i8_workspace_bytes(d, nq);
     pl.scores_bytes = scratch_scores;
@@ -598,6 +619,11 @@ tq_status score_impl(const tq_params* p, Workspace ws, const float* q, int64_t l
       a.cb = make_codebook(p);
       if (launch_gemm(N_CODE, E_STORE_N, p->bits_mse, a, n_groups, s) != hipSuccess) return TQ_ERR_HIP;
     }
+  }
+  if (topk > 0 && pl.topk_chunks > 0) {
+    if (launch_topk(scores, nq, n_per_group, ld_scores, topk, nullptr, nullptr, s, pl.topk_chunks, part_val, part_idx) != hipSuccess)
+      return TQ_ERR_HIP;
+    return from_hip(launch_topk_merge(part_val, part_idx, nq, pl.topk_chunks, topk, topk_idx, topk_val, s));
   }
   if (topk > 0) return from_hip(launch_topk(scores, nq, n_per_group, ld_scores, topk, topk_idx, topk_val, s));
   return TQ_OK;

@@ -181,8 +181,12 @@ hipError_t launch_stage_unpack(const Codebook& cb, int d, const uint32_t* idx, i
 // out[c][r] = in[r][c] for a d x d matrix
 hipError_t launch_transpose(int d, const float* in, float* out, hipStream_t stream);
 
-// per-row top-k of scores[rows][ld] over the first n columns
+// per-row top-k of scores[rows][ld] over the first n columns.  A few long rows are cut into chunks (topk_chunks > 0):
+// the call then writes the k best pairs of every chunk to part_val / part_idx [rows][chunks][k] and
+// launch_topk_merge(part_val, part_idx, rows, chunks, k, ...) joins them.
+int topk_chunks(int64_t rows, int64_t n, int k);
 hipError_t launch_topk(const float* scores, int64_t rows, int64_t n, int64_t ld, int k,
-                       int32_t* out_idx, float* out_val, hipStream_t stream);
+                       int32_t* out_idx, float* out_val, hipStream_t stream, int chunks = 0, float* part_val = nullptr,
+                       int32_t* part_idx = nullptr);
 
 }  // namespace tq

@@ -575,7 +575,7 @@ __global__ __launch_bounds__(512) void score_bf3_kernel(const Bf3Args a) {
 __global__ __launch_bounds__(64) void topk_merge_kernel(const float* __restrict__ part_val, const int32_t* __restrict__ part_idx,
                                                         const int cands, const int k, int32_t* __restrict__ out_idx,
                                                         float* __restrict__ out_val) {
-  constexpr int PER = 64;  // pairs per lane: ranges <= 256 and k <= KL give at most 4096 pairs
+  constexpr int PER = 64;  // pairs per lane: at most 4096 pairs per row (checked at launch)
   const int lane = threadIdx.x;
   const int64_t row = blockIdx.x;
   const float NEG = -__builtin_inff();
@@ -698,7 +698,7 @@ int score_bf3_topk_ranges(int bits, bool prod, int64_t n, int n_groups, int q_pe
 hipError_t launch_topk_merge(const float* part_val, const int32_t* part_idx, int64_t rows, int ranges, int k,
                              int32_t* out_idx, float* out_val, hipStream_t s) {
   if (rows == 0) return hipSuccess;
-  if (ranges < 1 || ranges > 256 || k < 1 || k > KL || rows > 0x7fffffff) return hipErrorInvalidValue;
+  if (ranges < 1 || k < 1 || k > 64 || (int64_t)ranges * k > 4096 || rows > 0x7fffffff) return hipErrorInvalidValue;
   hipLaunchKernelGGL(topk_merge_kernel, dim3((unsigned)rows), dim3(64), 0, s, part_val, part_idx, ranges * k, k, out_idx, out_val);
   return hipGetLastError();
 }

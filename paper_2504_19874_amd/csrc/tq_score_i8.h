@@ -1,6 +1,6 @@
 // Shared by the two few-query scoring kernels on the integer matrix cores
-// (tq_score_i8.hip: any d that is a multiple of 128 up to 512, queries prepared by a
-// kernel of their own; tq_score_i8_128.hip: d = 128 with everything in one kernel).
+// (tq_score_i8.hip: any d that is a multiple of 128 up to 4096, queries prepared by a
+// kernel of their own, 512 coordinates per launch; tq_score_i8_128.hip: d = 128 with everything in one kernel).
 #pragma once
 #include "tq_internal.h"
 
@@ -36,9 +36,16 @@ struct ScoreI8Args {
   int q_per_group;
   float kappa;
   float coef[16];  // coef[0]: factor of sum_j qr_j; coef[S]: factor of M_S (odd |S| only)
+  // tq_score_i8.hip only: one launch covers k-steps [k0, k0 + ks_slice) of the d / 64; a launch with `accumulate`
+  // adds its masked sums to the scores an earlier launch left (the terms that do not depend on the code are
+  // added by the launch without it)
+  int k0;
+  int ks_slice;
+  int accumulate;
 };
 
-constexpr int I8_MAX_KS = 8;  // d <= 512
+constexpr int I8_MAX_KS = 8;     // k-steps of one launch: 512 coordinates (the A operands of a launch sit in registers)
+constexpr int I8_MAX_D = 4096;   // longer vectors take several launches, each adding its 512 coordinates
 // the terms the kernel evaluates: plane subsets of odd size (symmetric codebook)
 __host__ __device__ constexpr bool i8_term(int m) { return __builtin_popcount((unsigned)m) & 1; }
 // tiles of 16 keys per wavefront: as many as the register file holds code words for

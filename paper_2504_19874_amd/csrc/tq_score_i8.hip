@@ -164,6 +164,64 @@ __global__ __launch_bounds__(512) void prep_i8_kernel(const int d, const int d_h
   }
 }
 
+// The same images for vectors of more than 512 coordinates, from queries that a matrix-vector kernel has already
+// rotated (y0 = Pi q, y1 = S q, [nq][d] fp32): scale, sums and digit bytes as prep_i8_kernel writes them.
+// grid (nq, 1 or 2), 512 threads.
+__global__ __launch_bounds__(512) void digitise_i8_kernel(const int d, const float* __restrict__ y0,
+                                                          const float* __restrict__ y1, uint4* __restrict__ img,
+                                                          float* __restrict__ scal) {
+  __shared__ float red_mx[8];
+  __shared__ long long red_tot[8];
+  const int tid = threadIdx.x;
+  const int64_t q = blockIdx.x;
+  const int mat = blockIdx.y;
+  const float* const y = (mat == 0 ? y0 : y1) + q * d;
+  float mx = 0.f;
+  for (int k = tid; k < d; k += 512) mx = fmaxf(mx, fabsf(y[k]));
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+  if ((tid & 63) == 0) red_mx[tid >> 6] = mx;
+  __syncthreads();
+  mx = red_mx[0];
+#pragma unroll
+  for (int w = 1; w < 8; ++w) mx = fmaxf(mx, red_mx[w]);
+  int e = 0;
+  if (mx > 0.f) (void)frexpf(mx, &e);  // mx = f * 2^e, f in [0.5, 1): |Q| < 2^20 below
+  const float sc = ldexpf(1.f, 19 - e);
+  long long tot = 0;  // up to 4096 values below 2^20
+  for (int k = tid; k < d; k += 512) tot += __float2int_rn(y[k] * sc);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) tot += __shfl_xor(tot, off);
+  if ((tid & 63) == 0) red_tot[tid >> 6] = tot;
+  __syncthreads();
+  if (tid == 0) {
+    long long t = 0;
+#pragma unroll
+    for (int w = 0; w < 8; ++w) t += red_tot[w];
+    scal[(q * 2 + mat) * 4 + 0] = ldexpf(1.f, e - 19);
+    scal[(q * 2 + mat) * 4 + 1] = (float)t * ldexpf(1.f, e - 19);
+    scal[(q * 2 + mat) * 4 + 2] = 0.f;  // one instance
+    scal[(q * 2 + mat) * 4 + 3] = (float)t * ldexpf(1.f, e - 19);
+  }
+  const int ks = d >> 6;
+  for (int u = tid; u < ks * 16; u += 512) {  // unit = (k-step s, digit dg, k-chunk kq)
+    const int kq = u & 3, dg = (u >> 2) & 3, s = u >> 4;
+    const int c0 = i8_coord0(s, kq);
+    uint32_t w[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      const int Q = __float2int_rn(y[c0 + k] * sc);
+      const int d0 = ((Q + 64) & 127) - 64;
+      const int Q1 = (Q - d0) >> 7;
+      const int d1 = ((Q1 + 64) & 127) - 64;
+      const int d2 = (Q1 - d1) >> 7;
+      const int dig = dg == 0 ? d0 : dg == 1 ? d1 : dg == 2 ? d2 : 0;
+      w[k >> 2] |= ((uint32_t)dig & 0xFFu) << (8 * (k & 3));
+    }
+    img[((q * 2 + mat) * ks + s) * 16 + dg * 4 + kq] = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+}
+
 // KSM: compile-time bound on the number of 64-coordinate k-steps (register arrays).
 // A wavefront owns i8_tiles() tiles of 16 keys and requests all their code words up front.
 template <int BITS, bool PROD, int KSM>
@@ -181,7 +239,8 @@ __global__ __launch_bounds__(512) void score_i8_kernel(const ScoreI8Args a) {
   const int group = blockIdx.y;
   const int q0 = blockIdx.z * 4;
   const int d = a.d;
-  const int ks = d >> 6;  // k-steps of 64 coordinates (even)
+  const int ks_all = d >> 6;   // k-steps of 64 coordinates of the whole vector (even): the stride of the images
+  const int ks = a.ks_slice;   // k-steps of this launch (even, at most KSM), starting at a.k0
   const int gi = ks >> 1;
 
   // lane = row + 16*kq of the A operand, row = 4*query + digit
@@ -200,8 +259,8 @@ __global__ __launch_bounds__(512) void score_i8_kernel(const ScoreI8Args a) {
   for (int s = 0; s < KSM; ++s) {
     uint4 r = make_uint4(0, 0, 0, 0), z = make_uint4(0, 0, 0, 0);
     if (s < ks) {
-      if (BITS > 0) r = a.img[((qrow * 2 + 0) * ks + s) * 16 + a_digit * 4 + kq];
-      if (PROD) z = a.img[((qrow * 2 + 1) * ks + s) * 16 + a_digit * 4 + kq];
+      if (BITS > 0) r = a.img[((qrow * 2 + 0) * ks_all + a.k0 + s) * 16 + a_digit * 4 + kq];
+      if (PROD) z = a.img[((qrow * 2 + 1) * ks_all + a.k0 + s) * 16 + a_digit * 4 + kq];
     }
     ar[s] = v4i{(int)r.x, (int)r.y, (int)r.z, (int)r.w};
     as_[s] = v4i{(int)z.x, (int)z.y, (int)z.z, (int)z.w};
@@ -229,8 +288,9 @@ __global__ __launch_bounds__(512) void score_i8_kernel(const ScoreI8Args a) {
     // one base address per array and lane; without clamping the tiles are constant offsets from it
     const int64_t key0 = wave_key0 + col;
     const int64_t row0 = gbase + (key0 < a.n ? key0 : a.n - 1);
-    const uint32_t* const pi0 = a.idx + row0 * words_per_row + kq * BITS;
-    const uint32_t* const pz0 = a.qjl + (PROD ? row0 * groups + kq : 0);
+    const int g0 = 2 * a.k0;  // first plane-word group of this launch (a k-step is two groups)
+    const uint32_t* const pi0 = a.idx + row0 * words_per_row + (g0 + kq) * BITS;
+    const uint32_t* const pz0 = a.qjl + (PROD ? row0 * groups + g0 + kq : 0);
     const float* const pg0 = a.gamma + (PROD ? row0 : 0);
     const float* const pn0 = a.norm + (a.norm != nullptr ? row0 : 0);
 #pragma unroll
@@ -288,8 +348,10 @@ __global__ __launch_bounds__(512) void score_i8_kernel(const ScoreI8Args a) {
   float cr[NM > 0 ? NM : 1];
 #pragma unroll
   for (int m = 1; m <= NM; ++m) cr[m - 1] = a.coef[m] * r_inv;
-  const float base_r = a.coef[0] * r_sum;
+  const bool add = a.accumulate != 0;  // uniform: the code-independent terms came with an earlier launch
+  const float base_r = add ? 0.f : a.coef[0] * r_sum;
   const float zs = 2.f * s_inv;
+  if (add) s_sum = 0.f;
   float* const out0 = a.scores + ((int64_t)group * a.q_per_group + q0 + kq) * a.lds + wave_key0 + col;
 
   // The tiles run as a three-stage software pipeline, written out in source order: while the
@@ -342,7 +404,7 @@ __global__ __launch_bounds__(512) void score_i8_kernel(const ScoreI8Args a) {
         if (i8_term(m)) total = fmaf(cr[m - 1], digits_sum(c[j++]), total);
       if (PROD) total = fmaf(a.kappa * kg[t], fmaf(zs, digits_sum(c[NT - 1]), -s_sum), total);
       total *= nu[t];
-      if (out_live && (FULL || wave_key0 + t * 16 + col < a.n)) out0[t * 16] = total;
+      if (out_live && (FULL || wave_key0 + t * 16 + col < a.n)) out0[t * 16] = add ? out0[t * 16] + total : total;
     };
     if (PIPE) {
       lookups(0, bop[0]);
@@ -399,7 +461,7 @@ static hipError_t launch_one(const ScoreI8Args& a, int n_groups, hipStream_t s) 
 
 template <int BITS, bool PROD>
 static hipError_t launch_ks(const ScoreI8Args& a, int n_groups, hipStream_t s) {
-  const int ks = a.d >> 6;
+  const int ks = a.ks_slice;
   if (ks <= 2) return launch_one<BITS, PROD, 2>(a, n_groups, s);
   if (ks <= 4) return launch_one<BITS, PROD, 4>(a, n_groups, s);
   return launch_one<BITS, PROD, 8>(a, n_groups, s);
@@ -410,8 +472,11 @@ static hipError_t launch_bits(const ScoreI8Args& a, bool prod, int n_groups, hip
   return prod ? launch_ks<BITS, true>(a, n_groups, s) : launch_ks<BITS, false>(a, n_groups, s);
 }
 
+// digit images and scalars of nq queries; beyond 512 coordinates also the rotated / sketched queries in fp32,
+// which a kernel of their own digitises
 size_t score_i8_workspace_bytes(int d, int64_t nq) {
-  return (size_t)nq * 2 * ((size_t)(d >> 6) * 256 + 16) + 512;
+  const size_t images = (size_t)nq * 2 * ((size_t)(d >> 6) * 256 + 16) + 512;
+  return d > 64 * I8_MAX_KS ? images + 2 * ((size_t)nq * d * sizeof(float) + 256) : images;
 }
 
 // Walsh coefficients of the centroid table over the bit planes of the index:
@@ -463,7 +528,7 @@ bool i8_coefficients(int bits, const Codebook& cb, float* coef) {
 }
 
 bool score_i8_applicable(int bits, int d, const Codebook& cb) {
-  if (bits < 0 || bits > 4 || d % 128 != 0 || d > 64 * I8_MAX_KS) return false;
+  if (bits < 0 || bits > 4 || d % 128 != 0 || d > I8_MAX_D) return false;
   double w[16];
   i8_walsh(bits, cb, w);
   for (int sset = 1; sset < (1 << bits); ++sset)
@@ -492,7 +557,7 @@ hipError_t launch_score_i8(int bits, bool prod, const float* Pi, const float* S,
                            const float* norm, float* scores, int64_t lds, int64_t n, int d, int n_groups,
                            int q_per_group, float kappa, const Codebook& cb, hipStream_t stream) {
   if (n_groups == 0 || q_per_group == 0) return hipSuccess;
-  if (bits < 0 || bits > 4 || d % 128 != 0 || d > 64 * I8_MAX_KS) return hipErrorInvalidValue;
+  if (bits < 0 || bits > 4 || d % 128 != 0 || d > I8_MAX_D) return hipErrorInvalidValue;
   const int64_t nq = (int64_t)n_groups * q_per_group;
   uint4* img = static_cast<uint4*>(workspace);
   float* scal = reinterpret_cast<float*>(static_cast<char*>(workspace) + (size_t)nq * 2 * (d >> 6) * 256);
@@ -500,6 +565,7 @@ hipError_t launch_score_i8(int bits, bool prod, const float* Pi, const float* S,
   ScoreI8Args a;
   a.img = img; a.scal = scal; a.PiT = PiT; a.ST = ST; a.x = q; a.ldx = ldq; a.idx = idx; a.qjl = qjl; a.gamma = gamma; a.norm = norm;
   a.scores = scores; a.lds = lds; a.n = n; a.total_rows = (int64_t)n_groups * n; a.group_stride = n; a.d = d; a.q_per_group = q_per_group; a.kappa = kappa;
+  a.k0 = 0; a.ks_slice = d >> 6; a.accumulate = 0;
   if (!i8_coefficients(bits, cb, a.coef)) return hipErrorInvalidValue;  // see score_i8_applicable
   // d = 128 with the transposed matrices at hand and 16-byte aligned codes: one kernel does it all
   const auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
@@ -507,22 +573,40 @@ hipError_t launch_score_i8(int bits, bool prod, const float* Pi, const float* S,
       (!prod || (ST != nullptr && al16(qjl))))
     return launch_score_i8_128(bits, prod, a, n_groups, stream);
   const dim3 pgrid((unsigned)nq, prod ? 2 : 1);
-  switch (d >> 7) {
-    case 1: hipLaunchKernelGGL(prep_i8_kernel<1>, pgrid, dim3(512), 0, stream, d, 0, Pi, S, q, ldq, img, scal); break;
-    case 2: hipLaunchKernelGGL(prep_i8_kernel<2>, pgrid, dim3(512), 0, stream, d, 0, Pi, S, q, ldq, img, scal); break;
-    case 3: hipLaunchKernelGGL(prep_i8_kernel<3>, pgrid, dim3(512), 0, stream, d, 0, Pi, S, q, ldq, img, scal); break;
-    default: hipLaunchKernelGGL(prep_i8_kernel<4>, pgrid, dim3(512), 0, stream, d, 0, Pi, S, q, ldq, img, scal); break;
+  if (d > 64 * I8_MAX_KS) {
+    // long vectors: the matrix-vector kernel rotates the queries into the workspace, then their digits are written
+    const size_t images = ((size_t)nq * 2 * ((size_t)(d >> 6) * 256 + 16) + 512 + 255) / 256 * 256;
+    float* const qr = reinterpret_cast<float*>(static_cast<char*>(workspace) + images);
+    float* const qs = reinterpret_cast<float*>(static_cast<char*>(workspace) + images + ((size_t)nq * d * sizeof(float) + 255) / 256 * 256);
+    if (const hipError_t e = launch_matvec_small(d, (int)nq, Pi, prod ? S : nullptr, q, ldq, qr, qs, stream); e != hipSuccess) return e;
+    hipLaunchKernelGGL(digitise_i8_kernel, pgrid, dim3(512), 0, stream, d, qr, qs, img, scal);
+  } else {
+    switch (d >> 7) {
+      case 1: hipLaunchKernelGGL(prep_i8_kernel<1>, pgrid, dim3(512), 0, stream, d, 0, Pi, S, q, ldq, img, scal); break;
+      case 2: hipLaunchKernelGGL(prep_i8_kernel<2>, pgrid, dim3(512), 0, stream, d, 0, Pi, S, q, ldq, img, scal); break;
+      case 3: hipLaunchKernelGGL(prep_i8_kernel<3>, pgrid, dim3(512), 0, stream, d, 0, Pi, S, q, ldq, img, scal); break;
+      default: hipLaunchKernelGGL(prep_i8_kernel<4>, pgrid, dim3(512), 0, stream, d, 0, Pi, S, q, ldq, img, scal); break;
+    }
   }
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  switch (bits) {
-    case 0: return launch_bits<0>(a, prod, n_groups, stream);
-    case 1: return launch_bits<1>(a, prod, n_groups, stream);
-    case 2: return launch_bits<2>(a, prod, n_groups, stream);
-    case 3: return launch_bits<3>(a, prod, n_groups, stream);
-    case 4: return launch_bits<4>(a, prod, n_groups, stream);
-    default: return hipErrorInvalidValue;
+  if (const hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+  // 512 coordinates per launch; the launches after the first add to the scores
+  const int ks_all = d >> 6;
+  for (int k0 = 0; k0 < ks_all; k0 += I8_MAX_KS) {
+    a.k0 = k0;
+    a.ks_slice = ks_all - k0 < I8_MAX_KS ? ks_all - k0 : I8_MAX_KS;
+    a.accumulate = k0 > 0;
+    hipError_t e;
+    switch (bits) {
+      case 0: e = launch_bits<0>(a, prod, n_groups, stream); break;
+      case 1: e = launch_bits<1>(a, prod, n_groups, stream); break;
+      case 2: e = launch_bits<2>(a, prod, n_groups, stream); break;
+      case 3: e = launch_bits<3>(a, prod, n_groups, stream); break;
+      case 4: e = launch_bits<4>(a, prod, n_groups, stream); break;
+      default: return hipErrorInvalidValue;
+    }
+    if (e != hipSuccess) return e;
   }
+  return hipSuccess;
 }
 
 }  // namespace tq

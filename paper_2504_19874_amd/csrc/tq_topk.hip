@@ -3,6 +3,9 @@
 // list of the k best (value, index) it has seen while striding over the row,
 // then the 256 lists are merged by k rounds of a workgroup-wide arg-max.
 // Order: larger score first; equal scores by lower index.
+// A few long rows (one query against a million codes) would leave the chip to
+// a few workgroups: such rows are cut into chunks, one workgroup per (row,
+// chunk) writes the chunk's k best pairs, and launch_topk_merge joins them.
 #include "tq_internal.h"
 
 namespace tq {
@@ -12,10 +15,10 @@ __device__ __forceinline__ bool better(float va, int ia, float vb, int ib) {
 }
 
 template <int KMAX>
-__global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ scores, const int64_t n,
+__global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ scores, const int64_t n_row,
                                                    const int64_t ld, const int k, const int vec4,
                                                    int32_t* __restrict__ out_idx,
-                                                   float* __restrict__ out_val) {
+                                                   float* __restrict__ out_val, const int64_t chunk_len) {
   extern __shared__ unsigned char smem_raw[];
   float* cand_v = reinterpret_cast<float*>(smem_raw);            // [256 * k]
   int* cand_i = reinterpret_cast<int*>(cand_v + 256 * k);        // [256 * k]
@@ -24,7 +27,12 @@ __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ sco
   __shared__ int red_slot[4];
 
   const int tid = threadIdx.x;
-  const float* row = scores + (int64_t)blockIdx.x * ld;
+  // chunk_len > 0: workgroup (row, chunk) takes columns [c0, c0 + chunk_len) of the row (chunk_len is a multiple of
+  // 4, so a chunk is as aligned as the row) and writes k (value, index) pairs, -inf / INT_MAX where it has fewer
+  const int64_t c0 = chunk_len > 0 ? (int64_t)blockIdx.y * chunk_len : 0;
+  const int64_t n = chunk_len > 0 ? (n_row - c0 < chunk_len ? n_row - c0 : chunk_len) : n_row;
+  const float* row = scores + (int64_t)blockIdx.x * ld + c0;
+  const int64_t out_row = chunk_len > 0 ? (int64_t)blockIdx.x * gridDim.y + blockIdx.y : blockIdx.x;
   const float NEG = -__builtin_inff();
 
   float bv[KMAX];
@@ -74,16 +82,16 @@ __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ sco
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         if (i0 + 256 * u >= n4) break;  // padding of the last round: no element, no index
-        const int id = (int)((i0 + 256 * u) << 2);
+        const int id = (int)(c0 + ((i0 + 256 * u) << 2));
         consider(v[u].x, id);
         consider(v[u].y, id + 1);
         consider(v[u].z, id + 2);
         consider(v[u].w, id + 3);
       }
     }
-    for (int64_t i = (n4 << 2) + tid; i < n; i += 256) consider(row[i], (int)i);
+    for (int64_t i = (n4 << 2) + tid; i < n; i += 256) consider(row[i], (int)(c0 + i));
   } else {
-    for (int64_t i = tid; i < n; i += 256) consider(row[i], (int)i);
+    for (int64_t i = tid; i < n; i += 256) consider(row[i], (int)(c0 + i));
   }
 #pragma unroll
   for (int j = 0; j < KMAX; ++j)
@@ -128,29 +136,49 @@ __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ sco
       }
     if (tid == fw) ++cursor;
     if (tid == 0) {
-      out_idx[(int64_t)blockIdx.x * k + r] = (fi == 0x7fffffff) ? -1 : fi;
-      if (out_val != nullptr) out_val[(int64_t)blockIdx.x * k + r] = fv;
+      out_idx[out_row * k + r] = (fi == 0x7fffffff && chunk_len == 0) ? -1 : fi;
+      if (out_val != nullptr) out_val[out_row * k + r] = fv;
     }
     __syncthreads();
   }
 }
 
+// Chunks per row when a call's rows are too few to fill the chip: 0 (one workgroup per row) unless the rows are
+// few and long; then chunks of at least 8192 scores, about four workgroups per compute unit in all, and no more
+// pairs per row than the joining kernel takes (4096).
+int topk_chunks(int64_t rows, int64_t n, int k) {
+  if (k < 1 || rows < 1 || rows > 128 || n < 65536) return 0;
+  int64_t c = (4 * (int64_t)device_cu_count() + rows - 1) / rows;
+  if (c > n / 8192) c = n / 8192;
+  if (c > 4096 / k) c = 4096 / k;
+  if (c > 65535) c = 65535;
+  return c >= 2 ? (int)c : 0;
+}
+
+// chunks == 0: the rows' k best straight to out_idx / out_val.  chunks > 0 (from topk_chunks): the k best of every
+// chunk to part_idx / part_val [rows][chunks][k], to be joined by launch_topk_merge.
 hipError_t launch_topk(const float* scores, int64_t rows, int64_t n, int64_t ld, int k,
-                       int32_t* out_idx, float* out_val, hipStream_t stream) {
+                       int32_t* out_idx, float* out_val, hipStream_t stream, int chunks, float* part_val,
+                       int32_t* part_idx) {
   if (rows == 0 || k == 0) return hipSuccess;
   if (k < 1 || k > 64 || rows > 0x7fffffff || n > 0x7fffffff) return hipErrorInvalidValue;
+  if (chunks > 0 && (part_val == nullptr || part_idx == nullptr || chunks > 65535)) return hipErrorInvalidValue;
   const size_t smem = (size_t)256 * k * 8;
   const int vec4 = (ld % 4 == 0) && ((reinterpret_cast<uintptr_t>(scores) & 15u) == 0);
+  const int64_t chunk_len = chunks > 0 ? ((n + chunks - 1) / chunks + 3) / 4 * 4 : 0;
+  const dim3 grid((unsigned)rows, chunks > 0 ? (unsigned)chunks : 1u);
+  if (chunks > 0) {
+    out_idx = part_idx;
+    out_val = part_val;
+  }
   if (k <= 16)
-    hipLaunchKernelGGL((topk_kernel<16>), dim3((unsigned)rows), dim3(256), smem, stream, scores, n, ld, k, vec4,
-                       out_idx, out_val);
+    hipLaunchKernelGGL((topk_kernel<16>), grid, dim3(256), smem, stream, scores, n, ld, k, vec4, out_idx, out_val, chunk_len);
   else {
     // more than 64 KB of dynamic LDS has to be allowed explicitly
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&topk_kernel<64>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((topk_kernel<64>), dim3((unsigned)rows), dim3(256), smem, stream, scores, n, ld, k, vec4,
-                       out_idx, out_val);
+    hipLaunchKernelGGL((topk_kernel<64>), grid, dim3(256), smem, stream, scores, n, ld, k, vec4, out_idx, out_val, chunk_len);
   }
   return hipGetLastError();
 }

@@ -455,6 +455,9 @@ def test_dequantize(d, bits_mse, n, prod, with_norm):
     (128, 1, False, 33, 4, 8292, 0), (128, 0, True, 33, 3, 8292, 0), (128, 3, False, 33, 4, 8200, 5),
     (128, 4, True, 33, 2, 8292, 0), (128, 2, False, 33, 4, 8292, 0), (128, 1, True, 20, 4, 8292, 0),
     (128, 3, True, 20, 4, 8292, 0), (128, 4, False, 20, 4, 8292, 3),
+    # few queries against long codes: the integer-matrix-core kernel, 512 coordinates per launch
+    (1536, 4, False, 1, 4, 2100, 10), (3072, 1, True, 1, 1, 700, 0), (1024, 2, True, 2, 5, 1500, 0), (640, 3, True, 1, 16, 900, 5),
+    (768, 0, True, 1, 3, 130, 0), (2048, 2, False, 3, 9, 257, 3), (1536, 3, True, 1, 13, 4100, 0),
 ])
 def test_score_and_topk(d, bits_mse, prod, n_groups, qpg, npg, topk):
     p, Pi, S, c32, t32 = setup(d, bits_mse, prod)
@@ -588,6 +591,19 @@ def test_topk_inside_the_scoring_kernel(d, bits_mse, prod, n_groups, qpg, npg, t
     _, ws = _topk_both_ways(p, q, n_groups, qpg, c, npg, topk)
     if topk <= 16 and npg >= 5000:
         assert ws < nq * npg  # far below a score matrix (4 bytes per pair)
+
+
+@pytest.mark.parametrize("d,bits_mse,prod,n_groups,qpg,npg,topk", [
+    (128, 2, True, 2, 4, 70001, 10), (1536, 4, False, 1, 1, 66000, 64), (128, 1, False, 3, 33, 131072, 5),
+    (256, 3, True, 1, 2, 65536, 1), (128, 4, False, 1, 128, 65537, 16),
+])
+def test_topk_over_a_few_long_rows(d, bits_mse, prod, n_groups, qpg, npg, topk):
+    """Few queries against many codes: the rows of the score matrix are cut into chunks, one workgroup per (row,
+    chunk), and the chunks' lists are joined; same answer as a stable sort of the scores the call wrote."""
+    p, Pi, S, c32, t32 = setup(d, bits_mse, prod)
+    c = _random_codes(p, d, bits_mse, prod, n_groups * npg, d + npg)
+    q = dev(W.gaussian_queries(n_groups * qpg, d, 3, unit=False))
+    _topk_both_ways(p, q, n_groups, qpg, c, npg, topk)
 
 
 def test_topk_inside_the_scoring_kernel_on_adversarial_orders():
