@@ -71,7 +71,8 @@
  *     below 4e-5 of a coordinate's typical size), at every d;
  *   scoring: two bf16 pieces of each factor (many queries; scores within
  *     3e-6 |q| norm of the exact ones) or int8 digits (few queries: up to 32
- *     per group at d <= 512, up to 16 per group and 64 in all at d <= 4096,
+ *     per group at d <= 1024, up to 16 per group at d <= 4096 (64 in all
+ *     beyond d = 512),
  *     d a multiple of 128, codebook symmetric about zero).
  * At d = 128, fp32 inputs and smaller batches run on the fp32 matrix
  * instructions.  All paths meet the same tolerances (indices equal to an fp32

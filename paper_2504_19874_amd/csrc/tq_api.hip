@@ -469,8 +469,11 @@ ScorePlan plan_route(const tq_params* p, bool prod, int n_groups, int q_per_grou
   // few queries per code; with a short code list also a few more (every block of 4 queries re-reads the
   // codes, which costs less than the launches of the contraction path while the list is short)
   // (beyond 512 coordinates that kernel takes one launch per 512 and a matrix-vector kernel rotates the queries:
-  // up to 16 queries per group, where the dense contraction would run on tiles that are mostly padding)
-  if ((d <= 512 ? (q_per_group <= 32 || (q_per_group <= 64 && n_per_group <= 16384)) : (q_per_group <= 16 && nq <= 64)) &&
+  // up to 16 queries per group, where the dense contraction would run on tiles that are mostly padding; up to 32
+  // at d <= 1024, where the alternative is the lane-per-key kernel: measured at d = 1024 and 10^6 codes, 17-32
+  // queries take 2.1-3.2 ms there and 1.1-1.7 ms here)
+  if ((d <= 512 ? (q_per_group <= 32 || (q_per_group <= 64 && n_per_group <= 16384))
+                : ((q_per_group <= 16 || (q_per_group <= 32 && d <= 1024)) && nq <= 64)) &&
       score_i8_applicable(p->bits_mse, d, make_codebook(p))) {
     pl.route = ScorePlan::R_I8;
     pl.img_bytes = score_i8_workspace_bytes(d, nq);
