@@ -145,7 +145,9 @@ __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ sco
 
 // Chunks per row when a call's rows are too few to fill the chip: 0 (one workgroup per row) unless the rows are
 // few and long; then chunks of at least 8192 scores, about four workgroups per compute unit in all, and no more
-// pairs per row than the joining kernel takes (4096).
+// pairs per row than the joining kernel takes (4096).  (Short chunks are the cheaper ones: while a thread has seen
+// fewer than some hundred scores nearly every score enters some lane's list, so a wavefront pays the insertion
+// for every element; one row of 10^6 scores: 35 us in 122 chunks, 103 us in 30.)
 int topk_chunks(int64_t rows, int64_t n, int k) {
   if (k < 1 || rows < 1 || rows > 128 || n < 65536) return 0;
   int64_t c = (4 * (int64_t)device_cu_count() + rows - 1) / rows;
