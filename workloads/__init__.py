@@ -56,6 +56,9 @@ CONFIGS = {
     "C3h": Config("C3h", "prod", 3, 128, 65536, 8, 32, 4, "bf16", False, 0, 2, 3, 100, 200, 64),
     "C4": Config("C4", "mse", 4, 1536, 1000000, 1, 1000, 1000, "f32", True, 10, 4, 5, 101, 201),
     "C5": Config("C5", "prod", 2, 3072, 1000000, 1, 1000, 1000, "f32", True, 10, 6, 7, 102, 202),
+    # the same two indexes searched online: four queries at a time instead of a batch of 1000
+    "C4q": Config("C4q", "mse", 4, 1536, 1000000, 1, 4, 4, "f32", True, 10, 4, 5, 101, 201),
+    "C5q": Config("C5q", "prod", 2, 3072, 1000000, 1, 4, 4, "f32", True, 10, 6, 7, 102, 202),
 }
 
 
