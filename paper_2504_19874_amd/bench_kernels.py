@@ -248,7 +248,9 @@ def main():
         out_b = 0 if cfg.topk else 4 * pairs
         report("score" + (f"+top{cfg.topk}" if cfg.topk else ""), cfg, timed(score, reps),
                2.0 * pairs * d * (2 if prod else 1) + 2.0 * nq * dd * (2 if prod else 1),
-               n * code_b + out_b + 4 * nq * d, {"scores_per_s": None, "pairs": pairs})
+               n * code_b + out_b + 4 * nq * d, {"scores_per_s": None, "pairs": pairs},
+               # a few queries per code run on the int8 cores and read the codes once per four queries
+               bound="hbm" if cfg.q_per_group <= 16 and d > 128 else None)
 
     if on("attend") and not cfg.topk and cfg.q_per_group <= 32 and not big:
         # attention read-out: the key codes above plus a value cache of the same shape
