@@ -224,7 +224,8 @@ __global__ __launch_bounds__(512) void digitise_i8_kernel(const int d, const flo
 
 // KSM: compile-time bound on the number of 64-coordinate k-steps (register arrays).
 // A wavefront owns i8_tiles() tiles of 16 keys and requests all their code words up front.
-template <int BITS, bool PROD, int KSM>
+// WALK: the grid is sized to the chip and a workgroup walks several blocks of keys (see launch_one).
+template <int BITS, bool PROD, int KSM, bool WALK = (BITS < 4)>
 __global__ __launch_bounds__(512) void score_i8_kernel(const ScoreI8Args a) {
   __shared__ __attribute__((aligned(16))) uint2 expand_s[256 * I8_COPIES];  // [256][32]: byte -> one byte per bit
   constexpr int GI = KSM / 2;      // plane-word groups per lane
@@ -274,6 +275,53 @@ __global__ __launch_bounds__(512) void score_i8_kernel(const ScoreI8Args a) {
     s_sum = a.scal[(orow * 2 + 1) * 4 + 1];
   }
 
+  // ---- 2. every code word of this wavefront's keys goes in flight: the first tile can start
+  // while the later ones are still on their way ------------------------------------------
+  const int groups = d >> 5;
+  const int words_per_row = groups * BITS;
+  const int64_t gbase = (int64_t)group * a.n;
+  // A workgroup walks blocks of 8 x 16 TILES keys (the grid may be sized to the chip instead of to the keys): the
+  // table and the query operands are set up once per workgroup.  The first block's code words are requested
+  // before the table is filled, so that the fill runs while they are on their way.
+  const int64_t nblk = (a.n + 8 * 16 * TILES - 1) / (8 * 16 * TILES);
+  int64_t blk = blockIdx.x;  // below nblk: the grid has at most that many workgroups along x
+  int64_t wave_key0 = (blk * 8 + wave) * (16 * TILES);
+  bool full = wave_key0 + 16 * TILES <= a.n;  // uniform: no key of this wavefront is past the end
+  uint32_t pw[TILES][GI][NW], zw[TILES][GI];
+  float kg[TILES], nu[TILES];
+  auto load_codes = [&](auto clamp_c) {
+    constexpr bool CLAMP = decltype(clamp_c)::value;
+    // one base address per array and lane; without clamping the tiles are constant offsets from it
+    const int64_t key0 = wave_key0 + col;
+    const int64_t row0 = gbase + (key0 < a.n ? key0 : a.n - 1);
+    const int g0 = 2 * a.k0;  // first plane-word group of this launch (a k-step is two groups)
+    const uint32_t* const pi0 = a.idx + row0 * words_per_row + (g0 + kq) * BITS;
+    const uint32_t* const pz0 = a.qjl + (PROD ? row0 * groups + g0 + kq : 0);
+    const float* const pg0 = a.gamma + (PROD ? row0 : 0);
+    const float* const pn0 = a.norm + (a.norm != nullptr ? row0 : 0);
+#pragma unroll
+    for (int t = 0; t < TILES; ++t) {
+      // rows advance by 16 per tile; a clamped row (results of such lanes are not stored) moves
+      // back by the same number of rows in every array
+      int back = 0;
+      if (CLAMP) back = (int)(key0 + 16 * t < a.n ? 0 : key0 + 16 * t - (a.n - 1)) - (int)(key0 < a.n ? 0 : key0 - (a.n - 1));
+      const int dr = 16 * t - back;  // row - row0
+      const uint32_t* pi = pi0 + dr * words_per_row;
+      const uint32_t* pz = pz0 + dr * groups;
+#pragma unroll
+      for (int i = 0; i < GI; ++i) {
+        const int io = i < gi ? i : 0;
+#pragma unroll
+        for (int pl = 0; pl < BITS; ++pl) pw[t][i][pl] = pi[io * 4 * BITS + pl];
+        zw[t][i] = PROD ? pz[io * 4] : 0u;
+      }
+      kg[t] = PROD ? pg0[dr] : 0.f;
+      nu[t] = a.norm != nullptr ? pn0[dr] : 1.f;
+    }
+  };
+  if (full) load_codes(std::false_type{});
+  else load_codes(std::true_type{});
+
   // ---- 3. the expansion table, 32 bank-private copies ------------------------------------
   // thread -> (entry tid/32 + 16 i, copy tid%32): consecutive threads write consecutive
   // addresses; the low nibble of the entry is the thread's own, the high nibble is i
@@ -310,53 +358,7 @@ __global__ __launch_bounds__(512) void score_i8_kernel(const ScoreI8Args a) {
   const float base_r = add ? 0.f : a.coef[0] * r_sum;
   const float zs = 2.f * s_inv;
   if (add) s_sum = 0.f;
-  // ---- 2. every code word of this wavefront's keys goes in flight: the first tile can start
-  // while the later ones are still on their way ------------------------------------------
-  const int groups = d >> 5;
-  const int words_per_row = groups * BITS;
-  const int64_t gbase = (int64_t)group * a.n;
-  // A workgroup walks blocks of 8 x 16 TILES keys (the grid is sized to the chip, not to the keys): the table above
-  // and the query operands are set up once per workgroup instead of once per block of keys
-  const int64_t nblk = (a.n + 8 * 16 * TILES - 1) / (8 * 16 * TILES);
-  for (int64_t blk = blockIdx.x; blk < nblk; blk += gridDim.x) {
-  const int64_t wave_key0 = (blk * 8 + wave) * (16 * TILES);
-  const bool full = wave_key0 + 16 * TILES <= a.n;  // uniform: no key of this wavefront is past the end
-  uint32_t pw[TILES][GI][NW], zw[TILES][GI];
-  float kg[TILES], nu[TILES];
-  auto load_codes = [&](auto clamp_c) {
-    constexpr bool CLAMP = decltype(clamp_c)::value;
-    // one base address per array and lane; without clamping the tiles are constant offsets from it
-    const int64_t key0 = wave_key0 + col;
-    const int64_t row0 = gbase + (key0 < a.n ? key0 : a.n - 1);
-    const int g0 = 2 * a.k0;  // first plane-word group of this launch (a k-step is two groups)
-    const uint32_t* const pi0 = a.idx + row0 * words_per_row + (g0 + kq) * BITS;
-    const uint32_t* const pz0 = a.qjl + (PROD ? row0 * groups + g0 + kq : 0);
-    const float* const pg0 = a.gamma + (PROD ? row0 : 0);
-    const float* const pn0 = a.norm + (a.norm != nullptr ? row0 : 0);
-#pragma unroll
-    for (int t = 0; t < TILES; ++t) {
-      // rows advance by 16 per tile; a clamped row (results of such lanes are not stored) moves
-      // back by the same number of rows in every array
-      int back = 0;
-      if (CLAMP) back = (int)(key0 + 16 * t < a.n ? 0 : key0 + 16 * t - (a.n - 1)) - (int)(key0 < a.n ? 0 : key0 - (a.n - 1));
-      const int dr = 16 * t - back;  // row - row0
-      const uint32_t* pi = pi0 + dr * words_per_row;
-      const uint32_t* pz = pz0 + dr * groups;
-#pragma unroll
-      for (int i = 0; i < GI; ++i) {
-        const int io = i < gi ? i : 0;
-#pragma unroll
-        for (int pl = 0; pl < BITS; ++pl) pw[t][i][pl] = pi[io * 4 * BITS + pl];
-        zw[t][i] = PROD ? pz[io * 4] : 0u;
-      }
-      kg[t] = PROD ? pg0[dr] : 0.f;
-      nu[t] = a.norm != nullptr ? pn0[dr] : 1.f;
-    }
-  };
-  if (full) load_codes(std::false_type{});
-  else load_codes(std::true_type{});
-
-  float* const out0 = a.scores + ((int64_t)group * a.q_per_group + q0 + kq) * a.lds + wave_key0 + col;
+  float* out0 = a.scores + ((int64_t)group * a.q_per_group + q0 + kq) * a.lds + wave_key0 + col;
 
   // The tiles run as a three-stage software pipeline, written out in source order: while the
   // MFMAs of tile t issue, the table lookups of tile t+1 are already on their way and the
@@ -451,18 +453,30 @@ __global__ __launch_bounds__(512) void score_i8_kernel(const ScoreI8Args a) {
       }
     }
   };
-  if (full) run_tiles(std::true_type{});
-  else run_tiles(std::false_type{});
-  }  // blocks of keys
+  while (true) {
+    if (full) run_tiles(std::true_type{});
+    else run_tiles(std::false_type{});
+    if constexpr (!WALK) break;  // a workgroup per block of keys: straight-line code
+    blk += gridDim.x;
+    if (blk >= nblk) break;  // uniform over the workgroup
+    wave_key0 = (blk * 8 + wave) * (16 * TILES);
+    full = wave_key0 + 16 * TILES <= a.n;
+    out0 = a.scores + ((int64_t)group * a.q_per_group + q0 + kq) * a.lds + wave_key0 + col;
+    if (full) load_codes(std::false_type{});
+    else load_codes(std::true_type{});
+  }
 }
 
 template <int BITS, bool PROD, int KSM>
 static hipError_t launch_one(const ScoreI8Args& a, int n_groups, hipStream_t s) {
   const int64_t per_wg = 8 * 16 * i8_tiles(BITS, KSM);
-  // two workgroups fit a compute unit (64 KB of LDS each): about that many in all, each walking its share of the keys
+  // two workgroups fit a compute unit (64 KB of LDS each): about that many in all, each walking its share of the
+  // keys.  Up to 3 index bits, that is: the 4-bit kernel, with half the keys per block, loses more to the loads of
+  // a block waiting for the block before it than it gains (d = 1536, 10^6 codes: 92 against 84 us per launch; 1 + 1
+  // bits at d = 3072: 86 against 110), so there every block of keys gets a workgroup of its own.
   const int64_t others = (int64_t)n_groups * ((a.q_per_group + 3) / 4);
-  int64_t gx = (2 * (int64_t)device_cu_count() + others - 1) / others;
   const int64_t nblk = (a.n + per_wg - 1) / per_wg;
+  int64_t gx = BITS >= 4 ? nblk : (2 * (int64_t)device_cu_count() + others - 1) / others;
   if (gx > nblk) gx = nblk;
   if (gx < 1) gx = 1;
   const dim3 grid((unsigned)gx, n_groups, (a.q_per_group + 3) / 4);
