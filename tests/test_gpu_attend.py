@@ -62,7 +62,10 @@ def check_attend(out, want, q, scale, k_norm, v_tilde, p_want, d, n_groups, qpg,
     for g in range(n_groups):
         rows = slice(g * qpg, (g + 1) * qpg)
         e = 1e-4 * abs(scale) * qn[rows] * float(k_norm[g * npg:(g + 1) * npg].max())
-        size = p_want[rows] @ np.abs(v_tilde[g * npg:(g + 1) * npg])  # sum_i p_i |v~_i|, per coordinate
+        vt_g = v_tilde[g * npg:(g + 1) * npg]
+        # sum_i p_i (|v~_i| + ||v~_i|| / sqrt(d)) per coordinate: the scale of a dequantised coordinate (a coordinate
+        # that cancels to nearly zero is still only known to 1e-4 of the vector's typical coordinate)
+        size = p_want[rows] @ (np.abs(vt_g) + np.linalg.norm(vt_g, axis=1, keepdims=True) / math.sqrt(vt_g.shape[1]))
         lim = (P.REL_TOL + np.expm1(2 * e))[:, None] * (size + np.abs(want[rows]))
         err = np.abs(out[rows] - want[rows])
         worst = float((err / np.maximum(lim, 1e-300)).max())

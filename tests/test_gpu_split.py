@@ -306,6 +306,7 @@ def test_split_decode_configurations_full_size(name):
     (32, 2, 64, 1, 4, 4100),   # keys in two instances as well (scored by tq_score first)
     (96, 1, 0, 1, 5, 700),     # 1 + 2 bits
     (64, 2, 0, 3, 1, 1),       # one token
+    (96, 2, 32, 3, 2, 1),      # one token, keys in two instances: the output is one dequantised value vector
 ])
 def test_attend_with_values_in_two_instances(d_hi, vbits_lo, kd_hi, n_groups, qpg, npg):
     """tq_attend with a value cache quantised as two instances (outlier channels one bit wider): softmax of the
@@ -345,7 +346,10 @@ def test_attend_with_values_in_two_instances(d_hi, vbits_lo, kd_hi, n_groups, qp
     for g in range(n_groups):
         rows, toks = slice(g * qpg, (g + 1) * qpg), slice(g * npg, (g + 1) * npg)
         want = o.attend(q[rows], kt[toks], vt[toks], scale)
-        size = o.attend(q[rows], kt[toks], np.abs(vt[toks]), scale)
+        # scale of a dequantised coordinate: |v~| + ||v~|| / sqrt(d) (a coordinate that cancels to nearly zero is still
+        # only known to 1e-4 of the vector's typical coordinate), carried through the same softmax
+        floor = np.linalg.norm(vt[toks], axis=1, keepdims=True) / math.sqrt(D)
+        size = o.attend(q[rows], kt[toks], np.abs(vt[toks]) + floor, scale)
         e = 1e-4 * scale * qn[rows] * k_norm_max
         lim = (P.REL_TOL + np.expm1(2 * e))[:, None] * (size + np.abs(want))
         worst = float((np.abs(got[rows] - want) / np.maximum(lim, 1e-300)).max())
