@@ -32,6 +32,7 @@ constexpr int64_t kChunkRows = 65536;  // rows per pass when a residual workspac
 // Row strides of vectors (x, q) and of dequantised output: the kernels address a tile's rows with 32-bit byte
 // offsets from a 64-bit tile base (up to 256 rows of ld * 4 bytes)
 constexpr int64_t kMaxRowStride = int64_t(1) << 22;
+constexpr int64_t kRowsQuantMax = 64;  // Quant_mse of at most this many long vectors: the matrix-vector route
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -190,6 +191,13 @@ tq_status quantize_common(const tq_params* p, const void* x, int32_t dtype, int6
   const NKind nk = dtype == TQ_F32 ? N_F32 : N_BF16;
 
   if (!prod) {
+    // a handful of long vectors: a matrix-vector product per vector instead of the tiled contraction's serial k-loop,
+    // when the workspace holds the rotated vectors
+    if (n <= kRowsQuantMax && d >= 512 && d <= 4096 && !fp32_mfma_only(p)) {
+      Workspace ws{static_cast<char*>(p->workspace), p->workspace_bytes, 0};
+      if (float* const yw = static_cast<float*>(ws.take((size_t)n * d * sizeof(float))); yw != nullptr)
+        return from_hip(launch_quant_rows(p->bits_mse, dtype == TQ_BF16, x, ldx, n, d, p->Pi, make_codebook(p), yw, idx, norm, stream));
+    }
     a.X = x;
     a.n = n;
     a.rownorm_out = norm;

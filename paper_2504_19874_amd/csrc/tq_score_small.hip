@@ -68,13 +68,17 @@ __global__ __launch_bounds__(256) void matvec_small_kernel(const int d, const in
 __global__ __launch_bounds__(256) void matvec_rows_kernel(const int d, const int nq, const float* __restrict__ W0,
                                                           const float* __restrict__ W1, const float* __restrict__ x,
                                                           const int64_t ldx, float* __restrict__ out0,
-                                                          float* __restrict__ out1) {
+                                                          float* __restrict__ out1, const int x_bf16) {
   extern __shared__ __attribute__((aligned(16))) float xs[];  // [MV_Q][d]
   const int tid = threadIdx.x, lane = tid & 63;
   const int q0 = blockIdx.y * MV_Q;
   for (int e = tid; e < MV_Q * d; e += 256) {
     const int r = e / d, k = e - r * d;
-    xs[e] = (q0 + r < nq) ? x[(int64_t)(q0 + r) * ldx + k] : 0.f;
+    float v = 0.f;
+    if (q0 + r < nq)
+      v = x_bf16 ? __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(x)[(int64_t)(q0 + r) * ldx + k] << 16)
+                 : x[(int64_t)(q0 + r) * ldx + k];
+    xs[e] = v;
   }
   __syncthreads();
   const int j = blockIdx.x * 4 + (tid >> 6);
@@ -99,13 +103,82 @@ __global__ __launch_bounds__(256) void matvec_rows_kernel(const int d, const int
   }
 }
 
+// Alg. 1 for a handful of long vectors (adding to an index one vector at a time): y = Pi x by the row-per-wavefront
+// kernel above, then one workgroup per vector takes the norm of x, scales, decides and packs.  (The tiled contraction
+// walks d / 32 k-steps in series whatever the batch: 78 us for one vector at d = 1536.)  Rotating first and dividing
+// by the norm afterwards differs from the other kernels' order by rounding only.
+template <int BITS>
+__global__ __launch_bounds__(256) void quant_rows_finish_kernel(const int d, const void* __restrict__ x, const int64_t ldx,
+                                                                const int x_bf16, const float* __restrict__ yw,
+                                                                const Codebook cb, uint32_t* __restrict__ idx,
+                                                                float* __restrict__ norm) {
+  __shared__ float red_s[4];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int64_t row = blockIdx.x;
+  float inv = 1.f;
+  if (norm != nullptr) {
+    float ss = 0.f;
+    for (int k = tid; k < d; k += 256) {
+      const float v = x_bf16 ? __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(x)[row * ldx + k] << 16)
+                             : reinterpret_cast<const float*>(x)[row * ldx + k];
+      ss = fmaf(v, v, ss);
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+    if (lane == 0) red_s[tid >> 6] = ss;
+    __syncthreads();
+    const float nu = sqrtf((red_s[0] + red_s[1]) + (red_s[2] + red_s[3]));
+    inv = nu > 0.f ? 1.f / nu : 0.f;  // a zero row stays zero
+    if (tid == 0) norm[row] = nu;
+  }
+  if (BITS == 0) return;
+  const int groups = d >> 5;
+  for (int j0 = 0; j0 < d; j0 += 256) {  // uniform trip count; a wavefront covers 64 consecutive coordinates
+    const int j = j0 + tid;
+    int code = 0;
+    if (j < d) {
+      const float y = yw[row * d + j] * inv;
+#pragma unroll
+      for (int t = 0; t < (1 << BITS) - 1; ++t) code += (y >= cb.t[t]) ? 1 : 0;  // on a boundary: the upper cell
+    }
+    const int g = (j0 + (tid & ~63)) >> 5;  // first of the wavefront's two groups of 32
+#pragma unroll
+    for (int pl = 0; pl < BITS; ++pl) {
+      const unsigned long long m = __ballot((code >> pl) & 1);
+      if (lane == 0 && g < groups) idx[row * (int64_t)(groups * BITS) + g * BITS + pl] = (uint32_t)m;
+      if (lane == 32 && g + 1 < groups) idx[row * (int64_t)(groups * BITS) + (g + 1) * BITS + pl] = (uint32_t)(m >> 32);
+    }
+  }
+}
+
+hipError_t launch_quant_rows(int bits, bool bf16, const void* x, int64_t ldx, int64_t n, int d, const float* Pi,
+                             const Codebook& cb, float* yw, uint32_t* idx, float* norm, hipStream_t stream) {
+  if (n == 0) return hipSuccess;
+  if (n > 65535 * MV_Q || d % 32 != 0 || (size_t)MV_Q * d * sizeof(float) > 65536) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(matvec_rows_kernel, dim3((d + 3) / 4, (unsigned)((n + MV_Q - 1) / MV_Q), 1), dim3(256),
+                     (size_t)MV_Q * d * sizeof(float), stream, d, (int)n, Pi, nullptr, static_cast<const float*>(x), ldx, yw,
+                     nullptr, bf16 ? 1 : 0);
+  if (const hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+  const dim3 grid((unsigned)n);
+  const int xb = bf16 ? 1 : 0;
+  switch (bits) {
+    case 0: hipLaunchKernelGGL(quant_rows_finish_kernel<0>, grid, dim3(256), 0, stream, d, x, ldx, xb, yw, cb, idx, norm); break;
+    case 1: hipLaunchKernelGGL(quant_rows_finish_kernel<1>, grid, dim3(256), 0, stream, d, x, ldx, xb, yw, cb, idx, norm); break;
+    case 2: hipLaunchKernelGGL(quant_rows_finish_kernel<2>, grid, dim3(256), 0, stream, d, x, ldx, xb, yw, cb, idx, norm); break;
+    case 3: hipLaunchKernelGGL(quant_rows_finish_kernel<3>, grid, dim3(256), 0, stream, d, x, ldx, xb, yw, cb, idx, norm); break;
+    case 4: hipLaunchKernelGGL(quant_rows_finish_kernel<4>, grid, dim3(256), 0, stream, d, x, ldx, xb, yw, cb, idx, norm); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
 hipError_t launch_matvec_small(int d, int nq, const float* W0, const float* W1, const float* x,
                                int64_t ldx, float* out0, float* out1, hipStream_t stream) {
   if (nq == 0) return hipSuccess;
   if (d % 4 != 0 || (size_t)MV_Q * d * sizeof(float) > 65536) return hipErrorInvalidValue;
   if (d >= 512) {
     hipLaunchKernelGGL(matvec_rows_kernel, dim3((d + 3) / 4, (nq + MV_Q - 1) / MV_Q, W1 != nullptr ? 2 : 1), dim3(256),
-                       (size_t)MV_Q * d * sizeof(float), stream, d, nq, W0, W1, x, ldx, out0, out1);
+                       (size_t)MV_Q * d * sizeof(float), stream, d, nq, W0, W1, x, ldx, out0, out1, 0);
     return hipGetLastError();
   }
   hipLaunchKernelGGL(matvec_small_kernel, dim3((d + 63) / 64, (nq + MV_Q - 1) / MV_Q, W1 != nullptr ? 2 : 1),

@@ -157,6 +157,34 @@ def test_quantize_mse(d, bits, n, kind):
         P.check_close(norm.cpu().numpy(), nu_or, 0.0, "norm", rel=2e-6)
 
 
+@pytest.mark.parametrize("d,bits,n,kind", [(1536, 4, 1, "unit"), (1536, 4, 8, "f32"), (3072, 2, 64, "bf16"), (512, 3, 5, "f32"),
+                                          (1024, 1, 33, "bf16unit"), (768, 4, 64, "unit"), (4096, 2, 3, "f32"), (544, 0, 7, "f32")])
+def test_quantize_a_handful_of_long_vectors(d, bits, n, kind):
+    """Up to 64 vectors at d >= 512 with a workspace at hand: y = Pi x by the matrix-vector kernel, then norm, decision
+    and packing per vector; without a workspace the tiled contraction.  Both against the oracle."""
+    p, Pi, _, c32, t32 = setup(d, bits, False)
+    x_or, x_dev, normalise = _quant_inputs(n, d, kind, 13 * d + bits)
+    idx_or, nu_or, y_or = o.quant_mse(x_or, Pi, t32, normalise)
+    keep = (p.workspace, p.c.workspace, p.c.workspace_bytes)
+    try:
+        for with_workspace in (True, False):
+            if with_workspace:
+                p.reserve(n, 0, 0)
+                assert p.c.workspace_bytes >= n * d * 4
+            else:
+                p.workspace, p.c.workspace, p.c.workspace_bytes = None, 0, 0
+            idx = torch.full((n + 1, max(1, p.idx_words)), -5, dtype=torch.int32, device=DEV)
+            norm = torch.full((n + 1,), -5.0, dtype=torch.float32, device=DEV) if normalise else None
+            tq.tq_quantize_mse(p, x_dev, idx[:n], None if norm is None else norm[:n])
+            assert bool((idx[n] == -5).all()) and (norm is None or float(norm[n]) == -5.0)
+            if bits:
+                P.check_indices(o.unpack_planes(words(idx[:n])[:, : p.idx_words], bits, d), idx_or, y_or, t32)
+            if normalise:
+                P.check_close(norm[:n].cpu().numpy(), nu_or, 0.0, "norm", rel=2e-6)
+    finally:
+        p.workspace, p.c.workspace, p.c.workspace_bytes = keep
+
+
 def _run_prod(p, x_dev, n, normalise):
     idx = torch.zeros((n, max(1, p.idx_words)), dtype=torch.int32, device=DEV)
     qjl = torch.zeros((n, p.qjl_words), dtype=torch.int32, device=DEV)
