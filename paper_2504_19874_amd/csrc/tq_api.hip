@@ -32,7 +32,13 @@ constexpr int64_t kChunkRows = 65536;  // rows per pass when a residual workspac
 // Row strides of vectors (x, q) and of dequantised output: the kernels address a tile's rows with 32-bit byte
 // offsets from a 64-bit tile base (up to 256 rows of ld * 4 bytes)
 constexpr int64_t kMaxRowStride = int64_t(1) << 22;
-constexpr int64_t kRowsQuantMax = 64;  // Quant_mse of at most this many long vectors: the matrix-vector route
+constexpr int64_t kRowsQuantMax = 64;  // at most this many long vectors take the matrix-vector route of the quantiser
+// That route reads every matrix once per block of four vectors, the tiled contraction once per 128: it wins while
+// blocks x d^2 x matrices stays below about 4e7 elements (measured: d = 1536, Alg. 1: 14 / 18 / 52 us for 1 / 8 / 64
+// vectors against 78; d = 3072, Alg. 2: 47 / 112 us for 1 / 8 against 223, but 722 us for 64).
+bool rows_route_serves(int64_t n, int d, int matrices) {
+  return n <= kRowsQuantMax && d >= 512 && d <= 4096 && ((n + 3) / 4) * (int64_t)d * d * matrices <= 150ll * 512 * 512;
+}
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -193,7 +199,7 @@ tq_status quantize_common(const tq_params* p, const void* x, int32_t dtype, int6
   if (!prod) {
     // a handful of long vectors: a matrix-vector product per vector instead of the tiled contraction's serial k-loop,
     // when the workspace holds the rotated vectors
-    if (n <= kRowsQuantMax && d >= 512 && d <= 4096 && !fp32_mfma_only(p)) {
+    if (rows_route_serves(n, d, 1) && !fp32_mfma_only(p)) {
       Workspace ws{static_cast<char*>(p->workspace), p->workspace_bytes, 0};
       if (float* const yw = static_cast<float*>(ws.take((size_t)n * d * sizeof(float))); yw != nullptr)
         return from_hip(launch_quant_rows(p->bits_mse, dtype == TQ_BF16, x, ldx, n, d, p->Pi, make_codebook(p), yw, idx, norm, stream));
@@ -203,6 +209,16 @@ tq_status quantize_common(const tq_params* p, const void* x, int32_t dtype, int6
     a.rownorm_out = norm;
     a.words_out = idx;
     return from_hip(launch_gemm(nk, E_QUANT, p->bits_mse, a, 1, stream));
+  }
+
+  // a handful of long vectors: the matrix-vector route (see above), the sketch included
+  if (rows_route_serves(n, d, 2) && !fp32_mfma_only(p)) {
+    Workspace ws2{static_cast<char*>(p->workspace), p->workspace_bytes, 0};
+    float* const yw = static_cast<float*>(ws2.take((size_t)n * d * sizeof(float)));
+    float* const ew = static_cast<float*>(ws2.take((size_t)n * d * sizeof(float)));
+    if (yw != nullptr && ew != nullptr)
+      return from_hip(launch_quant_rows(p->bits_mse, dtype == TQ_BF16, x, ldx, n, d, p->Pi, make_codebook(p), yw, idx, norm, stream,
+                                        p->SPiT, ew, qjl, gamma));
   }
 
   // prod: pass 1 writes idx and the rotated-basis residual e = y - c[idx];
@@ -330,6 +346,8 @@ size_t tq_workspace_bytes(const tq_params* p, int64_t n, int64_t nq, int32_t top
   const size_t d = (size_t)p->d;
   const size_t rows = (size_t)(n < kChunkRows ? n : kChunkRows);
   size_t bytes = round_up(rows * d * sizeof(float), 256);          // residual of quantize_prod
+  // a handful of long vectors: their rotated coordinates beside the residual (the matrix-vector route)
+  bytes += round_up((size_t)(n < kRowsQuantMax ? n : kRowsQuantMax) * d * sizeof(float), 256);
   bytes += 2 * round_up((size_t)nq * d * sizeof(float), 256);      // rotated / sketched queries
   bytes += round_up(score_i8_workspace_bytes(p->d, nq), 256);      // or their int8 digit images
   if (topk > 0) bytes += round_up((size_t)nq * (size_t)(n + 3) * sizeof(float), 256);  // scores when not returned

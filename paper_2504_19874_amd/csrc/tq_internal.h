@@ -132,10 +132,13 @@ hipError_t launch_dequant128_bf3(int bits, bool prod, const uint32_t* idx, const
                                  const void* image, hipStream_t s);
 
 // few queries per code (tq_score_small.hip)
-// Quant_mse for a handful of long vectors: y = Pi x by a matrix-vector kernel into yw [n][d], then norm, decision
-// and packing per vector (tq_score_small.hip).  d a multiple of 32 up to 4096.
+// Quant_mse / Quant_prod for a handful of long vectors: y = Pi x by a matrix-vector kernel into yw [n][d], then norm,
+// decision and packing per vector (tq_score_small.hip); with ew != NULL also the residual e = y - c[idx] into ew
+// [n][d], gamma = |e|, u = (S Pi^T) e by the same matrix-vector kernel and its signs into qjl.  d a multiple of 32 up
+// to 4096.
 hipError_t launch_quant_rows(int bits, bool bf16, const void* x, int64_t ldx, int64_t n, int d, const float* Pi,
-                             const Codebook& cb, float* yw, uint32_t* idx, float* norm, hipStream_t stream);
+                             const Codebook& cb, float* yw, uint32_t* idx, float* norm, hipStream_t stream,
+                             const float* SPiT = nullptr, float* ew = nullptr, uint32_t* qjl = nullptr, float* gamma = nullptr);
 hipError_t launch_matvec_small(int d, int nq, const float* W0, const float* W1, const float* x,
                                int64_t ldx, float* out0, float* out1, hipStream_t stream);
 hipError_t launch_score_small(int bits, bool prod, const float* qr, const float* qs, const uint32_t* idx,

@@ -107,12 +107,15 @@ __global__ __launch_bounds__(256) void matvec_rows_kernel(const int d, const int
 // kernel above, then one workgroup per vector takes the norm of x, scales, decides and packs.  (The tiled contraction
 // walks d / 32 k-steps in series whatever the batch: 78 us for one vector at d = 1536.)  Rotating first and dividing
 // by the norm afterwards differs from the other kernels' order by rounding only.
+// ew != NULL (Alg. 2): the residual in the rotated basis, e = y - c[idx], goes to ew [n][d] and its norm to gamma.
 template <int BITS>
 __global__ __launch_bounds__(256) void quant_rows_finish_kernel(const int d, const void* __restrict__ x, const int64_t ldx,
                                                                 const int x_bf16, const float* __restrict__ yw,
                                                                 const Codebook cb, uint32_t* __restrict__ idx,
-                                                                float* __restrict__ norm) {
+                                                                float* __restrict__ norm, float* __restrict__ ew,
+                                                                float* __restrict__ gamma) {
   __shared__ float red_s[4];
+  __shared__ float red_e[4];
   const int tid = threadIdx.x, lane = tid & 63;
   const int64_t row = blockIdx.x;
   float inv = 1.f;
@@ -131,8 +134,9 @@ __global__ __launch_bounds__(256) void quant_rows_finish_kernel(const int d, con
     inv = nu > 0.f ? 1.f / nu : 0.f;  // a zero row stays zero
     if (tid == 0) norm[row] = nu;
   }
-  if (BITS == 0) return;
+  if (BITS == 0 && ew == nullptr) return;
   const int groups = d >> 5;
+  float ee = 0.f;
   for (int j0 = 0; j0 < d; j0 += 256) {  // uniform trip count; a wavefront covers 64 consecutive coordinates
     const int j = j0 + tid;
     int code = 0;
@@ -140,6 +144,14 @@ __global__ __launch_bounds__(256) void quant_rows_finish_kernel(const int d, con
       const float y = yw[row * d + j] * inv;
 #pragma unroll
       for (int t = 0; t < (1 << BITS) - 1; ++t) code += (y >= cb.t[t]) ? 1 : 0;  // on a boundary: the upper cell
+      if (ew != nullptr) {
+        float c = cb.c[0];
+#pragma unroll
+        for (int t = 1; t < (1 << BITS); ++t) c = code == t ? cb.c[t] : c;
+        const float e = y - c;
+        ew[row * d + j] = e;
+        ee = fmaf(e, e, ee);
+      }
     }
     const int g = (j0 + (tid & ~63)) >> 5;  // first of the wavefront's two groups of 32
 #pragma unroll
@@ -149,10 +161,18 @@ __global__ __launch_bounds__(256) void quant_rows_finish_kernel(const int d, con
       if (lane == 32 && g + 1 < groups) idx[row * (int64_t)(groups * BITS) + (g + 1) * BITS + pl] = (uint32_t)(m >> 32);
     }
   }
+  if (ew != nullptr) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) ee += __shfl_xor(ee, off);
+    if (lane == 0) red_e[tid >> 6] = ee;
+    __syncthreads();
+    if (tid == 0) gamma[row] = sqrtf((red_e[0] + red_e[1]) + (red_e[2] + red_e[3]));
+  }
 }
 
 hipError_t launch_quant_rows(int bits, bool bf16, const void* x, int64_t ldx, int64_t n, int d, const float* Pi,
-                             const Codebook& cb, float* yw, uint32_t* idx, float* norm, hipStream_t stream) {
+                             const Codebook& cb, float* yw, uint32_t* idx, float* norm, hipStream_t stream,
+                             const float* SPiT, float* ew, uint32_t* qjl, float* gamma) {
   if (n == 0) return hipSuccess;
   if (n > 65535 * MV_Q || d % 32 != 0 || (size_t)MV_Q * d * sizeof(float) > 65536) return hipErrorInvalidValue;
   hipLaunchKernelGGL(matvec_rows_kernel, dim3((d + 3) / 4, (unsigned)((n + MV_Q - 1) / MV_Q), 1), dim3(256),
@@ -162,14 +182,19 @@ hipError_t launch_quant_rows(int bits, bool bf16, const void* x, int64_t ldx, in
   const dim3 grid((unsigned)n);
   const int xb = bf16 ? 1 : 0;
   switch (bits) {
-    case 0: hipLaunchKernelGGL(quant_rows_finish_kernel<0>, grid, dim3(256), 0, stream, d, x, ldx, xb, yw, cb, idx, norm); break;
-    case 1: hipLaunchKernelGGL(quant_rows_finish_kernel<1>, grid, dim3(256), 0, stream, d, x, ldx, xb, yw, cb, idx, norm); break;
-    case 2: hipLaunchKernelGGL(quant_rows_finish_kernel<2>, grid, dim3(256), 0, stream, d, x, ldx, xb, yw, cb, idx, norm); break;
-    case 3: hipLaunchKernelGGL(quant_rows_finish_kernel<3>, grid, dim3(256), 0, stream, d, x, ldx, xb, yw, cb, idx, norm); break;
-    case 4: hipLaunchKernelGGL(quant_rows_finish_kernel<4>, grid, dim3(256), 0, stream, d, x, ldx, xb, yw, cb, idx, norm); break;
+    case 0: hipLaunchKernelGGL(quant_rows_finish_kernel<0>, grid, dim3(256), 0, stream, d, x, ldx, xb, yw, cb, idx, norm, ew, gamma); break;
+    case 1: hipLaunchKernelGGL(quant_rows_finish_kernel<1>, grid, dim3(256), 0, stream, d, x, ldx, xb, yw, cb, idx, norm, ew, gamma); break;
+    case 2: hipLaunchKernelGGL(quant_rows_finish_kernel<2>, grid, dim3(256), 0, stream, d, x, ldx, xb, yw, cb, idx, norm, ew, gamma); break;
+    case 3: hipLaunchKernelGGL(quant_rows_finish_kernel<3>, grid, dim3(256), 0, stream, d, x, ldx, xb, yw, cb, idx, norm, ew, gamma); break;
+    case 4: hipLaunchKernelGGL(quant_rows_finish_kernel<4>, grid, dim3(256), 0, stream, d, x, ldx, xb, yw, cb, idx, norm, ew, gamma); break;
     default: return hipErrorInvalidValue;
   }
-  return hipGetLastError();
+  if (const hipError_t e = hipGetLastError(); e != hipSuccess || ew == nullptr) return e;
+  // Alg. 2: u = (S Pi^T) e, again one wavefront per matrix row (into the buffer the rotation has left), signs packed
+  hipLaunchKernelGGL(matvec_rows_kernel, dim3((d + 3) / 4, (unsigned)((n + MV_Q - 1) / MV_Q), 1), dim3(256),
+                     (size_t)MV_Q * d * sizeof(float), stream, d, (int)n, SPiT, nullptr, ew, (int64_t)d, yw, nullptr, 0);
+  if (const hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+  return launch_stage_sign_pack(d, yw, n, qjl, stream);
 }
 
 hipError_t launch_matvec_small(int d, int nq, const float* W0, const float* W1, const float* x,

@@ -185,6 +185,17 @@ def test_quantize_a_handful_of_long_vectors(d, bits, n, kind):
         p.workspace, p.c.workspace, p.c.workspace_bytes = keep
 
 
+@pytest.mark.parametrize("d,bits_mse,n,kind", [(1536, 1, 1, "unit"), (3072, 1, 8, "f32"), (512, 3, 64, "bf16"), (1024, 0, 5, "f32"),
+                                              (768, 4, 33, "unit"), (2048, 2, 2, "bf16unit"), (544, 2, 9, "f32")])
+def test_quantize_prod_of_a_handful_of_long_vectors(d, bits_mse, n, kind):
+    """Alg. 2 on the matrix-vector route (up to 64 vectors, d >= 512, workspace sized by tq_workspace_bytes)."""
+    p, Pi, S, c32, t32 = setup(d, bits_mse, True)
+    x_or, x_dev, normalise = _quant_inputs(n, d, kind, 17 * d + bits_mse)
+    assert tq.tq_workspace_bytes(p, n, 0, 0) >= 2 * n * d * 4
+    out = _run_prod(p, x_dev, n, normalise)
+    _check_prod(p, Pi, S, c32, t32, x_or, normalise, *out)
+
+
 def _run_prod(p, x_dev, n, normalise):
     idx = torch.zeros((n, max(1, p.idx_words)), dtype=torch.int32, device=DEV)
     qjl = torch.zeros((n, p.qjl_words), dtype=torch.int32, device=DEV)
