@@ -69,7 +69,8 @@
  *     3 bits up to d = 96, 2 bits at d = 32);
  *     Up to 64 vectors at d >= 512 with params.workspace large enough for
  *     their rotated coordinates (tq_workspace_bytes counts them) are rotated by
- *     plain fp32 multiply-adds, one matrix-vector product per vector;
+ *     plain fp32 multiply-adds, one matrix-vector product per vector, and so
+ *     are a handful of long vectors in tq_dequantize;
  *   dequantise, large batches: two pieces of each factor (error
  *     below 4e-5 of a coordinate's typical size), at every d;
  *   scoring: two bf16 pieces of each factor (many queries; scores within

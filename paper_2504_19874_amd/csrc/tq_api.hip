@@ -36,8 +36,10 @@ constexpr int64_t kRowsQuantMax = 64;  // at most this many long vectors take th
 // That route reads every matrix once per block of four vectors, the tiled contraction once per 128: it wins while
 // blocks x d^2 x matrices stays below about 4e7 elements (measured: d = 1536, Alg. 1: 14 / 18 / 52 us for 1 / 8 / 64
 // vectors against 78; d = 3072, Alg. 2: 47 / 112 us for 1 / 8 against 223, but 722 us for 64).
-bool rows_route_serves(int64_t n, int d, int matrices) {
-  return n <= kRowsQuantMax && d >= 512 && d <= 4096 && ((n + 3) / 4) * (int64_t)d * d * matrices <= 150ll * 512 * 512;
+// (The dequantiser's route reads both matrices in one kernel and has no second stage: d = 1536, Alg. 1: 10 / 12 / 50
+// us for 1 / 8 / 64 vectors against 108; d = 3072, Alg. 2: 17 us for one against 153; its bound is twice as wide.)
+bool rows_route_serves(int64_t n, int d, int matrices, int64_t limit = 150) {
+  return n <= kRowsQuantMax && d >= 512 && d <= 4096 && ((n + 3) / 4) * (int64_t)d * d * matrices <= limit * 512 * 512;
 }
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -413,6 +415,11 @@ tq_status tq_dequantize(const tq_params* p, const uint32_t* idx, const uint32_t*
                                       kappa_of(p->d), make_codebook(p), 0, 0.f, make_codebook(p),
                                       static_cast<hipStream_t>(stream)));
   }
+  // a handful of long vectors: matrix-vector products (the matrices are read once per block of 4 vectors, 2 with a
+  // sketch; the same bound as for the quantiser's route)
+  if (p->d < 4096 && !fp32_mfma_only(p) && rows_route_serves(prod ? 2 * n : n, p->d, prod ? 2 : 1, 300))
+    return from_hip(launch_dequant_rows(p->bits_mse, prod, p->d, n, idx, qjl, gamma, norm, p->PiT, p->ST, make_codebook(p),
+                                        kappa_of(p->d), x_out, ldo, static_cast<hipStream_t>(stream)));
   // x~_i[k] = <e_k, DeQuant(code i)>: the scoring contraction with the rows of Pi^T (and S^T) as the queries,
   // stored one row per code; on the bf16 matrix cores where that kernel takes the codes
   if (!fp32_mfma_only(p) && score_bf3_applicable(p->bits_mse, prod, p->d, n, 1, p->d, make_codebook(p)))

@@ -139,6 +139,10 @@ hipError_t launch_dequant128_bf3(int bits, bool prod, const uint32_t* idx, const
 hipError_t launch_quant_rows(int bits, bool bf16, const void* x, int64_t ldx, int64_t n, int d, const float* Pi,
                              const Codebook& cb, float* yw, uint32_t* idx, float* norm, hipStream_t stream,
                              const float* SPiT = nullptr, float* ew = nullptr, uint32_t* qjl = nullptr, float* gamma = nullptr);
+// DeQuant for a handful of long vectors by matrix-vector products (tq_score_small.hip); d a multiple of 32 up to 4096
+hipError_t launch_dequant_rows(int bits, bool prod, int d, int64_t n, const uint32_t* idx, const uint32_t* qjl,
+                               const float* gamma, const float* norm, const float* PiT, const float* ST, const Codebook& cb,
+                               float kappa, float* out, int64_t ldo, hipStream_t s);
 hipError_t launch_matvec_small(int d, int nq, const float* W0, const float* W1, const float* x,
                                int64_t ldx, float* out0, float* out1, hipStream_t stream);
 hipError_t launch_score_small(int bits, bool prod, const float* qr, const float* qs, const uint32_t* idx,

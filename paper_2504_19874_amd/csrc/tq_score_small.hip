@@ -197,6 +197,105 @@ hipError_t launch_quant_rows(int bits, bool bf16, const void* x, int64_t ldx, in
   return launch_stage_sign_pack(d, yw, n, qjl, stream);
 }
 
+// DeQuant of Alg. 1 / Alg. 2 for a handful of long vectors: x~[k] = nu (sum_j Pi^T[k][j] c[idx_j] + kappa gamma
+// sum_j S^T[k][j] z_j), one wavefront per output coordinate k (a row of Pi^T and of S^T, 1 KB per load), the decoded
+// codes of Q vectors in LDS (4 for Alg. 1; 2 for Alg. 2, whose sign vector sits beside them).
+template <int BITS, bool PROD>
+__global__ __launch_bounds__(256) void dequant_rows_kernel(const int d, const int n, const uint32_t* __restrict__ idx,
+                                                           const uint32_t* __restrict__ qjl, const float* __restrict__ gamma,
+                                                           const float* __restrict__ norm, const float* __restrict__ PiT,
+                                                           const float* __restrict__ ST, const Codebook cb, const float kappa,
+                                                           float* __restrict__ out, const int64_t ldo) {
+  constexpr int Q = PROD ? 2 : 4;
+  extern __shared__ __attribute__((aligned(16))) float ys[];  // [Q][d], then (PROD) [Q][d] of +-kappa gamma
+  __shared__ float cent_s[16];
+  float* const zs = ys + Q * d;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int q0 = blockIdx.y * Q;
+  if (tid < 16) cent_s[tid] = cb.c[tid];
+  __syncthreads();
+  const int groups = d >> 5;
+  for (int e = tid; e < Q * d; e += 256) {
+    const int r = e / d, k = e - r * d;
+    const int64_t row = q0 + r;
+    float y = 0.f, z = 0.f;
+    if (row < n) {
+      int code = 0;
+#pragma unroll
+      for (int pl = 0; pl < BITS; ++pl) code |= (int)((idx[row * (int64_t)(groups * BITS) + (k >> 5) * BITS + pl] >> (k & 31)) & 1u) << pl;
+      y = cent_s[code];
+      if (PROD) {
+        const float kg = kappa * gamma[row];
+        z = ((qjl[row * groups + (k >> 5)] >> (k & 31)) & 1u) ? kg : -kg;
+      }
+    }
+    ys[e] = y;
+    if (PROD) zs[e] = z;
+  }
+  __syncthreads();
+  const int j = blockIdx.x * 4 + (tid >> 6);
+  if (j >= d) return;  // the whole wavefront
+  const float4* w4 = reinterpret_cast<const float4*>(PiT + (int64_t)j * d);
+  const float4* s4 = PROD ? reinterpret_cast<const float4*>(ST + (int64_t)j * d) : nullptr;
+  float acc[Q];
+#pragma unroll
+  for (int r = 0; r < Q; ++r) acc[r] = 0.f;
+  for (int k4 = lane; k4 < d / 4; k4 += 64) {
+    const float4 w = w4[k4];
+    float4 sv = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (PROD) sv = s4[k4];
+#pragma unroll
+    for (int r = 0; r < Q; ++r) {
+      const float4 v = reinterpret_cast<const float4*>(ys + r * d)[k4];
+      acc[r] = fmaf(w.x, v.x, fmaf(w.y, v.y, fmaf(w.z, v.z, fmaf(w.w, v.w, acc[r]))));
+      if (PROD) {
+        const float4 u = reinterpret_cast<const float4*>(zs + r * d)[k4];
+        acc[r] = fmaf(sv.x, u.x, fmaf(sv.y, u.y, fmaf(sv.z, u.z, fmaf(sv.w, u.w, acc[r]))));
+      }
+    }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1)
+#pragma unroll
+    for (int r = 0; r < Q; ++r) acc[r] += __shfl_xor(acc[r], off);
+  if (lane < Q && q0 + lane < n) {
+    float v = acc[0];
+#pragma unroll
+    for (int r = 1; r < Q; ++r) v = lane == r ? acc[r] : v;
+    const float nu = norm != nullptr ? norm[q0 + lane] : 1.f;
+    out[(int64_t)(q0 + lane) * ldo + j] = nu * v;
+  }
+}
+
+template <int BITS>
+static hipError_t dequant_rows_bits(bool prod, int d, int n, const uint32_t* idx, const uint32_t* qjl, const float* gamma,
+                                    const float* norm, const float* PiT, const float* ST, const Codebook& cb, float kappa,
+                                    float* out, int64_t ldo, hipStream_t s) {
+  const int Q = prod ? 2 : 4;
+  const dim3 grid((d + 3) / 4, (n + Q - 1) / Q);
+  const size_t lds = (size_t)(prod ? 2 : 1) * Q * d * sizeof(float);
+  if (prod)
+    hipLaunchKernelGGL((dequant_rows_kernel<BITS, true>), grid, dim3(256), lds, s, d, n, idx, qjl, gamma, norm, PiT, ST, cb, kappa, out, ldo);
+  else
+    hipLaunchKernelGGL((dequant_rows_kernel<BITS, false>), grid, dim3(256), lds, s, d, n, idx, qjl, gamma, norm, PiT, ST, cb, kappa, out, ldo);
+  return hipGetLastError();
+}
+
+hipError_t launch_dequant_rows(int bits, bool prod, int d, int64_t n, const uint32_t* idx, const uint32_t* qjl,
+                               const float* gamma, const float* norm, const float* PiT, const float* ST, const Codebook& cb,
+                               float kappa, float* out, int64_t ldo, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  if (n > 65535 || d % 32 != 0 || (size_t)4 * d * sizeof(float) > 65536) return hipErrorInvalidValue;
+  switch (bits) {
+    case 0: return dequant_rows_bits<0>(prod, d, (int)n, idx, qjl, gamma, norm, PiT, ST, cb, kappa, out, ldo, s);
+    case 1: return dequant_rows_bits<1>(prod, d, (int)n, idx, qjl, gamma, norm, PiT, ST, cb, kappa, out, ldo, s);
+    case 2: return dequant_rows_bits<2>(prod, d, (int)n, idx, qjl, gamma, norm, PiT, ST, cb, kappa, out, ldo, s);
+    case 3: return dequant_rows_bits<3>(prod, d, (int)n, idx, qjl, gamma, norm, PiT, ST, cb, kappa, out, ldo, s);
+    case 4: return dequant_rows_bits<4>(prod, d, (int)n, idx, qjl, gamma, norm, PiT, ST, cb, kappa, out, ldo, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
 hipError_t launch_matvec_small(int d, int nq, const float* W0, const float* W1, const float* x,
                                int64_t ldx, float* out0, float* out1, hipStream_t stream) {
   if (nq == 0) return hipSuccess;

@@ -450,6 +450,9 @@ def test_empty_and_error_paths():
     # d = 128 above the small-batch threshold: the bf16-piece contraction (rows of Pi^T as queries)
     (128, 2, 30000, True, True), (128, 3, 25000, False, False), (128, 0, 26001, True, True), (128, 4, 24600, False, True),
     (128, 1, 8200, True, True), (128, 1, 9000, False, False), (128, 2, 8193, True, False),
+    # a handful of long vectors: matrix-vector products
+    (1536, 4, 1, False, True), (3072, 1, 8, True, True), (512, 3, 31, True, False), (1024, 0, 5, True, True),
+    (768, 2, 64, False, False), (544, 1, 3, True, True), (3584, 2, 2, True, True), (2048, 3, 13, False, True),
 ])
 def test_dequantize(d, bits_mse, n, prod, with_norm):
     p, Pi, S, c32, t32 = setup(d, bits_mse, prod)
