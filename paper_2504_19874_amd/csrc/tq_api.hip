@@ -579,8 +579,10 @@ tq_status score_impl(const tq_params* p, Workspace ws, const float* q, int64_t l
   }
   float* part_val = pl.part_bytes ? static_cast<float*>(ws.take(pl.part_bytes)) : nullptr;
   int32_t* part_idx = pl.part_bytes ? static_cast<int32_t*>(ws.take(pl.part_bytes)) : nullptr;
+  // the chunks of a top-k over a score matrix are an optimisation: without room for their lists, one workgroup per row
+  const int topk_chunks = (part_val != nullptr && part_idx != nullptr) ? pl.topk_chunks : 0;
   if ((pl.img_bytes && img == nullptr) || (pl.q_bytes && (qr == nullptr || (prod && qs == nullptr))) ||
-      (pl.part_bytes && (part_val == nullptr || part_idx == nullptr)))
+      (pl.ranges > 0 && (part_val == nullptr || part_idx == nullptr)))
     return TQ_ERR_WORKSPACE;
 
   if (pl.route == ScorePlan::R_SPLIT_I8) {
@@ -656,10 +658,10 @@ tq_status score_impl(const tq_params* p, Workspace ws, const float* q, int64_t l
       if (launch_gemm(N_CODE, E_STORE_N, p->bits_mse, a, n_groups, s) != hipSuccess) return TQ_ERR_HIP;
     }
   }
-  if (topk > 0 && pl.topk_chunks > 0) {
-    if (launch_topk(scores, nq, n_per_group, ld_scores, topk, nullptr, nullptr, s, pl.topk_chunks, part_val, part_idx) != hipSuccess)
+  if (topk > 0 && topk_chunks > 0) {
+    if (launch_topk(scores, nq, n_per_group, ld_scores, topk, nullptr, nullptr, s, topk_chunks, part_val, part_idx) != hipSuccess)
       return TQ_ERR_HIP;
-    return from_hip(launch_topk_merge(part_val, part_idx, nq, pl.topk_chunks, topk, topk_idx, topk_val, s));
+    return from_hip(launch_topk_merge(part_val, part_idx, nq, topk_chunks, topk, topk_idx, topk_val, s));
   }
   if (topk > 0) return from_hip(launch_topk(scores, nq, n_per_group, ld_scores, topk, topk_idx, topk_val, s));
   return TQ_OK;

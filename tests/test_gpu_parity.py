@@ -646,6 +646,21 @@ def test_topk_over_a_few_long_rows(d, bits_mse, prod, n_groups, qpg, npg, topk):
     c = _random_codes(p, d, bits_mse, prod, n_groups * npg, d + npg)
     q = dev(W.gaussian_queries(n_groups * qpg, d, 3, unit=False))
     _topk_both_ways(p, q, n_groups, qpg, c, npg, topk)
+    # a workspace without room for the chunks' lists (sized as for a call without top-k): one workgroup per row
+    # (few-query routes only: the many-query kernel's own selection cannot do without its lists)
+    if qpg > 16:
+        return
+    nq = n_groups * qpg
+    keep = (p.workspace, p.c.workspace, p.c.workspace_bytes)
+    try:
+        p.workspace, p.c.workspace, p.c.workspace_bytes = None, 0, 0
+        p.reserve_score(n_groups, qpg, npg, prod, True, 0)
+        scores = torch.zeros((nq, npg), dtype=torch.float32, device=DEV)
+        ti = torch.full((nq, topk), -5, dtype=torch.int32, device=DEV)
+        tq.tq_score(p, q, n_groups, qpg, c["idx"], c["qjl"], c["gamma"], c["norm"], npg, scores, topk, ti, None)
+        assert np.array_equal(ti.cpu().numpy(), o.topk(scores.cpu().numpy(), topk))
+    finally:
+        p.workspace, p.c.workspace, p.c.workspace_bytes = keep
 
 
 def test_topk_inside_the_scoring_kernel_on_adversarial_orders():
